@@ -1,0 +1,364 @@
+"""Pins for the CPU oracle: every check here compares it with something other than itself —
+finite differences, closed forms, library routines called as black boxes, brute force.
+The paper prints no worked numeric example, so no fixture comes from the paper."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import nmt_oracle as O
+from paper_1802_07170_amd import inputs as I
+
+
+def tiny_cfg(H=4, E=3, V=11, L=1):
+    return dict(src_vocab=V, tgt_vocab=V + 2, emb=E, hidden=H, layers=L)
+
+
+def rand_params(cfg, seed, scale=0.5):
+    rng = np.random.default_rng(seed)
+    return {n: rng.uniform(-scale, scale, size=s) for n, s in O.param_shapes(cfg)}
+
+
+def tiny_batch(cfg, seed=0):
+    # ragged lengths; id 5 repeats on both sides, id 7 never occurs
+    rng = np.random.default_rng(seed)
+    src_len = np.array([4, 2, 3])
+    tgt_len = np.array([3, 5, 1])
+    S, T = 4, 5
+    pool_s = np.array([4, 5, 6, 8, 9, 10])
+    src = rng.choice(pool_s, size=(3, S))
+    tgt = rng.choice(pool_s, size=(3, T))
+    src[0, 0] = src[0, 1] = src[1, 0] = 5
+    tgt[1, 0] = tgt[1, 2] = tgt[0, 1] = 5
+    src[np.arange(S)[None] >= src_len[:, None]] = 0
+    tgt[np.arange(T)[None] >= tgt_len[:, None]] = 0
+    return src, src_len, tgt, tgt_len
+
+
+# ---------------------------------------------------------------------------------------------
+# whole backward: central finite differences on every parameter tensor
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("H,L,logit_tanh", [(4, 1, False), (6, 2, False), (4, 2, True)])
+def test_finite_differences_every_tensor(H, L, logit_tanh):
+    cfg = tiny_cfg(H=H, L=L)
+    p = rand_params(cfg, seed=H + L)
+    batch = tiny_batch(cfg)
+    loss, g, _ = O.train_step(cfg, p, *batch, logit_tanh=logit_tanh)
+    rng = np.random.default_rng(1)
+    eps = 1e-5
+    for name, shape in O.param_shapes(cfg):
+        n = int(np.prod(shape))
+        # all entries of small tensors, a seeded sample of the large ones
+        idxs = range(n) if n <= 40 else rng.choice(n, size=40, replace=False)
+        for k in idxs:
+            idx = np.unravel_index(k, shape)
+            old = p[name][idx]
+            p[name][idx] = old + eps
+            lp = O.train_step(cfg, p, *batch, logit_tanh=logit_tanh)[0]
+            p[name][idx] = old - eps
+            lm = O.train_step(cfg, p, *batch, logit_tanh=logit_tanh)[0]
+            p[name][idx] = old
+            fd = (lp - lm) / (2 * eps)
+            assert abs(fd - g[name][idx]) <= 1e-6 * max(1.0, abs(fd)) + 1e-9, (name, idx, fd, g[name][idx])
+    # an id that never occurs gets an exactly zero embedding gradient
+    assert np.all(g["E_src"][7] == 0) and np.all(g["E_tgt"][7] == 0)
+    assert np.any(g["E_src"][5] != 0) and np.any(g["E_tgt"][5] != 0)
+
+
+# ---------------------------------------------------------------------------------------------
+# LSTM closed forms
+# ---------------------------------------------------------------------------------------------
+def test_lstm_zero_weights_gives_zero_state():
+    T, B, K, h = 5, 2, 3, 4
+    X = np.random.default_rng(0).normal(size=(T, B, K))
+    Y, hf, cf, _ = O.lstm_forward(X, np.ones((T, B)), np.zeros((4 * h, K + h)), np.zeros(4 * h),
+                                  np.zeros((B, h)), np.zeros((B, h)))
+    assert np.all(Y == 0) and np.all(hf == 0) and np.all(cf == 0)
+
+
+def test_lstm_bias_only_geometric_series():
+    T, B, K, h = 6, 2, 3, 4
+    rng = np.random.default_rng(1)
+    b = rng.normal(size=4 * h)
+    X = rng.normal(size=(T, B, K))
+    Y, _, _, sv = O.lstm_forward(X, np.ones((T, B)), np.zeros((4 * h, K + h)), b,
+                                 np.zeros((B, h)), np.zeros((B, h)))
+    sg = lambda x: 1 / (1 + np.exp(-x))
+    bi, bf, bg, bo = b[:h], b[h:2 * h], b[2 * h:3 * h], b[3 * h:]
+    for t in range(T):
+        c_t = sg(bi) * np.tanh(bg) * (1 - sg(bf) ** (t + 1)) / (1 - sg(bf))
+        h_t = sg(bo) * np.tanh(c_t)
+        np.testing.assert_allclose(Y[t], np.broadcast_to(h_t, (B, h)), rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(sv["Cst"][t], np.broadcast_to(c_t, (B, h)), rtol=1e-12, atol=1e-14)
+
+
+def test_lstm_saturated_gates_carry_the_cell():
+    T, B, K, h = 4, 2, 3, 4
+    rng = np.random.default_rng(2)
+    b = np.concatenate([np.full(h, -60.0), np.full(h, 60.0), rng.normal(size=h), rng.normal(size=h)])
+    c0 = rng.normal(size=(B, h))
+    Y, _, cf, _ = O.lstm_forward(rng.normal(size=(T, B, K)), np.ones((T, B)), np.zeros((4 * h, K + h)),
+                                 b, np.zeros((B, h)), c0)
+    np.testing.assert_allclose(cf, c0, rtol=1e-12)
+    exp_h = (1 / (1 + np.exp(-b[3 * h:]))) * np.tanh(c0)
+    for t in range(T):
+        np.testing.assert_allclose(Y[t], exp_h, rtol=1e-12)
+
+
+def test_gate_order_distinguishes_i_f_g_o():
+    # one step from (h,c) = (0, c0) with only biases: each gate block has its own role
+    h = 3
+    b = np.array([0.3] * h + [-0.7] * h + [1.1] * h + [0.2] * h)
+    c0 = np.full((1, h), 0.9)
+    hn, cn, _ = O.cell_forward(np.zeros((1, 2)), np.zeros((1, h)), c0, np.zeros((4 * h, 2 + h)), b)
+    sg = lambda x: 1 / (1 + math.exp(-x))
+    c_exp = sg(-0.7) * 0.9 + sg(0.3) * math.tanh(1.1)
+    np.testing.assert_allclose(cn, c_exp, rtol=1e-13)
+    np.testing.assert_allclose(hn, sg(0.2) * math.tanh(c_exp), rtol=1e-13)
+
+
+# ---------------------------------------------------------------------------------------------
+# LSTM layer against torch.nn.LSTM (fp64), called as a black box
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bidir", [False, True])
+def test_lstm_layer_matches_torch_lstm(bidir):
+    T, B, K, h = 7, 3, 5, 4
+    rng = np.random.default_rng(3)
+    X = rng.normal(size=(T, B, K))
+    lstm = torch.nn.LSTM(K, h, bidirectional=bidir).double()
+    outs = []
+    for d, sfx in enumerate(["", "_reverse"][: 2 if bidir else 1]):
+        W = rng.uniform(-0.5, 0.5, size=(4 * h, K + h))
+        b = rng.uniform(-0.5, 0.5, size=4 * h)
+        with torch.no_grad():
+            getattr(lstm, "weight_ih_l0" + sfx).copy_(torch.from_numpy(W[:, :K]))
+            getattr(lstm, "weight_hh_l0" + sfx).copy_(torch.from_numpy(W[:, K:]))
+            getattr(lstm, "bias_ih_l0" + sfx).copy_(torch.from_numpy(b))
+            getattr(lstm, "bias_hh_l0" + sfx).zero_()
+        Y, hf, cf, _ = O.lstm_forward(X, np.ones((T, B)), W, b, np.zeros((B, h)), np.zeros((B, h)),
+                                      reverse=(d == 1))
+        outs.append((Y, hf, cf))
+    with torch.no_grad():
+        ty, (th, tc) = lstm(torch.from_numpy(X))
+    for d, (Y, hf, cf) in enumerate(outs):
+        np.testing.assert_allclose(Y, ty[:, :, d * h:(d + 1) * h].numpy(), rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(hf, th[d].numpy(), rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(cf, tc[d].numpy(), rtol=1e-10, atol=1e-12)
+
+
+# ---------------------------------------------------------------------------------------------
+# masks: a padded batch equals every sentence run alone, unpadded
+# ---------------------------------------------------------------------------------------------
+def test_padded_batch_equals_single_sentences():
+    cfg = tiny_cfg(H=6, L=2)
+    p = rand_params(cfg, seed=5)
+    src, sl, tgt, tl = tiny_batch(cfg)
+    loss, g, _ = O.train_step(cfg, p, src, sl, tgt, tl)
+    n_tok = tl.sum()
+    tot = 0.0
+    gsum = {k: np.zeros_like(v) for k, v in g.items()}
+    for b in range(len(sl)):
+        lb, gb, _ = O.train_step(cfg, p, src[b:b + 1, :sl[b]], sl[b:b + 1], tgt[b:b + 1, :tl[b]], tl[b:b + 1])
+        tot += lb * tl[b]
+        for k in gsum:
+            gsum[k] += gb[k] * tl[b]
+    assert abs(tot / n_tok - loss) < 1e-12
+    for k in g:
+        np.testing.assert_allclose(g[k], gsum[k] / n_tok, rtol=1e-9, atol=1e-13, err_msg=k)
+    # permuting the batch changes nothing
+    perm = np.array([2, 0, 1])
+    loss2, g2, _ = O.train_step(cfg, p, src[perm], sl[perm], tgt[perm], tl[perm])
+    assert abs(loss2 - loss) < 1e-12
+    for k in g:
+        np.testing.assert_allclose(g[k], g2[k], rtol=1e-9, atol=1e-13)
+
+
+# ---------------------------------------------------------------------------------------------
+# attention
+# ---------------------------------------------------------------------------------------------
+def test_attention_rows_sum_to_one_and_vanish_on_padding():
+    rng = np.random.default_rng(6)
+    S, B, H = 5, 3, 4
+    lens = np.array([5, 2, 1])
+    mask = (np.arange(S)[:, None] < lens[None]).astype(float)
+    Hs = rng.normal(size=(S, B, H)) * mask[:, :, None]
+    Ht = rng.normal(size=(B, H))
+    Wa, Wc = rng.normal(size=(H, H)), rng.normal(size=(H, 2 * H))
+    Ho, c = O.attention_forward(Hs, mask, Ht, Wa, Wc)
+    np.testing.assert_allclose(c["a"].sum(1), 1.0, rtol=1e-14)
+    assert np.all(c["a"][mask.T == 0] == 0.0)
+    # a single valid source position: a = 1 and the context is that state
+    assert c["a"][2, 0] == 1.0
+    np.testing.assert_allclose(c["Cs"][2], Hs[0, 2], rtol=1e-14)
+    # explicit formula for one sentence: scores H_s^T W_a H_t, Eq. 4
+    b = 0
+    s = np.array([Hs[i, b] @ Wa @ Ht[b] for i in range(S)])
+    a = np.exp(s) / np.exp(s).sum()
+    np.testing.assert_allclose(c["a"][b], a, rtol=1e-12)
+    np.testing.assert_allclose(Ho[b], np.tanh(Wc @ np.concatenate([a @ Hs[:, b], Ht[b]])), rtol=1e-12)
+    # W_a = 0: uniform weights over the valid positions, context = their mean
+    _, c0 = O.attention_forward(Hs, mask, Ht, np.zeros((H, H)), Wc)
+    for b in range(B):
+        np.testing.assert_allclose(c0["a"][b, :lens[b]], 1.0 / lens[b], rtol=1e-14)
+        np.testing.assert_allclose(c0["Cs"][b], Hs[:lens[b], b].mean(0), rtol=1e-13)
+
+
+# ---------------------------------------------------------------------------------------------
+# output layer
+# ---------------------------------------------------------------------------------------------
+def test_zero_output_layer_gives_log_vocab():
+    cfg = tiny_cfg(H=4, L=1)
+    p = rand_params(cfg, seed=7)
+    p["W_o"][:] = 0
+    p["B_o"][:] = 0
+    loss, g, _ = O.train_step(cfg, p, *tiny_batch(cfg))
+    assert abs(loss - math.log(cfg["tgt_vocab"])) < 1e-13
+    assert abs(g["B_o"].sum()) < 1e-15
+
+
+def test_output_layer_matches_torch_log_softmax():
+    rng = np.random.default_rng(8)
+    B, H, V = 4, 5, 9
+    Ho, Wo, Bo = rng.normal(size=(B, H)), rng.normal(size=(V, H)), rng.normal(size=V)
+    y = np.array([0, 3, 8, 3])
+    lse, nll, cache = O.output_forward(Ho, y, Wo, Bo)
+    tHo = torch.tensor(Ho, requires_grad=True)
+    tWo = torch.tensor(Wo, requires_grad=True)
+    tBo = torch.tensor(Bo, requires_grad=True)
+    lp = torch.log_softmax(tHo @ tWo.T + tBo, dim=1)
+    tn = -lp[torch.arange(B), torch.tensor(y)]
+    np.testing.assert_allclose(nll, tn.detach().numpy(), rtol=1e-12)
+    w = np.array([0.25, 0.0, 0.5, 0.25])
+    (tn * torch.tensor(w)).sum().backward()
+    dHo, dWo, dBo = O.output_backward(w, cache, Wo)
+    np.testing.assert_allclose(dHo, tHo.grad.numpy(), rtol=1e-11, atol=1e-14)
+    np.testing.assert_allclose(dWo, tWo.grad.numpy(), rtol=1e-11, atol=1e-14)
+    np.testing.assert_allclose(dBo, tBo.grad.numpy(), rtol=1e-11, atol=1e-14)
+    assert abs(dBo.sum()) < 1e-15
+
+
+# ---------------------------------------------------------------------------------------------
+# second, independent derivation of the whole model: torch autograd, sentence by sentence,
+# unpadded, with torch's own LSTMCell for the recurrences
+# ---------------------------------------------------------------------------------------------
+def torch_restatement(cfg, p, src, sl, tgt, tl, bos=2):
+    H, L, E = cfg["hidden"], cfg["layers"], cfg["emb"]
+    Hd = H // 2
+    tp = {k: torch.tensor(np.asarray(v, np.float64), requires_grad=True) for k, v in p.items()}
+
+    def cell(x, h, c, W, b):
+        K = x.shape[0]
+        pre = W[:, :K] @ x + W[:, K:] @ h + b
+        n = h.shape[0]
+        i, f = torch.sigmoid(pre[:n]), torch.sigmoid(pre[n:2 * n])
+        g, o = torch.tanh(pre[2 * n:3 * n]), torch.sigmoid(pre[3 * n:])
+        c = f * c + i * g
+        return o * torch.tanh(c), c
+
+    total = 0.0
+    for b in range(len(sl)):
+        xs = [tp["E_src"][int(t)] for t in src[b, :sl[b]]]
+        n = len(xs)
+        # bottom layer, two directions
+        hf, cf = torch.zeros(Hd, dtype=torch.float64), torch.zeros(Hd, dtype=torch.float64)
+        yf = []
+        for t in range(n):
+            hf, cf = cell(xs[t], hf, cf, tp["enc.l0.fwd.W"], tp["enc.l0.fwd.b"])
+            yf.append(hf)
+        hb, cb = torch.zeros(Hd, dtype=torch.float64), torch.zeros(Hd, dtype=torch.float64)
+        yb = [None] * n
+        for t in range(n - 1, -1, -1):
+            hb, cb = cell(xs[t], hb, cb, tp["enc.l0.bwd.W"], tp["enc.l0.bwd.b"])
+            yb[t] = hb
+        ys = [torch.cat([yf[t], yb[t]]) for t in range(n)]
+        fin = [(torch.cat([hf, hb]), torch.cat([cf, cb]))]
+        for l in range(1, L):
+            h, c = torch.zeros(H, dtype=torch.float64), torch.zeros(H, dtype=torch.float64)
+            nxt = []
+            for t in range(n):
+                h, c = cell(ys[t], h, c, tp[f"enc.l{l}.W"], tp[f"enc.l{l}.b"])
+                nxt.append(h)
+            ys = nxt
+            fin.append((h, c))
+        Hs = torch.stack(ys)                                     # [n, H]
+        st = list(fin)
+        ho = torch.zeros(H, dtype=torch.float64)
+        prev = bos
+        for j in range(tl[b]):
+            x = torch.cat([tp["E_tgt"][prev], ho])
+            for l in range(L):
+                st[l] = cell(x, st[l][0], st[l][1], tp[f"dec.l{l}.W"], tp[f"dec.l{l}.b"])
+                x = st[l][0]
+            ht = x
+            a = torch.softmax(Hs @ (tp["W_a"] @ ht), dim=0)
+            ho = torch.tanh(tp["W_c"] @ torch.cat([a @ Hs, ht]))
+            lp = torch.log_softmax(tp["W_o"] @ ho + tp["B_o"], dim=0)
+            total = total - lp[int(tgt[b, j])]
+            prev = int(tgt[b, j])
+    loss = total / float(tl.sum())
+    loss.backward()
+    return float(loss.detach()), {k: (v.grad.numpy() if v.grad is not None else np.zeros(v.shape)) for k, v in tp.items()}
+
+
+@pytest.mark.parametrize("H,L", [(4, 1), (8, 3)])
+def test_full_model_matches_torch_autograd_restatement(H, L):
+    cfg = tiny_cfg(H=H, E=5, V=13, L=L)
+    p = rand_params(cfg, seed=11)
+    batch = tiny_batch(cfg, seed=3)
+    loss, g, _ = O.train_step(cfg, p, *batch)
+    tloss, tg = torch_restatement(cfg, p, *batch)
+    assert abs(loss - tloss) < 1e-12
+    for k in g:
+        np.testing.assert_allclose(g[k], tg[k], rtol=1e-9, atol=1e-13, err_msg=k)
+
+
+def test_intermediates_are_consistent():
+    cfg = tiny_cfg(H=6, L=2)
+    p = rand_params(cfg, seed=12)
+    src, sl, tgt, tl = tiny_batch(cfg)
+    loss, _, it = O.train_step(cfg, p, src, sl, tgt, tl, want_intermediates=True)
+    assert np.array_equal(it["x_src"][1, 0], p["E_src"][src[0, 1]])
+    assert np.array_equal(it["x_tgt"][0, 1], p["E_tgt"][2])            # BOS first
+    assert np.array_equal(it["x_tgt"][2, 1], p["E_tgt"][tgt[1, 1]])
+    assert np.all(it["h_s"][it["mask_src"] == 0] == 0)
+    np.testing.assert_allclose(it["att_a"].sum(2), 1.0, rtol=1e-13)
+    assert abs(it["nll"].sum() / tl.sum() - loss) < 1e-13
+
+
+# ---------------------------------------------------------------------------------------------
+# the first workload at initialisation, SGD, and the counter-based initialiser
+# ---------------------------------------------------------------------------------------------
+def test_tiny_config_loss_is_near_log_vocab_and_sgd_descends():
+    c = I.CONFIGS["tiny"]
+    cfg = I.model_cfg(c)
+    p = I.make_params(cfg, c["seed"])
+    batch = I.make_batch(c)
+    loss, g, _ = O.train_step(cfg, p, *batch)
+    assert abs(loss - math.log(1000)) < 0.05
+    p2 = O.sgd_update(p, g, 1.0)
+    for k in p:
+        np.testing.assert_allclose(p2[k], p[k].astype(np.float64) - g[k], rtol=0, atol=0)
+    loss2 = O.train_step(cfg, p2, *batch)[0]
+    assert loss2 < loss
+
+
+def test_counter_initialiser():
+    cfg = tiny_cfg(H=4, L=1)
+    a = O.init_params_counter(cfg, seed=0, scale=0.1)
+    b = O.init_params_counter(cfg, seed=0, scale=0.1)
+    # element 0 with seed 0 is the first output of SplitMix64 seeded with 0: 0xE220A8397B1DCDAF
+    u = 0xE220A8397B1DCDAF >> 40
+    assert a["E_src"].reshape(-1)[0] == np.float32((np.float32(u) * np.float32(2 ** -23) - np.float32(1)) * np.float32(0.1))
+    flat = np.concatenate([v.reshape(-1) for v in a.values()])
+    assert all(np.array_equal(a[k], b[k]) for k in a)
+    assert flat.min() >= -0.1 and flat.max() < 0.1 and abs(flat.mean()) < 0.02
+    c = O.init_params_counter(cfg, seed=1, scale=0.1)
+    # seed s, element n uses counter s + n: a shift by one element
+    assert np.array_equal(np.concatenate([v.reshape(-1) for v in c.values()])[:-1], flat[1:])
+
+
+def test_param_tables_agree():
+    for c in I.CONFIGS.values():
+        cfg = I.model_cfg(c)
+        assert O.param_shapes(cfg) == I.param_table(cfg)
