@@ -1,0 +1,121 @@
+/* cytonmt_hip.h — C ABI of the MI355X (gfx950) training-step library.
+ *
+ * One call of cmt_train_step runs one full training step (forward + backward) of the
+ * attention-based stacked-LSTM encoder-decoder of the paper's Method section (Eq. 1-7):
+ * bidirectional bottom encoder layer, input-feeding decoder, multiplicative ("general")
+ * attention, attentional tanh layer H_o = tanh(W_c [C_s; H_t]), and the vocabulary projection
+ * with log-softmax cross-entropy of Eq. 1.  Every step of the path runs in hand-written HIP
+ * kernels; the host side only validates arguments and enqueues launches.
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary host memory.
+ *   - The caller owns every device buffer (parameters, gradients, workspace, ids, lengths) and
+ *     the HIP stream; the library owns only the host-side handle and a few bytes of pinned host
+ *     memory.  It never allocates or frees device memory.
+ *   - All work is enqueued on the stream given to cmt_create.  Calls that return data to host
+ *     memory synchronise that stream before returning.
+ *   - Every function returns CMT_OK (0) or a negative error code; nothing throws or aborts
+ *     across this boundary.  cmt_last_error gives the text of the last failure on a handle.
+ *   - Matrices are row-major [out, in].  Flat parameter / gradient vectors are fp32 in the
+ *     canonical order listed at cmt_param_info.
+ */
+#ifndef CYTONMT_HIP_H
+#define CYTONMT_HIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CMT_OK          0
+#define CMT_EINVAL     -1   /* null pointer, bad shape, B/S/T beyond the configured maxima        */
+#define CMT_ERANGE     -2   /* a token id outside [0, vocab) or a length outside [1, S] / [1, T]   */
+#define CMT_ENONFINITE -3   /* the loss came out NaN or Inf                                        */
+#define CMT_EHIP       -4   /* a HIP runtime call failed                                           */
+
+/* Network shape (hyperparameter table of the paper: embedding size, hidden size, depth,
+ * bidirectional encoder, LSTM) and the largest batch the workspace must hold. */
+typedef struct cmt_config {
+  int32_t src_vocab, tgt_vocab;  /* vocabulary sizes; both multiples of 8                          */
+  int32_t emb_dim;               /* embedding size, multiple of 8                                   */
+  int32_t hidden;                /* hidden size H, multiple of 16, at most 1024; the bottom encoder */
+                                 /* layer is two LSTMs of width H/2                                 */
+  int32_t layers;                /* encoder depth = decoder depth, 1..8                             */
+  int32_t max_batch, max_src_len, max_tgt_len;
+  int32_t precision;             /* 0: fp32 storage and fp32 matrix cores; 1: bf16 operands with    */
+                                 /* fp32 accumulation, fp32 master weights, fp32 state and sums     */
+  int32_t bos_id, pad_id;        /* decoder input at step 0; id stored in padded slots              */
+} cmt_config;
+
+typedef struct cmt_handle cmt_handle;
+
+/* Bytes the caller must provide: flat fp32 parameters, flat fp32 gradients, workspace.
+ * Returns CMT_EINVAL for a configuration the kernels do not support. */
+int cmt_query_sizes(const cmt_config* cfg, size_t* param_bytes, size_t* grad_bytes, size_t* workspace_bytes);
+
+/* Binds caller-owned device buffers (each 256-byte aligned, sizes from cmt_query_sizes) and a
+ * HIP stream (hipStream_t passed as void*; NULL = the default stream).  The buffers must stay
+ * alive until cmt_destroy.  Parameters are uninitialised until cmt_init_params / cmt_set_params. */
+int cmt_create(const cmt_config* cfg, void* params_dev, void* grads_dev, void* workspace_dev,
+               void* hip_stream, cmt_handle** out);
+void cmt_destroy(cmt_handle* h);
+
+/* Parameter table.  Canonical order: E_src[Vs,E], E_tgt[Vt,E], enc.l0.fwd.W[4Hd,E+Hd], .b[4Hd],
+ * enc.l0.bwd.W, .b, enc.l{1..}.W[4H,2H], .b[4H], dec.l0.W[4H,E+2H] (columns [emb; H_o feed; h]),
+ * .b, dec.l{1..}.W[4H,2H], .b, W_a[H,H], W_c[H,2H] (columns [C_s; H_t]), W_o[Vt,H], B_o[Vt].
+ * LSTM weight rows are the gate blocks i, f, g, o; columns are [input; recurrent].
+ * name points into the handle (valid until cmt_destroy); cols = 1 for vectors. */
+int cmt_param_count(const cmt_handle* h);
+int cmt_param_info(const cmt_handle* h, int idx, const char** name, int64_t* rows, int64_t* cols,
+                   size_t* offset_elems);
+
+/* uniform[-scale, scale) from a counter-based generator: flat element n takes the top 24 bits u
+ * of SplitMix64(seed + n) and becomes (u * 2^-23 - 1) * scale in fp32.  Device-side. */
+int cmt_init_params(cmt_handle* h, uint64_t seed, float scale);
+/* Copy the whole flat fp32 parameter vector from / to host memory. */
+int cmt_set_params(cmt_handle* h, const float* host_src);
+int cmt_get_params(cmt_handle* h, float* host_dst);
+
+/* One training step (Eq. 1-7 forward, then the gradient of the mean cross-entropy).
+ *   src_ids_dev [B,S] row-major int32, src_len_dev [B] int32 in [1,S],
+ *   tgt_ids_dev [B,T] row-major int32, tgt_len_dev [B] int32 in [1,T]  (device memory, read only).
+ * The decoder runs tgt_len[b] steps: its input at step j is bos_id for j = 0, else tgt_ids[b,j-1];
+ * the label at step j is tgt_ids[b,j].  Slots beyond a length are ignored.
+ * On return the gradient buffer holds d(loss)/d(parameter) for every parameter (overwritten, not
+ * accumulated; rows of unused embedding ids are zero) and *loss_host the mean cross-entropy per
+ * valid target token.  Synchronises the stream.  Parameters are never modified.
+ * CMT_ERANGE / CMT_ENONFINITE leave the gradient buffer undefined. */
+int cmt_train_step(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* src_len_dev,
+                   const int32_t* tgt_ids_dev, const int32_t* tgt_len_dev,
+                   int32_t B, int32_t S, int32_t T, float* loss_host);
+/* Same work, but only enqueues it: no synchronisation, no error-flag or loss read-back.  The loss
+ * and flag of the last enqueued step are fetched (with a synchronisation) by cmt_fetch_loss. */
+int cmt_train_step_async(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* src_len_dev,
+                         const int32_t* tgt_ids_dev, const int32_t* tgt_len_dev,
+                         int32_t B, int32_t S, int32_t T);
+int cmt_fetch_loss(cmt_handle* h, float* loss_host);
+
+int cmt_get_grads(cmt_handle* h, float* host_dst);
+
+/* Plain SGD (hyperparameter table: optimizer SGD, learning rate 1.0): p <- p - lr * g on the flat
+ * fp32 master vector, then refreshes the kernels' working copies (bf16 casts, transposes). */
+int cmt_sgd_update(cmt_handle* h, float lr);
+
+/* Copies a named intermediate of the last step to host memory as fp32, for per-kernel parity
+ * tests.  Names: "x_src" [S,Bp,E], "x_tgt" [T,Bp,E], "mask_src" [S,Bp], "mask_tgt" [T,Bp],
+ * "h_s" [S,Bp,H], "h_t" [T,Bp,H], "att_a" [T,Bp,S], "att_cs" [T,Bp,H], "h_o" [T,Bp,H],
+ * "lse" [T,Bp], "nll" [T,Bp]; Bp = B rounded up to a multiple of 16 (extra rows are padding).
+ * bytes must equal the tensor's size; values at masked positions are unspecified except for
+ * the masks, "att_a" (exactly 0 on padded source positions) and "nll" (0 on padded targets). */
+int cmt_debug_fetch(cmt_handle* h, const char* name, float* host_dst, size_t bytes);
+/* Padded batch pitch Bp used by cmt_debug_fetch for the last step. */
+int cmt_padded_batch(const cmt_handle* h);
+
+const char* cmt_last_error(const cmt_handle* h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,701 @@
+// Host side of the C ABI (include/cytonmt_hip.h): argument validation, the workspace layout, and
+// the kernel schedule of one training step.  No arithmetic of the method happens here.
+//
+// Schedule of one step (all on the caller's stream):
+//   gather -> encoder layers (input GEMM batched over all source positions, then one fused
+//   recurrent kernel per position) -> attention-key hoist K = H_s W_a -> decoder time loop (per
+//   step: one fused LSTM kernel per layer, attention, attentional tanh layer) -> fused vocabulary
+//   projection / log-softmax / cross-entropy -> its fused backward -> decoder loop backwards ->
+//   deferred attention gradients -> encoder loops backwards -> weight gradients as GEMMs batched
+//   over all time steps (the paper's calculateGradient accumulation becomes the k = B*T
+//   contraction) -> deterministic embedding scatter.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/cytonmt_hip.h"
+#include "kernels.h"
+
+using namespace cmt;
+
+namespace {
+
+struct ParamInfo { std::string name; int64_t rows, cols; size_t off; };
+
+// one LSTM (layer, direction)
+struct LD {
+  int Kin = 0, Hh = 0;
+  size_t w_off = 0, b_off = 0;       // element offsets in the flat parameter vector
+  char* W = nullptr;                 // T [4Hh, Kin+Hh]
+  char* Wt = nullptr;                // T [Kin+Hh, 4Hh]
+  char* Hst = nullptr;               // T [(Lmax+1), Bp, Hh]
+  float* Cst = nullptr;              // [(Lmax+1), Bp, Hh]
+  float* Gs = nullptr;               // [Lmax, Bp, 4Hh] gate activations
+  float* Gx = nullptr;               // [Lmax, Bp, 4Hh] batched input pre-activations (may be null)
+  char* dG = nullptr;                // T [Lmax, Bp, 4Hh]
+  char* dGT = nullptr;               // T [4Hh, Lmax*Bp]
+  char* HstT = nullptr;              // T [Hh, (Lmax+1)*Bp]
+  float* dh = nullptr; float* dc = nullptr;   // [Bp, Hh]
+};
+
+struct Bump {
+  char* base; size_t off = 0;
+  explicit Bump(char* b) : base(b) {}
+  char* take(size_t bytes) {
+    off = (off + 255) & ~(size_t)255;
+    char* p = base ? base + off : nullptr;
+    off += bytes;
+    return p;
+  }
+};
+
+}  // namespace
+
+struct cmt_handle {
+  cmt_config cfg;
+  int prec = 0; size_t esz = 4;
+  hipStream_t st = nullptr;
+  float* params = nullptr; float* grads = nullptr; char* ws = nullptr;
+  size_t nparams = 0;
+  std::vector<ParamInfo> table;
+  std::string err;
+  int Bpm = 0;                          // padded max batch
+  // last-step shape
+  int B = 0, Bp = 0, S = 0, T = 0;
+  bool have_step = false;
+  // pinned host
+  float* h_loss = nullptr; int* h_flags = nullptr;
+
+  // parameter working copies
+  char* Pc = nullptr;                   // T copy of the flat parameter vector (bf16 path) or the master itself
+  std::vector<LD> enc, dec;             // enc: [l0 fwd, l0 bwd, l1, ...]; dec: [l0, l1, ...]
+  size_t off_Esrc = 0, off_Etgt = 0, off_Wa = 0, off_Wc = 0, off_Wo = 0, off_Bo = 0;
+  char *WaT = nullptr, *WcT = nullptr, *WoT = nullptr;
+
+  // source side
+  char* Xs = nullptr; float* mask_s = nullptr; int32_t* tok_s = nullptr; int32_t* len_s = nullptr;
+  char* Y0 = nullptr; char* Y0T = nullptr; char* Kmat = nullptr;
+  float* dHs = nullptr; char* dK = nullptr; char* dKT = nullptr;
+  float* dYa = nullptr; float* dYb = nullptr; float* dXs = nullptr; char* XsT = nullptr;
+  // target side
+  char* Xt = nullptr; float* mask_t = nullptr; int32_t* tok_t = nullptr; int32_t* labels = nullptr; int32_t* len_t = nullptr;
+  char* HoBuf = nullptr; char* HoBufT = nullptr; char* Cs = nullptr; char* CsT = nullptr;
+  float* att_a = nullptr; float* att_ds = nullptr; float* dCs = nullptr;
+  char* dPre = nullptr; char* dPreT = nullptr;
+  float* dHoCE = nullptr; float* dHoPart = nullptr;
+  float* dHt = nullptr; float* dHoFeed = nullptr; float* dxl = nullptr;
+  float* dXt = nullptr; char* XtT = nullptr;
+  float *pmax = nullptr, *psum = nullptr, *zy = nullptr, *lse = nullptr, *nll = nullptr, *rowscale = nullptr;
+  float* loss = nullptr; int* flags = nullptr; float* colscr = nullptr;
+  size_t ws_bytes = 0;
+
+  const char* Pw(size_t off) const { return Pc + off * esz; }
+};
+
+namespace {
+
+int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+bool config_ok(const cmt_config* c, std::string* why) {
+  auto bad = [&](const char* m) { if (why) *why = m; return false; };
+  if (!c) return bad("null config");
+  if (c->src_vocab < 8 || c->tgt_vocab < 8 || c->src_vocab % 8 || c->tgt_vocab % 8) return bad("vocabulary sizes must be positive multiples of 8");
+  if (c->emb_dim < 8 || c->emb_dim % 8 || c->emb_dim > 2048) return bad("emb_dim must be a multiple of 8 in [8, 2048]");
+  if (c->hidden < 16 || c->hidden % 16 || c->hidden > 1024) return bad("hidden must be a multiple of 16 in [16, 1024]");
+  if (c->layers < 1 || c->layers > 8) return bad("layers must be in [1, 8]");
+  if (c->max_batch < 1 || c->max_batch > 4096) return bad("max_batch must be in [1, 4096]");
+  if (c->max_src_len < 1 || c->max_src_len > 512) return bad("max_src_len must be in [1, 512]");
+  if (c->max_tgt_len < 1 || c->max_tgt_len > 4096) return bad("max_tgt_len must be in [1, 4096]");
+  if (c->precision != 0 && c->precision != 1) return bad("precision must be 0 (fp32) or 1 (bf16)");
+  if (c->bos_id < 0 || c->bos_id >= c->tgt_vocab) return bad("bos_id outside the target vocabulary");
+  if (c->pad_id < 0 || c->pad_id >= c->tgt_vocab || c->pad_id >= c->src_vocab) return bad("pad_id outside a vocabulary");
+  return true;
+}
+
+void build_table(const cmt_config& c, std::vector<ParamInfo>& t, size_t& total) {
+  const int64_t Vs = c.src_vocab, Vt = c.tgt_vocab, E = c.emb_dim, H = c.hidden, Hd = H / 2;
+  size_t off = 0;
+  auto add = [&](const std::string& n, int64_t r, int64_t cc) { t.push_back({n, r, cc, off}); off += (size_t)(r * cc); };
+  add("E_src", Vs, E); add("E_tgt", Vt, E);
+  add("enc.l0.fwd.W", 4 * Hd, E + Hd); add("enc.l0.fwd.b", 4 * Hd, 1);
+  add("enc.l0.bwd.W", 4 * Hd, E + Hd); add("enc.l0.bwd.b", 4 * Hd, 1);
+  for (int l = 1; l < c.layers; ++l) {
+    add("enc.l" + std::to_string(l) + ".W", 4 * H, 2 * H); add("enc.l" + std::to_string(l) + ".b", 4 * H, 1);
+  }
+  add("dec.l0.W", 4 * H, E + 2 * H); add("dec.l0.b", 4 * H, 1);
+  for (int l = 1; l < c.layers; ++l) {
+    add("dec.l" + std::to_string(l) + ".W", 4 * H, 2 * H); add("dec.l" + std::to_string(l) + ".b", 4 * H, 1);
+  }
+  add("W_a", H, H); add("W_c", H, 2 * H); add("W_o", Vt, H); add("B_o", Vt, 1);
+  total = off;
+}
+
+size_t find_off(const std::vector<ParamInfo>& t, const std::string& n) {
+  for (auto& p : t) if (p.name == n) return p.off;
+  return 0;
+}
+
+// Carves the workspace.  With base == nullptr only the size is computed.
+size_t layout(cmt_handle* h, char* base) {
+  const cmt_config& c = h->cfg;
+  const size_t esz = h->esz;
+  const int E = c.emb_dim, H = c.hidden, Hd = H / 2, L = c.layers;
+  const int Bp = h->Bpm, Sm = c.max_src_len, Tm = c.max_tgt_len;
+  const size_t Ms = (size_t)Sm * Bp, Mt = (size_t)Tm * Bp;
+  Bump a(base);
+  h->Pc = c.precision ? a.take(h->nparams * esz) : (char*)h->params;
+  auto ld_alloc = [&](LD& d, int Kin, int Hh, int Lm, bool gx) {
+    d.Kin = Kin; d.Hh = Hh;
+    const size_t M = (size_t)Lm * Bp;
+    d.Wt = a.take((size_t)(Kin + Hh) * 4 * Hh * esz);
+    d.Hst = a.take((M + Bp) * Hh * esz);
+    d.Cst = (float*)a.take((M + Bp) * Hh * 4);
+    d.Gs = (float*)a.take(M * 4 * Hh * 4);
+    d.Gx = gx ? (float*)a.take(M * 4 * Hh * 4) : nullptr;
+    d.dG = a.take(M * 4 * Hh * esz);
+    d.dGT = a.take(M * 4 * Hh * esz);
+    d.HstT = a.take((M + Bp) * Hh * esz);
+    d.dh = (float*)a.take((size_t)Bp * Hh * 4);
+    d.dc = (float*)a.take((size_t)Bp * Hh * 4);
+  };
+  h->enc.assign(L + 1, LD());
+  h->dec.assign(L, LD());
+  ld_alloc(h->enc[0], E, Hd, Sm, true);
+  ld_alloc(h->enc[1], E, Hd, Sm, true);
+  for (int l = 1; l < L; ++l) ld_alloc(h->enc[l + 1], H, H, Sm, true);
+  ld_alloc(h->dec[0], E + H, H, Tm, true);
+  for (int l = 1; l < L; ++l) ld_alloc(h->dec[l], H, H, Tm, false);
+  h->WaT = a.take((size_t)H * H * esz);
+  h->WcT = a.take((size_t)2 * H * H * esz);
+  h->WoT = a.take((size_t)H * c.tgt_vocab * esz);
+  // source side
+  h->Xs = a.take(Ms * E * esz); h->XsT = a.take(Ms * E * esz);
+  h->mask_s = (float*)a.take(Ms * 4); h->tok_s = (int32_t*)a.take(Ms * 4); h->len_s = (int32_t*)a.take((size_t)Bp * 4);
+  h->Y0 = a.take(Ms * H * esz); h->Y0T = a.take(Ms * H * esz); h->Kmat = a.take(Ms * H * esz);
+  h->dHs = (float*)a.take(Ms * H * 4); h->dK = a.take(Ms * H * esz); h->dKT = a.take(Ms * H * esz);
+  h->dYa = (float*)a.take(Ms * H * 4); h->dYb = (float*)a.take(Ms * H * 4);
+  h->dXs = (float*)a.take(Ms * E * 4);
+  // target side
+  h->Xt = a.take(Mt * E * esz); h->XtT = a.take(Mt * E * esz);
+  h->mask_t = (float*)a.take(Mt * 4); h->tok_t = (int32_t*)a.take(Mt * 4); h->labels = (int32_t*)a.take(Mt * 4);
+  h->len_t = (int32_t*)a.take((size_t)Bp * 4);
+  h->HoBuf = a.take((Mt + Bp) * H * esz); h->HoBufT = a.take((Mt + Bp) * H * esz);
+  h->Cs = a.take(Mt * H * esz); h->CsT = a.take(Mt * H * esz);
+  h->att_a = (float*)a.take(Mt * Sm * 4); h->att_ds = (float*)a.take(Mt * Sm * 4);
+  h->dCs = (float*)a.take(Mt * H * 4);
+  h->dPre = a.take(Mt * H * esz); h->dPreT = a.take(Mt * H * esz);
+  h->dHoCE = (float*)a.take(Mt * H * 4);
+  h->dHoPart = (float*)a.take((size_t)16 * Mt * H * 4);
+  h->dHt = (float*)a.take((size_t)Bp * H * 4); h->dHoFeed = (float*)a.take((size_t)Bp * H * 4);
+  h->dxl = (float*)a.take((size_t)Bp * H * 4);
+  h->dXt = (float*)a.take(Mt * E * 4);
+  const int np = ce_num_partials(c.tgt_vocab);
+  h->pmax = (float*)a.take(Mt * np * 4); h->psum = (float*)a.take(Mt * np * 4);
+  h->zy = (float*)a.take(Mt * 4); h->lse = (float*)a.take(Mt * 4); h->nll = (float*)a.take(Mt * 4);
+  h->rowscale = (float*)a.take(Mt * 4);
+  h->loss = (float*)a.take(256); h->flags = (int*)a.take(256);
+  h->colscr = (float*)a.take((size_t)16 * 4 * H * 4);
+  return (a.off + 255) & ~(size_t)255;
+}
+
+void bind_params(cmt_handle* h) {
+  const cmt_config& c = h->cfg;
+  auto& t = h->table;
+  h->off_Esrc = find_off(t, "E_src"); h->off_Etgt = find_off(t, "E_tgt");
+  h->off_Wa = find_off(t, "W_a"); h->off_Wc = find_off(t, "W_c");
+  h->off_Wo = find_off(t, "W_o"); h->off_Bo = find_off(t, "B_o");
+  auto bind = [&](LD& d, const std::string& n) {
+    d.w_off = find_off(t, n + ".W"); d.b_off = find_off(t, n + ".b");
+    d.W = h->Pc + d.w_off * h->esz;
+  };
+  bind(h->enc[0], "enc.l0.fwd"); bind(h->enc[1], "enc.l0.bwd");
+  for (int l = 1; l < c.layers; ++l) bind(h->enc[l + 1], "enc.l" + std::to_string(l));
+  for (int l = 0; l < c.layers; ++l) bind(h->dec[l], "dec.l" + std::to_string(l));
+}
+
+// refresh the kernels' working copies of the parameters: operand-type cast, transposes
+void refresh_params(cmt_handle* h) {
+  const cmt_config& c = h->cfg;
+  const int H = c.hidden, p = h->prec;
+  hipStream_t st = h->st;
+  if (p) launch_cast(1, h->params, h->Pc, h->nparams, st);
+  auto tr = [&](LD& d) { launch_transpose(p, d.W, d.Kin + d.Hh, d.Wt, 4 * d.Hh, 4 * d.Hh, d.Kin + d.Hh, st); };
+  for (auto& d : h->enc) tr(d);
+  for (auto& d : h->dec) tr(d);
+  launch_transpose(p, h->Pw(h->off_Wa), H, h->WaT, H, H, H, st);
+  launch_transpose(p, h->Pw(h->off_Wc), 2 * H, h->WcT, H, H, 2 * H, st);
+  launch_transpose(p, h->Pw(h->off_Wo), H, h->WoT, c.tgt_vocab, c.tgt_vocab, H, st);
+}
+
+int fail(cmt_handle* h, int code, const std::string& msg) {
+  if (h) h->err = msg;
+  return code;
+}
+int hip_fail(cmt_handle* h, hipError_t e, const char* what) {
+  return fail(h, CMT_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+// ------------------------------------------------------------------------------------------------
+// the schedule
+// ------------------------------------------------------------------------------------------------
+void run_lstm_layer_bwd(cmt_handle* h, LD& d, int Lsteps, const float* mask, const float* dY, int lddy, int dy_col,
+                        bool reverse_dir, int wt_row0, int nrows, float* dx_out /*per-step, or null*/,
+                        float* dh_buf, float* dc_buf) {
+  // generic helper used by the encoder layers: loops over the steps in the reverse of the
+  // processing order; per step the cell backward, then dh_prev += dgates * W_h.
+  const int p = h->prec, Bp = h->Bp, Hh = d.Hh;
+  const size_t esz = h->esz;
+  hipStream_t st = h->st;
+  for (int k = 0; k < Lsteps; ++k) {
+    const int t = reverse_dir ? k : Lsteps - 1 - k;
+    const int slot_prev = reverse_dir ? t + 1 : t, slot_next = reverse_dir ? t : t + 1;
+    LstmBwdPoint q;
+    q.dy = dY ? dY + (size_t)t * Bp * lddy + dy_col : nullptr; q.lddy = lddy;
+    q.dh = dh_buf; q.dc = dc_buf;
+    q.gsave = d.Gs + (size_t)t * Bp * 4 * Hh;
+    q.cprev = d.Cst + (size_t)slot_prev * Bp * Hh; q.cnext = d.Cst + (size_t)slot_next * Bp * Hh;
+    q.mask = mask + (size_t)t * Bp;
+    q.dg = d.dG + (size_t)t * Bp * 4 * Hh * esz;
+    launch_lstm_bwd_point(p, q, Bp, Hh, st);
+    StepGemm g{};
+    g.a0 = q.dg; g.lda0 = 4 * Hh; g.K0 = 4 * Hh; g.w0_off = 0;
+    g.a1 = nullptr; g.lda1 = 0; g.K1 = 0; g.w1_off = 0;
+    g.W = d.Wt + (size_t)wt_row0 * 4 * Hh * esz; g.ldw = 4 * Hh;
+    g.N = nrows; g.mode = 1;
+    g.out0 = dx_out; g.ld0 = Hh; g.nsplit = dx_out ? nrows - Hh : 0; g.acc0 = 0;
+    g.out1 = dh_buf; g.ld1 = Hh; g.acc1 = 1;
+    launch_step_gemm(p, g, Bp, st);
+  }
+}
+
+void weight_grads(cmt_handle* h, LD& d, int Lsteps, const std::vector<std::pair<const char*, int>>& segs /* (XT ptr, ld) */,
+                  const std::vector<int>& seg_k) {
+  // dW[:, segment] = dG^T * X_segment as one GEMM with k = Lsteps * Bp; db = column sums of dG
+  const int p = h->prec, Bp = h->Bp, Hh = d.Hh;
+  const int M = Lsteps * Bp;
+  hipStream_t st = h->st;
+  launch_transpose(p, d.dG, 4 * Hh, d.dGT, M, M, 4 * Hh, st);
+  float* dW = h->grads + d.w_off;
+  int col = 0;
+  for (size_t i = 0; i < segs.size(); ++i) {
+    launch_gemm_nt(p, d.dGT, M, segs[i].first, segs[i].second, 4 * Hh, seg_k[i], M, dW + col, nullptr, d.Kin + Hh, nullptr, 0, st);
+    col += seg_k[i];
+  }
+  launch_colsum(p, d.dG, M, 4 * Hh, h->colscr, h->grads + d.b_off, st);
+}
+
+int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, const int32_t* tgt_ids,
+                 const int32_t* tgt_len, int B, int S, int T) {
+  const cmt_config& c = h->cfg;
+  if (!src_ids || !src_len || !tgt_ids || !tgt_len) return fail(h, CMT_EINVAL, "null input pointer");
+  if (B < 1 || B > c.max_batch || S < 1 || S > c.max_src_len || T < 1 || T > c.max_tgt_len)
+    return fail(h, CMT_EINVAL, "B, S or T outside [1, configured maximum]");
+  const int p = h->prec, E = c.emb_dim, H = c.hidden, Hd = H / 2, L = c.layers, V = c.tgt_vocab;
+  const int Bp = round_up(B, 16);
+  const size_t esz = h->esz;
+  hipStream_t st = h->st;
+  h->B = B; h->Bp = Bp; h->S = S; h->T = T;
+  const int Ms = S * Bp, Mt = T * Bp;
+  const size_t BH = (size_t)Bp * H;
+  float* G = h->grads;
+  float* P = h->params;
+
+  launch_fill_f32((float*)h->flags, 1, 0.f, st);
+  // ---- embeddings, masks ------------------------------------------------------------------------
+  launch_gather(p, h->Pw(h->off_Esrc), c.src_vocab, E, src_ids, src_len, B, Bp, S, 0, 0, h->Xs, h->mask_s, h->tok_s,
+                nullptr, h->len_s, h->flags, st);
+  launch_gather(p, h->Pw(h->off_Etgt), c.tgt_vocab, E, tgt_ids, tgt_len, B, Bp, T, 1, c.bos_id, h->Xt, h->mask_t,
+                h->tok_t, h->labels, h->len_t, h->flags, st);
+
+  // ---- encoder layer 0: two directions ------------------------------------------------------------
+  LD& ef = h->enc[0]; LD& eb = h->enc[1];
+  for (LD* d : {&ef, &eb})
+    launch_gemm_nt(p, h->Xs, E, d->W, E + Hd, Ms, 4 * Hd, E, d->Gx, nullptr, 4 * Hd, P + d->b_off, 0, st);
+  const size_t BHd = (size_t)Bp * Hd;
+  launch_fill_T(p, ef.Hst, BHd, st); launch_fill_f32(ef.Cst, BHd, 0.f, st);
+  launch_fill_T(p, eb.Hst + (size_t)S * BHd * esz, BHd, st); launch_fill_f32(eb.Cst + (size_t)S * BHd, BHd, 0.f, st);
+  for (int k = 0; k < S; ++k) {
+    const int tf = k, tb = S - 1 - k;
+    LstmFwdDir d[2];
+    for (int i = 0; i < 2; ++i) {
+      LD& e = i ? eb : ef;
+      const int t = i ? tb : tf;
+      const int sp = i ? t + 1 : t, sn = i ? t : t + 1;
+      d[i].x = nullptr; d[i].ldx = 0; d[i].Kx = 0;
+      d[i].hprev = e.Hst + sp * BHd * esz; d[i].ldh = Hd;
+      d[i].W = e.W; d[i].ldw = E + Hd; d[i].wx_off = 0; d[i].wh_off = E;
+      d[i].gx = e.Gx + (size_t)t * Bp * 4 * Hd; d[i].ldgx = 4 * Hd; d[i].bias = nullptr;
+      d[i].cprev = e.Cst + sp * BHd; d[i].mask = h->mask_s + (size_t)t * Bp;
+      d[i].hnext = e.Hst + sn * BHd * esz; d[i].cnext = e.Cst + sn * BHd;
+      d[i].gsave = e.Gs + (size_t)t * Bp * 4 * Hd;
+      d[i].ycat = h->Y0 + ((size_t)t * BH + (i ? Hd : 0)) * esz; d[i].ldy = H;
+    }
+    launch_lstm_fwd(p, d, 2, Bp, Hd, st);
+  }
+  // ---- encoder layers >= 1 ------------------------------------------------------------------------
+  const char* Yprev = h->Y0;                       // [S*Bp, H]
+  for (int l = 1; l < L; ++l) {
+    LD& e = h->enc[l + 1];
+    launch_gemm_nt(p, Yprev, H, e.W, 2 * H, Ms, 4 * H, H, e.Gx, nullptr, 4 * H, P + e.b_off, 0, st);
+    launch_fill_T(p, e.Hst, BH, st); launch_fill_f32(e.Cst, BH, 0.f, st);
+    for (int t = 0; t < S; ++t) {
+      LstmFwdDir d;
+      d.x = nullptr; d.ldx = 0; d.Kx = 0;
+      d.hprev = e.Hst + t * BH * esz; d.ldh = H;
+      d.W = e.W; d.ldw = 2 * H; d.wx_off = 0; d.wh_off = H;
+      d.gx = e.Gx + (size_t)t * Bp * 4 * H; d.ldgx = 4 * H; d.bias = nullptr;
+      d.cprev = e.Cst + t * BH; d.mask = h->mask_s + (size_t)t * Bp;
+      d.hnext = e.Hst + (t + 1) * BH * esz; d.cnext = e.Cst + (t + 1) * BH;
+      d.gsave = e.Gs + (size_t)t * Bp * 4 * H; d.ycat = nullptr; d.ldy = 0;
+      launch_lstm_fwd(p, &d, 1, Bp, H, st);
+    }
+    Yprev = e.Hst + BH * esz;
+  }
+  const char* Hs = Yprev;                          // source-side top-layer states [S, Bp, H]
+  // attention keys K_i = W_a^T H_s^i for all i at once (Eq. 4 regrouped)
+  launch_gemm_nt(p, Hs, H, h->WaT, H, Ms, H, H, nullptr, h->Kmat, H, nullptr, 0, st);
+
+  // ---- decoder initial state = encoder final state of the same depth ------------------------------
+  {
+    LD& d0 = h->dec[0];
+    launch_copy2d_T(p, ef.Hst + (size_t)S * BHd * esz, Hd, d0.Hst, H, Bp, Hd, st);
+    launch_copy2d_T(p, eb.Hst, Hd, d0.Hst + (size_t)Hd * esz, H, Bp, Hd, st);
+    launch_copy2d_f32(ef.Cst + (size_t)S * BHd, Hd, d0.Cst, H, Bp, Hd, st);
+    launch_copy2d_f32(eb.Cst, Hd, d0.Cst + Hd, H, Bp, Hd, st);
+    for (int l = 1; l < L; ++l) {
+      LD& e = h->enc[l + 1]; LD& d = h->dec[l];
+      launch_copy2d_T(p, e.Hst + (size_t)S * BH * esz, H, d.Hst, H, Bp, H, st);
+      launch_copy2d_f32(e.Cst + (size_t)S * BH, H, d.Cst, H, Bp, H, st);
+    }
+  }
+  // ---- decoder time loop --------------------------------------------------------------------------
+  {
+    LD& d0 = h->dec[0];
+    launch_gemm_nt(p, h->Xt, E, d0.W, E + 2 * H, Mt, 4 * H, E, d0.Gx, nullptr, 4 * H, P + d0.b_off, 0, st);
+    launch_fill_T(p, h->HoBuf, BH, st);
+    for (int j = 0; j < T; ++j) {
+      for (int l = 0; l < L; ++l) {
+        LD& e = h->dec[l];
+        LstmFwdDir d;
+        if (l == 0) {
+          d.x = h->HoBuf + j * BH * esz; d.ldx = H; d.Kx = H; d.wx_off = E; d.wh_off = E + H;
+          d.gx = e.Gx + (size_t)j * Bp * 4 * H; d.ldgx = 4 * H; d.bias = nullptr; d.ldw = E + 2 * H;
+        } else {
+          d.x = h->dec[l - 1].Hst + (j + 1) * BH * esz; d.ldx = H; d.Kx = H; d.wx_off = 0; d.wh_off = H;
+          d.gx = nullptr; d.ldgx = 0; d.bias = P + e.b_off; d.ldw = 2 * H;
+        }
+        d.hprev = e.Hst + j * BH * esz; d.ldh = H; d.W = e.W;
+        d.cprev = e.Cst + j * BH; d.mask = h->mask_t + (size_t)j * Bp;
+        d.hnext = e.Hst + (j + 1) * BH * esz; d.cnext = e.Cst + (j + 1) * BH;
+        d.gsave = e.Gs + (size_t)j * Bp * 4 * H; d.ycat = nullptr; d.ldy = 0;
+        launch_lstm_fwd(p, &d, 1, Bp, H, st);
+      }
+      const char* Ht = h->dec[L - 1].Hst + (j + 1) * BH * esz;
+      launch_att_fwd(p, h->Kmat, Hs, Ht, h->len_s, S, Bp, H, h->att_a + (size_t)j * Bp * S, h->Cs + j * BH * esz, st);
+      StepGemm g{};
+      g.a0 = h->Cs + j * BH * esz; g.lda0 = H; g.K0 = H; g.w0_off = 0;
+      g.a1 = Ht; g.lda1 = H; g.K1 = H; g.w1_off = H;
+      g.W = h->Pw(h->off_Wc); g.ldw = 2 * H; g.N = H; g.mode = 0;
+      g.outT = h->HoBuf + (j + 1) * BH * esz; g.ldo = H;
+      launch_step_gemm(p, g, Bp, st);
+    }
+  }
+  // ---- Eq. 1: fused projection + log-softmax + cross-entropy --------------------------------------
+  const char* Ho = h->HoBuf + BH * esz;            // [T*Bp, H]
+  const int np = ce_num_partials(V);
+  launch_ce_fwd(p, Ho, h->Pw(h->off_Wo), P + h->off_Bo, h->labels, Mt, V, H, h->pmax, h->psum, h->zy, st);
+  launch_ce_reduce(h->pmax, h->psum, h->zy, h->mask_t, Mt, np, h->lse, h->nll, h->rowscale, h->loss, h->flags, st);
+
+  // =================================== backward ======================================================
+  const int ldHoT = Mt + Bp;
+  launch_transpose(p, h->HoBuf, H, h->HoBufT, ldHoT, Mt + Bp, H, st);
+  const char* HoT = h->HoBufT + (size_t)Bp * esz;  // columns of H_o^{<0..T-1>}
+  const int nsplit = ce_bwd_nsplit(Mt, V);
+  launch_ce_bwd_dh(p, Ho, h->Pw(h->off_Wo), h->WoT, P + h->off_Bo, h->labels, h->lse, h->rowscale, Mt, V, H, nsplit,
+                   h->dHoPart, st);
+  launch_sum_parts(h->dHoPart, nsplit, (size_t)Mt * H, h->dHoCE, st);
+  launch_ce_bwd_dw(p, Ho, HoT, ldHoT, h->Pw(h->off_Wo), P + h->off_Bo, h->labels, h->lse, h->rowscale, Mt, V, H,
+                   G + h->off_Wo, G + h->off_Bo, st);
+
+  // ---- decoder loop backwards -----------------------------------------------------------------------
+  for (int l = 0; l < L; ++l) { launch_fill_f32(h->dec[l].dh, BH, 0.f, st); launch_fill_f32(h->dec[l].dc, BH, 0.f, st); }
+  for (int j = T - 1; j >= 0; --j) {
+    char* dpre = h->dPre + j * BH * esz;
+    launch_tanh_bwd(p, h->dHoCE + j * BH, j < T - 1 ? h->dHoFeed : nullptr, h->HoBuf + (j + 1) * BH * esz, dpre, (int)BH, st);
+    {   // [dC_s ; dH_t] = dpre W_c
+      StepGemm g{};
+      g.a0 = dpre; g.lda0 = H; g.K0 = H; g.w0_off = 0; g.K1 = 0;
+      g.W = h->WcT; g.ldw = H; g.N = 2 * H; g.mode = 1;
+      g.out0 = h->dCs + j * BH; g.ld0 = H; g.nsplit = H; g.acc0 = 0;
+      g.out1 = h->dHt; g.ld1 = H; g.acc1 = 0;
+      launch_step_gemm(p, g, Bp, st);
+    }
+    launch_att_bwd(p, h->Kmat, Hs, h->dCs + j * BH, h->att_a + (size_t)j * Bp * S, h->len_s, S, Bp, H,
+                   h->att_ds + (size_t)j * Bp * S, h->dHt, st);
+    for (int l = L - 1; l >= 0; --l) {
+      LD& e = h->dec[l];
+      LstmBwdPoint q;
+      q.dy = (l == L - 1) ? h->dHt : h->dxl; q.lddy = H;
+      q.dh = e.dh; q.dc = e.dc;
+      q.gsave = e.Gs + (size_t)j * Bp * 4 * H;
+      q.cprev = e.Cst + j * BH; q.cnext = e.Cst + (j + 1) * BH;
+      q.mask = h->mask_t + (size_t)j * Bp;
+      q.dg = e.dG + (size_t)j * Bp * 4 * H * esz;
+      launch_lstm_bwd_point(p, q, Bp, H, st);
+      StepGemm g{};
+      g.a0 = q.dg; g.lda0 = 4 * H; g.K0 = 4 * H; g.w0_off = 0; g.K1 = 0;
+      g.W = e.Wt + (size_t)(l == 0 ? E : 0) * 4 * H * esz; g.ldw = 4 * H;
+      g.N = 2 * H; g.mode = 1;
+      g.out0 = (l == 0) ? h->dHoFeed : h->dxl; g.ld0 = H; g.nsplit = H; g.acc0 = 0;
+      g.out1 = e.dh; g.ld1 = H; g.acc1 = 1;
+      launch_step_gemm(p, g, Bp, st);
+    }
+  }
+  // ---- attention gradients that do not feed the decoder recurrence, batched over all steps ---------
+  const char* HtAll = h->dec[L - 1].Hst + BH * esz;      // H_t^{<0..T-1>}
+  launch_att_deferred(p, h->att_a, h->att_ds, h->dCs, HtAll, (int)BH, S, T, Bp, H, h->dHs, h->dK, st);
+  launch_gemm_nt(p, h->dK, H, h->Pw(h->off_Wa), H, Ms, H, H, h->dHs, nullptr, H, nullptr, 1, st);   // dHs += dK W_a^T
+
+  // transposed activations for the weight-gradient GEMMs
+  auto transpose_states = [&](LD& d, int Lsteps) {
+    launch_transpose(p, d.Hst, d.Hh, d.HstT, (Lsteps + 1) * Bp, (Lsteps + 1) * Bp, d.Hh, st);
+  };
+  for (auto& d : h->enc) transpose_states(d, S);
+  for (auto& d : h->dec) transpose_states(d, T);
+  launch_transpose(p, h->Y0, H, h->Y0T, Ms, Ms, H, st);
+  launch_transpose(p, h->Xs, E, h->XsT, Ms, Ms, E, st);
+  launch_transpose(p, h->Xt, E, h->XtT, Mt, Mt, E, st);
+  launch_transpose(p, h->Cs, H, h->CsT, Mt, Mt, H, st);
+  launch_transpose(p, h->dPre, H, h->dPreT, Mt, Mt, H, st);
+  launch_transpose(p, h->dK, H, h->dKT, Ms, Ms, H, st);
+  // encoder layer outputs, transposed: layer 0 -> Y0T (ld Ms); layer l >= 1 -> HstT + Bp (ld (S+1)Bp)
+  auto encYT = [&](int l, int* ld) -> const char* {
+    if (l == 0) { *ld = Ms; return h->Y0T; }
+    *ld = (S + 1) * Bp; return h->enc[l + 1].HstT + (size_t)Bp * esz;
+  };
+  {   // dW_a[r,c] = sum_i H_s[i,r] dK[i,c];  dW_c = dpre^T [C_s ; H_t]
+    int ld; const char* HsT = encYT(L - 1, &ld);
+    launch_gemm_nt(p, HsT, ld, h->dKT, Ms, H, H, Ms, G + h->off_Wa, nullptr, H, nullptr, 0, st);
+    launch_gemm_nt(p, h->dPreT, Mt, h->CsT, Mt, H, H, Mt, G + h->off_Wc, nullptr, 2 * H, nullptr, 0, st);
+    launch_gemm_nt(p, h->dPreT, Mt, h->dec[L - 1].HstT + (size_t)Bp * esz, (T + 1) * Bp, H, H, Mt, G + h->off_Wc + H, nullptr,
+                   2 * H, nullptr, 0, st);
+  }
+  // decoder weight gradients
+  for (int l = 0; l < L; ++l) {
+    LD& e = h->dec[l];
+    if (l == 0)
+      weight_grads(h, e, T, {{h->XtT, Mt}, {h->HoBufT, ldHoT}, {e.HstT, (T + 1) * Bp}}, {E, H, H});
+    else
+      weight_grads(h, e, T, {{h->dec[l - 1].HstT + (size_t)Bp * esz, (T + 1) * Bp}, {e.HstT, (T + 1) * Bp}}, {H, H});
+  }
+  // target embedding gradient
+  launch_gemm_nt(p, h->dec[0].dG, 4 * H, h->dec[0].Wt, 4 * H, Mt, E, 4 * H, h->dXt, nullptr, E, nullptr, 0, st);
+  launch_embed_scatter(h->dXt, h->tok_t, Mt, c.tgt_vocab, E, G + h->off_Etgt, st);
+
+  // ---- encoder backwards ------------------------------------------------------------------------------
+  const float* dY = h->dHs;
+  float* dYnext = h->dYa;
+  for (int l = L - 1; l >= 1; --l) {
+    LD& e = h->enc[l + 1];
+    // gradient of the final state = gradient of the decoder's initial state of the same depth
+    run_lstm_layer_bwd(h, e, S, h->mask_s, dY, H, 0, false, H, H, nullptr, h->dec[l].dh, h->dec[l].dc);
+    launch_gemm_nt(p, e.dG, 4 * H, e.Wt, 4 * H, Ms, H, 4 * H, dYnext, nullptr, H, nullptr, 0, st);   // dX = dG W_x
+    int ld; const char* XT = encYT(l - 1, &ld);
+    weight_grads(h, e, S, {{XT, ld}, {e.HstT, (S + 1) * Bp}}, {H, H});
+    dY = dYnext;
+    dYnext = (dYnext == h->dYa) ? h->dYb : h->dYa;
+  }
+  {
+    LD& d0 = h->dec[0];
+    launch_copy2d_f32(d0.dh, H, ef.dh, Hd, Bp, Hd, st); launch_copy2d_f32(d0.dh + Hd, H, eb.dh, Hd, Bp, Hd, st);
+    launch_copy2d_f32(d0.dc, H, ef.dc, Hd, Bp, Hd, st); launch_copy2d_f32(d0.dc + Hd, H, eb.dc, Hd, Bp, Hd, st);
+    run_lstm_layer_bwd(h, ef, S, h->mask_s, dY, H, 0, false, E, Hd, nullptr, ef.dh, ef.dc);
+    run_lstm_layer_bwd(h, eb, S, h->mask_s, dY, H, Hd, true, E, Hd, nullptr, eb.dh, eb.dc);
+    launch_gemm_nt(p, ef.dG, 4 * Hd, ef.Wt, 4 * Hd, Ms, E, 4 * Hd, h->dXs, nullptr, E, nullptr, 0, st);
+    launch_gemm_nt(p, eb.dG, 4 * Hd, eb.Wt, 4 * Hd, Ms, E, 4 * Hd, h->dXs, nullptr, E, nullptr, 1, st);
+    weight_grads(h, ef, S, {{h->XsT, Ms}, {ef.HstT, (S + 1) * Bp}}, {E, Hd});
+    weight_grads(h, eb, S, {{h->XsT, Ms}, {eb.HstT + (size_t)Bp * esz, (S + 1) * Bp}}, {E, Hd});
+    launch_embed_scatter(h->dXs, h->tok_s, Ms, c.src_vocab, E, G + h->off_Esrc, st);
+  }
+  (void)hipMemcpyAsync(h->h_loss, h->loss, 2 * sizeof(float), hipMemcpyDeviceToHost, st);
+  (void)hipMemcpyAsync(h->h_flags, h->flags, sizeof(int), hipMemcpyDeviceToHost, st);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(h, e, "enqueue");
+  h->have_step = true;
+  return CMT_OK;
+}
+
+}  // namespace
+
+// ================================================================================================
+extern "C" {
+
+int cmt_query_sizes(const cmt_config* cfg, size_t* param_bytes, size_t* grad_bytes, size_t* workspace_bytes) {
+  if (!config_ok(cfg, nullptr)) return CMT_EINVAL;
+  cmt_handle tmp;
+  tmp.cfg = *cfg; tmp.prec = cfg->precision; tmp.esz = cfg->precision ? 2 : 4;
+  tmp.Bpm = round_up(cfg->max_batch, 16);
+  build_table(tmp.cfg, tmp.table, tmp.nparams);
+  const size_t ws = layout(&tmp, nullptr);
+  if (param_bytes) *param_bytes = tmp.nparams * 4;
+  if (grad_bytes) *grad_bytes = tmp.nparams * 4;
+  if (workspace_bytes) *workspace_bytes = ws;
+  return CMT_OK;
+}
+
+int cmt_create(const cmt_config* cfg, void* params_dev, void* grads_dev, void* workspace_dev, void* hip_stream,
+               cmt_handle** out) {
+  if (!out) return CMT_EINVAL;
+  *out = nullptr;
+  std::string why;
+  if (!config_ok(cfg, &why)) return CMT_EINVAL;
+  if (!params_dev || !grads_dev || !workspace_dev) return CMT_EINVAL;
+  if (((uintptr_t)params_dev | (uintptr_t)grads_dev | (uintptr_t)workspace_dev) & 255) return CMT_EINVAL;
+  cmt_handle* h = new cmt_handle();
+  h->cfg = *cfg; h->prec = cfg->precision; h->esz = cfg->precision ? 2 : 4;
+  h->st = (hipStream_t)hip_stream;
+  h->params = (float*)params_dev; h->grads = (float*)grads_dev; h->ws = (char*)workspace_dev;
+  h->Bpm = round_up(cfg->max_batch, 16);
+  build_table(h->cfg, h->table, h->nparams);
+  h->ws_bytes = layout(h, h->ws);
+  bind_params(h);
+  hipError_t e = hipHostMalloc((void**)&h->h_loss, 256, hipHostMallocDefault);
+  if (e != hipSuccess) { delete h; return CMT_EHIP; }
+  h->h_flags = (int*)(h->h_loss + 8);
+  h->h_loss[0] = 0.f; h->h_loss[1] = 0.f; *h->h_flags = 0;
+  *out = h;
+  return CMT_OK;
+}
+
+void cmt_destroy(cmt_handle* h) {
+  if (!h) return;
+  if (h->h_loss) (void)hipHostFree(h->h_loss);
+  delete h;
+}
+
+int cmt_param_count(const cmt_handle* h) { return h ? (int)h->table.size() : CMT_EINVAL; }
+
+int cmt_param_info(const cmt_handle* h, int idx, const char** name, int64_t* rows, int64_t* cols, size_t* offset_elems) {
+  if (!h || idx < 0 || idx >= (int)h->table.size()) return CMT_EINVAL;
+  const ParamInfo& p = h->table[idx];
+  if (name) *name = p.name.c_str();
+  if (rows) *rows = p.rows;
+  if (cols) *cols = p.cols;
+  if (offset_elems) *offset_elems = p.off;
+  return CMT_OK;
+}
+
+int cmt_init_params(cmt_handle* h, uint64_t seed, float scale) {
+  if (!h) return CMT_EINVAL;
+  launch_init_uniform(h->params, h->nparams, seed, scale, h->st);
+  refresh_params(h);
+  hipError_t e = hipStreamSynchronize(h->st);
+  if (e != hipSuccess) return hip_fail(h, e, "cmt_init_params");
+  return CMT_OK;
+}
+
+int cmt_set_params(cmt_handle* h, const float* host_src) {
+  if (!h || !host_src) return fail(h, CMT_EINVAL, "null pointer");
+  hipError_t e = hipMemcpyAsync(h->params, host_src, h->nparams * 4, hipMemcpyHostToDevice, h->st);
+  if (e != hipSuccess) return hip_fail(h, e, "cmt_set_params copy");
+  refresh_params(h);
+  e = hipStreamSynchronize(h->st);
+  if (e != hipSuccess) return hip_fail(h, e, "cmt_set_params");
+  return CMT_OK;
+}
+
+int cmt_get_params(cmt_handle* h, float* host_dst) {
+  if (!h || !host_dst) return fail(h, CMT_EINVAL, "null pointer");
+  hipError_t e = hipMemcpyAsync(host_dst, h->params, h->nparams * 4, hipMemcpyDeviceToHost, h->st);
+  if (e == hipSuccess) e = hipStreamSynchronize(h->st);
+  if (e != hipSuccess) return hip_fail(h, e, "cmt_get_params");
+  return CMT_OK;
+}
+
+int cmt_get_grads(cmt_handle* h, float* host_dst) {
+  if (!h || !host_dst) return fail(h, CMT_EINVAL, "null pointer");
+  hipError_t e = hipMemcpyAsync(host_dst, h->grads, h->nparams * 4, hipMemcpyDeviceToHost, h->st);
+  if (e == hipSuccess) e = hipStreamSynchronize(h->st);
+  if (e != hipSuccess) return hip_fail(h, e, "cmt_get_grads");
+  return CMT_OK;
+}
+
+int cmt_train_step_async(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* src_len_dev,
+                         const int32_t* tgt_ids_dev, const int32_t* tgt_len_dev, int32_t B, int32_t S, int32_t T) {
+  if (!h) return CMT_EINVAL;
+  return enqueue_step(h, src_ids_dev, src_len_dev, tgt_ids_dev, tgt_len_dev, B, S, T);
+}
+
+int cmt_fetch_loss(cmt_handle* h, float* loss_host) {
+  if (!h) return CMT_EINVAL;
+  if (!h->have_step) return fail(h, CMT_EINVAL, "no step has been run");
+  hipError_t e = hipStreamSynchronize(h->st);
+  if (e != hipSuccess) return hip_fail(h, e, "cmt_fetch_loss");
+  const int flags = *h->h_flags;
+  if (loss_host) *loss_host = h->h_loss[0];
+  if (flags & 3) return fail(h, CMT_ERANGE, (flags & 1) ? "a token id is outside its vocabulary" : "a length is outside [1, padded length]");
+  if (flags & 4) return fail(h, CMT_ENONFINITE, "the loss is not finite");
+  return CMT_OK;
+}
+
+int cmt_train_step(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* src_len_dev, const int32_t* tgt_ids_dev,
+                   const int32_t* tgt_len_dev, int32_t B, int32_t S, int32_t T, float* loss_host) {
+  const int rc = cmt_train_step_async(h, src_ids_dev, src_len_dev, tgt_ids_dev, tgt_len_dev, B, S, T);
+  if (rc != CMT_OK) return rc;
+  return cmt_fetch_loss(h, loss_host);
+}
+
+int cmt_sgd_update(cmt_handle* h, float lr) {
+  if (!h) return CMT_EINVAL;
+  if (!isfinite(lr)) return fail(h, CMT_EINVAL, "learning rate is not finite");
+  launch_sgd(h->params, h->grads, h->nparams, lr, h->st);
+  refresh_params(h);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(h, e, "cmt_sgd_update");
+  return CMT_OK;
+}
+
+int cmt_padded_batch(const cmt_handle* h) { return h ? h->Bp : CMT_EINVAL; }
+
+int cmt_debug_fetch(cmt_handle* h, const char* name, float* host_dst, size_t bytes) {
+  if (!h || !name || !host_dst) return fail(h, CMT_EINVAL, "null pointer");
+  if (!h->have_step) return fail(h, CMT_EINVAL, "no step has been run");
+  const int H = h->cfg.hidden, E = h->cfg.emb_dim, L = h->cfg.layers;
+  const size_t Bp = h->Bp, S = h->S, T = h->T, BH = Bp * H;
+  const void* src = nullptr; size_t n = 0; bool isT = false;
+  const std::string s(name);
+  if (s == "x_src") { src = h->Xs; n = S * Bp * E; isT = true; }
+  else if (s == "x_tgt") { src = h->Xt; n = T * Bp * E; isT = true; }
+  else if (s == "mask_src") { src = h->mask_s; n = S * Bp; }
+  else if (s == "mask_tgt") { src = h->mask_t; n = T * Bp; }
+  else if (s == "h_s") { src = (L == 1) ? h->Y0 : h->enc[L].Hst + BH * h->esz; n = S * BH; isT = true; }
+  else if (s == "h_t") { src = h->dec[L - 1].Hst + BH * h->esz; n = T * BH; isT = true; }
+  else if (s == "att_a") { src = h->att_a; n = T * Bp * S; }
+  else if (s == "att_cs") { src = h->Cs; n = T * BH; isT = true; }
+  else if (s == "h_o") { src = h->HoBuf + BH * h->esz; n = T * BH; isT = true; }
+  else if (s == "lse") { src = h->lse; n = T * Bp; }
+  else if (s == "nll") { src = h->nll; n = T * Bp; }
+  else return fail(h, CMT_EINVAL, "unknown intermediate name");
+  if (bytes != n * 4) return fail(h, CMT_EINVAL, "size mismatch for the requested intermediate");
+  hipError_t e;
+  if (isT && h->prec) {
+    std::vector<uint16_t> tmp(n);
+    e = hipMemcpyAsync(tmp.data(), src, n * 2, hipMemcpyDeviceToHost, h->st);
+    if (e == hipSuccess) e = hipStreamSynchronize(h->st);
+    if (e != hipSuccess) return hip_fail(h, e, "cmt_debug_fetch");
+    for (size_t i = 0; i < n; ++i) { uint32_t u = ((uint32_t)tmp[i]) << 16; memcpy(&host_dst[i], &u, 4); }
+  } else {
+    e = hipMemcpyAsync(host_dst, src, n * 4, hipMemcpyDeviceToHost, h->st);
+    if (e == hipSuccess) e = hipStreamSynchronize(h->st);
+    if (e != hipSuccess) return hip_fail(h, e, "cmt_debug_fetch");
+  }
+  return CMT_OK;
+}
+
+const char* cmt_last_error(const cmt_handle* h) { return h ? h->err.c_str() : "null handle"; }
+
+}  // extern "C"

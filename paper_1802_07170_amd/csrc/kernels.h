@@ -1,0 +1,124 @@
+// Host-callable launchers of the gfx950 kernels.  `prec` selects the storage type of GEMM
+// operands: 0 = float, 1 = bf16 (raw uint16).  "T*" in comments means that type.
+// All launchers only enqueue work on `st`; none allocates or synchronises.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cmt {
+
+// ---- gemm.hip ----------------------------------------------------------------------------------
+// C[M,N] = A[M,K] * B[N,K]^T (+ bias[N]) (+ previous C when accumulate), both operands with k
+// contiguous.  Writes fp32 to Cf (if non-null) and T to Ct (if non-null), same ldc.
+// K, lda, ldb multiples of 8.
+void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, int M, int N, int K,
+                    float* Cf, void* Ct, int ldc, const float* bias, int accumulate, hipStream_t st);
+// out[C,R] = in[R,C]^T for T matrices (ldin, ldout in elements).
+void launch_transpose(int prec, const void* in, int ldin, void* out, int ldout, int R, int C, hipStream_t st);
+
+// ---- ce.hip ------------------------------------------------------------------------------------
+// Eq. 1 forward, fused: logits tile by tile, never stored.  Ho [M,H] T, Wo [V,H] T, Bo [V] fp32,
+// labels [M] int32.  pmax/psum [M, np] fp32 with np = ce_num_partials(V); zy [M] fp32.
+int ce_num_partials(int V);
+void launch_ce_fwd(int prec, const void* Ho, const void* Wo, const float* Bo, const int32_t* labels,
+                   int M, int V, int H, float* pmax, float* psum, float* zy, hipStream_t st);
+// lse[M], nll[M] (masked), rowscale[M] = mask / n_tok, loss = sum nll / n_tok; flags |= 4 if the loss
+// is not finite.  One launch, deterministic summation order.
+void launch_ce_reduce(const float* pmax, const float* psum, const float* zy, const float* mask, int M, int np,
+                      float* lse, float* nll, float* rowscale, float* loss, int* flags, hipStream_t st);
+// Eq. 1 backward, fused: dz = (softmax(z) - onehot) * rowscale is rebuilt per tile from lse and used
+// as a matrix-core operand straight from LDS.
+//   dHo_part [nsplit, M, H] fp32 partial sums over vocabulary ranges (ce_bwd_nsplit(M, V) of them)
+//   dWo [V,H] fp32, dBo [V] fp32 written in full.
+// WoT [H, V] and HoT [H, M] are the transposed operand copies.
+int ce_bwd_nsplit(int M, int V);
+void launch_ce_bwd_dh(int prec, const void* Ho, const void* Wo, const void* WoT, const float* Bo,
+                      const int32_t* labels, const float* lse, const float* rowscale,
+                      int M, int V, int H, int nsplit, float* dHo_part, hipStream_t st);
+void launch_ce_bwd_dw(int prec, const void* Ho, const void* HoT, int ldhot, const void* Wo, const float* Bo,
+                      const int32_t* labels, const float* lse, const float* rowscale,
+                      int M, int V, int H, float* dWo, float* dBo, hipStream_t st);
+
+// ---- step.hip ----------------------------------------------------------------------------------
+// One recurrent step of one LSTM layer (or of both directions of the bottom encoder layer when
+// ndir = 2): gates = Gx + [x; h_prev] W^T, then the cell, fused.
+struct LstmFwdDir {
+  const void* x;  int ldx;  int Kx;     // per-step input segment (T*, [Bp, Kx]); Kx = 0 if none
+  const void* hprev; int ldh;           // previous state (T*, [Bp, Hh])
+  const void* W;  int ldw;  int wx_off, wh_off;   // weights T* [4Hh, ldw]; column offsets of the segments
+  const float* gx; int ldgx;            // batched input pre-activations incl. bias [Bp, 4Hh], or null
+  const float* bias;                    // [4Hh], used when gx is null
+  const float* cprev;                   // [Bp, Hh]
+  const float* mask;                    // [Bp] 1 = valid step
+  void* hnext; float* cnext;            // [Bp, Hh]
+  float* gsave;                         // [Bp, 4Hh] gate activations kept for the backward pass
+  void* ycat; int ldy;                  // optional second copy of h (T*, row pitch ldy), or null
+};
+void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh, hipStream_t st);
+
+// out[Bp, N] = [a0; a1] W^T with an epilogue.  W rows are output columns; w0_off / w1_off are the
+// column offsets inside a weight row that pair with the two activation segments.
+struct StepGemm {
+  const void* a0; int lda0; int K0; int w0_off;
+  const void* a1; int lda1; int K1; int w1_off;
+  const void* W; int ldw;
+  int N;
+  int mode;            // 0: tanh -> outT (T*) [Bp,N]          (attentional layer, Eq. 7)
+                       // 1: fp32 outputs: columns < nsplit go to out0[b,n], the others to out1[b,n-nsplit];
+                       //    acc0 / acc1 = 1 adds to what is there, 0 overwrites
+  void* outT; int ldo;
+  float* out0; int ld0; int nsplit; int acc0;
+  float* out1; int ld1; int acc1;
+};
+void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st);
+
+// Cell backward for one step of one layer: builds dgates (T*) from the incoming state gradients.
+struct LstmBwdPoint {
+  const float* dy; int lddy;           // gradient arriving at this step's output [Bp, Hh] (or null)
+  float* dh;                           // [Bp,Hh] in: d state after the step; out: (1-m) * total (pass-through)
+  float* dc;                           // [Bp,Hh] in/out cell-state gradient
+  const float* gsave;                  // [Bp,4Hh]
+  const float* cprev; const float* cnext;  // [Bp,Hh]
+  const float* mask;                   // [Bp]
+  void* dg;                            // T* [Bp,4Hh]
+};
+void launch_lstm_bwd_point(int prec, const LstmBwdPoint& p, int Bp, int Hh, hipStream_t st);
+
+// Attention forward for one decoder step (Eq. 3-5 with the key hoist K_i = W_a^T H_s^i):
+// s_i = K_i . H_t, softmax over i < src_len[b], C_s = sum a_i H_s^i.
+void launch_att_fwd(int prec, const void* Kmat, const void* Hs, const void* Ht, const int32_t* src_len,
+                    int S, int Bp, int H, float* a /*[Bp,S]*/, void* Cs /*T* [Bp,H]*/, hipStream_t st);
+// Attention backward for one step: da_i = dCs . H_s^i, ds = a (da - sum a da), dHt += sum ds_i K_i.
+void launch_att_bwd(int prec, const void* Kmat, const void* Hs, const float* dCs, const float* a,
+                    const int32_t* src_len, int S, int Bp, int H, float* ds /*[Bp,S]*/, float* dHt /*[Bp,H]*/, hipStream_t st);
+// After the decoder loop: dHs_ctx[i,b,:] = sum_j a[j,b,i] dCs[j,b,:], dK[i,b,:] = sum_j ds[j,b,i] Ht[j,b,:].
+void launch_att_deferred(int prec, const float* a, const float* ds, const float* dCs, const void* Ht, int ldht,
+                         int S, int T, int Bp, int H, float* dHs, void* dK, hipStream_t st);
+// dpre = (dHo_ce + dHo_feed) * (1 - Ho^2) -> T*; dHo_feed may be null.
+void launch_tanh_bwd(int prec, const float* dHo_ce, const float* dHo_feed, const void* Ho, void* dpre,
+                     int n, hipStream_t st);
+
+// ---- misc.hip ----------------------------------------------------------------------------------
+// Embedding gather + masks + input validation (flags |= 1 bad id, |= 2 bad length).
+// ids [B, L] row-major; out[t, b, :] = table[shift ? (t == 0 ? bos : ids[b, t-1]) : ids[b, t]] as T;
+// rows b >= B are zero.  mask[t, b] = t < len[b].  labels[t, b] = ids[b, t] (only when shift).
+void launch_gather(int prec, const void* table, int vocab, int E, const int32_t* ids, const int32_t* len,
+                   int B, int Bp, int L, int shift, int bos, void* out, float* mask, int32_t* tok,
+                   int32_t* labels, int32_t* len_p, int* flags, hipStream_t st);
+// Dense embedding gradient: dE[V,E] = 0, then row id gets the sum of dX rows of its occurrences,
+// added in ascending position order by the block of the first occurrence (no atomics).
+void launch_embed_scatter(const float* dX, const int32_t* tok, int n, int V, int E, float* dE, hipStream_t st);
+void launch_fill_f32(float* p, size_t n, float v, hipStream_t st);
+void launch_fill_T(int prec, void* p, size_t n, hipStream_t st);      // zeros
+void launch_cast(int prec, const float* src, void* dst, size_t n, hipStream_t st);   // fp32 -> T
+// 2-D copies with pitches (elements): fp32 -> fp32, T -> T.
+void launch_copy2d_f32(const float* src, int lds, float* dst, int ldd, int rows, int cols, hipStream_t st);
+void launch_copy2d_T(int prec, const void* src, int lds, void* dst, int ldd, int rows, int cols, hipStream_t st);
+void launch_add_f32(float* dst, const float* src, size_t n, hipStream_t st);          // dst += src
+void launch_sum_parts(const float* parts, int nparts, size_t n, float* out, hipStream_t st);
+// db[n] = sum_m dG[m, n] over M rows of a T matrix [M, N].
+void launch_colsum(int prec, const void* dG, int M, int N, float* scratch /*[16*N]*/, float* db, hipStream_t st);
+void launch_sgd(float* p, const float* g, size_t n, float lr, hipStream_t st);
+void launch_init_uniform(float* p, size_t n, uint64_t seed, float scale, hipStream_t st);
+
+}  // namespace cmt

@@ -1,0 +1,237 @@
+// Memory-bound helpers of the training step: embedding gather (the paper's EmbeddingLayer
+// forward) with masks and input validation, the deterministic embedding-gradient scatter (the
+// paper's `firstOccurs` idea: the first occurrence of a word owns its gradient row), SGD, the
+// counter-based initialiser, casts, copies and small reductions.
+#include "common.h"
+#include "kernels.h"
+
+namespace cmt {
+
+// one workgroup per (position t, sentence b)
+template <typename T>
+__global__ __launch_bounds__(128) void gather_kernel(const T* __restrict__ table, int vocab, int E,
+                                                     const int32_t* __restrict__ ids, const int32_t* __restrict__ len,
+                                                     int B, int Bp, int L, int shift, int bos, T* __restrict__ out,
+                                                     float* __restrict__ mask, int32_t* __restrict__ tok,
+                                                     int32_t* __restrict__ labels, int32_t* __restrict__ len_p,
+                                                     int* __restrict__ flags) {
+  const int t = blockIdx.x, b = blockIdx.y;
+  const size_t row = (size_t)t * Bp + b;
+  constexpr int EPC = 16 / sizeof(T);
+  uint4* o = reinterpret_cast<uint4*>(out + row * E);
+  const int nch = E / EPC;
+  if (b >= B) {
+    for (int c = threadIdx.x; c < nch; c += 128) o[c] = make_uint4(0, 0, 0, 0);
+    if (threadIdx.x == 0) {
+      mask[row] = 0.f; tok[row] = -1;
+      if (labels) labels[row] = 0;
+      if (t == 0) len_p[b] = 0;
+    }
+    return;
+  }
+  int n = len[b];
+  if (n < 1 || n > L) { if (threadIdx.x == 0) atomicOr(flags, 2); n = n < 1 ? 1 : L; }
+  int id = shift ? (t == 0 ? bos : ids[(size_t)b * L + t - 1]) : ids[(size_t)b * L + t];
+  const bool valid = t < n;
+  if (id < 0 || id >= vocab) { if (valid && threadIdx.x == 0) atomicOr(flags, 1); id = 0; }
+  const uint4* src = reinterpret_cast<const uint4*>(table + (size_t)id * E);
+  for (int c = threadIdx.x; c < nch; c += 128) o[c] = src[c];
+  if (threadIdx.x == 0) {
+    mask[row] = valid ? 1.f : 0.f;
+    tok[row] = valid ? id : -1;
+    if (labels) {
+      int y = ids[(size_t)b * L + t];
+      if (y < 0 || y >= vocab) { if (valid) atomicOr(flags, 1); y = 0; }
+      labels[row] = y;
+    }
+    if (t == 0) len_p[b] = n;
+  }
+}
+
+void launch_gather(int prec, const void* table, int vocab, int E, const int32_t* ids, const int32_t* len,
+                   int B, int Bp, int L, int shift, int bos, void* out, float* mask, int32_t* tok,
+                   int32_t* labels, int32_t* len_p, int* flags, hipStream_t st) {
+  dim3 grid(L, Bp);
+  if (prec) hipLaunchKernelGGL(gather_kernel<bf16_t>, grid, dim3(128), 0, st, (const bf16_t*)table, vocab, E, ids, len, B, Bp, L,
+                               shift, bos, (bf16_t*)out, mask, tok, labels, len_p, flags);
+  else hipLaunchKernelGGL(gather_kernel<float>, grid, dim3(128), 0, st, (const float*)table, vocab, E, ids, len, B, Bp, L,
+                          shift, bos, (float*)out, mask, tok, labels, len_p, flags);
+}
+
+// One workgroup per position p.  If no earlier position holds the same id, this workgroup sums the
+// gradient rows of every occurrence q >= p in ascending q and stores the row; otherwise it exits.
+constexpr int SCAT_MAXC = 8;     // columns per thread: E <= 256 * 8
+__global__ __launch_bounds__(256) void embed_scatter_kernel(const float* __restrict__ dX, const int32_t* __restrict__ tok,
+                                                            int n, int E, float* __restrict__ dE) {
+  __shared__ int s_found;
+  __shared__ int s_list[256];
+  __shared__ int s_wcnt[4];
+  const int p = blockIdx.x, t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const int id = tok[p];
+  if (id < 0) return;
+  if (t == 0) s_found = 0;
+  __syncthreads();
+  for (int q = t; q < p; q += 256)
+    if (tok[q] == id) s_found = 1;
+  __syncthreads();
+  if (s_found) return;
+  float acc[SCAT_MAXC];
+#pragma unroll
+  for (int c = 0; c < SCAT_MAXC; ++c) acc[c] = 0.f;
+  for (int base = p; base < n; base += 256) {
+    const int q = base + t;
+    const bool match = q < n && tok[q] == id;
+    const unsigned long long bal = __ballot(match);
+    if (lane == 0) s_wcnt[w] = __popcll(bal);
+    __syncthreads();
+    int off = 0;
+    for (int k = 0; k < w; ++k) off += s_wcnt[k];
+    const int total = s_wcnt[0] + s_wcnt[1] + s_wcnt[2] + s_wcnt[3];
+    if (match) s_list[off + __popcll(bal & ((1ull << lane) - 1ull))] = q;
+    __syncthreads();
+    for (int k = 0; k < total; ++k) {
+      const float* r = dX + (size_t)s_list[k] * E;
+#pragma unroll
+      for (int c = 0; c < SCAT_MAXC; ++c)
+        if (t + 256 * c < E) acc[c] += r[t + 256 * c];
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int c = 0; c < SCAT_MAXC; ++c)
+    if (t + 256 * c < E) dE[(size_t)id * E + t + 256 * c] = acc[c];
+}
+
+__global__ __launch_bounds__(256) void fill_f32_kernel(float* __restrict__ p, size_t n, float v) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < n; i += stride) p[i] = v;
+}
+static inline int grid_for(size_t n, int per_block = 256) {
+  size_t g = (n + per_block - 1) / per_block;
+  return (int)(g > 65536 ? 65536 : (g < 1 ? 1 : g));
+}
+void launch_fill_f32(float* p, size_t n, float v, hipStream_t st) {
+  if (n == 0) return;
+  hipLaunchKernelGGL(fill_f32_kernel, dim3(grid_for(n)), dim3(256), 0, st, p, n, v);
+}
+void launch_fill_T(int prec, void* p, size_t n, hipStream_t st) {
+  // zero bits are zero in both types; fill as 32-bit words (n even for bf16 by construction of the callers)
+  const size_t words = prec ? (n + 1) / 2 : n;
+  launch_fill_f32((float*)p, words, 0.f, st);
+}
+
+void launch_embed_scatter(const float* dX, const int32_t* tok, int n, int V, int E, float* dE, hipStream_t st) {
+  launch_fill_f32(dE, (size_t)V * E, 0.f, st);
+  hipLaunchKernelGGL(embed_scatter_kernel, dim3(n), dim3(256), 0, st, dX, tok, n, E, dE);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void copy2d_kernel(const T* __restrict__ s, int lds, T* __restrict__ d, int ldd, int rows,
+                                                     int cols) {
+  const size_t n = (size_t)rows * cols;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < n; i += stride) {
+    const size_t r = i / cols, c = i - r * cols;
+    d[r * ldd + c] = s[r * lds + c];
+  }
+}
+void launch_copy2d_f32(const float* src, int lds, float* dst, int ldd, int rows, int cols, hipStream_t st) {
+  if (rows <= 0 || cols <= 0) return;
+  hipLaunchKernelGGL(copy2d_kernel<float>, dim3(grid_for((size_t)rows * cols)), dim3(256), 0, st, src, lds, dst, ldd, rows, cols);
+}
+void launch_copy2d_T(int prec, const void* src, int lds, void* dst, int ldd, int rows, int cols, hipStream_t st) {
+  if (rows <= 0 || cols <= 0) return;
+  if (prec) hipLaunchKernelGGL(copy2d_kernel<bf16_t>, dim3(grid_for((size_t)rows * cols)), dim3(256), 0, st, (const bf16_t*)src,
+                               lds, (bf16_t*)dst, ldd, rows, cols);
+  else launch_copy2d_f32((const float*)src, lds, (float*)dst, ldd, rows, cols, st);
+}
+
+__global__ __launch_bounds__(256) void cast_bf16_kernel(const float* __restrict__ s, bf16_t* __restrict__ d, size_t n) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < n; i += stride) d[i] = f2bf(s[i]);
+}
+void launch_cast(int prec, const float* src, void* dst, size_t n, hipStream_t st) {
+  if (n == 0) return;
+  if (prec) hipLaunchKernelGGL(cast_bf16_kernel, dim3(grid_for(n)), dim3(256), 0, st, src, (bf16_t*)dst, n);
+  else hipLaunchKernelGGL(copy2d_kernel<float>, dim3(grid_for(n)), dim3(256), 0, st, src, 0, (float*)dst, 0, 1, (int)n);
+}
+
+__global__ __launch_bounds__(256) void add_f32_kernel(float* __restrict__ d, const float* __restrict__ s, size_t n) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < n; i += stride) d[i] += s[i];
+}
+void launch_add_f32(float* dst, const float* src, size_t n, hipStream_t st) {
+  if (n == 0) return;
+  hipLaunchKernelGGL(add_f32_kernel, dim3(grid_for(n)), dim3(256), 0, st, dst, src, n);
+}
+
+__global__ __launch_bounds__(256) void sum_parts_kernel(const float* __restrict__ parts, int nparts, size_t n,
+                                                        float* __restrict__ out) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < n; i += stride) {
+    float a = 0.f;
+    for (int p = 0; p < nparts; ++p) a += parts[(size_t)p * n + i];
+    out[i] = a;
+  }
+}
+void launch_sum_parts(const float* parts, int nparts, size_t n, float* out, hipStream_t st) {
+  if (n == 0) return;
+  hipLaunchKernelGGL(sum_parts_kernel, dim3(grid_for(n)), dim3(256), 0, st, parts, nparts, n, out);
+}
+
+// column sums of a T matrix [M, N]: 64 columns x 4 row groups per block, 16 row splits over grid.y
+constexpr int COLSUM_SPLITS = 16;
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ G, int M, int N, float* __restrict__ parts) {
+  __shared__ float red[4][64];
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63), rg = threadIdx.x >> 6;
+  const int rows_per = (M + COLSUM_SPLITS - 1) / COLSUM_SPLITS;
+  const int r0 = blockIdx.y * rows_per, r1 = min(M, r0 + rows_per);
+  float a = 0.f;
+  if (c < N)
+    for (int r = r0 + rg; r < r1; r += 4) a += to_f<T>(G[(size_t)r * N + c]);
+  red[rg][threadIdx.x & 63] = a;
+  __syncthreads();
+  if (rg == 0 && c < N) parts[(size_t)blockIdx.y * N + c] = red[0][threadIdx.x] + red[1][threadIdx.x] + red[2][threadIdx.x] + red[3][threadIdx.x];
+}
+void launch_colsum(int prec, const void* dG, int M, int N, float* scratch, float* db, hipStream_t st) {
+  dim3 grid((N + 63) / 64, COLSUM_SPLITS);
+  if (prec) hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)dG, M, N, scratch);
+  else hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, st, (const float*)dG, M, N, scratch);
+  launch_sum_parts(scratch, COLSUM_SPLITS, (size_t)N, db, st);
+}
+
+__global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ p, const float* __restrict__ g, size_t n, float lr) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < n; i += stride) p[i] = p[i] - lr * g[i];
+}
+void launch_sgd(float* p, const float* g, size_t n, float lr, hipStream_t st) {
+  if (n == 0) return;
+  hipLaunchKernelGGL(sgd_kernel, dim3(grid_for(n)), dim3(256), 0, st, p, g, n, lr);
+}
+
+// SplitMix64 of (seed + element index); top 24 bits -> uniform [-scale, scale)
+__global__ __launch_bounds__(256) void init_uniform_kernel(float* __restrict__ p, size_t n, uint64_t seed, float scale) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < n; i += stride) {
+    uint64_t x = seed + (uint64_t)i + 0x9E3779B97F4A7C15ull;
+    x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+    x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+    x = x ^ (x >> 31);
+    const float u = (float)(uint32_t)(x >> 40);
+    p[i] = (u * (2.0f / 16777216.0f) - 1.0f) * scale;
+  }
+}
+void launch_init_uniform(float* p, size_t n, uint64_t seed, float scale, hipStream_t st) {
+  if (n == 0) return;
+  hipLaunchKernelGGL(init_uniform_kernel, dim3(grid_for(n)), dim3(256), 0, st, p, n, seed, scale);
+}
+
+}  // namespace cmt
