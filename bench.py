@@ -1,0 +1,121 @@
+"""Throughput of one full training step (forward + backward) on one MI355X.
+
+python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload medium] [--no-cpu-baseline]
+
+Prints ONE JSON line: target tokens/s of the whole step with inputs resident in HBM, the roofline
+figures of the dominant kernel (measured live with HIP events), and the CPU oracle timed on a
+bounded sample of the same workload."""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from paper_1802_07170_amd import inputs as I  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+MFMA_FP32_PEAK_TFLOPS = 157.3
+
+
+def gemm_flops_per_step(cfg, B, S, T):
+    """Algorithmic multiply-add flops (x2) of one forward+backward step on the padded batch:
+    per position, forward, with E = emb, H = hidden; backward = 2x forward (data + weight grads)."""
+    E, H, L, V = cfg["emb"], cfg["hidden"], cfg["layers"], cfg["tgt_vocab"]
+    Hd = H // 2
+    enc = 2 * 2 * 4 * Hd * (E + Hd) + (L - 1) * 2 * 4 * H * 2 * H
+    dec = 2 * 4 * H * (E + 2 * H) + (L - 1) * 2 * 4 * H * 2 * H
+    att = 2 * H * H + 4 * S * H + 2 * H * 2 * H
+    out = 2 * H * V
+    return 3.0 * (B * S * enc + B * T * (dec + att + out))
+
+
+def cpu_baseline(c, cfg, params, batch, budget_sentences):
+    """The fp64 oracle, as it stands, on the first sentences of the same batch."""
+    from oracle import nmt_oracle as O
+    src, sl, tgt, tl = batch
+    n = min(budget_sentences, src.shape[0])
+    S, T = int(sl[:n].max()), int(tl[:n].max())
+    sub = (src[:n, :S], sl[:n], tgt[:n, :T], tl[:n])
+    t0 = time.time()
+    O.train_step(cfg, params, *sub)
+    dt = time.time() - t0
+    return dict(value=float(tl[:n].sum() / dt), unit="tokens/s", cores=int(os.cpu_count() if not os.environ.get("OMP_NUM_THREADS") else int(os.environ["OMP_NUM_THREADS"])),
+                kind="oracle", sample=f"first {n} sentences of the batch ({int(tl[:n].sum())} target tokens), one step, {dt:.1f} s")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="medium", choices=list(I.CONFIGS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sentences", type=int, default=8)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives are built); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1802_07170_amd import binding
+
+    c = I.CONFIGS[args.workload]
+    cfg = I.model_cfg(c)
+    params = I.make_params(cfg, c["seed"])
+    batch = I.make_batch(c)
+    src, sl, tgt, tl = batch
+    B, S = src.shape
+    T = tgt.shape[1]
+    n_tok, n_src = int(tl.sum()), int(sl.sum())
+    tr = binding.Trainer(cfg, B, S, T, precision=c["precision"])
+    tr.set_params(I.flatten(params, cfg))
+    dev = tr.upload_batch(*batch)
+
+    for _ in range(args.warmup):
+        tr.train_step_async(dev)
+    loss = tr.fetch_loss()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        tr.train_step_async(dev)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    loss = tr.fetch_loss()
+    ms = dt / args.steps * 1e3
+    flops = gemm_flops_per_step(cfg, B, S, T)
+
+    out = {
+        "metric": "target tokens/sec per train step (fwd+bwd) on 1 MI355X",
+        "value": n_tok / (dt / args.steps), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if c["precision"] else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: L={cfg['layers']} H=E={cfg['hidden']} V={cfg['tgt_vocab']} B={B} S={S} T={T}",
+                   "target_tokens": n_tok, "source_tokens": n_src, "loss": loss},
+        "source_tokens_per_s": n_src / (dt / args.steps),
+        "gemm_tflops_padded": flops / (dt / args.steps) / 1e12,
+        "mfma_peak_frac_whole_step": flops / (dt / args.steps) / 1e12 / (MFMA_BF16_PEAK_TFLOPS if c["precision"] else MFMA_FP32_PEAK_TFLOPS),
+    }
+    # dominant kernel of the step (largest share of kernel time in the rocprofv3 trace under
+    # profiles/): the fused decoder LSTM step.  It is bound by streaming the layer's weights.
+    us, nbytes = tr.time_kernel("lstm_fwd_dec", 400)
+    achieved = nbytes / (us * 1e-6) / 1e9
+    out["roofline"] = {"kernel": "lstm_fwd_kernel (decoder layer step: gate GEMM + fused cell)", "bound": "hbm",
+                       "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                       "traffic": None, "us_per_launch": us, "algorithmic_bytes_per_launch": nbytes}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(c, cfg, params, batch, args.cpu_sentences)
+    tr.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -113,6 +113,13 @@ int cmt_debug_fetch(cmt_handle* h, const char* name, float* host_dst, size_t byt
 /* Padded batch pitch Bp used by cmt_debug_fetch for the last step. */
 int cmt_padded_batch(const cmt_handle* h);
 
+/* Measurement aid: launches one kernel of the last step `iters` times back to back on the handle's
+ * stream, with the operands that step used (results are rewritten with identical values), timed
+ * by HIP events.  Names: "lstm_fwd_dec" = the fused decoder LSTM step (gate GEMM + cell), cycling
+ * over the decoder layers.  Returns the mean microseconds per launch and the algorithmic bytes one
+ * launch moves (weights + activations + state read once, outputs written once).  Synchronises. */
+int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_launch, double* algo_bytes);
+
 const char* cmt_last_error(const cmt_handle* h);
 
 #ifdef __cplusplus

@@ -17,7 +17,7 @@ EXPORTS = [
     "cmt_query_sizes", "cmt_create", "cmt_destroy", "cmt_param_count", "cmt_param_info",
     "cmt_init_params", "cmt_set_params", "cmt_get_params", "cmt_train_step", "cmt_train_step_async",
     "cmt_fetch_loss", "cmt_get_grads", "cmt_sgd_update", "cmt_debug_fetch", "cmt_padded_batch",
-    "cmt_last_error",
+    "cmt_time_kernel", "cmt_last_error",
 ]
 
 
@@ -65,6 +65,7 @@ def load_library():
     lib.cmt_sgd_update.argtypes = [vp, C.c_float]
     lib.cmt_debug_fetch.argtypes = [vp, C.c_char_p, vp, sz]
     lib.cmt_padded_batch.argtypes = [vp]
+    lib.cmt_time_kernel.argtypes = [vp, C.c_char_p, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_double)]
     lib.cmt_last_error.argtypes = [vp]
     lib.cmt_last_error.restype = C.c_char_p
     for name in EXPORTS:
@@ -179,6 +180,12 @@ class Trainer:
 
     def sgd_update(self, lr):
         self._check(self.lib.cmt_sgd_update(self.h, lr))
+
+    def time_kernel(self, name, iters):
+        """(microseconds per launch, algorithmic bytes per launch) of one kernel of the last step."""
+        us, nbytes = C.c_float(), C.c_double()
+        self._check(self.lib.cmt_time_kernel(self.h, name.encode(), iters, C.byref(us), C.byref(nbytes)))
+        return us.value, nbytes.value
 
     def padded_batch(self):
         return self.lib.cmt_padded_batch(self.h)

@@ -40,6 +40,8 @@ struct LD {
   char* dGT = nullptr;               // T [4Hh, Lmax*Bp]
   char* HstT = nullptr;              // T [Hh, (Lmax+1)*Bp]
   float* dh = nullptr; float* dc = nullptr;   // [Bp, Hh]
+  float* part = nullptr;             // [8][Bp][4Hh] forward partial planes (k split over workgroups)
+  float* bwdp = nullptr;             // [8][Bp][2Hh] backward step-GEMM planes
 };
 
 struct Bump {
@@ -84,10 +86,10 @@ struct cmt_handle {
   // target side
   char* Xt = nullptr; float* mask_t = nullptr; int32_t* tok_t = nullptr; int32_t* labels = nullptr; int32_t* len_t = nullptr;
   char* HoBuf = nullptr; char* HoBufT = nullptr; char* Cs = nullptr; char* CsT = nullptr;
-  float* att_a = nullptr; float* att_ds = nullptr; float* dCs = nullptr;
+  float* att_a = nullptr; float* att_ds = nullptr; float* dCs = nullptr; float* dots = nullptr;
   char* dPre = nullptr; char* dPreT = nullptr;
   float* dHoCE = nullptr; float* dHoPart = nullptr;
-  float* dHt = nullptr; float* dHoFeed = nullptr; float* dxl = nullptr;
+  float* dHt = nullptr; float* wcp = nullptr;
   float* dXt = nullptr; char* XtT = nullptr;
   float *pmax = nullptr, *psum = nullptr, *zy = nullptr, *lse = nullptr, *nll = nullptr, *rowscale = nullptr;
   float* loss = nullptr; int* flags = nullptr; float* colscr = nullptr;
@@ -161,6 +163,8 @@ size_t layout(cmt_handle* h, char* base) {
     d.HstT = a.take((M + Bp) * Hh * esz);
     d.dh = (float*)a.take((size_t)Bp * Hh * 4);
     d.dc = (float*)a.take((size_t)Bp * Hh * 4);
+    d.part = (float*)a.take((size_t)8 * Bp * 4 * Hh * 4);
+    d.bwdp = (float*)a.take((size_t)8 * Bp * 2 * Hh * 4);
   };
   h->enc.assign(L + 1, LD());
   h->dec.assign(L, LD());
@@ -187,11 +191,12 @@ size_t layout(cmt_handle* h, char* base) {
   h->Cs = a.take(Mt * H * esz); h->CsT = a.take(Mt * H * esz);
   h->att_a = (float*)a.take(Mt * Sm * 4); h->att_ds = (float*)a.take(Mt * Sm * 4);
   h->dCs = (float*)a.take(Mt * H * 4);
+  h->dots = (float*)a.take((size_t)Bp * Sm * 4);
   h->dPre = a.take(Mt * H * esz); h->dPreT = a.take(Mt * H * esz);
   h->dHoCE = (float*)a.take(Mt * H * 4);
   h->dHoPart = (float*)a.take((size_t)16 * Mt * H * 4);
-  h->dHt = (float*)a.take((size_t)Bp * H * 4); h->dHoFeed = (float*)a.take((size_t)Bp * H * 4);
-  h->dxl = (float*)a.take((size_t)Bp * H * 4);
+  h->dHt = (float*)a.take((size_t)Bp * H * 4);
+  h->wcp = (float*)a.take((size_t)8 * Bp * 2 * H * 4);
   h->dXt = (float*)a.take(Mt * E * 4);
   const int np = ce_num_partials(c.tgt_vocab);
   h->pmax = (float*)a.take(Mt * np * 4); h->psum = (float*)a.take(Mt * np * 4);
@@ -243,31 +248,33 @@ int hip_fail(cmt_handle* h, hipError_t e, const char* what) {
 // the schedule
 // ------------------------------------------------------------------------------------------------
 void run_lstm_layer_bwd(cmt_handle* h, LD& d, int Lsteps, const float* mask, const float* dY, int lddy, int dy_col,
-                        bool reverse_dir, int wt_row0, int nrows, float* dx_out /*per-step, or null*/,
-                        float* dh_buf, float* dc_buf) {
-  // generic helper used by the encoder layers: loops over the steps in the reverse of the
-  // processing order; per step the cell backward, then dh_prev += dgates * W_h.
+                        bool reverse_dir, float* dh_buf, float* dc_buf) {
+  // encoder layers: loops over the steps in the reverse of the processing order; per step the cell
+  // backward, then the recurrent part of d state = dgates * W_h as planes for the next step.
   const int p = h->prec, Bp = h->Bp, Hh = d.Hh;
   const size_t esz = h->esz;
   hipStream_t st = h->st;
+  const int kb = step_kblocks(p, Hh, 4 * Hh, Bp);
+  const size_t pstride = (size_t)Bp * Hh;
   for (int k = 0; k < Lsteps; ++k) {
     const int t = reverse_dir ? k : Lsteps - 1 - k;
     const int slot_prev = reverse_dir ? t + 1 : t, slot_next = reverse_dir ? t : t + 1;
     LstmBwdPoint q;
-    q.dy = dY ? dY + (size_t)t * Bp * lddy + dy_col : nullptr; q.lddy = lddy;
+    q.dy = Planes{dY + (size_t)t * Bp * lddy, lddy, 1, 0}; q.dy_col = dy_col;
+    q.dhrec = Planes{d.bwdp, Hh, k == 0 ? 0 : kb, pstride}; q.dhrec_col = 0;
     q.dh = dh_buf; q.dc = dc_buf;
     q.gsave = d.Gs + (size_t)t * Bp * 4 * Hh;
     q.cprev = d.Cst + (size_t)slot_prev * Bp * Hh; q.cnext = d.Cst + (size_t)slot_next * Bp * Hh;
     q.mask = mask + (size_t)t * Bp;
     q.dg = d.dG + (size_t)t * Bp * 4 * Hh * esz;
     launch_lstm_bwd_point(p, q, Bp, Hh, st);
+    if (k + 1 == Lsteps) break;                      // the initial encoder state is a constant
     StepGemm g{};
     g.a0 = q.dg; g.lda0 = 4 * Hh; g.K0 = 4 * Hh; g.w0_off = 0;
     g.a1 = nullptr; g.lda1 = 0; g.K1 = 0; g.w1_off = 0;
-    g.W = d.Wt + (size_t)wt_row0 * 4 * Hh * esz; g.ldw = 4 * Hh;
-    g.N = nrows; g.mode = 1;
-    g.out0 = dx_out; g.ld0 = Hh; g.nsplit = dx_out ? nrows - Hh : 0; g.acc0 = 0;
-    g.out1 = dh_buf; g.ld1 = Hh; g.acc1 = 1;
+    g.W = d.Wt + (size_t)d.Kin * 4 * Hh * esz; g.ldw = 4 * Hh;
+    g.N = Hh; g.mode = 1;
+    g.out = d.bwdp; g.ldout = Hh; g.plane_stride = pstride;
     launch_step_gemm(p, g, Bp, st);
   }
 }
@@ -286,6 +293,27 @@ void weight_grads(cmt_handle* h, LD& d, int Lsteps, const std::vector<std::pair<
     col += seg_k[i];
   }
   launch_colsum(p, d.dG, M, 4 * Hh, h->colscr, h->grads + d.b_off, st);
+}
+
+// forward step j of decoder layer l (layer 0 takes [H_o^{<j-1>}; h] per step, its embedding part is pre-batched)
+void dec_lstm_fwd(cmt_handle* h, int l, int j) {
+  const cmt_config& c = h->cfg;
+  const int E = c.emb_dim, H = c.hidden, Bp = h->Bp;
+  const size_t esz = h->esz, BH = (size_t)Bp * H;
+  LD& e = h->dec[l];
+  LstmFwdDir d;
+  if (l == 0) {
+    d.x = h->HoBuf + j * BH * esz; d.ldx = H; d.Kx = H; d.wx_off = E; d.wh_off = E + H;
+    d.gx = e.Gx + (size_t)j * Bp * 4 * H; d.ldgx = 4 * H; d.bias = nullptr; d.ldw = E + 2 * H;
+  } else {
+    d.x = h->dec[l - 1].Hst + (j + 1) * BH * esz; d.ldx = H; d.Kx = H; d.wx_off = 0; d.wh_off = H;
+    d.gx = nullptr; d.ldgx = 0; d.bias = h->params + e.b_off; d.ldw = 2 * H;
+  }
+  d.hprev = e.Hst + j * BH * esz; d.ldh = H; d.W = e.W;
+  d.cprev = e.Cst + j * BH; d.mask = h->mask_t + (size_t)j * Bp;
+  d.hnext = e.Hst + (j + 1) * BH * esz; d.cnext = e.Cst + (j + 1) * BH;
+  d.gsave = e.Gs + (size_t)j * Bp * 4 * H; d.ycat = nullptr; d.ldy = 0; d.part = e.part;
+  launch_lstm_fwd(h->prec, &d, 1, Bp, H, h->st);
 }
 
 int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, const int32_t* tgt_ids,
@@ -332,7 +360,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       d[i].cprev = e.Cst + sp * BHd; d[i].mask = h->mask_s + (size_t)t * Bp;
       d[i].hnext = e.Hst + sn * BHd * esz; d[i].cnext = e.Cst + sn * BHd;
       d[i].gsave = e.Gs + (size_t)t * Bp * 4 * Hd;
-      d[i].ycat = h->Y0 + ((size_t)t * BH + (i ? Hd : 0)) * esz; d[i].ldy = H;
+      d[i].ycat = h->Y0 + ((size_t)t * BH + (i ? Hd : 0)) * esz; d[i].ldy = H; d[i].part = e.part;
     }
     launch_lstm_fwd(p, d, 2, Bp, Hd, st);
   }
@@ -350,7 +378,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       d.gx = e.Gx + (size_t)t * Bp * 4 * H; d.ldgx = 4 * H; d.bias = nullptr;
       d.cprev = e.Cst + t * BH; d.mask = h->mask_s + (size_t)t * Bp;
       d.hnext = e.Hst + (t + 1) * BH * esz; d.cnext = e.Cst + (t + 1) * BH;
-      d.gsave = e.Gs + (size_t)t * Bp * 4 * H; d.ycat = nullptr; d.ldy = 0;
+      d.gsave = e.Gs + (size_t)t * Bp * 4 * H; d.ycat = nullptr; d.ldy = 0; d.part = e.part;
       launch_lstm_fwd(p, &d, 1, Bp, H, st);
     }
     Yprev = e.Hst + BH * esz;
@@ -378,29 +406,15 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     launch_gemm_nt(p, h->Xt, E, d0.W, E + 2 * H, Mt, 4 * H, E, d0.Gx, nullptr, 4 * H, P + d0.b_off, 0, st);
     launch_fill_T(p, h->HoBuf, BH, st);
     for (int j = 0; j < T; ++j) {
-      for (int l = 0; l < L; ++l) {
-        LD& e = h->dec[l];
-        LstmFwdDir d;
-        if (l == 0) {
-          d.x = h->HoBuf + j * BH * esz; d.ldx = H; d.Kx = H; d.wx_off = E; d.wh_off = E + H;
-          d.gx = e.Gx + (size_t)j * Bp * 4 * H; d.ldgx = 4 * H; d.bias = nullptr; d.ldw = E + 2 * H;
-        } else {
-          d.x = h->dec[l - 1].Hst + (j + 1) * BH * esz; d.ldx = H; d.Kx = H; d.wx_off = 0; d.wh_off = H;
-          d.gx = nullptr; d.ldgx = 0; d.bias = P + e.b_off; d.ldw = 2 * H;
-        }
-        d.hprev = e.Hst + j * BH * esz; d.ldh = H; d.W = e.W;
-        d.cprev = e.Cst + j * BH; d.mask = h->mask_t + (size_t)j * Bp;
-        d.hnext = e.Hst + (j + 1) * BH * esz; d.cnext = e.Cst + (j + 1) * BH;
-        d.gsave = e.Gs + (size_t)j * Bp * 4 * H; d.ycat = nullptr; d.ldy = 0;
-        launch_lstm_fwd(p, &d, 1, Bp, H, st);
-      }
+      for (int l = 0; l < L; ++l) dec_lstm_fwd(h, l, j);
       const char* Ht = h->dec[L - 1].Hst + (j + 1) * BH * esz;
-      launch_att_fwd(p, h->Kmat, Hs, Ht, h->len_s, S, Bp, H, h->att_a + (size_t)j * Bp * S, h->Cs + j * BH * esz, st);
+      launch_att_fwd(p, h->Kmat, Hs, Ht, h->len_s, S, Bp, H, h->dots, h->att_a + (size_t)j * Bp * S, h->Cs + j * BH * esz, st);
       StepGemm g{};
       g.a0 = h->Cs + j * BH * esz; g.lda0 = H; g.K0 = H; g.w0_off = 0;
       g.a1 = Ht; g.lda1 = H; g.K1 = H; g.w1_off = H;
       g.W = h->Pw(h->off_Wc); g.ldw = 2 * H; g.N = H; g.mode = 0;
       g.outT = h->HoBuf + (j + 1) * BH * esz; g.ldo = H;
+      g.out = h->wcp; g.ldout = H; g.plane_stride = BH;
       launch_step_gemm(p, g, Bp, st);
     }
   }
@@ -423,41 +437,51 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
 
   // ---- decoder loop backwards -----------------------------------------------------------------------
   for (int l = 0; l < L; ++l) { launch_fill_f32(h->dec[l].dh, BH, 0.f, st); launch_fill_f32(h->dec[l].dc, BH, 0.f, st); }
+  const int kbd = step_kblocks(p, 2 * H, 4 * H, Bp);                  // planes written by a decoder layer's backward GEMM
+  const size_t pstr = (size_t)Bp * 2 * H;
   for (int j = T - 1; j >= 0; --j) {
     char* dpre = h->dPre + j * BH * esz;
-    launch_tanh_bwd(p, h->dHoCE + j * BH, j < T - 1 ? h->dHoFeed : nullptr, h->HoBuf + (j + 1) * BH * esz, dpre, (int)BH, st);
-    {   // [dC_s ; dH_t] = dpre W_c
+    const bool last = j == T - 1;
+    // dH_o = cross-entropy part + what step j+1's bottom layer sent back through the input feed
+    launch_tanh_bwd(p, h->dHoCE + j * BH, Planes{h->dec[0].bwdp, 2 * H, last ? 0 : kbd, pstr}, h->HoBuf + (j + 1) * BH * esz,
+                    dpre, Bp, H, st);
+    const int kbw = step_kblocks(p, 2 * H, H, Bp);
+    {   // [dC_s ; dH_t] = dpre W_c, as planes
       StepGemm g{};
       g.a0 = dpre; g.lda0 = H; g.K0 = H; g.w0_off = 0; g.K1 = 0;
       g.W = h->WcT; g.ldw = H; g.N = 2 * H; g.mode = 1;
-      g.out0 = h->dCs + j * BH; g.ld0 = H; g.nsplit = H; g.acc0 = 0;
-      g.out1 = h->dHt; g.ld1 = H; g.acc1 = 0;
+      g.out = h->wcp; g.ldout = 2 * H; g.plane_stride = pstr;
       launch_step_gemm(p, g, Bp, st);
     }
-    launch_att_bwd(p, h->Kmat, Hs, h->dCs + j * BH, h->att_a + (size_t)j * Bp * S, h->len_s, S, Bp, H,
-                   h->att_ds + (size_t)j * Bp * S, h->dHt, st);
+    launch_att_bwd(p, h->Kmat, Hs, Planes{h->wcp, 2 * H, kbw, pstr}, h->dCs + j * BH, h->att_a + (size_t)j * Bp * S,
+                   h->len_s, S, Bp, H, h->dots, h->att_ds + (size_t)j * Bp * S, h->dHt, st);
     for (int l = L - 1; l >= 0; --l) {
       LD& e = h->dec[l];
       LstmBwdPoint q;
-      q.dy = (l == L - 1) ? h->dHt : h->dxl; q.lddy = H;
+      if (l == L - 1) q.dy = Planes{h->dHt, H, 1, 0};
+      else q.dy = Planes{h->dec[l + 1].bwdp, 2 * H, kbd, pstr};      // dx of the layer above, columns [0, H)
+      q.dy_col = 0;
+      q.dhrec = Planes{e.bwdp, 2 * H, last ? 0 : kbd, pstr}; q.dhrec_col = H;
       q.dh = e.dh; q.dc = e.dc;
       q.gsave = e.Gs + (size_t)j * Bp * 4 * H;
       q.cprev = e.Cst + j * BH; q.cnext = e.Cst + (j + 1) * BH;
       q.mask = h->mask_t + (size_t)j * Bp;
       q.dg = e.dG + (size_t)j * Bp * 4 * H * esz;
       launch_lstm_bwd_point(p, q, Bp, H, st);
-      StepGemm g{};
+      StepGemm g{};                                  // [dx ; dh_prev] = dgates [W_x ; W_h] (bottom layer: [feed ; h])
       g.a0 = q.dg; g.lda0 = 4 * H; g.K0 = 4 * H; g.w0_off = 0; g.K1 = 0;
       g.W = e.Wt + (size_t)(l == 0 ? E : 0) * 4 * H * esz; g.ldw = 4 * H;
       g.N = 2 * H; g.mode = 1;
-      g.out0 = (l == 0) ? h->dHoFeed : h->dxl; g.ld0 = H; g.nsplit = H; g.acc0 = 0;
-      g.out1 = e.dh; g.ld1 = H; g.acc1 = 1;
+      g.out = e.bwdp; g.ldout = 2 * H; g.plane_stride = pstr;
       launch_step_gemm(p, g, Bp, st);
     }
   }
+  // gradient of the decoder's initial state: pass-through part + the last GEMM's recurrent part
+  for (int l = 0; l < L; ++l)
+    launch_planes_add(h->dec[l].dh, h->dec[l].dh, Planes{h->dec[l].bwdp, 2 * H, kbd, pstr}, H, Bp, H, st);
   // ---- attention gradients that do not feed the decoder recurrence, batched over all steps ---------
   const char* HtAll = h->dec[L - 1].Hst + BH * esz;      // H_t^{<0..T-1>}
-  launch_att_deferred(p, h->att_a, h->att_ds, h->dCs, HtAll, (int)BH, S, T, Bp, H, h->dHs, h->dK, st);
+  launch_att_deferred(p, h->att_a, h->att_ds, h->dCs, H, HtAll, (int)BH, S, T, Bp, H, h->dHs, h->dK, st);
   launch_gemm_nt(p, h->dK, H, h->Pw(h->off_Wa), H, Ms, H, H, h->dHs, nullptr, H, nullptr, 1, st);   // dHs += dK W_a^T
 
   // transposed activations for the weight-gradient GEMMs
@@ -502,7 +526,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   for (int l = L - 1; l >= 1; --l) {
     LD& e = h->enc[l + 1];
     // gradient of the final state = gradient of the decoder's initial state of the same depth
-    run_lstm_layer_bwd(h, e, S, h->mask_s, dY, H, 0, false, H, H, nullptr, h->dec[l].dh, h->dec[l].dc);
+    run_lstm_layer_bwd(h, e, S, h->mask_s, dY, H, 0, false, h->dec[l].dh, h->dec[l].dc);
     launch_gemm_nt(p, e.dG, 4 * H, e.Wt, 4 * H, Ms, H, 4 * H, dYnext, nullptr, H, nullptr, 0, st);   // dX = dG W_x
     int ld; const char* XT = encYT(l - 1, &ld);
     weight_grads(h, e, S, {{XT, ld}, {e.HstT, (S + 1) * Bp}}, {H, H});
@@ -513,8 +537,8 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     LD& d0 = h->dec[0];
     launch_copy2d_f32(d0.dh, H, ef.dh, Hd, Bp, Hd, st); launch_copy2d_f32(d0.dh + Hd, H, eb.dh, Hd, Bp, Hd, st);
     launch_copy2d_f32(d0.dc, H, ef.dc, Hd, Bp, Hd, st); launch_copy2d_f32(d0.dc + Hd, H, eb.dc, Hd, Bp, Hd, st);
-    run_lstm_layer_bwd(h, ef, S, h->mask_s, dY, H, 0, false, E, Hd, nullptr, ef.dh, ef.dc);
-    run_lstm_layer_bwd(h, eb, S, h->mask_s, dY, H, Hd, true, E, Hd, nullptr, eb.dh, eb.dc);
+    run_lstm_layer_bwd(h, ef, S, h->mask_s, dY, H, 0, false, ef.dh, ef.dc);
+    run_lstm_layer_bwd(h, eb, S, h->mask_s, dY, H, Hd, true, eb.dh, eb.dc);
     launch_gemm_nt(p, ef.dG, 4 * Hd, ef.Wt, 4 * Hd, Ms, E, 4 * Hd, h->dXs, nullptr, E, nullptr, 0, st);
     launch_gemm_nt(p, eb.dG, 4 * Hd, eb.Wt, 4 * Hd, Ms, E, 4 * Hd, h->dXs, nullptr, E, nullptr, 1, st);
     weight_grads(h, ef, S, {{h->XsT, Ms}, {ef.HstT, (S + 1) * Bp}}, {E, Hd});
@@ -656,6 +680,38 @@ int cmt_sgd_update(cmt_handle* h, float lr) {
   refresh_params(h);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(h, e, "cmt_sgd_update");
+  return CMT_OK;
+}
+
+int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_launch, double* algo_bytes) {
+  if (!h || !name || iters < 1 || !us_per_launch || !algo_bytes) return fail(h, CMT_EINVAL, "bad argument");
+  if (!h->have_step) return fail(h, CMT_EINVAL, "no step has been run");
+  const int H = h->cfg.hidden, L = h->cfg.layers, E = h->cfg.emb_dim, Bp = h->Bp, T = h->T;
+  const double esz = (double)h->esz;
+  const std::string s(name);
+  if (s != "lstm_fwd_dec") return fail(h, CMT_EINVAL, "unknown kernel name");
+  // decoder LSTM forward step at the middle target position, cycling over the layers like the real loop
+  const int j = T / 2;
+  const int K = (L > 1) ? 2 * H : 2 * H;              // per-step contraction (layer 0: [feed; h], others: [x; h])
+  *algo_bytes = 4.0 * H * K * esz                     // weights, read once
+              + (double)Bp * K * esz                  // [x; h_prev]
+              + (double)Bp * 4 * H * 4                // bias / pre-batched input part
+              + (double)Bp * H * 4                    // c_prev
+              + (double)Bp * H * (esz + 4)            // h, c out
+              + (double)Bp * 4 * H * 4;               // gate activations kept for backward
+  (void)E;
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return fail(h, CMT_EHIP, "event create");
+  for (int i = 0; i < 8; ++i) dec_lstm_fwd(h, L > 1 ? 1 + i % (L - 1) : 0, j);
+  (void)hipEventRecord(e0, h->st);
+  for (int i = 0; i < iters; ++i) dec_lstm_fwd(h, L > 1 ? 1 + i % (L - 1) : 0, j);
+  (void)hipEventRecord(e1, h->st);
+  hipError_t e = hipEventSynchronize(e1);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+  if (e != hipSuccess) return hip_fail(h, e, "cmt_time_kernel");
+  *us_per_launch = ms * 1e3f / iters;
   return CMT_OK;
 }
 

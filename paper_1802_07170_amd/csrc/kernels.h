@@ -40,6 +40,12 @@ void launch_ce_bwd_dw(int prec, const void* Ho, const void* HoT, int ldhot, cons
                       int M, int V, int H, float* dWo, float* dBo, hipStream_t st);
 
 // ---- step.hip ----------------------------------------------------------------------------------
+// A value delivered as `np` partial planes: v(b, c) = sum_k p[k * stride + b * ld + c]  (np = 0: zero).
+struct Planes { const float* p; int ld; int np; size_t stride; };
+// Number of k-blocks (= planes written) by launch_step_gemm for N output columns, contraction
+// length K and padded batch Bp (at most 8).
+int step_kblocks(int prec, int N, int K, int Bp);
+
 // One recurrent step of one LSTM layer (or of both directions of the bottom encoder layer when
 // ndir = 2): gates = Gx + [x; h_prev] W^T, then the cell, fused.
 struct LstmFwdDir {
@@ -53,29 +59,31 @@ struct LstmFwdDir {
   void* hnext; float* cnext;            // [Bp, Hh]
   float* gsave;                         // [Bp, 4Hh] gate activations kept for the backward pass
   void* ycat; int ldy;                  // optional second copy of h (T*, row pitch ldy), or null
+  float* part;                          // [8][Bp][4Hh] scratch planes, used when the k range is split
 };
 void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh, hipStream_t st);
 
-// out[Bp, N] = [a0; a1] W^T with an epilogue.  W rows are output columns; w0_off / w1_off are the
-// column offsets inside a weight row that pair with the two activation segments.
+// [a0; a1] W^T for one step.  W rows are output columns; w0_off / w1_off are the column offsets
+// inside a weight row that pair with the two activation segments.
 struct StepGemm {
   const void* a0; int lda0; int K0; int w0_off;
   const void* a1; int lda1; int K1; int w1_off;
   const void* W; int ldw;
   int N;
-  int mode;            // 0: tanh -> outT (T*) [Bp,N]          (attentional layer, Eq. 7)
-                       // 1: fp32 outputs: columns < nsplit go to out0[b,n], the others to out1[b,n-nsplit];
-                       //    acc0 / acc1 = 1 adds to what is there, 0 overwrites
+  int mode;            // 0: tanh of the sum -> outT (T*) [Bp, N]   (attentional layer, Eq. 7);
+                       //    `out` is scratch for the planes when the k range is split
+                       // 1: partial planes out[kb][b][n] (fp32, row pitch ldout, plane pitch plane_stride),
+                       //    kb < step_kblocks(prec, K0 + K1); the consumer sums them
   void* outT; int ldo;
-  float* out0; int ld0; int nsplit; int acc0;
-  float* out1; int ld1; int acc1;
+  float* out; int ldout; size_t plane_stride;
 };
 void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st);
 
 // Cell backward for one step of one layer: builds dgates (T*) from the incoming state gradients.
 struct LstmBwdPoint {
-  const float* dy; int lddy;           // gradient arriving at this step's output [Bp, Hh] (or null)
-  float* dh;                           // [Bp,Hh] in: d state after the step; out: (1-m) * total (pass-through)
+  Planes dy; int dy_col;               // gradient arriving at this step's output: columns dy_col + [0, Hh)
+  Planes dhrec; int dhrec_col;         // recurrent part of d state from the next step's GEMM
+  float* dh;                           // [Bp,Hh] in: pass-through part of d state; out: (1-m) * total
   float* dc;                           // [Bp,Hh] in/out cell-state gradient
   const float* gsave;                  // [Bp,4Hh]
   const float* cprev; const float* cnext;  // [Bp,Hh]
@@ -83,20 +91,26 @@ struct LstmBwdPoint {
   void* dg;                            // T* [Bp,4Hh]
 };
 void launch_lstm_bwd_point(int prec, const LstmBwdPoint& p, int Bp, int Hh, hipStream_t st);
+// out[Bp, cols] = base (or 0) + planes columns col0 + [0, cols)
+void launch_planes_add(float* out, const float* base, const Planes& p, int col0, int Bp, int cols, hipStream_t st);
 
 // Attention forward for one decoder step (Eq. 3-5 with the key hoist K_i = W_a^T H_s^i):
-// s_i = K_i . H_t, softmax over i < src_len[b], C_s = sum a_i H_s^i.
+// s_i = K_i . H_t, softmax over i < src_len[b], C_s = sum a_i H_s^i.  dots [Bp,S] is scratch.
 void launch_att_fwd(int prec, const void* Kmat, const void* Hs, const void* Ht, const int32_t* src_len,
-                    int S, int Bp, int H, float* a /*[Bp,S]*/, void* Cs /*T* [Bp,H]*/, hipStream_t st);
-// Attention backward for one step: da_i = dCs . H_s^i, ds = a (da - sum a da), dHt += sum ds_i K_i.
-void launch_att_bwd(int prec, const void* Kmat, const void* Hs, const float* dCs, const float* a,
-                    const int32_t* src_len, int S, int Bp, int H, float* ds /*[Bp,S]*/, float* dHt /*[Bp,H]*/, hipStream_t st);
+                    int S, int Bp, int H, float* dots, float* a /*[Bp,S]*/, void* Cs /*T* [Bp,H]*/, hipStream_t st);
+// Attention backward for one step.  dCst: planes [.., Bp, 2H] fp32 from the step GEMM dpre W_c:
+// columns [0,H) = dC_s, [H,2H) = the part of dH_t that came through the concatenation.
+// da_i = dC_s . H_s^i, ds = a (da - sum a da), dHt = dCst[:, H:] + sum ds_i K_i;
+// dCs_sum [Bp,H] receives the summed dC_s (kept for the deferred gradients).
+void launch_att_bwd(int prec, const void* Kmat, const void* Hs, const Planes& dCst, float* dCs_sum, const float* a,
+                    const int32_t* src_len, int S, int Bp, int H, float* dots, float* ds /*[Bp,S]*/,
+                    float* dHt /*[Bp,H]*/, hipStream_t st);
 // After the decoder loop: dHs_ctx[i,b,:] = sum_j a[j,b,i] dCs[j,b,:], dK[i,b,:] = sum_j ds[j,b,i] Ht[j,b,:].
-void launch_att_deferred(int prec, const float* a, const float* ds, const float* dCs, const void* Ht, int ldht,
+void launch_att_deferred(int prec, const float* a, const float* ds, const float* dCs, int lddc, const void* Ht, int ldht,
                          int S, int T, int Bp, int H, float* dHs, void* dK, hipStream_t st);
-// dpre = (dHo_ce + dHo_feed) * (1 - Ho^2) -> T*; dHo_feed may be null.
-void launch_tanh_bwd(int prec, const float* dHo_ce, const float* dHo_feed, const void* Ho, void* dpre,
-                     int n, hipStream_t st);
+// dpre = (dHo_ce + feed) * (1 - Ho^2) -> T*
+void launch_tanh_bwd(int prec, const float* dHo_ce, const Planes& feed, const void* Ho, void* dpre, int Bp, int H,
+                     hipStream_t st);
 
 // ---- misc.hip ----------------------------------------------------------------------------------
 // Embedding gather + masks + input validation (flags |= 1 bad id, |= 2 bad length).

@@ -2,82 +2,106 @@
 // Per step the batch is tiny (M = B <= 128) and the work is bound by streaming the layer's
 // weights, so these kernels put the WEIGHT rows on the matrix cores' row side (16 rows per
 // workgroup, read exactly once per step straight from global memory into MFMA fragments, no LDS
-// staging) and the batch on the column side; the wavefronts of a workgroup split the k range and
-// combine their partial tiles through LDS.  For the LSTM the 16 rows of a workgroup are the four
-// gates of four hidden units, so that after the reduction every lane holds i, f, g, o of one
-// (unit, sentence) pair and the cell update is fused in-register.
+// staging) and the batch on the column side.  The wavefronts of a workgroup split the k range;
+// every wavefront issues all of its loads before its first MFMA so that a whole workgroup's
+// operand bytes are in flight at once, and the partial tiles are combined through LDS.  A k range
+// longer than one workgroup covers is split over workgroups, which then write partial "planes"
+// that the consuming kernel sums (no atomics, fixed order).
+// For the LSTM the 16 rows of a workgroup are the four gates of four hidden units, so that after
+// the reduction every lane holds i, f, g, o of one (unit, sentence) pair and the cell update is
+// fused in-register.
+// Workgroup numbering is XCD-aware: the hardware deals consecutive workgroup ids round-robin to
+// the 8 XCDs, so the two batch halves that share a weight tile are given ids 8 apart.
+#include <stdlib.h>
+
 #include "common.h"
 #include "kernels.h"
 
 namespace cmt {
 
-constexpr int STEP_MAXBT = 4;          // batch tiles (of 16 sentences) per workgroup pass
+constexpr int STEP_MAXBT = 4;          // batch tiles (of 16 sentences) per workgroup
 
-// Fragment of the concatenated k axis [a0 (K0) ; a1 (K1)], 8 elements at chunk index `chunk`.
-template <typename T>
-__device__ __forceinline__ void load_seg_frags(Frag<T>& fw, Frag<T> (&fx)[STEP_MAXBT], int chunk, int nc0, int nc,
-                                               const T* wrow, int w0_off, int w1_off,
-                                               const T* a0, int lda0, const T* a1, int lda1,
-                                               int brow_base, int Bp, int nbt) {
-  if (chunk >= nc) {
-    fw.zero();
-#pragma unroll
-    for (int b = 0; b < STEP_MAXBT; ++b) fx[b].zero();
-    return;
-  }
-  const bool first = chunk < nc0;
-  const int kk = first ? chunk * 8 : (chunk - nc0) * 8;
-  fw.load(wrow + (first ? w0_off : w1_off) + kk);
-  const T* a = first ? a0 : a1;
-  const int lda = first ? lda0 : lda1;
-#pragma unroll
-  for (int b = 0; b < STEP_MAXBT; ++b) {
-    if (b < nbt) {
-      int r = brow_base + 16 * b;
-      r = r < Bp ? r : Bp - 1;
-      fx[b].load(a + (size_t)r * lda + kk);
-    } else {
-      fx[b].zero();
-    }
-  }
+struct StepGrid { int nx, kb, nz; };
+__device__ __forceinline__ bool decode_block(const StepGrid& g, int& x, int& kb, int& z) {
+  const int L = blockIdx.x;
+  const int xcd = L & 7;
+  int r = L >> 3;
+  z = r % g.nz; r /= g.nz;
+  kb = r % g.kb; r /= g.kb;
+  x = xcd + 8 * r;
+  return x < g.nx;
 }
+static inline int step_grid_blocks(const StepGrid& g) { return ((g.nx + 7) / 8) * 8 * g.kb * g.nz; }
 
-// Runs the split-k contraction for one 16-row weight tile and reduces across wavefronts.
-// On return, wavefronts w < nbt hold in `res` the full sums of batch tile w:
-// res[i] = row (4 * (lane / 16) + i) of the weight tile, sentence 16 * (bt0 + w) + lane % 16.
-template <typename T, int KS>
-__device__ __forceinline__ bool step_contract(const T* wrow, int w0_off, int w1_off, const T* a0, int lda0, int K0,
-                                              const T* a1, int lda1, int K1, int Bp, int bt0, int nbt, v4f& res,
-                                              float* red /* [KS][STEP_MAXBT][64][4] */) {
+// Split-k contraction of RT 16-row weight tiles against up to 64 sentences inside one workgroup.
+// Wavefront w takes k-steps w + KS * (u + U * round); fragment chunk c of the concatenated k axis
+// [a0 (K0); a1 (K1)] covers 8 elements; all loads of a round are issued before its first MFMA.
+// The partial tiles go through LDS; afterwards tile t = rt * STEP_MAXBT + bt is summed by wavefront
+// t % KS.  red must hold KS * RT * STEP_MAXBT * 256 floats.
+template <typename T, int RT, int KS, int U>
+__device__ __forceinline__ void step_contract(const T* const (&wrow)[RT], int w0_off, int w1_off, const T* a0, int lda0,
+                                              int K0, const T* a1, int lda1, int K1, int Bp, int bt0, int nbt, float* red) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int nc0 = K0 >> 3, nc = (K0 + K1) >> 3;
   const int nsteps = (nc + 3) >> 2;
-  const int brow_base = 16 * bt0 + (lane & 15);
-  v4f acc[STEP_MAXBT];
+  const int brow = 16 * bt0 + (lane & 15);
+  v4f acc[RT][STEP_MAXBT];
 #pragma unroll
-  for (int b = 0; b < STEP_MAXBT; ++b) acc[b] = v4f{0.f, 0.f, 0.f, 0.f};
-  // interleaved k-steps: wavefront w takes steps w, w + KS, ...; two steps in flight
-  for (int s = w; s < nsteps; s += 2 * KS) {
-    Frag<T> fw0, fw1, fx0[STEP_MAXBT], fx1[STEP_MAXBT];
-    load_seg_frags<T>(fw0, fx0, 4 * s + (lane >> 4), nc0, nc, wrow, w0_off, w1_off, a0, lda0, a1, lda1, brow_base, Bp, nbt);
-    const int s1 = s + KS;
-    load_seg_frags<T>(fw1, fx1, s1 < nsteps ? 4 * s1 + (lane >> 4) : nc, nc0, nc, wrow, w0_off, w1_off, a0, lda0, a1, lda1,
-                      brow_base, Bp, nbt);
+  for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-    for (int b = 0; b < STEP_MAXBT; ++b) mma16(acc[b], fw0, fx0[b]);
+    for (int b = 0; b < STEP_MAXBT; ++b) acc[rt][b] = v4f{0.f, 0.f, 0.f, 0.f};
+  for (int s0 = 0; s0 < nsteps; s0 += KS * U) {
+    Frag<T> fw[U][RT], fx[U][STEP_MAXBT];
 #pragma unroll
-    for (int b = 0; b < STEP_MAXBT; ++b) mma16(acc[b], fw1, fx1[b]);
+    for (int u = 0; u < U; ++u) {
+      const int chunk = 4 * (s0 + w + KS * u) + (lane >> 4);
+      if (chunk < nc) {
+        const bool first = chunk < nc0;
+        const int kk = first ? chunk * 8 : (chunk - nc0) * 8;
+        const int wo = (first ? w0_off : w1_off) + kk;
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) fw[u][rt].load(wrow[rt] + wo);
+        const T* a = first ? a0 : a1;
+        const int lda = first ? lda0 : lda1;
+#pragma unroll
+        for (int b = 0; b < STEP_MAXBT; ++b) {
+          if (b < nbt) fx[u][b].load(a + (size_t)min(brow + 16 * b, Bp - 1) * lda + kk);
+          else fx[u][b].zero();
+        }
+      } else {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) fw[u][rt].zero();
+#pragma unroll
+        for (int b = 0; b < STEP_MAXBT; ++b) fx[u][b].zero();
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int b = 0; b < STEP_MAXBT; ++b) mma16(acc[rt][b], fw[u][rt], fx[u][b]);
   }
 #pragma unroll
-  for (int b = 0; b < STEP_MAXBT; ++b)
-    *reinterpret_cast<v4f*>(red + ((w * STEP_MAXBT + b) * 64 + lane) * 4) = acc[b];
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int b = 0; b < STEP_MAXBT; ++b)
+      *reinterpret_cast<v4f*>(red + (((w * RT + rt) * STEP_MAXBT + b) * 64 + lane) * 4) = acc[rt][b];
   __syncthreads();
-  if (w >= nbt) return false;
+}
+template <int RT, int KS>
+__device__ __forceinline__ v4f step_tile_sum(const float* red, int rt, int bt) {
+  const int lane = threadIdx.x & 63;
   v4f r = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int k = 0; k < KS; ++k) r += *reinterpret_cast<const v4f*>(red + ((k * STEP_MAXBT + w) * 64 + lane) * 4);
-  res = r;
-  return true;
+  for (int k = 0; k < KS; ++k) r += *reinterpret_cast<const v4f*>(red + (((k * RT + rt) * STEP_MAXBT + bt) * 64 + lane) * 4);
+  return r;
+}
+
+__device__ __forceinline__ float planes_get(const Planes& p, int b, int c) {
+  float v = 0.f;
+  for (int k = 0; k < p.np; ++k) v += p.p[(size_t)k * p.stride + (size_t)b * p.ld + c];
+  return v;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -85,106 +109,275 @@ __device__ __forceinline__ bool step_contract(const T* wrow, int w0_off, int w1_
 // ------------------------------------------------------------------------------------------------
 struct LstmFwdArgs { LstmFwdDir d[2]; };
 
-template <typename T, int KS>
-__global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(LstmFwdArgs args, int Bp, int Hh) {
-  __shared__ __align__(16) float red[KS * STEP_MAXBT * 64 * 4];
-  const LstmFwdDir& d = args.d[blockIdx.z];
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int u0 = blockIdx.x * 4;
-  const int bt0 = blockIdx.y * STEP_MAXBT;
-  const int nbt = min(STEP_MAXBT, (Bp + 15) / 16 - bt0);
-  // weight-tile row m = lane % 16: gate m % 4 of unit u0 + m / 4
-  const int m = lane & 15;
-  const int unit_ld = min(u0 + (m >> 2), Hh - 1);
-  const T* wrow = (const T*)d.W + (size_t)((m & 3) * Hh + unit_ld) * d.ldw;
-  v4f pre;
-  if (!step_contract<T, KS>(wrow, d.wx_off, d.wh_off, (const T*)d.x, d.ldx, d.Kx, (const T*)d.hprev, d.ldh, Hh, Bp, bt0,
-                            nbt, pre, red))
-    return;
-  const int u = u0 + (lane >> 4);
-  const int b = 16 * (bt0 + w) + (lane & 15);
-  if (u >= Hh || b >= Bp) return;
-  float p[4];
-#pragma unroll
-  for (int g = 0; g < 4; ++g)
-    p[g] = pre[g] + (d.gx ? d.gx[(size_t)b * d.ldgx + g * Hh + u] : d.bias[g * Hh + u]);
+__device__ __forceinline__ void lstm_cell_store(const LstmFwdDir& d, int b, int u, int Hh, const float (&p)[4],
+                                                bool is_bf16) {
   const float ig = sigm(p[0]), fg = sigm(p[1]), gg = tanhf(p[2]), og = sigm(p[3]);
   const float cp = d.cprev[(size_t)b * Hh + u];
   const float cn = fg * cp + ig * gg;
   const float hn = og * tanhf(cn);
   const bool valid = d.mask[b] > 0.f;
-  const T hp = ((const T*)d.hprev)[(size_t)b * d.ldh + u];
-  const T hout = valid ? from_f<T>(hn) : hp;
-  ((T*)d.hnext)[(size_t)b * Hh + u] = hout;
   d.cnext[(size_t)b * Hh + u] = valid ? cn : cp;
   float* gs = d.gsave + (size_t)b * 4 * Hh + u;
   gs[0] = ig; gs[Hh] = fg; gs[2 * Hh] = gg; gs[3 * Hh] = og;
-  if (d.ycat) ((T*)d.ycat)[(size_t)b * d.ldy + u] = hout;
+  if (is_bf16) {
+    const bf16_t hp = ((const bf16_t*)d.hprev)[(size_t)b * d.ldh + u];
+    const bf16_t ho = valid ? f2bf(hn) : hp;
+    ((bf16_t*)d.hnext)[(size_t)b * Hh + u] = ho;
+    if (d.ycat) ((bf16_t*)d.ycat)[(size_t)b * d.ldy + u] = ho;
+  } else {
+    const float hp = ((const float*)d.hprev)[(size_t)b * d.ldh + u];
+    const float ho = valid ? hn : hp;
+    ((float*)d.hnext)[(size_t)b * Hh + u] = ho;
+    if (d.ycat) ((float*)d.ycat)[(size_t)b * d.ldy + u] = ho;
+  }
 }
 
+// RT row tiles = 4 * RT hidden units x 4 gates per workgroup; the whole k range inside the workgroup.
+template <typename T, int RT, int KS, int U>
+__global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(LstmFwdArgs args, int Bp, int Hh, StepGrid sg, int ndir) {
+  __shared__ __align__(16) float red[KS * RT * STEP_MAXBT * 256];
+  int x, kb, z;
+  if (!decode_block(sg, x, kb, z)) return;
+  const int nxd = sg.nx / ndir;                    // unit blocks per direction
+  const int dir = x / nxd;
+  const LstmFwdDir& d = args.d[dir];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int u0 = (x - dir * nxd) * 4 * RT;
+  const int bt0 = z * STEP_MAXBT;
+  const int nbt = min(STEP_MAXBT, (Bp + 15) / 16 - bt0);
+  // row m = lane % 16 of row tile rt: gate m % 4 of unit u0 + 4 * rt + m / 4
+  const int m = lane & 15;
+  const T* wrow[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+    wrow[rt] = (const T*)d.W + (size_t)((m & 3) * Hh + min(u0 + 4 * rt + (m >> 2), Hh - 1)) * d.ldw;
+  step_contract<T, RT, KS, U>(wrow, d.wx_off, d.wh_off, (const T*)d.x, d.ldx, d.Kx, (const T*)d.hprev, d.ldh, Hh, Bp, bt0,
+                              nbt, red);
+  for (int t = w; t < RT * STEP_MAXBT; t += KS) {
+    const int rt = t / STEP_MAXBT, bt = t - rt * STEP_MAXBT;
+    if (bt >= nbt) continue;
+    const v4f pre = step_tile_sum<RT, KS>(red, rt, bt);
+    const int u = u0 + 4 * rt + (lane >> 4);
+    const int b = 16 * (bt0 + bt) + (lane & 15);
+    if (u >= Hh || b >= Bp) continue;
+    float p[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      p[g] = pre[g] + (d.gx ? d.gx[(size_t)b * d.ldgx + g * Hh + u] : d.bias[g * Hh + u]);
+    lstm_cell_store(d, b, u, Hh, p, sizeof(T) == 2);
+  }
+}
+
+// cell update from partial planes (only when the k range was split over workgroups)
+template <typename T>
+__global__ __launch_bounds__(256) void lstm_cell_kernel(LstmFwdArgs args, int Bp, int Hh, int np) {
+  const LstmFwdDir& d = args.d[blockIdx.y];
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= Bp * Hh) return;
+  const int b = idx / Hh, u = idx - b * Hh;
+  float p[4];
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    float v = d.gx ? d.gx[(size_t)b * d.ldgx + g * Hh + u] : d.bias[g * Hh + u];
+    for (int k = 0; k < np; ++k) v += d.part[((size_t)k * Bp + b) * 4 * Hh + g * Hh + u];
+    p[g] = v;
+  }
+  lstm_cell_store(d, b, u, Hh, p, sizeof(T) == 2);
+}
+
+template <typename T, int RT, int KS, int U>
+static void lstm_fwd_go(const LstmFwdArgs& a, int Bp, int Hh, int ndir, hipStream_t st) {
+  const int nbt = (Bp + 15) / 16;
+  StepGrid sg{((Hh + 4 * RT - 1) / (4 * RT)) * ndir, 1, (nbt + STEP_MAXBT - 1) / STEP_MAXBT};
+  hipLaunchKernelGGL((lstm_fwd_kernel<T, RT, KS, U>), dim3(step_grid_blocks(sg)), dim3(64 * KS), 0, st, a, Bp, Hh, sg, ndir);
+}
+
+// Ways to run the step: the fused kernel above with 16 / 32 / 64 gate rows per workgroup (one
+// launch; fewer, fatter workgroups move less activation traffic through L2), or the 2-D step GEMM
+// on the packed gate rows followed by the cell kernel (two launches).
+// `how` (env CMT_LSTM_FWD for experiments): 0 = choose by size, 1/2/4 = fused with that many row
+// tiles, 9 = split.
+static int g_lstm_fwd_how = -1;
 void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh, hipStream_t st) {
+  if (g_lstm_fwd_how < 0) {
+    const char* e = getenv("CMT_LSTM_FWD");
+    g_lstm_fwd_how = e ? atoi(e) : 0;
+  }
   LstmFwdArgs a;
   a.d[0] = dirs[0];
   a.d[1] = dirs[ndir > 1 ? 1 : 0];
-  const int nbt = (Bp + 15) / 16;
-  dim3 grid((Hh + 3) / 4, (nbt + STEP_MAXBT - 1) / STEP_MAXBT, ndir);
   const int K = dirs[0].Kx + Hh;
-  if (K >= 1024) {
-    if (prec) hipLaunchKernelGGL((lstm_fwd_kernel<bf16_t, 8>), grid, dim3(512), 0, st, a, Bp, Hh);
-    else hipLaunchKernelGGL((lstm_fwd_kernel<float, 8>), grid, dim3(512), 0, st, a, Bp, Hh);
+  int how = g_lstm_fwd_how;
+  if (how == 0) how = 1;
+  if (how == 9) {
+    int np = 1;
+    for (int i = 0; i < ndir; ++i) {
+      const LstmFwdDir& d = dirs[i];
+      StepGemm g{};
+      g.a0 = d.x; g.lda0 = d.ldx; g.K0 = d.Kx; g.w0_off = d.wx_off;
+      g.a1 = d.hprev; g.lda1 = d.ldh; g.K1 = Hh; g.w1_off = d.wh_off;
+      g.W = d.W; g.ldw = d.ldw; g.N = 4 * Hh; g.mode = 1;
+      g.out = d.part; g.ldout = 4 * Hh; g.plane_stride = (size_t)Bp * 4 * Hh;
+      launch_step_gemm(prec, g, Bp, st);
+      np = step_kblocks(prec, 4 * Hh, K, Bp);
+    }
+    dim3 grid((Bp * Hh + 255) / 256, ndir);
+    if (prec) hipLaunchKernelGGL(lstm_cell_kernel<bf16_t>, grid, dim3(256), 0, st, a, Bp, Hh, np);
+    else hipLaunchKernelGGL(lstm_cell_kernel<float>, grid, dim3(256), 0, st, a, Bp, Hh, np);
+    return;
+  }
+  const int nsteps = (K / 8 + 3) / 4;
+  if (prec) {
+    if (how == 4) lstm_fwd_go<bf16_t, 4, 8, 4>(a, Bp, Hh, ndir, st);
+    else if (how == 2) lstm_fwd_go<bf16_t, 2, 8, 4>(a, Bp, Hh, ndir, st);
+    else if (nsteps > 32) lstm_fwd_go<bf16_t, 1, 16, 4>(a, Bp, Hh, ndir, st);
+    else if (nsteps > 16) lstm_fwd_go<bf16_t, 1, 16, 2>(a, Bp, Hh, ndir, st);
+    else if (nsteps > 8) lstm_fwd_go<bf16_t, 1, 8, 2>(a, Bp, Hh, ndir, st);
+    else lstm_fwd_go<bf16_t, 1, 4, 2>(a, Bp, Hh, ndir, st);
   } else {
-    if (prec) hipLaunchKernelGGL((lstm_fwd_kernel<bf16_t, 4>), grid, dim3(256), 0, st, a, Bp, Hh);
-    else hipLaunchKernelGGL((lstm_fwd_kernel<float, 4>), grid, dim3(256), 0, st, a, Bp, Hh);
+    if (how == 4) lstm_fwd_go<float, 4, 8, 2>(a, Bp, Hh, ndir, st);
+    else if (how == 2) lstm_fwd_go<float, 2, 8, 2>(a, Bp, Hh, ndir, st);
+    else if (nsteps > 16) lstm_fwd_go<float, 1, 16, 2>(a, Bp, Hh, ndir, st);
+    else if (nsteps > 8) lstm_fwd_go<float, 1, 8, 2>(a, Bp, Hh, ndir, st);
+    else lstm_fwd_go<float, 1, 4, 2>(a, Bp, Hh, ndir, st);
   }
 }
 
 // ------------------------------------------------------------------------------------------------
-// generic step GEMM with epilogue
+// generic step GEMM, 2-D decomposition: a workgroup owns 64 weight rows x all (<= 64) sentences x a
+// k block.  Its 4 wavefronts split the k-steps; each loads every operand element it needs exactly
+// once (4 weight + 4 activation fragments per k-step feed 16 MFMAs), so the bytes that cross L2
+// are rows/64 * B * K for the activations instead of rows/16 * B * K.  The k blocks write planes
+// out[kb][b][n] that the consumer sums.
 // ------------------------------------------------------------------------------------------------
-template <typename T, int KS>
-__global__ __launch_bounds__(64 * KS) void step_gemm_kernel(StepGemm g, int Bp) {
-  __shared__ __align__(16) float red[KS * STEP_MAXBT * 64 * 4];
+struct Step2dPlan { int kb, steps_per_block, u; };
+static Step2dPlan plan2d(int prec, int N, int K, int Bp) {
+  const int nsteps = (K / 8 + 3) / 4;
+  const int nrb = (N + 63) / 64, nz = ((Bp + 15) / 16 + STEP_MAXBT - 1) / STEP_MAXBT;
+  const int u = prec ? 4 : 2;
+  int kb = (256 + nrb * nz - 1) / (nrb * nz);          // enough workgroups for 256 CUs
+  const int kb_max = (nsteps + 3) / 4;                  // at least one k-step per wavefront
+  if (kb > kb_max) kb = kb_max;
+  if (kb > 8) kb = 8;
+  if (kb < 1) kb = 1;
+  int spb = (nsteps + kb - 1) / kb;
+  spb = (spb + 3) / 4 * 4;
+  kb = (nsteps + spb - 1) / spb;
+  Step2dPlan p{kb, spb, u};
+  if (spb <= 4) p.u = 1;
+  else if (spb <= 8 && p.u > 2) p.u = 2;
+  return p;
+}
+int step_kblocks(int prec, int N, int K, int Bp) { return plan2d(prec, N, K, Bp).kb; }
+
+template <typename T, int U>
+__global__ __launch_bounds__(256) void step2d_kernel(StepGemm g, int Bp, StepGrid sg, int spb) {
+  __shared__ __align__(16) float red[4 * 16 * 64 * 4];
+  int x, kb, z;
+  if (!decode_block(sg, x, kb, z)) return;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int n0 = blockIdx.x * 16;
-  const int bt0 = blockIdx.y * STEP_MAXBT;
+  const int n0 = x * 64;
+  const int bt0 = z * STEP_MAXBT;
   const int nbt = min(STEP_MAXBT, (Bp + 15) / 16 - bt0);
-  const int nrow = min(n0 + (lane & 15), g.N - 1);
-  const T* wrow = (const T*)g.W + (size_t)nrow * g.ldw;
-  v4f r;
-  if (!step_contract<T, KS>(wrow, g.w0_off, g.w1_off, (const T*)g.a0, g.lda0, g.K0, (const T*)g.a1, g.lda1, g.K1, Bp, bt0,
-                            nbt, r, red))
-    return;
-  const int b = 16 * (bt0 + w) + (lane & 15);
-  if (b >= Bp) return;
+  const T* wrow[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int n = n0 + 4 * (lane >> 4) + i;
-    if (n >= g.N) continue;
-    if (g.mode == 0) {
-      ((T*)g.outT)[(size_t)b * g.ldo + n] = from_f<T>(tanhf(r[i]));
-    } else if (n < g.nsplit) {
-      float* o = g.out0 + (size_t)b * g.ld0 + n;
-      *o = g.acc0 ? *o + r[i] : r[i];
+  for (int rt = 0; rt < 4; ++rt)
+    wrow[rt] = (const T*)g.W + (size_t)min(n0 + 16 * rt + (lane & 15), g.N - 1) * g.ldw;
+  const int nc0 = g.K0 >> 3, nc = (g.K0 + g.K1) >> 3;
+  const int brow = 16 * bt0 + (lane & 15);
+  const T* a0 = (const T*)g.a0; const T* a1 = (const T*)g.a1;
+  v4f acc[4][STEP_MAXBT];
+#pragma unroll
+  for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+    for (int b = 0; b < STEP_MAXBT; ++b) acc[rt][b] = v4f{0.f, 0.f, 0.f, 0.f};
+  const int s_begin = kb * spb, s_end = s_begin + spb;
+  for (int s0 = s_begin; s0 < s_end; s0 += 4 * U) {
+    Frag<T> fw[U][4], fx[U][STEP_MAXBT];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int s = s0 + w + 4 * u;
+      const int chunk = 4 * s + (lane >> 4);
+      if (s < s_end && chunk < nc) {
+        const bool first = chunk < nc0;
+        const int kk = first ? chunk * 8 : (chunk - nc0) * 8;
+        const int wo = (first ? g.w0_off : g.w1_off) + kk;
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) fw[u][rt].load(wrow[rt] + wo);
+        const T* a = first ? a0 : a1;
+        const int lda = first ? g.lda0 : g.lda1;
+#pragma unroll
+        for (int b = 0; b < STEP_MAXBT; ++b) {
+          if (b < nbt) fx[u][b].load(a + (size_t)min(brow + 16 * b, Bp - 1) * lda + kk);
+          else fx[u][b].zero();
+        }
+      } else {
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) fw[u][rt].zero();
+#pragma unroll
+        for (int b = 0; b < STEP_MAXBT; ++b) fx[u][b].zero();
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+        for (int b = 0; b < STEP_MAXBT; ++b) mma16(acc[rt][b], fw[u][rt], fx[u][b]);
+  }
+#pragma unroll
+  for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+    for (int b = 0; b < STEP_MAXBT; ++b)
+      *reinterpret_cast<v4f*>(red + (((w * 4 + rt) * STEP_MAXBT + b) * 64 + lane) * 4) = acc[rt][b];
+  __syncthreads();
+  // wavefront w finishes row tile w for all batch tiles
+  const int n = n0 + 16 * w + 4 * (lane >> 4);
+#pragma unroll
+  for (int bt = 0; bt < STEP_MAXBT; ++bt) {
+    if (bt >= nbt) break;
+    const int b = 16 * (bt0 + bt) + (lane & 15);
+    v4f r = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) r += *reinterpret_cast<const v4f*>(red + (((k * 4 + w) * STEP_MAXBT + bt) * 64 + lane) * 4);
+    if (b >= Bp || n >= g.N) continue;
+    if (g.mode == 0 && sg.kb == 1) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (n + i < g.N) ((T*)g.outT)[(size_t)b * g.ldo + n + i] = from_f<T>(tanhf(r[i]));
     } else {
-      float* o = g.out1 + (size_t)b * g.ld1 + (n - g.nsplit);
-      *o = g.acc1 ? *o + r[i] : r[i];
+      float* o = g.out + (size_t)kb * g.plane_stride + (size_t)b * g.ldout + n;
+      if (n + 3 < g.N && (g.ldout & 3) == 0) *reinterpret_cast<v4f*>(o) = r;
+      else
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (n + i < g.N) o[i] = r[i];
     }
   }
 }
 
+template <typename T>
+__global__ __launch_bounds__(256) void tanh_planes_kernel(Planes p, T* __restrict__ out, int ldo, int Bp, int N) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= Bp * N) return;
+  const int b = idx / N, n = idx - b * N;
+  out[(size_t)b * ldo + n] = from_f<T>(tanhf(planes_get(p, b, n)));
+}
+
 void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st) {
   const int nbt = (Bp + 15) / 16;
-  dim3 grid((g.N + 15) / 16, (nbt + STEP_MAXBT - 1) / STEP_MAXBT);
-  const int K = g.K0 + g.K1;
-  if (K >= 2048) {
-    if (prec) hipLaunchKernelGGL((step_gemm_kernel<bf16_t, 16>), grid, dim3(1024), 0, st, g, Bp);
-    else hipLaunchKernelGGL((step_gemm_kernel<float, 16>), grid, dim3(1024), 0, st, g, Bp);
-  } else if (K >= 1024) {
-    if (prec) hipLaunchKernelGGL((step_gemm_kernel<bf16_t, 8>), grid, dim3(512), 0, st, g, Bp);
-    else hipLaunchKernelGGL((step_gemm_kernel<float, 8>), grid, dim3(512), 0, st, g, Bp);
-  } else {
-    if (prec) hipLaunchKernelGGL((step_gemm_kernel<bf16_t, 4>), grid, dim3(256), 0, st, g, Bp);
-    else hipLaunchKernelGGL((step_gemm_kernel<float, 4>), grid, dim3(256), 0, st, g, Bp);
+  const Step2dPlan pl = plan2d(prec, g.N, g.K0 + g.K1, Bp);
+  StepGrid sg{(g.N + 63) / 64, pl.kb, (nbt + STEP_MAXBT - 1) / STEP_MAXBT};
+  const dim3 grid(step_grid_blocks(sg));
+#define GO(TT, UU) hipLaunchKernelGGL((step2d_kernel<TT, UU>), grid, dim3(256), 0, st, g, Bp, sg, pl.steps_per_block)
+  if (prec) { if (pl.u == 4) GO(bf16_t, 4); else if (pl.u == 2) GO(bf16_t, 2); else GO(bf16_t, 1); }
+  else { if (pl.u == 2) GO(float, 2); else GO(float, 1); }
+#undef GO
+  if (g.mode == 0 && pl.kb > 1) {
+    Planes p{g.out, g.ldout, pl.kb, g.plane_stride};
+    const int n = Bp * g.N;
+    if (prec) hipLaunchKernelGGL(tanh_planes_kernel<bf16_t>, dim3((n + 255) / 256), dim3(256), 0, st, p, (bf16_t*)g.outT, g.ldo, Bp, g.N);
+    else hipLaunchKernelGGL(tanh_planes_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, st, p, (float*)g.outT, g.ldo, Bp, g.N);
   }
 }
 
@@ -196,9 +389,7 @@ __global__ __launch_bounds__(256) void lstm_bwd_point_kernel(LstmBwdPoint p, int
   const int idx = blockIdx.x * 256 + threadIdx.x;
   if (idx >= Bp * Hh) return;
   const int b = idx / Hh, u = idx - b * Hh;
-  const float dh_state = p.dh[idx];
-  const float dc_state = p.dc[idx];
-  const float dy = p.dy ? p.dy[(size_t)b * p.lddy + u] : 0.f;
+  const float dh_state = p.dh[idx] + planes_get(p.dhrec, b, p.dhrec_col + u);
   T* dg = (T*)p.dg + (size_t)b * 4 * Hh + u;
   if (!(p.mask[b] > 0.f)) {                       // masked step: state passes through, no gate gradient
     const T z = from_f<T>(0.f);
@@ -206,6 +397,8 @@ __global__ __launch_bounds__(256) void lstm_bwd_point_kernel(LstmBwdPoint p, int
     p.dh[idx] = dh_state;                          // (an output of a masked step is the constant 0: dy is dropped)
     return;
   }
+  const float dc_state = p.dc[idx];
+  const float dy = planes_get(p.dy, b, p.dy_col + u);
   const float* gs = p.gsave + (size_t)b * 4 * Hh + u;
   const float ig = gs[0], fg = gs[Hh], gg = gs[2 * Hh], og = gs[3 * Hh];
   const float cp = p.cprev[idx], cn = p.cnext[idx];
@@ -218,7 +411,7 @@ __global__ __launch_bounds__(256) void lstm_bwd_point_kernel(LstmBwdPoint p, int
   dg[2 * Hh] = from_f<T>(dc * ig * (1.f - gg * gg));
   dg[3 * Hh] = from_f<T>(dog * og * (1.f - og));
   p.dc[idx] = dc * fg;
-  p.dh[idx] = 0.f;                                 // the recurrent GEMM adds dgates * W_h onto this
+  p.dh[idx] = 0.f;                                 // the recurrent part arrives as planes of the step GEMM
 }
 
 void launch_lstm_bwd_point(int prec, const LstmBwdPoint& p, int Bp, int Hh, hipStream_t st) {
@@ -227,155 +420,171 @@ void launch_lstm_bwd_point(int prec, const LstmBwdPoint& p, int Bp, int Hh, hipS
   else hipLaunchKernelGGL(lstm_bwd_point_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, st, p, Bp, Hh);
 }
 
+// out[b, c] = base[b, c] + sum of planes (plain fp32 [Bp, cols])
+__global__ __launch_bounds__(256) void planes_add_kernel(float* __restrict__ out, const float* __restrict__ base, Planes p,
+                                                         int col0, int Bp, int cols) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= Bp * cols) return;
+  const int b = idx / cols, c = idx - b * cols;
+  out[idx] = (base ? base[idx] : 0.f) + planes_get(p, b, col0 + c);
+}
+void launch_planes_add(float* out, const float* base, const Planes& p, int col0, int Bp, int cols, hipStream_t st) {
+  hipLaunchKernelGGL(planes_add_kernel, dim3((Bp * cols + 255) / 256), dim3(256), 0, st, out, base, p, col0, Bp, cols);
+}
+
 // ------------------------------------------------------------------------------------------------
-// attention, one workgroup per sentence
+// attention: a "dots" kernel (one wavefront per (sentence, source position)) and a "mix" kernel
+// (softmax or its backward on the dots, then a weighted sum of rows), both spread over the chip
 // ------------------------------------------------------------------------------------------------
-// dots[i] = vec . Mat[i, b, :] for i < n (vec fp32 in LDS); one wavefront per source position.
-template <typename T>
-__device__ __forceinline__ void att_dots(const T* __restrict__ Mat, size_t pitch /*elements between i*/, int n, int H,
-                                         const float* vec, float* dots) {
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  for (int i = w; i < n; i += nw) {
-    const T* row = Mat + (size_t)i * pitch;
-    float a = 0.f;
-    for (int c = lane; c < (H >> 3); c += 64) {
+// dots[b, i] = vec[b, :] . Mat[i, b, :] for i < len[b].  The vector is either a T row (forward: H_t)
+// or the sum of fp32 planes (backward: dC_s from the step GEMM); in the latter case the wavefront of
+// position 0 also stores the summed vector to vsum[b, :] for the deferred attention gradients.
+template <typename T, bool PLANES>
+__global__ __launch_bounds__(256) void att_dots_kernel(const T* __restrict__ Mat, const T* __restrict__ vec, int ldv, Planes vp,
+                                                       float* __restrict__ vsum, const int32_t* __restrict__ len, int S,
+                                                       int Bp, int H, float* __restrict__ dots) {
+  const int lane = threadIdx.x & 63;
+  const int i = blockIdx.x * 4 + (threadIdx.x >> 6), b = blockIdx.y;
+  if (i >= S) return;
+  const bool active = i < len[b];
+  if (!active && !(PLANES && i == 0)) return;
+  const T* row = Mat + ((size_t)i * Bp + b) * H;
+  float a = 0.f;
+  for (int c = lane; c < (H >> 3); c += 64) {
+    float v[8];
+    if (PLANES) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = 0.f;
+      for (int k = 0; k < vp.np; ++k) {
+        Frag<float> fv;
+        fv.load(vp.p + (size_t)k * vp.stride + (size_t)b * vp.ld + 8 * c);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] += fv.get(e);
+      }
+      if (i == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vsum[(size_t)b * H + 8 * c + e] = v[e];
+      }
+    } else {
+      Frag<T> fv;
+      fv.load(vec + (size_t)b * ldv + 8 * c);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = fv.get(e);
+    }
+    if (active) {
       Frag<T> f;
       f.load(row + 8 * c);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) a += f.get(e) * vec[8 * c + e];
+      for (int e = 0; e < 8; ++e) a += f.get(e) * v[e];
     }
-    a = wave_sum(a);
-    if (lane == 0) dots[i] = a;
   }
-}
-// out[h] = sum_{i<n} coef[i] * Mat[i, b, h]; the thread block splits i into groups and reduces in LDS.
-// Returns the value for column-chunk owners (threads with group 0) in res[8].
-template <typename T>
-__device__ __forceinline__ bool att_wsum(const T* __restrict__ Mat, size_t pitch, int n, int H, const float* coef,
-                                         float* part /* [ng][H] */, float (&res)[8], int& chunk_out) {
-  const int nch = H >> 3;                                   // chunks of 8 columns
-  const int ng = max(1, (int)blockDim.x / nch);
-  const int t = threadIdx.x;
-  const int g = t / nch, c = t - g * nch;
-  float a[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) a[e] = 0.f;
-  if (g < ng) {
-    for (int i = g; i < n; i += ng) {
-      Frag<T> f;
-      f.load(Mat + (size_t)i * pitch + 8 * c);
-      const float w = coef[i];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) a[e] += w * f.get(e);
-    }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) part[(size_t)g * H + 8 * c + e] = a[e];
-  }
-  __syncthreads();
-  if (g != 0) return false;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    float s = 0.f;
-    for (int k = 0; k < ng; ++k) s += part[(size_t)k * H + 8 * c + e];
-    res[e] = s;
-  }
-  chunk_out = c;
-  return true;
+  if (!active) return;
+  a = wave_sum(a);
+  if (lane == 0) dots[(size_t)b * S + i] = a;
 }
 
-constexpr int ATT_MAXH = 1024, ATT_MAXS = 512;
-
-template <typename T>
-__global__ __launch_bounds__(256) void att_fwd_kernel(const T* __restrict__ Kmat, const T* __restrict__ Hs,
-                                                      const T* __restrict__ Ht, const int32_t* __restrict__ src_len,
-                                                      int S, int Bp, int H, float* __restrict__ a_out, T* __restrict__ Cs) {
-  __shared__ float vec[ATT_MAXH];
+constexpr int ATT_MAXS = 512;
+// MODE 0 (forward, Eq. 3 and 5): a = softmax(dots) over i < len, written by the h-chunk 0 block;
+//                                out = sum_i a_i Mat[i,b,:]  -> T
+// MODE 1 (backward): ds = a (dots - sum a dots), written by the h-chunk 0 block;
+//                    out = add[b,:] + sum_i ds_i Mat[i,b,:]  -> fp32
+// grid (H / 64 column chunks, Bp); 256 threads = 8 column-octets x 32 position groups
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void att_mix_kernel(const T* __restrict__ Mat, const float* __restrict__ dots,
+                                                      const float* __restrict__ a_in, const int32_t* __restrict__ len,
+                                                      int S, int Bp, int H, float* __restrict__ coef_out,
+                                                      void* __restrict__ out, Planes add, int add_col) {
   __shared__ float sc[ATT_MAXS];
-  __shared__ float part[2048];
-  const int b = blockIdx.x, t = threadIdx.x;
-  const int n = min(src_len[b], S);
-  for (int h = t; h < H; h += 256) vec[h] = to_f<T>(Ht[(size_t)b * H + h]);
-  __syncthreads();
-  const size_t pitch = (size_t)Bp * H;
-  att_dots<T>(Kmat + (size_t)b * H, pitch, n, H, vec, sc);
-  __syncthreads();
-  if (t < 64) {                                            // softmax over the valid positions (Eq. 3)
-    float mx = -INFINITY;
-    for (int i = t; i < n; i += 64) mx = fmaxf(mx, sc[i]);
-    mx = wave_max(mx);
-    float s = 0.f;
-    for (int i = t; i < n; i += 64) { const float e = expf(sc[i] - mx); sc[i] = e; s += e; }
-    s = wave_sum(s);
-    const float inv = n > 0 ? 1.f / s : 0.f;
-    for (int i = t; i < S; i += 64) {
-      const float a = i < n ? sc[i] * inv : 0.f;
-      if (i < n) sc[i] = a;
-      a_out[(size_t)b * S + i] = a;
+  __shared__ float part[32][65];
+  const int b = blockIdx.y, t = threadIdx.x;
+  const int n = min(len[b], S);
+  if (t < 64) {
+    if (MODE == 0) {
+      float mx = -INFINITY;
+      for (int i = t; i < n; i += 64) mx = fmaxf(mx, dots[(size_t)b * S + i]);
+      mx = wave_max(mx);
+      float s = 0.f;
+      for (int i = t; i < n; i += 64) { const float e = expf(dots[(size_t)b * S + i] - mx); sc[i] = e; s += e; }
+      s = wave_sum(s);
+      const float inv = n > 0 ? 1.f / s : 0.f;
+      for (int i = t; i < S; i += 64) {
+        const float a = i < n ? sc[i] * inv : 0.f;
+        if (i < n) sc[i] = a;
+        if (blockIdx.x == 0) coef_out[(size_t)b * S + i] = a;
+      }
+    } else {
+      float dot = 0.f;
+      for (int i = t; i < n; i += 64) dot += a_in[(size_t)b * S + i] * dots[(size_t)b * S + i];
+      dot = wave_sum(dot);
+      for (int i = t; i < S; i += 64) {
+        const float v = i < n ? a_in[(size_t)b * S + i] * (dots[(size_t)b * S + i] - dot) : 0.f;
+        if (i < n) sc[i] = v;
+        if (blockIdx.x == 0) coef_out[(size_t)b * S + i] = v;
+      }
     }
   }
   __syncthreads();
-  float res[8]; int c;
-  if (att_wsum<T>(Hs + (size_t)b * H, pitch, n, H, sc, part, res, c)) {
+  const int oct = t & 7, grp = t >> 3;                       // 8 octets = 64 columns; 32 position groups
+  const int h0 = blockIdx.x * 64 + oct * 8;
+  float acc[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) Cs[(size_t)b * H + 8 * c + e] = from_f<T>(res[e]);
+  for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+  if (h0 < H) {
+    for (int i = grp; i < n; i += 32) {
+      Frag<T> f;
+      f.load(Mat + ((size_t)i * Bp + b) * H + h0);
+      const float w = sc[i];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += w * f.get(e);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) part[grp][oct * 8 + e] = acc[e];
+  __syncthreads();
+  if (t < 64) {
+    const int h = blockIdx.x * 64 + t;
+    if (h < H) {
+      float s = 0.f;
+#pragma unroll
+      for (int g = 0; g < 32; ++g) s += part[g][t];
+      if (MODE == 0) ((T*)out)[(size_t)b * H + h] = from_f<T>(s);
+      else ((float*)out)[(size_t)b * H + h] = s + planes_get(add, b, add_col + h);
+    }
   }
 }
 
 void launch_att_fwd(int prec, const void* Kmat, const void* Hs, const void* Ht, const int32_t* src_len,
-                    int S, int Bp, int H, float* a, void* Cs, hipStream_t st) {
-  if (prec) hipLaunchKernelGGL(att_fwd_kernel<bf16_t>, dim3(Bp), dim3(256), 0, st, (const bf16_t*)Kmat, (const bf16_t*)Hs,
-                               (const bf16_t*)Ht, src_len, S, Bp, H, a, (bf16_t*)Cs);
-  else hipLaunchKernelGGL(att_fwd_kernel<float>, dim3(Bp), dim3(256), 0, st, (const float*)Kmat, (const float*)Hs,
-                          (const float*)Ht, src_len, S, Bp, H, a, (float*)Cs);
-}
-
-template <typename T>
-__global__ __launch_bounds__(256) void att_bwd_kernel(const T* __restrict__ Kmat, const T* __restrict__ Hs,
-                                                      const float* __restrict__ dCs, const float* __restrict__ a,
-                                                      const int32_t* __restrict__ src_len, int S, int Bp, int H,
-                                                      float* __restrict__ ds_out, float* __restrict__ dHt) {
-  __shared__ float vec[ATT_MAXH];
-  __shared__ float sc[ATT_MAXS];
-  __shared__ float part[2048];
-  const int b = blockIdx.x, t = threadIdx.x;
-  const int n = min(src_len[b], S);
-  for (int h = t; h < H; h += 256) vec[h] = dCs[(size_t)b * H + h];
-  __syncthreads();
-  const size_t pitch = (size_t)Bp * H;
-  att_dots<T>(Hs + (size_t)b * H, pitch, n, H, vec, sc);          // da_i = dC_s . H_s^i
-  __syncthreads();
-  if (t < 64) {                                                   // ds = a (da - sum a da)
-    float dot = 0.f;
-    for (int i = t; i < n; i += 64) dot += a[(size_t)b * S + i] * sc[i];
-    dot = wave_sum(dot);
-    for (int i = t; i < S; i += 64) {
-      const float v = i < n ? a[(size_t)b * S + i] * (sc[i] - dot) : 0.f;
-      if (i < n) sc[i] = v;
-      ds_out[(size_t)b * S + i] = v;
-    }
-  }
-  __syncthreads();
-  float res[8]; int c;
-  if (att_wsum<T>(Kmat + (size_t)b * H, pitch, n, H, sc, part, res, c)) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) dHt[(size_t)b * H + 8 * c + e] += res[e];
+                    int S, int Bp, int H, float* dots, float* a, void* Cs, hipStream_t st) {
+  dim3 gd((S + 3) / 4, Bp), gm((H + 63) / 64, Bp);
+  const Planes none{nullptr, 0, 0, 0};
+  if (prec) {
+    hipLaunchKernelGGL((att_dots_kernel<bf16_t, false>), gd, dim3(256), 0, st, (const bf16_t*)Kmat, (const bf16_t*)Ht, H, none, nullptr, src_len, S, Bp, H, dots);
+    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 0>), gm, dim3(256), 0, st, (const bf16_t*)Hs, dots, nullptr, src_len, S, Bp, H, a, Cs, none, 0);
+  } else {
+    hipLaunchKernelGGL((att_dots_kernel<float, false>), gd, dim3(256), 0, st, (const float*)Kmat, (const float*)Ht, H, none, nullptr, src_len, S, Bp, H, dots);
+    hipLaunchKernelGGL((att_mix_kernel<float, 0>), gm, dim3(256), 0, st, (const float*)Hs, dots, nullptr, src_len, S, Bp, H, a, Cs, none, 0);
   }
 }
 
-void launch_att_bwd(int prec, const void* Kmat, const void* Hs, const float* dCs, const float* a, const int32_t* src_len,
-                    int S, int Bp, int H, float* ds, float* dHt, hipStream_t st) {
-  if (prec) hipLaunchKernelGGL(att_bwd_kernel<bf16_t>, dim3(Bp), dim3(256), 0, st, (const bf16_t*)Kmat, (const bf16_t*)Hs,
-                               dCs, a, src_len, S, Bp, H, ds, dHt);
-  else hipLaunchKernelGGL(att_bwd_kernel<float>, dim3(Bp), dim3(256), 0, st, (const float*)Kmat, (const float*)Hs, dCs, a,
-                          src_len, S, Bp, H, ds, dHt);
+void launch_att_bwd(int prec, const void* Kmat, const void* Hs, const Planes& dCst, float* dCs_sum, const float* a,
+                    const int32_t* src_len, int S, int Bp, int H, float* dots, float* ds, float* dHt, hipStream_t st) {
+  // dCst planes [.., Bp, 2H]: columns [0,H) = dC_s, columns [H,2H) = the direct part of dH_t
+  dim3 gd((S + 3) / 4, Bp), gm((H + 63) / 64, Bp);
+  if (prec) {
+    hipLaunchKernelGGL((att_dots_kernel<bf16_t, true>), gd, dim3(256), 0, st, (const bf16_t*)Hs, nullptr, 0, dCst, dCs_sum, src_len, S, Bp, H, dots);
+    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 1>), gm, dim3(256), 0, st, (const bf16_t*)Kmat, dots, a, src_len, S, Bp, H, ds, dHt, dCst, H);
+  } else {
+    hipLaunchKernelGGL((att_dots_kernel<float, true>), gd, dim3(256), 0, st, (const float*)Hs, nullptr, 0, dCst, dCs_sum, src_len, S, Bp, H, dots);
+    hipLaunchKernelGGL((att_mix_kernel<float, 1>), gm, dim3(256), 0, st, (const float*)Kmat, dots, a, src_len, S, Bp, H, ds, dHt, dCst, H);
+  }
 }
 
 // After the decoder loop: for a block (sentence b, 256 hidden columns, 32 source positions):
 //   dHs[i,b,h] = sum_j a[j,b,i] dCs[j,b,h]        dK[i,b,h] = sum_j ds[j,b,i] Ht[j,b,h]
 template <typename T>
 __global__ __launch_bounds__(256) void att_deferred_kernel(const float* __restrict__ a, const float* __restrict__ ds,
-                                                           const float* __restrict__ dCs, const T* __restrict__ Ht, int ldht,
-                                                           int S, int Tn, int Bp, int H, float* __restrict__ dHs,
+                                                           const float* __restrict__ dCs, int lddc, const T* __restrict__ Ht,
+                                                           int ldht, int S, int Tn, int Bp, int H, float* __restrict__ dHs,
                                                            T* __restrict__ dK) {
   __shared__ float sa[32], sd[32];
   const int b = blockIdx.x, h = blockIdx.y * 256 + threadIdx.x, i0 = blockIdx.z * 32;
@@ -391,7 +600,7 @@ __global__ __launch_bounds__(256) void att_deferred_kernel(const float* __restri
     }
     __syncthreads();
     if (h < H) {
-      const float dc = dCs[((size_t)j * Bp + b) * H + h];
+      const float dc = dCs[((size_t)j * Bp + b) * lddc + h];
       const float ht = to_f<T>(Ht[(size_t)j * ldht + (size_t)b * H + h]);
 #pragma unroll
       for (int i = 0; i < 32; ++i) { accC[i] += sa[i] * dc; accK[i] += sd[i] * ht; }
@@ -408,30 +617,33 @@ __global__ __launch_bounds__(256) void att_deferred_kernel(const float* __restri
   }
 }
 
-void launch_att_deferred(int prec, const float* a, const float* ds, const float* dCs, const void* Ht, int ldht,
+void launch_att_deferred(int prec, const float* a, const float* ds, const float* dCs, int lddc, const void* Ht, int ldht,
                          int S, int T, int Bp, int H, float* dHs, void* dK, hipStream_t st) {
   dim3 grid(Bp, (H + 255) / 256, (S + 31) / 32);
-  if (prec) hipLaunchKernelGGL(att_deferred_kernel<bf16_t>, grid, dim3(256), 0, st, a, ds, dCs, (const bf16_t*)Ht, ldht, S, T,
+  if (prec) hipLaunchKernelGGL(att_deferred_kernel<bf16_t>, grid, dim3(256), 0, st, a, ds, dCs, lddc, (const bf16_t*)Ht, ldht, S, T,
                                Bp, H, dHs, (bf16_t*)dK);
-  else hipLaunchKernelGGL(att_deferred_kernel<float>, grid, dim3(256), 0, st, a, ds, dCs, (const float*)Ht, ldht, S, T, Bp, H,
+  else hipLaunchKernelGGL(att_deferred_kernel<float>, grid, dim3(256), 0, st, a, ds, dCs, lddc, (const float*)Ht, ldht, S, T, Bp, H,
                           dHs, (float*)dK);
 }
 
+// dpre = (dHo_ce + feed) * (1 - Ho^2) -> T; feed arrives as planes (np = 0: none)
 template <typename T>
-__global__ __launch_bounds__(256) void tanh_bwd_kernel(const float* __restrict__ dce, const float* __restrict__ dfeed,
-                                                       const T* __restrict__ Ho, T* __restrict__ dpre, int n) {
+__global__ __launch_bounds__(256) void tanh_bwd_kernel(const float* __restrict__ dce, Planes feed, const T* __restrict__ Ho,
+                                                       T* __restrict__ dpre, int Bp, int H) {
   const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= n) return;
+  if (i >= Bp * H) return;
+  const int b = i / H, h = i - b * H;
   const float ho = to_f<T>(Ho[i]);
-  const float d = dce[i] + (dfeed ? dfeed[i] : 0.f);
+  const float d = dce[i] + planes_get(feed, b, h);
   dpre[i] = from_f<T>(d * (1.f - ho * ho));
 }
 
-void launch_tanh_bwd(int prec, const float* dHo_ce, const float* dHo_feed, const void* Ho, void* dpre, int n, hipStream_t st) {
-  if (prec) hipLaunchKernelGGL(tanh_bwd_kernel<bf16_t>, dim3((n + 255) / 256), dim3(256), 0, st, dHo_ce, dHo_feed,
-                               (const bf16_t*)Ho, (bf16_t*)dpre, n);
-  else hipLaunchKernelGGL(tanh_bwd_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, st, dHo_ce, dHo_feed,
-                          (const float*)Ho, (float*)dpre, n);
+void launch_tanh_bwd(int prec, const float* dHo_ce, const Planes& feed, const void* Ho, void* dpre, int Bp, int H, hipStream_t st) {
+  const int n = Bp * H;
+  if (prec) hipLaunchKernelGGL(tanh_bwd_kernel<bf16_t>, dim3((n + 255) / 256), dim3(256), 0, st, dHo_ce, feed,
+                               (const bf16_t*)Ho, (bf16_t*)dpre, Bp, H);
+  else hipLaunchKernelGGL(tanh_bwd_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, st, dHo_ce, feed,
+                          (const float*)Ho, (float*)dpre, Bp, H);
 }
 
 }  // namespace cmt
