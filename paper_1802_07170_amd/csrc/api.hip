@@ -12,6 +12,7 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <string>
@@ -93,6 +94,9 @@ struct cmt_handle {
   float* dXt = nullptr; char* XtT = nullptr;
   float *pmax = nullptr, *psum = nullptr, *zy = nullptr, *lse = nullptr, *nll = nullptr, *rowscale = nullptr;
   float* loss = nullptr; int* flags = nullptr; float* colscr = nullptr;
+  char* dzs = nullptr; char* dzTs = nullptr; float* ce_colscr = nullptr; float* dbo_parts = nullptr;
+  float* gsplit = nullptr; size_t gsplit_floats = 0;
+  int ce_bwd_fused = 0;                 // 1: rebuild dz in LDS inside the product kernels; 0: slab staging
   size_t ws_bytes = 0;
 
   const char* Pw(size_t off) const { return Pc + off * esz; }
@@ -204,6 +208,11 @@ size_t layout(cmt_handle* h, char* base) {
   h->rowscale = (float*)a.take(Mt * 4);
   h->loss = (float*)a.take(256); h->flags = (int*)a.take(256);
   h->colscr = (float*)a.take((size_t)16 * 4 * H * 4);
+  h->dzs = a.take(ce_slab_elems(c.tgt_vocab) * esz); h->dzTs = a.take(ce_slab_elems(c.tgt_vocab) * esz);
+  h->ce_colscr = (float*)a.take((size_t)16 * c.tgt_vocab * 4);
+  h->dbo_parts = (float*)a.take((Mt / CE_SLAB_ROWS + 1) * c.tgt_vocab * 4);
+  h->gsplit_floats = (size_t)8 * CE_SLAB_ROWS * 1024;
+  h->gsplit = (float*)a.take(h->gsplit_floats * 4);
   return (a.off + 255) & ~(size_t)255;
 }
 
@@ -421,19 +430,25 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   // ---- Eq. 1: fused projection + log-softmax + cross-entropy --------------------------------------
   const char* Ho = h->HoBuf + BH * esz;            // [T*Bp, H]
   const int np = ce_num_partials(V);
-  launch_ce_fwd(p, Ho, h->Pw(h->off_Wo), P + h->off_Bo, h->labels, Mt, V, H, h->pmax, h->psum, h->zy, st);
+  launch_ce_fwd(p, Ho, H, h->Pw(h->off_Wo), P + h->off_Bo, h->labels, Mt, V, H, h->pmax, h->psum, h->zy, st);
   launch_ce_reduce(h->pmax, h->psum, h->zy, h->mask_t, Mt, np, h->lse, h->nll, h->rowscale, h->loss, h->flags, st);
 
   // =================================== backward ======================================================
   const int ldHoT = Mt + Bp;
   launch_transpose(p, h->HoBuf, H, h->HoBufT, ldHoT, Mt + Bp, H, st);
   const char* HoT = h->HoBufT + (size_t)Bp * esz;  // columns of H_o^{<0..T-1>}
-  const int nsplit = ce_bwd_nsplit(Mt, V);
-  launch_ce_bwd_dh(p, Ho, h->Pw(h->off_Wo), h->WoT, P + h->off_Bo, h->labels, h->lse, h->rowscale, Mt, V, H, nsplit,
-                   h->dHoPart, st);
-  launch_sum_parts(h->dHoPart, nsplit, (size_t)Mt * H, h->dHoCE, st);
-  launch_ce_bwd_dw(p, Ho, HoT, ldHoT, h->Pw(h->off_Wo), P + h->off_Bo, h->labels, h->lse, h->rowscale, Mt, V, H,
-                   G + h->off_Wo, G + h->off_Bo, st);
+  if (h->ce_bwd_fused) {
+    const int nsplit = ce_bwd_nsplit(Mt, V);
+    launch_ce_bwd_dh(p, Ho, h->Pw(h->off_Wo), h->WoT, P + h->off_Bo, h->labels, h->lse, h->rowscale, Mt, V, H, nsplit,
+                     h->dHoPart, st);
+    launch_sum_parts(h->dHoPart, nsplit, (size_t)Mt * H, h->dHoCE, st);
+    launch_ce_bwd_dw(p, Ho, HoT, ldHoT, h->Pw(h->off_Wo), P + h->off_Bo, h->labels, h->lse, h->rowscale, Mt, V, H,
+                     G + h->off_Wo, G + h->off_Bo, st);
+  } else {
+    launch_ce_bwd_slab(p, Ho, H, HoT, ldHoT, h->Pw(h->off_Wo), h->WoT, P + h->off_Bo, h->labels, h->lse, h->rowscale, Mt, V,
+                       H, h->dzs, h->dzTs, h->dHoCE, G + h->off_Wo, G + h->off_Bo, h->ce_colscr, h->dbo_parts, h->gsplit,
+                       h->gsplit_floats, st);
+  }
 
   // ---- decoder loop backwards -----------------------------------------------------------------------
   for (int l = 0; l < L; ++l) { launch_fill_f32(h->dec[l].dh, BH, 0.f, st); launch_fill_f32(h->dec[l].dc, BH, 0.f, st); }
@@ -584,6 +599,10 @@ int cmt_create(const cmt_config* cfg, void* params_dev, void* grads_dev, void* w
   h->st = (hipStream_t)hip_stream;
   h->params = (float*)params_dev; h->grads = (float*)grads_dev; h->ws = (char*)workspace_dev;
   h->Bpm = round_up(cfg->max_batch, 16);
+  {
+    const char* e = getenv("CMT_CE_BWD");
+    h->ce_bwd_fused = (e && std::string(e) == "fused") ? 1 : 0;
+  }
   build_table(h->cfg, h->table, h->nparams);
   h->ws_bytes = layout(h, h->ws);
   bind_params(h);

@@ -11,39 +11,50 @@
 
 namespace cmt {
 
-int ce_num_partials(int V) { return 2 * ((V + GEMM_BN - 1) / GEMM_BN); }
+constexpr int CE_TA = 4, CE_TB = 4;                       // 256 x 256 logit tile per workgroup
+using CeTile = GemmTile<CE_TA, CE_TB>;
+int ce_num_partials(int V) { return 2 * ((V + CeTile::BN - 1) / CeTile::BN); }
 
 template <typename T>
-__global__ __launch_bounds__(256) void ce_fwd_kernel(const T* __restrict__ Ho, const T* __restrict__ Wo,
+__global__ __launch_bounds__(256) void ce_fwd_kernel(const T* __restrict__ Ho, int ldho, const T* __restrict__ Wo,
                                                      const float* __restrict__ Bo, const int32_t* __restrict__ labels,
                                                      int M, int V, int H, float* __restrict__ pmax,
                                                      float* __restrict__ psum, float* __restrict__ zy, int np) {
-  __shared__ __align__(16) char smem[GEMM_SMEM_BYTES];
-  const int m0 = blockIdx.y * GEMM_BM, n0 = blockIdx.x * GEMM_BN;
-  v16f acc[2][2];
-  gemm_mainloop<T>(Ho, H, Wo, H, M, V, H, m0, n0, acc, smem);
+  __shared__ __align__(16) char smem[CeTile::SMEM_BYTES];
+  const int m0 = blockIdx.y * CeTile::BM, n0 = blockIdx.x * CeTile::BN;
+  v16f acc[CE_TA][CE_TB];
+  gemm_mainloop<T, CE_TA, CE_TB>(Ho, ldho, Wo, H, M, V, H, m0, n0, acc, smem);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int wm = w >> 1, wn = w & 1;
-  const int c0 = n0 + wn * 64 + (lane & 31), c1 = c0 + 32;
-  const float b0 = c0 < V ? Bo[c0] : 0.f, b1 = c1 < V ? Bo[c1] : 0.f;
+  int col[CE_TB];
+  float bo[CE_TB];
+#pragma unroll
+  for (int b = 0; b < CE_TB; ++b) {
+    col[b] = n0 + wn * 32 * CE_TB + b * 32 + (lane & 31);
+    bo[b] = col[b] < V ? Bo[col[b]] : 0.f;
+  }
   const int pidx = blockIdx.x * 2 + wn;
 #pragma unroll
-  for (int mt = 0; mt < 2; ++mt) {
+  for (int mt = 0; mt < CE_TA; ++mt) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int row = m0 + wm * 64 + mt * 32 + acc32_row(lane, i);
-      const float z0 = c0 < V ? acc[mt][0][i] + b0 : -INFINITY;
-      const float z1 = c1 < V ? acc[mt][1][i] + b1 : -INFINITY;
-      if (row < M) {
-        const int y = labels[row];
-        if (y == c0) zy[row] = z0;
-        if (y == c1) zy[row] = z1;
+      const int row = m0 + wm * 32 * CE_TA + mt * 32 + acc32_row(lane, i);
+      const int y = row < M ? labels[row] : -1;
+      float z[CE_TB];
+      float mx = -INFINITY;
+#pragma unroll
+      for (int b = 0; b < CE_TB; ++b) {
+        z[b] = col[b] < V ? acc[mt][b][i] + bo[b] : -INFINITY;
+        if (y == col[b]) zy[row] = z[b];
+        mx = fmaxf(mx, z[b]);
       }
-      float mx = fmaxf(z0, z1);
 #pragma unroll
       for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
       float e = 0.f;
-      if (mx > -INFINITY) e = expf(z0 - mx) + expf(z1 - mx);      // exp(-inf) = 0 for columns past V
+      if (mx > -INFINITY) {
+#pragma unroll
+        for (int b = 0; b < CE_TB; ++b) e += expf(z[b] - mx);              // exp(-inf) = 0 for columns past V
+      }
 #pragma unroll
       for (int o = 16; o > 0; o >>= 1) e += __shfl_xor(e, o, 64);
       if ((lane & 31) == 0 && row < M) {
@@ -54,15 +65,15 @@ __global__ __launch_bounds__(256) void ce_fwd_kernel(const T* __restrict__ Ho, c
   }
 }
 
-void launch_ce_fwd(int prec, const void* Ho, const void* Wo, const float* Bo, const int32_t* labels,
+void launch_ce_fwd(int prec, const void* Ho, int ldho, const void* Wo, const float* Bo, const int32_t* labels,
                    int M, int V, int H, float* pmax, float* psum, float* zy, hipStream_t st) {
-  dim3 grid((V + GEMM_BN - 1) / GEMM_BN, (M + GEMM_BM - 1) / GEMM_BM);
+  dim3 grid((V + CeTile::BN - 1) / CeTile::BN, (M + CeTile::BM - 1) / CeTile::BM);
   const int np = ce_num_partials(V);
   if (prec)
-    hipLaunchKernelGGL(ce_fwd_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)Ho, (const bf16_t*)Wo, Bo, labels,
+    hipLaunchKernelGGL(ce_fwd_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)Ho, ldho, (const bf16_t*)Wo, Bo, labels,
                        M, V, H, pmax, psum, zy, np);
   else
-    hipLaunchKernelGGL(ce_fwd_kernel<float>, grid, dim3(256), 0, st, (const float*)Ho, (const float*)Wo, Bo, labels,
+    hipLaunchKernelGGL(ce_fwd_kernel<float>, grid, dim3(256), 0, st, (const float*)Ho, ldho, (const float*)Wo, Bo, labels,
                        M, V, H, pmax, psum, zy, np);
 }
 
@@ -297,6 +308,94 @@ void launch_ce_bwd_dw(int prec, const void* Ho, const void* HoT, int ldhot, cons
   else
     ce_bwd_dispatch<float, 1>((const float*)Wo, V, (const float*)Ho, M, (const float*)HoT, ldhot, Bo, labels, lse,
                               rowscale, H, 1, dWo, dBo, st);
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward, slab variant.  For a slab of at most CE_SLAB_ROWS rows the logits are rebuilt tile by
+// tile (same main loop as the forward kernel) and dz = (softmax(z) - onehot) * mask / n_tok is
+// written, in the operand type, as dz[rows, V] and dz^T[V, rows]; two plain GEMMs then give
+// dH_o = dz W_o and dW_o += dz^T H_o at full matrix-core tiles.  Recomputing a dz element costs
+// 2H flops against 6 bytes of slab traffic, so on this machine staging a bounded slab beats
+// rebuilding dz a second time; the slab is reused for every group of rows, its size does not grow
+// with the batch, and the full [rows, vocabulary] matrix never exists.
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void ce_dz_kernel(const T* __restrict__ Ho, int ldho, const T* __restrict__ Wo,
+                                                    const float* __restrict__ Bo, const int32_t* __restrict__ labels,
+                                                    const float* __restrict__ lse, const float* __restrict__ rowscale,
+                                                    int Mc, int V, int H, T* __restrict__ dz, int ldz,
+                                                    T* __restrict__ dzT, int ldzt, int ntn) {
+  using G = GemmTile<2, 2, 128>;
+  __shared__ __align__(16) char smem[G::SMEM_BYTES];
+  const int per = gridDim.x >> 3;
+  const int id = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  const int m0 = (id / ntn) * G::BM, n0 = (id % ntn) * G::BN;
+  if (m0 >= Mc) return;
+  v16f acc[2][2];
+  gemm_mainloop<T, 2, 2, 128>(Ho, ldho, Wo, H, Mc, V, H, m0, n0, acc, smem);
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int wm = w >> 1, wn = w & 1;
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt) {
+    const int col = n0 + wn * 64 + nt * 32 + (lane & 31);
+    if (col >= V) continue;
+    const float bo = Bo[col];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {                       // 4 groups of 4 consecutive rows
+        const int row0 = m0 + wm * 64 + mt * 32 + acc32_row(lane, 4 * q);
+        T v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int row = row0 + i;
+          float d = 0.f;
+          if (row < Mc)
+            d = (expf(acc[mt][nt][4 * q + i] + bo - lse[row]) - (labels[row] == col ? 1.f : 0.f)) * rowscale[row];
+          v[i] = from_f<T>(d);
+          if (row < Mc) dz[(size_t)row * ldz + col] = v[i];
+        }
+        if (row0 < Mc) {                                  // ldzt and row0 are multiples of 4: one aligned store
+          T* o = dzT + (size_t)col * ldzt + row0;
+          if (sizeof(T) == 2) *reinterpret_cast<uint2*>(o) = *reinterpret_cast<const uint2*>(v);
+          else *reinterpret_cast<uint4*>(o) = *reinterpret_cast<const uint4*>(v);
+        }
+      }
+    }
+  }
+}
+
+size_t ce_slab_elems(int V) { return (size_t)CE_SLAB_ROWS * V; }
+
+void launch_ce_bwd_slab(int prec, const void* Ho, int ldho, const void* HoT, int ldhot, const void* Wo, const void* WoT,
+                        const float* Bo, const int32_t* labels, const float* lse, const float* rowscale, int M, int V, int H,
+                        void* dz, void* dzT, float* dHo, float* dWo, float* dBo, float* colscratch, float* dbo_parts,
+                        float* split_scratch, size_t split_scratch_floats, hipStream_t st) {
+  using G = GemmTile<2, 2, 128>;
+  const size_t esz = prec ? 2 : 4;
+  const int nslab = (M + CE_SLAB_ROWS - 1) / CE_SLAB_ROWS;
+  for (int s = 0; s < nslab; ++s) {
+    const int m0 = s * CE_SLAB_ROWS;
+    const int Mc = M - m0 < CE_SLAB_ROWS ? M - m0 : CE_SLAB_ROWS;     // multiple of 16 (rows come in padded batches)
+    const int ntm = (Mc + G::BM - 1) / G::BM, ntn = (V + G::BN - 1) / G::BN;
+    const int grid = ((ntm * ntn + 7) / 8) * 8;
+    const char* ho = (const char*)Ho + (size_t)m0 * ldho * esz;
+    if (prec)
+      hipLaunchKernelGGL(ce_dz_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, (const bf16_t*)ho, ldho, (const bf16_t*)Wo, Bo,
+                         labels + m0, lse + m0, rowscale + m0, Mc, V, H, (bf16_t*)dz, V, (bf16_t*)dzT, CE_SLAB_ROWS, ntn);
+    else
+      hipLaunchKernelGGL(ce_dz_kernel<float>, dim3(grid), dim3(256), 0, st, (const float*)ho, ldho, (const float*)Wo, Bo,
+                         labels + m0, lse + m0, rowscale + m0, Mc, V, H, (float*)dz, V, (float*)dzT, CE_SLAB_ROWS, ntn);
+    // dH_o[slab] = dz W_o            (k = V)
+    launch_gemm_nt(prec, dz, V, WoT, V, Mc, H, V, dHo + (size_t)m0 * H, nullptr, H, nullptr, 0, st, split_scratch,
+                   split_scratch_floats);
+    // dW_o (+)= dz^T H_o[slab]       (k = slab rows)
+    launch_gemm_nt(prec, dzT, CE_SLAB_ROWS, (const char*)HoT + (size_t)m0 * esz, ldhot, V, H, Mc, dWo, nullptr, H, nullptr,
+                   s > 0, st);
+    // dB_o parts: column sums of the slab
+    launch_colsum(prec, dz, Mc, V, colscratch, dbo_parts + (size_t)s * V, st);
+  }
+  launch_sum_parts(dbo_parts, nslab, (size_t)V, dBo, st);
 }
 
 }  // namespace cmt

@@ -7,26 +7,38 @@
 
 namespace cmt {
 
-template <typename T>
+// blockIdx.y = k split index: each split contracts kchunk elements of k and, when there is more
+// than one, writes its own fp32 plane Cf + split * plane_stride (summed afterwards, fixed order).
+template <typename T, int TA, int TB, int KB>
 __global__ __launch_bounds__(256) void gemm_nt_kernel(const T* __restrict__ A, int lda, const T* __restrict__ B, int ldb,
                                                       int M, int N, int K, float* __restrict__ Cf, T* __restrict__ Ct,
-                                                      int ldc, const float* __restrict__ bias, int accumulate) {
-  __shared__ __align__(16) char smem[GEMM_SMEM_BYTES];
-  const int m0 = blockIdx.y * GEMM_BM, n0 = blockIdx.x * GEMM_BN;
-  v16f acc[2][2];
-  gemm_mainloop<T>(A, lda, B, ldb, M, N, K, m0, n0, acc, smem);
+                                                      int ldc, const float* __restrict__ bias, int accumulate, int ntn,
+                                                      int kchunk, size_t plane_stride) {
+  using G = GemmTile<TA, TB, KB>;
+  __shared__ __align__(16) char smem[G::SMEM_BYTES];
+  // consecutive workgroup ids go round-robin to the 8 XCDs: give each XCD a contiguous band of
+  // tiles that share their A rows, so that operand tiles are re-read from that XCD's L2
+  const int per = gridDim.x >> 3;
+  const int id = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  const int m0 = (id / ntn) * G::BM, n0 = (id % ntn) * G::BN;
+  if (m0 >= M) return;
+  const int k0 = blockIdx.y * kchunk;
+  const int klen = min(kchunk, K - k0);
+  v16f acc[TA][TB];
+  gemm_mainloop<T, TA, TB, KB>(A + k0, lda, B + k0, ldb, M, N, klen, m0, n0, acc, smem);
+  if (gridDim.y > 1) Cf += blockIdx.y * plane_stride;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int wm = w >> 1, wn = w & 1;
 #pragma unroll
-  for (int nt = 0; nt < 2; ++nt) {
-    const int col = n0 + wn * 64 + nt * 32 + (lane & 31);
+  for (int nt = 0; nt < TB; ++nt) {
+    const int col = n0 + wn * 32 * TB + nt * 32 + (lane & 31);
     if (col >= N) continue;
     const float bv = bias ? bias[col] : 0.f;
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
+    for (int mt = 0; mt < TA; ++mt) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const int row = m0 + wm * 64 + mt * 32 + acc32_row(lane, i);
+        const int row = m0 + wm * 32 * TA + mt * 32 + acc32_row(lane, i);
         if (row >= M) continue;
         const size_t o = (size_t)row * ldc + col;
         float v = acc[mt][nt][i] + bv;
@@ -38,16 +50,57 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const T* __restrict__ A, i
   }
 }
 
+// out = sum of planes (+ bias per column) (+ previous out)
+__global__ __launch_bounds__(256) void gemm_planes_sum_kernel(const float* __restrict__ planes, int np, size_t stride,
+                                                              float* __restrict__ out, int M, int N, int ldc,
+                                                              const float* __restrict__ bias, int accumulate) {
+  const size_t n = (size_t)M * N;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const size_t r = i / N, c = i - r * N;
+    float v = bias ? bias[c] : 0.f;
+    for (int p = 0; p < np; ++p) v += planes[(size_t)p * stride + i];
+    float* o = out + r * ldc + c;
+    *o = accumulate ? *o + v : v;
+  }
+}
+
 void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, int M, int N, int K,
-                    float* Cf, void* Ct, int ldc, const float* bias, int accumulate, hipStream_t st) {
+                    float* Cf, void* Ct, int ldc, const float* bias, int accumulate, hipStream_t st,
+                    float* split_scratch, size_t split_scratch_floats) {
   if (M <= 0 || N <= 0) return;
-  dim3 grid((N + GEMM_BN - 1) / GEMM_BN, (M + GEMM_BM - 1) / GEMM_BM);
+  using G = GemmTile<2, 2, 128>;
+  const int ntm = (M + G::BM - 1) / G::BM, ntn = (N + G::BN - 1) / G::BN;
+  const int nb = ntm * ntn;
+  const int grid = ((nb + 7) / 8) * 8;
+  const int esz = prec ? 2 : 4;
+  const int bk = 128 / esz;
+  // few output tiles but a long contraction: split k over workgroups
+  int ks = 1;
+  if (split_scratch && Cf && !Ct && nb < 128 && K >= 16 * bk) {
+    ks = (256 + nb - 1) / nb;
+    if (ks > 8) ks = 8;
+    while (ks > 1 && ((size_t)ks * M * N > split_scratch_floats || K / ks < 4 * bk)) --ks;
+  }
+  int kchunk = K;
+  if (ks > 1) kchunk = ((K + ks - 1) / ks + bk - 1) / bk * bk;
+  const int nks = (K + kchunk - 1) / kchunk;
+  const size_t pstride = (size_t)M * N;
+  float* out = nks > 1 ? split_scratch : Cf;
+  const int oldc = nks > 1 ? N : ldc;
+  const float* obias = nks > 1 ? nullptr : bias;
+  const int oacc = nks > 1 ? 0 : accumulate;
   if (prec)
-    hipLaunchKernelGGL(gemm_nt_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)A, lda,
-                       (const bf16_t*)B, ldb, M, N, K, Cf, (bf16_t*)Ct, ldc, bias, accumulate);
+    hipLaunchKernelGGL((gemm_nt_kernel<bf16_t, 2, 2, 128>), dim3(grid, nks), dim3(256), 0, st, (const bf16_t*)A, lda,
+                       (const bf16_t*)B, ldb, M, N, K, out, (bf16_t*)Ct, oldc, obias, oacc, ntn, kchunk, pstride);
   else
-    hipLaunchKernelGGL(gemm_nt_kernel<float>, grid, dim3(256), 0, st, (const float*)A, lda,
-                       (const float*)B, ldb, M, N, K, Cf, (float*)Ct, ldc, bias, accumulate);
+    hipLaunchKernelGGL((gemm_nt_kernel<float, 2, 2, 128>), dim3(grid, nks), dim3(256), 0, st, (const float*)A, lda,
+                       (const float*)B, ldb, M, N, K, out, (float*)Ct, oldc, obias, oacc, ntn, kchunk, pstride);
+  if (nks > 1) {
+    size_t g = (pstride + 255) / 256;
+    if (g > 4096) g = 4096;
+    hipLaunchKernelGGL(gemm_planes_sum_kernel, dim3((unsigned)g), dim3(256), 0, st, split_scratch, nks, pstride, Cf, M, N, ldc,
+                       bias, accumulate);
+  }
 }
 
 // 64x64 tiles through LDS; reads and writes are both row-contiguous.

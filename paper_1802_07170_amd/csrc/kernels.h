@@ -11,8 +11,11 @@ namespace cmt {
 // C[M,N] = A[M,K] * B[N,K]^T (+ bias[N]) (+ previous C when accumulate), both operands with k
 // contiguous.  Writes fp32 to Cf (if non-null) and T to Ct (if non-null), same ldc.
 // K, lda, ldb multiples of 8.
+// When split_scratch is given and the output has few tiles but K is long, k is split over workgroups
+// into fp32 planes in the scratch (at most 8 * M * N floats) that a second kernel sums.
 void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, int M, int N, int K,
-                    float* Cf, void* Ct, int ldc, const float* bias, int accumulate, hipStream_t st);
+                    float* Cf, void* Ct, int ldc, const float* bias, int accumulate, hipStream_t st,
+                    float* split_scratch = nullptr, size_t split_scratch_floats = 0);
 // out[C,R] = in[R,C]^T for T matrices (ldin, ldout in elements).
 void launch_transpose(int prec, const void* in, int ldin, void* out, int ldout, int R, int C, hipStream_t st);
 
@@ -20,7 +23,7 @@ void launch_transpose(int prec, const void* in, int ldin, void* out, int ldout, 
 // Eq. 1 forward, fused: logits tile by tile, never stored.  Ho [M,H] T, Wo [V,H] T, Bo [V] fp32,
 // labels [M] int32.  pmax/psum [M, np] fp32 with np = ce_num_partials(V); zy [M] fp32.
 int ce_num_partials(int V);
-void launch_ce_fwd(int prec, const void* Ho, const void* Wo, const float* Bo, const int32_t* labels,
+void launch_ce_fwd(int prec, const void* Ho, int ldho, const void* Wo, const float* Bo, const int32_t* labels,
                    int M, int V, int H, float* pmax, float* psum, float* zy, hipStream_t st);
 // lse[M], nll[M] (masked), rowscale[M] = mask / n_tok, loss = sum nll / n_tok; flags |= 4 if the loss
 // is not finite.  One launch, deterministic summation order.
@@ -38,6 +41,17 @@ void launch_ce_bwd_dh(int prec, const void* Ho, const void* Wo, const void* WoT,
 void launch_ce_bwd_dw(int prec, const void* Ho, const void* HoT, int ldhot, const void* Wo, const float* Bo,
                       const int32_t* labels, const float* lse, const float* rowscale,
                       int M, int V, int H, float* dWo, float* dBo, hipStream_t st);
+
+// Slab variant of the backward: dz is staged for at most CE_SLAB_ROWS rows at a time (dz [rows, V] and
+// dzT [V, CE_SLAB_ROWS], both T, ce_slab_elems(V) elements each) and consumed by two plain GEMMs.
+// dHo [M,H], dWo [V,H], dBo [V] fp32 are written in full.  colscratch: 16 * V floats; dbo_parts:
+// ceil(M / CE_SLAB_ROWS) * V floats.
+constexpr int CE_SLAB_ROWS = 1024;
+size_t ce_slab_elems(int V);
+void launch_ce_bwd_slab(int prec, const void* Ho, int ldho, const void* HoT, int ldhot, const void* Wo, const void* WoT,
+                        const float* Bo, const int32_t* labels, const float* lse, const float* rowscale, int M, int V, int H,
+                        void* dz, void* dzT, float* dHo, float* dWo, float* dBo, float* colscratch, float* dbo_parts,
+                        float* split_scratch, size_t split_scratch_floats, hipStream_t st);
 
 // ---- step.hip ----------------------------------------------------------------------------------
 // A value delivered as `np` partial planes: v(b, c) = sum_k p[k * stride + b * ld + c]  (np = 0: zero).

@@ -58,15 +58,16 @@ void launch_gather(int prec, const void* table, int vocab, int E, const int32_t*
                           shift, bos, (float*)out, mask, tok, labels, len_p, flags);
 }
 
-// One workgroup per position p.  If no earlier position holds the same id, this workgroup sums the
-// gradient rows of every occurrence q >= p in ascending q and stores the row; otherwise it exits.
-constexpr int SCAT_MAXC = 8;     // columns per thread: E <= 256 * 8
+// One workgroup per (position p, block of 256 columns).  If no earlier position holds the same id,
+// this workgroup sums the gradient rows of every occurrence q >= p in ascending q and stores its
+// part of the row; otherwise it exits.  Rows are fetched 8 at a time so their loads overlap.
 __global__ __launch_bounds__(256) void embed_scatter_kernel(const float* __restrict__ dX, const int32_t* __restrict__ tok,
                                                             int n, int E, float* __restrict__ dE) {
   __shared__ int s_found;
   __shared__ int s_list[256];
   __shared__ int s_wcnt[4];
   const int p = blockIdx.x, t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const int col = blockIdx.y * 256 + t;
   const int id = tok[p];
   if (id < 0) return;
   if (t == 0) s_found = 0;
@@ -75,9 +76,7 @@ __global__ __launch_bounds__(256) void embed_scatter_kernel(const float* __restr
     if (tok[q] == id) s_found = 1;
   __syncthreads();
   if (s_found) return;
-  float acc[SCAT_MAXC];
-#pragma unroll
-  for (int c = 0; c < SCAT_MAXC; ++c) acc[c] = 0.f;
+  float acc = 0.f;
   for (int base = p; base < n; base += 256) {
     const int q = base + t;
     const bool match = q < n && tok[q] == id;
@@ -89,17 +88,18 @@ __global__ __launch_bounds__(256) void embed_scatter_kernel(const float* __restr
     const int total = s_wcnt[0] + s_wcnt[1] + s_wcnt[2] + s_wcnt[3];
     if (match) s_list[off + __popcll(bal & ((1ull << lane) - 1ull))] = q;
     __syncthreads();
-    for (int k = 0; k < total; ++k) {
-      const float* r = dX + (size_t)s_list[k] * E;
+    if (col < E) {
+      for (int k = 0; k < total; k += 8) {
+        float v[8];
 #pragma unroll
-      for (int c = 0; c < SCAT_MAXC; ++c)
-        if (t + 256 * c < E) acc[c] += r[t + 256 * c];
+        for (int j = 0; j < 8; ++j) v[j] = k + j < total ? dX[(size_t)s_list[k + j] * E + col] : 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc += v[j];
+      }
     }
     __syncthreads();
   }
-#pragma unroll
-  for (int c = 0; c < SCAT_MAXC; ++c)
-    if (t + 256 * c < E) dE[(size_t)id * E + t + 256 * c] = acc[c];
+  if (col < E) dE[(size_t)id * E + col] = acc;
 }
 
 __global__ __launch_bounds__(256) void fill_f32_kernel(float* __restrict__ p, size_t n, float v) {
@@ -123,7 +123,7 @@ void launch_fill_T(int prec, void* p, size_t n, hipStream_t st) {
 
 void launch_embed_scatter(const float* dX, const int32_t* tok, int n, int V, int E, float* dE, hipStream_t st) {
   launch_fill_f32(dE, (size_t)V * E, 0.f, st);
-  hipLaunchKernelGGL(embed_scatter_kernel, dim3(n), dim3(256), 0, st, dX, tok, n, E, dE);
+  hipLaunchKernelGGL(embed_scatter_kernel, dim3(n, (E + 255) / 256), dim3(256), 0, st, dX, tok, n, E, dE);
 }
 
 template <typename T>

@@ -357,12 +357,7 @@ __global__ __launch_bounds__(256) void step2d_kernel(StepGemm g, int Bp, StepGri
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void tanh_planes_kernel(Planes p, T* __restrict__ out, int ldo, int Bp, int N) {
-  const int idx = blockIdx.x * 256 + threadIdx.x;
-  if (idx >= Bp * N) return;
-  const int b = idx / N, n = idx - b * N;
-  out[(size_t)b * ldo + n] = from_f<T>(tanhf(planes_get(p, b, n)));
-}
+__global__ __launch_bounds__(256) void tanh_planes_kernel(Planes p, T* __restrict__ out, int ldo, int Bp, int N);
 
 void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st) {
   const int nbt = (Bp + 15) / 16;
@@ -375,7 +370,7 @@ void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st) {
 #undef GO
   if (g.mode == 0 && pl.kb > 1) {
     Planes p{g.out, g.ldout, pl.kb, g.plane_stride};
-    const int n = Bp * g.N;
+    const int n = Bp * (g.N >> 2);
     if (prec) hipLaunchKernelGGL(tanh_planes_kernel<bf16_t>, dim3((n + 255) / 256), dim3(256), 0, st, p, (bf16_t*)g.outT, g.ldo, Bp, g.N);
     else hipLaunchKernelGGL(tanh_planes_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, st, p, (float*)g.outT, g.ldo, Bp, g.N);
   }
@@ -384,38 +379,81 @@ void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st) {
 // ------------------------------------------------------------------------------------------------
 // LSTM cell backward (pointwise), one thread per (sentence, unit)
 // ------------------------------------------------------------------------------------------------
+// sum of the planes for 4 consecutive columns (c, ld and stride are multiples of 4); the loads of
+// all planes (at most 8) are independent and issued together
+__device__ __forceinline__ float4 planes_get4(const Planes& p, int b, int c) {
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  const float* base = p.p + (size_t)b * p.ld + c;
+  float4 t[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k)
+    t[k] = k < p.np ? *reinterpret_cast<const float4*>(base + (size_t)k * p.stride) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+  for (int k = 0; k < 8; ++k) { v.x += t[k].x; v.y += t[k].y; v.z += t[k].z; v.w += t[k].w; }
+  for (int k = 8; k < p.np; ++k) {
+    const float4 q = *reinterpret_cast<const float4*>(base + (size_t)k * p.stride);
+    v.x += q.x; v.y += q.y; v.z += q.z; v.w += q.w;
+  }
+  return v;
+}
+template <typename T> __device__ __forceinline__ void store4(T* p, const float (&v)[4]);
+template <> __device__ __forceinline__ void store4<float>(float* p, const float (&v)[4]) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+}
+template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t* p, const float (&v)[4]) {
+  uint2 o;
+  o.x = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
+  o.y = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
+  *reinterpret_cast<uint2*>(p) = o;
+}
+
+// one thread per (sentence, 4 consecutive units)
 template <typename T>
 __global__ __launch_bounds__(256) void lstm_bwd_point_kernel(LstmBwdPoint p, int Bp, int Hh) {
-  const int idx = blockIdx.x * 256 + threadIdx.x;
-  if (idx >= Bp * Hh) return;
-  const int b = idx / Hh, u = idx - b * Hh;
-  const float dh_state = p.dh[idx] + planes_get(p.dhrec, b, p.dhrec_col + u);
+  const int idx4 = blockIdx.x * 256 + threadIdx.x;
+  const int hq = Hh >> 2;
+  if (idx4 >= Bp * hq) return;
+  const int b = idx4 / hq, u = (idx4 - b * hq) * 4;
+  const size_t idx = (size_t)b * Hh + u;
+  const float4 rec = planes_get4(p.dhrec, b, p.dhrec_col + u);
+  const float4 dhp = *reinterpret_cast<const float4*>(p.dh + idx);
+  const float dh_state[4] = {dhp.x + rec.x, dhp.y + rec.y, dhp.z + rec.z, dhp.w + rec.w};
   T* dg = (T*)p.dg + (size_t)b * 4 * Hh + u;
+  const float zero[4] = {0.f, 0.f, 0.f, 0.f};
   if (!(p.mask[b] > 0.f)) {                       // masked step: state passes through, no gate gradient
-    const T z = from_f<T>(0.f);
-    dg[0] = z; dg[Hh] = z; dg[2 * Hh] = z; dg[3 * Hh] = z;
-    p.dh[idx] = dh_state;                          // (an output of a masked step is the constant 0: dy is dropped)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) store4<T>(dg + g * Hh, zero);
+    store4<float>(p.dh + idx, dh_state);           // (an output of a masked step is the constant 0: dy is dropped)
     return;
   }
-  const float dc_state = p.dc[idx];
-  const float dy = planes_get(p.dy, b, p.dy_col + u);
+  const float4 dy4 = planes_get4(p.dy, b, p.dy_col + u);
+  const float4 dc4 = *reinterpret_cast<const float4*>(p.dc + idx);
   const float* gs = p.gsave + (size_t)b * 4 * Hh + u;
-  const float ig = gs[0], fg = gs[Hh], gg = gs[2 * Hh], og = gs[3 * Hh];
-  const float cp = p.cprev[idx], cn = p.cnext[idx];
-  const float tc = tanhf(cn);
-  const float dh = dh_state + dy;
-  const float dog = dh * tc;
-  const float dc = dc_state + dh * og * (1.f - tc * tc);
-  dg[0] = from_f<T>(dc * gg * ig * (1.f - ig));
-  dg[Hh] = from_f<T>(dc * cp * fg * (1.f - fg));
-  dg[2 * Hh] = from_f<T>(dc * ig * (1.f - gg * gg));
-  dg[3 * Hh] = from_f<T>(dog * og * (1.f - og));
-  p.dc[idx] = dc * fg;
-  p.dh[idx] = 0.f;                                 // the recurrent part arrives as planes of the step GEMM
+  const float4 i4 = *reinterpret_cast<const float4*>(gs), f4 = *reinterpret_cast<const float4*>(gs + Hh);
+  const float4 g4 = *reinterpret_cast<const float4*>(gs + 2 * Hh), o4 = *reinterpret_cast<const float4*>(gs + 3 * Hh);
+  const float4 cp4 = *reinterpret_cast<const float4*>(p.cprev + idx), cn4 = *reinterpret_cast<const float4*>(p.cnext + idx);
+  float di[4], df[4], dgg[4], dout[4], dcn[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float ig = (&i4.x)[e], fg = (&f4.x)[e], gg = (&g4.x)[e], og = (&o4.x)[e];
+    const float cp = (&cp4.x)[e], cn = (&cn4.x)[e];
+    const float tc = tanhf(cn);
+    const float dh = dh_state[e] + (&dy4.x)[e];
+    const float dog = dh * tc;
+    const float dc = (&dc4.x)[e] + dh * og * (1.f - tc * tc);
+    di[e] = dc * gg * ig * (1.f - ig);
+    df[e] = dc * cp * fg * (1.f - fg);
+    dgg[e] = dc * ig * (1.f - gg * gg);
+    dout[e] = dog * og * (1.f - og);
+    dcn[e] = dc * fg;
+  }
+  store4<T>(dg, di); store4<T>(dg + Hh, df); store4<T>(dg + 2 * Hh, dgg); store4<T>(dg + 3 * Hh, dout);
+  store4<float>(p.dc + idx, dcn);
+  store4<float>(p.dh + idx, zero);                 // the recurrent part arrives as planes of the step GEMM
 }
 
 void launch_lstm_bwd_point(int prec, const LstmBwdPoint& p, int Bp, int Hh, hipStream_t st) {
-  const int n = Bp * Hh;
+  const int n = Bp * (Hh >> 2);
   if (prec) hipLaunchKernelGGL(lstm_bwd_point_kernel<bf16_t>, dim3((n + 255) / 256), dim3(256), 0, st, p, Bp, Hh);
   else hipLaunchKernelGGL(lstm_bwd_point_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, st, p, Bp, Hh);
 }
@@ -626,20 +664,41 @@ void launch_att_deferred(int prec, const float* a, const float* ds, const float*
                           dHs, (float*)dK);
 }
 
-// dpre = (dHo_ce + feed) * (1 - Ho^2) -> T; feed arrives as planes (np = 0: none)
+template <typename T>
+__global__ __launch_bounds__(256) void tanh_planes_kernel(Planes p, T* __restrict__ out, int ldo, int Bp, int N) {
+  const int i4 = blockIdx.x * 256 + threadIdx.x;
+  const int nq = N >> 2;
+  if (i4 >= Bp * nq) return;
+  const int b = i4 / nq, n = (i4 - b * nq) * 4;
+  const float4 v = planes_get4(p, b, n);
+  const float o[4] = {tanhf(v.x), tanhf(v.y), tanhf(v.z), tanhf(v.w)};
+  store4<T>(out + (size_t)b * ldo + n, o);
+}
+template __global__ void tanh_planes_kernel<bf16_t>(Planes, bf16_t*, int, int, int);
+template __global__ void tanh_planes_kernel<float>(Planes, float*, int, int, int);
+
+// dpre = (dHo_ce + feed) * (1 - Ho^2) -> T; feed arrives as planes (np = 0: none); 4 columns per thread
 template <typename T>
 __global__ __launch_bounds__(256) void tanh_bwd_kernel(const float* __restrict__ dce, Planes feed, const T* __restrict__ Ho,
                                                        T* __restrict__ dpre, int Bp, int H) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= Bp * H) return;
-  const int b = i / H, h = i - b * H;
-  const float ho = to_f<T>(Ho[i]);
-  const float d = dce[i] + planes_get(feed, b, h);
-  dpre[i] = from_f<T>(d * (1.f - ho * ho));
+  const int i4 = blockIdx.x * 256 + threadIdx.x;
+  const int hq = H >> 2;
+  if (i4 >= Bp * hq) return;
+  const int b = i4 / hq, h = (i4 - b * hq) * 4;
+  const size_t i = (size_t)b * H + h;
+  const float4 d = *reinterpret_cast<const float4*>(dce + i);
+  const float4 f = planes_get4(feed, b, h);
+  float o[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float ho = to_f<T>(Ho[i + e]);
+    o[e] = ((&d.x)[e] + (&f.x)[e]) * (1.f - ho * ho);
+  }
+  store4<T>(dpre + i, o);
 }
 
 void launch_tanh_bwd(int prec, const float* dHo_ce, const Planes& feed, const void* Ho, void* dpre, int Bp, int H, hipStream_t st) {
-  const int n = Bp * H;
+  const int n = Bp * (H >> 2);
   if (prec) hipLaunchKernelGGL(tanh_bwd_kernel<bf16_t>, dim3((n + 255) / 256), dim3(256), 0, st, dHo_ce, feed,
                                (const bf16_t*)Ho, (bf16_t*)dpre, Bp, H);
   else hipLaunchKernelGGL(tanh_bwd_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, st, dHo_ce, feed,

@@ -124,6 +124,21 @@ def test_ragged_small_nets(prec, B, S, T, H, E, L):
     tr.close()
 
 
+@pytest.mark.parametrize("mode", ["slab", "fused"])
+@pytest.mark.parametrize("prec", [0, 1])
+def test_both_cross_entropy_backward_variants(monkeypatch, mode, prec):
+    """The output-layer backward exists twice: dz staged in a bounded slab of <= 1024 rows (default),
+    and dz rebuilt in LDS inside the product kernels.  1120 rows here: two slabs, the second partial;
+    a vocabulary that is not a multiple of any tile."""
+    monkeypatch.setenv("CMT_CE_BWD", mode)
+    cfg = dict(src_vocab=104, tgt_vocab=328, emb=16, hidden=48, layers=1)
+    rng = np.random.default_rng(7)
+    params = I.make_params(cfg, seed=3, scale=0.3)
+    batch = ragged_batch(rng, 70, 4, 14, cfg["src_vocab"], cfg["tgt_vocab"])
+    loss, oloss, worst, tr = run_case(cfg, params, batch, prec, check_inter=False)
+    tr.close()
+
+
 def test_two_steps_are_bit_identical_and_sgd_matches_oracle():
     from paper_1802_07170_amd import binding
     c = I.CONFIGS["tiny"]
