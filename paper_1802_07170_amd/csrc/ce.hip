@@ -11,7 +11,7 @@
 
 namespace cmt {
 
-constexpr int CE_TA = 4, CE_TB = 4;                       // 256 x 256 logit tile per workgroup
+constexpr int CE_TA = 2, CE_TB = 2;                       // 128 x 128 logit tile per workgroup
 using CeTile = GemmTile<CE_TA, CE_TB>;
 int ce_num_partials(int V) { return 2 * ((V + CeTile::BN - 1) / CeTile::BN); }
 
@@ -139,7 +139,7 @@ void launch_ce_reduce(const float* pmax, const float* psum, const float* zy, con
 // split by columns, 32*HT per wavefront.
 // ------------------------------------------------------------------------------------------------
 template <typename T, int HT, int MODE>
-__global__ __launch_bounds__(512) void ce_bwd_kernel(const T* __restrict__ P, int nP, const T* __restrict__ Q, int nQ,
+__global__ __launch_bounds__(512) void ce_bwd_kernel(const T* __restrict__ P, int ldp, int nP, const T* __restrict__ Q, int ldq, int nQ,
                                                      const T* __restrict__ QT, int ldqt, const float* __restrict__ Bo,
                                                      const int32_t* __restrict__ labels, const float* __restrict__ lse,
                                                      const float* __restrict__ rowscale, int H, int tiles_per_split,
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(512) void ce_bwd_kernel(const T* __restrict__ P, in
 
   const int mt1 = w & 1, nt1 = w >> 1;                      // this wavefront's score tile
   const int prow = min(p0 + 32 * mt1 + (lane & 31), nP - 1);
-  const T* pa = P + (size_t)prow * H + 8 * (lane >> 5);
+  const T* pa = P + (size_t)prow * ldp + 8 * (lane >> 5);
   const int hbase = w * 32 * HT;
 
   for (int qt = t_begin; qt < t_end; ++qt) {
@@ -187,7 +187,7 @@ __global__ __launch_bounds__(512) void ce_bwd_kernel(const T* __restrict__ P, in
 #pragma unroll
     for (int i = 0; i < 16; ++i) s[i] = 0.f;
     const int qrow = min(q0 + 32 * nt1 + (lane & 31), nQ - 1);
-    const T* pb = Q + (size_t)qrow * H + 8 * (lane >> 5);
+    const T* pb = Q + (size_t)qrow * ldq + 8 * (lane >> 5);
     for (int k = 0; k < H; k += 64) {
       Frag<T> fa[4], fb[4];
 #pragma unroll
@@ -273,14 +273,14 @@ int ce_bwd_nsplit(int M, int V) {
 }
 
 template <typename T, int MODE>
-static void ce_bwd_dispatch(const T* P, int nP, const T* Q, int nQ, const T* QT, int ldqt, const float* Bo,
+static void ce_bwd_dispatch(const T* P, int ldp, int nP, const T* Q, int ldq, int nQ, const T* QT, int ldqt, const float* Bo,
                             const int32_t* labels, const float* lse, const float* rowscale, int H, int nsplit,
                             float* out, float* dBo, hipStream_t st) {
   const int ntiles = (nQ + 127) / 128;
   const int tps = (ntiles + nsplit - 1) / nsplit;
   dim3 grid((nP + 63) / 64, nsplit);
 #define CE_BWD_GO(HT)                                                                                          \
-  hipLaunchKernelGGL((ce_bwd_kernel<T, HT, MODE>), grid, dim3(512), 0, st, P, nP, Q, nQ, QT, ldqt, Bo, labels, \
+  hipLaunchKernelGGL((ce_bwd_kernel<T, HT, MODE>), grid, dim3(512), 0, st, P, ldp, nP, Q, ldq, nQ, QT, ldqt, Bo, labels, \
                      lse, rowscale, H, tps, out, dBo)
   if (H <= 256) CE_BWD_GO(1);
   else if (H <= 512) CE_BWD_GO(2);
@@ -288,25 +288,25 @@ static void ce_bwd_dispatch(const T* P, int nP, const T* Q, int nQ, const T* QT,
 #undef CE_BWD_GO
 }
 
-void launch_ce_bwd_dh(int prec, const void* Ho, const void* Wo, const void* WoT, const float* Bo,
+void launch_ce_bwd_dh(int prec, const void* Ho, int ldho, const void* Wo, const void* WoT, const float* Bo,
                       const int32_t* labels, const float* lse, const float* rowscale,
                       int M, int V, int H, int nsplit, float* dHo_part, hipStream_t st) {
   if (prec)
-    ce_bwd_dispatch<bf16_t, 0>((const bf16_t*)Ho, M, (const bf16_t*)Wo, V, (const bf16_t*)WoT, V, Bo, labels, lse,
+    ce_bwd_dispatch<bf16_t, 0>((const bf16_t*)Ho, ldho, M, (const bf16_t*)Wo, H, V, (const bf16_t*)WoT, V, Bo, labels, lse,
                                rowscale, H, nsplit, dHo_part, nullptr, st);
   else
-    ce_bwd_dispatch<float, 0>((const float*)Ho, M, (const float*)Wo, V, (const float*)WoT, V, Bo, labels, lse,
+    ce_bwd_dispatch<float, 0>((const float*)Ho, ldho, M, (const float*)Wo, H, V, (const float*)WoT, V, Bo, labels, lse,
                               rowscale, H, nsplit, dHo_part, nullptr, st);
 }
 
-void launch_ce_bwd_dw(int prec, const void* Ho, const void* HoT, int ldhot, const void* Wo, const float* Bo,
+void launch_ce_bwd_dw(int prec, const void* Ho, int ldho, const void* HoT, int ldhot, const void* Wo, const float* Bo,
                       const int32_t* labels, const float* lse, const float* rowscale,
                       int M, int V, int H, float* dWo, float* dBo, hipStream_t st) {
   if (prec)
-    ce_bwd_dispatch<bf16_t, 1>((const bf16_t*)Wo, V, (const bf16_t*)Ho, M, (const bf16_t*)HoT, ldhot, Bo, labels, lse,
+    ce_bwd_dispatch<bf16_t, 1>((const bf16_t*)Wo, H, V, (const bf16_t*)Ho, ldho, M, (const bf16_t*)HoT, ldhot, Bo, labels, lse,
                                rowscale, H, 1, dWo, dBo, st);
   else
-    ce_bwd_dispatch<float, 1>((const float*)Wo, V, (const float*)Ho, M, (const float*)HoT, ldhot, Bo, labels, lse,
+    ce_bwd_dispatch<float, 1>((const float*)Wo, H, V, (const float*)Ho, ldho, M, (const float*)HoT, ldhot, Bo, labels, lse,
                               rowscale, H, 1, dWo, dBo, st);
 }
 
@@ -393,7 +393,7 @@ void launch_ce_bwd_slab(int prec, const void* Ho, int ldho, const void* HoT, int
     launch_gemm_nt(prec, dzT, CE_SLAB_ROWS, (const char*)HoT + (size_t)m0 * esz, ldhot, V, H, Mc, dWo, nullptr, H, nullptr,
                    s > 0, st);
     // dB_o parts: column sums of the slab
-    launch_colsum(prec, dz, Mc, V, colscratch, dbo_parts + (size_t)s * V, st);
+    launch_colsum(prec, dz, V, Mc, V, colscratch, dbo_parts + (size_t)s * V, st);
   }
   launch_sum_parts(dbo_parts, nslab, (size_t)V, dBo, st);
 }

@@ -35,10 +35,10 @@ void launch_ce_reduce(const float* pmax, const float* psum, const float* zy, con
 //   dWo [V,H] fp32, dBo [V] fp32 written in full.
 // WoT [H, V] and HoT [H, M] are the transposed operand copies.
 int ce_bwd_nsplit(int M, int V);
-void launch_ce_bwd_dh(int prec, const void* Ho, const void* Wo, const void* WoT, const float* Bo,
+void launch_ce_bwd_dh(int prec, const void* Ho, int ldho, const void* Wo, const void* WoT, const float* Bo,
                       const int32_t* labels, const float* lse, const float* rowscale,
                       int M, int V, int H, int nsplit, float* dHo_part, hipStream_t st);
-void launch_ce_bwd_dw(int prec, const void* Ho, const void* HoT, int ldhot, const void* Wo, const float* Bo,
+void launch_ce_bwd_dw(int prec, const void* Ho, int ldho, const void* HoT, int ldhot, const void* Wo, const float* Bo,
                       const int32_t* labels, const float* lse, const float* rowscale,
                       int M, int V, int H, float* dWo, float* dBo, hipStream_t st);
 
@@ -70,7 +70,7 @@ struct LstmFwdDir {
   const float* bias;                    // [4Hh], used when gx is null
   const float* cprev;                   // [Bp, Hh]
   const float* mask;                    // [Bp] 1 = valid step
-  void* hnext; float* cnext;            // [Bp, Hh]
+  void* hnext; int ldhn; float* cnext;  // next state (T*, row pitch ldhn); cell state [Bp, Hh]
   float* gsave;                         // [Bp, 4Hh] gate activations kept for the backward pass
   void* ycat; int ldy;                  // optional second copy of h (T*, row pitch ldy), or null
   float* part;                          // [8][Bp][4Hh] scratch planes, used when the k range is split
@@ -102,7 +102,7 @@ struct LstmBwdPoint {
   const float* gsave;                  // [Bp,4Hh]
   const float* cprev; const float* cnext;  // [Bp,Hh]
   const float* mask;                   // [Bp]
-  void* dg;                            // T* [Bp,4Hh]
+  void* dg; int lddg;                  // T* [Bp,4Hh], row pitch lddg
 };
 void launch_lstm_bwd_point(int prec, const LstmBwdPoint& p, int Bp, int Hh, hipStream_t st);
 // out[Bp, cols] = base (or 0) + planes columns col0 + [0, cols)
@@ -110,21 +110,23 @@ void launch_planes_add(float* out, const float* base, const Planes& p, int col0,
 
 // Attention forward for one decoder step (Eq. 3-5 with the key hoist K_i = W_a^T H_s^i):
 // s_i = K_i . H_t, softmax over i < src_len[b], C_s = sum a_i H_s^i.  dots [Bp,S] is scratch.
-void launch_att_fwd(int prec, const void* Kmat, const void* Hs, const void* Ht, const int32_t* src_len,
-                    int S, int Bp, int H, float* dots, float* a /*[Bp,S]*/, void* Cs /*T* [Bp,H]*/, hipStream_t st);
+// ldk / lds / ldt / ldcs: row pitches (elements) of Kmat, Hs, Ht and Cs.
+void launch_att_fwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds, const void* Ht, int ldt,
+                    const int32_t* src_len, int S, int Bp, int H, float* dots, float* a /*[Bp,S]*/,
+                    void* Cs /*T* [Bp,ldcs]*/, int ldcs, hipStream_t st);
 // Attention backward for one step.  dCst: planes [.., Bp, 2H] fp32 from the step GEMM dpre W_c:
 // columns [0,H) = dC_s, [H,2H) = the part of dH_t that came through the concatenation.
 // da_i = dC_s . H_s^i, ds = a (da - sum a da), dHt = dCst[:, H:] + sum ds_i K_i;
 // dCs_sum [Bp,H] receives the summed dC_s (kept for the deferred gradients).
-void launch_att_bwd(int prec, const void* Kmat, const void* Hs, const Planes& dCst, float* dCs_sum, const float* a,
+void launch_att_bwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds, const Planes& dCst, float* dCs_sum, const float* a,
                     const int32_t* src_len, int S, int Bp, int H, float* dots, float* ds /*[Bp,S]*/,
                     float* dHt /*[Bp,H]*/, hipStream_t st);
 // After the decoder loop: dHs_ctx[i,b,:] = sum_j a[j,b,i] dCs[j,b,:], dK[i,b,:] = sum_j ds[j,b,i] Ht[j,b,:].
 void launch_att_deferred(int prec, const float* a, const float* ds, const float* dCs, int lddc, const void* Ht, int ldht,
                          int S, int T, int Bp, int H, float* dHs, void* dK, hipStream_t st);
 // dpre = (dHo_ce + feed) * (1 - Ho^2) -> T*
-void launch_tanh_bwd(int prec, const float* dHo_ce, const Planes& feed, const void* Ho, void* dpre, int Bp, int H,
-                     hipStream_t st);
+void launch_tanh_bwd(int prec, const float* dHo_ce, const Planes& feed, const void* Ho, int ldho, void* dpre, int ldp,
+                     int Bp, int H, hipStream_t st);
 
 // ---- misc.hip ----------------------------------------------------------------------------------
 // Embedding gather + masks + input validation (flags |= 1 bad id, |= 2 bad length).
@@ -145,7 +147,7 @@ void launch_copy2d_T(int prec, const void* src, int lds, void* dst, int ldd, int
 void launch_add_f32(float* dst, const float* src, size_t n, hipStream_t st);          // dst += src
 void launch_sum_parts(const float* parts, int nparts, size_t n, float* out, hipStream_t st);
 // db[n] = sum_m dG[m, n] over M rows of a T matrix [M, N].
-void launch_colsum(int prec, const void* dG, int M, int N, float* scratch /*[16*N]*/, float* db, hipStream_t st);
+void launch_colsum(int prec, const void* dG, int ld, int M, int N, float* scratch /*[16*N]*/, float* db, hipStream_t st);
 void launch_sgd(float* p, const float* g, size_t n, float lr, hipStream_t st);
 void launch_init_uniform(float* p, size_t n, uint64_t seed, float scale, hipStream_t st);
 

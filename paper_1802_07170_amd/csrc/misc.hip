@@ -187,22 +187,22 @@ void launch_sum_parts(const float* parts, int nparts, size_t n, float* out, hipS
 // column sums of a T matrix [M, N]: 64 columns x 4 row groups per block, 16 row splits over grid.y
 constexpr int COLSUM_SPLITS = 16;
 template <typename T>
-__global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ G, int M, int N, float* __restrict__ parts) {
+__global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ G, int ld, int M, int N, float* __restrict__ parts) {
   __shared__ float red[4][64];
   const int c = blockIdx.x * 64 + (threadIdx.x & 63), rg = threadIdx.x >> 6;
   const int rows_per = (M + COLSUM_SPLITS - 1) / COLSUM_SPLITS;
   const int r0 = blockIdx.y * rows_per, r1 = min(M, r0 + rows_per);
   float a = 0.f;
   if (c < N)
-    for (int r = r0 + rg; r < r1; r += 4) a += to_f<T>(G[(size_t)r * N + c]);
+    for (int r = r0 + rg; r < r1; r += 4) a += to_f<T>(G[(size_t)r * ld + c]);
   red[rg][threadIdx.x & 63] = a;
   __syncthreads();
   if (rg == 0 && c < N) parts[(size_t)blockIdx.y * N + c] = red[0][threadIdx.x] + red[1][threadIdx.x] + red[2][threadIdx.x] + red[3][threadIdx.x];
 }
-void launch_colsum(int prec, const void* dG, int M, int N, float* scratch, float* db, hipStream_t st) {
+void launch_colsum(int prec, const void* dG, int ld, int M, int N, float* scratch, float* db, hipStream_t st) {
   dim3 grid((N + 63) / 64, COLSUM_SPLITS);
-  if (prec) hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)dG, M, N, scratch);
-  else hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, st, (const float*)dG, M, N, scratch);
+  if (prec) hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)dG, ld, M, N, scratch);
+  else hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, st, (const float*)dG, ld, M, N, scratch);
   launch_sum_parts(scratch, COLSUM_SPLITS, (size_t)N, db, st);
 }
 

@@ -122,12 +122,12 @@ __device__ __forceinline__ void lstm_cell_store(const LstmFwdDir& d, int b, int 
   if (is_bf16) {
     const bf16_t hp = ((const bf16_t*)d.hprev)[(size_t)b * d.ldh + u];
     const bf16_t ho = valid ? f2bf(hn) : hp;
-    ((bf16_t*)d.hnext)[(size_t)b * Hh + u] = ho;
+    ((bf16_t*)d.hnext)[(size_t)b * d.ldhn + u] = ho;
     if (d.ycat) ((bf16_t*)d.ycat)[(size_t)b * d.ldy + u] = ho;
   } else {
     const float hp = ((const float*)d.hprev)[(size_t)b * d.ldh + u];
     const float ho = valid ? hn : hp;
-    ((float*)d.hnext)[(size_t)b * Hh + u] = ho;
+    ((float*)d.hnext)[(size_t)b * d.ldhn + u] = ho;
     if (d.ycat) ((float*)d.ycat)[(size_t)b * d.ldy + u] = ho;
   }
 }
@@ -418,7 +418,7 @@ __global__ __launch_bounds__(256) void lstm_bwd_point_kernel(LstmBwdPoint p, int
   const float4 rec = planes_get4(p.dhrec, b, p.dhrec_col + u);
   const float4 dhp = *reinterpret_cast<const float4*>(p.dh + idx);
   const float dh_state[4] = {dhp.x + rec.x, dhp.y + rec.y, dhp.z + rec.z, dhp.w + rec.w};
-  T* dg = (T*)p.dg + (size_t)b * 4 * Hh + u;
+  T* dg = (T*)p.dg + (size_t)b * p.lddg + u;
   const float zero[4] = {0.f, 0.f, 0.f, 0.f};
   if (!(p.mask[b] > 0.f)) {                       // masked step: state passes through, no gate gradient
 #pragma unroll
@@ -478,7 +478,7 @@ void launch_planes_add(float* out, const float* base, const Planes& p, int col0,
 // or the sum of fp32 planes (backward: dC_s from the step GEMM); in the latter case the wavefront of
 // position 0 also stores the summed vector to vsum[b, :] for the deferred attention gradients.
 template <typename T, bool PLANES>
-__global__ __launch_bounds__(256) void att_dots_kernel(const T* __restrict__ Mat, const T* __restrict__ vec, int ldv, Planes vp,
+__global__ __launch_bounds__(256) void att_dots_kernel(const T* __restrict__ Mat, int ldm, const T* __restrict__ vec, int ldv, Planes vp,
                                                        float* __restrict__ vsum, const int32_t* __restrict__ len, int S,
                                                        int Bp, int H, float* __restrict__ dots) {
   const int lane = threadIdx.x & 63;
@@ -486,7 +486,7 @@ __global__ __launch_bounds__(256) void att_dots_kernel(const T* __restrict__ Mat
   if (i >= S) return;
   const bool active = i < len[b];
   if (!active && !(PLANES && i == 0)) return;
-  const T* row = Mat + ((size_t)i * Bp + b) * H;
+  const T* row = Mat + ((size_t)i * Bp + b) * ldm;
   float a = 0.f;
   for (int c = lane; c < (H >> 3); c += 64) {
     float v[8];
@@ -528,7 +528,7 @@ constexpr int ATT_MAXS = 512;
 //                    out = add[b,:] + sum_i ds_i Mat[i,b,:]  -> fp32
 // grid (H / 64 column chunks, Bp); 256 threads = 8 column-octets x 32 position groups
 template <typename T, int MODE>
-__global__ __launch_bounds__(256) void att_mix_kernel(const T* __restrict__ Mat, const float* __restrict__ dots,
+__global__ __launch_bounds__(256) void att_mix_kernel(const T* __restrict__ Mat, int ldm, int ldo, const float* __restrict__ dots,
                                                       const float* __restrict__ a_in, const int32_t* __restrict__ len,
                                                       int S, int Bp, int H, float* __restrict__ coef_out,
                                                       void* __restrict__ out, Planes add, int add_col) {
@@ -570,7 +570,7 @@ __global__ __launch_bounds__(256) void att_mix_kernel(const T* __restrict__ Mat,
   if (h0 < H) {
     for (int i = grp; i < n; i += 32) {
       Frag<T> f;
-      f.load(Mat + ((size_t)i * Bp + b) * H + h0);
+      f.load(Mat + ((size_t)i * Bp + b) * ldm + h0);
       const float w = sc[i];
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[e] += w * f.get(e);
@@ -585,35 +585,35 @@ __global__ __launch_bounds__(256) void att_mix_kernel(const T* __restrict__ Mat,
       float s = 0.f;
 #pragma unroll
       for (int g = 0; g < 32; ++g) s += part[g][t];
-      if (MODE == 0) ((T*)out)[(size_t)b * H + h] = from_f<T>(s);
+      if (MODE == 0) ((T*)out)[(size_t)b * ldo + h] = from_f<T>(s);
       else ((float*)out)[(size_t)b * H + h] = s + planes_get(add, b, add_col + h);
     }
   }
 }
 
-void launch_att_fwd(int prec, const void* Kmat, const void* Hs, const void* Ht, const int32_t* src_len,
-                    int S, int Bp, int H, float* dots, float* a, void* Cs, hipStream_t st) {
+void launch_att_fwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds, const void* Ht, int ldt,
+                    const int32_t* src_len, int S, int Bp, int H, float* dots, float* a, void* Cs, int ldcs, hipStream_t st) {
   dim3 gd((S + 3) / 4, Bp), gm((H + 63) / 64, Bp);
   const Planes none{nullptr, 0, 0, 0};
   if (prec) {
-    hipLaunchKernelGGL((att_dots_kernel<bf16_t, false>), gd, dim3(256), 0, st, (const bf16_t*)Kmat, (const bf16_t*)Ht, H, none, nullptr, src_len, S, Bp, H, dots);
-    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 0>), gm, dim3(256), 0, st, (const bf16_t*)Hs, dots, nullptr, src_len, S, Bp, H, a, Cs, none, 0);
+    hipLaunchKernelGGL((att_dots_kernel<bf16_t, false>), gd, dim3(256), 0, st, (const bf16_t*)Kmat, ldk, (const bf16_t*)Ht, ldt, none, nullptr, src_len, S, Bp, H, dots);
+    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 0>), gm, dim3(256), 0, st, (const bf16_t*)Hs, lds, ldcs, dots, nullptr, src_len, S, Bp, H, a, Cs, none, 0);
   } else {
-    hipLaunchKernelGGL((att_dots_kernel<float, false>), gd, dim3(256), 0, st, (const float*)Kmat, (const float*)Ht, H, none, nullptr, src_len, S, Bp, H, dots);
-    hipLaunchKernelGGL((att_mix_kernel<float, 0>), gm, dim3(256), 0, st, (const float*)Hs, dots, nullptr, src_len, S, Bp, H, a, Cs, none, 0);
+    hipLaunchKernelGGL((att_dots_kernel<float, false>), gd, dim3(256), 0, st, (const float*)Kmat, ldk, (const float*)Ht, ldt, none, nullptr, src_len, S, Bp, H, dots);
+    hipLaunchKernelGGL((att_mix_kernel<float, 0>), gm, dim3(256), 0, st, (const float*)Hs, lds, ldcs, dots, nullptr, src_len, S, Bp, H, a, Cs, none, 0);
   }
 }
 
-void launch_att_bwd(int prec, const void* Kmat, const void* Hs, const Planes& dCst, float* dCs_sum, const float* a,
+void launch_att_bwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds, const Planes& dCst, float* dCs_sum, const float* a,
                     const int32_t* src_len, int S, int Bp, int H, float* dots, float* ds, float* dHt, hipStream_t st) {
   // dCst planes [.., Bp, 2H]: columns [0,H) = dC_s, columns [H,2H) = the direct part of dH_t
   dim3 gd((S + 3) / 4, Bp), gm((H + 63) / 64, Bp);
   if (prec) {
-    hipLaunchKernelGGL((att_dots_kernel<bf16_t, true>), gd, dim3(256), 0, st, (const bf16_t*)Hs, nullptr, 0, dCst, dCs_sum, src_len, S, Bp, H, dots);
-    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 1>), gm, dim3(256), 0, st, (const bf16_t*)Kmat, dots, a, src_len, S, Bp, H, ds, dHt, dCst, H);
+    hipLaunchKernelGGL((att_dots_kernel<bf16_t, true>), gd, dim3(256), 0, st, (const bf16_t*)Hs, lds, nullptr, 0, dCst, dCs_sum, src_len, S, Bp, H, dots);
+    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 1>), gm, dim3(256), 0, st, (const bf16_t*)Kmat, ldk, 0, dots, a, src_len, S, Bp, H, ds, dHt, dCst, H);
   } else {
-    hipLaunchKernelGGL((att_dots_kernel<float, true>), gd, dim3(256), 0, st, (const float*)Hs, nullptr, 0, dCst, dCs_sum, src_len, S, Bp, H, dots);
-    hipLaunchKernelGGL((att_mix_kernel<float, 1>), gm, dim3(256), 0, st, (const float*)Kmat, dots, a, src_len, S, Bp, H, ds, dHt, dCst, H);
+    hipLaunchKernelGGL((att_dots_kernel<float, true>), gd, dim3(256), 0, st, (const float*)Hs, lds, nullptr, 0, dCst, dCs_sum, src_len, S, Bp, H, dots);
+    hipLaunchKernelGGL((att_mix_kernel<float, 1>), gm, dim3(256), 0, st, (const float*)Kmat, ldk, 0, dots, a, src_len, S, Bp, H, ds, dHt, dCst, H);
   }
 }
 
@@ -639,7 +639,7 @@ __global__ __launch_bounds__(256) void att_deferred_kernel(const float* __restri
     __syncthreads();
     if (h < H) {
       const float dc = dCs[((size_t)j * Bp + b) * lddc + h];
-      const float ht = to_f<T>(Ht[(size_t)j * ldht + (size_t)b * H + h]);
+      const float ht = to_f<T>(Ht[((size_t)j * Bp + b) * ldht + h]);
 #pragma unroll
       for (int i = 0; i < 32; ++i) { accC[i] += sa[i] * dc; accK[i] += sd[i] * ht; }
     }
@@ -680,7 +680,7 @@ template __global__ void tanh_planes_kernel<float>(Planes, float*, int, int, int
 // dpre = (dHo_ce + feed) * (1 - Ho^2) -> T; feed arrives as planes (np = 0: none); 4 columns per thread
 template <typename T>
 __global__ __launch_bounds__(256) void tanh_bwd_kernel(const float* __restrict__ dce, Planes feed, const T* __restrict__ Ho,
-                                                       T* __restrict__ dpre, int Bp, int H) {
+                                                       int ldho, T* __restrict__ dpre, int ldp, int Bp, int H) {
   const int i4 = blockIdx.x * 256 + threadIdx.x;
   const int hq = H >> 2;
   if (i4 >= Bp * hq) return;
@@ -691,18 +691,19 @@ __global__ __launch_bounds__(256) void tanh_bwd_kernel(const float* __restrict__
   float o[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    const float ho = to_f<T>(Ho[i + e]);
+    const float ho = to_f<T>(Ho[(size_t)b * ldho + h + e]);
     o[e] = ((&d.x)[e] + (&f.x)[e]) * (1.f - ho * ho);
   }
-  store4<T>(dpre + i, o);
+  store4<T>(dpre + (size_t)b * ldp + h, o);
 }
 
-void launch_tanh_bwd(int prec, const float* dHo_ce, const Planes& feed, const void* Ho, void* dpre, int Bp, int H, hipStream_t st) {
+void launch_tanh_bwd(int prec, const float* dHo_ce, const Planes& feed, const void* Ho, int ldho, void* dpre, int ldp, int Bp, int H,
+                     hipStream_t st) {
   const int n = Bp * (H >> 2);
   if (prec) hipLaunchKernelGGL(tanh_bwd_kernel<bf16_t>, dim3((n + 255) / 256), dim3(256), 0, st, dHo_ce, feed,
-                               (const bf16_t*)Ho, (bf16_t*)dpre, Bp, H);
+                               (const bf16_t*)Ho, ldho, (bf16_t*)dpre, ldp, Bp, H);
   else hipLaunchKernelGGL(tanh_bwd_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, st, dHo_ce, feed,
-                          (const float*)Ho, (float*)dpre, Bp, H);
+                          (const float*)Ho, ldho, (float*)dpre, ldp, Bp, H);
 }
 
 }  // namespace cmt
