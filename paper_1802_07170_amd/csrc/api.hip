@@ -103,6 +103,11 @@ struct cmt_handle {
   float* loss = nullptr; int* flags = nullptr; float* colscr = nullptr;
   char* dzs = nullptr; char* dzTs = nullptr; float* ce_colscr = nullptr; float* dbo_parts = nullptr;
   float* gsplit = nullptr; size_t gsplit_floats = 0;
+  hipStream_t side = nullptr;           // library-owned second stream for work off the recurrences' critical path
+  std::vector<hipEvent_t> ev; size_t ev_next = 0;
+  int use_side = 1;
+  char* dzs2 = nullptr; char* dzTs2 = nullptr; float* gsplit2 = nullptr;
+  int kb_bwd = 0, kb_wc = 0;            // caps on the k blocks of the backward step GEMMs (0 = default)
   int ce_bwd_fused = 0;                 // 1: rebuild dz in LDS inside the product kernels; 0: slab staging
   size_t ws_bytes = 0;
 
@@ -222,6 +227,8 @@ size_t layout(cmt_handle* h, char* base) {
   h->dbo_parts = (float*)a.take((Mt / CE_SLAB_ROWS + 1) * c.tgt_vocab * 4);
   h->gsplit_floats = (size_t)8 * CE_SLAB_ROWS * 1024;
   h->gsplit = (float*)a.take(h->gsplit_floats * 4);
+  h->gsplit2 = (float*)a.take(h->gsplit_floats * 4);
+  h->dzs2 = a.take(ce_slab_elems(c.tgt_vocab) * esz); h->dzTs2 = a.take(ce_slab_elems(c.tgt_vocab) * esz);
   return (a.off + 255) & ~(size_t)255;
 }
 
@@ -272,7 +279,7 @@ void run_lstm_layer_bwd(cmt_handle* h, LD& d, int Lsteps, const float* mask, con
   const int p = h->prec, Bp = h->Bp, Hh = d.Hh;
   const size_t esz = h->esz;
   hipStream_t st = h->st;
-  const int kb = step_kblocks(p, Hh, 4 * Hh, Bp);
+  const int kb = step_kblocks(p, Hh, 4 * Hh, Bp, h->kb_bwd);
   const size_t pstride = (size_t)Bp * Hh;
   for (int k = 0; k < Lsteps; ++k) {
     const int t = reverse_dir ? k : Lsteps - 1 - k;
@@ -291,18 +298,25 @@ void run_lstm_layer_bwd(cmt_handle* h, LD& d, int Lsteps, const float* mask, con
     g.a0 = q.dg; g.lda0 = d.pg; g.K0 = 4 * Hh; g.w0_off = 0;
     g.a1 = nullptr; g.lda1 = 0; g.K1 = 0; g.w1_off = 0;
     g.W = d.Wt + (size_t)d.Kin * 4 * Hh * esz; g.ldw = 4 * Hh;
-    g.N = Hh; g.mode = 1;
+    g.N = Hh; g.mode = 1; g.max_kb = h->kb_bwd;
     g.out = d.bwdp; g.ldout = Hh; g.plane_stride = pstride;
     launch_step_gemm(p, g, Bp, st);
   }
 }
 
+// make stream `to` wait for everything enqueued so far on stream `from`
+void stream_after(cmt_handle* h, hipStream_t to, hipStream_t from) {
+  if (to == from) return;
+  hipEvent_t e = h->ev[h->ev_next++ % h->ev.size()];
+  (void)hipEventRecord(e, from);
+  (void)hipStreamWaitEvent(to, e, 0);
+}
+
 void weight_grads(cmt_handle* h, LD& d, int Lsteps, const std::vector<std::pair<const char*, int>>& segs /* (XT ptr, ld) */,
-                  const std::vector<int>& seg_k) {
+                  const std::vector<int>& seg_k, hipStream_t st) {
   // dW[:, segment] = dG^T * X_segment as one GEMM with k = Lsteps * Bp; db = column sums of dG
   const int p = h->prec, Bp = h->Bp, Hh = d.Hh;
   const int M = Lsteps * Bp;
-  hipStream_t st = h->st;
   launch_transpose(p, d.dG, d.pg, d.dGT, M, M, 4 * Hh, st);
   float* dW = h->grads + d.w_off;
   int col = 0;
@@ -448,25 +462,61 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   launch_ce_reduce(h->pmax, h->psum, h->zy, h->mask_t, Mt, np, h->lse, h->nll, h->rowscale, h->loss, h->flags, st);
 
   // =================================== backward ======================================================
+  // The recurrences' backward loops are chains of short dependent kernels that leave most of the
+  // chip idle; everything that does not feed them (transposes, weight gradients, dW_o, embedding
+  // scatters) runs on the library's second stream and joins at the end of the step.
+  hipStream_t sd = h->use_side ? h->side : st;
   const int ldHoT = Mt + Bp;
-  launch_transpose(p, h->HoBuf, PH, h->HoBufT, ldHoT, Mt + Bp, H, st);
   const char* HoT = h->HoBufT + (size_t)Bp * esz;  // columns of H_o^{<0..T-1>}
+  auto transpose_states = [&](LD& d, int Lsteps) {
+    launch_transpose(p, d.Hst, d.ph, d.HstT, (Lsteps + 1) * Bp, (Lsteps + 1) * Bp, d.Hh, sd);
+  };
+  stream_after(h, sd, st);
+  launch_transpose(p, h->HoBuf, PH, h->HoBufT, ldHoT, Mt + Bp, H, sd);
+  for (auto& d : h->enc) transpose_states(d, S);
+  for (auto& d : h->dec) transpose_states(d, T);
+  launch_transpose(p, h->Y0, H, h->Y0T, Ms, Ms, H, sd);
+  launch_transpose(p, h->Xs, E, h->XsT, Ms, Ms, E, sd);
+  launch_transpose(p, h->Xt, E, h->XtT, Mt, Mt, E, sd);
+  launch_transpose(p, h->Cs, PH, h->CsT, Mt, Mt, H, sd);
+
   if (h->ce_bwd_fused) {
     const int nsplit = ce_bwd_nsplit(Mt, V);
     launch_ce_bwd_dh(p, Ho, PH, h->Pw(h->off_Wo), h->WoT, P + h->off_Bo, h->labels, h->lse, h->rowscale, Mt, V, H, nsplit,
                      h->dHoPart, st);
     launch_sum_parts(h->dHoPart, nsplit, (size_t)Mt * H, h->dHoCE, st);
     launch_ce_bwd_dw(p, Ho, PH, HoT, ldHoT, h->Pw(h->off_Wo), P + h->off_Bo, h->labels, h->lse, h->rowscale, Mt, V, H,
-                     G + h->off_Wo, G + h->off_Bo, st);
+                     G + h->off_Wo, G + h->off_Bo, sd);
   } else {
-    launch_ce_bwd_slab(p, Ho, PH, HoT, ldHoT, h->Pw(h->off_Wo), h->WoT, P + h->off_Bo, h->labels, h->lse, h->rowscale, Mt, V,
-                       H, h->dzs, h->dzTs, h->dHoCE, G + h->off_Wo, G + h->off_Bo, h->ce_colscr, h->dbo_parts, h->gsplit,
-                       h->gsplit_floats, st);
+    // slabs of <= CE_SLAB_ROWS rows, two slab buffers: the main stream rebuilds dz and takes dH_o (the
+    // decoder needs it), the second stream takes dW_o and dB_o
+    const int nslab = (Mt + CE_SLAB_ROWS - 1) / CE_SLAB_ROWS;
+    std::vector<hipEvent_t> done(nslab, nullptr);
+    for (int sl = 0; sl < nslab; ++sl) {
+      const int m0 = sl * CE_SLAB_ROWS;
+      const int Mc = Mt - m0 < CE_SLAB_ROWS ? Mt - m0 : CE_SLAB_ROWS;
+      char* dz = (sl & 1) ? h->dzs2 : h->dzs;
+      char* dzT = (sl & 1) ? h->dzTs2 : h->dzTs;
+      if (sl >= 2 && sd != st) (void)hipStreamWaitEvent(st, done[sl - 2], 0);
+      launch_ce_dz(p, Ho + (size_t)m0 * PH * esz, PH, h->Pw(h->off_Wo), P + h->off_Bo, h->labels + m0, h->lse + m0,
+                   h->rowscale + m0, Mc, V, H, dz, dzT, st);
+      stream_after(h, sd, st);
+      launch_gemm_nt(p, dz, V, h->WoT, V, Mc, H, V, h->dHoCE + (size_t)m0 * H, nullptr, H, nullptr, 0, st, h->gsplit,
+                     h->gsplit_floats);                                   // dH_o[slab] = dz W_o
+      launch_gemm_nt(p, dzT, CE_SLAB_ROWS, HoT + (size_t)m0 * esz, ldHoT, V, H, Mc, G + h->off_Wo, nullptr, H, nullptr, sl > 0,
+                     sd);                                                 // dW_o (+)= dz^T H_o[slab]
+      launch_colsum(p, dz, V, Mc, V, h->ce_colscr, h->dbo_parts + (size_t)sl * V, sd);
+      if (sd != st) {
+        done[sl] = h->ev[h->ev_next++ % h->ev.size()];
+        (void)hipEventRecord(done[sl], sd);
+      }
+    }
+    launch_sum_parts(h->dbo_parts, nslab, (size_t)V, G + h->off_Bo, sd);
   }
 
   // ---- decoder loop backwards -----------------------------------------------------------------------
   for (int l = 0; l < L; ++l) { launch_fill_f32(h->dec[l].dh, BH, 0.f, st); launch_fill_f32(h->dec[l].dc, BH, 0.f, st); }
-  const int kbd = step_kblocks(p, 2 * H, 4 * H, Bp);                  // planes written by a decoder layer's backward GEMM
+  const int kbd = step_kblocks(p, 2 * H, 4 * H, Bp, h->kb_bwd);       // planes written by a decoder layer's backward GEMM
   const size_t pstr = (size_t)Bp * 2 * H;
   for (int j = T - 1; j >= 0; --j) {
     char* dpre = h->dPre + j * BP * esz;
@@ -474,11 +524,11 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     // dH_o = cross-entropy part + what step j+1's bottom layer sent back through the input feed
     launch_tanh_bwd(p, h->dHoCE + j * BH, Planes{h->dec[0].bwdp, 2 * H, last ? 0 : kbd, pstr}, h->HoBuf + (j + 1) * BP * esz,
                     PH, dpre, PH, Bp, H, st);
-    const int kbw = step_kblocks(p, 2 * H, H, Bp);
+    const int kbw = step_kblocks(p, 2 * H, H, Bp, h->kb_wc);
     {   // [dC_s ; dH_t] = dpre W_c, as planes
       StepGemm g{};
       g.a0 = dpre; g.lda0 = PH; g.K0 = H; g.w0_off = 0; g.K1 = 0;
-      g.W = h->WcT; g.ldw = H; g.N = 2 * H; g.mode = 1;
+      g.W = h->WcT; g.ldw = H; g.N = 2 * H; g.mode = 1; g.max_kb = h->kb_wc;
       g.out = h->wcp; g.ldout = 2 * H; g.plane_stride = pstr;
       launch_step_gemm(p, g, Bp, st);
     }
@@ -500,7 +550,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       StepGemm g{};                                  // [dx ; dh_prev] = dgates [W_x ; W_h] (bottom layer: [feed ; h])
       g.a0 = q.dg; g.lda0 = e.pg; g.K0 = 4 * H; g.w0_off = 0; g.K1 = 0;
       g.W = e.Wt + (size_t)(l == 0 ? E : 0) * 4 * H * esz; g.ldw = 4 * H;
-      g.N = 2 * H; g.mode = 1;
+      g.N = 2 * H; g.mode = 1; g.max_kb = h->kb_bwd;
       g.out = e.bwdp; g.ldout = 2 * H; g.plane_stride = pstr;
       launch_step_gemm(p, g, Bp, st);
     }
@@ -508,46 +558,39 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   // gradient of the decoder's initial state: pass-through part + the last GEMM's recurrent part
   for (int l = 0; l < L; ++l)
     launch_planes_add(h->dec[l].dh, h->dec[l].dh, Planes{h->dec[l].bwdp, 2 * H, kbd, pstr}, H, Bp, H, st);
-  // ---- attention gradients that do not feed the decoder recurrence, batched over all steps ---------
-  const char* HtAll = h->dec[L - 1].Hst + BP * esz;      // H_t^{<0..T-1>}
-  launch_att_deferred(p, h->att_a, h->att_ds, h->dCs, H, HtAll, PH, S, T, Bp, H, h->dHs, h->dK, st);
-  launch_gemm_nt(p, h->dK, H, h->Pw(h->off_Wa), H, Ms, H, H, h->dHs, nullptr, H, nullptr, 1, st);   // dHs += dK W_a^T
 
-  // transposed activations for the weight-gradient GEMMs
-  auto transpose_states = [&](LD& d, int Lsteps) {
-    launch_transpose(p, d.Hst, d.ph, d.HstT, (Lsteps + 1) * Bp, (Lsteps + 1) * Bp, d.Hh, st);
-  };
-  for (auto& d : h->enc) transpose_states(d, S);
-  for (auto& d : h->dec) transpose_states(d, T);
-  launch_transpose(p, h->Y0, H, h->Y0T, Ms, Ms, H, st);
-  launch_transpose(p, h->Xs, E, h->XsT, Ms, Ms, E, st);
-  launch_transpose(p, h->Xt, E, h->XtT, Mt, Mt, E, st);
-  launch_transpose(p, h->Cs, PH, h->CsT, Mt, Mt, H, st);
-  launch_transpose(p, h->dPre, PH, h->dPreT, Mt, Mt, H, st);
-  launch_transpose(p, h->dK, H, h->dKT, Ms, Ms, H, st);
+  // ---- second stream: everything that only needed the decoder's dgates and dpre -----------------------
+  stream_after(h, sd, st);
+  launch_transpose(p, h->dPre, PH, h->dPreT, Mt, Mt, H, sd);
   // encoder layer outputs, transposed: layer 0 -> Y0T (ld Ms); layer l >= 1 -> HstT + Bp (ld (S+1)Bp)
   auto encYT = [&](int l, int* ld) -> const char* {
     if (l == 0) { *ld = Ms; return h->Y0T; }
     *ld = (S + 1) * Bp; return h->enc[l + 1].HstT + (size_t)Bp * esz;
   };
-  {   // dW_a[r,c] = sum_i H_s[i,r] dK[i,c];  dW_c = dpre^T [C_s ; H_t]
-    int ld; const char* HsT = encYT(L - 1, &ld);
-    launch_gemm_nt(p, HsT, ld, h->dKT, Ms, H, H, Ms, G + h->off_Wa, nullptr, H, nullptr, 0, st);
-    launch_gemm_nt(p, h->dPreT, Mt, h->CsT, Mt, H, H, Mt, G + h->off_Wc, nullptr, 2 * H, nullptr, 0, st);
-    launch_gemm_nt(p, h->dPreT, Mt, h->dec[L - 1].HstT + (size_t)Bp * esz, (T + 1) * Bp, H, H, Mt, G + h->off_Wc + H, nullptr,
-                   2 * H, nullptr, 0, st);
-  }
-  // decoder weight gradients
+  // dW_c = dpre^T [C_s ; H_t]
+  launch_gemm_nt(p, h->dPreT, Mt, h->CsT, Mt, H, H, Mt, G + h->off_Wc, nullptr, 2 * H, nullptr, 0, sd, h->gsplit2, h->gsplit_floats);
+  launch_gemm_nt(p, h->dPreT, Mt, h->dec[L - 1].HstT + (size_t)Bp * esz, (T + 1) * Bp, H, H, Mt, G + h->off_Wc + H, nullptr,
+                 2 * H, nullptr, 0, sd, h->gsplit2, h->gsplit_floats);
   for (int l = 0; l < L; ++l) {
     LD& e = h->dec[l];
     if (l == 0)
-      weight_grads(h, e, T, {{h->XtT, Mt}, {h->HoBufT, ldHoT}, {e.HstT, (T + 1) * Bp}}, {E, H, H});
+      weight_grads(h, e, T, {{h->XtT, Mt}, {h->HoBufT, ldHoT}, {e.HstT, (T + 1) * Bp}}, {E, H, H}, sd);
     else
-      weight_grads(h, e, T, {{h->dec[l - 1].HstT + (size_t)Bp * esz, (T + 1) * Bp}, {e.HstT, (T + 1) * Bp}}, {H, H});
+      weight_grads(h, e, T, {{h->dec[l - 1].HstT + (size_t)Bp * esz, (T + 1) * Bp}, {e.HstT, (T + 1) * Bp}}, {H, H}, sd);
   }
-  // target embedding gradient
-  launch_gemm_nt(p, h->dec[0].dG, h->dec[0].pg, h->dec[0].Wt, 4 * H, Mt, E, 4 * H, h->dXt, nullptr, E, nullptr, 0, st);
-  launch_embed_scatter(h->dXt, h->tok_t, Mt, c.tgt_vocab, E, G + h->off_Etgt, st);
+  launch_gemm_nt(p, h->dec[0].dG, h->dec[0].pg, h->dec[0].Wt, 4 * H, Mt, E, 4 * H, h->dXt, nullptr, E, nullptr, 0, sd);
+  launch_embed_scatter(h->dXt, h->tok_t, Mt, c.tgt_vocab, E, G + h->off_Etgt, sd);
+
+  // ---- attention gradients that do not feed the decoder recurrence, batched over all steps ---------
+  const char* HtAll = h->dec[L - 1].Hst + BP * esz;      // H_t^{<0..T-1>}
+  launch_att_deferred(p, h->att_a, h->att_ds, h->dCs, H, HtAll, PH, S, T, Bp, H, h->dHs, h->dK, st);
+  launch_gemm_nt(p, h->dK, H, h->Pw(h->off_Wa), H, Ms, H, H, h->dHs, nullptr, H, nullptr, 1, st);   // dHs += dK W_a^T
+  stream_after(h, sd, st);
+  launch_transpose(p, h->dK, H, h->dKT, Ms, Ms, H, sd);
+  {   // dW_a[r,c] = sum_i H_s[i,r] dK[i,c]
+    int ld; const char* HsT = encYT(L - 1, &ld);
+    launch_gemm_nt(p, HsT, ld, h->dKT, Ms, H, H, Ms, G + h->off_Wa, nullptr, H, nullptr, 0, sd, h->gsplit2, h->gsplit_floats);
+  }
 
   // ---- encoder backwards ------------------------------------------------------------------------------
   const float* dY = h->dHs;
@@ -557,8 +600,9 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     // gradient of the final state = gradient of the decoder's initial state of the same depth
     run_lstm_layer_bwd(h, e, S, h->mask_s, dY, H, 0, false, h->dec[l].dh, h->dec[l].dc);
     launch_gemm_nt(p, e.dG, e.pg, e.Wt, 4 * H, Ms, H, 4 * H, dYnext, nullptr, H, nullptr, 0, st);   // dX = dG W_x
+    stream_after(h, sd, st);
     int ld; const char* XT = encYT(l - 1, &ld);
-    weight_grads(h, e, S, {{XT, ld}, {e.HstT, (S + 1) * Bp}}, {H, H});
+    weight_grads(h, e, S, {{XT, ld}, {e.HstT, (S + 1) * Bp}}, {H, H}, sd);
     dY = dYnext;
     dYnext = (dYnext == h->dYa) ? h->dYb : h->dYa;
   }
@@ -567,13 +611,16 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     launch_copy2d_f32(d0.dh, H, ef.dh, Hd, Bp, Hd, st); launch_copy2d_f32(d0.dh + Hd, H, eb.dh, Hd, Bp, Hd, st);
     launch_copy2d_f32(d0.dc, H, ef.dc, Hd, Bp, Hd, st); launch_copy2d_f32(d0.dc + Hd, H, eb.dc, Hd, Bp, Hd, st);
     run_lstm_layer_bwd(h, ef, S, h->mask_s, dY, H, 0, false, ef.dh, ef.dc);
+    stream_after(h, sd, st);
+    weight_grads(h, ef, S, {{h->XsT, Ms}, {ef.HstT, (S + 1) * Bp}}, {E, Hd}, sd);
     run_lstm_layer_bwd(h, eb, S, h->mask_s, dY, H, Hd, true, eb.dh, eb.dc);
-    launch_gemm_nt(p, ef.dG, ef.pg, ef.Wt, 4 * Hd, Ms, E, 4 * Hd, h->dXs, nullptr, E, nullptr, 0, st);
-    launch_gemm_nt(p, eb.dG, eb.pg, eb.Wt, 4 * Hd, Ms, E, 4 * Hd, h->dXs, nullptr, E, nullptr, 1, st);
-    weight_grads(h, ef, S, {{h->XsT, Ms}, {ef.HstT, (S + 1) * Bp}}, {E, Hd});
-    weight_grads(h, eb, S, {{h->XsT, Ms}, {eb.HstT + (size_t)Bp * esz, (S + 1) * Bp}}, {E, Hd});
-    launch_embed_scatter(h->dXs, h->tok_s, Ms, c.src_vocab, E, G + h->off_Esrc, st);
+    stream_after(h, sd, st);
+    weight_grads(h, eb, S, {{h->XsT, Ms}, {eb.HstT + (size_t)Bp * esz, (S + 1) * Bp}}, {E, Hd}, sd);
+    launch_gemm_nt(p, ef.dG, ef.pg, ef.Wt, 4 * Hd, Ms, E, 4 * Hd, h->dXs, nullptr, E, nullptr, 0, sd);
+    launch_gemm_nt(p, eb.dG, eb.pg, eb.Wt, 4 * Hd, Ms, E, 4 * Hd, h->dXs, nullptr, E, nullptr, 1, sd);
+    launch_embed_scatter(h->dXs, h->tok_s, Ms, c.src_vocab, E, G + h->off_Esrc, sd);
   }
+  stream_after(h, st, sd);                         // join: the step is complete on the caller's stream
   (void)hipMemcpyAsync(h->h_loss, h->loss, 2 * sizeof(float), hipMemcpyDeviceToHost, st);
   (void)hipMemcpyAsync(h->h_flags, h->flags, sizeof(int), hipMemcpyDeviceToHost, st);
   hipError_t e = hipGetLastError();
@@ -616,12 +663,20 @@ int cmt_create(const cmt_config* cfg, void* params_dev, void* grads_dev, void* w
   {
     const char* e = getenv("CMT_CE_BWD");
     h->ce_bwd_fused = (e && std::string(e) == "fused") ? 1 : 0;
+    const char* k1 = getenv("CMT_KB_BWD"); h->kb_bwd = k1 ? atoi(k1) : 0;
+    const char* k2 = getenv("CMT_KB_WC"); h->kb_wc = k2 ? atoi(k2) : 2;
+    const char* k3 = getenv("CMT_SIDE_STREAM"); h->use_side = k3 ? atoi(k3) : 1;
   }
   build_table(h->cfg, h->table, h->nparams);
   h->ws_bytes = layout(h, h->ws);
   bind_params(h);
   hipError_t e = hipHostMalloc((void**)&h->h_loss, 256, hipHostMallocDefault);
   if (e != hipSuccess) { delete h; return CMT_EHIP; }
+  // second stream at the default priority, and a pool of events for the hand-offs between the two
+  if (hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking) != hipSuccess) { (void)hipHostFree(h->h_loss); delete h; return CMT_EHIP; }
+  h->ev.resize(512);
+  for (auto& ev : h->ev)
+    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) { delete h; return CMT_EHIP; }
   h->h_flags = (int*)(h->h_loss + 8);
   h->h_loss[0] = 0.f; h->h_loss[1] = 0.f; *h->h_flags = 0;
   *out = h;
@@ -631,6 +686,8 @@ int cmt_create(const cmt_config* cfg, void* params_dev, void* grads_dev, void* w
 void cmt_destroy(cmt_handle* h) {
   if (!h) return;
   if (h->h_loss) (void)hipHostFree(h->h_loss);
+  for (auto ev : h->ev) if (ev) (void)hipEventDestroy(ev);
+  if (h->side) (void)hipStreamDestroy(h->side);
   delete h;
 }
 

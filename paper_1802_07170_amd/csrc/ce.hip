@@ -367,35 +367,17 @@ __global__ __launch_bounds__(256) void ce_dz_kernel(const T* __restrict__ Ho, in
 
 size_t ce_slab_elems(int V) { return (size_t)CE_SLAB_ROWS * V; }
 
-void launch_ce_bwd_slab(int prec, const void* Ho, int ldho, const void* HoT, int ldhot, const void* Wo, const void* WoT,
-                        const float* Bo, const int32_t* labels, const float* lse, const float* rowscale, int M, int V, int H,
-                        void* dz, void* dzT, float* dHo, float* dWo, float* dBo, float* colscratch, float* dbo_parts,
-                        float* split_scratch, size_t split_scratch_floats, hipStream_t st) {
+void launch_ce_dz(int prec, const void* Ho, int ldho, const void* Wo, const float* Bo, const int32_t* labels, const float* lse,
+                  const float* rowscale, int Mc, int V, int H, void* dz, void* dzT, hipStream_t st) {
   using G = GemmTile<2, 2, 128>;
-  const size_t esz = prec ? 2 : 4;
-  const int nslab = (M + CE_SLAB_ROWS - 1) / CE_SLAB_ROWS;
-  for (int s = 0; s < nslab; ++s) {
-    const int m0 = s * CE_SLAB_ROWS;
-    const int Mc = M - m0 < CE_SLAB_ROWS ? M - m0 : CE_SLAB_ROWS;     // multiple of 16 (rows come in padded batches)
-    const int ntm = (Mc + G::BM - 1) / G::BM, ntn = (V + G::BN - 1) / G::BN;
-    const int grid = ((ntm * ntn + 7) / 8) * 8;
-    const char* ho = (const char*)Ho + (size_t)m0 * ldho * esz;
-    if (prec)
-      hipLaunchKernelGGL(ce_dz_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, (const bf16_t*)ho, ldho, (const bf16_t*)Wo, Bo,
-                         labels + m0, lse + m0, rowscale + m0, Mc, V, H, (bf16_t*)dz, V, (bf16_t*)dzT, CE_SLAB_ROWS, ntn);
-    else
-      hipLaunchKernelGGL(ce_dz_kernel<float>, dim3(grid), dim3(256), 0, st, (const float*)ho, ldho, (const float*)Wo, Bo,
-                         labels + m0, lse + m0, rowscale + m0, Mc, V, H, (float*)dz, V, (float*)dzT, CE_SLAB_ROWS, ntn);
-    // dH_o[slab] = dz W_o            (k = V)
-    launch_gemm_nt(prec, dz, V, WoT, V, Mc, H, V, dHo + (size_t)m0 * H, nullptr, H, nullptr, 0, st, split_scratch,
-                   split_scratch_floats);
-    // dW_o (+)= dz^T H_o[slab]       (k = slab rows)
-    launch_gemm_nt(prec, dzT, CE_SLAB_ROWS, (const char*)HoT + (size_t)m0 * esz, ldhot, V, H, Mc, dWo, nullptr, H, nullptr,
-                   s > 0, st);
-    // dB_o parts: column sums of the slab
-    launch_colsum(prec, dz, V, Mc, V, colscratch, dbo_parts + (size_t)s * V, st);
-  }
-  launch_sum_parts(dbo_parts, nslab, (size_t)V, dBo, st);
+  const int ntm = (Mc + G::BM - 1) / G::BM, ntn = (V + G::BN - 1) / G::BN;
+  const int grid = ((ntm * ntn + 7) / 8) * 8;
+  if (prec)
+    hipLaunchKernelGGL(ce_dz_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, (const bf16_t*)Ho, ldho, (const bf16_t*)Wo, Bo, labels,
+                       lse, rowscale, Mc, V, H, (bf16_t*)dz, V, (bf16_t*)dzT, CE_SLAB_ROWS, ntn);
+  else
+    hipLaunchKernelGGL(ce_dz_kernel<float>, dim3(grid), dim3(256), 0, st, (const float*)Ho, ldho, (const float*)Wo, Bo, labels, lse,
+                       rowscale, Mc, V, H, (float*)dz, V, (float*)dzT, CE_SLAB_ROWS, ntn);
 }
 
 }  // namespace cmt

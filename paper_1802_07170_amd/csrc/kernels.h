@@ -42,23 +42,21 @@ void launch_ce_bwd_dw(int prec, const void* Ho, int ldho, const void* HoT, int l
                       const int32_t* labels, const float* lse, const float* rowscale,
                       int M, int V, int H, float* dWo, float* dBo, hipStream_t st);
 
-// Slab variant of the backward: dz is staged for at most CE_SLAB_ROWS rows at a time (dz [rows, V] and
-// dzT [V, CE_SLAB_ROWS], both T, ce_slab_elems(V) elements each) and consumed by two plain GEMMs.
-// dHo [M,H], dWo [V,H], dBo [V] fp32 are written in full.  colscratch: 16 * V floats; dbo_parts:
-// ceil(M / CE_SLAB_ROWS) * V floats.
+// Slab variant of the backward: for at most CE_SLAB_ROWS rows the logits are rebuilt and
+// dz = (softmax(z) - onehot) * rowscale is staged as dz [Mc, V] and dzT [V, CE_SLAB_ROWS] (both T,
+// ce_slab_elems(V) elements each); the caller then takes dH_o[rows] = dz W_o and dW_o += dz^T H_o[rows]
+// with launch_gemm_nt and dB_o with launch_colsum.  Ho, labels, lse, rowscale point at the slab's first row.
 constexpr int CE_SLAB_ROWS = 1024;
 size_t ce_slab_elems(int V);
-void launch_ce_bwd_slab(int prec, const void* Ho, int ldho, const void* HoT, int ldhot, const void* Wo, const void* WoT,
-                        const float* Bo, const int32_t* labels, const float* lse, const float* rowscale, int M, int V, int H,
-                        void* dz, void* dzT, float* dHo, float* dWo, float* dBo, float* colscratch, float* dbo_parts,
-                        float* split_scratch, size_t split_scratch_floats, hipStream_t st);
+void launch_ce_dz(int prec, const void* Ho, int ldho, const void* Wo, const float* Bo, const int32_t* labels, const float* lse,
+                  const float* rowscale, int Mc, int V, int H, void* dz, void* dzT, hipStream_t st);
 
 // ---- step.hip ----------------------------------------------------------------------------------
 // A value delivered as `np` partial planes: v(b, c) = sum_k p[k * stride + b * ld + c]  (np = 0: zero).
 struct Planes { const float* p; int ld; int np; size_t stride; };
 // Number of k-blocks (= planes written) by launch_step_gemm for N output columns, contraction
 // length K and padded batch Bp (at most 8).
-int step_kblocks(int prec, int N, int K, int Bp);
+int step_kblocks(int prec, int N, int K, int Bp, int max_kb = 0);
 
 // One recurrent step of one LSTM layer (or of both directions of the bottom encoder layer when
 // ndir = 2): gates = Gx + [x; h_prev] W^T, then the cell, fused.
@@ -90,6 +88,7 @@ struct StepGemm {
                        //    kb < step_kblocks(prec, K0 + K1); the consumer sums them
   void* outT; int ldo;
   float* out; int ldout; size_t plane_stride;
+  int max_kb;          // cap on the number of k blocks (planes); 0 = default (8)
 };
 void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st);
 

@@ -109,24 +109,34 @@ __device__ __forceinline__ float planes_get(const Planes& p, int b, int c) {
 // ------------------------------------------------------------------------------------------------
 struct LstmFwdArgs { LstmFwdDir d[2]; };
 
-__device__ __forceinline__ void lstm_cell_store(const LstmFwdDir& d, int b, int u, int Hh, const float (&p)[4],
-                                                bool is_bf16) {
-  const float ig = sigm(p[0]), fg = sigm(p[1]), gg = tanhf(p[2]), og = sigm(p[3]);
-  const float cp = d.cprev[(size_t)b * Hh + u];
-  const float cn = fg * cp + ig * gg;
+// everything the cell update of one (sentence, unit) reads besides the GEMM result; loaded before the
+// contraction so that its latency hides behind the weight stream
+struct CellIn { float add[4]; float cp, hp, mask; };
+__device__ __forceinline__ CellIn cell_load(const LstmFwdDir& d, int b, int u, int Hh, bool is_bf16) {
+  CellIn in;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) in.add[g] = d.gx ? d.gx[(size_t)b * d.ldgx + g * Hh + u] : d.bias[g * Hh + u];
+  in.cp = d.cprev[(size_t)b * Hh + u];
+  in.mask = d.mask[b];
+  in.hp = is_bf16 ? bf2f(((const bf16_t*)d.hprev)[(size_t)b * d.ldh + u]) : ((const float*)d.hprev)[(size_t)b * d.ldh + u];
+  return in;
+}
+__device__ __forceinline__ void cell_finish(const LstmFwdDir& d, int b, int u, int Hh, const float (&pre)[4], const CellIn& in,
+                                            bool is_bf16) {
+  const float ig = sigm(pre[0] + in.add[0]), fg = sigm(pre[1] + in.add[1]);
+  const float gg = tanhf(pre[2] + in.add[2]), og = sigm(pre[3] + in.add[3]);
+  const float cn = fg * in.cp + ig * gg;
   const float hn = og * tanhf(cn);
-  const bool valid = d.mask[b] > 0.f;
-  d.cnext[(size_t)b * Hh + u] = valid ? cn : cp;
+  const bool valid = in.mask > 0.f;
+  d.cnext[(size_t)b * Hh + u] = valid ? cn : in.cp;
   float* gs = d.gsave + (size_t)b * 4 * Hh + u;
   gs[0] = ig; gs[Hh] = fg; gs[2 * Hh] = gg; gs[3 * Hh] = og;
   if (is_bf16) {
-    const bf16_t hp = ((const bf16_t*)d.hprev)[(size_t)b * d.ldh + u];
-    const bf16_t ho = valid ? f2bf(hn) : hp;
+    const bf16_t ho = f2bf(valid ? hn : in.hp);          // a carried state is already a bf16 value: exact
     ((bf16_t*)d.hnext)[(size_t)b * d.ldhn + u] = ho;
     if (d.ycat) ((bf16_t*)d.ycat)[(size_t)b * d.ldy + u] = ho;
   } else {
-    const float hp = ((const float*)d.hprev)[(size_t)b * d.ldh + u];
-    const float ho = valid ? hn : hp;
+    const float ho = valid ? hn : in.hp;
     ((float*)d.hnext)[(size_t)b * d.ldhn + u] = ho;
     if (d.ycat) ((float*)d.ycat)[(size_t)b * d.ldy + u] = ho;
   }
@@ -151,6 +161,15 @@ __global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(LstmFwdArgs args, int
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt)
     wrow[rt] = (const T*)d.W + (size_t)((m & 3) * Hh + min(u0 + 4 * rt + (m >> 2), Hh - 1)) * d.ldw;
+  // the first tile this wavefront will finish: fetch its cell inputs now
+  CellIn in0;
+  bool have0 = false;
+  if (w < RT * STEP_MAXBT) {
+    const int rt = w / STEP_MAXBT, bt = w - rt * STEP_MAXBT;
+    const int u = u0 + 4 * rt + (lane >> 4), b = 16 * (bt0 + bt) + (lane & 15);
+    have0 = bt < nbt && u < Hh && b < Bp;
+    if (have0) in0 = cell_load(d, b, u, Hh, sizeof(T) == 2);
+  }
   step_contract<T, RT, KS, U>(wrow, d.wx_off, d.wh_off, (const T*)d.x, d.ldx, d.Kx, (const T*)d.hprev, d.ldh, Hh, Bp, bt0,
                               nbt, red);
   for (int t = w; t < RT * STEP_MAXBT; t += KS) {
@@ -160,11 +179,9 @@ __global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(LstmFwdArgs args, int
     const int u = u0 + 4 * rt + (lane >> 4);
     const int b = 16 * (bt0 + bt) + (lane & 15);
     if (u >= Hh || b >= Bp) continue;
-    float p[4];
-#pragma unroll
-    for (int g = 0; g < 4; ++g)
-      p[g] = pre[g] + (d.gx ? d.gx[(size_t)b * d.ldgx + g * Hh + u] : d.bias[g * Hh + u]);
-    lstm_cell_store(d, b, u, Hh, p, sizeof(T) == 2);
+    const float p[4] = {pre[0], pre[1], pre[2], pre[3]};
+    if (t == w && have0) cell_finish(d, b, u, Hh, p, in0, sizeof(T) == 2);
+    else cell_finish(d, b, u, Hh, p, cell_load(d, b, u, Hh, sizeof(T) == 2), sizeof(T) == 2);
   }
 }
 
@@ -178,11 +195,11 @@ __global__ __launch_bounds__(256) void lstm_cell_kernel(LstmFwdArgs args, int Bp
   float p[4];
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
-    float v = d.gx ? d.gx[(size_t)b * d.ldgx + g * Hh + u] : d.bias[g * Hh + u];
+    float v = 0.f;
     for (int k = 0; k < np; ++k) v += d.part[((size_t)k * Bp + b) * 4 * Hh + g * Hh + u];
     p[g] = v;
   }
-  lstm_cell_store(d, b, u, Hh, p, sizeof(T) == 2);
+  cell_finish(d, b, u, Hh, p, cell_load(d, b, u, Hh, sizeof(T) == 2), sizeof(T) == 2);
 }
 
 template <typename T, int RT, int KS, int U>
@@ -208,7 +225,7 @@ void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh,
   a.d[1] = dirs[ndir > 1 ? 1 : 0];
   const int K = dirs[0].Kx + Hh;
   int how = g_lstm_fwd_how;
-  if (how == 0) how = 1;
+  if (how == 0) how = (Bp > 64) ? 2 : 1;           // measured: 32 gate rows per workgroup win once the batch exceeds 64
   if (how == 9) {
     int np = 1;
     for (int i = 0; i < ndir; ++i) {
@@ -251,7 +268,7 @@ void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh,
 // out[kb][b][n] that the consumer sums.
 // ------------------------------------------------------------------------------------------------
 struct Step2dPlan { int kb, steps_per_block, u; };
-static Step2dPlan plan2d(int prec, int N, int K, int Bp) {
+static Step2dPlan plan2d(int prec, int N, int K, int Bp, int max_kb) {
   const int nsteps = (K / 8 + 3) / 4;
   const int nrb = (N + 63) / 64, nz = ((Bp + 15) / 16 + STEP_MAXBT - 1) / STEP_MAXBT;
   const int u = prec ? 4 : 2;
@@ -259,6 +276,7 @@ static Step2dPlan plan2d(int prec, int N, int K, int Bp) {
   const int kb_max = (nsteps + 3) / 4;                  // at least one k-step per wavefront
   if (kb > kb_max) kb = kb_max;
   if (kb > 8) kb = 8;
+  if (max_kb > 0 && kb > max_kb) kb = max_kb;
   if (kb < 1) kb = 1;
   int spb = (nsteps + kb - 1) / kb;
   spb = (spb + 3) / 4 * 4;
@@ -268,7 +286,7 @@ static Step2dPlan plan2d(int prec, int N, int K, int Bp) {
   else if (spb <= 8 && p.u > 2) p.u = 2;
   return p;
 }
-int step_kblocks(int prec, int N, int K, int Bp) { return plan2d(prec, N, K, Bp).kb; }
+int step_kblocks(int prec, int N, int K, int Bp, int max_kb) { return plan2d(prec, N, K, Bp, max_kb).kb; }
 
 template <typename T, int U>
 __global__ __launch_bounds__(256) void step2d_kernel(StepGemm g, int Bp, StepGrid sg, int spb) {
@@ -361,7 +379,7 @@ __global__ __launch_bounds__(256) void tanh_planes_kernel(Planes p, T* __restric
 
 void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st) {
   const int nbt = (Bp + 15) / 16;
-  const Step2dPlan pl = plan2d(prec, g.N, g.K0 + g.K1, Bp);
+  const Step2dPlan pl = plan2d(prec, g.N, g.K0 + g.K1, Bp, g.max_kb);
   StepGrid sg{(g.N + 63) / 64, pl.kb, (nbt + STEP_MAXBT - 1) / STEP_MAXBT};
   const dim3 grid(step_grid_blocks(sg));
 #define GO(TT, UU) hipLaunchKernelGGL((step2d_kernel<TT, UU>), grid, dim3(256), 0, st, g, Bp, sg, pl.steps_per_block)
