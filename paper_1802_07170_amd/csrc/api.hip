@@ -272,38 +272,6 @@ int hip_fail(cmt_handle* h, hipError_t e, const char* what) {
 // ------------------------------------------------------------------------------------------------
 // the schedule
 // ------------------------------------------------------------------------------------------------
-void run_lstm_layer_bwd(cmt_handle* h, LD& d, int Lsteps, const float* mask, const float* dY, int lddy, int dy_col,
-                        bool reverse_dir, float* dh_buf, float* dc_buf) {
-  // encoder layers: loops over the steps in the reverse of the processing order; per step the cell
-  // backward, then the recurrent part of d state = dgates * W_h as planes for the next step.
-  const int p = h->prec, Bp = h->Bp, Hh = d.Hh;
-  const size_t esz = h->esz;
-  hipStream_t st = h->st;
-  const int kb = step_kblocks(p, Hh, 4 * Hh, Bp, h->kb_bwd);
-  const size_t pstride = (size_t)Bp * Hh;
-  for (int k = 0; k < Lsteps; ++k) {
-    const int t = reverse_dir ? k : Lsteps - 1 - k;
-    const int slot_prev = reverse_dir ? t + 1 : t, slot_next = reverse_dir ? t : t + 1;
-    LstmBwdPoint q;
-    q.dy = Planes{dY + (size_t)t * Bp * lddy, lddy, 1, 0}; q.dy_col = dy_col;
-    q.dhrec = Planes{d.bwdp, Hh, k == 0 ? 0 : kb, pstride}; q.dhrec_col = 0;
-    q.dh = dh_buf; q.dc = dc_buf;
-    q.gsave = d.Gs + (size_t)t * Bp * 4 * Hh;
-    q.cprev = d.Cst + (size_t)slot_prev * Bp * Hh; q.cnext = d.Cst + (size_t)slot_next * Bp * Hh;
-    q.mask = mask + (size_t)t * Bp;
-    q.dg = d.dG + (size_t)t * Bp * d.pg * esz; q.lddg = d.pg;
-    launch_lstm_bwd_point(p, q, Bp, Hh, st);
-    if (k + 1 == Lsteps) break;                      // the initial encoder state is a constant
-    StepGemm g{};
-    g.a0 = q.dg; g.lda0 = d.pg; g.K0 = 4 * Hh; g.w0_off = 0;
-    g.a1 = nullptr; g.lda1 = 0; g.K1 = 0; g.w1_off = 0;
-    g.W = d.Wt + (size_t)d.Kin * 4 * Hh * esz; g.ldw = 4 * Hh;
-    g.N = Hh; g.mode = 1; g.max_kb = h->kb_bwd;
-    g.out = d.bwdp; g.ldout = Hh; g.plane_stride = pstride;
-    launch_step_gemm(p, g, Bp, st);
-  }
-}
-
 // make stream `to` wait for everything enqueued so far on stream `from`
 void stream_after(cmt_handle* h, hipStream_t to, hipStream_t from) {
   if (to == from) return;
@@ -398,25 +366,39 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     }
     launch_lstm_fwd(p, d, 2, Bp, Hd, st);
   }
-  // ---- encoder layers >= 1 ------------------------------------------------------------------------
+  // ---- encoder layers >= 1: a wavefront over (layer, position) ------------------------------------
+  // Layer l at position t needs layer l-1 at t and itself at t-1, so all layers advance together
+  // along diagonals: one launch carries up to L-1 layer-steps (S + L - 2 launches instead of
+  // (L-1) S).  Layer 1 keeps its input part batched over all positions (the bottom layer is
+  // complete by then); layers above take [x; h] W^T per step.
   const char* Yprev = h->Y0;                       // [S*Bp, H]
   int ldY = H;
-  for (int l = 1; l < L; ++l) {
-    LD& e = h->enc[l + 1];
-    launch_gemm_nt(p, Yprev, ldY, e.W, 2 * H, Ms, 4 * H, H, e.Gx, nullptr, 4 * H, P + e.b_off, 0, st);
-    launch_fill_T(p, e.Hst, BP, st); launch_fill_f32(e.Cst, BH, 0.f, st);
-    for (int t = 0; t < S; ++t) {
-      LstmFwdDir d;
-      d.x = nullptr; d.ldx = 0; d.Kx = 0;
-      d.hprev = e.Hst + t * BP * esz; d.ldh = e.ph;
-      d.W = e.W; d.ldw = 2 * H; d.wx_off = 0; d.wh_off = H;
-      d.gx = e.Gx + (size_t)t * Bp * 4 * H; d.ldgx = 4 * H; d.bias = nullptr;
-      d.cprev = e.Cst + t * BH; d.mask = h->mask_s + (size_t)t * Bp;
-      d.hnext = e.Hst + (t + 1) * BP * esz; d.ldhn = e.ph; d.cnext = e.Cst + (t + 1) * BH;
-      d.gsave = e.Gs + (size_t)t * Bp * 4 * H; d.ycat = nullptr; d.ldy = 0; d.part = e.part;
-      launch_lstm_fwd(p, &d, 1, Bp, H, st);
+  if (L > 1) {
+    LD& e1 = h->enc[2];
+    launch_gemm_nt(p, h->Y0, H, e1.W, 2 * H, Ms, 4 * H, H, e1.Gx, nullptr, 4 * H, P + e1.b_off, 0, st);
+    for (int l = 1; l < L; ++l) { launch_fill_T(p, h->enc[l + 1].Hst, BP, st); launch_fill_f32(h->enc[l + 1].Cst, BH, 0.f, st); }
+    for (int dg = 0; dg < S + L - 2; ++dg) {
+      LstmFwdDir dirs[STEP_MAX_INST];
+      int n = 0;
+      for (int l = 1; l < L; ++l) {
+        const int t = dg - (l - 1);
+        if (t < 0 || t >= S) continue;
+        LD& e = h->enc[l + 1];
+        LstmFwdDir& d = dirs[n++];
+        if (l == 1) {
+          d.x = nullptr; d.ldx = 0; d.Kx = 0; d.gx = e.Gx + (size_t)t * Bp * 4 * H; d.ldgx = 4 * H; d.bias = nullptr;
+        } else {
+          d.x = h->enc[l].Hst + (t + 1) * BP * esz; d.ldx = PH; d.Kx = H; d.gx = nullptr; d.ldgx = 0; d.bias = P + e.b_off;
+        }
+        d.hprev = e.Hst + t * BP * esz; d.ldh = e.ph;
+        d.W = e.W; d.ldw = 2 * H; d.wx_off = 0; d.wh_off = H;
+        d.cprev = e.Cst + t * BH; d.mask = h->mask_s + (size_t)t * Bp;
+        d.hnext = e.Hst + (t + 1) * BP * esz; d.ldhn = e.ph; d.cnext = e.Cst + (t + 1) * BH;
+        d.gsave = e.Gs + (size_t)t * Bp * 4 * H; d.ycat = nullptr; d.ldy = 0; d.part = e.part;
+      }
+      launch_lstm_fwd(p, dirs, n, Bp, H, st);
     }
-    Yprev = e.Hst + BP * esz; ldY = e.ph;
+    Yprev = h->enc[L].Hst + BP * esz; ldY = PH;
   }
   const char* Hs = Yprev;
   const int ldHs = ldY;                          // source-side top-layer states [S, Bp, H]
@@ -593,28 +575,87 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   }
 
   // ---- encoder backwards ------------------------------------------------------------------------------
-  const float* dY = h->dHs;
-  float* dYnext = h->dYa;
-  for (int l = L - 1; l >= 1; --l) {
-    LD& e = h->enc[l + 1];
-    // gradient of the final state = gradient of the decoder's initial state of the same depth
-    run_lstm_layer_bwd(h, e, S, h->mask_s, dY, H, 0, false, h->dec[l].dh, h->dec[l].dc);
-    launch_gemm_nt(p, e.dG, e.pg, e.Wt, 4 * H, Ms, H, 4 * H, dYnext, nullptr, H, nullptr, 0, st);   // dX = dG W_x
+  // Upper layers: the same wavefront, top layer first.  Per diagonal one pointwise launch (cell
+  // backward of every active layer-step) and one step-GEMM launch ([dx; dh_prev] = dgates [W_x; W_h]).
+  if (L > 1) {
+    const int Nplan = L > 2 ? 2 * H : H;
+    const int kbE = step_kblocks(p, Nplan, 4 * H, Bp, h->kb_bwd);
+    const size_t pstrE = (size_t)Bp * 2 * H;
+    for (int dg = 0; dg < S + L - 2; ++dg) {
+      LstmBwdPoint pts[STEP_MAX_INST];
+      StepGemm gs[STEP_MAX_INST];
+      int n = 0, ng = 0;
+      for (int l = L - 1; l >= 1; --l) {
+        const int k = dg - (L - 1 - l);
+        if (k < 0 || k >= S) continue;
+        const int t = S - 1 - k;
+        LD& e = h->enc[l + 1];
+        LstmBwdPoint& q = pts[n++];
+        if (l == L - 1) q.dy = Planes{h->dHs + (size_t)t * Bp * H, H, 1, 0};
+        else q.dy = Planes{h->enc[l + 2].bwdp, 2 * H, kbE, pstrE};          // dx of the layer above (its columns [0, H))
+        q.dy_col = 0;
+        q.dhrec = Planes{e.bwdp, 2 * H, k == 0 ? 0 : kbE, pstrE};
+        q.dhrec_col = (l == 1) ? 0 : H;                                     // layer 1 only computes the recurrent part
+        // gradient of the final state = gradient of the decoder's initial state of the same depth
+        q.dh = h->dec[l].dh; q.dc = h->dec[l].dc;
+        q.gsave = e.Gs + (size_t)t * Bp * 4 * H;
+        q.cprev = e.Cst + t * BH; q.cnext = e.Cst + (t + 1) * BH;
+        q.mask = h->mask_s + (size_t)t * Bp;
+        q.dg = e.dG + (size_t)t * Bp * e.pg * esz; q.lddg = e.pg;
+        if (l == 1 && k == S - 1) continue;                                 // the initial state is a constant
+        StepGemm& g = gs[ng++];
+        g = StepGemm{};
+        g.a0 = q.dg; g.lda0 = e.pg; g.K0 = 4 * H; g.w0_off = 0; g.K1 = 0;
+        g.W = e.Wt + (size_t)(l == 1 ? H : 0) * 4 * H * esz; g.ldw = 4 * H;
+        g.N = (l == 1) ? H : 2 * H; g.mode = 1; g.max_kb = h->kb_bwd;
+        g.out = e.bwdp; g.ldout = 2 * H; g.plane_stride = pstrE;
+      }
+      launch_lstm_bwd_point_multi(p, pts, n, Bp, H, st);
+      if (ng) launch_step_gemm_multi(p, gs, ng, Nplan, Bp, st);
+    }
+    LD& e1 = h->enc[2];
+    launch_gemm_nt(p, e1.dG, e1.pg, e1.Wt, 4 * H, Ms, H, 4 * H, h->dYa, nullptr, H, nullptr, 0, st);   // layer 0's dY = dG_1 W_x
     stream_after(h, sd, st);
-    int ld; const char* XT = encYT(l - 1, &ld);
-    weight_grads(h, e, S, {{XT, ld}, {e.HstT, (S + 1) * Bp}}, {H, H}, sd);
-    dY = dYnext;
-    dYnext = (dYnext == h->dYa) ? h->dYb : h->dYa;
+    for (int l = L - 1; l >= 1; --l) {
+      LD& e = h->enc[l + 1];
+      int ld; const char* XT = encYT(l - 1, &ld);
+      weight_grads(h, e, S, {{XT, ld}, {e.HstT, (S + 1) * Bp}}, {H, H}, sd);
+    }
   }
-  {
+  {   // bottom layer: the two directions run in the same launches
+    const float* dY0 = L > 1 ? h->dYa : h->dHs;
     LD& d0 = h->dec[0];
     launch_copy2d_f32(d0.dh, H, ef.dh, Hd, Bp, Hd, st); launch_copy2d_f32(d0.dh + Hd, H, eb.dh, Hd, Bp, Hd, st);
     launch_copy2d_f32(d0.dc, H, ef.dc, Hd, Bp, Hd, st); launch_copy2d_f32(d0.dc + Hd, H, eb.dc, Hd, Bp, Hd, st);
-    run_lstm_layer_bwd(h, ef, S, h->mask_s, dY, H, 0, false, ef.dh, ef.dc);
+    const int kb0 = step_kblocks(p, Hd, 4 * Hd, Bp, h->kb_bwd);
+    const size_t pstr0 = (size_t)Bp * Hd;
+    for (int k = 0; k < S; ++k) {
+      LstmBwdPoint pts[2];
+      StepGemm gs[2];
+      for (int i = 0; i < 2; ++i) {
+        LD& e = i ? eb : ef;
+        const int t = i ? k : S - 1 - k;                                    // reverse of each direction's processing order
+        const int slot_prev = i ? t + 1 : t, slot_next = i ? t : t + 1;
+        LstmBwdPoint& q = pts[i];
+        q.dy = Planes{dY0 + (size_t)t * Bp * H, H, 1, 0}; q.dy_col = i ? Hd : 0;
+        q.dhrec = Planes{e.bwdp, Hd, k == 0 ? 0 : kb0, pstr0}; q.dhrec_col = 0;
+        q.dh = e.dh; q.dc = e.dc;
+        q.gsave = e.Gs + (size_t)t * Bp * 4 * Hd;
+        q.cprev = e.Cst + (size_t)slot_prev * BHd; q.cnext = e.Cst + (size_t)slot_next * BHd;
+        q.mask = h->mask_s + (size_t)t * Bp;
+        q.dg = e.dG + (size_t)t * Bp * e.pg * esz; q.lddg = e.pg;
+        StepGemm& g = gs[i];
+        g = StepGemm{};
+        g.a0 = q.dg; g.lda0 = e.pg; g.K0 = 4 * Hd; g.w0_off = 0; g.K1 = 0;
+        g.W = e.Wt + (size_t)E * 4 * Hd * esz; g.ldw = 4 * Hd;
+        g.N = Hd; g.mode = 1; g.max_kb = h->kb_bwd;
+        g.out = e.bwdp; g.ldout = Hd; g.plane_stride = pstr0;
+      }
+      launch_lstm_bwd_point_multi(p, pts, 2, Bp, Hd, st);
+      if (k + 1 < S) launch_step_gemm_multi(p, gs, 2, Hd, Bp, st);          // the initial state is a constant
+    }
     stream_after(h, sd, st);
     weight_grads(h, ef, S, {{h->XsT, Ms}, {ef.HstT, (S + 1) * Bp}}, {E, Hd}, sd);
-    run_lstm_layer_bwd(h, eb, S, h->mask_s, dY, H, Hd, true, eb.dh, eb.dc);
-    stream_after(h, sd, st);
     weight_grads(h, eb, S, {{h->XsT, Ms}, {eb.HstT + (size_t)Bp * esz, (S + 1) * Bp}}, {E, Hd}, sd);
     launch_gemm_nt(p, ef.dG, ef.pg, ef.Wt, 4 * Hd, Ms, E, 4 * Hd, h->dXs, nullptr, E, nullptr, 0, sd);
     launch_gemm_nt(p, eb.dG, eb.pg, eb.Wt, 4 * Hd, Ms, E, 4 * Hd, h->dXs, nullptr, E, nullptr, 1, sd);

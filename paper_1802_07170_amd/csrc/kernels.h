@@ -53,6 +53,9 @@ void launch_ce_dz(int prec, const void* Ho, int ldho, const void* Wo, const floa
 
 // ---- step.hip ----------------------------------------------------------------------------------
 // A value delivered as `np` partial planes: v(b, c) = sum_k p[k * stride + b * ld + c]  (np = 0: zero).
+// Independent instances (layers / directions working on different time steps) that one launch of a
+// step kernel can carry.
+constexpr int STEP_MAX_INST = 8;
 struct Planes { const float* p; int ld; int np; size_t stride; };
 // Number of k-blocks (= planes written) by launch_step_gemm for N output columns, contraction
 // length K and padded batch Bp (at most 8).
@@ -73,6 +76,7 @@ struct LstmFwdDir {
   void* ycat; int ldy;                  // optional second copy of h (T*, row pitch ldy), or null
   float* part;                          // [8][Bp][4Hh] scratch planes, used when the k range is split
 };
+// ndir <= STEP_MAX_INST instances of equal hidden width Hh in one launch.
 void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh, hipStream_t st);
 
 // [a0; a1] W^T for one step.  W rows are output columns; w0_off / w1_off are the column offsets
@@ -91,6 +95,10 @@ struct StepGemm {
   int max_kb;          // cap on the number of k blocks (planes); 0 = default (8)
 };
 void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st);
+// n <= STEP_MAX_INST instances in one launch (mode 1 only): same K0 + K1 and max_kb, N may differ; the
+// number of planes each instance writes is step_kblocks of the widest one.
+// n_plan > 0 fixes the width the k-block plan is made for (so that it does not change from launch to launch).
+void launch_step_gemm_multi(int prec, const StepGemm* gs, int n, int n_plan, int Bp, hipStream_t st);
 
 // Cell backward for one step of one layer: builds dgates (T*) from the incoming state gradients.
 struct LstmBwdPoint {
@@ -104,6 +112,7 @@ struct LstmBwdPoint {
   void* dg; int lddg;                  // T* [Bp,4Hh], row pitch lddg
 };
 void launch_lstm_bwd_point(int prec, const LstmBwdPoint& p, int Bp, int Hh, hipStream_t st);
+void launch_lstm_bwd_point_multi(int prec, const LstmBwdPoint* ps, int n, int Bp, int Hh, hipStream_t st);
 // out[Bp, cols] = base (or 0) + planes columns col0 + [0, cols)
 void launch_planes_add(float* out, const float* base, const Planes& p, int col0, int Bp, int cols, hipStream_t st);
 

@@ -22,6 +22,8 @@ namespace cmt {
 constexpr int STEP_MAXBT = 4;          // batch tiles (of 16 sentences) per workgroup
 
 struct StepGrid { int nx, kb, nz; };
+struct StepGemmArgs { StepGemm g[STEP_MAX_INST]; };
+struct LstmBwdPointArgs { LstmBwdPoint p[STEP_MAX_INST]; };
 __device__ __forceinline__ bool decode_block(const StepGrid& g, int& x, int& kb, int& z) {
   const int L = blockIdx.x;
   const int xcd = L & 7;
@@ -107,7 +109,7 @@ __device__ __forceinline__ float planes_get(const Planes& p, int b, int c) {
 // ------------------------------------------------------------------------------------------------
 // LSTM forward step
 // ------------------------------------------------------------------------------------------------
-struct LstmFwdArgs { LstmFwdDir d[2]; };
+struct LstmFwdArgs { LstmFwdDir d[STEP_MAX_INST]; };
 
 // everything the cell update of one (sentence, unit) reads besides the GEMM result; loaded before the
 // contraction so that its latency hides behind the weight stream
@@ -221,9 +223,11 @@ void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh,
     g_lstm_fwd_how = e ? atoi(e) : 0;
   }
   LstmFwdArgs a;
-  a.d[0] = dirs[0];
-  a.d[1] = dirs[ndir > 1 ? 1 : 0];
-  const int K = dirs[0].Kx + Hh;
+  int K = 0;
+  for (int i = 0; i < STEP_MAX_INST; ++i) {
+    a.d[i] = dirs[i < ndir ? i : 0];
+    if (i < ndir && dirs[i].Kx + Hh > K) K = dirs[i].Kx + Hh;      // instances may differ in their input width
+  }
   int how = g_lstm_fwd_how;
   if (how == 0) how = (Bp > 64) ? 2 : 1;           // measured: 32 gate rows per workgroup win once the batch exceeds 64
   if (how == 9) {
@@ -289,10 +293,12 @@ static Step2dPlan plan2d(int prec, int N, int K, int Bp, int max_kb) {
 int step_kblocks(int prec, int N, int K, int Bp, int max_kb) { return plan2d(prec, N, K, Bp, max_kb).kb; }
 
 template <typename T, int U>
-__global__ __launch_bounds__(256) void step2d_kernel(StepGemm g, int Bp, StepGrid sg, int spb) {
+__global__ __launch_bounds__(256) void step2d_kernel(StepGemmArgs args, int Bp, StepGrid sg, int spb) {
   __shared__ __align__(16) float red[4 * 16 * 64 * 4];
+  const StepGemm& g = args.g[blockIdx.y];
   int x, kb, z;
   if (!decode_block(sg, x, kb, z)) return;
+  if (x * 64 >= g.N) return;                       // instances of one launch may differ in N
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int n0 = x * 64;
   const int bt0 = z * STEP_MAXBT;
@@ -377,12 +383,35 @@ __global__ __launch_bounds__(256) void step2d_kernel(StepGemm g, int Bp, StepGri
 template <typename T>
 __global__ __launch_bounds__(256) void tanh_planes_kernel(Planes p, T* __restrict__ out, int ldo, int Bp, int N);
 
+// n instances in one launch (blockIdx.y); they share the contraction length and the k-block plan,
+// which is the plan of the widest instance.
+void launch_step_gemm_multi(int prec, const StepGemm* gs, int n, int n_plan, int Bp, hipStream_t st) {
+  const int nbt = (Bp + 15) / 16;
+  StepGemmArgs a;
+  int Nmax = 0;
+  for (int i = 0; i < STEP_MAX_INST; ++i) {
+    a.g[i] = gs[i < n ? i : 0];
+    if (i < n && gs[i].N > Nmax) Nmax = gs[i].N;
+  }
+  if (n_plan > Nmax) Nmax = n_plan;
+  const StepGemm& g = gs[0];
+  const Step2dPlan pl = plan2d(prec, Nmax, g.K0 + g.K1, Bp, g.max_kb);
+  StepGrid sg{(Nmax + 63) / 64, pl.kb, (nbt + STEP_MAXBT - 1) / STEP_MAXBT};
+  const dim3 grid(step_grid_blocks(sg), n);
+#define GO(TT, UU) hipLaunchKernelGGL((step2d_kernel<TT, UU>), grid, dim3(256), 0, st, a, Bp, sg, pl.steps_per_block)
+  if (prec) { if (pl.u == 4) GO(bf16_t, 4); else if (pl.u == 2) GO(bf16_t, 2); else GO(bf16_t, 1); }
+  else { if (pl.u == 2) GO(float, 2); else GO(float, 1); }
+#undef GO
+}
+
 void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st) {
   const int nbt = (Bp + 15) / 16;
   const Step2dPlan pl = plan2d(prec, g.N, g.K0 + g.K1, Bp, g.max_kb);
   StepGrid sg{(g.N + 63) / 64, pl.kb, (nbt + STEP_MAXBT - 1) / STEP_MAXBT};
   const dim3 grid(step_grid_blocks(sg));
-#define GO(TT, UU) hipLaunchKernelGGL((step2d_kernel<TT, UU>), grid, dim3(256), 0, st, g, Bp, sg, pl.steps_per_block)
+  StepGemmArgs a;
+  for (int i = 0; i < STEP_MAX_INST; ++i) a.g[i] = g;
+#define GO(TT, UU) hipLaunchKernelGGL((step2d_kernel<TT, UU>), grid, dim3(256), 0, st, a, Bp, sg, pl.steps_per_block)
   if (prec) { if (pl.u == 4) GO(bf16_t, 4); else if (pl.u == 2) GO(bf16_t, 2); else GO(bf16_t, 1); }
   else { if (pl.u == 2) GO(float, 2); else GO(float, 1); }
 #undef GO
@@ -427,7 +456,8 @@ template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t* p, const floa
 
 // one thread per (sentence, 4 consecutive units)
 template <typename T>
-__global__ __launch_bounds__(256) void lstm_bwd_point_kernel(LstmBwdPoint p, int Bp, int Hh) {
+__global__ __launch_bounds__(256) void lstm_bwd_point_kernel(LstmBwdPointArgs args, int Bp, int Hh) {
+  const LstmBwdPoint& p = args.p[blockIdx.y];
   const int idx4 = blockIdx.x * 256 + threadIdx.x;
   const int hq = Hh >> 2;
   if (idx4 >= Bp * hq) return;
@@ -470,10 +500,16 @@ __global__ __launch_bounds__(256) void lstm_bwd_point_kernel(LstmBwdPoint p, int
   store4<float>(p.dh + idx, zero);                 // the recurrent part arrives as planes of the step GEMM
 }
 
+void launch_lstm_bwd_point_multi(int prec, const LstmBwdPoint* ps, int n, int Bp, int Hh, hipStream_t st) {
+  LstmBwdPointArgs a;
+  for (int i = 0; i < STEP_MAX_INST; ++i) a.p[i] = ps[i < n ? i : 0];
+  const int cnt = Bp * (Hh >> 2);
+  const dim3 grid((cnt + 255) / 256, n);
+  if (prec) hipLaunchKernelGGL(lstm_bwd_point_kernel<bf16_t>, grid, dim3(256), 0, st, a, Bp, Hh);
+  else hipLaunchKernelGGL(lstm_bwd_point_kernel<float>, grid, dim3(256), 0, st, a, Bp, Hh);
+}
 void launch_lstm_bwd_point(int prec, const LstmBwdPoint& p, int Bp, int Hh, hipStream_t st) {
-  const int n = Bp * (Hh >> 2);
-  if (prec) hipLaunchKernelGGL(lstm_bwd_point_kernel<bf16_t>, dim3((n + 255) / 256), dim3(256), 0, st, p, Bp, Hh);
-  else hipLaunchKernelGGL(lstm_bwd_point_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, st, p, Bp, Hh);
+  launch_lstm_bwd_point_multi(prec, &p, 1, Bp, Hh, st);
 }
 
 // out[b, c] = base[b, c] + sum of planes (plain fp32 [Bp, cols])
