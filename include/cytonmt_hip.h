@@ -10,10 +10,15 @@
  * Conventions
  *   - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary host memory.
  *   - The caller owns every device buffer (parameters, gradients, workspace, ids, lengths) and
- *     the HIP stream; the library owns only the host-side handle and a few bytes of pinned host
- *     memory.  It never allocates or frees device memory.
- *   - All work is enqueued on the stream given to cmt_create.  Calls that return data to host
- *     memory synchronise that stream before returning.
+ *     the HIP stream; the library owns only the host-side handle, a few bytes of pinned host
+ *     memory, one internal non-blocking stream of default priority and a pool of events.  It
+ *     never allocates or frees device memory.
+ *   - All work is ordered on the stream given to cmt_create: inside a training step the
+ *     library forks work that is off the recurrences' critical path onto its internal stream
+ *     and joins it back before the step's last kernel, so whatever the caller enqueues on its
+ *     stream afterwards sees the finished step.  Calls that return data to host memory
+ *     synchronise that stream before returning.  Environment variable CMT_SIDE_STREAM=0 (read
+ *     in cmt_create) keeps everything on the caller's stream.
  *   - Every function returns CMT_OK (0) or a negative error code; nothing throws or aborts
  *     across this boundary.  cmt_last_error gives the text of the last failure on a handle.
  *   - Matrices are row-major [out, in].  Flat parameter / gradient vectors are fp32 in the
