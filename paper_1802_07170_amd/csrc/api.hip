@@ -96,7 +96,7 @@ struct cmt_handle {
   char* HoBuf = nullptr; char* HoBufT = nullptr; char* Cs = nullptr; char* CsT = nullptr;
   float* att_a = nullptr; float* att_ds = nullptr; float* dCs = nullptr; float* dots = nullptr;
   char* dPre = nullptr; char* dPreT = nullptr;
-  float* dHoCE = nullptr; float* dHoPart = nullptr;
+  float* dHoCE = nullptr;
   float* dHt = nullptr; float* wcp = nullptr;
   float* dXt = nullptr; char* XtT = nullptr;
   float *pmax = nullptr, *psum = nullptr, *zy = nullptr, *lse = nullptr, *nll = nullptr, *rowscale = nullptr;
@@ -108,7 +108,6 @@ struct cmt_handle {
   int use_side = 1;
   char* dzs2 = nullptr; char* dzTs2 = nullptr; float* gsplit2 = nullptr;
   int kb_bwd = 0, kb_wc = 0;            // caps on the k blocks of the backward step GEMMs (0 = default)
-  int ce_bwd_fused = 0;                 // 1: rebuild dz in LDS inside the product kernels; 0: slab staging
   size_t ws_bytes = 0;
 
   const char* Pw(size_t off) const { return Pc + off * esz; }
@@ -212,7 +211,6 @@ size_t layout(cmt_handle* h, char* base) {
   h->dots = (float*)a.take((size_t)Bp * Sm * 4);
   h->dPre = a.take(Mt * PH * esz); h->dPreT = a.take(Mt * H * esz);
   h->dHoCE = (float*)a.take(Mt * H * 4);
-  h->dHoPart = (float*)a.take((size_t)16 * Mt * H * 4);
   h->dHt = (float*)a.take((size_t)Bp * H * 4);
   h->wcp = (float*)a.take((size_t)8 * Bp * 2 * H * 4);
   h->dXt = (float*)a.take(Mt * E * 4);
@@ -340,6 +338,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
                 nullptr, h->len_s, h->flags, st);
   launch_gather(p, h->Pw(h->off_Etgt), c.tgt_vocab, E, tgt_ids, tgt_len, B, Bp, T, 1, c.bos_id, h->Xt, h->mask_t,
                 h->tok_t, h->labels, h->len_t, h->flags, st);
+  launch_ce_rowscale(h->mask_t, Mt, h->rowscale, h->loss, st);   // n_tok and mask / n_tok: the lengths give them
 
   // ---- encoder layer 0: two directions ------------------------------------------------------------
   LD& ef = h->enc[0]; LD& eb = h->enc[1];
@@ -437,16 +436,12 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       launch_step_gemm(p, g, Bp, st);
     }
   }
-  // ---- Eq. 1: fused projection + log-softmax + cross-entropy --------------------------------------
-  const char* Ho = h->HoBuf + BP * esz;            // [T*Bp, H], row pitch PH
-  const int np = ce_num_partials(V);
-  launch_ce_fwd(p, Ho, PH, h->Pw(h->off_Wo), P + h->off_Bo, h->labels, Mt, V, H, h->pmax, h->psum, h->zy, st);
-  launch_ce_reduce(h->pmax, h->psum, h->zy, h->mask_t, Mt, np, h->lse, h->nll, h->rowscale, h->loss, h->flags, st);
-
-  // =================================== backward ======================================================
+  // =================================== output layer (Eq. 1) and backward ==============================
   // The recurrences' backward loops are chains of short dependent kernels that leave most of the
   // chip idle; everything that does not feed them (transposes, weight gradients, dW_o, embedding
   // scatters) runs on the library's second stream and joins at the end of the step.
+  const char* Ho = h->HoBuf + BP * esz;            // [T*Bp, H], row pitch PH
+  const int np = ce_num_partials(V);
   hipStream_t sd = h->use_side ? h->side : st;
   const int ldHoT = Mt + Bp;
   const char* HoT = h->HoBufT + (size_t)Bp * esz;  // columns of H_o^{<0..T-1>}
@@ -461,27 +456,24 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   launch_transpose(p, h->Xs, E, h->XsT, Ms, Ms, E, sd);
   launch_transpose(p, h->Xt, E, h->XtT, Mt, Mt, E, sd);
   launch_transpose(p, h->Cs, PH, h->CsT, Mt, Mt, H, sd);
-
-  if (h->ce_bwd_fused) {
-    const int nsplit = ce_bwd_nsplit(Mt, V);
-    launch_ce_bwd_dh(p, Ho, PH, h->Pw(h->off_Wo), h->WoT, P + h->off_Bo, h->labels, h->lse, h->rowscale, Mt, V, H, nsplit,
-                     h->dHoPart, st);
-    launch_sum_parts(h->dHoPart, nsplit, (size_t)Mt * H, h->dHoCE, st);
-    launch_ce_bwd_dw(p, Ho, PH, HoT, ldHoT, h->Pw(h->off_Wo), P + h->off_Bo, h->labels, h->lse, h->rowscale, Mt, V, H,
-                     G + h->off_Wo, G + h->off_Bo, sd);
-  } else {
-    // slabs of <= CE_SLAB_ROWS rows, two slab buffers: the main stream rebuilds dz and takes dH_o (the
-    // decoder needs it), the second stream takes dW_o and dB_o
+  {
+    // Slabs of <= CE_SLAB_ROWS rows, equal sizes, two slab buffer pairs.  Per slab the main stream
+    // takes forward (logits -> e, partials), lse / nll, e -> dz and dz^T, and dH_o = dz W_o (the
+    // decoder needs it); the second stream takes dW_o += dz^T H_o and dB_o.
     const int nslab = (Mt + CE_SLAB_ROWS - 1) / CE_SLAB_ROWS;
+    const int rows = (((Mt + nslab - 1) / nslab) + 63) / 64 * 64;
     std::vector<hipEvent_t> done(nslab, nullptr);
-    for (int sl = 0; sl < nslab; ++sl) {
-      const int m0 = sl * CE_SLAB_ROWS;
-      const int Mc = Mt - m0 < CE_SLAB_ROWS ? Mt - m0 : CE_SLAB_ROWS;
+    int sl = 0;
+    for (int m0 = 0; m0 < Mt; m0 += rows, ++sl) {
+      const int Mc = Mt - m0 < rows ? Mt - m0 : rows;
       char* dz = (sl & 1) ? h->dzs2 : h->dzs;
       char* dzT = (sl & 1) ? h->dzTs2 : h->dzTs;
       if (sl >= 2 && sd != st) (void)hipStreamWaitEvent(st, done[sl - 2], 0);
-      launch_ce_dz(p, Ho + (size_t)m0 * PH * esz, PH, h->Pw(h->off_Wo), P + h->off_Bo, h->labels + m0, h->lse + m0,
-                   h->rowscale + m0, Mc, V, H, dz, dzT, st);
+      launch_ce_fwd(p, Ho + (size_t)m0 * PH * esz, PH, h->Pw(h->off_Wo), P + h->off_Bo, h->labels + m0, Mc, V, H, dz,
+                    h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, h->zy + m0, st);
+      launch_ce_rows(h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, h->zy + m0, h->mask_t + m0, Mc, np, h->lse + m0,
+                     h->nll + m0, st);
+      launch_ce_scale(p, dz, V, Mc, h->pmax + (size_t)m0 * np, h->lse + m0, h->labels + m0, h->rowscale + m0, dzT, st);
       stream_after(h, sd, st);
       launch_gemm_nt(p, dz, V, h->WoT, V, Mc, H, V, h->dHoCE + (size_t)m0 * H, nullptr, H, nullptr, 0, st, h->gsplit,
                      h->gsplit_floats);                                   // dH_o[slab] = dz W_o
@@ -493,7 +485,8 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
         (void)hipEventRecord(done[sl], sd);
       }
     }
-    launch_sum_parts(h->dbo_parts, nslab, (size_t)V, G + h->off_Bo, sd);
+    launch_sum_parts(h->dbo_parts, sl, (size_t)V, G + h->off_Bo, sd);
+    launch_ce_loss(h->nll, Mt, h->loss, h->flags, st);
   }
 
   // ---- decoder loop backwards -----------------------------------------------------------------------
@@ -702,8 +695,6 @@ int cmt_create(const cmt_config* cfg, void* params_dev, void* grads_dev, void* w
   h->params = (float*)params_dev; h->grads = (float*)grads_dev; h->ws = (char*)workspace_dev;
   h->Bpm = round_up(cfg->max_batch, 16);
   {
-    const char* e = getenv("CMT_CE_BWD");
-    h->ce_bwd_fused = (e && std::string(e) == "fused") ? 1 : 0;
     const char* k1 = getenv("CMT_KB_BWD"); h->kb_bwd = k1 ? atoi(k1) : 0;
     const char* k2 = getenv("CMT_KB_WC"); h->kb_wc = k2 ? atoi(k2) : 2;
     const char* k3 = getenv("CMT_SIDE_STREAM"); h->use_side = k3 ? atoi(k3) : 1;

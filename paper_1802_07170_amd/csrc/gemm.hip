@@ -4,17 +4,29 @@
 // weight-gradient operands into that form.
 #include "gemm_core.h"
 #include "kernels.h"
+#include <cstdlib>
 
 namespace cmt {
 
+// Dispatch thresholds, from measurements on MI355X (bf16, k = 1024 .. 4096): with 208 tiles of
+// 256 x 256 the big tile already wins (628 against 546 TFLOP/s), with 128 it loses.
+static int env_int(const char* name, int dflt) {
+  const char* e = getenv(name);
+  return e && *e ? atoi(e) : dflt;
+}
+static const int GEMM_BIG_MIN_TILES = env_int("CMT_GEMM_BIG_MIN_TILES", 192);
+static const int GEMM_SPLIT_BELOW = env_int("CMT_GEMM_SPLIT_BELOW", 128);
+static const int GEMM_SPLIT_TARGET = env_int("CMT_GEMM_SPLIT_TARGET", 256);
+static const int GEMM_SPLIT_MAX = env_int("CMT_GEMM_SPLIT_MAX", 8);
+
 // blockIdx.y = k split index: each split contracts kchunk elements of k and, when there is more
 // than one, writes its own fp32 plane Cf + split * plane_stride (summed afterwards, fixed order).
-template <typename T, int TA, int TB, int KB>
-__global__ __launch_bounds__(256) void gemm_nt_kernel(const T* __restrict__ A, int lda, const T* __restrict__ B, int ldb,
-                                                      int M, int N, int K, float* __restrict__ Cf, T* __restrict__ Ct,
-                                                      int ldc, const float* __restrict__ bias, int accumulate, int ntn,
-                                                      int kchunk, size_t plane_stride) {
-  using G = GemmTile<TA, TB, KB>;
+template <typename T, int WM, int WN, int TA, int TB, int KB>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_nt_kernel(const T* __restrict__ A, int lda, const T* __restrict__ B, int ldb,
+                                                               int M, int N, int K, float* __restrict__ Cf, T* __restrict__ Ct,
+                                                               int ldc, const float* __restrict__ bias, int accumulate, int ntn,
+                                                               int kchunk, size_t plane_stride) {
+  using G = GemmTile<WM, WN, TA, TB, KB>;
   __shared__ __align__(16) char smem[G::SMEM_BYTES];
   // consecutive workgroup ids go round-robin to the 8 XCDs: give each XCD a contiguous band of
   // tiles that share their A rows, so that operand tiles are re-read from that XCD's L2
@@ -25,10 +37,10 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const T* __restrict__ A, i
   const int k0 = blockIdx.y * kchunk;
   const int klen = min(kchunk, K - k0);
   v16f acc[TA][TB];
-  gemm_mainloop<T, TA, TB, KB>(A + k0, lda, B + k0, ldb, M, N, klen, m0, n0, acc, smem);
+  gemm_mainloop<T, WM, WN, TA, TB, KB>(A + k0, lda, B + k0, ldb, M, N, klen, m0, n0, acc, smem);
   if (gridDim.y > 1) Cf += blockIdx.y * plane_stride;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int wm = w >> 1, wn = w & 1;
+  const int wm = w / WN, wn = w % WN;
 #pragma unroll
   for (int nt = 0; nt < TB; ++nt) {
     const int col = n0 + wn * 32 * TB + nt * 32 + (lane & 31);
@@ -64,21 +76,36 @@ __global__ __launch_bounds__(256) void gemm_planes_sum_kernel(const float* __res
   }
 }
 
+template <typename T, int WM, int WN, int TA, int TB>
+static void gemm_go(dim3 grid, hipStream_t st, const void* A, int lda, const void* B, int ldb, int M, int N, int K, float* out,
+                    void* Ct, int ldc, const float* bias, int acc, int ntn, int kchunk, size_t pstride) {
+  hipLaunchKernelGGL((gemm_nt_kernel<T, WM, WN, TA, TB, 128>), grid, dim3(64 * WM * WN), 0, st, (const T*)A, lda, (const T*)B, ldb,
+                     M, N, K, out, (T*)Ct, ldc, bias, acc, ntn, kchunk, pstride);
+}
+
 void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, int M, int N, int K,
                     float* Cf, void* Ct, int ldc, const float* bias, int accumulate, hipStream_t st,
                     float* split_scratch, size_t split_scratch_floats) {
   if (M <= 0 || N <= 0) return;
-  using G = GemmTile<2, 2, 128>;
+  // enough 256 x 256 tiles to fill the chip: the big tile (half the L2 traffic per flop)
+  const int ntm_b = (M + GemmBig::BM - 1) / GemmBig::BM, ntn_b = (N + GemmBig::BN - 1) / GemmBig::BN;
+  if (ntm_b * ntn_b >= GEMM_BIG_MIN_TILES) {
+    const int grid = ((ntm_b * ntn_b + 7) / 8) * 8;
+    if (prec) gemm_go<bf16_t, 4, 4, 2, 2>(dim3(grid, 1), st, A, lda, B, ldb, M, N, K, Cf, Ct, ldc, bias, accumulate, ntn_b, K, 0);
+    else gemm_go<float, 4, 4, 2, 2>(dim3(grid, 1), st, A, lda, B, ldb, M, N, K, Cf, Ct, ldc, bias, accumulate, ntn_b, K, 0);
+    return;
+  }
+  using G = GemmSmall;
   const int ntm = (M + G::BM - 1) / G::BM, ntn = (N + G::BN - 1) / G::BN;
   const int nb = ntm * ntn;
   const int grid = ((nb + 7) / 8) * 8;
   const int esz = prec ? 2 : 4;
   const int bk = 128 / esz;
-  // few output tiles but a long contraction: split k over workgroups
+  // few output tiles but a long contraction: split k over workgroups (two workgroups per CU wanted)
   int ks = 1;
-  if (split_scratch && Cf && !Ct && nb < 128 && K >= 16 * bk) {
-    ks = (256 + nb - 1) / nb;
-    if (ks > 8) ks = 8;
+  if (split_scratch && Cf && !Ct && nb < GEMM_SPLIT_BELOW && K >= 16 * bk) {
+    ks = (GEMM_SPLIT_TARGET + nb - 1) / nb;
+    if (ks > GEMM_SPLIT_MAX) ks = GEMM_SPLIT_MAX;
     while (ks > 1 && ((size_t)ks * M * N > split_scratch_floats || K / ks < 4 * bk)) --ks;
   }
   int kchunk = K;
@@ -89,12 +116,8 @@ void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, in
   const int oldc = nks > 1 ? N : ldc;
   const float* obias = nks > 1 ? nullptr : bias;
   const int oacc = nks > 1 ? 0 : accumulate;
-  if (prec)
-    hipLaunchKernelGGL((gemm_nt_kernel<bf16_t, 2, 2, 128>), dim3(grid, nks), dim3(256), 0, st, (const bf16_t*)A, lda,
-                       (const bf16_t*)B, ldb, M, N, K, out, (bf16_t*)Ct, oldc, obias, oacc, ntn, kchunk, pstride);
-  else
-    hipLaunchKernelGGL((gemm_nt_kernel<float, 2, 2, 128>), dim3(grid, nks), dim3(256), 0, st, (const float*)A, lda,
-                       (const float*)B, ldb, M, N, K, out, (float*)Ct, oldc, obias, oacc, ntn, kchunk, pstride);
+  if (prec) gemm_go<bf16_t, 2, 2, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, out, Ct, oldc, obias, oacc, ntn, kchunk, pstride);
+  else gemm_go<float, 2, 2, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, out, Ct, oldc, obias, oacc, ntn, kchunk, pstride);
   if (nks > 1) {
     size_t g = (pstride + 255) / 256;
     if (g > 4096) g = 4096;

@@ -1,31 +1,38 @@
 // LDS-tiled matrix-core main loop for C = A * B^T with both operands k-contiguous (the paper's
 // LinearLayer forward GEMM form; every batched-over-time contraction of the step is brought to
-// this form).  256 threads = 4 wavefronts in a 2x2 grid; each wavefront owns TA x TB MFMA 32x32
-// tiles, so the workgroup tile is (64 TA) x (64 TB).  Measured on MI355X the 128 x 128 tile
-// (TA = TB = 2, 72 KB of LDS, two workgroups per CU hiding each other's barriers) beats the larger
-// register tiles, which fall to one workgroup per CU.  Tiles of KB bytes of k per row are
-// double-buffered in LDS; the next tile's global loads are in flight while the current one feeds
-// the matrix cores.
+// this form).  WM x WN wavefronts; each wavefront owns TA x TB MFMA 32x32 tiles, so the workgroup
+// tile is (32 TA WM) x (32 TB WN).  Two shapes are used:
+//   * 2x2 wavefronts, 2x2 tiles each: 128 x 128, 256 threads, 72 KB of LDS, two workgroups per CU
+//     hiding each other's barriers.  Reads 32 KB from L2 per 2 x 128 x 128 x 64 flops: at the
+//     800 TFLOP/s it reaches, L2 -> CU traffic is 12 TB/s, which is what bounds it.
+//   * 4x4 wavefronts, 2x2 tiles each: 256 x 256, 1024 threads, 144 KB of LDS, one workgroup per CU.
+//     Half the L2 traffic per flop: 1.1 PFLOP/s on large problems, and faster than the small tile
+//     whenever there are about 200 or more tiles.
+// Tiles of KB bytes of k per row are double-buffered in LDS; the next tile's global loads are in
+// flight while the current one feeds the matrix cores.
 #pragma once
 #include "common.h"
 
 namespace cmt {
 
-// KB = bytes of k per row and stage (128 or 64); LDS row pitch = KB + 16 (padding against bank conflicts)
-template <int TA, int TB, int KB = 128> struct GemmTile {
-  static constexpr int BM = 64 * TA, BN = 64 * TB;
+// KB = bytes of k per row and stage; LDS row pitch = KB + 16 (padding against bank conflicts)
+template <int WM, int WN, int TA, int TB, int KB = 128> struct GemmTile {
+  static constexpr int NT = 64 * WM * WN;                  // threads
+  static constexpr int BM = 32 * TA * WM, BN = 32 * TB * WN;
   static constexpr int ROWB = KB + 16;
   static constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int SMEM_BYTES = 2 * STAGE_BYTES;
 };
+using GemmSmall = GemmTile<2, 2, 2, 2, 128>;               // 128 x 128, 256 threads
+using GemmBig = GemmTile<4, 4, 2, 2, 128>;                 // 256 x 256, 1024 threads
 
-template <typename T, int ROWS, int KB>
+template <typename T, int NT, int ROWS, int KB>
 __device__ __forceinline__ void gemm_load_tile(const T* __restrict__ P, int ld, int rows, int K, int r0, int k0,
-                                               uint4 (&regs)[ROWS * KB / 4096]) {
+                                               uint4 (&regs)[ROWS * KB / 16 / NT]) {
   constexpr int EPC = 16 / sizeof(T);                     // elements per 16-byte chunk
   constexpr int CPR = KB / 16;                            // chunks per row
-  constexpr int RPP = 256 / CPR;                          // rows per pass
+  constexpr int RPP = NT / CPR;                           // rows per pass
   const int t = threadIdx.x;
   const int kc = k0 + (t % CPR) * EPC;
 #pragma unroll
@@ -36,24 +43,26 @@ __device__ __forceinline__ void gemm_load_tile(const T* __restrict__ P, int ld, 
     else regs[p] = make_uint4(0, 0, 0, 0);
   }
 }
-template <int ROWS, int KB>
-__device__ __forceinline__ void gemm_store_tile(char* tile, const uint4 (&regs)[ROWS * KB / 4096]) {
-  constexpr int CPR = KB / 16, RPP = 256 / CPR;
+template <int NT, int ROWS, int KB>
+__device__ __forceinline__ void gemm_store_tile(char* tile, const uint4 (&regs)[ROWS * KB / 16 / NT]) {
+  constexpr int CPR = KB / 16, RPP = NT / CPR;
   const int t = threadIdx.x;
 #pragma unroll
   for (int p = 0; p < ROWS / RPP; ++p)
     *reinterpret_cast<uint4*>(tile + ((t / CPR) + RPP * p) * (KB + 16) + (t % CPR) * 16) = regs[p];
 }
 
-// acc[a][b]: rows m0 + wm*32*TA + a*32 + acc32_row(lane,i), cols n0 + wn*32*TB + b*32 + lane%32
-template <typename T, int TA, int TB, int KB = 128>
+// With w = wavefront index, wm = w / WN, wn = w % WN:
+// acc[a][b]: rows m0 + (wm*TA + a)*32 + acc32_row(lane,i), cols n0 + (wn*TB + b)*32 + lane%32
+template <typename T, int WM, int WN, int TA, int TB, int KB>
 __device__ __forceinline__ void gemm_mainloop(const T* __restrict__ A, int lda, const T* __restrict__ B, int ldb,
                                               int M, int N, int K, int m0, int n0, v16f (&acc)[TA][TB], char* smem) {
-  using G = GemmTile<TA, TB, KB>;
+  using G = GemmTile<WM, WN, TA, TB, KB>;
+  constexpr int NT = G::NT;
   constexpr int BK = KB / sizeof(T);
   constexpr int GEMM_ROWB = G::ROWB;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int wm = w >> 1, wn = w & 1;
+  const int wm = w / WN, wn = w % WN;
 #pragma unroll
   for (int a = 0; a < TA; ++a)
 #pragma unroll
@@ -61,11 +70,11 @@ __device__ __forceinline__ void gemm_mainloop(const T* __restrict__ A, int lda, 
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-  uint4 ra[G::BM * KB / 4096], rb[G::BN * KB / 4096];
-  gemm_load_tile<T, G::BM, KB>(A, lda, M, K, m0, 0, ra);
-  gemm_load_tile<T, G::BN, KB>(B, ldb, N, K, n0, 0, rb);
-  gemm_store_tile<G::BM, KB>(smem, ra);
-  gemm_store_tile<G::BN, KB>(smem + G::A_BYTES, rb);
+  uint4 ra[G::BM * KB / 16 / NT], rb[G::BN * KB / 16 / NT];
+  gemm_load_tile<T, NT, G::BM, KB>(A, lda, M, K, m0, 0, ra);
+  gemm_load_tile<T, NT, G::BN, KB>(B, ldb, N, K, n0, 0, rb);
+  gemm_store_tile<NT, G::BM, KB>(smem, ra);
+  gemm_store_tile<NT, G::BN, KB>(smem + G::A_BYTES, rb);
   __syncthreads();
   const int nk = (K + BK - 1) / BK;
   for (int kt = 0; kt < nk; ++kt) {
@@ -73,8 +82,8 @@ __device__ __forceinline__ void gemm_mainloop(const T* __restrict__ A, int lda, 
     char* nxt = smem + ((kt + 1) & 1) * G::STAGE_BYTES;
     const bool more = kt + 1 < nk;
     if (more) {
-      gemm_load_tile<T, G::BM, KB>(A, lda, M, K, m0, (kt + 1) * BK, ra);
-      gemm_load_tile<T, G::BN, KB>(B, ldb, N, K, n0, (kt + 1) * BK, rb);
+      gemm_load_tile<T, NT, G::BM, KB>(A, lda, M, K, m0, (kt + 1) * BK, ra);
+      gemm_load_tile<T, NT, G::BN, KB>(B, ldb, N, K, n0, (kt + 1) * BK, rb);
     }
     const char* ta = cur + (wm * 32 * TA + (lane & 31)) * GEMM_ROWB + (lane >> 5) * 8 * sizeof(T);
     const char* tb = cur + G::A_BYTES + (wn * 32 * TB + (lane & 31)) * GEMM_ROWB + (lane >> 5) * 8 * sizeof(T);
@@ -91,8 +100,8 @@ __device__ __forceinline__ void gemm_mainloop(const T* __restrict__ A, int lda, 
         for (int b = 0; b < TB; ++b) mma32(acc[a][b], fa[a], fb[b]);
     }
     if (more) {
-      gemm_store_tile<G::BM, KB>(nxt, ra);
-      gemm_store_tile<G::BN, KB>(nxt + G::A_BYTES, rb);
+      gemm_store_tile<NT, G::BM, KB>(nxt, ra);
+      gemm_store_tile<NT, G::BN, KB>(nxt + G::A_BYTES, rb);
     }
     __syncthreads();
   }

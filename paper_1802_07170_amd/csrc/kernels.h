@@ -20,36 +20,27 @@ void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, in
 void launch_transpose(int prec, const void* in, int ldin, void* out, int ldout, int R, int C, hipStream_t st);
 
 // ---- ce.hip ------------------------------------------------------------------------------------
-// Eq. 1 forward, fused: logits tile by tile, never stored.  Ho [M,H] T, Wo [V,H] T, Bo [V] fp32,
-// labels [M] int32.  pmax/psum [M, np] fp32 with np = ce_num_partials(V); zy [M] fp32.
-int ce_num_partials(int V);
-void launch_ce_fwd(int prec, const void* Ho, int ldho, const void* Wo, const float* Bo, const int32_t* labels,
-                   int M, int V, int H, float* pmax, float* psum, float* zy, hipStream_t st);
-// lse[M], nll[M] (masked), rowscale[M] = mask / n_tok, loss = sum nll / n_tok; flags |= 4 if the loss
-// is not finite.  One launch, deterministic summation order.
-void launch_ce_reduce(const float* pmax, const float* psum, const float* zy, const float* mask, int M, int np,
-                      float* lse, float* nll, float* rowscale, float* loss, int* flags, hipStream_t st);
-// Eq. 1 backward, fused: dz = (softmax(z) - onehot) * rowscale is rebuilt per tile from lse and used
-// as a matrix-core operand straight from LDS.
-//   dHo_part [nsplit, M, H] fp32 partial sums over vocabulary ranges (ce_bwd_nsplit(M, V) of them)
-//   dWo [V,H] fp32, dBo [V] fp32 written in full.
-// WoT [H, V] and HoT [H, M] are the transposed operand copies.
-int ce_bwd_nsplit(int M, int V);
-void launch_ce_bwd_dh(int prec, const void* Ho, int ldho, const void* Wo, const void* WoT, const float* Bo,
-                      const int32_t* labels, const float* lse, const float* rowscale,
-                      int M, int V, int H, int nsplit, float* dHo_part, hipStream_t st);
-void launch_ce_bwd_dw(int prec, const void* Ho, int ldho, const void* HoT, int ldhot, const void* Wo, const float* Bo,
-                      const int32_t* labels, const float* lse, const float* rowscale,
-                      int M, int V, int H, float* dWo, float* dBo, hipStream_t st);
-
-// Slab variant of the backward: for at most CE_SLAB_ROWS rows the logits are rebuilt and
-// dz = (softmax(z) - onehot) * rowscale is staged as dz [Mc, V] and dzT [V, CE_SLAB_ROWS] (both T,
-// ce_slab_elems(V) elements each); the caller then takes dH_o[rows] = dz W_o and dW_o += dz^T H_o[rows]
-// with launch_gemm_nt and dB_o with launch_colsum.  Ho, labels, lse, rowscale point at the slab's first row.
+// Eq. 1 for a slab of M <= CE_SLAB_ROWS rows (all row pointers at the slab's first row).
+// Forward: Ho [M,H] T, Wo [V,H] T, Bo [V] fp32, labels [M] int32.  Per row and group of 64
+// vocabulary columns: pmax = max z, psum = sum exp(z - pmax) ([M, np] fp32, np = ce_num_partials(V));
+// zy [M] = the label's logit; E [M, V] T = exp(z - pmax of its group).
 constexpr int CE_SLAB_ROWS = 1024;
-size_t ce_slab_elems(int V);
-void launch_ce_dz(int prec, const void* Ho, int ldho, const void* Wo, const float* Bo, const int32_t* labels, const float* lse,
-                  const float* rowscale, int Mc, int V, int H, void* dz, void* dzT, hipStream_t st);
+int ce_num_partials(int V);
+size_t ce_slab_elems(int V);                                 // elements of a slab buffer (E / dz, and dzT)
+void launch_ce_fwd(int prec, const void* Ho, int ldho, const void* Wo, const float* Bo, const int32_t* labels,
+                   int M, int V, int H, void* E, float* pmax, float* psum, float* zy, hipStream_t st);
+// rowscale[M] = mask / n_tok and loss[1] = n_tok (needs only the masks; M = all rows of the batch).
+void launch_ce_rowscale(const float* mask, int M, float* rowscale, float* loss, hipStream_t st);
+// lse[M], nll[M] (masked) from the partials.
+void launch_ce_rows(const float* pmax, const float* psum, const float* zy, const float* mask, int M, int np, float* lse,
+                    float* nll, hipStream_t st);
+// loss[0] = sum nll / loss[1]; flags |= 4 if it is not finite.  One block, deterministic order.
+void launch_ce_loss(const float* nll, int M, float* loss, int* flags, hipStream_t st);
+// Backward: E -> dz = (E * exp(pmax - lse) - onehot) * rowscale in place ([Mc, V] T) and
+// dzT [V, CE_SLAB_ROWS] T (columns >= Mc up to the next multiple of 64 are zero-filled).  The caller
+// then takes dH_o[rows] = dz W_o and dW_o += dz^T H_o[rows] with launch_gemm_nt, dB_o with launch_colsum.
+void launch_ce_scale(int prec, void* E, int V, int Mc, const float* pmax, const float* lse, const int32_t* labels,
+                     const float* rowscale, void* dzT, hipStream_t st);
 
 // ---- step.hip ----------------------------------------------------------------------------------
 // A value delivered as `np` partial planes: v(b, c) = sum_k p[k * stride + b * ld + c]  (np = 0: zero).
