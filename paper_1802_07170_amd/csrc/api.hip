@@ -101,7 +101,7 @@ struct cmt_handle {
   float* dXt = nullptr; char* XtT = nullptr;
   float *pmax = nullptr, *psum = nullptr, *zy = nullptr, *lse = nullptr, *nll = nullptr, *rowscale = nullptr;
   float* loss = nullptr; int* flags = nullptr; float* colscr = nullptr;
-  char* dzs = nullptr; char* dzTs = nullptr; float* ce_colscr = nullptr; float* dbo_parts = nullptr;
+  char* dzs = nullptr; char* dzTs = nullptr; float* dbo_parts = nullptr;
   float* gsplit = nullptr; size_t gsplit_floats = 0;
   hipStream_t side = nullptr;           // library-owned second stream for work off the recurrences' critical path
   std::vector<hipEvent_t> ev; size_t ev_next = 0;
@@ -221,8 +221,7 @@ size_t layout(cmt_handle* h, char* base) {
   h->loss = (float*)a.take(256); h->flags = (int*)a.take(256);
   h->colscr = (float*)a.take((size_t)16 * 4 * H * 4);
   h->dzs = a.take(ce_slab_elems(c.tgt_vocab) * esz); h->dzTs = a.take(ce_slab_elems(c.tgt_vocab) * esz);
-  h->ce_colscr = (float*)a.take((size_t)16 * c.tgt_vocab * 4);
-  h->dbo_parts = (float*)a.take((Mt / CE_SLAB_ROWS + 1) * c.tgt_vocab * 4);
+  h->dbo_parts = (float*)a.take((Mt / 64 + Mt / 256 + 4) * c.tgt_vocab * 4);
   h->gsplit_floats = (size_t)8 * CE_SLAB_ROWS * 1024;
   h->gsplit = (float*)a.take(h->gsplit_floats * 4);
   h->gsplit2 = (float*)a.take(h->gsplit_floats * 4);
@@ -460,12 +459,15 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     // Slabs of <= CE_SLAB_ROWS rows, equal sizes, two slab buffer pairs.  Per slab the main stream
     // takes forward (logits -> e, partials), lse / nll, e -> dz and dz^T, and dH_o = dz W_o (the
     // decoder needs it); the second stream takes dW_o += dz^T H_o and dB_o.
-    const int nslab = (Mt + CE_SLAB_ROWS - 1) / CE_SLAB_ROWS;
-    const int rows = (((Mt + nslab - 1) / nslab) + 63) / 64 * 64;
+    // Equal slabs of whole 256-row tiles where possible, the remainder going to the last one.
+    int nslab = (Mt + CE_SLAB_ROWS - 1) / CE_SLAB_ROWS;
+    int rows = Mt / nslab / 256 * 256;
+    if (rows == 0) rows = (((Mt + nslab - 1) / nslab) + 63) / 64 * 64;
+    while (Mt - (nslab - 1) * rows > CE_SLAB_ROWS) ++nslab;
     std::vector<hipEvent_t> done(nslab, nullptr);
-    int sl = 0;
-    for (int m0 = 0; m0 < Mt; m0 += rows, ++sl) {
-      const int Mc = Mt - m0 < rows ? Mt - m0 : rows;
+    int sl = 0, n_dbo = 0;
+    for (int m0 = 0; m0 < Mt; ++sl) {
+      const int Mc = (sl == nslab - 1 || Mt - m0 < rows) ? Mt - m0 : rows;
       char* dz = (sl & 1) ? h->dzs2 : h->dzs;
       char* dzT = (sl & 1) ? h->dzTs2 : h->dzTs;
       if (sl >= 2 && sd != st) (void)hipStreamWaitEvent(st, done[sl - 2], 0);
@@ -473,19 +475,21 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
                     h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, h->zy + m0, st);
       launch_ce_rows(h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, h->zy + m0, h->mask_t + m0, Mc, np, h->lse + m0,
                      h->nll + m0, st);
-      launch_ce_scale(p, dz, V, Mc, h->pmax + (size_t)m0 * np, h->lse + m0, h->labels + m0, h->rowscale + m0, dzT, st);
+      launch_ce_scale(p, dz, V, Mc, h->pmax + (size_t)m0 * np, h->lse + m0, h->labels + m0, h->rowscale + m0, dzT,
+                      h->dbo_parts + (size_t)n_dbo * V, st);
+      n_dbo += (Mc + 63) / 64;
       stream_after(h, sd, st);
       launch_gemm_nt(p, dz, V, h->WoT, V, Mc, H, V, h->dHoCE + (size_t)m0 * H, nullptr, H, nullptr, 0, st, h->gsplit,
                      h->gsplit_floats);                                   // dH_o[slab] = dz W_o
       launch_gemm_nt(p, dzT, CE_SLAB_ROWS, HoT + (size_t)m0 * esz, ldHoT, V, H, Mc, G + h->off_Wo, nullptr, H, nullptr, sl > 0,
                      sd);                                                 // dW_o (+)= dz^T H_o[slab]
-      launch_colsum(p, dz, V, Mc, V, h->ce_colscr, h->dbo_parts + (size_t)sl * V, sd);
       if (sd != st) {
         done[sl] = h->ev[h->ev_next++ % h->ev.size()];
         (void)hipEventRecord(done[sl], sd);
       }
+      m0 += Mc;
     }
-    launch_sum_parts(h->dbo_parts, sl, (size_t)V, G + h->off_Bo, sd);
+    launch_sum_parts(h->dbo_parts, n_dbo, (size_t)V, G + h->off_Bo, st);
     launch_ce_loss(h->nll, Mt, h->loss, h->flags, st);
   }
 

@@ -161,14 +161,16 @@ void launch_ce_loss(const float* nll, int M, float* loss, int* flags, hipStream_
 }
 
 // ------------------------------------------------------------------------------------------------
-// e -> dz, in place, and dz^T.  One workgroup per 64 rows x 64 columns (= one group of partials):
+// e -> dz, in place, dz^T, and per block of 64 rows the column sums of dz (partial dB_o, summed by
+// the caller in a fixed order).  One workgroup per 64 rows x 64 columns (= one group of partials):
 // thread t takes row t / 4 and 16 consecutive columns; the transpose goes through LDS so that both
 // the dz rows and the dz^T rows leave as 16-byte stores.
 // ------------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void ce_scale_kernel(T* __restrict__ E, int V, int Mc, const float* __restrict__ pmax, int np,
                                                        const float* __restrict__ lse, const int32_t* __restrict__ labels,
-                                                       const float* __restrict__ rowscale, T* __restrict__ dzT, int ldzt) {
+                                                       const float* __restrict__ rowscale, T* __restrict__ dzT, int ldzt,
+                                                       float* __restrict__ dbo_part) {
   constexpr int VE = 16 / sizeof(T);                      // elements per 16-byte vector
   constexpr int NV = 16 / VE;                             // vectors per thread
   __shared__ __align__(16) T tile[64][64 + VE];
@@ -202,25 +204,33 @@ __global__ __launch_bounds__(256) void ce_scale_kernel(T* __restrict__ E, int V,
   __syncthreads();
   {
     const int c = t >> 2, col = c0 + c, rb = (t & 3) * 16;
+    float cs = 0.f;                                         // this block's share of dB_o[col]: 64 rows in fixed order
     if (col < V) {
 #pragma unroll
-      for (int v = 0; v < NV; ++v)                          // rows past Mc hold zeros; the slab is CE_SLAB_ROWS wide
-        *reinterpret_cast<uint4*>(dzT + (size_t)col * ldzt + r0 + rb + v * VE) =
-            *reinterpret_cast<const uint4*>(&tile[c][rb + v * VE]);
+      for (int v = 0; v < NV; ++v) {                        // rows past Mc hold zeros; the slab is CE_SLAB_ROWS wide
+        const uint4 x = *reinterpret_cast<const uint4*>(&tile[c][rb + v * VE]);
+        *reinterpret_cast<uint4*>(dzT + (size_t)col * ldzt + r0 + rb + v * VE) = x;
+        const T* xe = reinterpret_cast<const T*>(&x);
+#pragma unroll
+        for (int j = 0; j < VE; ++j) cs += to_f<T>(xe[j]);
+      }
     }
+    cs += __shfl_xor(cs, 1, 64);
+    cs += __shfl_xor(cs, 2, 64);
+    if ((t & 3) == 0 && col < V) dbo_part[(size_t)blockIdx.y * V + col] = cs;
   }
 }
 
 void launch_ce_scale(int prec, void* E, int V, int Mc, const float* pmax, const float* lse, const int32_t* labels,
-                     const float* rowscale, void* dzT, hipStream_t st) {
+                     const float* rowscale, void* dzT, float* dbo_part, hipStream_t st) {
   dim3 grid((V + 63) / 64, (Mc + 63) / 64);
   const int np = ce_num_partials(V);
   if (prec)
     hipLaunchKernelGGL(ce_scale_kernel<bf16_t>, grid, dim3(256), 0, st, (bf16_t*)E, V, Mc, pmax, np, lse, labels, rowscale,
-                       (bf16_t*)dzT, CE_SLAB_ROWS);
+                       (bf16_t*)dzT, CE_SLAB_ROWS, dbo_part);
   else
     hipLaunchKernelGGL(ce_scale_kernel<float>, grid, dim3(256), 0, st, (float*)E, V, Mc, pmax, np, lse, labels, rowscale,
-                       (float*)dzT, CE_SLAB_ROWS);
+                       (float*)dzT, CE_SLAB_ROWS, dbo_part);
 }
 
 }  // namespace cmt

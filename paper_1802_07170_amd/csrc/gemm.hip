@@ -16,8 +16,9 @@ static int env_int(const char* name, int dflt) {
 }
 static const int GEMM_BIG_MIN_TILES = env_int("CMT_GEMM_BIG_MIN_TILES", 192);
 static const int GEMM_SPLIT_BELOW = env_int("CMT_GEMM_SPLIT_BELOW", 128);
-static const int GEMM_SPLIT_TARGET = env_int("CMT_GEMM_SPLIT_TARGET", 256);
-static const int GEMM_SPLIT_MAX = env_int("CMT_GEMM_SPLIT_MAX", 8);
+static const int GEMM_SPLIT_TARGET = env_int("CMT_GEMM_SPLIT_TARGET", 512);
+static const int GEMM_SPLIT_MAX = env_int("CMT_GEMM_SPLIT_MAX", 16);
+
 
 // blockIdx.y = k split index: each split contracts kchunk elements of k and, when there is more
 // than one, writes its own fp32 plane Cf + split * plane_stride (summed afterwards, fixed order).

@@ -38,9 +38,10 @@ void launch_ce_rows(const float* pmax, const float* psum, const float* zy, const
 void launch_ce_loss(const float* nll, int M, float* loss, int* flags, hipStream_t st);
 // Backward: E -> dz = (E * exp(pmax - lse) - onehot) * rowscale in place ([Mc, V] T) and
 // dzT [V, CE_SLAB_ROWS] T (columns >= Mc up to the next multiple of 64 are zero-filled).  The caller
-// then takes dH_o[rows] = dz W_o and dW_o += dz^T H_o[rows] with launch_gemm_nt, dB_o with launch_colsum.
+// then takes dH_o[rows] = dz W_o and dW_o += dz^T H_o[rows] with launch_gemm_nt.  dbo_part
+// [ceil(Mc / 64), V] fp32: column sums of dz over each block of 64 rows (dB_o = their sum over all slabs).
 void launch_ce_scale(int prec, void* E, int V, int Mc, const float* pmax, const float* lse, const int32_t* labels,
-                     const float* rowscale, void* dzT, hipStream_t st);
+                     const float* rowscale, void* dzT, float* dbo_part, hipStream_t st);
 
 // ---- step.hip ----------------------------------------------------------------------------------
 // A value delivered as `np` partial planes: v(b, c) = sum_k p[k * stride + b * ld + c]  (np = 0: zero).
