@@ -286,7 +286,8 @@ void weight_grads(cmt_handle* h, LD& d, int Lsteps, const std::vector<std::pair<
   float* dW = h->grads + d.w_off;
   int col = 0;
   for (size_t i = 0; i < segs.size(); ++i) {
-    launch_gemm_nt(p, d.dGT, M, segs[i].first, segs[i].second, 4 * Hh, seg_k[i], M, dW + col, nullptr, d.Kin + Hh, nullptr, 0, st);
+    launch_gemm_nt(p, d.dGT, M, segs[i].first, segs[i].second, 4 * Hh, seg_k[i], M, dW + col, nullptr, d.Kin + Hh, nullptr, 0, st,
+                   h->gsplit2, h->gsplit_floats);
     col += seg_k[i];
   }
   launch_colsum(p, d.dG, d.pg, M, 4 * Hh, h->colscr, h->grads + d.b_off, st);

@@ -15,7 +15,7 @@ static int env_int(const char* name, int dflt) {
   return e && *e ? atoi(e) : dflt;
 }
 static const int GEMM_BIG_MIN_TILES = env_int("CMT_GEMM_BIG_MIN_TILES", 192);
-static const int GEMM_SPLIT_BELOW = env_int("CMT_GEMM_SPLIT_BELOW", 128);
+static const int GEMM_SPLIT_BELOW = env_int("CMT_GEMM_SPLIT_BELOW", 129);
 static const int GEMM_SPLIT_TARGET = env_int("CMT_GEMM_SPLIT_TARGET", 512);
 static const int GEMM_SPLIT_MAX = env_int("CMT_GEMM_SPLIT_MAX", 16);
 
