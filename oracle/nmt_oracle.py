@@ -22,6 +22,14 @@ The backward pass is written by hand from these definitions: a weight used at ev
 per-step gradients (the paper's calculateGradient accumulates with beta = 1), and a value with two
 consumers sums their gradients (the paper's DuplicateLayer).
 
+Regularisation of the Settings section / hyperparameter table (both off by default):
+  * dropout p on the hidden states passed from a recurrent layer to the layer above it (encoder and
+    decoder, every layer but the top one; the recurrent connection itself is not dropped) and on
+    the output H_o: a kept entry is scaled by 1/(1-p); the dropped H_o is what the output layer and
+    the next step's input feed see.  The masks come from a counter-based generator (dropout_mask);
+  * label smoothing eps: the target distribution of Eq. 1 becomes (1-eps) onehot(y) + eps/V, so a
+    token's loss is (1-eps) nll + eps (lse - mean_v z_v).
+
 Readings of points the paper leaves open: gate order i, f, g, o in the packed weight rows, one
 bias per gate, no peepholes, initial encoder state zero, no bias on W_a and W_c, padded source
 positions get attention weight exactly 0, a padded step leaves the LSTM state unchanged and emits
@@ -30,8 +38,10 @@ a zero output.
 Parity pins (tests/test_oracle_*.py): central finite differences on every parameter tensor,
 closed-form LSTM outputs for zero / bias-only / saturated gates, torch.nn.LSTM (fp64) on random
 inputs, torch.log_softmax, a torch-autograd restatement of the full model, padded-batch ==
-per-sentence brute force, attention rows summing to one, loss == log V for a zero output layer.
-No function here is unpinned.
+per-sentence brute force, attention rows summing to one, loss == log V for a zero output layer;
+dropout and label smoothing: finite differences with the masks held fixed, the same torch
+restatement with masks and torch's own label-smoothed cross-entropy, SplitMix64's published first
+outputs, keep rate and values of the masks.  No function here is unpinned.
 """
 from __future__ import annotations
 
@@ -198,21 +208,26 @@ def attention_backward(dHo, cache, Hs, W_a, W_c):
 # ----------------------------------------------------------------------------------------------
 # output layer (Eq. 1) for one decoder step, whole batch
 # ----------------------------------------------------------------------------------------------
-def output_forward(Ho, labels, W_o, B_o, logit_tanh=False):
-    """Returns lse [B], nll [B] (unmasked), cache."""
+def output_forward(Ho, labels, W_o, B_o, logit_tanh=False, label_smoothing=0.0):
+    """Returns lse [B], the per-row loss [B] (unmasked), cache.  The row loss is the cross-entropy
+    against the target distribution q = (1 - eps) onehot(label) + eps / V (eps = 0: plain nll)."""
     u = Ho @ W_o.T + B_o
     z = np.tanh(u) if logit_tanh else u
     zmax = z.max(axis=1, keepdims=True)
     lse = (zmax + np.log(np.exp(z - zmax).sum(axis=1, keepdims=True)))[:, 0]
     nll = lse - z[np.arange(z.shape[0]), labels]
-    return lse, nll, dict(z=z, lse=lse, labels=labels, Ho=Ho, logit_tanh=logit_tanh)
+    eps = label_smoothing
+    row = (1.0 - eps) * nll + eps * (lse - z.mean(axis=1))      # -sum_v q_v log p_v
+    return lse, row, dict(z=z, lse=lse, labels=labels, Ho=Ho, logit_tanh=logit_tanh, eps=eps)
 
 
 def output_backward(w, cache, W_o):
-    """w [B]: d loss / d nll per row (mask / N_tok).  Returns dHo, dW_o, dB_o."""
+    """w [B]: d loss / d (row loss) per row (mask / N_tok).  Returns dHo, dW_o, dB_o."""
     z, lse, labels, Ho = cache["z"], cache["lse"], cache["labels"], cache["Ho"]
-    dz = np.exp(z - lse[:, None])
-    dz[np.arange(z.shape[0]), labels] -= 1.0
+    eps = cache["eps"]
+    dz = np.exp(z - lse[:, None])                                # p - q
+    dz[np.arange(z.shape[0]), labels] -= 1.0 - eps
+    dz -= eps / z.shape[1]
     dz *= w[:, None]
     if cache["logit_tanh"]:
         dz = dz * (1.0 - z * z)
@@ -228,8 +243,35 @@ def make_masks(src_len, tgt_len, S, T):
     return src_mask, tgt_mask
 
 
+def splitmix64(x):
+    """The SplitMix64 output function on uint64 arrays: x + golden gamma, then the two
+    xor-shift-multiply rounds and the final xor-shift (the published generator's step)."""
+    with np.errstate(over="ignore"):
+        x = x + np.uint64(0x9E3779B97F4A7C15)
+        x = (x ^ (x >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+        x = (x ^ (x >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+        return x ^ (x >> np.uint64(31))
+
+
+DROPOUT_SITE_ENC, DROPOUT_SITE_DEC, DROPOUT_SITE_HO = 0, 16, 32   # + layer number for the first two
+
+
+def dropout_mask(seed, site, T, B, H, p):
+    """Keep-and-rescale factors [T,B,H] of one dropout site.  Element (t, b, h) is kept iff the top
+    24 bits of SplitMix64(seed + site * 2^48 + (t B + b) H + h) are >= floor(float32(p) * 2^24);
+    kept entries are 1 / (1 - p), dropped ones 0.  B is the real batch size, so the masks do not
+    depend on how a batch is padded."""
+    if p <= 0.0:
+        return np.ones((T, B, H), F64)
+    n = T * B * H
+    key = (np.arange(n, dtype=np.uint64) + np.uint64((int(seed) + (int(site) << 48)) & ((1 << 64) - 1)))
+    u = (splitmix64(key) >> np.uint64(40)).astype(np.int64)
+    thresh = int(np.floor(float(np.float32(p)) * 16777216.0))
+    return ((u >= thresh).astype(F64) / (1.0 - float(np.float32(p)))).reshape(T, B, H)
+
+
 def train_step(cfg, params, src_ids, src_len, tgt_ids, tgt_len, bos_id=2, logit_tanh=False,
-               want_intermediates=False):
+               want_intermediates=False, dropout=0.0, dropout_seed=0, label_smoothing=0.0):
     """One forward + backward pass.
 
     params: dict name -> float64 array (see param_shapes).  src_ids [B,S], tgt_ids [B,T] int;
@@ -259,8 +301,11 @@ def train_step(cfg, params, src_ids, src_len, tgt_ids, tgt_len, bos_id=2, logit_
     enc_Y = [np.concatenate([Yf, Yb], axis=2)]
     enc_fin = [(np.concatenate([hf, hb], axis=1), np.concatenate([cf, cb], axis=1))]
     enc_sv = [(sv_f, sv_b)]
+    D_enc = [dropout_mask(dropout_seed, DROPOUT_SITE_ENC + l, S, B, H, dropout) for l in range(L - 1)]
+    D_dec = [dropout_mask(dropout_seed, DROPOUT_SITE_DEC + l, T, B, H, dropout) for l in range(L - 1)]
+    D_ho = dropout_mask(dropout_seed, DROPOUT_SITE_HO, T, B, H, dropout)
     for l in range(1, L):
-        Y, h, c, sv = lstm_forward(enc_Y[-1], src_mask, p[f"enc.l{l}.W"], p[f"enc.l{l}.b"], z_h, z_h)
+        Y, h, c, sv = lstm_forward(enc_Y[-1] * D_enc[l - 1], src_mask, p[f"enc.l{l}.W"], p[f"enc.l{l}.b"], z_h, z_h)
         enc_Y.append(Y)
         enc_fin.append((h, c))
         enc_sv.append(sv)
@@ -280,14 +325,15 @@ def train_step(cfg, params, src_ids, src_len, tgt_ids, tgt_len, bos_id=2, logit_
         for l in range(L):
             _, h[l], c[l], cache = masked_step_forward(x, h[l], c[l], m, p[f"dec.l{l}.W"], p[f"dec.l{l}.b"])
             step_caches.append(cache)
-            x = h[l]
+            x = h[l] * D_dec[l][j] if l < L - 1 else h[l]
         Ho, acache = attention_forward(Hs, src_mask, h[L - 1], p["W_a"], p["W_c"])
-        lse, nll, ocache = output_forward(Ho, tgt_ids[:, j], p["W_o"], p["B_o"], logit_tanh)
+        Ho_d = Ho * D_ho[j]                          # what the output layer and the input feed see
+        lse, nll, ocache = output_forward(Ho_d, tgt_ids[:, j], p["W_o"], p["B_o"], logit_tanh, label_smoothing)
         nll_all[j], lse_all[j] = nll, lse
         dec_caches.append(step_caches)
         att_caches.append(acache)
         out_caches.append(ocache)
-        Ho_prev = Ho
+        Ho_prev = Ho_d
     loss = float((nll_all * tgt_mask).sum() / n_tok)
 
     # ---- backward ---------------------------------------------------------------------------
@@ -302,7 +348,7 @@ def train_step(cfg, params, src_ids, src_len, tgt_ids, tgt_len, bos_id=2, logit_
         dHo, dWo, dBo = output_backward(tgt_mask[j] / n_tok, out_caches[j], p["W_o"])
         g["W_o"] += dWo
         g["B_o"] += dBo
-        dHo += dHo_feed
+        dHo = (dHo + dHo_feed) * D_ho[j]
         dHt, dHs_j, dWa, dWc = attention_backward(dHo, att_caches[j], Hs, p["W_a"], p["W_c"])
         g["W_a"] += dWa
         g["W_c"] += dWc
@@ -313,7 +359,7 @@ def train_step(cfg, params, src_ids, src_len, tgt_ids, tgt_len, bos_id=2, logit_
                 np.zeros_like(dy), dh[l] + dy, dc[l], dec_caches[j][l], p[f"dec.l{l}.W"])
             g[f"dec.l{l}.W"] += dW
             g[f"dec.l{l}.b"] += db
-            dy = dx
+            dy = dx * D_dec[l - 1][j] if l > 0 else dx
         dXt[j] = dy[:, :E]
         dHo_feed = dy[:, E:]
     # (H_o^{<-1>} is the constant zero vector: the last dHo_feed is dropped.)
@@ -323,6 +369,7 @@ def train_step(cfg, params, src_ids, src_len, tgt_ids, tgt_len, bos_id=2, logit_
     dY = dHs
     for l in range(L - 1, 0, -1):
         dY, dW, db, _, _ = lstm_backward(dY, dh[l], dc[l], enc_sv[l], p[f"enc.l{l}.W"])
+        dY = dY * D_enc[l - 1]
         g[f"enc.l{l}.W"] += dW
         g[f"enc.l{l}.b"] += db
     sv_f, sv_b = enc_sv[0]
@@ -345,7 +392,8 @@ def train_step(cfg, params, src_ids, src_len, tgt_ids, tgt_len, bos_id=2, logit_
             att_a=np.stack([ac["a"] for ac in att_caches]),          # [T,B,S]
             att_cs=np.stack([ac["Cs"] for ac in att_caches]),        # [T,B,H]
             h_t=np.stack([ac["Ht"] for ac in att_caches]),           # [T,B,H]
-            h_o=np.stack([ac["Ho"] for ac in att_caches]),           # [T,B,H]
+            h_o=np.stack([ac["Ho"] for ac in att_caches]),           # [T,B,H], before dropout
+            h_o_drop=np.stack([ac["Ho"] for ac in att_caches]) * D_ho,
             lse=lse_all, nll=nll_all * tgt_mask,
             enc_y=enc_Y, enc_final=enc_fin,
         )
@@ -368,12 +416,7 @@ def init_params_counter(cfg, seed, scale):
     for name, shape in param_shapes(cfg):
         n = int(np.prod(shape))
         idx = (np.arange(n0, n0 + n, dtype=np.uint64) + np.uint64(seed & mask))
-        with np.errstate(over="ignore"):
-            x = idx + np.uint64(0x9E3779B97F4A7C15)
-            x = (x ^ (x >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
-            x = (x ^ (x >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
-            x = x ^ (x >> np.uint64(31))
-        u = (x >> np.uint64(40)).astype(np.float32)               # 24 bits, exact in float32
+        u = (splitmix64(idx) >> np.uint64(40)).astype(np.float32)  # 24 bits, exact in float32
         v = (u * np.float32(2.0 / 16777216.0) - np.float32(1.0)) * np.float32(scale)
         out[name] = v.astype(np.float32).reshape(shape)
         n0 += n

@@ -242,7 +242,9 @@ def test_output_layer_matches_torch_log_softmax():
 # second, independent derivation of the whole model: torch autograd, sentence by sentence,
 # unpadded, with torch's own LSTMCell for the recurrences
 # ---------------------------------------------------------------------------------------------
-def torch_restatement(cfg, p, src, sl, tgt, tl, bos=2):
+def torch_restatement(cfg, p, src, sl, tgt, tl, bos=2, masks=None, eps=0.0):
+    """masks: None, or dict with "enc"[l] [S,B,H], "dec"[l] [T,B,H], "ho" [T,B,H] keep-and-rescale
+    factors (given as data); eps: label smoothing, through torch's own cross_entropy."""
     H, L, E = cfg["hidden"], cfg["layers"], cfg["emb"]
     Hd = H // 2
     tp = {k: torch.tensor(np.asarray(v, np.float64), requires_grad=True) for k, v in p.items()}
@@ -277,7 +279,8 @@ def torch_restatement(cfg, p, src, sl, tgt, tl, bos=2):
             h, c = torch.zeros(H, dtype=torch.float64), torch.zeros(H, dtype=torch.float64)
             nxt = []
             for t in range(n):
-                h, c = cell(ys[t], h, c, tp[f"enc.l{l}.W"], tp[f"enc.l{l}.b"])
+                xin = ys[t] if masks is None else ys[t] * torch.tensor(masks["enc"][l - 1][t, b])
+                h, c = cell(xin, h, c, tp[f"enc.l{l}.W"], tp[f"enc.l{l}.b"])
                 nxt.append(h)
             ys = nxt
             fin.append((h, c))
@@ -290,11 +293,16 @@ def torch_restatement(cfg, p, src, sl, tgt, tl, bos=2):
             for l in range(L):
                 st[l] = cell(x, st[l][0], st[l][1], tp[f"dec.l{l}.W"], tp[f"dec.l{l}.b"])
                 x = st[l][0]
-            ht = x
+                if masks is not None and l < L - 1:
+                    x = x * torch.tensor(masks["dec"][l][j, b])
+            ht = st[L - 1][0]
             a = torch.softmax(Hs @ (tp["W_a"] @ ht), dim=0)
             ho = torch.tanh(tp["W_c"] @ torch.cat([a @ Hs, ht]))
-            lp = torch.log_softmax(tp["W_o"] @ ho + tp["B_o"], dim=0)
-            total = total - lp[int(tgt[b, j])]
+            if masks is not None:
+                ho = ho * torch.tensor(masks["ho"][j, b])
+            z = tp["W_o"] @ ho + tp["B_o"]
+            total = total + torch.nn.functional.cross_entropy(z[None], torch.tensor([int(tgt[b, j])]),
+                                                              label_smoothing=eps, reduction="sum")
             prev = int(tgt[b, j])
     loss = total / float(tl.sum())
     loss.backward()
@@ -311,6 +319,119 @@ def test_full_model_matches_torch_autograd_restatement(H, L):
     assert abs(loss - tloss) < 1e-12
     for k in g:
         np.testing.assert_allclose(g[k], tg[k], rtol=1e-9, atol=1e-13, err_msg=k)
+
+
+# ---------------------------------------------------------------------------------------------
+# dropout and label smoothing (Settings section, hyperparameter table)
+# ---------------------------------------------------------------------------------------------
+def test_splitmix64_published_outputs():
+    """The generator's step against the outputs its public reference implementation is quoted with
+    (state advanced by the golden gamma before each output)."""
+    gamma, m64 = 0x9E3779B97F4A7C15, (1 << 64) - 1
+    x = np.array([(1234567 + n * gamma) & m64 for n in range(5)], dtype=np.uint64)
+    assert [int(v) for v in O.splitmix64(x)] == [6457827717110365317, 3203168211198807973, 9817491932198370423,
+                                                  4593380528125082431, 16408922859458223821]
+    x = np.array([(n * gamma) & m64 for n in range(3)], dtype=np.uint64)
+    assert [int(v) for v in O.splitmix64(x)] == [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4, 0x06C45D188009454F]
+
+
+def test_dropout_mask_values_rate_and_indexing():
+    p = 0.2
+    m = O.dropout_mask(99, O.DROPOUT_SITE_HO, 40, 16, 64, p)
+    assert set(np.unique(m)) == {0.0, 1.0 / (1.0 - float(np.float32(p)))}
+    n = m.size
+    keep = (m > 0).mean()
+    assert abs(keep - 0.8) < 5 * math.sqrt(0.8 * 0.2 / n)            # binomial, 5 sigma
+    assert abs(m.mean() - 1.0) < 5 * math.sqrt(0.2 / 0.8 / n)        # rescaling keeps the mean
+    # one element, by hand: key = seed + site * 2^48 + (t B + b) H + h
+    t, b, h = 3, 5, 7
+    key = np.array([99 + (O.DROPOUT_SITE_HO << 48) + (t * 16 + b) * 64 + h], dtype=np.uint64)
+    u = int(O.splitmix64(key)[0]) >> 40
+    assert (m[t, b, h] > 0) == (u >= int(np.float32(p) * 16777216.0))
+    # a longer batch of the same width sees the same factors on the shared steps; sites and seeds differ
+    assert np.array_equal(O.dropout_mask(99, O.DROPOUT_SITE_HO, 50, 16, 64, p)[:40], m)
+    assert not np.array_equal(O.dropout_mask(99, O.DROPOUT_SITE_DEC, 40, 16, 64, p), m)
+    assert not np.array_equal(O.dropout_mask(100, O.DROPOUT_SITE_HO, 40, 16, 64, p), m)
+    assert np.all(O.dropout_mask(1, 0, 3, 2, 4, 0.0) == 1.0)
+
+
+def test_no_regularisation_is_the_plain_step():
+    cfg = tiny_cfg(H=6, L=2)
+    p = rand_params(cfg, seed=5)
+    batch = tiny_batch(cfg)
+    a = O.train_step(cfg, p, *batch)
+    b = O.train_step(cfg, p, *batch, dropout=0.0, dropout_seed=77, label_smoothing=0.0)
+    assert a[0] == b[0] and all(np.array_equal(a[1][k], b[1][k]) for k in a[1])
+    c = O.train_step(cfg, p, *batch, dropout=0.3, dropout_seed=77)
+    assert c[0] != a[0]
+
+
+@pytest.mark.parametrize("H,L", [(4, 1), (6, 2), (4, 3)])
+def test_finite_differences_with_dropout_and_label_smoothing(H, L):
+    """The masks are constants of the step, so central differences apply unchanged."""
+    cfg = tiny_cfg(H=H, L=L)
+    p = rand_params(cfg, seed=20 + H + L)
+    batch = tiny_batch(cfg, seed=2)
+    kw = dict(dropout=0.3, dropout_seed=4242, label_smoothing=0.1)
+    loss, g, _ = O.train_step(cfg, p, *batch, **kw)
+    rng = np.random.default_rng(2)
+    eps = 1e-5
+    for name, shape in O.param_shapes(cfg):
+        n = int(np.prod(shape))
+        idxs = range(n) if n <= 30 else rng.choice(n, size=30, replace=False)
+        for k in idxs:
+            idx = np.unravel_index(k, shape)
+            old = p[name][idx]
+            p[name][idx] = old + eps
+            lp = O.train_step(cfg, p, *batch, **kw)[0]
+            p[name][idx] = old - eps
+            lm = O.train_step(cfg, p, *batch, **kw)[0]
+            p[name][idx] = old
+            fd = (lp - lm) / (2 * eps)
+            assert abs(fd - g[name][idx]) <= 1e-6 * max(1.0, abs(fd)) + 1e-9, (name, idx, fd, g[name][idx])
+
+
+@pytest.mark.parametrize("H,L", [(4, 1), (8, 3)])
+def test_regularised_model_matches_torch_autograd_restatement(H, L):
+    """Second derivation with the masks handed over as data and torch's own label-smoothed
+    cross-entropy: pins where the masks enter (which tensors, which consumers) and the smoothed loss."""
+    cfg = tiny_cfg(H=H, E=5, V=13, L=L)
+    p = rand_params(cfg, seed=31)
+    src, sl, tgt, tl = tiny_batch(cfg, seed=4)
+    B, S = src.shape
+    T = tgt.shape[1]
+    pd, seed, eps = 0.25, 2024, 0.1
+    masks = dict(enc=[O.dropout_mask(seed, O.DROPOUT_SITE_ENC + l, S, B, H, pd) for l in range(L - 1)],
+                 dec=[O.dropout_mask(seed, O.DROPOUT_SITE_DEC + l, T, B, H, pd) for l in range(L - 1)],
+                 ho=O.dropout_mask(seed, O.DROPOUT_SITE_HO, T, B, H, pd))
+    loss, g, it = O.train_step(cfg, p, src, sl, tgt, tl, dropout=pd, dropout_seed=seed, label_smoothing=eps,
+                               want_intermediates=True)
+    tloss, tg = torch_restatement(cfg, p, src, sl, tgt, tl, masks=masks, eps=eps)
+    assert abs(loss - tloss) < 1e-12
+    for k in g:
+        np.testing.assert_allclose(g[k], tg[k], rtol=1e-9, atol=1e-13, err_msg=k)
+    np.testing.assert_array_equal(it["h_o_drop"], it["h_o"] * masks["ho"])
+
+
+def test_label_smoothed_output_layer_matches_torch_and_closed_forms():
+    rng = np.random.default_rng(8)
+    B, H, V, eps = 5, 7, 19, 0.1
+    Ho = rng.normal(size=(B, H)); Wo = rng.normal(size=(V, H)); Bo = rng.normal(size=V)
+    y = rng.integers(0, V, size=B)
+    lse, row, cache = O.output_forward(Ho, y, Wo, Bo, label_smoothing=eps)
+    z = torch.tensor(Ho @ Wo.T + Bo)
+    ref = torch.nn.functional.cross_entropy(z, torch.tensor(y), label_smoothing=eps, reduction="none").numpy()
+    np.testing.assert_allclose(row, ref, rtol=1e-13)
+    # the definition written out: -sum_v q_v log p_v
+    logp = (z - torch.logsumexp(z, 1, keepdim=True)).numpy()
+    q = np.full((B, V), eps / V); q[np.arange(B), y] += 1 - eps
+    np.testing.assert_allclose(row, -(q * logp).sum(1), rtol=1e-13)
+    # gradient rows sum to zero (p and q both sum to one)
+    dHo, dWo, dBo = O.output_backward(np.ones(B), cache, Wo)
+    assert abs(dBo.sum()) < 1e-12
+    # a zero output layer predicts the uniform distribution: loss = log V whatever eps is
+    _, row0, _ = O.output_forward(Ho, y, np.zeros((V, H)), np.zeros(V), label_smoothing=eps)
+    np.testing.assert_allclose(row0, math.log(V), rtol=1e-14)
 
 
 def test_intermediates_are_consistent():
