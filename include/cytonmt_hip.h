@@ -104,14 +104,28 @@ int cmt_fetch_loss(cmt_handle* h, float* loss_host);
 
 int cmt_get_grads(cmt_handle* h, float* host_dst);
 
+/* Regularisation of the training step (Settings section; hyperparameter table: dropout 0.2, label
+ * smoothing 0.1).  Both are off (0) after cmt_create; the values set here apply to every later step.
+ *   dropout p in [0, 1): the hidden states a recurrent layer hands to the layer above it (encoder
+ *     and decoder, all layers but the top one) and the output H_o (as seen by the output layer and
+ *     by the next step's input feed) are multiplied by keep / (1 - p).  Element (t, b, h) of dropout
+ *     site s is kept iff the top 24 bits of SplitMix64(dropout_seed + s * 2^48 + (t * B + b) * H + h)
+ *     are >= floor(p * 2^24); s = l for the encoder layer l output, 16 + l for the decoder layer l
+ *     output, 32 for H_o; B is the step's batch size, H = hidden.  Nothing is stored: forward and
+ *     backward recompute the decision.  The caller changes dropout_seed from step to step.
+ *   label_smoothing eps in [0, 1): the target distribution of Eq. 1 becomes
+ *     (1 - eps) onehot(y) + eps / V; the loss returned is the cross-entropy against it.
+ * Returns CMT_EINVAL for values outside those ranges (the previous setting is kept). */
+int cmt_set_regularization(cmt_handle* h, float dropout, float label_smoothing, uint64_t dropout_seed);
+
 /* Plain SGD (hyperparameter table: optimizer SGD, learning rate 1.0): p <- p - lr * g on the flat
  * fp32 master vector, then refreshes the kernels' working copies (bf16 casts, transposes). */
 int cmt_sgd_update(cmt_handle* h, float lr);
 
 /* Copies a named intermediate of the last step to host memory as fp32, for per-kernel parity
  * tests.  Names: "x_src" [S,Bp,E], "x_tgt" [T,Bp,E], "mask_src" [S,Bp], "mask_tgt" [T,Bp],
- * "h_s" [S,Bp,H], "h_t" [T,Bp,H], "att_a" [T,Bp,S], "att_cs" [T,Bp,H], "h_o" [T,Bp,H],
- * "lse" [T,Bp], "nll" [T,Bp]; Bp = B rounded up to a multiple of 16 (extra rows are padding).
+ * "h_s" [S,Bp,H], "h_t" [T,Bp,H], "att_a" [T,Bp,S], "att_cs" [T,Bp,H], "h_o" [T,Bp,H] (before
+ * dropout), "h_o_drop" [T,Bp,H] (after), "lse" [T,Bp], "nll" [T,Bp] (the per-token loss); Bp = B rounded up to a multiple of 16 (extra rows are padding).
  * bytes must equal the tensor's size; values at masked positions are unspecified except for
  * the masks, "att_a" (exactly 0 on padded source positions) and "nll" (0 on padded targets). */
 int cmt_debug_fetch(cmt_handle* h, const char* name, float* host_dst, size_t bytes);

@@ -17,7 +17,7 @@ EXPORTS = [
     "cmt_query_sizes", "cmt_create", "cmt_destroy", "cmt_param_count", "cmt_param_info",
     "cmt_init_params", "cmt_set_params", "cmt_get_params", "cmt_train_step", "cmt_train_step_async",
     "cmt_fetch_loss", "cmt_get_grads", "cmt_sgd_update", "cmt_debug_fetch", "cmt_padded_batch",
-    "cmt_time_kernel", "cmt_last_error",
+    "cmt_time_kernel", "cmt_last_error", "cmt_set_regularization",
 ]
 
 
@@ -63,6 +63,7 @@ def load_library():
     lib.cmt_fetch_loss.argtypes = [vp, C.POINTER(C.c_float)]
     lib.cmt_get_grads.argtypes = [vp, vp]
     lib.cmt_sgd_update.argtypes = [vp, C.c_float]
+    lib.cmt_set_regularization.argtypes = [vp, C.c_float, C.c_float, C.c_uint64]
     lib.cmt_debug_fetch.argtypes = [vp, C.c_char_p, vp, sz]
     lib.cmt_padded_batch.argtypes = [vp]
     lib.cmt_time_kernel.argtypes = [vp, C.c_char_p, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_double)]
@@ -180,6 +181,10 @@ class Trainer:
 
     def sgd_update(self, lr):
         self._check(self.lib.cmt_sgd_update(self.h, lr))
+
+    def set_regularization(self, dropout=0.0, label_smoothing=0.0, dropout_seed=0):
+        """Dropout and label smoothing of the following steps (both 0 = off)."""
+        self._check(self.lib.cmt_set_regularization(self.h, dropout, label_smoothing, dropout_seed))
 
     def time_kernel(self, name, iters):
         """(microseconds per launch, algorithmic bytes per launch) of one kernel of the last step."""

@@ -41,6 +41,8 @@ struct LD {
   char* dG = nullptr;                // T [Lmax, Bp, 4Hh]
   char* dGT = nullptr;               // T [4Hh, Lmax*Bp]
   char* HstT = nullptr;              // T [Hh, (Lmax+1)*Bp]
+  char* Yd = nullptr;                // T [Lmax, Bp, Hh] the layer's output after dropout (row pitch ph) ...
+  char* YdT = nullptr;               // ... and its transpose [Hh, L*Bp]; used only while dropout is on
   float* dh = nullptr; float* dc = nullptr;   // [Bp, Hh]
   float* part = nullptr;             // [8][Bp][4Hh] forward partial planes (k split over workgroups)
   float* bwdp = nullptr;             // [8][Bp][2Hh] backward step-GEMM planes
@@ -108,6 +110,11 @@ struct cmt_handle {
   int use_side = 1;
   char* dzs2 = nullptr; char* dzTs2 = nullptr; float* gsplit2 = nullptr;
   int kb_bwd = 0, kb_wc = 0;            // caps on the k blocks of the backward step GEMMs (0 = default)
+  // regularisation of the next steps (cmt_set_regularization)
+  float drop_p = 0.f, drop_scale = 1.f, ls_eps = 0.f;
+  unsigned drop_thresh = 0; unsigned long long drop_seed = 0;
+  char* HoDrop = nullptr;               // H_o after dropout: what the output layer and the input feed read
+  float* psz = nullptr;                 // per-group sums of logits (label smoothing)
   size_t ws_bytes = 0;
 
   const char* Pw(size_t off) const { return Pc + off * esz; }
@@ -182,6 +189,8 @@ size_t layout(cmt_handle* h, char* base) {
     d.dc = (float*)a.take((size_t)Bp * Hh * 4);
     d.part = (float*)a.take((size_t)8 * Bp * 4 * Hh * 4);
     d.bwdp = (float*)a.take((size_t)8 * Bp * 2 * Hh * 4);
+    d.Yd = a.take(M * d.ph * esz);                 // the layer's output after dropout, and its transpose
+    d.YdT = a.take(M * Hh * esz);
   };
   h->enc.assign(L + 1, LD());
   h->dec.assign(L, LD());
@@ -205,6 +214,7 @@ size_t layout(cmt_handle* h, char* base) {
   h->mask_t = (float*)a.take(Mt * 4); h->tok_t = (int32_t*)a.take(Mt * 4); h->labels = (int32_t*)a.take(Mt * 4);
   h->len_t = (int32_t*)a.take((size_t)Bp * 4);
   h->HoBuf = a.take((Mt + Bp) * PH * esz); h->HoBufT = a.take((Mt + Bp) * H * esz);
+  h->HoDrop = a.take((Mt + Bp) * PH * esz);
   h->Cs = a.take(Mt * PH * esz); h->CsT = a.take(Mt * H * esz);
   h->att_a = (float*)a.take(Mt * Sm * 4); h->att_ds = (float*)a.take(Mt * Sm * 4);
   h->dCs = (float*)a.take(Mt * H * 4);
@@ -215,7 +225,7 @@ size_t layout(cmt_handle* h, char* base) {
   h->wcp = (float*)a.take((size_t)8 * Bp * 2 * H * 4);
   h->dXt = (float*)a.take(Mt * E * 4);
   const int np = ce_num_partials(c.tgt_vocab);
-  h->pmax = (float*)a.take(Mt * np * 4); h->psum = (float*)a.take(Mt * np * 4);
+  h->pmax = (float*)a.take(Mt * np * 4); h->psum = (float*)a.take(Mt * np * 4); h->psz = (float*)a.take(Mt * np * 4);
   h->zy = (float*)a.take(Mt * 4); h->lse = (float*)a.take(Mt * 4); h->nll = (float*)a.take(Mt * 4);
   h->rowscale = (float*)a.take(Mt * 4);
   h->loss = (float*)a.take(256); h->flags = (int*)a.take(256);
@@ -293,6 +303,19 @@ void weight_grads(cmt_handle* h, LD& d, int Lsteps, const std::vector<std::pair<
   launch_colsum(p, d.dG, d.pg, M, 4 * Hh, h->colscr, h->grads + d.b_off, st);
 }
 
+// dropout sites (the oracle and the tests use the same numbering): encoder layer l output, decoder
+// layer l output, H_o
+constexpr int DROP_SITE_ENC = 0, DROP_SITE_DEC = 16, DROP_SITE_HO = 32;
+DropSpec drop_spec(const cmt_handle* h, int site, int t) {
+  DropSpec d;
+  if (h->drop_p > 0.f) {
+    const unsigned long long H = (unsigned long long)h->cfg.hidden;
+    d.on = 1; d.thresh = h->drop_thresh; d.scale = h->drop_scale; d.width = h->cfg.hidden;
+    d.key0 = h->drop_seed + ((unsigned long long)site << 48) + (unsigned long long)t * (unsigned long long)h->B * H;
+  }
+  return d;
+}
+
 // forward step j of decoder layer l (layer 0 takes [H_o^{<j-1>}; h] per step, its embedding part is pre-batched)
 void dec_lstm_fwd(cmt_handle* h, int l, int j) {
   const cmt_config& c = h->cfg;
@@ -300,17 +323,22 @@ void dec_lstm_fwd(cmt_handle* h, int l, int j) {
   const size_t esz = h->esz, BH = (size_t)Bp * H, BP = (size_t)Bp * h->PH;
   LD& e = h->dec[l];
   LstmFwdDir d;
+  const bool drop = h->drop_p > 0.f;
   if (l == 0) {
-    d.x = h->HoBuf + j * BP * esz; d.ldx = h->PH; d.Kx = H; d.wx_off = E; d.wh_off = E + H;
+    d.x = (drop ? h->HoDrop : h->HoBuf) + j * BP * esz; d.ldx = h->PH; d.Kx = H; d.wx_off = E; d.wh_off = E + H;
     d.gx = e.Gx + (size_t)j * Bp * 4 * H; d.ldgx = 4 * H; d.bias = nullptr; d.ldw = E + 2 * H;
   } else {
-    d.x = h->dec[l - 1].Hst + (j + 1) * BP * esz; d.ldx = e.ph; d.Kx = H; d.wx_off = 0; d.wh_off = H;
+    d.x = drop ? h->dec[l - 1].Yd + j * BP * esz : h->dec[l - 1].Hst + (j + 1) * BP * esz;
+    d.ldx = e.ph; d.Kx = H; d.wx_off = 0; d.wh_off = H;
     d.gx = nullptr; d.ldgx = 0; d.bias = h->params + e.b_off; d.ldw = 2 * H;
   }
   d.hprev = e.Hst + j * BP * esz; d.ldh = e.ph; d.W = e.W;
   d.cprev = e.Cst + j * BH; d.mask = h->mask_t + (size_t)j * Bp;
   d.hnext = e.Hst + (j + 1) * BP * esz; d.ldhn = e.ph; d.cnext = e.Cst + (j + 1) * BH;
   d.gsave = e.Gs + (size_t)j * Bp * 4 * H; d.ycat = nullptr; d.ldy = 0; d.part = e.part;
+  if (drop && l + 1 < c.layers) {                  // what the layer above reads
+    d.ycat = e.Yd + j * BP * esz; d.ldy = e.ph; d.drop = drop_spec(h, DROP_SITE_DEC + l, j); d.drop_col0 = 0;
+  }
   launch_lstm_fwd(h->prec, &d, 1, Bp, H, h->st);
 }
 
@@ -328,6 +356,8 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   const int Ms = S * Bp, Mt = T * Bp;
   const size_t BH = (size_t)Bp * H;
   const int PH = h->PH;                            // row pitch of the H-wide per-step operands
+  const bool drop = h->drop_p > 0.f;
+  char* HoFeed = drop ? h->HoDrop : h->HoBuf;      // H_o as its consumers (output layer, input feed) see it
   const size_t BP = (size_t)Bp * PH;
   float* G = h->grads;
   float* P = h->params;
@@ -362,6 +392,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       d[i].hnext = e.Hst + sn * BPd * esz; d[i].ldhn = e.ph; d[i].cnext = e.Cst + sn * BHd;
       d[i].gsave = e.Gs + (size_t)t * Bp * 4 * Hd;
       d[i].ycat = h->Y0 + ((size_t)t * BH + (i ? Hd : 0)) * esz; d[i].ldy = H; d[i].part = e.part;
+      if (L > 1) { d[i].drop = drop_spec(h, DROP_SITE_ENC + 0, t); d[i].drop_col0 = i ? Hd : 0; }
     }
     launch_lstm_fwd(p, d, 2, Bp, Hd, st);
   }
@@ -387,13 +418,17 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
         if (l == 1) {
           d.x = nullptr; d.ldx = 0; d.Kx = 0; d.gx = e.Gx + (size_t)t * Bp * 4 * H; d.ldgx = 4 * H; d.bias = nullptr;
         } else {
-          d.x = h->enc[l].Hst + (t + 1) * BP * esz; d.ldx = PH; d.Kx = H; d.gx = nullptr; d.ldgx = 0; d.bias = P + e.b_off;
+          d.x = drop ? h->enc[l].Yd + t * BP * esz : h->enc[l].Hst + (t + 1) * BP * esz;
+          d.ldx = PH; d.Kx = H; d.gx = nullptr; d.ldgx = 0; d.bias = P + e.b_off;
         }
         d.hprev = e.Hst + t * BP * esz; d.ldh = e.ph;
         d.W = e.W; d.ldw = 2 * H; d.wx_off = 0; d.wh_off = H;
         d.cprev = e.Cst + t * BH; d.mask = h->mask_s + (size_t)t * Bp;
         d.hnext = e.Hst + (t + 1) * BP * esz; d.ldhn = e.ph; d.cnext = e.Cst + (t + 1) * BH;
         d.gsave = e.Gs + (size_t)t * Bp * 4 * H; d.ycat = nullptr; d.ldy = 0; d.part = e.part;
+        if (drop && l + 1 < L) {
+          d.ycat = e.Yd + t * BP * esz; d.ldy = e.ph; d.drop = drop_spec(h, DROP_SITE_ENC + l, t); d.drop_col0 = 0;
+        }
       }
       launch_lstm_fwd(p, dirs, n, Bp, H, st);
     }
@@ -422,6 +457,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     LD& d0 = h->dec[0];
     launch_gemm_nt(p, h->Xt, E, d0.W, E + 2 * H, Mt, 4 * H, E, d0.Gx, nullptr, 4 * H, P + d0.b_off, 0, st);
     launch_fill_T(p, h->HoBuf, BP, st);
+    if (drop) launch_fill_T(p, h->HoDrop, BP, st);
     for (int j = 0; j < T; ++j) {
       for (int l = 0; l < L; ++l) dec_lstm_fwd(h, l, j);
       const char* Ht = h->dec[L - 1].Hst + (j + 1) * BP * esz;
@@ -432,6 +468,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       g.a1 = Ht; g.lda1 = PH; g.K1 = H; g.w1_off = H;
       g.W = h->Pw(h->off_Wc); g.ldw = 2 * H; g.N = H; g.mode = 0;
       g.outT = h->HoBuf + (j + 1) * BP * esz; g.ldo = PH;
+      if (drop) { g.outD = h->HoDrop + (j + 1) * BP * esz; g.ldod = PH; g.drop = drop_spec(h, DROP_SITE_HO, j); }
       g.out = h->wcp; g.ldout = H; g.plane_stride = BH;
       launch_step_gemm(p, g, Bp, st);
     }
@@ -440,7 +477,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   // The recurrences' backward loops are chains of short dependent kernels that leave most of the
   // chip idle; everything that does not feed them (transposes, weight gradients, dW_o, embedding
   // scatters) runs on the library's second stream and joins at the end of the step.
-  const char* Ho = h->HoBuf + BP * esz;            // [T*Bp, H], row pitch PH
+  const char* Ho = HoFeed + BP * esz;              // [T*Bp, H], row pitch PH
   const int np = ce_num_partials(V);
   hipStream_t sd = h->use_side ? h->side : st;
   const int ldHoT = Mt + Bp;
@@ -449,9 +486,13 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     launch_transpose(p, d.Hst, d.ph, d.HstT, (Lsteps + 1) * Bp, (Lsteps + 1) * Bp, d.Hh, sd);
   };
   stream_after(h, sd, st);
-  launch_transpose(p, h->HoBuf, PH, h->HoBufT, ldHoT, Mt + Bp, H, sd);
+  launch_transpose(p, HoFeed, PH, h->HoBufT, ldHoT, Mt + Bp, H, sd);
   for (auto& d : h->enc) transpose_states(d, S);
   for (auto& d : h->dec) transpose_states(d, T);
+  if (drop) {                                      // inputs of the layers above, as they saw them
+    for (int l = 1; l + 1 < L; ++l) launch_transpose(p, h->enc[l + 1].Yd, PH, h->enc[l + 1].YdT, Ms, Ms, H, sd);
+    for (int l = 0; l + 1 < L; ++l) launch_transpose(p, h->dec[l].Yd, PH, h->dec[l].YdT, Mt, Mt, H, sd);
+  }
   launch_transpose(p, h->Y0, H, h->Y0T, Ms, Ms, H, sd);
   launch_transpose(p, h->Xs, E, h->XsT, Ms, Ms, E, sd);
   launch_transpose(p, h->Xt, E, h->XtT, Mt, Mt, E, sd);
@@ -466,6 +507,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     if (rows == 0) rows = (((Mt + nslab - 1) / nslab) + 63) / 64 * 64;
     while (Mt - (nslab - 1) * rows > CE_SLAB_ROWS) ++nslab;
     std::vector<hipEvent_t> done(nslab, nullptr);
+    const float eps = h->ls_eps;
     int sl = 0, n_dbo = 0;
     for (int m0 = 0; m0 < Mt; ++sl) {
       const int Mc = (sl == nslab - 1 || Mt - m0 < rows) ? Mt - m0 : rows;
@@ -473,10 +515,11 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       char* dzT = (sl & 1) ? h->dzTs2 : h->dzTs;
       if (sl >= 2 && sd != st) (void)hipStreamWaitEvent(st, done[sl - 2], 0);
       launch_ce_fwd(p, Ho + (size_t)m0 * PH * esz, PH, h->Pw(h->off_Wo), P + h->off_Bo, h->labels + m0, Mc, V, H, dz,
-                    h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, h->zy + m0, st);
-      launch_ce_rows(h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, h->zy + m0, h->mask_t + m0, Mc, np, h->lse + m0,
-                     h->nll + m0, st);
-      launch_ce_scale(p, dz, V, Mc, h->pmax + (size_t)m0 * np, h->lse + m0, h->labels + m0, h->rowscale + m0, dzT,
+                    h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, eps > 0.f ? h->psz + (size_t)m0 * np : nullptr,
+                    h->zy + m0, st);
+      launch_ce_rows(h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, h->psz + (size_t)m0 * np, h->zy + m0,
+                     h->mask_t + m0, Mc, np, eps, V, h->lse + m0, h->nll + m0, st);
+      launch_ce_scale(p, dz, V, Mc, h->pmax + (size_t)m0 * np, h->lse + m0, h->labels + m0, h->rowscale + m0, eps, dzT,
                       h->dbo_parts + (size_t)n_dbo * V, st);
       n_dbo += (Mc + 63) / 64;
       stream_after(h, sd, st);
@@ -503,7 +546,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     const bool last = j == T - 1;
     // dH_o = cross-entropy part + what step j+1's bottom layer sent back through the input feed
     launch_tanh_bwd(p, h->dHoCE + j * BH, Planes{h->dec[0].bwdp, 2 * H, last ? 0 : kbd, pstr}, h->HoBuf + (j + 1) * BP * esz,
-                    PH, dpre, PH, Bp, H, st);
+                    PH, dpre, PH, Bp, H, drop_spec(h, DROP_SITE_HO, j), st);
     const int kbw = step_kblocks(p, 2 * H, H, Bp, h->kb_wc);
     {   // [dC_s ; dH_t] = dpre W_c, as planes
       StepGemm g{};
@@ -518,8 +561,8 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       LD& e = h->dec[l];
       LstmBwdPoint q;
       if (l == L - 1) q.dy = Planes{h->dHt, H, 1, 0};
-      else q.dy = Planes{h->dec[l + 1].bwdp, 2 * H, kbd, pstr};      // dx of the layer above, columns [0, H)
-      q.dy_col = 0;
+      else { q.dy = Planes{h->dec[l + 1].bwdp, 2 * H, kbd, pstr}; q.drop_dy = drop_spec(h, DROP_SITE_DEC + l, j); }
+      q.dy_col = 0;                                                   // dx of the layer above, columns [0, H)
       q.dhrec = Planes{e.bwdp, 2 * H, last ? 0 : kbd, pstr}; q.dhrec_col = H;
       q.dh = e.dh; q.dc = e.dc;
       q.gsave = e.Gs + (size_t)j * Bp * 4 * H;
@@ -545,6 +588,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   // encoder layer outputs, transposed: layer 0 -> Y0T (ld Ms); layer l >= 1 -> HstT + Bp (ld (S+1)Bp)
   auto encYT = [&](int l, int* ld) -> const char* {
     if (l == 0) { *ld = Ms; return h->Y0T; }
+    if (drop && l + 1 < L) { *ld = Ms; return h->enc[l + 1].YdT; }
     *ld = (S + 1) * Bp; return h->enc[l + 1].HstT + (size_t)Bp * esz;
   };
   // dW_c = dpre^T [C_s ; H_t]
@@ -556,7 +600,9 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     if (l == 0)
       weight_grads(h, e, T, {{h->XtT, Mt}, {h->HoBufT, ldHoT}, {e.HstT, (T + 1) * Bp}}, {E, H, H}, sd);
     else
-      weight_grads(h, e, T, {{h->dec[l - 1].HstT + (size_t)Bp * esz, (T + 1) * Bp}, {e.HstT, (T + 1) * Bp}}, {H, H}, sd);
+      weight_grads(h, e, T, {drop ? std::pair<const char*, int>{h->dec[l - 1].YdT, Mt}
+                                  : std::pair<const char*, int>{h->dec[l - 1].HstT + (size_t)Bp * esz, (T + 1) * Bp},
+                             {e.HstT, (T + 1) * Bp}}, {H, H}, sd);
   }
   launch_gemm_nt(p, h->dec[0].dG, h->dec[0].pg, h->dec[0].Wt, 4 * H, Mt, E, 4 * H, h->dXt, nullptr, E, nullptr, 0, sd);
   launch_embed_scatter(h->dXt, h->tok_t, Mt, c.tgt_vocab, E, G + h->off_Etgt, sd);
@@ -590,8 +636,8 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
         LD& e = h->enc[l + 1];
         LstmBwdPoint& q = pts[n++];
         if (l == L - 1) q.dy = Planes{h->dHs + (size_t)t * Bp * H, H, 1, 0};
-        else q.dy = Planes{h->enc[l + 2].bwdp, 2 * H, kbE, pstrE};          // dx of the layer above (its columns [0, H))
-        q.dy_col = 0;
+        else { q.dy = Planes{h->enc[l + 2].bwdp, 2 * H, kbE, pstrE}; q.drop_dy = drop_spec(h, DROP_SITE_ENC + l, t); }
+        q.dy_col = 0;                                                       // dx of the layer above (its columns [0, H))
         q.dhrec = Planes{e.bwdp, 2 * H, k == 0 ? 0 : kbE, pstrE};
         q.dhrec_col = (l == 1) ? 0 : H;                                     // layer 1 only computes the recurrent part
         // gradient of the final state = gradient of the decoder's initial state of the same depth
@@ -636,6 +682,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
         const int slot_prev = i ? t + 1 : t, slot_next = i ? t : t + 1;
         LstmBwdPoint& q = pts[i];
         q.dy = Planes{dY0 + (size_t)t * Bp * H, H, 1, 0}; q.dy_col = i ? Hd : 0;
+        if (L > 1) q.drop_dy = drop_spec(h, DROP_SITE_ENC + 0, t);
         q.dhrec = Planes{e.bwdp, Hd, k == 0 ? 0 : kb0, pstr0}; q.dhrec_col = 0;
         q.dh = e.dh; q.dc = e.dc;
         q.gsave = e.Gs + (size_t)t * Bp * 4 * Hd;
@@ -810,6 +857,18 @@ int cmt_sgd_update(cmt_handle* h, float lr) {
   return CMT_OK;
 }
 
+int cmt_set_regularization(cmt_handle* h, float dropout, float label_smoothing, uint64_t dropout_seed) {
+  if (!h) return CMT_EINVAL;
+  if (!(dropout >= 0.f) || !(dropout < 1.f)) return fail(h, CMT_EINVAL, "dropout must be in [0, 1)");
+  if (!(label_smoothing >= 0.f) || !(label_smoothing < 1.f)) return fail(h, CMT_EINVAL, "label_smoothing must be in [0, 1)");
+  h->drop_p = dropout;
+  h->drop_thresh = (unsigned)floor((double)dropout * 16777216.0);
+  h->drop_scale = (float)(1.0 / (1.0 - (double)dropout));
+  h->drop_seed = dropout_seed;
+  h->ls_eps = label_smoothing;
+  return CMT_OK;
+}
+
 int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_launch, double* algo_bytes) {
   if (!h || !name || iters < 1 || !us_per_launch || !algo_bytes) return fail(h, CMT_EINVAL, "bad argument");
   if (!h->have_step) return fail(h, CMT_EINVAL, "no step has been run");
@@ -864,6 +923,9 @@ int cmt_debug_fetch(cmt_handle* h, const char* name, float* host_dst, size_t byt
   else if (s == "att_a") { src = h->att_a; rows = 1; cols = pitch = T * Bp * S; }
   else if (s == "att_cs") { src = h->Cs; rows = T * Bp; cols = H; pitch = h->PH; isT = true; }
   else if (s == "h_o") { src = h->HoBuf + BP * h->esz; rows = T * Bp; cols = H; pitch = h->PH; isT = true; }
+  else if (s == "h_o_drop") {
+    src = (h->drop_p > 0.f ? h->HoDrop : h->HoBuf) + BP * h->esz; rows = T * Bp; cols = H; pitch = h->PH; isT = true;
+  }
   else if (s == "lse") { src = h->lse; rows = 1; cols = pitch = T * Bp; }
   else if (s == "nll") { src = h->nll; rows = 1; cols = pitch = T * Bp; }
   else return fail(h, CMT_EINVAL, "unknown intermediate name");

@@ -6,7 +6,8 @@
 //                   itself is stored in the operand type (a multiplicative quantity, so bf16 keeps
 //                   its relative precision whatever the logit's magnitude);
 //   ce_row_kernel : row log-sum-exp from the partials, masked negative log-likelihood;
-//   ce_scale_kernel: dz = (e * exp(m - lse) - onehot) * mask / n_tok, elementwise, in place, plus
+//   ce_scale_kernel: dz = (e * exp(m - lse) - q) * mask / n_tok with q the target distribution
+//                   (onehot, or smoothed: (1 - eps) onehot + eps / V), elementwise, in place, plus
 //                   its transpose (through LDS), so that dH_o = dz W_o and dW_o += dz^T H_o are
 //                   plain k-contiguous GEMMs.
 #include "gemm_core.h"
@@ -22,7 +23,8 @@ template <typename T>
 __global__ __launch_bounds__(CeG::NT) void ce_fwd_kernel(const T* __restrict__ Ho, int ldho, const T* __restrict__ Wo,
                                                          const float* __restrict__ Bo, const int32_t* __restrict__ labels,
                                                          int M, int V, int H, T* __restrict__ E, float* __restrict__ pmax,
-                                                         float* __restrict__ psum, float* __restrict__ zy, int np, int ntn) {
+                                                         float* __restrict__ psum, float* __restrict__ psz,
+                                                         float* __restrict__ zy, int np, int ntn) {
   __shared__ __align__(16) char smem[CeG::SMEM_BYTES];
   const int per = gridDim.x >> 3;
   const int id = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
@@ -56,40 +58,48 @@ __global__ __launch_bounds__(CeG::NT) void ce_fwd_kernel(const T* __restrict__ H
       }
 #pragma unroll
       for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-      float e = 0.f;
+      float e = 0.f, sz = 0.f;
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
         const float eb = mx > -INFINITY ? expf(z[b] - mx) : 0.f;          // exp(-inf) = 0 for columns past V
         e += eb;
+        if (col[b] < V) sz += z[b];
         if (row < M && col[b] < V) E[(size_t)row * V + col[b]] = from_f<T>(eb);
       }
 #pragma unroll
       for (int o = 16; o > 0; o >>= 1) e += __shfl_xor(e, o, 64);
+      if (psz) {                                            // label smoothing needs the mean logit of the row
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) sz += __shfl_xor(sz, o, 64);
+      }
       if ((lane & 31) == 0 && row < M) {
         pmax[(size_t)row * np + pidx] = mx;
         psum[(size_t)row * np + pidx] = e;
+        if (psz) psz[(size_t)row * np + pidx] = sz;
       }
     }
   }
 }
 
 void launch_ce_fwd(int prec, const void* Ho, int ldho, const void* Wo, const float* Bo, const int32_t* labels,
-                   int M, int V, int H, void* E, float* pmax, float* psum, float* zy, hipStream_t st) {
+                   int M, int V, int H, void* E, float* pmax, float* psum, float* psz, float* zy, hipStream_t st) {
   const int ntm = (M + CeG::BM - 1) / CeG::BM, ntn = (V + CeG::BN - 1) / CeG::BN;
   const int grid = ((ntm * ntn + 7) / 8) * 8;
   const int np = ce_num_partials(V);
   if (prec)
     hipLaunchKernelGGL(ce_fwd_kernel<bf16_t>, dim3(grid), dim3(CeG::NT), 0, st, (const bf16_t*)Ho, ldho, (const bf16_t*)Wo, Bo,
-                       labels, M, V, H, (bf16_t*)E, pmax, psum, zy, np, ntn);
+                       labels, M, V, H, (bf16_t*)E, pmax, psum, psz, zy, np, ntn);
   else
     hipLaunchKernelGGL(ce_fwd_kernel<float>, dim3(grid), dim3(CeG::NT), 0, st, (const float*)Ho, ldho, (const float*)Wo, Bo,
-                       labels, M, V, H, (float*)E, pmax, psum, zy, np, ntn);
+                       labels, M, V, H, (float*)E, pmax, psum, psz, zy, np, ntn);
 }
 
-// one wavefront per row: combine the partials
+// one wavefront per row: combine the partials.  Row loss against the smoothed target distribution
+// (1 - eps) onehot(y) + eps / V:  (1 - eps) (lse - z_y) + eps (lse - mean_v z_v); eps = 0: plain nll.
 __global__ __launch_bounds__(256) void ce_row_kernel(const float* __restrict__ pmax, const float* __restrict__ psum,
-                                                     const float* __restrict__ zy, const float* __restrict__ mask,
-                                                     int M, int np, float* __restrict__ lse, float* __restrict__ nll) {
+                                                     const float* __restrict__ psz, const float* __restrict__ zy,
+                                                     const float* __restrict__ mask, int M, int np, float eps, int V,
+                                                     float* __restrict__ lse, float* __restrict__ nll) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (row >= M) return;
   float mx = -INFINITY;
@@ -101,10 +111,17 @@ __global__ __launch_bounds__(256) void ce_row_kernel(const float* __restrict__ p
     if (pm > -INFINITY) s += psum[(size_t)row * np + p] * expf(pm - mx);
   }
   s = wave_sum(s);
+  float sz = 0.f;
+  if (eps > 0.f) {
+    for (int p = lane; p < np; p += 64) sz += psz[(size_t)row * np + p];
+    sz = wave_sum(sz);
+  }
   if (lane == 0) {
     const float l = mx + logf(s);
     lse[row] = l;
-    nll[row] = mask[row] > 0.f ? l - zy[row] : 0.f;
+    float r = l - zy[row];
+    if (eps > 0.f) r = (1.f - eps) * r + eps * (l - sz / (float)V);
+    nll[row] = mask[row] > 0.f ? r : 0.f;
   }
 }
 
@@ -152,9 +169,9 @@ __global__ __launch_bounds__(1024) void ce_loss_kernel(const float* __restrict__
 void launch_ce_rowscale(const float* mask, int M, float* rowscale, float* loss, hipStream_t st) {
   hipLaunchKernelGGL(ce_rowscale_kernel, dim3(1), dim3(1024), 0, st, mask, M, rowscale, loss);
 }
-void launch_ce_rows(const float* pmax, const float* psum, const float* zy, const float* mask, int M, int np, float* lse,
-                    float* nll, hipStream_t st) {
-  hipLaunchKernelGGL(ce_row_kernel, dim3((M + 3) / 4), dim3(256), 0, st, pmax, psum, zy, mask, M, np, lse, nll);
+void launch_ce_rows(const float* pmax, const float* psum, const float* psz, const float* zy, const float* mask, int M, int np,
+                    float eps, int V, float* lse, float* nll, hipStream_t st) {
+  hipLaunchKernelGGL(ce_row_kernel, dim3((M + 3) / 4), dim3(256), 0, st, pmax, psum, psz, zy, mask, M, np, eps, V, lse, nll);
 }
 void launch_ce_loss(const float* nll, int M, float* loss, int* flags, hipStream_t st) {
   hipLaunchKernelGGL(ce_loss_kernel, dim3(1), dim3(1024), 0, st, nll, M, loss, flags);
@@ -169,8 +186,8 @@ void launch_ce_loss(const float* nll, int M, float* loss, int* flags, hipStream_
 template <typename T>
 __global__ __launch_bounds__(256) void ce_scale_kernel(T* __restrict__ E, int V, int Mc, const float* __restrict__ pmax, int np,
                                                        const float* __restrict__ lse, const int32_t* __restrict__ labels,
-                                                       const float* __restrict__ rowscale, T* __restrict__ dzT, int ldzt,
-                                                       float* __restrict__ dbo_part) {
+                                                       const float* __restrict__ rowscale, float eps, T* __restrict__ dzT,
+                                                       int ldzt, float* __restrict__ dbo_part) {
   constexpr int VE = 16 / sizeof(T);                      // elements per 16-byte vector
   constexpr int NV = 16 / VE;                             // vectors per thread
   __shared__ __align__(16) T tile[64][64 + VE];
@@ -179,6 +196,7 @@ __global__ __launch_bounds__(256) void ce_scale_kernel(T* __restrict__ E, int V,
   {
     const int r = t >> 2, row = r0 + r, cb = (t & 3) * 16;
     float f = 0.f, rs = 0.f;
+    const float epsv = eps / (float)V;                      // target distribution (1 - eps) onehot + eps / V
     int y = -1;
     if (row < Mc) {
       const float pm = pmax[(size_t)row * np + blockIdx.x];
@@ -194,7 +212,7 @@ __global__ __launch_bounds__(256) void ce_scale_kernel(T* __restrict__ E, int V,
       else *reinterpret_cast<uint4*>(x) = make_uint4(0, 0, 0, 0);
 #pragma unroll
       for (int j = 0; j < VE; ++j) {
-        const float d = row < Mc && col < V ? (to_f<T>(x[j]) * f - (y == col + j ? 1.f : 0.f)) * rs : 0.f;
+        const float d = row < Mc && col < V ? (to_f<T>(x[j]) * f - (y == col + j ? 1.f - eps : 0.f) - epsv) * rs : 0.f;
         x[j] = from_f<T>(d);
         tile[cb + v * VE + j][r] = x[j];
       }
@@ -222,15 +240,15 @@ __global__ __launch_bounds__(256) void ce_scale_kernel(T* __restrict__ E, int V,
 }
 
 void launch_ce_scale(int prec, void* E, int V, int Mc, const float* pmax, const float* lse, const int32_t* labels,
-                     const float* rowscale, void* dzT, float* dbo_part, hipStream_t st) {
+                     const float* rowscale, float eps, void* dzT, float* dbo_part, hipStream_t st) {
   dim3 grid((V + 63) / 64, (Mc + 63) / 64);
   const int np = ce_num_partials(V);
   if (prec)
     hipLaunchKernelGGL(ce_scale_kernel<bf16_t>, grid, dim3(256), 0, st, (bf16_t*)E, V, Mc, pmax, np, lse, labels, rowscale,
-                       (bf16_t*)dzT, CE_SLAB_ROWS, dbo_part);
+                       eps, (bf16_t*)dzT, CE_SLAB_ROWS, dbo_part);
   else
     hipLaunchKernelGGL(ce_scale_kernel<float>, grid, dim3(256), 0, st, (float*)E, V, Mc, pmax, np, lse, labels, rowscale,
-                       (float*)dzT, CE_SLAB_ROWS, dbo_part);
+                       eps, (float*)dzT, CE_SLAB_ROWS, dbo_part);
 }
 
 }  // namespace cmt

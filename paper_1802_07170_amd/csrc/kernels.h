@@ -23,25 +23,27 @@ void launch_transpose(int prec, const void* in, int ldin, void* out, int ldout, 
 // Eq. 1 for a slab of M <= CE_SLAB_ROWS rows (all row pointers at the slab's first row).
 // Forward: Ho [M,H] T, Wo [V,H] T, Bo [V] fp32, labels [M] int32.  Per row and group of 64
 // vocabulary columns: pmax = max z, psum = sum exp(z - pmax) ([M, np] fp32, np = ce_num_partials(V));
-// zy [M] = the label's logit; E [M, V] T = exp(z - pmax of its group).
+// zy [M] = the label's logit; E [M, V] T = exp(z - pmax of its group); psz [M, np] = sum of z over
+// the group (null unless label smoothing needs the row's mean logit).
 constexpr int CE_SLAB_ROWS = 1024;
 int ce_num_partials(int V);
 size_t ce_slab_elems(int V);                                 // elements of a slab buffer (E / dz, and dzT)
 void launch_ce_fwd(int prec, const void* Ho, int ldho, const void* Wo, const float* Bo, const int32_t* labels,
-                   int M, int V, int H, void* E, float* pmax, float* psum, float* zy, hipStream_t st);
+                   int M, int V, int H, void* E, float* pmax, float* psum, float* psz, float* zy, hipStream_t st);
 // rowscale[M] = mask / n_tok and loss[1] = n_tok (needs only the masks; M = all rows of the batch).
 void launch_ce_rowscale(const float* mask, int M, float* rowscale, float* loss, hipStream_t st);
-// lse[M], nll[M] (masked) from the partials.
-void launch_ce_rows(const float* pmax, const float* psum, const float* zy, const float* mask, int M, int np, float* lse,
-                    float* nll, hipStream_t st);
+// lse[M] and the masked row loss nll[M] = (1 - eps) (lse - zy) + eps (lse - mean_v z_v) from the partials
+// (label smoothing eps of the hyperparameter table; eps = 0: plain negative log-likelihood).
+void launch_ce_rows(const float* pmax, const float* psum, const float* psz, const float* zy, const float* mask, int M, int np,
+                    float eps, int V, float* lse, float* nll, hipStream_t st);
 // loss[0] = sum nll / loss[1]; flags |= 4 if it is not finite.  One block, deterministic order.
 void launch_ce_loss(const float* nll, int M, float* loss, int* flags, hipStream_t st);
-// Backward: E -> dz = (E * exp(pmax - lse) - onehot) * rowscale in place ([Mc, V] T) and
+// Backward: E -> dz = (E * exp(pmax - lse) - (1 - eps) onehot - eps / V) * rowscale in place ([Mc, V] T) and
 // dzT [V, CE_SLAB_ROWS] T (columns >= Mc up to the next multiple of 64 are zero-filled).  The caller
 // then takes dH_o[rows] = dz W_o and dW_o += dz^T H_o[rows] with launch_gemm_nt.  dbo_part
 // [ceil(Mc / 64), V] fp32: column sums of dz over each block of 64 rows (dB_o = their sum over all slabs).
 void launch_ce_scale(int prec, void* E, int V, int Mc, const float* pmax, const float* lse, const int32_t* labels,
-                     const float* rowscale, void* dzT, float* dbo_part, hipStream_t st);
+                     const float* rowscale, float eps, void* dzT, float* dbo_part, hipStream_t st);
 
 // ---- step.hip ----------------------------------------------------------------------------------
 // A value delivered as `np` partial planes: v(b, c) = sum_k p[k * stride + b * ld + c]  (np = 0: zero).
@@ -52,6 +54,13 @@ struct Planes { const float* p; int ld; int np; size_t stride; };
 // Number of k-blocks (= planes written) by launch_step_gemm for N output columns, contraction
 // length K and padded batch Bp (at most 8).
 int step_kblocks(int prec, int N, int K, int Bp, int max_kb = 0);
+
+// Dropout of one [Bp, width] slice of a dropout site (Settings section: dropout on the hidden states
+// between recurrent layers and on H_o).  Element (b, col) keeps its value, scaled by `scale`
+// = 1 / (1 - p), iff the top 24 bits of SplitMix64(key0 + b * width + col) are >= thresh
+// = floor(p * 2^24); key0 = seed + site * 2^48 + t * B * width with B the real batch size.
+// on = 0: identity.
+struct DropSpec { unsigned long long key0 = 0; unsigned thresh = 0; float scale = 1.f; int width = 0; int on = 0; };
 
 // One recurrent step of one LSTM layer (or of both directions of the bottom encoder layer when
 // ndir = 2): gates = Gx + [x; h_prev] W^T, then the cell, fused.
@@ -65,7 +74,9 @@ struct LstmFwdDir {
   const float* mask;                    // [Bp] 1 = valid step
   void* hnext; int ldhn; float* cnext;  // next state (T*, row pitch ldhn); cell state [Bp, Hh]
   float* gsave;                         // [Bp, 4Hh] gate activations kept for the backward pass
-  void* ycat; int ldy;                  // optional second copy of h (T*, row pitch ldy), or null
+  void* ycat; int ldy;                  // optional second copy of h (T*, row pitch ldy), or null:
+  DropSpec drop{}; int drop_col0 = 0;   //   the layer's output as the layer above sees it, i.e. after
+                                        //   dropout (columns drop_col0 + [0, Hh) of the site)
   float* part;                          // [8][Bp][4Hh] scratch planes, used when the k range is split
 };
 // ndir <= STEP_MAX_INST instances of equal hidden width Hh in one launch.
@@ -83,6 +94,8 @@ struct StepGemm {
                        // 1: partial planes out[kb][b][n] (fp32, row pitch ldout, plane pitch plane_stride),
                        //    kb < step_kblocks(prec, K0 + K1); the consumer sums them
   void* outT; int ldo;
+  void* outD = nullptr; int ldod = 0;  // mode 0: optional copy of outT after dropout `drop`
+  DropSpec drop{};
   float* out; int ldout; size_t plane_stride;
   int max_kb;          // cap on the number of k blocks (planes); 0 = default (8)
 };
@@ -95,6 +108,7 @@ void launch_step_gemm_multi(int prec, const StepGemm* gs, int n, int n_plan, int
 // Cell backward for one step of one layer: builds dgates (T*) from the incoming state gradients.
 struct LstmBwdPoint {
   Planes dy; int dy_col;               // gradient arriving at this step's output: columns dy_col + [0, Hh)
+  DropSpec drop_dy{};                  // dropout between this layer and its consumer (same columns)
   Planes dhrec; int dhrec_col;         // recurrent part of d state from the next step's GEMM
   float* dh;                           // [Bp,Hh] in: pass-through part of d state; out: (1-m) * total
   float* dc;                           // [Bp,Hh] in/out cell-state gradient
@@ -124,9 +138,10 @@ void launch_att_bwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds
 // After the decoder loop: dHs_ctx[i,b,:] = sum_j a[j,b,i] dCs[j,b,:], dK[i,b,:] = sum_j ds[j,b,i] Ht[j,b,:].
 void launch_att_deferred(int prec, const float* a, const float* ds, const float* dCs, int lddc, const void* Ht, int ldht,
                          int S, int T, int Bp, int H, float* dHs, void* dK, hipStream_t st);
-// dpre = (dHo_ce + feed) * (1 - Ho^2) -> T*
+// dpre = (dHo_ce + feed) * drop * (1 - Ho^2) -> T*   (Ho: before dropout; drop: the factors H_o's
+// consumers saw)
 void launch_tanh_bwd(int prec, const float* dHo_ce, const Planes& feed, const void* Ho, int ldho, void* dpre, int ldp,
-                     int Bp, int H, hipStream_t st);
+                     int Bp, int H, const DropSpec& drop, hipStream_t st);
 
 // ---- misc.hip ----------------------------------------------------------------------------------
 // Embedding gather + masks + input validation (flags |= 1 bad id, |= 2 bad length).

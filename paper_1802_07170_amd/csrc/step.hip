@@ -100,6 +100,17 @@ __device__ __forceinline__ v4f step_tile_sum(const float* red, int rt, int bt) {
   return r;
 }
 
+// keep-and-rescale factor of element (b, col) of a dropout slice (see DropSpec)
+__device__ __forceinline__ float drop_factor(const DropSpec& d, int b, int col) {
+  if (!d.on) return 1.f;
+  unsigned long long x = d.key0 + (unsigned long long)b * (unsigned long long)d.width + (unsigned long long)col;
+  x += 0x9E3779B97F4A7C15ull;
+  x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+  x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+  x ^= x >> 31;
+  return (unsigned)(x >> 40) >= d.thresh ? d.scale : 0.f;
+}
+
 __device__ __forceinline__ float planes_get(const Planes& p, int b, int c) {
   float v = 0.f;
   for (int k = 0; k < p.np; ++k) v += p.p[(size_t)k * p.stride + (size_t)b * p.ld + c];
@@ -133,14 +144,14 @@ __device__ __forceinline__ void cell_finish(const LstmFwdDir& d, int b, int u, i
   d.cnext[(size_t)b * Hh + u] = valid ? cn : in.cp;
   float* gs = d.gsave + (size_t)b * 4 * Hh + u;
   gs[0] = ig; gs[Hh] = fg; gs[2 * Hh] = gg; gs[3 * Hh] = og;
+  const float hv = valid ? hn : in.hp;
+  const float yv = d.ycat ? hv * drop_factor(d.drop, b, d.drop_col0 + u) : 0.f;
   if (is_bf16) {
-    const bf16_t ho = f2bf(valid ? hn : in.hp);          // a carried state is already a bf16 value: exact
-    ((bf16_t*)d.hnext)[(size_t)b * d.ldhn + u] = ho;
-    if (d.ycat) ((bf16_t*)d.ycat)[(size_t)b * d.ldy + u] = ho;
+    ((bf16_t*)d.hnext)[(size_t)b * d.ldhn + u] = f2bf(hv);   // a carried state is already a bf16 value: exact
+    if (d.ycat) ((bf16_t*)d.ycat)[(size_t)b * d.ldy + u] = f2bf(yv);
   } else {
-    const float ho = valid ? hn : in.hp;
-    ((float*)d.hnext)[(size_t)b * d.ldhn + u] = ho;
-    if (d.ycat) ((float*)d.ycat)[(size_t)b * d.ldy + u] = ho;
+    ((float*)d.hnext)[(size_t)b * d.ldhn + u] = hv;
+    if (d.ycat) ((float*)d.ycat)[(size_t)b * d.ldy + u] = yv;
   }
 }
 
@@ -368,7 +379,11 @@ __global__ __launch_bounds__(256) void step2d_kernel(StepGemmArgs args, int Bp, 
     if (g.mode == 0 && sg.kb == 1) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        if (n + i < g.N) ((T*)g.outT)[(size_t)b * g.ldo + n + i] = from_f<T>(tanhf(r[i]));
+        if (n + i < g.N) {
+          const float hv = tanhf(r[i]);
+          ((T*)g.outT)[(size_t)b * g.ldo + n + i] = from_f<T>(hv);
+          if (g.outD) ((T*)g.outD)[(size_t)b * g.ldod + n + i] = from_f<T>(hv * drop_factor(g.drop, b, n + i));
+        }
     } else {
       float* o = g.out + (size_t)kb * g.plane_stride + (size_t)b * g.ldout + n;
       if (n + 3 < g.N && (g.ldout & 3) == 0) *reinterpret_cast<v4f*>(o) = r;
@@ -381,7 +396,8 @@ __global__ __launch_bounds__(256) void step2d_kernel(StepGemmArgs args, int Bp, 
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void tanh_planes_kernel(Planes p, T* __restrict__ out, int ldo, int Bp, int N);
+__global__ __launch_bounds__(256) void tanh_planes_kernel(Planes p, T* __restrict__ out, int ldo, T* __restrict__ outD, int ldod,
+                                                          DropSpec drop, int Bp, int N);
 
 // n instances in one launch (blockIdx.y); they share the contraction length and the k-block plan,
 // which is the plan of the widest instance.
@@ -418,8 +434,10 @@ void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st) {
   if (g.mode == 0 && pl.kb > 1) {
     Planes p{g.out, g.ldout, pl.kb, g.plane_stride};
     const int n = Bp * (g.N >> 2);
-    if (prec) hipLaunchKernelGGL(tanh_planes_kernel<bf16_t>, dim3((n + 255) / 256), dim3(256), 0, st, p, (bf16_t*)g.outT, g.ldo, Bp, g.N);
-    else hipLaunchKernelGGL(tanh_planes_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, st, p, (float*)g.outT, g.ldo, Bp, g.N);
+    if (prec) hipLaunchKernelGGL(tanh_planes_kernel<bf16_t>, dim3((n + 255) / 256), dim3(256), 0, st, p, (bf16_t*)g.outT, g.ldo,
+                                 (bf16_t*)g.outD, g.ldod, g.drop, Bp, g.N);
+    else hipLaunchKernelGGL(tanh_planes_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, st, p, (float*)g.outT, g.ldo,
+                            (float*)g.outD, g.ldod, g.drop, Bp, g.N);
   }
 }
 
@@ -486,7 +504,7 @@ __global__ __launch_bounds__(256) void lstm_bwd_point_kernel(LstmBwdPointArgs ar
     const float ig = (&i4.x)[e], fg = (&f4.x)[e], gg = (&g4.x)[e], og = (&o4.x)[e];
     const float cp = (&cp4.x)[e], cn = (&cn4.x)[e];
     const float tc = tanhf(cn);
-    const float dh = dh_state[e] + (&dy4.x)[e];
+    const float dh = dh_state[e] + (&dy4.x)[e] * drop_factor(p.drop_dy, b, p.dy_col + u + e);
     const float dog = dh * tc;
     const float dc = (&dc4.x)[e] + dh * og * (1.f - tc * tc);
     di[e] = dc * gg * ig * (1.f - ig);
@@ -719,7 +737,8 @@ void launch_att_deferred(int prec, const float* a, const float* ds, const float*
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void tanh_planes_kernel(Planes p, T* __restrict__ out, int ldo, int Bp, int N) {
+__global__ __launch_bounds__(256) void tanh_planes_kernel(Planes p, T* __restrict__ out, int ldo, T* __restrict__ outD, int ldod,
+                                                          DropSpec drop, int Bp, int N) {
   const int i4 = blockIdx.x * 256 + threadIdx.x;
   const int nq = N >> 2;
   if (i4 >= Bp * nq) return;
@@ -727,14 +746,19 @@ __global__ __launch_bounds__(256) void tanh_planes_kernel(Planes p, T* __restric
   const float4 v = planes_get4(p, b, n);
   const float o[4] = {tanhf(v.x), tanhf(v.y), tanhf(v.z), tanhf(v.w)};
   store4<T>(out + (size_t)b * ldo + n, o);
+  if (outD) {
+    const float od[4] = {o[0] * drop_factor(drop, b, n), o[1] * drop_factor(drop, b, n + 1), o[2] * drop_factor(drop, b, n + 2),
+                         o[3] * drop_factor(drop, b, n + 3)};
+    store4<T>(outD + (size_t)b * ldod + n, od);
+  }
 }
-template __global__ void tanh_planes_kernel<bf16_t>(Planes, bf16_t*, int, int, int);
-template __global__ void tanh_planes_kernel<float>(Planes, float*, int, int, int);
+template __global__ void tanh_planes_kernel<bf16_t>(Planes, bf16_t*, int, bf16_t*, int, DropSpec, int, int);
+template __global__ void tanh_planes_kernel<float>(Planes, float*, int, float*, int, DropSpec, int, int);
 
 // dpre = (dHo_ce + feed) * (1 - Ho^2) -> T; feed arrives as planes (np = 0: none); 4 columns per thread
 template <typename T>
 __global__ __launch_bounds__(256) void tanh_bwd_kernel(const float* __restrict__ dce, Planes feed, const T* __restrict__ Ho,
-                                                       int ldho, T* __restrict__ dpre, int ldp, int Bp, int H) {
+                                                       int ldho, T* __restrict__ dpre, int ldp, int Bp, int H, DropSpec drop) {
   const int i4 = blockIdx.x * 256 + threadIdx.x;
   const int hq = H >> 2;
   if (i4 >= Bp * hq) return;
@@ -746,18 +770,18 @@ __global__ __launch_bounds__(256) void tanh_bwd_kernel(const float* __restrict__
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const float ho = to_f<T>(Ho[(size_t)b * ldho + h + e]);
-    o[e] = ((&d.x)[e] + (&f.x)[e]) * (1.f - ho * ho);
+    o[e] = ((&d.x)[e] + (&f.x)[e]) * drop_factor(drop, b, h + e) * (1.f - ho * ho);
   }
   store4<T>(dpre + (size_t)b * ldp + h, o);
 }
 
 void launch_tanh_bwd(int prec, const float* dHo_ce, const Planes& feed, const void* Ho, int ldho, void* dpre, int ldp, int Bp, int H,
-                     hipStream_t st) {
+                     const DropSpec& drop, hipStream_t st) {
   const int n = Bp * (H >> 2);
   if (prec) hipLaunchKernelGGL(tanh_bwd_kernel<bf16_t>, dim3((n + 255) / 256), dim3(256), 0, st, dHo_ce, feed,
-                               (const bf16_t*)Ho, ldho, (bf16_t*)dpre, ldp, Bp, H);
+                               (const bf16_t*)Ho, ldho, (bf16_t*)dpre, ldp, Bp, H, drop);
   else hipLaunchKernelGGL(tanh_bwd_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, st, dHo_ce, feed,
-                          (const float*)Ho, ldho, (float*)dpre, ldp, Bp, H);
+                          (const float*)Ho, ldho, (float*)dpre, ldp, Bp, H, drop);
 }
 
 }  // namespace cmt

@@ -37,7 +37,8 @@ def check_grads(g, og, prec, label=""):
     return worst
 
 
-def run_case(cfg, params, batch, prec, max_shape=None, check_inter=True):
+def run_case(cfg, params, batch, prec, max_shape=None, check_inter=True, reg=None):
+    """reg: None or (dropout, label_smoothing, dropout_seed) — handed to both sides."""
     from paper_1802_07170_amd import binding
     src, sl, tgt, tl = batch
     B, S = src.shape
@@ -46,9 +47,13 @@ def run_case(cfg, params, batch, prec, max_shape=None, check_inter=True):
     tr = binding.Trainer(cfg, mb, ms, mt, precision=prec)
     try:
         tr.set_params(I.flatten(params, cfg))
+        okw = {}
+        if reg:
+            tr.set_regularization(*reg)
+            okw = dict(dropout=reg[0], label_smoothing=reg[1], dropout_seed=reg[2])
         loss = tr.train_step(tr.upload_batch(*batch))
         g = I.unflatten(tr.get_grads(), cfg)
-        oloss, og, it = O.train_step(cfg, params, *batch, want_intermediates=True)
+        oloss, og, it = O.train_step(cfg, params, *batch, want_intermediates=True, **okw)
         tol = 1e-4 if prec == 0 else 2e-2
         assert abs(loss - oloss) <= tol * abs(oloss), (loss, oloss)
         worst = check_grads(g, og, prec)
@@ -75,6 +80,13 @@ def run_case(cfg, params, batch, prec, max_shape=None, check_inter=True):
                                  ("h_o", it["h_o"], vt)]:
                 got = tr.debug_fetch(name, (ref.shape[0], Bp, H))[:, :B]
                 assert np.abs(got[m] - ref[m]).max() <= atol, name
+            hod = tr.debug_fetch("h_o_drop", (T, Bp, H))[:, :B]
+            assert np.abs(hod[vt] - it["h_o_drop"][vt]).max() <= atol * (2 if reg else 1), "h_o_drop"
+            if reg and reg[0] > 0:
+                # the keep / drop decision is an integer comparison: the zero pattern is bit-exact
+                dropped = it["h_o_drop"][vt] == 0
+                assert np.array_equal(hod[vt][dropped], np.zeros(dropped.sum(), np.float32))
+                assert np.count_nonzero(hod[vt][~dropped]) >= 0.99 * (~dropped).sum()
             a = tr.debug_fetch("att_a", (T, Bp, S))[:, :B]
             assert np.abs(a[vt] - it["att_a"][vt]).max() <= atol
             pad = ~(vs.T)                                                              # [B,S]
@@ -134,6 +146,51 @@ def test_output_layer_over_two_slabs(prec):
     params = I.make_params(cfg, seed=3, scale=0.3)
     batch = ragged_batch(rng, 70, 4, 14, cfg["src_vocab"], cfg["tgt_vocab"])
     loss, oloss, worst, tr = run_case(cfg, params, batch, prec, check_inter=False)
+    tr.close()
+
+
+@pytest.mark.parametrize("prec", [0, 1])
+@pytest.mark.parametrize("B,S,T,H,E,L", [(5, 7, 9, 32, 24, 1), (19, 13, 11, 80, 40, 2), (6, 5, 6, 48, 16, 3),
+                                         (70, 5, 4, 64, 16, 4)])
+def test_dropout_and_label_smoothing(prec, B, S, T, H, E, L):
+    """The paper's regularisation (dropout 0.2 between recurrent layers and on H_o, label smoothing
+    0.1) with the same counter-based masks on both sides; batches that are not multiples of 16, so the
+    mask index must use the real batch size; 1 to 4 layers (0 to 3 inter-layer sites per stack)."""
+    cfg = dict(src_vocab=104, tgt_vocab=136, emb=E, hidden=H, layers=L)
+    rng = np.random.default_rng(300 + B)
+    params = I.make_params(cfg, seed=B + 1, scale=0.3)
+    batch = ragged_batch(rng, B, S, T, cfg["src_vocab"], cfg["tgt_vocab"])
+    loss, oloss, worst, tr = run_case(cfg, params, batch, prec, max_shape=(B + 3, S + 2, T + 5), reg=(0.2, 0.1, 987654321 + B))
+    # another seed gives another step; switching both off gives the plain step again
+    tr.set_regularization(0.2, 0.1, 5)
+    dev = tr.upload_batch(*batch)
+    assert tr.train_step(dev) != loss
+    tr.set_regularization(0.0, 0.0, 0)
+    plain = tr.train_step(dev)
+    oplain = O.train_step(cfg, params, *batch)[0]
+    assert abs(plain - oplain) <= (1e-4 if prec == 0 else 2e-2) * oplain
+    tr.close()
+
+
+def test_label_smoothing_alone_and_dropout_alone():
+    cfg = dict(src_vocab=104, tgt_vocab=328, emb=16, hidden=48, layers=2)
+    rng = np.random.default_rng(17)
+    params = I.make_params(cfg, seed=9, scale=0.3)
+    batch = ragged_batch(rng, 9, 6, 7, cfg["src_vocab"], cfg["tgt_vocab"])
+    for reg in [(0.0, 0.1, 0), (0.5, 0.0, 2 ** 40 + 3)]:
+        loss, oloss, worst, tr = run_case(cfg, params, batch, 0, reg=reg)
+        tr.close()
+
+
+def test_regularisation_arguments_are_checked():
+    from paper_1802_07170_amd import binding
+    cfg = dict(src_vocab=104, tgt_vocab=136, emb=24, hidden=32, layers=1)
+    tr = binding.Trainer(cfg, 4, 6, 6, precision=0)
+    for bad in [(1.0, 0.0), (-0.1, 0.0), (0.0, 1.0), (0.0, -0.5), (float("nan"), 0.0)]:
+        with pytest.raises(binding.CmtError) as e:
+            tr.set_regularization(bad[0], bad[1], 0)
+        assert e.value.code == binding.CMT_EINVAL
+    tr.set_regularization(0.2, 0.1, 1)
     tr.close()
 
 
