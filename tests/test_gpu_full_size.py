@@ -3,6 +3,9 @@ times.  Expected values are digests written by tests/golden/make_digests.py, whi
 CPU oracle: loss, per-tensor gradient norms, a seeded sample of entries of every gradient tensor,
 embedding-gradient rows of frequent and never-seen ids, per-position nll.
 
+The attn workload and the medium shape (well-conditioned initialisation) are also run with the
+paper's regularisation (dropout 0.2, label smoothing 0.1) at the bar.
+
 Three kinds of case:
   * bf16 path, bar of the task (loss rel 2e-2; gradients relative L2 <= 2e-2 and
     |g - g*| <= 2e-2 |g*| + 1e-3): the attn workload as specified, and the medium / large shapes
@@ -35,10 +38,14 @@ def sample_index(name, n):
     return np.sort(np.random.default_rng(seed).choice(n, size=SAMPLE, replace=False))
 
 
-def run_digest_case(name, scale, prec, mode):
-    """mode: 'bar' = the tolerance of the precision; 'chaotic' = see the module docstring."""
+REG = dict(dropout=0.2, label_smoothing=0.1, dropout_seed=20180207)     # as in tests/golden/make_digests.py
+
+
+def run_digest_case(name, scale, prec, mode, reg=False):
+    """mode: 'bar' = the tolerance of the precision; 'chaotic' = see the module docstring.
+    reg: the step with the paper's dropout and label smoothing."""
     from paper_1802_07170_amd import binding
-    path = os.path.join(GOLD, f"digest_{name}.npz" if scale is None else f"digest_{name}_s{scale}.npz")
+    path = os.path.join(GOLD, f"digest_{name}" + (f"_s{scale}" if scale is not None else "") + ("_reg" if reg else "") + ".npz")
     if not os.path.exists(path):
         pytest.skip(f"{path} not generated")
     d = np.load(path)
@@ -52,6 +59,8 @@ def run_digest_case(name, scale, prec, mode):
     tr = binding.Trainer(cfg, B, S, T, precision=prec)
     try:
         tr.set_params(I.flatten(params, cfg))
+        if reg:
+            tr.set_regularization(REG["dropout"], REG["label_smoothing"], REG["dropout_seed"])
         dev = tr.upload_batch(*batch)
         loss = tr.train_step(dev)
         flat = tr.get_grads()
@@ -112,6 +121,14 @@ def test_h1024_shapes_bf16_well_conditioned_init_at_the_bar(name):
 
 def test_medium_workload_fp32_path_at_the_bar():
     run_digest_case("medium", None, 0, "bar")
+
+
+def test_attn_workload_bf16_with_dropout_and_label_smoothing_at_the_bar():
+    run_digest_case("attn", None, 1, "bar", reg=True)
+
+
+def test_medium_shape_bf16_with_dropout_and_label_smoothing_at_the_bar():
+    run_digest_case("medium", "0.05", 1, "bar", reg=True)
 
 
 @pytest.mark.parametrize("name", ["medium", "large"])
