@@ -132,6 +132,29 @@ def main():
     out["roofline"] = {"kernel": "lstm_fwd_kernel (decoder layer step: gate GEMM + fused cell)", "bound": "hbm",
                        "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                        "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "us_per_launch": us, "algorithmic_bytes_per_launch": nbytes}
+    # the other kernel classes of the step, each replayed alone (no second stream active)
+    peak_mfma = MFMA_BF16_PEAK_TFLOPS if c["precision"] else MFMA_FP32_PEAK_TFLOPS
+    kernels = {}
+    for name, kind, iters in [("step2d_bwd_dec", "hbm", 400), ("att_fwd", "hbm", 400), ("gemm_gx", "mfma", 50),
+                              ("gemm_dw", "mfma", 50), ("ce_fwd", "mfma", 20)]:
+        kus, work = tr.time_kernel(name, iters)
+        if kind == "hbm":
+            a = work / (kus * 1e-6) / 1e9
+            kernels[name] = {"bound": "hbm", "us_per_launch": kus, "achieved": a, "unit": "GB/s", "peak": HBM_PEAK_GBS,
+                             "frac": a / HBM_PEAK_GBS}
+        else:
+            a = work / (kus * 1e-6) / 1e12
+            kernels[name] = {"bound": "mfma", "us_per_launch": kus, "achieved": a, "unit": "TFLOP/s", "peak": peak_mfma,
+                             "frac": a / peak_mfma}
+    out["other_kernels"] = kernels
+    # SGD update of all parameters incl. the refresh of the kernels' working copies (not part of a step)
+    tr.sgd_update(0.0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(3):
+        tr.sgd_update(0.0)
+    torch.cuda.synchronize()
+    out["sgd_update_ms"] = (time.perf_counter() - t0) / 3 * 1e3
     if args.calibration_copy:
         a = torch.zeros(64 << 20, dtype=torch.float32, device="cuda")
         b = torch.empty_like(a)

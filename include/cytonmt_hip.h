@@ -134,10 +134,17 @@ int cmt_padded_batch(const cmt_handle* h);
 
 /* Measurement aid: launches one kernel of the last step `iters` times back to back on the handle's
  * stream, with the operands that step used (results are rewritten with identical values), timed
- * by HIP events.  Names: "lstm_fwd_dec" = the fused decoder LSTM step (gate GEMM + cell), cycling
- * over the decoder layers.  Returns the mean microseconds per launch and the algorithmic bytes one
- * launch moves (weights + activations + state read once, outputs written once).  Synchronises. */
-int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_launch, double* algo_bytes);
+ * by HIP events.  Returns the mean microseconds per launch and the algorithmic work of one launch:
+ * bytes (operands read once, outputs written once) for the bandwidth-bound kernels, flops
+ * (2 per multiply-add) for the matrix-core-bound ones.  Names:
+ *   "lstm_fwd_dec"   fused decoder LSTM step (gate GEMM + cell), cycling over the layers   bytes
+ *   "step2d_bwd_dec" [dx; dh] = dgates [W_x; W_h] of a decoder layer's backward step       bytes
+ *   "att_fwd"        attention scores + softmax + context of one decoder step              bytes
+ *   "gemm_gx"        time-batched input-side GEMM [T Bp, E] x [E, 4H]                      flops
+ *   "gemm_dw"        time-batched weight-gradient GEMM [4H, T Bp] x [T Bp, H]              flops
+ *   "ce_fwd"         vocabulary projection + log-sum-exp partials of the first slab of rows flops
+ * Synchronises the stream. */
+int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_launch, double* algo_work);
 
 const char* cmt_last_error(const cmt_handle* h);
 

@@ -15,6 +15,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <functional>
 #include <string>
 #include <vector>
 
@@ -303,6 +304,15 @@ void weight_grads(cmt_handle* h, LD& d, int Lsteps, const std::vector<std::pair<
   launch_colsum(p, d.dG, d.pg, M, 4 * Hh, h->colscr, h->grads + d.b_off, st);
 }
 
+// The output layer's slabs: full slabs of CE_SLAB_ROWS rows and one remainder.  With 256 x 256 logit
+// tiles a full slab gives (V / 256) * 4 tiles, close to a whole number of rounds over the 256 CUs for
+// the vocabulary sizes of interest (32000: 500 tiles = 1.95 rounds), which equal-sized smaller slabs
+// do not (768 rows: 375 tiles = 1.46 rounds).  Returns the rows of all slabs but the last.
+int ce_slab_plan(int Mt, int* nslab_out) {
+  *nslab_out = (Mt + CE_SLAB_ROWS - 1) / CE_SLAB_ROWS;
+  return CE_SLAB_ROWS;
+}
+
 // dropout sites (the oracle and the tests use the same numbering): encoder layer l output, decoder
 // layer l output, H_o
 constexpr int DROP_SITE_ENC = 0, DROP_SITE_DEC = 16, DROP_SITE_HO = 32;
@@ -501,11 +511,8 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     // Slabs of <= CE_SLAB_ROWS rows, equal sizes, two slab buffer pairs.  Per slab the main stream
     // takes forward (logits -> e, partials), lse / nll, e -> dz and dz^T, and dH_o = dz W_o (the
     // decoder needs it); the second stream takes dW_o += dz^T H_o and dB_o.
-    // Equal slabs of whole 256-row tiles where possible, the remainder going to the last one.
-    int nslab = (Mt + CE_SLAB_ROWS - 1) / CE_SLAB_ROWS;
-    int rows = Mt / nslab / 256 * 256;
-    if (rows == 0) rows = (((Mt + nslab - 1) / nslab) + 63) / 64 * 64;
-    while (Mt - (nslab - 1) * rows > CE_SLAB_ROWS) ++nslab;
+    int nslab;
+    const int rows = ce_slab_plan(Mt, &nslab);
     std::vector<hipEvent_t> done(nslab, nullptr);
     const float eps = h->ls_eps;
     int sl = 0, n_dbo = 0;
@@ -514,12 +521,12 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       char* dz = (sl & 1) ? h->dzs2 : h->dzs;
       char* dzT = (sl & 1) ? h->dzTs2 : h->dzTs;
       if (sl >= 2 && sd != st) (void)hipStreamWaitEvent(st, done[sl - 2], 0);
-      launch_ce_fwd(p, Ho + (size_t)m0 * PH * esz, PH, h->Pw(h->off_Wo), P + h->off_Bo, h->labels + m0, Mc, V, H, dz,
+      launch_ce_fwd(p, Ho + (size_t)m0 * PH * esz, PH, h->Pw(h->off_Wo), P + h->off_Bo, h->labels + m0, Mc, V, H, dzT,
                     h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, eps > 0.f ? h->psz + (size_t)m0 * np : nullptr,
                     h->zy + m0, st);
       launch_ce_rows(h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, h->psz + (size_t)m0 * np, h->zy + m0,
                      h->mask_t + m0, Mc, np, eps, V, h->lse + m0, h->nll + m0, st);
-      launch_ce_scale(p, dz, V, Mc, h->pmax + (size_t)m0 * np, h->lse + m0, h->labels + m0, h->rowscale + m0, eps, dzT,
+      launch_ce_scale(p, dzT, V, Mc, h->pmax + (size_t)m0 * np, h->lse + m0, h->labels + m0, h->rowscale + m0, eps, dz,
                       h->dbo_parts + (size_t)n_dbo * V, st);
       n_dbo += (Mc + 63) / 64;
       stream_after(h, sd, st);
@@ -869,29 +876,87 @@ int cmt_set_regularization(cmt_handle* h, float dropout, float label_smoothing, 
   return CMT_OK;
 }
 
-int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_launch, double* algo_bytes) {
-  if (!h || !name || iters < 1 || !us_per_launch || !algo_bytes) return fail(h, CMT_EINVAL, "bad argument");
+int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_launch, double* algo_work) {
+  if (!h || !name || iters < 1 || !us_per_launch || !algo_work) return fail(h, CMT_EINVAL, "bad argument");
   if (!h->have_step) return fail(h, CMT_EINVAL, "no step has been run");
-  const int H = h->cfg.hidden, L = h->cfg.layers, E = h->cfg.emb_dim, Bp = h->Bp, T = h->T;
+  const cmt_config& c = h->cfg;
+  const int p = h->prec, H = c.hidden, L = c.layers, E = c.emb_dim, V = c.tgt_vocab, Bp = h->Bp, T = h->T, S = h->S;
+  const int PH = h->PH, Mt = T * Bp;
+  const size_t BP = (size_t)Bp * PH, BH = (size_t)Bp * H;
   const double esz = (double)h->esz;
+  const size_t es = h->esz;
+  hipStream_t st = h->st;
   const std::string s(name);
-  if (s != "lstm_fwd_dec") return fail(h, CMT_EINVAL, "unknown kernel name");
-  // decoder LSTM forward step at the middle target position, cycling over the layers like the real loop
-  const int j = T / 2;
-  const int K = (L > 1) ? 2 * H : 2 * H;              // per-step contraction (layer 0: [feed; h], others: [x; h])
-  *algo_bytes = 4.0 * H * K * esz                     // weights, read once
-              + (double)Bp * K * esz                  // [x; h_prev]
-              + (double)Bp * 4 * H * 4                // bias / pre-batched input part
-              + (double)Bp * H * 4                    // c_prev
-              + (double)Bp * H * (esz + 4)            // h, c out
-              + (double)Bp * 4 * H * 4;               // gate activations kept for backward
-  (void)E;
+  const int j = T / 2;                                  // the middle target position
+  std::function<void(int)> launch;
+  if (s == "lstm_fwd_dec") {
+    // decoder LSTM forward step, cycling over the layers like the real loop (weights not L2-resident)
+    const int K = 2 * H;                                // per-step contraction (layer 0: [feed; h], others: [x; h])
+    *algo_work = 4.0 * H * K * esz                      // weights, read once
+               + (double)Bp * K * esz                   // [x; h_prev]
+               + (double)Bp * 4 * H * 4                 // bias / pre-batched input part
+               + (double)Bp * H * 4                     // c_prev
+               + (double)Bp * H * (esz + 4)             // h, c out
+               + (double)Bp * 4 * H * 4;                // gate activations kept for backward
+    launch = [=](int i) { dec_lstm_fwd(h, L > 1 ? 1 + i % (L - 1) : 0, j); };
+  } else if (s == "step2d_bwd_dec") {
+    // [dx; dh_prev] = dgates [W_x; W_h] of a decoder layer, written as planes
+    const int kb = step_kblocks(p, 2 * H, 4 * H, Bp, h->kb_bwd);
+    *algo_work = 4.0 * H * 2 * H * esz + (double)Bp * 4 * H * esz + (double)kb * Bp * 2 * H * 4;
+    launch = [=](int i) {
+      LD& e = h->dec[L > 1 ? 1 + i % (L - 1) : 0];
+      StepGemm g{};
+      g.a0 = e.dG + (size_t)j * Bp * e.pg * es; g.lda0 = e.pg; g.K0 = 4 * H; g.w0_off = 0; g.K1 = 0;
+      g.W = e.Wt + (size_t)(&e == &h->dec[0] ? E : 0) * 4 * H * es; g.ldw = 4 * H;
+      g.N = 2 * H; g.mode = 1; g.max_kb = h->kb_bwd;
+      g.out = e.bwdp; g.ldout = 2 * H; g.plane_stride = (size_t)Bp * 2 * H;
+      launch_step_gemm(p, g, Bp, st);
+    };
+  } else if (s == "att_fwd") {
+    // scores + softmax + context of one decoder step: the keys and H_s of every sentence once
+    *algo_work = 2.0 * Bp * S * H * esz;
+    const char* Hs = L > 1 ? h->enc[L].Hst + BP * es : h->Y0;
+    const int ldHs = L > 1 ? PH : H;
+    launch = [=](int) {
+      launch_att_fwd(p, h->Kmat, H, Hs, ldHs, h->dec[L - 1].Hst + (j + 1) * BP * es, PH, h->len_s, S, Bp, H, h->dots,
+                     h->att_a + (size_t)j * Bp * S, h->Cs + j * BP * es, PH, st);
+    };
+  } else if (s == "gemm_gx") {
+    // time-batched input-side GEMM of the decoder's bottom layer: [T Bp, E] x [E, 4H]  (flops)
+    *algo_work = 2.0 * Mt * 4 * H * E;
+    launch = [=](int) {
+      LD& d0 = h->dec[0];
+      launch_gemm_nt(p, h->Xt, E, d0.W, E + 2 * H, Mt, 4 * H, E, d0.Gx, nullptr, 4 * H, h->params + d0.b_off, 0, st);
+    };
+  } else if (s == "gemm_dw") {
+    // weight gradient of a decoder layer's recurrent block: dG^T [4H, T Bp] x H^T [H, T Bp]^T  (flops)
+    *algo_work = 2.0 * 4 * H * H * Mt;
+    launch = [=](int) {
+      LD& e = h->dec[L - 1];
+      launch_gemm_nt(p, e.dGT, Mt, e.HstT, (T + 1) * Bp, 4 * H, H, Mt, h->grads + e.w_off + e.Kin, nullptr, e.Kin + H, nullptr, 0,
+                     st, h->gsplit2, h->gsplit_floats);
+    };
+  } else if (s == "ce_fwd") {
+    // vocabulary projection of one slab of rows with the partial log-sum-exp statistics  (flops)
+    int nslab;
+    const int rows = ce_slab_plan(Mt, &nslab);
+    const int Mc = nslab == 1 ? Mt : rows;              // the first slab
+    *algo_work = 2.0 * Mc * (double)V * H;
+    const char* Ho = (h->drop_p > 0.f ? h->HoDrop : h->HoBuf) + BP * es;
+    launch = [=](int) {
+      launch_ce_fwd(p, Ho, PH, h->Pw(h->off_Wo), h->params + h->off_Bo, h->labels, Mc, V, H, h->dzTs2, h->pmax, h->psum, nullptr,
+                    h->zy, st);
+    };
+  } else {
+    return fail(h, CMT_EINVAL, "unknown kernel name");
+  }
+  (void)BH;
   hipEvent_t e0, e1;
   if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return fail(h, CMT_EHIP, "event create");
-  for (int i = 0; i < 8; ++i) dec_lstm_fwd(h, L > 1 ? 1 + i % (L - 1) : 0, j);
-  (void)hipEventRecord(e0, h->st);
-  for (int i = 0; i < iters; ++i) dec_lstm_fwd(h, L > 1 ? 1 + i % (L - 1) : 0, j);
-  (void)hipEventRecord(e1, h->st);
+  for (int i = 0; i < 4; ++i) launch(i);
+  (void)hipEventRecord(e0, st);
+  for (int i = 0; i < iters; ++i) launch(i);
+  (void)hipEventRecord(e1, st);
   hipError_t e = hipEventSynchronize(e1);
   float ms = 0.f;
   if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);

@@ -1,15 +1,16 @@
 // Vocabulary projection + log-softmax + cross-entropy (Eq. 1), forward and backward, one slab of at
 // most CE_SLAB_ROWS target positions at a time; the full [rows, vocabulary] matrix never exists and
 // the logits are contracted exactly once:
-//   ce_fwd_kernel : logits of a 256 x 256 tile on the matrix cores; per row and group of 64 columns
-//                   the maximum m, the sum of e = exp(z - m) and the label's logit are kept, and e
-//                   itself is stored in the operand type (a multiplicative quantity, so bf16 keeps
-//                   its relative precision whatever the logit's magnitude);
+//   ce_fwd_kernel : logits of a 256 x 256 tile on the matrix cores; per target position and group of
+//                   64 vocabulary entries the maximum m, the sum of e = exp(z - m) and the label's
+//                   logit are kept, and e itself is stored (transposed, [V, slab rows]) in the
+//                   operand type (a multiplicative quantity, so bf16 keeps its relative precision
+//                   whatever the logit's magnitude);
 //   ce_row_kernel : row log-sum-exp from the partials, masked negative log-likelihood;
-//   ce_scale_kernel: dz = (e * exp(m - lse) - q) * mask / n_tok with q the target distribution
+//   ce_scale_kernel: dz^T = (e^T * exp(m - lse) - q) * mask / n_tok with q the target distribution
 //                   (onehot, or smoothed: (1 - eps) onehot + eps / V), elementwise, in place, plus
-//                   its transpose (through LDS), so that dH_o = dz W_o and dW_o += dz^T H_o are
-//                   plain k-contiguous GEMMs.
+//                   dz (through LDS), so that dH_o = dz W_o and dW_o += dz^T H_o are plain
+//                   k-contiguous GEMMs.
 #include "gemm_core.h"
 #include "kernels.h"
 
@@ -19,79 +20,76 @@ using CeG = GemmBig;                                      // 256 x 256 logit til
 int ce_num_partials(int V) { return 4 * ((V + CeG::BN - 1) / CeG::BN); }
 size_t ce_slab_elems(int V) { return (size_t)CE_SLAB_ROWS * V; }
 
+// The tile is computed transposed — vocabulary rows on the matrix cores' row side, target positions
+// on the column side — so that in the accumulator layout a lane holds 32 vocabulary entries of ONE
+// target position (two 32x32 tiles x 16 registers) and the other 32 of the wavefront's 64 sit in the
+// lane 32 away: the row statistics need one cross-lane exchange instead of a 32-lane butterfly.
 template <typename T>
 __global__ __launch_bounds__(CeG::NT) void ce_fwd_kernel(const T* __restrict__ Ho, int ldho, const T* __restrict__ Wo,
                                                          const float* __restrict__ Bo, const int32_t* __restrict__ labels,
-                                                         int M, int V, int H, T* __restrict__ E, float* __restrict__ pmax,
-                                                         float* __restrict__ psum, float* __restrict__ psz,
-                                                         float* __restrict__ zy, int np, int ntn) {
+                                                         int M, int V, int H, T* __restrict__ ET, int ldet,
+                                                         float* __restrict__ pmax, float* __restrict__ psum,
+                                                         float* __restrict__ psz, float* __restrict__ zy, int np, int ntn) {
   __shared__ __align__(16) char smem[CeG::SMEM_BYTES];
-  const int per = gridDim.x >> 3;
-  const int id = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
-  const int m0 = (id / ntn) * CeG::BM, n0 = (id % ntn) * CeG::BN;
-  if (m0 >= M) return;
+  int v0, r0;                                             // tile: vocabulary rows v0.., target positions r0..
+  if (!gemm_tile_of_block((V + CeG::BM - 1) / CeG::BM, ntn, CeG::BM, CeG::BN, v0, r0)) return;
   v16f acc[2][2];
-  gemm_mainloop<T, 4, 4, 2, 2, 128>(Ho, ldho, Wo, H, M, V, H, m0, n0, acc, smem);
+  gemm_mainloop<T, 4, 4, 2, 2, 128>(Wo, H, Ho, ldho, V, M, H, v0, r0, acc, smem);
+  float* sbo = reinterpret_cast<float*>(smem);            // the main loop ends with a barrier: LDS is free
+  if (threadIdx.x < CeG::BM) sbo[threadIdx.x] = v0 + (int)threadIdx.x < V ? Bo[v0 + threadIdx.x] : 0.f;
+  __syncthreads();
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int wm = w >> 2, wn = w & 3;
-  int col[2];
-  float bo[2];
+  const int pidx = (v0 >> 6) + wm;                        // this wavefront's group of 64 vocabulary entries
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {
-    col[b] = n0 + wn * 64 + b * 32 + (lane & 31);
-    bo[b] = col[b] < V ? Bo[col[b]] : 0.f;
-  }
-  const int pidx = (n0 >> 6) + wn;
+  for (int nt = 0; nt < 2; ++nt) {
+    const int r = r0 + wn * 64 + nt * 32 + (lane & 31);
+    const int y = r < M ? labels[r] : -1;
+    float z[2][16];
+    float mx = -INFINITY, sz = 0.f;
 #pragma unroll
-  for (int mt = 0; mt < 2; ++mt) {
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int row = m0 + wm * 64 + mt * 32 + acc32_row(lane, i);
-      const int y = row < M ? labels[row] : -1;
-      float z[2];
-      float mx = -INFINITY;
-#pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        z[b] = col[b] < V ? acc[mt][b][i] + bo[b] : -INFINITY;
-        if (y == col[b]) zy[row] = z[b];
-        mx = fmaxf(mx, z[b]);
+      for (int i = 0; i < 16; ++i) {
+        const int vl = wm * 64 + mt * 32 + acc32_row(lane, i);
+        const bool in = v0 + vl < V;
+        z[mt][i] = in ? acc[mt][nt][i] + sbo[vl] : -INFINITY;
+        if (in) sz += z[mt][i];
+        if (v0 + vl == y) zy[r] = z[mt][i];
+        mx = fmaxf(mx, z[mt][i]);
       }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    float e = 0.f;
 #pragma unroll
-      for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-      float e = 0.f, sz = 0.f;
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        const float eb = mx > -INFINITY ? expf(z[b] - mx) : 0.f;          // exp(-inf) = 0 for columns past V
-        e += eb;
-        if (col[b] < V) sz += z[b];
-        if (row < M && col[b] < V) E[(size_t)row * V + col[b]] = from_f<T>(eb);
+      for (int i = 0; i < 16; ++i) {
+        const int v = v0 + wm * 64 + mt * 32 + acc32_row(lane, i);
+        const float ev = mx > -INFINITY ? expf(z[mt][i] - mx) : 0.f;      // exp(-inf) = 0 past the vocabulary
+        e += ev;
+        if (r < M && v < V) ET[(size_t)v * ldet + r] = from_f<T>(ev);
       }
-#pragma unroll
-      for (int o = 16; o > 0; o >>= 1) e += __shfl_xor(e, o, 64);
-      if (psz) {                                            // label smoothing needs the mean logit of the row
-#pragma unroll
-        for (int o = 16; o > 0; o >>= 1) sz += __shfl_xor(sz, o, 64);
-      }
-      if ((lane & 31) == 0 && row < M) {
-        pmax[(size_t)row * np + pidx] = mx;
-        psum[(size_t)row * np + pidx] = e;
-        if (psz) psz[(size_t)row * np + pidx] = sz;
-      }
+    e += __shfl_xor(e, 32, 64);
+    if (psz) sz += __shfl_xor(sz, 32, 64);                // label smoothing needs the mean logit of the row
+    if (lane < 32 && r < M) {
+      pmax[(size_t)r * np + pidx] = mx;
+      psum[(size_t)r * np + pidx] = e;
+      if (psz) psz[(size_t)r * np + pidx] = sz;
     }
   }
 }
 
 void launch_ce_fwd(int prec, const void* Ho, int ldho, const void* Wo, const float* Bo, const int32_t* labels,
-                   int M, int V, int H, void* E, float* pmax, float* psum, float* psz, float* zy, hipStream_t st) {
-  const int ntm = (M + CeG::BM - 1) / CeG::BM, ntn = (V + CeG::BN - 1) / CeG::BN;
-  const int grid = ((ntm * ntn + 7) / 8) * 8;
+                   int M, int V, int H, void* ET, float* pmax, float* psum, float* psz, float* zy, hipStream_t st) {
+  const int ntv = (V + CeG::BM - 1) / CeG::BM, ntr = (M + CeG::BN - 1) / CeG::BN;
+  const int grid = ((ntv * ntr + 7) / 8) * 8;
   const int np = ce_num_partials(V);
   if (prec)
     hipLaunchKernelGGL(ce_fwd_kernel<bf16_t>, dim3(grid), dim3(CeG::NT), 0, st, (const bf16_t*)Ho, ldho, (const bf16_t*)Wo, Bo,
-                       labels, M, V, H, (bf16_t*)E, pmax, psum, psz, zy, np, ntn);
+                       labels, M, V, H, (bf16_t*)ET, CE_SLAB_ROWS, pmax, psum, psz, zy, np, ntr);
   else
     hipLaunchKernelGGL(ce_fwd_kernel<float>, dim3(grid), dim3(CeG::NT), 0, st, (const float*)Ho, ldho, (const float*)Wo, Bo,
-                       labels, M, V, H, (float*)E, pmax, psum, psz, zy, np, ntn);
+                       labels, M, V, H, (float*)ET, CE_SLAB_ROWS, pmax, psum, psz, zy, np, ntr);
 }
 
 // one wavefront per row: combine the partials.  Row loss against the smoothed target distribution
@@ -178,77 +176,82 @@ void launch_ce_loss(const float* nll, int M, float* loss, int* flags, hipStream_
 }
 
 // ------------------------------------------------------------------------------------------------
-// e -> dz, in place, dz^T, and per block of 64 rows the column sums of dz (partial dB_o, summed by
-// the caller in a fixed order).  One workgroup per 64 rows x 64 columns (= one group of partials):
-// thread t takes row t / 4 and 16 consecutive columns; the transpose goes through LDS so that both
-// the dz rows and the dz^T rows leave as 16-byte stores.
+// e^T -> dz^T in place, dz through an LDS transpose, and per block of 64 target positions the column
+// sums of dz (partial dB_o, summed by the caller in a fixed order).  One workgroup per 64 vocabulary
+// entries (= one group of partials) x 64 target positions: thread t first takes vocabulary entry
+// t / 4 and 16 consecutive positions, then position t / 4 and 16 consecutive vocabulary entries, so
+// that both matrices move as 16-byte vectors.
 // ------------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void ce_scale_kernel(T* __restrict__ E, int V, int Mc, const float* __restrict__ pmax, int np,
-                                                       const float* __restrict__ lse, const int32_t* __restrict__ labels,
-                                                       const float* __restrict__ rowscale, float eps, T* __restrict__ dzT,
-                                                       int ldzt, float* __restrict__ dbo_part) {
+__global__ __launch_bounds__(256) void ce_scale_kernel(T* __restrict__ ET, int ldet, int V, int Mc, const float* __restrict__ pmax,
+                                                       int np, const float* __restrict__ lse, const int32_t* __restrict__ labels,
+                                                       const float* __restrict__ rowscale, float eps, T* __restrict__ dz,
+                                                       float* __restrict__ dbo_part) {
   constexpr int VE = 16 / sizeof(T);                      // elements per 16-byte vector
   constexpr int NV = 16 / VE;                             // vectors per thread
-  __shared__ __align__(16) T tile[64][64 + VE];
-  const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+  __shared__ __align__(16) T tile[64][64 + VE];           // [position][vocabulary entry]
+  __shared__ float sf[64], srs[64];
+  __shared__ int sy[64];
+  const int v0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
   const int t = threadIdx.x;
-  {
-    const int r = t >> 2, row = r0 + r, cb = (t & 3) * 16;
+  if (t < 64) {
+    const int r = r0 + t;
     float f = 0.f, rs = 0.f;
-    const float epsv = eps / (float)V;                      // target distribution (1 - eps) onehot + eps / V
     int y = -1;
-    if (row < Mc) {
-      const float pm = pmax[(size_t)row * np + blockIdx.x];
-      f = pm > -INFINITY ? expf(pm - lse[row]) : 0.f;
-      rs = rowscale[row];
-      y = labels[row];
+    if (r < Mc) {
+      const float pm = pmax[(size_t)r * np + blockIdx.x];
+      f = pm > -INFINITY ? expf(pm - lse[r]) : 0.f;
+      rs = rowscale[r];
+      y = labels[r];
     }
+    sf[t] = f; srs[t] = rs; sy[t] = y;
+  }
+  __syncthreads();
+  const float epsv = eps / (float)V;                      // target distribution (1 - eps) onehot + eps / V
+  {
+    const int vl = t >> 2, v = v0 + vl, rb = (t & 3) * 16;
+    float cs = 0.f;                                       // this block's share of dB_o[v]: 64 positions in fixed order
 #pragma unroll
-    for (int v = 0; v < NV; ++v) {
-      const int col = c0 + cb + v * VE;
+    for (int q = 0; q < NV; ++q) {
       T x[VE];
-      if (row < Mc && col < V) *reinterpret_cast<uint4*>(x) = *reinterpret_cast<const uint4*>(E + (size_t)row * V + col);
+      if (v < V) *reinterpret_cast<uint4*>(x) = *reinterpret_cast<const uint4*>(ET + (size_t)v * ldet + r0 + rb + q * VE);
       else *reinterpret_cast<uint4*>(x) = make_uint4(0, 0, 0, 0);
 #pragma unroll
       for (int j = 0; j < VE; ++j) {
-        const float d = row < Mc && col < V ? (to_f<T>(x[j]) * f - (y == col + j ? 1.f - eps : 0.f) - epsv) * rs : 0.f;
+        const int rl = rb + q * VE + j;
+        const float d = v < V && r0 + rl < Mc ? (to_f<T>(x[j]) * sf[rl] - (sy[rl] == v ? 1.f - eps : 0.f) - epsv) * srs[rl] : 0.f;
         x[j] = from_f<T>(d);
-        tile[cb + v * VE + j][r] = x[j];
+        cs += to_f<T>(x[j]);
+        tile[rl][vl] = x[j];
       }
-      if (row < Mc && col < V) *reinterpret_cast<uint4*>(E + (size_t)row * V + col) = *reinterpret_cast<const uint4*>(x);
-    }
-  }
-  __syncthreads();
-  {
-    const int c = t >> 2, col = c0 + c, rb = (t & 3) * 16;
-    float cs = 0.f;                                         // this block's share of dB_o[col]: 64 rows in fixed order
-    if (col < V) {
-#pragma unroll
-      for (int v = 0; v < NV; ++v) {                        // rows past Mc hold zeros; the slab is CE_SLAB_ROWS wide
-        const uint4 x = *reinterpret_cast<const uint4*>(&tile[c][rb + v * VE]);
-        *reinterpret_cast<uint4*>(dzT + (size_t)col * ldzt + r0 + rb + v * VE) = x;
-        const T* xe = reinterpret_cast<const T*>(&x);
-#pragma unroll
-        for (int j = 0; j < VE; ++j) cs += to_f<T>(xe[j]);
-      }
+      if (v < V) *reinterpret_cast<uint4*>(ET + (size_t)v * ldet + r0 + rb + q * VE) = *reinterpret_cast<const uint4*>(x);
     }
     cs += __shfl_xor(cs, 1, 64);
     cs += __shfl_xor(cs, 2, 64);
-    if ((t & 3) == 0 && col < V) dbo_part[(size_t)blockIdx.y * V + col] = cs;
+    if ((t & 3) == 0 && v < V) dbo_part[(size_t)blockIdx.y * V + v] = cs;
+  }
+  __syncthreads();
+  {
+    const int rl = t >> 2, r = r0 + rl, vb = (t & 3) * 16;
+    if (r < Mc) {
+#pragma unroll
+      for (int q = 0; q < NV; ++q)
+        if (v0 + vb + q * VE < V)
+          *reinterpret_cast<uint4*>(dz + (size_t)r * V + v0 + vb + q * VE) = *reinterpret_cast<const uint4*>(&tile[rl][vb + q * VE]);
+    }
   }
 }
 
-void launch_ce_scale(int prec, void* E, int V, int Mc, const float* pmax, const float* lse, const int32_t* labels,
-                     const float* rowscale, float eps, void* dzT, float* dbo_part, hipStream_t st) {
+void launch_ce_scale(int prec, void* ET, int V, int Mc, const float* pmax, const float* lse, const int32_t* labels,
+                     const float* rowscale, float eps, void* dz, float* dbo_part, hipStream_t st) {
   dim3 grid((V + 63) / 64, (Mc + 63) / 64);
   const int np = ce_num_partials(V);
   if (prec)
-    hipLaunchKernelGGL(ce_scale_kernel<bf16_t>, grid, dim3(256), 0, st, (bf16_t*)E, V, Mc, pmax, np, lse, labels, rowscale,
-                       eps, (bf16_t*)dzT, CE_SLAB_ROWS, dbo_part);
+    hipLaunchKernelGGL(ce_scale_kernel<bf16_t>, grid, dim3(256), 0, st, (bf16_t*)ET, CE_SLAB_ROWS, V, Mc, pmax, np, lse, labels,
+                       rowscale, eps, (bf16_t*)dz, dbo_part);
   else
-    hipLaunchKernelGGL(ce_scale_kernel<float>, grid, dim3(256), 0, st, (float*)E, V, Mc, pmax, np, lse, labels, rowscale,
-                       eps, (float*)dzT, CE_SLAB_ROWS, dbo_part);
+    hipLaunchKernelGGL(ce_scale_kernel<float>, grid, dim3(256), 0, st, (float*)ET, CE_SLAB_ROWS, V, Mc, pmax, np, lse, labels,
+                       rowscale, eps, (float*)dz, dbo_part);
 }
 
 }  // namespace cmt

@@ -29,12 +29,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_kernel(const T* __restri
                                                                int kchunk, size_t plane_stride) {
   using G = GemmTile<WM, WN, TA, TB, KB>;
   __shared__ __align__(16) char smem[G::SMEM_BYTES];
-  // consecutive workgroup ids go round-robin to the 8 XCDs: give each XCD a contiguous band of
-  // tiles that share their A rows, so that operand tiles are re-read from that XCD's L2
-  const int per = gridDim.x >> 3;
-  const int id = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
-  const int m0 = (id / ntn) * G::BM, n0 = (id % ntn) * G::BN;
-  if (m0 >= M) return;
+  int m0, n0;
+  if (!gemm_tile_of_block((M + G::BM - 1) / G::BM, ntn, G::BM, G::BN, m0, n0)) return;
   const int k0 = blockIdx.y * kchunk;
   const int klen = min(kchunk, K - k0);
   v16f acc[TA][TB];

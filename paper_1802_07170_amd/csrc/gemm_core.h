@@ -27,6 +27,25 @@ template <int WM, int WN, int TA, int TB, int KB = 128> struct GemmTile {
 using GemmSmall = GemmTile<2, 2, 2, 2, 128>;               // 128 x 128, 256 threads
 using GemmBig = GemmTile<4, 4, 2, 2, 128>;                 // 256 x 256, 1024 threads
 
+// Workgroup id -> output tile.  Consecutive workgroup ids go round-robin to the 8 XCDs (each with
+// its own L2), so XCD x is given the contiguous range of tile numbers [x * per, (x + 1) * per); tile
+// numbers run down groups of GROUP_M tile rows column by column, so that the ~32 tiles an XCD works
+// on at a time form a block of GROUP_M x 8 tiles that share their A and B panels in that L2 (a strip
+// of 1 x 32 tiles would pull 33 panels through L2 instead of 12).  Returns false for padding ids.
+constexpr int GEMM_GROUP_M = 4;
+__device__ __forceinline__ bool gemm_tile_of_block(int ntm, int ntn, int bm, int bn, int& m0, int& n0) {
+  const int per = gridDim.x >> 3;
+  const int id = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  if (id >= ntm * ntn) return false;
+  const int gsz = GEMM_GROUP_M * ntn;
+  const int grp = id / gsz, rem = id - grp * gsz;
+  const int first = grp * GEMM_GROUP_M;
+  const int gm = min(GEMM_GROUP_M, ntm - first);
+  m0 = (first + rem % gm) * bm;
+  n0 = (rem / gm) * bn;
+  return true;
+}
+
 template <typename T, int NT, int ROWS, int KB>
 __device__ __forceinline__ void gemm_load_tile(const T* __restrict__ P, int ld, int rows, int K, int r0, int k0,
                                                uint4 (&regs)[ROWS * KB / 16 / NT]) {

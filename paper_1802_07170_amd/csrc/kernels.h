@@ -23,13 +23,13 @@ void launch_transpose(int prec, const void* in, int ldin, void* out, int ldout, 
 // Eq. 1 for a slab of M <= CE_SLAB_ROWS rows (all row pointers at the slab's first row).
 // Forward: Ho [M,H] T, Wo [V,H] T, Bo [V] fp32, labels [M] int32.  Per row and group of 64
 // vocabulary columns: pmax = max z, psum = sum exp(z - pmax) ([M, np] fp32, np = ce_num_partials(V));
-// zy [M] = the label's logit; E [M, V] T = exp(z - pmax of its group); psz [M, np] = sum of z over
-// the group (null unless label smoothing needs the row's mean logit).
+// zy [M] = the label's logit; ET [V, CE_SLAB_ROWS] T = exp(z - pmax of its group), transposed;
+// psz [M, np] = sum of z over the group (null unless label smoothing needs the row's mean logit).
 constexpr int CE_SLAB_ROWS = 1024;
 int ce_num_partials(int V);
 size_t ce_slab_elems(int V);                                 // elements of a slab buffer (E / dz, and dzT)
 void launch_ce_fwd(int prec, const void* Ho, int ldho, const void* Wo, const float* Bo, const int32_t* labels,
-                   int M, int V, int H, void* E, float* pmax, float* psum, float* psz, float* zy, hipStream_t st);
+                   int M, int V, int H, void* ET, float* pmax, float* psum, float* psz, float* zy, hipStream_t st);
 // rowscale[M] = mask / n_tok and loss[1] = n_tok (needs only the masks; M = all rows of the batch).
 void launch_ce_rowscale(const float* mask, int M, float* rowscale, float* loss, hipStream_t st);
 // lse[M] and the masked row loss nll[M] = (1 - eps) (lse - zy) + eps (lse - mean_v z_v) from the partials
@@ -38,12 +38,12 @@ void launch_ce_rows(const float* pmax, const float* psum, const float* psz, cons
                     float eps, int V, float* lse, float* nll, hipStream_t st);
 // loss[0] = sum nll / loss[1]; flags |= 4 if it is not finite.  One block, deterministic order.
 void launch_ce_loss(const float* nll, int M, float* loss, int* flags, hipStream_t st);
-// Backward: E -> dz = (E * exp(pmax - lse) - (1 - eps) onehot - eps / V) * rowscale in place ([Mc, V] T) and
-// dzT [V, CE_SLAB_ROWS] T (columns >= Mc up to the next multiple of 64 are zero-filled).  The caller
+// Backward: ET -> dzT = (ET * exp(pmax - lse) - (1 - eps) onehot - eps / V) * rowscale in place
+// ([V, CE_SLAB_ROWS] T; columns >= Mc up to the next multiple of 64 are zero-filled) and dz [Mc, V] T.  The caller
 // then takes dH_o[rows] = dz W_o and dW_o += dz^T H_o[rows] with launch_gemm_nt.  dbo_part
 // [ceil(Mc / 64), V] fp32: column sums of dz over each block of 64 rows (dB_o = their sum over all slabs).
-void launch_ce_scale(int prec, void* E, int V, int Mc, const float* pmax, const float* lse, const int32_t* labels,
-                     const float* rowscale, float eps, void* dzT, float* dbo_part, hipStream_t st);
+void launch_ce_scale(int prec, void* ET, int V, int Mc, const float* pmax, const float* lse, const int32_t* labels,
+                     const float* rowscale, float eps, void* dz, float* dbo_part, hipStream_t st);
 
 // ---- step.hip ----------------------------------------------------------------------------------
 // A value delivered as `np` partial planes: v(b, c) = sum_k p[k * stride + b * ld + c]  (np = 0: zero).
