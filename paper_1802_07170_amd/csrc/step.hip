@@ -40,20 +40,20 @@ static inline int step_grid_blocks(const StepGrid& g) { return ((g.nx + 7) / 8) 
 // [a0 (K0); a1 (K1)] covers 8 elements; all loads of a round are issued before its first MFMA.
 // The partial tiles go through LDS; afterwards tile t = rt * STEP_MAXBT + bt is summed by wavefront
 // t % KS.  red must hold KS * RT * STEP_MAXBT * 256 floats.
-template <typename T, int RT, int KS, int U>
+template <typename T, int RT, int KS, int U, int BT = STEP_MAXBT>
 __device__ __forceinline__ void step_contract(const T* const (&wrow)[RT], int w0_off, int w1_off, const T* a0, int lda0,
                                               int K0, const T* a1, int lda1, int K1, int Bp, int bt0, int nbt, float* red) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int nc0 = K0 >> 3, nc = (K0 + K1) >> 3;
   const int nsteps = (nc + 3) >> 2;
   const int brow = 16 * bt0 + (lane & 15);
-  v4f acc[RT][STEP_MAXBT];
+  v4f acc[RT][BT];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-    for (int b = 0; b < STEP_MAXBT; ++b) acc[rt][b] = v4f{0.f, 0.f, 0.f, 0.f};
+    for (int b = 0; b < BT; ++b) acc[rt][b] = v4f{0.f, 0.f, 0.f, 0.f};
   for (int s0 = 0; s0 < nsteps; s0 += KS * U) {
-    Frag<T> fw[U][RT], fx[U][STEP_MAXBT];
+    Frag<T> fw[U][RT], fx[U][BT];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int chunk = 4 * (s0 + w + KS * u) + (lane >> 4);
@@ -66,7 +66,7 @@ __device__ __forceinline__ void step_contract(const T* const (&wrow)[RT], int w0
         const T* a = first ? a0 : a1;
         const int lda = first ? lda0 : lda1;
 #pragma unroll
-        for (int b = 0; b < STEP_MAXBT; ++b) {
+        for (int b = 0; b < BT; ++b) {
           if (b < nbt) fx[u][b].load(a + (size_t)min(brow + 16 * b, Bp - 1) * lda + kk);
           else fx[u][b].zero();
         }
@@ -74,7 +74,7 @@ __device__ __forceinline__ void step_contract(const T* const (&wrow)[RT], int w0
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) fw[u][rt].zero();
 #pragma unroll
-        for (int b = 0; b < STEP_MAXBT; ++b) fx[u][b].zero();
+        for (int b = 0; b < BT; ++b) fx[u][b].zero();
       }
     }
 #pragma unroll
@@ -82,21 +82,21 @@ __device__ __forceinline__ void step_contract(const T* const (&wrow)[RT], int w0
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-        for (int b = 0; b < STEP_MAXBT; ++b) mma16(acc[rt][b], fw[u][rt], fx[u][b]);
+        for (int b = 0; b < BT; ++b) mma16(acc[rt][b], fw[u][rt], fx[u][b]);
   }
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-    for (int b = 0; b < STEP_MAXBT; ++b)
-      *reinterpret_cast<v4f*>(red + (((w * RT + rt) * STEP_MAXBT + b) * 64 + lane) * 4) = acc[rt][b];
+    for (int b = 0; b < BT; ++b)
+      *reinterpret_cast<v4f*>(red + (((w * RT + rt) * BT + b) * 64 + lane) * 4) = acc[rt][b];
   __syncthreads();
 }
-template <int RT, int KS>
+template <int RT, int KS, int BT = STEP_MAXBT>
 __device__ __forceinline__ v4f step_tile_sum(const float* red, int rt, int bt) {
   const int lane = threadIdx.x & 63;
   v4f r = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int k = 0; k < KS; ++k) r += *reinterpret_cast<const v4f*>(red + (((k * RT + rt) * STEP_MAXBT + bt) * 64 + lane) * 4);
+  for (int k = 0; k < KS; ++k) r += *reinterpret_cast<const v4f*>(red + (((k * RT + rt) * BT + bt) * 64 + lane) * 4);
   return r;
 }
 
@@ -155,10 +155,13 @@ __device__ __forceinline__ void cell_finish(const LstmFwdDir& d, int b, int u, i
   }
 }
 
-// RT row tiles = 4 * RT hidden units x 4 gates per workgroup; the whole k range inside the workgroup.
-template <typename T, int RT, int KS, int U>
+// RT row tiles = 4 * RT hidden units x 4 gates, and BT batch tiles of 16 sentences, per workgroup; the
+// whole k range inside the workgroup.  Per workgroup RT weight slabs and BT activation slabs cross L2:
+// for 64 sentences RT = BT = 2 moves the fewest bytes (each weight slab is then read by two workgroups,
+// which the XCD-aware numbering puts on the same L2).
+template <typename T, int RT, int KS, int U, int BT>
 __global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(LstmFwdArgs args, int Bp, int Hh, StepGrid sg, int ndir) {
-  __shared__ __align__(16) float red[KS * RT * STEP_MAXBT * 256];
+  __shared__ __align__(16) float red[KS * RT * BT * 256];
   int x, kb, z;
   if (!decode_block(sg, x, kb, z)) return;
   const int nxd = sg.nx / ndir;                    // unit blocks per direction
@@ -166,8 +169,8 @@ __global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(LstmFwdArgs args, int
   const LstmFwdDir& d = args.d[dir];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int u0 = (x - dir * nxd) * 4 * RT;
-  const int bt0 = z * STEP_MAXBT;
-  const int nbt = min(STEP_MAXBT, (Bp + 15) / 16 - bt0);
+  const int bt0 = z * BT;
+  const int nbt = min(BT, (Bp + 15) / 16 - bt0);
   // row m = lane % 16 of row tile rt: gate m % 4 of unit u0 + 4 * rt + m / 4
   const int m = lane & 15;
   const T* wrow[RT];
@@ -177,18 +180,18 @@ __global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(LstmFwdArgs args, int
   // the first tile this wavefront will finish: fetch its cell inputs now
   CellIn in0;
   bool have0 = false;
-  if (w < RT * STEP_MAXBT) {
-    const int rt = w / STEP_MAXBT, bt = w - rt * STEP_MAXBT;
+  if (w < RT * BT) {
+    const int rt = w / BT, bt = w - rt * BT;
     const int u = u0 + 4 * rt + (lane >> 4), b = 16 * (bt0 + bt) + (lane & 15);
     have0 = bt < nbt && u < Hh && b < Bp;
     if (have0) in0 = cell_load(d, b, u, Hh, sizeof(T) == 2);
   }
-  step_contract<T, RT, KS, U>(wrow, d.wx_off, d.wh_off, (const T*)d.x, d.ldx, d.Kx, (const T*)d.hprev, d.ldh, Hh, Bp, bt0,
+  step_contract<T, RT, KS, U, BT>(wrow, d.wx_off, d.wh_off, (const T*)d.x, d.ldx, d.Kx, (const T*)d.hprev, d.ldh, Hh, Bp, bt0,
                               nbt, red);
-  for (int t = w; t < RT * STEP_MAXBT; t += KS) {
-    const int rt = t / STEP_MAXBT, bt = t - rt * STEP_MAXBT;
+  for (int t = w; t < RT * BT; t += KS) {
+    const int rt = t / BT, bt = t - rt * BT;
     if (bt >= nbt) continue;
-    const v4f pre = step_tile_sum<RT, KS>(red, rt, bt);
+    const v4f pre = step_tile_sum<RT, KS, BT>(red, rt, bt);
     const int u = u0 + 4 * rt + (lane >> 4);
     const int b = 16 * (bt0 + bt) + (lane & 15);
     if (u >= Hh || b >= Bp) continue;
@@ -215,11 +218,11 @@ __global__ __launch_bounds__(256) void lstm_cell_kernel(LstmFwdArgs args, int Bp
   cell_finish(d, b, u, Hh, p, cell_load(d, b, u, Hh, sizeof(T) == 2), sizeof(T) == 2);
 }
 
-template <typename T, int RT, int KS, int U>
+template <typename T, int RT, int KS, int U, int BT = STEP_MAXBT>
 static void lstm_fwd_go(const LstmFwdArgs& a, int Bp, int Hh, int ndir, hipStream_t st) {
   const int nbt = (Bp + 15) / 16;
-  StepGrid sg{((Hh + 4 * RT - 1) / (4 * RT)) * ndir, 1, (nbt + STEP_MAXBT - 1) / STEP_MAXBT};
-  hipLaunchKernelGGL((lstm_fwd_kernel<T, RT, KS, U>), dim3(step_grid_blocks(sg)), dim3(64 * KS), 0, st, a, Bp, Hh, sg, ndir);
+  StepGrid sg{((Hh + 4 * RT - 1) / (4 * RT)) * ndir, 1, (nbt + BT - 1) / BT};
+  hipLaunchKernelGGL((lstm_fwd_kernel<T, RT, KS, U, BT>), dim3(step_grid_blocks(sg)), dim3(64 * KS), 0, st, a, Bp, Hh, sg, ndir);
 }
 
 // Ways to run the step: the fused kernel above with 16 / 32 / 64 gate rows per workgroup (one
@@ -240,7 +243,10 @@ void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh,
     if (i < ndir && dirs[i].Kx + Hh > K) K = dirs[i].Kx + Hh;      // instances may differ in their input width
   }
   int how = g_lstm_fwd_how;
-  if (how == 0) how = (Bp > 64) ? 2 : 1;           // measured: 32 gate rows per workgroup win once the batch exceeds 64
+  const int nbt = (Bp + 15) / 16;
+  // measured (bf16, hidden 1024): 64 sentences — 32 gate rows x 32 sentences per workgroup: 9.9 us against
+  // 11.3 us for 16 rows x 64 sentences; more than 64 sentences — 32 rows x 64 sentences
+  if (how == 0) how = (Bp > 64) ? 2 : (prec && nbt == 4) ? 6 : 1;   // (32 sentences: 16 rows x 32 sentences is faster)
   if (how == 9) {
     int np = 1;
     for (int i = 0; i < ndir; ++i) {
@@ -260,7 +266,12 @@ void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh,
   }
   const int nsteps = (K / 8 + 3) / 4;
   if (prec) {
-    if (how == 4) lstm_fwd_go<bf16_t, 4, 8, 4>(a, Bp, Hh, ndir, st);
+    if (how == 6) {
+      if (nsteps > 32) lstm_fwd_go<bf16_t, 2, 8, 4, 2>(a, Bp, Hh, ndir, st);
+      else if (nsteps > 16) lstm_fwd_go<bf16_t, 2, 8, 2, 2>(a, Bp, Hh, ndir, st);
+      else lstm_fwd_go<bf16_t, 2, 4, 2, 2>(a, Bp, Hh, ndir, st);
+    }
+    else if (how == 4) lstm_fwd_go<bf16_t, 4, 8, 4>(a, Bp, Hh, ndir, st);
     else if (how == 2) lstm_fwd_go<bf16_t, 2, 8, 4>(a, Bp, Hh, ndir, st);
     else if (nsteps > 32) lstm_fwd_go<bf16_t, 1, 16, 4>(a, Bp, Hh, ndir, st);
     else if (nsteps > 16) lstm_fwd_go<bf16_t, 1, 16, 2>(a, Bp, Hh, ndir, st);
