@@ -410,6 +410,32 @@ template <typename T>
 __global__ __launch_bounds__(256) void tanh_planes_kernel(Planes p, T* __restrict__ out, int ldo, T* __restrict__ outD, int ldod,
                                                           DropSpec drop, int Bp, int N);
 
+// mode 0 in one launch: 16 weight rows x 16 sentences per workgroup with the whole k range inside it
+// (split over its wavefronts, combined through LDS), tanh and the optional dropped copy in the
+// epilogue.  No planes, no second kernel; each weight slab is read by the batch's 16-sentence groups
+// from the same L2.
+template <typename T, int KS, int U>
+__global__ __launch_bounds__(64 * KS) void step_tanh_kernel(StepGemm g, int Bp, StepGrid sg) {
+  __shared__ __align__(16) float red[KS * 256];
+  int x, kb, z;
+  if (!decode_block(sg, x, kb, z)) return;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int n0 = x * 16;
+  const T* wrow[1] = {(const T*)g.W + (size_t)min(n0 + (lane & 15), g.N - 1) * g.ldw};
+  step_contract<T, 1, KS, U, 1>(wrow, g.w0_off, g.w1_off, (const T*)g.a0, g.lda0, g.K0, (const T*)g.a1, g.lda1, g.K1, Bp, z, 1, red);
+  if (w != 0) return;
+  const v4f r = step_tile_sum<1, KS, 1>(red, 0, 0);
+  const int n = n0 + 4 * (lane >> 4), b = 16 * z + (lane & 15);
+  if (b >= Bp) return;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (n + i < g.N) {
+      const float hv = tanhf(r[i]);
+      ((T*)g.outT)[(size_t)b * g.ldo + n + i] = from_f<T>(hv);
+      if (g.outD) ((T*)g.outD)[(size_t)b * g.ldod + n + i] = from_f<T>(hv * drop_factor(g.drop, b, n + i));
+    }
+}
+
 // n instances in one launch (blockIdx.y); they share the contraction length and the k-block plan,
 // which is the plan of the widest instance.
 void launch_step_gemm_multi(int prec, const StepGemm* gs, int n, int n_plan, int Bp, hipStream_t st) {
@@ -431,8 +457,23 @@ void launch_step_gemm_multi(int prec, const StepGemm* gs, int n, int n_plan, int
 #undef GO
 }
 
+static int g_step_tanh = -1;
 void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st) {
   const int nbt = (Bp + 15) / 16;
+  if (g_step_tanh < 0) {
+    const char* e = getenv("CMT_STEP_TANH");
+    g_step_tanh = e ? atoi(e) : 1;
+  }
+  if (g.mode == 0 && g_step_tanh) {
+    StepGrid sg{(g.N + 15) / 16, 1, nbt};
+    const dim3 grid(step_grid_blocks(sg));
+    const int nsteps = ((g.K0 + g.K1) / 8 + 3) / 4;
+#define GO(TT, KS, UU) hipLaunchKernelGGL((step_tanh_kernel<TT, KS, UU>), grid, dim3(64 * KS), 0, st, g, Bp, sg)
+    if (prec) { if (nsteps > 32) GO(bf16_t, 16, 4); else if (nsteps > 16) GO(bf16_t, 16, 2); else GO(bf16_t, 8, 2); }
+    else { if (nsteps > 16) GO(float, 16, 2); else GO(float, 8, 2); }
+#undef GO
+    return;
+  }
   const Step2dPlan pl = plan2d(prec, g.N, g.K0 + g.K1, Bp, g.max_kb);
   StepGrid sg{(g.N + 63) / 64, pl.kb, (nbt + STEP_MAXBT - 1) / STEP_MAXBT};
   const dim3 grid(step_grid_blocks(sg));
