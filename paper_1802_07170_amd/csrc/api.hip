@@ -111,6 +111,9 @@ struct cmt_handle {
   int use_side = 1;
   char* dzs2 = nullptr; char* dzTs2 = nullptr; float* gsplit2 = nullptr;
   int kb_bwd = 0, kb_wc = 0;            // caps on the k blocks of the backward step GEMMs (0 = default)
+  // phase timing of a step on the caller's stream (measurement aid, env CMT_PHASE_TIMING=1)
+  int phase_timing = 0;
+  std::vector<hipEvent_t> phase_ev; std::vector<const char*> phase_name; size_t phase_n = 0;
   // regularisation of the next steps (cmt_set_regularization)
   float drop_p = 0.f, drop_scale = 1.f, ls_eps = 0.f;
   unsigned drop_thresh = 0; unsigned long long drop_seed = 0;
@@ -304,6 +307,18 @@ void weight_grads(cmt_handle* h, LD& d, int Lsteps, const std::vector<std::pair<
   launch_colsum(p, d.dG, d.pg, M, 4 * Hh, h->colscr, h->grads + d.b_off, st);
 }
 
+// marks the start of a phase of the step on the caller's stream (only when phase timing is on)
+void phase_mark(cmt_handle* h, const char* name) {
+  if (!h->phase_timing) return;
+  if (h->phase_n >= h->phase_ev.size()) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return;
+    h->phase_ev.push_back(e); h->phase_name.push_back(name);
+  }
+  h->phase_name[h->phase_n] = name;
+  (void)hipEventRecord(h->phase_ev[h->phase_n++], h->st);
+}
+
 // The output layer's slabs: full slabs of CE_SLAB_ROWS rows and one remainder.  With 256 x 256 logit
 // tiles a full slab gives (V / 256) * 4 tiles, close to a whole number of rounds over the 256 CUs for
 // the vocabulary sizes of interest (32000: 500 tiles = 1.95 rounds), which equal-sized smaller slabs
@@ -372,6 +387,8 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   float* G = h->grads;
   float* P = h->params;
 
+  h->phase_n = 0;
+  phase_mark(h, "gathers + encoder bottom layer");
   launch_fill_f32((float*)h->flags, 1, 0.f, st);
   // ---- embeddings, masks ------------------------------------------------------------------------
   launch_gather(p, h->Pw(h->off_Esrc), c.src_vocab, E, src_ids, src_len, B, Bp, S, 0, 0, h->Xs, h->mask_s, h->tok_s,
@@ -406,6 +423,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     }
     launch_lstm_fwd(p, d, 2, Bp, Hd, st);
   }
+  phase_mark(h, "encoder upper layers");
   // ---- encoder layers >= 1: a wavefront over (layer, position) ------------------------------------
   // Layer l at position t needs layer l-1 at t and itself at t-1, so all layers advance together
   // along diagonals: one launch carries up to L-1 layer-steps (S + L - 2 launches instead of
@@ -449,6 +467,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   // attention keys K_i = W_a^T H_s^i for all i at once (Eq. 4 regrouped)
   launch_gemm_nt(p, Hs, ldHs, h->WaT, H, Ms, H, H, nullptr, h->Kmat, H, nullptr, 0, st);
 
+  phase_mark(h, "keys, decoder init, decoder input GEMM");
   // ---- decoder initial state = encoder final state of the same depth ------------------------------
   {
     LD& d0 = h->dec[0];
@@ -468,6 +487,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     launch_gemm_nt(p, h->Xt, E, d0.W, E + 2 * H, Mt, 4 * H, E, d0.Gx, nullptr, 4 * H, P + d0.b_off, 0, st);
     launch_fill_T(p, h->HoBuf, BP, st);
     if (drop) launch_fill_T(p, h->HoDrop, BP, st);
+    phase_mark(h, "decoder forward loop");
     for (int j = 0; j < T; ++j) {
       for (int l = 0; l < L; ++l) dec_lstm_fwd(h, l, j);
       const char* Ht = h->dec[L - 1].Hst + (j + 1) * BP * esz;
@@ -483,6 +503,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       launch_step_gemm(p, g, Bp, st);
     }
   }
+  phase_mark(h, "output layer forward + backward");
   // =================================== output layer (Eq. 1) and backward ==============================
   // The recurrences' backward loops are chains of short dependent kernels that leave most of the
   // chip idle; everything that does not feed them (transposes, weight gradients, dW_o, embedding
@@ -544,6 +565,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     launch_ce_loss(h->nll, Mt, h->loss, h->flags, st);
   }
 
+  phase_mark(h, "decoder backward loop");
   // ---- decoder loop backwards -----------------------------------------------------------------------
   for (int l = 0; l < L; ++l) { launch_fill_f32(h->dec[l].dh, BH, 0.f, st); launch_fill_f32(h->dec[l].dc, BH, 0.f, st); }
   const int kbd = step_kblocks(p, 2 * H, 4 * H, Bp, h->kb_bwd);       // planes written by a decoder layer's backward GEMM
@@ -589,6 +611,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   for (int l = 0; l < L; ++l)
     launch_planes_add(h->dec[l].dh, h->dec[l].dh, Planes{h->dec[l].bwdp, 2 * H, kbd, pstr}, H, Bp, H, st);
 
+  phase_mark(h, "deferred attention gradients");
   // ---- second stream: everything that only needed the decoder's dgates and dpre -----------------------
   stream_after(h, sd, st);
   launch_transpose(p, h->dPre, PH, h->dPreT, Mt, Mt, H, sd);
@@ -625,6 +648,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     launch_gemm_nt(p, HsT, ld, h->dKT, Ms, H, H, Ms, G + h->off_Wa, nullptr, H, nullptr, 0, sd, h->gsplit2, h->gsplit_floats);
   }
 
+  phase_mark(h, "encoder upper layers backward");
   // ---- encoder backwards ------------------------------------------------------------------------------
   // Upper layers: the same wavefront, top layer first.  Per diagonal one pointwise launch (cell
   // backward of every active layer-step) and one step-GEMM launch ([dx; dh_prev] = dgates [W_x; W_h]).
@@ -673,6 +697,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       weight_grads(h, e, S, {{XT, ld}, {e.HstT, (S + 1) * Bp}}, {H, H}, sd);
     }
   }
+  phase_mark(h, "encoder bottom layer backward");
   {   // bottom layer: the two directions run in the same launches
     const float* dY0 = L > 1 ? h->dYa : h->dHs;
     LD& d0 = h->dec[0];
@@ -713,7 +738,9 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     launch_gemm_nt(p, eb.dG, eb.pg, eb.Wt, 4 * Hd, Ms, E, 4 * Hd, h->dXs, nullptr, E, nullptr, 1, sd);
     launch_embed_scatter(h->dXs, h->tok_s, Ms, c.src_vocab, E, G + h->off_Esrc, sd);
   }
+  phase_mark(h, "wait for the second stream");
   stream_after(h, st, sd);                         // join: the step is complete on the caller's stream
+  phase_mark(h, "end");
   (void)hipMemcpyAsync(h->h_loss, h->loss, 2 * sizeof(float), hipMemcpyDeviceToHost, st);
   (void)hipMemcpyAsync(h->h_flags, h->flags, sizeof(int), hipMemcpyDeviceToHost, st);
   hipError_t e = hipGetLastError();
@@ -757,6 +784,7 @@ int cmt_create(const cmt_config* cfg, void* params_dev, void* grads_dev, void* w
     const char* k1 = getenv("CMT_KB_BWD"); h->kb_bwd = k1 ? atoi(k1) : 0;
     const char* k2 = getenv("CMT_KB_WC"); h->kb_wc = k2 ? atoi(k2) : 2;
     const char* k3 = getenv("CMT_SIDE_STREAM"); h->use_side = k3 ? atoi(k3) : 1;
+    const char* k4 = getenv("CMT_PHASE_TIMING"); h->phase_timing = k4 ? atoi(k4) : 0;
   }
   build_table(h->cfg, h->table, h->nparams);
   h->ws_bytes = layout(h, h->ws);
@@ -840,6 +868,16 @@ int cmt_fetch_loss(cmt_handle* h, float* loss_host) {
   if (!h->have_step) return fail(h, CMT_EINVAL, "no step has been run");
   hipError_t e = hipStreamSynchronize(h->st);
   if (e != hipSuccess) return hip_fail(h, e, "cmt_fetch_loss");
+  if (h->phase_timing && h->phase_n > 1) {          // phases of the last step, as the caller's stream saw them
+    float total = 0.f;
+    for (size_t i = 0; i + 1 < h->phase_n; ++i) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, h->phase_ev[i], h->phase_ev[i + 1]) != hipSuccess) break;
+      fprintf(stderr, "[cytonmt_hip] %-40s %8.3f ms\n", h->phase_name[i], ms);
+      total += ms;
+    }
+    fprintf(stderr, "[cytonmt_hip] %-40s %8.3f ms\n", "step", total);
+  }
   const int flags = *h->h_flags;
   if (loss_host) *loss_host = h->h_loss[0];
   if (flags & 3) return fail(h, CMT_ERANGE, (flags & 1) ? "a token id is outside its vocabulary" : "a length is outside [1, padded length]");
