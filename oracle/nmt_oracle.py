@@ -22,6 +22,9 @@ The backward pass is written by hand from these definitions: a weight used at ev
 per-step gradients (the paper's calculateGradient accumulates with beta = 1), and a value with two
 consumers sums their gradients (the paper's DuplicateLayer).
 
+greedy_decode is the forward-only companion (hyperparameter table: beam search, here with beam
+size 1): the same encoder and decoder step, the arg-max token fed back.
+
 Regularisation of the Settings section / hyperparameter table (both off by default):
   * dropout p on the hidden states passed from a recurrent layer to the layer above it (encoder and
     decoder, every layer but the top one; the recurrent connection itself is not dropped) and on
@@ -398,6 +401,61 @@ def train_step(cfg, params, src_ids, src_len, tgt_ids, tgt_len, bos_id=2, logit_
             enc_y=enc_Y, enc_final=enc_fin,
         )
     return loss, g, inter
+
+
+def greedy_decode(cfg, params, src_ids, src_len, max_len, bos_id=2, eos_id=3, pad_id=0):
+    """Forward-only translation with the arg-max token fed back (beam size 1; no dropout).
+
+    The encoder and one decoder step are exactly those of train_step.  At step j the decoder input is
+    BOS (j = 0) or the previous output token; the output token is argmax_v (W_o H_o + B_o)_v, the
+    lowest index winning a tie.  A sentence ends with the step that emits eos_id (kept in the output)
+    or at step max_len - 1.  Returns ids [B, max_len] (pad_id after the end), lengths [B], and for
+    every emitted token the gap between the best and second-best logit [B, max_len] (inf after the
+    end), which tells a parity test how close to a tie a decision was."""
+    p = {k: np.asarray(v, F64) for k, v in params.items()}
+    src_ids = np.asarray(src_ids)
+    B, S = src_ids.shape
+    H, L = cfg["hidden"], cfg["layers"]
+    Hd = H // 2
+    src_mask, _ = make_masks(src_len, np.ones(B, int), S, 1)
+    Xs = p["E_src"][src_ids.T]
+    z_d = np.zeros((B, Hd), F64)
+    z_h = np.zeros((B, H), F64)
+    Yf, hf, cf, _ = lstm_forward(Xs, src_mask, p["enc.l0.fwd.W"], p["enc.l0.fwd.b"], z_d, z_d)
+    Yb, hb, cb, _ = lstm_forward(Xs, src_mask, p["enc.l0.bwd.W"], p["enc.l0.bwd.b"], z_d, z_d, reverse=True)
+    Y = np.concatenate([Yf, Yb], axis=2)
+    h = [np.concatenate([hf, hb], axis=1)]
+    c = [np.concatenate([cf, cb], axis=1)]
+    for l in range(1, L):
+        Y, hl, cl, _ = lstm_forward(Y, src_mask, p[f"enc.l{l}.W"], p[f"enc.l{l}.b"], z_h, z_h)
+        h.append(hl)
+        c.append(cl)
+    Hs = Y
+    ids = np.full((B, max_len), pad_id, np.int64)
+    lens = np.zeros(B, np.int64)
+    gaps = np.full((B, max_len), np.inf)
+    done = np.zeros(B, bool)
+    tok = np.full(B, bos_id, np.int64)
+    Ho = z_h
+    ones = np.ones((B, 1), F64)
+    for j in range(max_len):
+        x = np.concatenate([p["E_tgt"][tok], Ho], axis=1)
+        for l in range(L):
+            _, h[l], c[l], _ = masked_step_forward(x, h[l], c[l], ones, p[f"dec.l{l}.W"], p[f"dec.l{l}.b"])
+            x = h[l]
+        Ho, _ = attention_forward(Hs, src_mask, h[L - 1], p["W_a"], p["W_c"])
+        z = Ho @ p["W_o"].T + p["B_o"]
+        tok = z.argmax(axis=1)                       # first maximum = lowest index
+        top2 = np.partition(z, -2, axis=1)[:, -2:]
+        for b in range(B):
+            if done[b]:
+                continue
+            ids[b, j] = tok[b]
+            gaps[b, j] = top2[b, 1] - top2[b, 0]
+            if tok[b] == eos_id or j == max_len - 1:
+                done[b] = True
+                lens[b] = j + 1
+    return ids, lens, gaps
 
 
 def sgd_update(params, grads, lr):

@@ -367,36 +367,21 @@ void dec_lstm_fwd(cmt_handle* h, int l, int j) {
   launch_lstm_fwd(h->prec, &d, 1, Bp, H, h->st);
 }
 
-int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, const int32_t* tgt_ids,
-                 const int32_t* tgt_len, int B, int S, int T) {
+// Encoder forward for the batch whose source embeddings, masks and lengths are in the workspace
+// (gather done by the caller): bottom layer (both directions per launch), upper layers as a
+// wavefront, attention keys, and the decoder's initial states.  Returns H_s (top-layer states) and
+// its row pitch.
+void enqueue_encoder(cmt_handle* h, int S, const char** Hs_out, int* ldHs_out) {
   const cmt_config& c = h->cfg;
-  if (!src_ids || !src_len || !tgt_ids || !tgt_len) return fail(h, CMT_EINVAL, "null input pointer");
-  if (B < 1 || B > c.max_batch || S < 1 || S > c.max_src_len || T < 1 || T > c.max_tgt_len)
-    return fail(h, CMT_EINVAL, "B, S or T outside [1, configured maximum]");
-  const int p = h->prec, E = c.emb_dim, H = c.hidden, Hd = H / 2, L = c.layers, V = c.tgt_vocab;
-  const int Bp = round_up(B, 16);
+  const int p = h->prec, E = c.emb_dim, H = c.hidden, Hd = H / 2, L = c.layers, Bp = h->Bp;
   const size_t esz = h->esz;
   hipStream_t st = h->st;
-  h->B = B; h->Bp = Bp; h->S = S; h->T = T;
-  const int Ms = S * Bp, Mt = T * Bp;
+  const int Ms = S * Bp;
   const size_t BH = (size_t)Bp * H;
-  const int PH = h->PH;                            // row pitch of the H-wide per-step operands
+  const int PH = h->PH;
   const bool drop = h->drop_p > 0.f;
-  char* HoFeed = drop ? h->HoDrop : h->HoBuf;      // H_o as its consumers (output layer, input feed) see it
   const size_t BP = (size_t)Bp * PH;
-  float* G = h->grads;
   float* P = h->params;
-
-  h->phase_n = 0;
-  phase_mark(h, "gathers + encoder bottom layer");
-  launch_fill_f32((float*)h->flags, 1, 0.f, st);
-  // ---- embeddings, masks ------------------------------------------------------------------------
-  launch_gather(p, h->Pw(h->off_Esrc), c.src_vocab, E, src_ids, src_len, B, Bp, S, 0, 0, h->Xs, h->mask_s, h->tok_s,
-                nullptr, h->len_s, h->flags, st);
-  launch_gather(p, h->Pw(h->off_Etgt), c.tgt_vocab, E, tgt_ids, tgt_len, B, Bp, T, 1, c.bos_id, h->Xt, h->mask_t,
-                h->tok_t, h->labels, h->len_t, h->flags, st);
-  launch_ce_rowscale(h->mask_t, Mt, h->rowscale, h->loss, st);   // n_tok and mask / n_tok: the lengths give them
-
   // ---- encoder layer 0: two directions ------------------------------------------------------------
   LD& ef = h->enc[0]; LD& eb = h->enc[1];
   for (LD* d : {&ef, &eb})
@@ -464,6 +449,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   }
   const char* Hs = Yprev;
   const int ldHs = ldY;                          // source-side top-layer states [S, Bp, H]
+  *Hs_out = Hs; *ldHs_out = ldHs;
   // attention keys K_i = W_a^T H_s^i for all i at once (Eq. 4 regrouped)
   launch_gemm_nt(p, Hs, ldHs, h->WaT, H, Ms, H, H, nullptr, h->Kmat, H, nullptr, 0, st);
 
@@ -481,6 +467,42 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       launch_copy2d_f32(e.Cst + (size_t)S * BH, H, d.Cst, H, Bp, H, st);
     }
   }
+}
+
+int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, const int32_t* tgt_ids,
+                 const int32_t* tgt_len, int B, int S, int T) {
+  const cmt_config& c = h->cfg;
+  if (!src_ids || !src_len || !tgt_ids || !tgt_len) return fail(h, CMT_EINVAL, "null input pointer");
+  if (B < 1 || B > c.max_batch || S < 1 || S > c.max_src_len || T < 1 || T > c.max_tgt_len)
+    return fail(h, CMT_EINVAL, "B, S or T outside [1, configured maximum]");
+  const int p = h->prec, E = c.emb_dim, H = c.hidden, Hd = H / 2, L = c.layers, V = c.tgt_vocab;
+  const int Bp = round_up(B, 16);
+  const size_t esz = h->esz;
+  hipStream_t st = h->st;
+  h->B = B; h->Bp = Bp; h->S = S; h->T = T;
+  const int Ms = S * Bp, Mt = T * Bp;
+  const size_t BH = (size_t)Bp * H;
+  const int PH = h->PH;                            // row pitch of the H-wide per-step operands
+  const bool drop = h->drop_p > 0.f;
+  char* HoFeed = drop ? h->HoDrop : h->HoBuf;      // H_o as its consumers (output layer, input feed) see it
+  const size_t BP = (size_t)Bp * PH;
+  float* G = h->grads;
+  float* P = h->params;
+
+  h->phase_n = 0;
+  phase_mark(h, "gathers + encoder bottom layer");
+  launch_fill_f32((float*)h->flags, 1, 0.f, st);
+  // ---- embeddings, masks ------------------------------------------------------------------------
+  launch_gather(p, h->Pw(h->off_Esrc), c.src_vocab, E, src_ids, src_len, B, Bp, S, 0, 0, h->Xs, h->mask_s, h->tok_s,
+                nullptr, h->len_s, h->flags, st);
+  launch_gather(p, h->Pw(h->off_Etgt), c.tgt_vocab, E, tgt_ids, tgt_len, B, Bp, T, 1, c.bos_id, h->Xt, h->mask_t,
+                h->tok_t, h->labels, h->len_t, h->flags, st);
+  launch_ce_rowscale(h->mask_t, Mt, h->rowscale, h->loss, st);   // n_tok and mask / n_tok: the lengths give them
+
+  const char* Hs; int ldHs;                        // source-side top-layer states [S, Bp, H] and their row pitch
+  enqueue_encoder(h, S, &Hs, &ldHs);
+  LD& ef = h->enc[0]; LD& eb = h->enc[1];
+  const size_t BHd = (size_t)Bp * Hd;
   // ---- decoder time loop --------------------------------------------------------------------------
   {
     LD& d0 = h->dec[0];

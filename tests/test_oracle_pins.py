@@ -434,6 +434,46 @@ def test_label_smoothed_output_layer_matches_torch_and_closed_forms():
     np.testing.assert_allclose(row0, math.log(V), rtol=1e-14)
 
 
+# ---------------------------------------------------------------------------------------------
+# greedy decoding
+# ---------------------------------------------------------------------------------------------
+def test_greedy_decode_is_the_training_forward_with_its_own_output_fed_back():
+    """Teacher-forcing consistency: running the (pinned) training forward on the greedy output
+    reproduces the decoder states, and every emitted token is the arg-max of that forward's logits."""
+    cfg = tiny_cfg(H=8, E=5, V=13, L=2)
+    p = rand_params(cfg, seed=41, scale=0.8)
+    src, sl, _, _ = tiny_batch(cfg, seed=5)
+    max_len, eos = 6, 3
+    ids, lens, gaps = O.greedy_decode(cfg, p, src, sl, max_len, bos_id=2, eos_id=eos)
+    assert ids.shape == (3, max_len) and np.all((lens >= 1) & (lens <= max_len))
+    tgt = ids.copy()
+    _, _, it = O.train_step(cfg, p, src, sl, tgt, lens, want_intermediates=True)
+    z = it["h_o"] @ p["W_o"].T + p["B_o"]                        # [T,B,V]
+    for b in range(3):
+        for j in range(lens[b]):
+            assert z[j, b].argmax() == ids[b, j]
+            srt = np.sort(z[j, b])
+            assert abs((srt[-1] - srt[-2]) - gaps[b, j]) < 1e-12
+        assert np.all(ids[b, lens[b]:] == 0)                     # padding after the end
+        assert lens[b] == max_len or ids[b, lens[b] - 1] == eos
+        assert not np.any(ids[b, :lens[b] - 1] == eos)           # nothing is emitted after an end token
+
+
+def test_greedy_decode_end_token_and_length_cap():
+    cfg = tiny_cfg(H=4, L=1)
+    p = rand_params(cfg, seed=42)
+    src, sl, _, _ = tiny_batch(cfg)
+    p["B_o"] = p["B_o"].copy(); p["B_o"][3] = 1e3               # the end token always wins
+    ids, lens, _ = O.greedy_decode(cfg, p, src, sl, 5, eos_id=3)
+    assert np.all(lens == 1) and np.all(ids[:, 0] == 3) and np.all(ids[:, 1:] == 0)
+    p["B_o"][3] = -1e3                                           # the end token never wins: the cap ends it
+    ids, lens, _ = O.greedy_decode(cfg, p, src, sl, 5, eos_id=3)
+    assert np.all(lens == 5) and not np.any(ids == 3)
+    # sentences are independent: decoding one alone gives its row of the batch result
+    one, l1, _ = O.greedy_decode(cfg, p, src[1:2, :sl[1]], sl[1:2], 5, eos_id=3)
+    assert np.array_equal(one[0], ids[1]) and l1[0] == lens[1]
+
+
 def test_intermediates_are_consistent():
     cfg = tiny_cfg(H=6, L=2)
     p = rand_params(cfg, seed=12)
