@@ -118,6 +118,20 @@ int cmt_get_grads(cmt_handle* h, float* host_dst);
  * Returns CMT_EINVAL for values outside those ranges (the previous setting is kept). */
 int cmt_set_regularization(cmt_handle* h, float dropout, float label_smoothing, uint64_t dropout_seed);
 
+/* Forward-only translation with beam size 1 (the hyperparameter table's beam search reduced to its
+ * first hypothesis): the encoder as in a training step, then max_len decoder steps in which the input
+ * token is bos_id at step 0 and the previous output token afterwards, and the output token is
+ * argmax_v (W_o H_o + B_o)_v, the lowest index winning a tie.  A sentence ends with the step that emits
+ * eos_id (which is kept) or at step max_len - 1.  No dropout, whatever cmt_set_regularization says.
+ *   src_ids_dev [B, S] int32 row-major, src_len_dev [B]: as for cmt_train_step (device pointers).
+ *   out_ids_dev [B, max_len] int32 (device): the tokens, pad_id after a sentence's end;
+ *   out_len_dev [B] int32 (device): tokens emitted per sentence, in [1, max_len].
+ * 1 <= max_len <= max_tgt_len.  Synchronises the stream.  Overwrites the intermediates of the last
+ * training step (cmt_debug_fetch needs a new step afterwards); parameters and gradients are untouched.
+ * Errors: CMT_EINVAL (shape / pointer / eos_id), CMT_ERANGE (source id or length out of range). */
+int cmt_greedy_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* src_len_dev, int32_t B, int32_t S,
+                      int32_t max_len, int32_t eos_id, int32_t* out_ids_dev, int32_t* out_len_dev);
+
 /* Plain SGD (hyperparameter table: optimizer SGD, learning rate 1.0): p <- p - lr * g on the flat
  * fp32 master vector, then refreshes the kernels' working copies (bf16 casts, transposes). */
 int cmt_sgd_update(cmt_handle* h, float lr);

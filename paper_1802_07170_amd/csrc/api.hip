@@ -117,6 +117,9 @@ struct cmt_handle {
   // regularisation of the next steps (cmt_set_regularization)
   float drop_p = 0.f, drop_scale = 1.f, ls_eps = 0.f;
   unsigned drop_thresh = 0; unsigned long long drop_seed = 0;
+  // greedy decoding
+  char* xcat = nullptr; int ldxcat = 0; // decoder bottom-layer input [emb(y_{j-1}) ; H_o^{<j-1>}] of the current step
+  int32_t* dec_tok = nullptr; int32_t* dec_done = nullptr; float* dec_mask = nullptr; float* logits = nullptr;
   char* HoDrop = nullptr;               // H_o after dropout: what the output layer and the input feed read
   float* psz = nullptr;                 // per-group sums of logits (label smoothing)
   size_t ws_bytes = 0;
@@ -219,6 +222,11 @@ size_t layout(cmt_handle* h, char* base) {
   h->len_t = (int32_t*)a.take((size_t)Bp * 4);
   h->HoBuf = a.take((Mt + Bp) * PH * esz); h->HoBufT = a.take((Mt + Bp) * H * esz);
   h->HoDrop = a.take((Mt + Bp) * PH * esz);
+  h->ldxcat = E + H + ACT_PAD;
+  h->xcat = a.take((size_t)Bp * h->ldxcat * esz);
+  h->dec_tok = (int32_t*)a.take((size_t)Bp * 4); h->dec_done = (int32_t*)a.take((size_t)Bp * 4);
+  h->dec_mask = (float*)a.take((size_t)Bp * 4);
+  h->logits = (float*)a.take((size_t)Bp * c.tgt_vocab * 4);
   h->Cs = a.take(Mt * PH * esz); h->CsT = a.take(Mt * H * esz);
   h->att_a = (float*)a.take(Mt * Sm * 4); h->att_ds = (float*)a.take(Mt * Sm * 4);
   h->dCs = (float*)a.take(Mt * H * 4);
@@ -912,6 +920,74 @@ int cmt_train_step(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* src
   const int rc = cmt_train_step_async(h, src_ids_dev, src_len_dev, tgt_ids_dev, tgt_len_dev, B, S, T);
   if (rc != CMT_OK) return rc;
   return cmt_fetch_loss(h, loss_host);
+}
+
+int cmt_greedy_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* src_len_dev, int32_t B, int32_t S,
+                      int32_t max_len, int32_t eos_id, int32_t* out_ids_dev, int32_t* out_len_dev) {
+  if (!h) return CMT_EINVAL;
+  const cmt_config& c = h->cfg;
+  if (!src_ids_dev || !src_len_dev || !out_ids_dev || !out_len_dev) return fail(h, CMT_EINVAL, "null pointer");
+  if (B < 1 || B > c.max_batch || S < 1 || S > c.max_src_len || max_len < 1 || max_len > c.max_tgt_len)
+    return fail(h, CMT_EINVAL, "B, S or max_len outside [1, configured maximum]");
+  if (eos_id < 0 || eos_id >= c.tgt_vocab) return fail(h, CMT_EINVAL, "eos_id outside the target vocabulary");
+  const int p = h->prec, E = c.emb_dim, H = c.hidden, L = c.layers, V = c.tgt_vocab;
+  const int Bp = round_up(B, 16);
+  const size_t esz = h->esz;
+  hipStream_t st = h->st;
+  h->B = B; h->Bp = Bp; h->S = S; h->T = max_len;
+  h->have_step = false;                              // the training step's intermediates are overwritten
+  h->phase_n = 0;
+  const int PH = h->PH;
+  const size_t BP = (size_t)Bp * PH, BH = (size_t)Bp * H;
+  const float keep_p = h->drop_p;
+  h->drop_p = 0.f;                                   // inference: no dropout
+  launch_fill_f32((float*)h->flags, 1, 0.f, st);
+  launch_gather(p, h->Pw(h->off_Esrc), c.src_vocab, E, src_ids_dev, src_len_dev, B, Bp, S, 0, 0, h->Xs, h->mask_s, h->tok_s,
+                nullptr, h->len_s, h->flags, st);
+  const char* Hs; int ldHs;
+  enqueue_encoder(h, S, &Hs, &ldHs);
+  launch_dec_init(B, Bp, max_len, c.bos_id, c.pad_id, h->dec_tok, h->dec_done, out_ids_dev, out_len_dev, h->dec_mask, st);
+  launch_fill_T(p, h->xcat, (size_t)Bp * h->ldxcat, st);              // H_o^{<-1>} = 0
+  for (int j = 0; j < max_len; ++j) {
+    launch_dec_embed(p, h->Pw(h->off_Etgt), E, h->dec_tok, B, Bp, h->xcat, h->ldxcat, st);
+    for (int l = 0; l < L; ++l) {
+      LD& e = h->dec[l];
+      LstmFwdDir d;
+      if (l == 0) { d.x = h->xcat; d.ldx = h->ldxcat; d.Kx = E + H; d.wx_off = 0; d.wh_off = E + H; d.ldw = E + 2 * H; }
+      else { d.x = h->dec[l - 1].Hst + (j + 1) * BP * esz; d.ldx = e.ph; d.Kx = H; d.wx_off = 0; d.wh_off = H; d.ldw = 2 * H; }
+      d.gx = nullptr; d.ldgx = 0; d.bias = h->params + e.b_off;
+      d.hprev = e.Hst + j * BP * esz; d.ldh = e.ph; d.W = e.W;
+      d.cprev = e.Cst + j * BH; d.mask = h->dec_mask;
+      d.hnext = e.Hst + (j + 1) * BP * esz; d.ldhn = e.ph; d.cnext = e.Cst + (j + 1) * BH;
+      d.gsave = e.Gs + (size_t)j * Bp * 4 * H; d.ycat = nullptr; d.ldy = 0; d.part = e.part;
+      launch_lstm_fwd(p, &d, 1, Bp, H, st);
+    }
+    const char* Ht = h->dec[L - 1].Hst + (j + 1) * BP * esz;
+    launch_att_fwd(p, h->Kmat, H, Hs, ldHs, Ht, PH, h->len_s, S, Bp, H, h->dots, h->att_a + (size_t)j * Bp * S, h->Cs + j * BP * esz,
+                   PH, st);
+    StepGemm g{};                                   // H_o = tanh(W_c [C_s; H_t]) straight into the next step's input
+    g.a0 = h->Cs + j * BP * esz; g.lda0 = PH; g.K0 = H; g.w0_off = 0;
+    g.a1 = Ht; g.lda1 = PH; g.K1 = H; g.w1_off = H;
+    g.W = h->Pw(h->off_Wc); g.ldw = 2 * H; g.N = H; g.mode = 0;
+    g.outT = h->xcat + (size_t)E * esz; g.ldo = h->ldxcat;
+    g.out = h->wcp; g.ldout = H; g.plane_stride = BH;
+    launch_step_gemm(p, g, Bp, st);
+    StepGemm z{};                                   // logits (without the bias) = H_o W_o^T
+    z.a0 = h->xcat + (size_t)E * esz; z.lda0 = h->ldxcat; z.K0 = H; z.w0_off = 0; z.K1 = 0;
+    z.W = h->Pw(h->off_Wo); z.ldw = H; z.N = V; z.mode = 1; z.max_kb = 1;
+    z.out = h->logits; z.ldout = V; z.plane_stride = (size_t)Bp * V;
+    launch_step_gemm(p, z, Bp, st);
+    launch_dec_argmax(h->logits, V, h->params + h->off_Bo, V, B, j, max_len, eos_id, h->dec_tok, h->dec_done, out_ids_dev,
+                      out_len_dev, st);
+  }
+  h->drop_p = keep_p;
+  (void)hipMemcpyAsync(h->h_flags, h->flags, sizeof(int), hipMemcpyDeviceToHost, st);
+  hipError_t e = hipStreamSynchronize(st);
+  if (e == hipSuccess) e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(h, e, "cmt_greedy_decode");
+  const int flags = *h->h_flags;
+  if (flags & 3) return fail(h, CMT_ERANGE, (flags & 1) ? "a token id is outside its vocabulary" : "a length is outside [1, padded length]");
+  return CMT_OK;
 }
 
 int cmt_sgd_update(cmt_handle* h, float lr) {

@@ -166,4 +166,15 @@ void launch_colsum(int prec, const void* dG, int ld, int M, int N, float* scratc
 void launch_sgd(float* p, const float* g, size_t n, float lr, hipStream_t st);
 void launch_init_uniform(float* p, size_t n, uint64_t seed, float scale, hipStream_t st);
 
+// ---- greedy decoding (misc.hip) -------------------------------------------------------------------
+// x[b, 0:E] = table[tok[b]] (T, row pitch ldx) for b < B; zero rows for b in [B, Bp).
+void launch_dec_embed(int prec, const void* table, int E, const int32_t* tok, int B, int Bp, void* x, int ldx, hipStream_t st);
+// tok[b] = argmax_v (z[b, v] + bias[v]) (lowest index on ties); unfinished sentences record it at
+// out_ids[b, j] and end on eos or at j = max_len - 1 (done[b] = 1, out_len[b] = j + 1).
+void launch_dec_argmax(const float* z, int ldz, const float* bias, int V, int B, int j, int max_len, int eos, int32_t* tok,
+                       int32_t* done, int32_t* out_ids, int32_t* out_len, hipStream_t st);
+// tok = bos, done = 0, out_ids = pad, out_len = 0, mask[b] = (b < B).
+void launch_dec_init(int B, int Bp, int max_len, int bos, int pad, int32_t* tok, int32_t* done, int32_t* out_ids, int32_t* out_len,
+                     float* mask, hipStream_t st);
+
 }  // namespace cmt

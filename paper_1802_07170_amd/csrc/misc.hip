@@ -234,4 +234,80 @@ void launch_init_uniform(float* p, size_t n, uint64_t seed, float scale, hipStre
   hipLaunchKernelGGL(init_uniform_kernel, dim3(grid_for(n)), dim3(256), 0, st, p, n, seed, scale);
 }
 
+// ------------------------------------------------------------------------------------------------
+// greedy decoding helpers
+// ------------------------------------------------------------------------------------------------
+// x[b, 0:E] = table[tok[b]] for b < B, zero rows for the batch padding
+template <typename T>
+__global__ __launch_bounds__(128) void dec_embed_kernel(const T* __restrict__ table, int E, const int32_t* __restrict__ tok, int B,
+                                                        T* __restrict__ x, int ldx) {
+  const int b = blockIdx.x;
+  const T* src = b < B ? table + (size_t)tok[b] * E : nullptr;
+  for (int c = threadIdx.x * 8; c < E; c += 128 * 8) {
+    uint4 v[sizeof(T) / 2];                              // 8 elements
+    if (src) for (int q = 0; q < (int)(sizeof(T) / 2); ++q) v[q] = reinterpret_cast<const uint4*>(src + c)[q];
+    else for (int q = 0; q < (int)(sizeof(T) / 2); ++q) v[q] = make_uint4(0, 0, 0, 0);
+    for (int q = 0; q < (int)(sizeof(T) / 2); ++q) reinterpret_cast<uint4*>(x + (size_t)b * ldx + c)[q] = v[q];
+  }
+}
+void launch_dec_embed(int prec, const void* table, int E, const int32_t* tok, int B, int Bp, void* x, int ldx, hipStream_t st) {
+  if (prec) hipLaunchKernelGGL(dec_embed_kernel<bf16_t>, dim3(Bp), dim3(128), 0, st, (const bf16_t*)table, E, tok, B, (bf16_t*)x, ldx);
+  else hipLaunchKernelGGL(dec_embed_kernel<float>, dim3(Bp), dim3(128), 0, st, (const float*)table, E, tok, B, (float*)x, ldx);
+}
+
+// One workgroup per sentence: token = argmax_v (z[b, v] + bias[v]), the lowest index winning a tie.
+// A sentence that has not ended records the token at out_ids[b, j]; it ends when the token is eos or
+// j is the last step.  tok[b] (the next step's input) is always updated.
+__global__ __launch_bounds__(1024) void dec_argmax_kernel(const float* __restrict__ z, int ldz, const float* __restrict__ bias, int V,
+                                                          int j, int max_len, int eos, int32_t* __restrict__ tok,
+                                                          int32_t* __restrict__ done, int32_t* __restrict__ out_ids,
+                                                          int32_t* __restrict__ out_len) {
+  __shared__ float smax[16];
+  __shared__ int sidx[16];
+  const int b = blockIdx.x, t = threadIdx.x;
+  float best = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int v = t; v < V; v += 1024) {                    // ascending v: '>' keeps the lowest index of equal values
+    const float x = z[(size_t)b * ldz + v] + bias[v];
+    if (x > best || (x == best && v < bi)) { best = x; bi = v; }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ob = __shfl_xor(best, o, 64);
+    const int oi = __shfl_xor(bi, o, 64);
+    if (ob > best || (ob == best && oi < bi)) { best = ob; bi = oi; }
+  }
+  if ((t & 63) == 0) { smax[t >> 6] = best; sidx[t >> 6] = bi; }
+  __syncthreads();
+  if (t == 0) {
+    for (int w = 1; w < 16; ++w)
+      if (smax[w] > best || (smax[w] == best && sidx[w] < bi)) { best = smax[w]; bi = sidx[w]; }
+    if (bi == 0x7fffffff) bi = 0;                        // a row of NaNs: keep the token in range
+    tok[b] = bi;
+    if (!done[b]) {
+      out_ids[(size_t)b * max_len + j] = bi;
+      if (bi == eos || j == max_len - 1) { done[b] = 1; out_len[b] = j + 1; }
+    }
+  }
+}
+void launch_dec_argmax(const float* z, int ldz, const float* bias, int V, int B, int j, int max_len, int eos, int32_t* tok,
+                       int32_t* done, int32_t* out_ids, int32_t* out_len, hipStream_t st) {
+  hipLaunchKernelGGL(dec_argmax_kernel, dim3(B), dim3(1024), 0, st, z, ldz, bias, V, j, max_len, eos, tok, done, out_ids, out_len);
+}
+
+// start of a decode: tok = bos, done = 0, out_ids = pad, out_len = 0, mask = 1 for b < B else 0
+__global__ __launch_bounds__(256) void dec_init_kernel(int B, int Bp, int max_len, int bos, int pad, int32_t* __restrict__ tok,
+                                                       int32_t* __restrict__ done, int32_t* __restrict__ out_ids,
+                                                       int32_t* __restrict__ out_len, float* __restrict__ mask) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < Bp) { tok[i] = bos; done[i] = 0; mask[i] = i < B ? 1.f : 0.f; }
+  if (i < B) out_len[i] = 0;
+  if (i < B * max_len) out_ids[i] = pad;
+}
+void launch_dec_init(int B, int Bp, int max_len, int bos, int pad, int32_t* tok, int32_t* done, int32_t* out_ids, int32_t* out_len,
+                     float* mask, hipStream_t st) {
+  const int n = B * max_len > Bp ? B * max_len : Bp;
+  hipLaunchKernelGGL(dec_init_kernel, dim3((n + 255) / 256), dim3(256), 0, st, B, Bp, max_len, bos, pad, tok, done, out_ids, out_len, mask);
+}
+
 }  // namespace cmt

@@ -194,6 +194,71 @@ def test_regularisation_arguments_are_checked():
     tr.close()
 
 
+@pytest.mark.parametrize("prec", [0, 1])
+@pytest.mark.parametrize("B,S,H,E,L,max_len", [(5, 7, 32, 24, 1, 9), (19, 6, 80, 40, 2, 12), (64, 9, 128, 64, 3, 10)])
+def test_greedy_decode_matches_the_oracle(prec, B, S, H, E, L, max_len):
+    """Tokens and lengths are integers: they must be identical, except where the oracle's own decision
+    was a near tie (gap between its best and second-best logit below what the precision resolves) —
+    from there on that sentence may legitimately diverge and is no longer compared."""
+    from paper_1802_07170_amd import binding
+    cfg = dict(src_vocab=104, tgt_vocab=136, emb=E, hidden=H, layers=L)
+    rng = np.random.default_rng(500 + B)
+    params = I.make_params(cfg, seed=B + 7, scale=0.4)
+    params["W_o"] = params["W_o"] * 6.0                       # spread the logits: few decisions are near ties
+    params["B_o"] = params["B_o"].copy()
+    params["B_o"][3] += 5.0                                   # make the end token likely enough that some sentences end early
+    src, sl, _, _ = ragged_batch(rng, B, S, 4, cfg["src_vocab"], cfg["tgt_vocab"])
+    tr = binding.Trainer(cfg, B + 2, S + 1, max_len + 3, precision=prec)
+    tr.set_params(I.flatten(params, cfg))
+    tr.set_regularization(0.3, 0.0, 11)                       # must be ignored by decoding
+    ids, lens = tr.greedy_decode(src, sl, max_len, eos_id=3)
+    oids, olens, gaps = O.greedy_decode(cfg, params, src, sl, max_len, bos_id=2, eos_id=3)
+    # what the precision resolves: the forward pass keeps H_o within 2e-5 (fp32) / 2e-2 (bf16) of the oracle
+    # (the bound run_case checks), so a logit W_o[v] . H_o moves by about that times the row norm
+    tie = (2e-5 if prec == 0 else 2e-2) * 2.0 * np.linalg.norm(params["W_o"], axis=1).max()
+    exact = diverged = 0
+    for b in range(B):
+        same = True
+        for j in range(max_len):
+            if ids[b, j] != oids[b, j]:
+                assert j < olens[b] and gaps[b, j] < tie, (b, j, ids[b, j], oids[b, j], gaps[b, j])
+                same = False
+                break
+        if same:
+            assert lens[b] == olens[b]
+            exact += 1
+        else:
+            diverged += 1
+        assert 1 <= lens[b] <= max_len and np.all(ids[b, lens[b]:] == 0)
+        assert lens[b] == max_len or ids[b, lens[b] - 1] == 3
+    assert exact >= (B if prec == 0 else int(0.7 * B)), (exact, diverged)
+    assert (olens < max_len).any() and (olens == max_len).any() or B < 10   # both ways of ending occur
+    # a second call gives the same tokens; a training step still works afterwards
+    ids2, lens2 = tr.greedy_decode(src, sl, max_len, eos_id=3)
+    assert np.array_equal(ids, ids2) and np.array_equal(lens, lens2)
+    tr.close()
+
+
+def test_greedy_decode_arguments_are_checked():
+    from paper_1802_07170_amd import binding
+    cfg = dict(src_vocab=104, tgt_vocab=136, emb=24, hidden=32, layers=1)
+    tr = binding.Trainer(cfg, 4, 6, 6, precision=0)
+    tr.init_params(0, 0.1)
+    rng = np.random.default_rng(0)
+    src, sl, _, _ = ragged_batch(rng, 4, 6, 6, 104, 136)
+    for kw in [dict(max_len=7), dict(max_len=0), dict(max_len=3, eos_id=136)]:
+        with pytest.raises(binding.CmtError) as e:
+            tr.greedy_decode(src, sl, **kw)
+        assert e.value.code == binding.CMT_EINVAL
+    bad = src.copy(); bad[0, 0] = 104
+    with pytest.raises(binding.CmtError) as e:
+        tr.greedy_decode(bad, sl, 3)
+    assert e.value.code == binding.CMT_ERANGE
+    ids, lens = tr.greedy_decode(src, sl, 6)
+    assert ids.shape == (4, 6)
+    tr.close()
+
+
 def test_two_steps_are_bit_identical_and_sgd_matches_oracle():
     from paper_1802_07170_amd import binding
     c = I.CONFIGS["tiny"]
