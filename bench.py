@@ -137,6 +137,16 @@ def main():
     out["roofline"] = {"kernel": "lstm_fwd_kernel (decoder layer step: gate GEMM + fused cell)", "bound": "hbm",
                        "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                        "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "us_per_launch": us, "algorithmic_bytes_per_launch": nbytes}
+    # forward-only greedy translation of the same source batch (not part of the headline metric)
+    max_len = T
+    tr.greedy_decode(src, sl, max_len)
+    t0 = time.perf_counter()
+    ids, lens = tr.greedy_decode(src, sl, max_len)
+    dtd = time.perf_counter() - t0
+    out["greedy_decode"] = {"ms": dtd * 1e3, "steps": max_len, "emitted_tokens": int(lens.sum()),
+                            "tokens_per_s": float(lens.sum() / dtd), "us_per_decoder_step": dtd / max_len * 1e6}
+    tr.train_step_async(dev)
+    torch.cuda.synchronize()
     # the other kernel classes of the step, each replayed alone (no second stream active)
     peak_mfma = MFMA_BF16_PEAK_TFLOPS if c["precision"] else MFMA_FP32_PEAK_TFLOPS
     kernels = {}
