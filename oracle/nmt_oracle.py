@@ -22,8 +22,9 @@ The backward pass is written by hand from these definitions: a weight used at ev
 per-step gradients (the paper's calculateGradient accumulates with beta = 1), and a value with two
 consumers sums their gradients (the paper's DuplicateLayer).
 
-greedy_decode is the forward-only companion (hyperparameter table: beam search, here with beam
-size 1): the same encoder and decoder step, the arg-max token fed back.
+greedy_decode and beam_decode are the forward-only companions (hyperparameter table: beam search
+size 10, length penalty 0.6): the same encoder and decoder step, the arg-max token or the best
+`beam` extensions fed back.
 
 Regularisation of the Settings section / hyperparameter table (both off by default):
   * dropout p on the hidden states passed from a recurrent layer to the layer above it (encoder and
@@ -456,6 +457,100 @@ def greedy_decode(cfg, params, src_ids, src_len, max_len, bos_id=2, eos_id=3, pa
                 done[b] = True
                 lens[b] = j + 1
     return ids, lens, gaps
+
+
+def length_penalty(length, alpha):
+    """Length normalisation of Wu et al. (2016), which the paper's Settings section names:
+    lp(Y) = ((5 + |Y|) / 6) ** alpha."""
+    return ((5.0 + length) / 6.0) ** alpha
+
+
+def beam_decode(cfg, params, src_ids, src_len, max_len, beam, alpha, bos_id=2, eos_id=3, pad_id=0):
+    """Beam search (hyperparameter table: beam size 10, length penalty 0.6), sentence by sentence.
+
+    A hypothesis carries the sum of log p(token) of its tokens.  At every step the `beam` best
+    one-token extensions over all live hypotheses are taken (equal scores: the lower (hypothesis
+    slot, token) pair first).  An extension that ends in eos_id leaves the beam as a finished
+    hypothesis of length = its number of tokens (eos included); the others stay live, best first.
+    A sentence is done when no hypothesis is live or after max_len steps; hypotheses still live then
+    are finished as they are.  The result is the finished hypothesis with the largest
+    score / length_penalty(length, alpha) (equal values: the one finished first).  No dropout.
+
+    Returns ids [B, max_len] (pad_id after the end), lengths [B], normalised scores [B], and
+    margins [B]: the smallest score gap met at any decision that shaped the result (the beam
+    boundary at every step, and the final winner against the runner-up), for parity tests."""
+    p = {k: np.asarray(v, F64) for k, v in params.items()}
+    src_ids = np.asarray(src_ids)
+    B = src_ids.shape[0]
+    H, L = cfg["hidden"], cfg["layers"]
+    Hd = H // 2
+    out_ids = np.full((B, max_len), pad_id, np.int64)
+    out_len = np.zeros(B, np.int64)
+    out_score = np.zeros(B, F64)
+    margins = np.full(B, np.inf)
+    for b in range(B):
+        n = int(src_len[b])
+        Xs = p["E_src"][src_ids[b, :n]][:, None, :]              # [n, 1, E]
+        m1 = np.ones((n, 1), F64)
+        z_d, z_h = np.zeros((1, Hd), F64), np.zeros((1, H), F64)
+        Yf, hf, cf, _ = lstm_forward(Xs, m1, p["enc.l0.fwd.W"], p["enc.l0.fwd.b"], z_d, z_d)
+        Yb, hb, cb, _ = lstm_forward(Xs, m1, p["enc.l0.bwd.W"], p["enc.l0.bwd.b"], z_d, z_d, reverse=True)
+        Y = np.concatenate([Yf, Yb], axis=2)
+        h = [np.concatenate([hf, hb], axis=1)]
+        c = [np.concatenate([cf, cb], axis=1)]
+        for l in range(1, L):
+            Y, hl, cl, _ = lstm_forward(Y, m1, p[f"enc.l{l}.W"], p[f"enc.l{l}.b"], z_h, z_h)
+            h.append(hl)
+            c.append(cl)
+        Hs1 = Y                                                   # [n, 1, H]
+        live_tok = [[]]                                           # token lists of the live hypotheses
+        live_score = np.zeros(1, F64)
+        prev = np.array([bos_id])
+        Ho = z_h
+        finished = []                                             # (normalised score, order, tokens)
+        for j in range(max_len):
+            k = len(live_tok)
+            x = np.concatenate([p["E_tgt"][prev], Ho], axis=1)
+            ones = np.ones((k, 1), F64)
+            for l in range(L):
+                _, h[l], c[l], _ = masked_step_forward(x, h[l], c[l], ones, p[f"dec.l{l}.W"], p[f"dec.l{l}.b"])
+                x = h[l]
+            Hs = np.repeat(Hs1, k, axis=1)
+            Ho, _ = attention_forward(Hs, np.ones((n, k), F64), h[L - 1], p["W_a"], p["W_c"])
+            z = Ho @ p["W_o"].T + p["B_o"]
+            zmax = z.max(axis=1, keepdims=True)
+            logp = z - (zmax + np.log(np.exp(z - zmax).sum(axis=1, keepdims=True)))
+            cand = (live_score[:, None] + logp).reshape(-1)       # flat index = slot * V + token
+            order = np.lexsort((np.arange(cand.size), -cand))     # by score descending, then flat index
+            top = order[:beam]
+            if cand.size > beam:
+                margins[b] = min(margins[b], cand[order[beam - 1]] - cand[order[beam]])
+            V = z.shape[1]
+            new_tok, new_score, parents = [], [], []
+            for rank, f in enumerate(top):
+                slot, tok = int(f // V), int(f % V)
+                seq = live_tok[slot] + [tok]
+                if tok == eos_id or j == max_len - 1:
+                    finished.append((cand[f] / length_penalty(len(seq), alpha), len(finished), seq))
+                else:
+                    new_tok.append(seq)
+                    new_score.append(cand[f])
+                    parents.append(slot)
+            if not new_tok:
+                break
+            live_tok, live_score = new_tok, np.array(new_score)
+            h = [hh[parents] for hh in h]
+            c = [cc[parents] for cc in c]
+            Ho = Ho[parents]
+            prev = np.array([seq[-1] for seq in live_tok])
+        finished.sort(key=lambda t: (-t[0], t[1]))
+        best = finished[0]
+        if len(finished) > 1:
+            margins[b] = min(margins[b], best[0] - finished[1][0])
+        out_ids[b, :len(best[2])] = best[2]
+        out_len[b] = len(best[2])
+        out_score[b] = best[0]
+    return out_ids, out_len, out_score, margins
 
 
 def sgd_update(params, grads, lr):

@@ -474,6 +474,46 @@ def test_greedy_decode_end_token_and_length_cap():
     assert np.array_equal(one[0], ids[1]) and l1[0] == lens[1]
 
 
+def test_beam_of_one_is_greedy_and_length_penalty_closed_form():
+    assert O.length_penalty(1, 0.6) == 1.0 and O.length_penalty(7, 1.0) == 2.0
+    assert abs(O.length_penalty(19, 0.5) - 2.0) < 1e-15
+    cfg = tiny_cfg(H=8, E=5, V=13, L=2)
+    p = rand_params(cfg, seed=43, scale=0.8)
+    src, sl, _, _ = tiny_batch(cfg, seed=6)
+    gids, glens, _ = O.greedy_decode(cfg, p, src, sl, 6, eos_id=3)
+    bids, blens, bscore, _ = O.beam_decode(cfg, p, src, sl, 6, beam=1, alpha=0.6, eos_id=3)
+    assert np.array_equal(gids, bids) and np.array_equal(glens, blens)
+    # the score of the beam-1 result is the summed log-probability of the greedy tokens / lp
+    _, _, it = O.train_step(cfg, p, src, sl, gids, glens, want_intermediates=True)
+    for b in range(3):
+        np.testing.assert_allclose(bscore[b], -it["nll"][:glens[b], b].sum() / O.length_penalty(glens[b], 0.6), rtol=1e-12)
+
+
+def test_wide_beam_finds_the_best_sequence_by_brute_force():
+    """With a beam at least as wide as the number of prefixes nothing is pruned, so the result must
+    be the best of ALL sequences (ending in the end token, or of full length) under the normalised
+    score; enumerate them with the teacher-forced training forward."""
+    import itertools
+    cfg = dict(src_vocab=9, tgt_vocab=5, emb=3, hidden=4, layers=1)
+    p = rand_params(cfg, seed=44, scale=1.5)
+    src = np.array([[4, 5, 6], [7, 8, 0]]); sl = np.array([3, 2])
+    max_len, eos, alpha, V = 3, 3, 0.6, 5
+    ids, lens, score, _ = O.beam_decode(cfg, p, src, sl, max_len, beam=V ** max_len, alpha=alpha, eos_id=eos)
+    for b in range(2):
+        best = (-np.inf, None)
+        for n in range(1, max_len + 1):
+            for seq in itertools.product(range(V), repeat=n):
+                if eos in seq[:-1] or (n < max_len and seq[-1] != eos):
+                    continue                                      # not a complete hypothesis
+                tgt = np.zeros((1, max_len), int); tgt[0, :n] = seq
+                _, _, it = O.train_step(cfg, p, src[b:b + 1, :sl[b]], sl[b:b + 1], tgt, np.array([n]), want_intermediates=True)
+                val = -it["nll"][:n, 0].sum() / O.length_penalty(n, alpha)
+                if val > best[0]:
+                    best = (val, seq)
+        assert tuple(ids[b, :lens[b]]) == best[1], (b, ids[b], best)
+        assert abs(score[b] - best[0]) < 1e-12
+
+
 def test_intermediates_are_consistent():
     cfg = tiny_cfg(H=6, L=2)
     p = rand_params(cfg, seed=12)
