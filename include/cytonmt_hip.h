@@ -132,6 +132,24 @@ int cmt_set_regularization(cmt_handle* h, float dropout, float label_smoothing, 
 int cmt_greedy_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* src_len_dev, int32_t B, int32_t S,
                       int32_t max_len, int32_t eos_id, int32_t* out_ids_dev, int32_t* out_len_dev);
 
+/* Beam search (hyperparameter table: beam search size 10, length penalty 0.6; the Settings section
+ * names the length normalisation of Wu et al. 2016: lp(Y) = ((5 + |Y|) / 6) ^ length_penalty).
+ * The decoder runs on B * beam rows, one per hypothesis, so B * beam <= max_batch is required.
+ * A hypothesis carries the sum of log p(token) of its tokens.  At every step the `beam` best
+ * one-token extensions over a sentence's live hypotheses are taken (equal scores: the lower
+ * (hypothesis slot, token) pair first); an extension ending in eos_id leaves the beam as a finished
+ * hypothesis of length = its token count (eos included), the others stay live, best first.  A
+ * sentence is done when no hypothesis is live or after max_len steps (hypotheses still live then
+ * are finished as they are).  Returned per sentence: the finished hypothesis with the largest
+ * score / lp(length) (equal values: the one finished first).  No dropout.
+ *   out_ids_dev [B, max_len] int32, pad_id after the end; out_len_dev [B] int32; out_score_dev [B]
+ *   fp32 normalised scores (all device pointers).  1 <= beam <= 16, 1 <= max_len <= max_tgt_len
+ *   (max_tgt_len >= 2).  Scores are accumulated in fp32.  Synchronises the stream; overwrites the
+ *   intermediates of the last training step.  Errors as for cmt_greedy_decode. */
+int cmt_beam_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* src_len_dev, int32_t B, int32_t S,
+                    int32_t max_len, int32_t beam, float length_penalty, int32_t eos_id, int32_t* out_ids_dev,
+                    int32_t* out_len_dev, float* out_score_dev);
+
 /* Plain SGD (hyperparameter table: optimizer SGD, learning rate 1.0): p <- p - lr * g on the flat
  * fp32 master vector, then refreshes the kernels' working copies (bf16 casts, transposes). */
 int cmt_sgd_update(cmt_handle* h, float lr);

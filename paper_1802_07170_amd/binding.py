@@ -17,7 +17,7 @@ EXPORTS = [
     "cmt_query_sizes", "cmt_create", "cmt_destroy", "cmt_param_count", "cmt_param_info",
     "cmt_init_params", "cmt_set_params", "cmt_get_params", "cmt_train_step", "cmt_train_step_async",
     "cmt_fetch_loss", "cmt_get_grads", "cmt_sgd_update", "cmt_debug_fetch", "cmt_padded_batch",
-    "cmt_time_kernel", "cmt_last_error", "cmt_set_regularization", "cmt_greedy_decode",
+    "cmt_time_kernel", "cmt_last_error", "cmt_set_regularization", "cmt_greedy_decode", "cmt_beam_decode",
 ]
 
 
@@ -65,6 +65,7 @@ def load_library():
     lib.cmt_sgd_update.argtypes = [vp, C.c_float]
     lib.cmt_set_regularization.argtypes = [vp, C.c_float, C.c_float, C.c_uint64]
     lib.cmt_greedy_decode.argtypes = [vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, vp]
+    lib.cmt_beam_decode.argtypes = [vp, vp, vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_int32, vp, vp, vp]
     lib.cmt_debug_fetch.argtypes = [vp, C.c_char_p, vp, sz]
     lib.cmt_padded_batch.argtypes = [vp]
     lib.cmt_time_kernel.argtypes = [vp, C.c_char_p, C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_double)]
@@ -195,6 +196,20 @@ class Trainer:
         self._check(self.lib.cmt_greedy_decode(self.h, src.data_ptr(), sl.data_ptr(), B, S, max_len, eos_id, out.data_ptr(),
                                                olen.data_ptr()))
         return out.cpu().numpy(), olen.cpu().numpy()
+
+    def beam_decode(self, src_ids, src_len, max_len, beam=10, length_penalty=0.6, eos_id=3):
+        """Beam search over a batch: ids [B, max_len], lengths [B], normalised scores [B] (numpy)."""
+        torch = self.torch
+        src = torch.from_numpy(np.ascontiguousarray(src_ids, np.int32)).to(self.device)
+        sl = torch.from_numpy(np.ascontiguousarray(src_len, np.int32)).to(self.device)
+        B, S = src.shape
+        out = torch.empty((B, max_len), dtype=torch.int32, device=self.device)
+        olen = torch.empty((B,), dtype=torch.int32, device=self.device)
+        osc = torch.empty((B,), dtype=torch.float32, device=self.device)
+        torch.cuda.synchronize(self.device)
+        self._check(self.lib.cmt_beam_decode(self.h, src.data_ptr(), sl.data_ptr(), B, S, max_len, beam, length_penalty, eos_id,
+                                             out.data_ptr(), olen.data_ptr(), osc.data_ptr()))
+        return out.cpu().numpy(), olen.cpu().numpy(), osc.cpu().numpy()
 
     def set_regularization(self, dropout=0.0, label_smoothing=0.0, dropout_seed=0):
         """Dropout and label smoothing of the following steps (both 0 = off)."""

@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcytonmt_hip.so")
-SOURCES = ["api.hip", "gemm.hip", "ce.hip", "step.hip", "misc.hip"]
+SOURCES = ["api.hip", "gemm.hip", "ce.hip", "step.hip", "misc.hip", "beam.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -120,6 +120,9 @@ struct cmt_handle {
   // greedy decoding
   char* xcat = nullptr; int ldxcat = 0; // decoder bottom-layer input [emb(y_{j-1}) ; H_o^{<j-1>}] of the current step
   int32_t* dec_tok = nullptr; int32_t* dec_done = nullptr; float* dec_mask = nullptr; float* logits = nullptr;
+  // beam search: encoder outputs repeated per hypothesis row, and the search state
+  char* Hs_exp = nullptr; char* K_exp = nullptr; int32_t* len_exp = nullptr;
+  BeamState beam{};
   char* HoDrop = nullptr;               // H_o after dropout: what the output layer and the input feed read
   float* psz = nullptr;                 // per-group sums of logits (label smoothing)
   size_t ws_bytes = 0;
@@ -227,6 +230,18 @@ size_t layout(cmt_handle* h, char* base) {
   h->dec_tok = (int32_t*)a.take((size_t)Bp * 4); h->dec_done = (int32_t*)a.take((size_t)Bp * 4);
   h->dec_mask = (float*)a.take((size_t)Bp * 4);
   h->logits = (float*)a.take((size_t)Bp * c.tgt_vocab * 4);
+  h->Hs_exp = a.take(Ms * H * esz); h->K_exp = a.take(Ms * H * esz);
+  h->len_exp = (int32_t*)a.take((size_t)Bp * 4);
+  {
+    BeamState& bs = h->beam;
+    bs.cum = (float*)a.take((size_t)Bp * 4); bs.new_cum = (float*)a.take((size_t)Bp * 4); bs.mask = (float*)a.take((size_t)Bp * 4);
+    bs.tok = (int32_t*)a.take((size_t)Bp * 4); bs.new_tok = (int32_t*)a.take((size_t)Bp * 4);
+    bs.parent = (int32_t*)a.take((size_t)Bp * 4); bs.nlive = (int32_t*)a.take((size_t)Bp * 4);
+    bs.fin_score = (float*)a.take((size_t)Bp * 4); bs.fin_step = (int32_t*)a.take((size_t)Bp * 4);
+    bs.fin_par = (int32_t*)a.take((size_t)Bp * 4); bs.fin_tok = (int32_t*)a.take((size_t)Bp * 4);
+    bs.hist_tok = (int32_t*)a.take(Mt * 4); bs.hist_par = (int32_t*)a.take(Mt * 4);
+    bs.hist_ld = Bp;
+  }
   h->Cs = a.take(Mt * PH * esz); h->CsT = a.take(Mt * H * esz);
   h->att_a = (float*)a.take(Mt * Sm * 4); h->att_ds = (float*)a.take(Mt * Sm * 4);
   h->dCs = (float*)a.take(Mt * H * 4);
@@ -985,6 +1000,94 @@ int cmt_greedy_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* 
   hipError_t e = hipStreamSynchronize(st);
   if (e == hipSuccess) e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(h, e, "cmt_greedy_decode");
+  const int flags = *h->h_flags;
+  if (flags & 3) return fail(h, CMT_ERANGE, (flags & 1) ? "a token id is outside its vocabulary" : "a length is outside [1, padded length]");
+  return CMT_OK;
+}
+
+int cmt_beam_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* src_len_dev, int32_t B, int32_t S,
+                    int32_t max_len, int32_t beam, float length_penalty, int32_t eos_id, int32_t* out_ids_dev,
+                    int32_t* out_len_dev, float* out_score_dev) {
+  if (!h) return CMT_EINVAL;
+  const cmt_config& c = h->cfg;
+  if (!src_ids_dev || !src_len_dev || !out_ids_dev || !out_len_dev || !out_score_dev) return fail(h, CMT_EINVAL, "null pointer");
+  if (B < 1 || S < 1 || S > c.max_src_len || max_len < 1 || max_len > c.max_tgt_len)
+    return fail(h, CMT_EINVAL, "B, S or max_len outside [1, configured maximum]");
+  if (beam < 1 || beam > 16) return fail(h, CMT_EINVAL, "beam must be in [1, 16]");
+  if ((long long)B * beam > c.max_batch) return fail(h, CMT_EINVAL, "B * beam exceeds max_batch (one decoder row per hypothesis)");
+  if (c.max_tgt_len < 2) return fail(h, CMT_EINVAL, "beam search needs max_tgt_len >= 2 (state double buffer)");
+  if (!(length_penalty >= 0.f) || !isfinite(length_penalty)) return fail(h, CMT_EINVAL, "length_penalty must be finite and >= 0");
+  if (eos_id < 0 || eos_id >= c.tgt_vocab) return fail(h, CMT_EINVAL, "eos_id outside the target vocabulary");
+  const int p = h->prec, E = c.emb_dim, H = c.hidden, L = c.layers, V = c.tgt_vocab, K = beam;
+  const int BpE = round_up(B, 16);                   // encoder rows
+  const int R = B * K, Rp = round_up(R, 16);         // decoder rows
+  const size_t esz = h->esz;
+  hipStream_t st = h->st;
+  h->B = B; h->Bp = BpE; h->S = S; h->T = max_len;
+  h->have_step = false;
+  h->phase_n = 0;
+  const int PH = h->PH;
+  const float keep_p = h->drop_p;
+  h->drop_p = 0.f;                                   // inference: no dropout
+  launch_fill_f32((float*)h->flags, 1, 0.f, st);
+  launch_gather(p, h->Pw(h->off_Esrc), c.src_vocab, E, src_ids_dev, src_len_dev, B, BpE, S, 0, 0, h->Xs, h->mask_s, h->tok_s,
+                nullptr, h->len_s, h->flags, st);
+  const char* Hs; int ldHs;
+  enqueue_encoder(h, S, &Hs, &ldHs);                 // also leaves the decoder's initial states in slot 0 (BpE rows)
+  h->drop_p = keep_p;
+  // one decoder row per hypothesis: encoder outputs, keys, lengths and initial states repeated K times
+  BeamState& bs = h->beam;
+  bs.hist_ld = Rp;
+  launch_beam_init(bs, B, Rp, K, c.bos_id, h->len_s, h->len_exp, st);
+  launch_beam_expand((int)esz, Hs, ldHs, BpE, h->Hs_exp, H, S, R, Rp, K, H, st);
+  launch_beam_expand((int)esz, h->Kmat, H, BpE, h->K_exp, H, S, R, Rp, K, H, st);
+  const size_t slotT = (size_t)Rp * PH * esz, slotC = (size_t)Rp * H * 4;   // state slots of Rp rows: 1 = read, 2 = written
+  for (int l = 0; l < L; ++l) {
+    LD& e = h->dec[l];
+    launch_beam_expand((int)esz, e.Hst, e.ph, BpE, e.Hst + slotT, e.ph, 1, R, Rp, K, H, st);
+    launch_beam_expand(4, e.Cst, H, BpE, (char*)e.Cst + slotC, H, 1, R, Rp, K, H, st);
+  }
+  launch_fill_T(p, h->xcat, (size_t)Rp * h->ldxcat, st);               // H_o^{<-1>} = 0
+  BeamReorder ro{};
+  for (int l = 0; l < L; ++l) {
+    LD& e = h->dec[l];
+    ro.h_src[l] = e.Hst + 2 * slotT; ro.h_dst[l] = e.Hst + slotT;
+    ro.c_src[l] = (const float*)((char*)e.Cst + 2 * slotC); ro.c_dst[l] = (float*)((char*)e.Cst + slotC);
+  }
+  ro.ldh = PH;
+  ro.ho_src = h->HoBuf; ro.ldho_src = PH; ro.ho_dst = h->xcat + (size_t)E * esz; ro.ldho_dst = h->ldxcat;
+  for (int j = 0; j < max_len; ++j) {
+    launch_dec_embed(p, h->Pw(h->off_Etgt), E, bs.tok, R, Rp, h->xcat, h->ldxcat, st);
+    for (int l = 0; l < L; ++l) {
+      LD& e = h->dec[l];
+      LstmFwdDir d;
+      if (l == 0) { d.x = h->xcat; d.ldx = h->ldxcat; d.Kx = E + H; d.wx_off = 0; d.wh_off = E + H; d.ldw = E + 2 * H; }
+      else { d.x = h->dec[l - 1].Hst + 2 * slotT; d.ldx = PH; d.Kx = H; d.wx_off = 0; d.wh_off = H; d.ldw = 2 * H; }
+      d.gx = nullptr; d.ldgx = 0; d.bias = h->params + e.b_off;
+      d.hprev = e.Hst + slotT; d.ldh = e.ph; d.W = e.W;
+      d.cprev = (const float*)((char*)e.Cst + slotC); d.mask = bs.mask;
+      d.hnext = e.Hst + 2 * slotT; d.ldhn = e.ph; d.cnext = (float*)((char*)e.Cst + 2 * slotC);
+      d.gsave = e.Gs; d.ycat = nullptr; d.ldy = 0; d.part = e.part;
+      launch_lstm_fwd(p, &d, 1, Rp, H, st);
+    }
+    const char* Ht = h->dec[L - 1].Hst + 2 * slotT;
+    launch_att_fwd(p, h->K_exp, H, h->Hs_exp, H, Ht, PH, h->len_exp, S, Rp, H, h->dots, h->att_a, h->Cs, PH, st);
+    StepGemm g{};
+    g.a0 = h->Cs; g.lda0 = PH; g.K0 = H; g.w0_off = 0;
+    g.a1 = Ht; g.lda1 = PH; g.K1 = H; g.w1_off = H;
+    g.W = h->Pw(h->off_Wc); g.ldw = 2 * H; g.N = H; g.mode = 0;
+    g.outT = h->HoBuf; g.ldo = PH;
+    g.out = h->wcp; g.ldout = H; g.plane_stride = (size_t)Rp * H;
+    launch_step_gemm(p, g, Rp, st);
+    launch_gemm_nt(p, h->HoBuf, PH, h->Pw(h->off_Wo), H, Rp, V, H, h->logits, nullptr, V, h->params + h->off_Bo, 0, st);
+    launch_beam_select(h->logits, V, bs, B, K, j, max_len, eos_id, length_penalty, st);
+    launch_beam_reorder(p, ro, bs, R, H, L, st);
+  }
+  launch_beam_finish(bs, B, K, max_len, c.pad_id, out_ids_dev, out_len_dev, out_score_dev, st);
+  (void)hipMemcpyAsync(h->h_flags, h->flags, sizeof(int), hipMemcpyDeviceToHost, st);
+  hipError_t e = hipStreamSynchronize(st);
+  if (e == hipSuccess) e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(h, e, "cmt_beam_decode");
   const int flags = *h->h_flags;
   if (flags & 3) return fail(h, CMT_ERANGE, (flags & 1) ? "a token id is outside its vocabulary" : "a length is outside [1, padded length]");
   return CMT_OK;

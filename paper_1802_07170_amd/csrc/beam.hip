@@ -1,0 +1,233 @@
+// Beam search bookkeeping on the device (hyperparameter table: beam size 10, length penalty 0.6;
+// the Settings section names the length normalisation of Wu et al. 2016).  The decoder runs on
+// R = B * K rows, row r = b * K + s holding live hypothesis s of sentence b.  Per step:
+//   beam_select_kernel  one workgroup per sentence: log-softmax of the live rows' logits, the K best
+//                       one-token extensions over all live hypotheses (equal scores: the lower
+//                       (slot, token) pair first), finished hypotheses split off, history written;
+//   beam_reorder_kernel the surviving hypotheses' decoder states and H_o move to their new rows.
+// After the last step beam_finish_kernel walks the back-pointers of each sentence's best finished
+// hypothesis.  Nothing returns to the host inside the loop.
+#include "common.h"
+#include "kernels.h"
+
+namespace cmt {
+
+// dst[i, r, 0:cols] = src[i, r / K, 0:cols] for r < R, zero rows for r in [R, Rp); i < n_outer.
+// Row pitches in elements; cols * sizeof(T) is a multiple of 16.
+template <typename T>
+__global__ __launch_bounds__(128) void beam_expand_kernel(const T* __restrict__ src, int ld_src, int rows_src, T* __restrict__ dst,
+                                                          int ld_dst, int R, int Rp, int K, int cols) {
+  const int r = blockIdx.x, i = blockIdx.y;
+  constexpr int VE = 16 / sizeof(T);
+  const T* s = r < R ? src + ((size_t)i * rows_src + r / K) * ld_src : nullptr;
+  T* d = dst + ((size_t)i * Rp + r) * ld_dst;
+  for (int c = threadIdx.x * VE; c < cols; c += 128 * VE)
+    *reinterpret_cast<uint4*>(d + c) = s ? *reinterpret_cast<const uint4*>(s + c) : make_uint4(0, 0, 0, 0);
+}
+void launch_beam_expand(int elem_bytes, const void* src, int ld_src, int rows_src, void* dst, int ld_dst, int n_outer, int R, int Rp,
+                        int K, int cols, hipStream_t st) {
+  dim3 grid(Rp, n_outer);
+  if (elem_bytes == 2)
+    hipLaunchKernelGGL(beam_expand_kernel<bf16_t>, grid, dim3(128), 0, st, (const bf16_t*)src, ld_src, rows_src, (bf16_t*)dst, ld_dst,
+                       R, Rp, K, cols);
+  else
+    hipLaunchKernelGGL(beam_expand_kernel<float>, grid, dim3(128), 0, st, (const float*)src, ld_src, rows_src, (float*)dst, ld_dst, R,
+                       Rp, K, cols);
+}
+
+// start of a search: one live hypothesis per sentence (slot 0, score 0, previous token bos)
+__global__ __launch_bounds__(256) void beam_init_kernel(BeamState bs, int B, int Rp, int K, int bos, const int32_t* __restrict__ len_src,
+                                                        int32_t* __restrict__ len_exp) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r < Rp) {
+    const int b = r / K, s = r - b * K;
+    const bool real = b < B;
+    bs.cum[r] = real && s == 0 ? 0.f : -INFINITY;
+    bs.tok[r] = bos;
+    bs.mask[r] = real && s == 0 ? 1.f : 0.f;
+    len_exp[r] = real ? len_src[b] : 0;
+  }
+  if (r < B) { bs.nlive[r] = 1; bs.fin_score[r] = -INFINITY; bs.fin_step[r] = -1; bs.fin_par[r] = 0; bs.fin_tok[r] = 0; }
+}
+void launch_beam_init(const BeamState& bs, int B, int Rp, int K, int bos, const int32_t* len_src, int32_t* len_exp, hipStream_t st) {
+  hipLaunchKernelGGL(beam_init_kernel, dim3((Rp + 255) / 256), dim3(256), 0, st, bs, B, Rp, K, bos, len_src, len_exp);
+}
+
+constexpr int BEAM_MAX = 16;
+
+// (value, flat index) ordering: larger value first, then lower index
+__device__ __forceinline__ bool beam_better(float v, int f, float bv, int bf) { return v > bv || (v == bv && f < bf); }
+
+__global__ __launch_bounds__(1024) void beam_select_kernel(const float* __restrict__ z, int V, BeamState bs, int K, int j, int max_len,
+                                                           int eos, float alpha) {
+  __shared__ float s_red[16];
+  __shared__ int s_redi[16];
+  __shared__ int s_redo[16];
+  __shared__ float s_lse[BEAM_MAX];
+  __shared__ float s_winv[BEAM_MAX];
+  __shared__ int s_winf[BEAM_MAX];
+  __shared__ float s_b;
+  __shared__ int s_bi, s_bo;
+  const int b = blockIdx.x, t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const int nl = bs.nlive[b];
+  const int row0 = b * K;
+  if (nl == 0) {                                         // the sentence is done (uniform over the workgroup)
+    if (t < K) { bs.parent[row0 + t] = -1; bs.new_cum[row0 + t] = -INFINITY; }
+    return;
+  }
+  // ---- log-sum-exp of every live row ---------------------------------------------------------------
+  for (int s = 0; s < nl; ++s) {
+    const float* zr = z + (size_t)(row0 + s) * V;
+    float mx = -INFINITY;
+    for (int v = t; v < V; v += 1024) mx = fmaxf(mx, zr[v]);
+    mx = wave_max(mx);
+    if (lane == 0) s_red[w] = mx;
+    __syncthreads();
+    mx = s_red[0];
+    for (int q = 1; q < 16; ++q) mx = fmaxf(mx, s_red[q]);
+    __syncthreads();
+    float e = 0.f;
+    for (int v = t; v < V; v += 1024) e += expf(zr[v] - mx);
+    e = wave_sum(e);
+    if (lane == 0) s_red[w] = e;
+    __syncthreads();
+    if (t == 0) {
+      float tot = 0.f;
+      for (int q = 0; q < 16; ++q) tot += s_red[q];
+      s_lse[s] = mx + logf(tot);
+    }
+    __syncthreads();
+  }
+  // ---- every thread's K best candidates, best first ---------------------------------------------------
+  float lv[BEAM_MAX];
+  int lf[BEAM_MAX];
+#pragma unroll
+  for (int q = 0; q < BEAM_MAX; ++q) { lv[q] = -INFINITY; lf[q] = 0x7fffffff; }
+  for (int s = 0; s < nl; ++s) {
+    const float base = bs.cum[row0 + s] - s_lse[s];
+    const float* zr = z + (size_t)(row0 + s) * V;
+    for (int v = t; v < V; v += 1024) {
+      const float val = base + zr[v];
+      const int f = s * V + v;
+      if (beam_better(val, f, lv[K - 1], lf[K - 1])) {   // insert, keeping the list sorted
+        int q = K - 1;
+        while (q > 0 && beam_better(val, f, lv[q - 1], lf[q - 1])) { lv[q] = lv[q - 1]; lf[q] = lf[q - 1]; --q; }
+        lv[q] = val; lf[q] = f;
+      }
+    }
+  }
+  // ---- K rounds: the best head over all threads wins, its owner moves to its next candidate -----------
+  int head = 0;
+  for (int round = 0; round < K; ++round) {
+    float bv = head < K ? lv[head] : -INFINITY;
+    int bf = head < K ? lf[head] : 0x7fffffff;
+    int bo = t;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const float ov = __shfl_xor(bv, o, 64);
+      const int of = __shfl_xor(bf, o, 64);
+      const int oo = __shfl_xor(bo, o, 64);
+      if (beam_better(ov, of, bv, bf)) { bv = ov; bf = of; bo = oo; }
+    }
+    if (lane == 0) { s_red[w] = bv; s_redi[w] = bf; s_redo[w] = bo; }
+    __syncthreads();
+    if (t == 0) {
+      float v = s_red[0]; int f = s_redi[0], o = s_redo[0];
+      for (int q = 1; q < 16; ++q)
+        if (beam_better(s_red[q], s_redi[q], v, f)) { v = s_red[q]; f = s_redi[q]; o = s_redo[q]; }
+      s_b = v; s_bi = f; s_bo = o;
+      s_winv[round] = v; s_winf[round] = f;
+    }
+    __syncthreads();
+    if (t == s_bo) ++head;
+    __syncthreads();
+  }
+  // ---- split the winners into finished and live hypotheses ---------------------------------------------
+  if (t == 0) {
+    int n_new = 0;
+    const bool last = j == max_len - 1;
+    for (int q = 0; q < K; ++q) {
+      const float v = s_winv[q];
+      const int f = s_winf[q];
+      if (!(v > -INFINITY)) break;                       // fewer candidates than K
+      const int s = f / V, tk = f - s * V;
+      if (tk == eos || last) {
+        const float norm = v / powf((5.f + (float)(j + 1)) / 6.f, alpha);
+        if (norm > bs.fin_score[b]) {                    // strict: the hypothesis finished first keeps a tie
+          bs.fin_score[b] = norm; bs.fin_step[b] = j; bs.fin_par[b] = s; bs.fin_tok[b] = tk;
+        }
+      } else {
+        const int r = row0 + n_new;
+        bs.new_cum[r] = v;
+        bs.parent[r] = row0 + s;
+        bs.new_tok[r] = tk;
+        bs.hist_tok[(size_t)j * bs.hist_ld + r] = tk;
+        bs.hist_par[(size_t)j * bs.hist_ld + r] = s;
+        ++n_new;
+      }
+    }
+    bs.nlive[b] = n_new;
+    for (int q = n_new; q < K; ++q) { bs.new_cum[row0 + q] = -INFINITY; bs.parent[row0 + q] = -1; }
+  }
+}
+void launch_beam_select(const float* z, int V, const BeamState& bs, int B, int K, int j, int max_len, int eos, float alpha,
+                        hipStream_t st) {
+  hipLaunchKernelGGL(beam_select_kernel, dim3(B), dim3(1024), 0, st, z, V, bs, K, j, max_len, eos, alpha);
+}
+
+// New row r takes the states of row parent[r] (or stays dead): per layer h (T) and c (fp32), and the
+// H_o that becomes its input feed; scores, tokens and masks are switched over.
+template <typename T>
+__global__ __launch_bounds__(256) void beam_reorder_kernel(BeamReorder ro, BeamState bs, int H, int L) {
+  const int r = blockIdx.x, t = threadIdx.x;
+  const int pr = bs.parent[r];
+  if (t == 0) {
+    bs.cum[r] = bs.new_cum[r];
+    bs.mask[r] = pr >= 0 ? 1.f : 0.f;
+    if (pr >= 0) bs.tok[r] = bs.new_tok[r];
+  }
+  if (pr < 0) return;
+  constexpr int VE = 16 / sizeof(T);
+  for (int l = 0; l < L; ++l) {
+    const T* hs = (const T*)ro.h_src[l] + (size_t)pr * ro.ldh;
+    T* hd = (T*)ro.h_dst[l] + (size_t)r * ro.ldh;
+    for (int c = t * VE; c < H; c += 256 * VE) *reinterpret_cast<uint4*>(hd + c) = *reinterpret_cast<const uint4*>(hs + c);
+    const float* cs = ro.c_src[l] + (size_t)pr * H;
+    float* cd = ro.c_dst[l] + (size_t)r * H;
+    for (int c = t * 4; c < H; c += 256 * 4) *reinterpret_cast<float4*>(cd + c) = *reinterpret_cast<const float4*>(cs + c);
+  }
+  const T* os = (const T*)ro.ho_src + (size_t)pr * ro.ldho_src;
+  T* od = (T*)ro.ho_dst + (size_t)r * ro.ldho_dst;
+  for (int c = t * VE; c < H; c += 256 * VE) *reinterpret_cast<uint4*>(od + c) = *reinterpret_cast<const uint4*>(os + c);
+}
+void launch_beam_reorder(int prec, const BeamReorder& ro, const BeamState& bs, int R, int H, int L, hipStream_t st) {
+  if (prec) hipLaunchKernelGGL(beam_reorder_kernel<bf16_t>, dim3(R), dim3(256), 0, st, ro, bs, H, L);
+  else hipLaunchKernelGGL(beam_reorder_kernel<float>, dim3(R), dim3(256), 0, st, ro, bs, H, L);
+}
+
+// one thread per sentence: walk the back-pointers of the best finished hypothesis
+__global__ __launch_bounds__(64) void beam_finish_kernel(BeamState bs, int B, int K, int max_len, int pad, int32_t* __restrict__ out_ids,
+                                                         int32_t* __restrict__ out_len, float* __restrict__ out_score) {
+  const int b = blockIdx.x * 64 + threadIdx.x;
+  if (b >= B) return;
+  const int j = bs.fin_step[b];
+  const int len = j + 1;
+  int32_t* o = out_ids + (size_t)b * max_len;
+  for (int q = 0; q < max_len; ++q) o[q] = pad;
+  out_len[b] = len;
+  out_score[b] = bs.fin_score[b];
+  if (j < 0) { out_len[b] = 0; return; }
+  o[j] = bs.fin_tok[b];
+  int s = bs.fin_par[b];
+  for (int q = j - 1; q >= 0; --q) {
+    const size_t i = (size_t)q * bs.hist_ld + b * K + s;
+    o[q] = bs.hist_tok[i];
+    s = bs.hist_par[i];
+  }
+}
+void launch_beam_finish(const BeamState& bs, int B, int K, int max_len, int pad, int32_t* out_ids, int32_t* out_len, float* out_score,
+                        hipStream_t st) {
+  hipLaunchKernelGGL(beam_finish_kernel, dim3((B + 63) / 64), dim3(64), 0, st, bs, B, K, max_len, pad, out_ids, out_len, out_score);
+}
+
+}  // namespace cmt

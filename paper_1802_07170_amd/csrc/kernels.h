@@ -177,4 +177,32 @@ void launch_dec_argmax(const float* z, int ldz, const float* bias, int V, int B,
 void launch_dec_init(int B, int Bp, int max_len, int bos, int pad, int32_t* tok, int32_t* done, int32_t* out_ids, int32_t* out_len,
                      float* mask, hipStream_t st);
 
+// ---- beam search (beam.hip) -----------------------------------------------------------------------
+// Device-side state of a search over R = B * K rows (row r = b * K + s: live hypothesis s of sentence b).
+struct BeamState {
+  float* cum; float* new_cum;            // [Rp] summed log-probabilities of the live hypotheses (-inf: dead slot)
+  int32_t* tok; int32_t* new_tok;        // [Rp] previous token of every row (next step's input)
+  int32_t* parent;                       // [Rp] row a new hypothesis continues (-1: dead slot)
+  float* mask;                           // [Rp] 1 = live row
+  int32_t* nlive;                        // [B] live hypotheses per sentence
+  float* fin_score; int32_t* fin_step; int32_t* fin_par; int32_t* fin_tok;   // [B] best finished hypothesis
+  int32_t* hist_tok; int32_t* hist_par;  // [steps, hist_ld] token / parent slot of every live hypothesis per step
+  int hist_ld;
+};
+struct BeamReorder {
+  const void* h_src[8]; void* h_dst[8]; int ldh;     // per layer: states written by the step -> states the next step reads
+  const float* c_src[8]; float* c_dst[8];
+  const void* ho_src; int ldho_src; void* ho_dst; int ldho_dst;   // H_o of the step -> input feed of the next
+};
+// dst[i, r, 0:cols] = src[i, r / K, 0:cols] (r < R), zero rows up to Rp; elem_bytes 2 or 4.
+void launch_beam_expand(int elem_bytes, const void* src, int ld_src, int rows_src, void* dst, int ld_dst, int n_outer, int R, int Rp,
+                        int K, int cols, hipStream_t st);
+void launch_beam_init(const BeamState& bs, int B, int Rp, int K, int bos, const int32_t* len_src, int32_t* len_exp, hipStream_t st);
+// z [Rp, V] = logits incl. bias.  Step j of max_len; K <= 16.
+void launch_beam_select(const float* z, int V, const BeamState& bs, int B, int K, int j, int max_len, int eos, float alpha,
+                        hipStream_t st);
+void launch_beam_reorder(int prec, const BeamReorder& ro, const BeamState& bs, int R, int H, int L, hipStream_t st);
+void launch_beam_finish(const BeamState& bs, int B, int K, int max_len, int pad, int32_t* out_ids, int32_t* out_len, float* out_score,
+                        hipStream_t st);
+
 }  // namespace cmt

@@ -239,6 +239,45 @@ def test_greedy_decode_matches_the_oracle(prec, B, S, H, E, L, max_len):
     tr.close()
 
 
+@pytest.mark.parametrize("prec", [0, 1])
+@pytest.mark.parametrize("B,S,H,E,L,max_len,beam", [(3, 5, 32, 24, 1, 7, 4), (6, 6, 80, 40, 2, 9, 10), (5, 4, 64, 32, 3, 8, 1),
+                                                     (7, 9, 128, 64, 2, 10, 10)])
+def test_beam_search_matches_the_oracle(prec, B, S, H, E, L, max_len, beam):
+    """Result hypothesis, its length and its normalised score against the oracle.  Every decision of a
+    search is a comparison of scores; the oracle reports the smallest gap met at a decision that
+    shaped its result (beam boundary per step, final winner vs runner-up).  Where that gap is below what
+    the precision resolves the sentence may legitimately differ and only its validity is checked."""
+    from paper_1802_07170_amd import binding
+    cfg = dict(src_vocab=104, tgt_vocab=136, emb=E, hidden=H, layers=L)
+    rng = np.random.default_rng(700 + B)
+    params = I.make_params(cfg, seed=B + 9, scale=0.4)
+    params["W_o"] = params["W_o"] * 6.0
+    params["B_o"] = params["B_o"].copy()
+    params["B_o"][3] += 3.0
+    src, sl, _, _ = ragged_batch(rng, B, S, 4, cfg["src_vocab"], cfg["tgt_vocab"])
+    tr = binding.Trainer(cfg, B * beam + 5, S + 1, max_len + 2, precision=prec)
+    tr.set_params(I.flatten(params, cfg))
+    ids, lens, score = tr.beam_decode(src, sl, max_len, beam=beam, length_penalty=0.6, eos_id=3)
+    oids, olens, oscore, margins = O.beam_decode(cfg, params, src, sl, max_len, beam, 0.6, bos_id=2, eos_id=3)
+    # a logit moves by about atol(H_o) * row norm (see the greedy test); a hypothesis score sums up to max_len of them
+    tol = (2e-5 if prec == 0 else 2e-2) * 2.0 * np.linalg.norm(params["W_o"], axis=1).max()
+    exact = 0
+    for b in range(B):
+        assert 1 <= lens[b] <= max_len and np.all(ids[b, lens[b]:] == 0)
+        assert lens[b] == max_len or ids[b, lens[b] - 1] == 3
+        assert not np.any(ids[b, :lens[b] - 1] == 3)
+        if margins[b] > tol * max_len:
+            assert np.array_equal(ids[b], oids[b]) and lens[b] == olens[b], (b, ids[b], oids[b], margins[b])
+        if np.array_equal(ids[b], oids[b]):
+            exact += 1
+            assert abs(score[b] - oscore[b]) <= tol * max_len / O.length_penalty(lens[b], 0.6) + 1e-4 * abs(oscore[b])
+    assert exact >= (B if prec == 0 else 1), exact
+    if beam == 1:
+        gids, glens = tr.greedy_decode(src, sl, max_len, eos_id=3)
+        assert np.array_equal(gids, ids) and np.array_equal(glens, lens)
+    tr.close()
+
+
 def test_greedy_decode_arguments_are_checked():
     from paper_1802_07170_amd import binding
     cfg = dict(src_vocab=104, tgt_vocab=136, emb=24, hidden=32, layers=1)
