@@ -69,6 +69,7 @@ def main():
     ap.add_argument("--workload", default="medium", choices=list(I.CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sentences", type=int, default=64)
+    ap.add_argument("--no-beam", action="store_true", help="skip the beam-search timing (it allocates a second, larger workspace)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run three plain 256 MiB device copies (the known-size kernel that the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by)")
@@ -147,6 +148,18 @@ def main():
                             "tokens_per_s": float(lens.sum() / dtd), "us_per_decoder_step": dtd / max_len * 1e6}
     tr.train_step_async(dev)
     torch.cuda.synchronize()
+    # beam search with the paper's settings (beam 10, length penalty 0.6): one decoder row per hypothesis,
+    # so it runs in a second handle whose workspace is sized for B * 10 rows
+    if not args.no_beam:
+        tb = binding.Trainer(cfg, B * 10, S, T, precision=c["precision"])
+        tb.set_params(I.flatten(params, cfg))
+        tb.beam_decode(src, sl, max_len, beam=10, length_penalty=0.6)
+        t0 = time.perf_counter()
+        bids, blens, bscore = tb.beam_decode(src, sl, max_len, beam=10, length_penalty=0.6)
+        dtb = time.perf_counter() - t0
+        out["beam_decode"] = {"beam": 10, "length_penalty": 0.6, "ms": dtb * 1e3, "steps": max_len,
+                              "emitted_tokens": int(blens.sum()), "tokens_per_s": float(blens.sum() / dtb)}
+        tb.close()
     # the other kernel classes of the step, each replayed alone (no second stream active)
     peak_mfma = MFMA_BF16_PEAK_TFLOPS if c["precision"] else MFMA_FP32_PEAK_TFLOPS
     kernels = {}
