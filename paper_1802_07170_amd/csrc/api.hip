@@ -45,7 +45,6 @@ struct LD {
   char* Yd = nullptr;                // T [Lmax, Bp, Hh] the layer's output after dropout (row pitch ph) ...
   char* YdT = nullptr;               // ... and its transpose [Hh, L*Bp]; used only while dropout is on
   float* dh = nullptr; float* dc = nullptr;   // [Bp, Hh]
-  float* part = nullptr;             // [8][Bp][4Hh] forward partial planes (k split over workgroups)
   float* bwdp = nullptr;             // [8][Bp][2Hh] backward step-GEMM planes
 };
 
@@ -93,7 +92,7 @@ struct cmt_handle {
   char* Xs = nullptr; float* mask_s = nullptr; int32_t* tok_s = nullptr; int32_t* len_s = nullptr;
   char* Y0 = nullptr; char* Y0T = nullptr; char* Kmat = nullptr;
   float* dHs = nullptr; char* dK = nullptr; char* dKT = nullptr;
-  float* dYa = nullptr; float* dYb = nullptr; float* dXs = nullptr; char* XsT = nullptr;
+  float* dYa = nullptr; float* dXs = nullptr; char* XsT = nullptr;
   // target side
   char* Xt = nullptr; float* mask_t = nullptr; int32_t* tok_t = nullptr; int32_t* labels = nullptr; int32_t* len_t = nullptr;
   char* HoBuf = nullptr; char* HoBufT = nullptr; char* Cs = nullptr; char* CsT = nullptr;
@@ -197,7 +196,6 @@ size_t layout(cmt_handle* h, char* base) {
     d.HstT = a.take((M + Bp) * Hh * esz);
     d.dh = (float*)a.take((size_t)Bp * Hh * 4);
     d.dc = (float*)a.take((size_t)Bp * Hh * 4);
-    d.part = (float*)a.take((size_t)8 * Bp * 4 * Hh * 4);
     d.bwdp = (float*)a.take((size_t)8 * Bp * 2 * Hh * 4);
     d.Yd = a.take(M * d.ph * esz);                 // the layer's output after dropout, and its transpose
     d.YdT = a.take(M * Hh * esz);
@@ -217,7 +215,7 @@ size_t layout(cmt_handle* h, char* base) {
   h->mask_s = (float*)a.take(Ms * 4); h->tok_s = (int32_t*)a.take(Ms * 4); h->len_s = (int32_t*)a.take((size_t)Bp * 4);
   h->Y0 = a.take(Ms * H * esz); h->Y0T = a.take(Ms * H * esz); h->Kmat = a.take(Ms * H * esz);
   h->dHs = (float*)a.take(Ms * H * 4); h->dK = a.take(Ms * H * esz); h->dKT = a.take(Ms * H * esz);
-  h->dYa = (float*)a.take(Ms * H * 4); h->dYb = (float*)a.take(Ms * H * 4);
+  h->dYa = (float*)a.take(Ms * H * 4);
   h->dXs = (float*)a.take(Ms * E * 4);
   // target side
   h->Xt = a.take(Mt * E * esz); h->XtT = a.take(Mt * E * esz);
@@ -383,7 +381,7 @@ void dec_lstm_fwd(cmt_handle* h, int l, int j) {
   d.hprev = e.Hst + j * BP * esz; d.ldh = e.ph; d.W = e.W;
   d.cprev = e.Cst + j * BH; d.mask = h->mask_t + (size_t)j * Bp;
   d.hnext = e.Hst + (j + 1) * BP * esz; d.ldhn = e.ph; d.cnext = e.Cst + (j + 1) * BH;
-  d.gsave = e.Gs + (size_t)j * Bp * 4 * H; d.ycat = nullptr; d.ldy = 0; d.part = e.part;
+  d.gsave = e.Gs + (size_t)j * Bp * 4 * H; d.ycat = nullptr; d.ldy = 0;
   if (drop && l + 1 < c.layers) {                  // what the layer above reads
     d.ycat = e.Yd + j * BP * esz; d.ldy = e.ph; d.drop = drop_spec(h, DROP_SITE_DEC + l, j); d.drop_col0 = 0;
   }
@@ -426,7 +424,7 @@ void enqueue_encoder(cmt_handle* h, int S, const char** Hs_out, int* ldHs_out) {
       d[i].cprev = e.Cst + sp * BHd; d[i].mask = h->mask_s + (size_t)t * Bp;
       d[i].hnext = e.Hst + sn * BPd * esz; d[i].ldhn = e.ph; d[i].cnext = e.Cst + sn * BHd;
       d[i].gsave = e.Gs + (size_t)t * Bp * 4 * Hd;
-      d[i].ycat = h->Y0 + ((size_t)t * BH + (i ? Hd : 0)) * esz; d[i].ldy = H; d[i].part = e.part;
+      d[i].ycat = h->Y0 + ((size_t)t * BH + (i ? Hd : 0)) * esz; d[i].ldy = H;
       if (L > 1) { d[i].drop = drop_spec(h, DROP_SITE_ENC + 0, t); d[i].drop_col0 = i ? Hd : 0; }
     }
     launch_lstm_fwd(p, d, 2, Bp, Hd, st);
@@ -461,7 +459,7 @@ void enqueue_encoder(cmt_handle* h, int S, const char** Hs_out, int* ldHs_out) {
         d.W = e.W; d.ldw = 2 * H; d.wx_off = 0; d.wh_off = H;
         d.cprev = e.Cst + t * BH; d.mask = h->mask_s + (size_t)t * Bp;
         d.hnext = e.Hst + (t + 1) * BP * esz; d.ldhn = e.ph; d.cnext = e.Cst + (t + 1) * BH;
-        d.gsave = e.Gs + (size_t)t * Bp * 4 * H; d.ycat = nullptr; d.ldy = 0; d.part = e.part;
+        d.gsave = e.Gs + (size_t)t * Bp * 4 * H; d.ycat = nullptr; d.ldy = 0;
         if (drop && l + 1 < L) {
           d.ycat = e.Yd + t * BP * esz; d.ldy = e.ph; d.drop = drop_spec(h, DROP_SITE_ENC + l, t); d.drop_col0 = 0;
         }
@@ -974,7 +972,7 @@ int cmt_greedy_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* 
       d.hprev = e.Hst + j * BP * esz; d.ldh = e.ph; d.W = e.W;
       d.cprev = e.Cst + j * BH; d.mask = h->dec_mask;
       d.hnext = e.Hst + (j + 1) * BP * esz; d.ldhn = e.ph; d.cnext = e.Cst + (j + 1) * BH;
-      d.gsave = e.Gs + (size_t)j * Bp * 4 * H; d.ycat = nullptr; d.ldy = 0; d.part = e.part;
+      d.gsave = e.Gs + (size_t)j * Bp * 4 * H; d.ycat = nullptr; d.ldy = 0;
       launch_lstm_fwd(p, &d, 1, Bp, H, st);
     }
     const char* Ht = h->dec[L - 1].Hst + (j + 1) * BP * esz;
@@ -1067,7 +1065,7 @@ int cmt_beam_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* sr
       d.hprev = e.Hst + slotT; d.ldh = e.ph; d.W = e.W;
       d.cprev = (const float*)((char*)e.Cst + slotC); d.mask = bs.mask;
       d.hnext = e.Hst + 2 * slotT; d.ldhn = e.ph; d.cnext = (float*)((char*)e.Cst + 2 * slotC);
-      d.gsave = e.Gs; d.ycat = nullptr; d.ldy = 0; d.part = e.part;
+      d.gsave = e.Gs; d.ycat = nullptr; d.ldy = 0;
       launch_lstm_fwd(p, &d, 1, Rp, H, st);
     }
     const char* Ht = h->dec[L - 1].Hst + 2 * slotT;

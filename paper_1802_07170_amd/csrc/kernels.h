@@ -77,7 +77,6 @@ struct LstmFwdDir {
   void* ycat; int ldy;                  // optional second copy of h (T*, row pitch ldy), or null:
   DropSpec drop{}; int drop_col0 = 0;   //   the layer's output as the layer above sees it, i.e. after
                                         //   dropout (columns drop_col0 + [0, Hh) of the site)
-  float* part;                          // [8][Bp][4Hh] scratch planes, used when the k range is split
 };
 // ndir <= STEP_MAX_INST instances of equal hidden width Hh in one launch.
 void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh, hipStream_t st);

@@ -201,23 +201,6 @@ __global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(LstmFwdArgs args, int
   }
 }
 
-// cell update from partial planes (only when the k range was split over workgroups)
-template <typename T>
-__global__ __launch_bounds__(256) void lstm_cell_kernel(LstmFwdArgs args, int Bp, int Hh, int np) {
-  const LstmFwdDir& d = args.d[blockIdx.y];
-  const int idx = blockIdx.x * 256 + threadIdx.x;
-  if (idx >= Bp * Hh) return;
-  const int b = idx / Hh, u = idx - b * Hh;
-  float p[4];
-#pragma unroll
-  for (int g = 0; g < 4; ++g) {
-    float v = 0.f;
-    for (int k = 0; k < np; ++k) v += d.part[((size_t)k * Bp + b) * 4 * Hh + g * Hh + u];
-    p[g] = v;
-  }
-  cell_finish(d, b, u, Hh, p, cell_load(d, b, u, Hh, sizeof(T) == 2), sizeof(T) == 2);
-}
-
 template <typename T, int RT, int KS, int U, int BT = STEP_MAXBT>
 static void lstm_fwd_go(const LstmFwdArgs& a, int Bp, int Hh, int ndir, hipStream_t st) {
   const int nbt = (Bp + 15) / 16;
@@ -225,11 +208,10 @@ static void lstm_fwd_go(const LstmFwdArgs& a, int Bp, int Hh, int ndir, hipStrea
   hipLaunchKernelGGL((lstm_fwd_kernel<T, RT, KS, U, BT>), dim3(step_grid_blocks(sg)), dim3(64 * KS), 0, st, a, Bp, Hh, sg, ndir);
 }
 
-// Ways to run the step: the fused kernel above with 16 / 32 / 64 gate rows per workgroup (one
-// launch; fewer, fatter workgroups move less activation traffic through L2), or the 2-D step GEMM
-// on the packed gate rows followed by the cell kernel (two launches).
-// `how` (env CMT_LSTM_FWD for experiments): 0 = choose by size, 1/2/4 = fused with that many row
-// tiles, 9 = split.
+// Shapes of the fused kernel: 16 / 32 / 64 gate rows per workgroup, with all sentences (up to 64) or
+// 32 of them; fewer, fatter workgroups move less activation traffic through L2.
+// `how` (env CMT_LSTM_FWD for experiments): 0 = choose by size, 1 / 2 / 4 = that many 16-row tiles x
+// 64 sentences, 6 = 32 rows x 32 sentences.
 static int g_lstm_fwd_how = -1;
 void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh, hipStream_t st) {
   if (g_lstm_fwd_how < 0) {
@@ -247,23 +229,6 @@ void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh,
   // measured (bf16, hidden 1024): 64 sentences — 32 gate rows x 32 sentences per workgroup: 9.9 us against
   // 11.3 us for 16 rows x 64 sentences; more than 64 sentences — 32 rows x 64 sentences
   if (how == 0) how = (Bp > 64) ? 2 : (prec && nbt == 4) ? 6 : 1;   // (32 sentences: 16 rows x 32 sentences is faster)
-  if (how == 9) {
-    int np = 1;
-    for (int i = 0; i < ndir; ++i) {
-      const LstmFwdDir& d = dirs[i];
-      StepGemm g{};
-      g.a0 = d.x; g.lda0 = d.ldx; g.K0 = d.Kx; g.w0_off = d.wx_off;
-      g.a1 = d.hprev; g.lda1 = d.ldh; g.K1 = Hh; g.w1_off = d.wh_off;
-      g.W = d.W; g.ldw = d.ldw; g.N = 4 * Hh; g.mode = 1;
-      g.out = d.part; g.ldout = 4 * Hh; g.plane_stride = (size_t)Bp * 4 * Hh;
-      launch_step_gemm(prec, g, Bp, st);
-      np = step_kblocks(prec, 4 * Hh, K, Bp);
-    }
-    dim3 grid((Bp * Hh + 255) / 256, ndir);
-    if (prec) hipLaunchKernelGGL(lstm_cell_kernel<bf16_t>, grid, dim3(256), 0, st, a, Bp, Hh, np);
-    else hipLaunchKernelGGL(lstm_cell_kernel<float>, grid, dim3(256), 0, st, a, Bp, Hh, np);
-    return;
-  }
   const int nsteps = (K / 8 + 3) / 4;
   if (prec) {
     if (how == 6) {
