@@ -1,17 +1,19 @@
 // Kernels of the two time loops (encoder / decoder recurrences and their backward passes).
-// Per step the batch is tiny (M = B <= 128) and the work is bound by streaming the layer's
-// weights, so these kernels put the WEIGHT rows on the matrix cores' row side (16 rows per
-// workgroup, read exactly once per step straight from global memory into MFMA fragments, no LDS
-// staging) and the batch on the column side.  The wavefronts of a workgroup split the k range;
-// every wavefront issues all of its loads before its first MFMA so that a whole workgroup's
-// operand bytes are in flight at once, and the partial tiles are combined through LDS.  A k range
-// longer than one workgroup covers is split over workgroups, which then write partial "planes"
-// that the consuming kernel sums (no atomics, fixed order).
-// For the LSTM the 16 rows of a workgroup are the four gates of four hidden units, so that after
-// the reduction every lane holds i, f, g, o of one (unit, sentence) pair and the cell update is
-// fused in-register.
+// Per step the batch is tiny (M = B <= 128): the layer's weights are streamed from HBM once, and what
+// a launch waits for is the traffic from L2 to the CUs — weights once, plus the step's activations once
+// per workgroup that needs them.  These kernels therefore put the WEIGHT rows on the matrix cores' row
+// side (16-row tiles read straight from global memory into MFMA fragments, no LDS staging) and the
+// batch on the column side, and choose how many row tiles and sentence tiles a workgroup owns so that
+// the sum of both kinds of traffic is small while the chip stays full.  The wavefronts of a workgroup
+// split the k range; every wavefront issues all loads of a round before its first MFMA so that a
+// whole workgroup's operand bytes are in flight at once, and the partial tiles are combined through
+// LDS.  A k range split over workgroups gives partial "planes" that the consuming kernel sums (no
+// atomics, fixed order).
+// For the LSTM a 16-row tile is the four gates of four hidden units, so that after the reduction
+// every lane holds i, f, g, o of one (unit, sentence) pair and the cell update is fused in-register.
 // Workgroup numbering is XCD-aware: the hardware deals consecutive workgroup ids round-robin to
-// the 8 XCDs, so the two batch halves that share a weight tile are given ids 8 apart.
+// the 8 XCDs, so the workgroups that share a weight tile (different sentence groups) get ids 8 apart
+// and meet in one L2.
 #include <stdlib.h>
 
 #include "common.h"
