@@ -132,7 +132,8 @@ def main():
     tr.train_step_async(dev)
     torch.cuda.synchronize()
     # dominant kernel of the step (largest share of kernel time in the rocprofv3 trace under
-    # profiles/): the fused decoder LSTM step.  It is bound by streaming the layer's weights.
+    # profiles/): the fused decoder LSTM step.  HBM carries its weights once; what it waits for is the
+    # L2 -> CU traffic of weights plus re-read activations (see the summaries under profiles/).
     us, nbytes = tr.time_kernel("lstm_fwd_dec", 400)
     achieved = nbytes / (us * 1e-6) / 1e9
     out["roofline"] = {"kernel": "lstm_fwd_kernel (decoder layer step: gate GEMM + fused cell)", "bound": "hbm",

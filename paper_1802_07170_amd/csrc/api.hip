@@ -1,14 +1,18 @@
 // Host side of the C ABI (include/cytonmt_hip.h): argument validation, the workspace layout, and
-// the kernel schedule of one training step.  No arithmetic of the method happens here.
+// the kernel schedules of a training step, of greedy decoding and of beam search.  No arithmetic of
+// the method happens here.
 //
-// Schedule of one step (all on the caller's stream):
-//   gather -> encoder layers (input GEMM batched over all source positions, then one fused
-//   recurrent kernel per position) -> attention-key hoist K = H_s W_a -> decoder time loop (per
-//   step: one fused LSTM kernel per layer, attention, attentional tanh layer) -> fused vocabulary
-//   projection / log-softmax / cross-entropy -> its fused backward -> decoder loop backwards ->
-//   deferred attention gradients -> encoder loops backwards -> weight gradients as GEMMs batched
-//   over all time steps (the paper's calculateGradient accumulation becomes the k = B*T
-//   contraction) -> deterministic embedding scatter.
+// Schedule of one training step:
+//   gathers -> encoder bottom layer (input GEMM batched over all source positions, then both
+//   directions in one fused recurrent kernel per position) -> upper encoder layers as a wavefront
+//   over (layer, position) -> attention-key hoist K = H_s W_a -> decoder time loop (per step: one
+//   fused LSTM kernel per layer, attention, attentional tanh layer) -> output layer in slabs of
+//   target positions (projection + log-sum-exp partials, e -> dz rescale, dH_o and dW_o GEMMs) ->
+//   decoder loop backwards -> deferred attention gradients -> encoder loops backwards.  Everything
+//   that does not feed a recurrence — transposes, weight gradients as GEMMs batched over all time
+//   steps (the paper's calculateGradient accumulation becomes the k = B*T contraction), dW_o, the
+//   deterministic embedding scatters — runs on the library's second stream and is joined before the
+//   step ends on the caller's stream.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdio.h>
