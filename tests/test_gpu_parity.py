@@ -282,6 +282,32 @@ def test_beam_search_matches_the_oracle(prec, B, S, H, E, L, max_len, beam):
     tr.close()
 
 
+def test_beam_search_edge_cases():
+    """A beam wider than the number of candidates of the first steps (vocabulary 8, beam 16), a single
+    step, and the argument checks."""
+    from paper_1802_07170_amd import binding
+    cfg = dict(src_vocab=104, tgt_vocab=8, emb=8, hidden=16, layers=1)
+    rng = np.random.default_rng(3)
+    params = I.make_params(cfg, seed=2, scale=0.5)
+    params["W_o"] = params["W_o"] * 8.0
+    src, sl, _, _ = ragged_batch(rng, 2, 3, 4, 104, 8)
+    tr = binding.Trainer(cfg, 40, 4, 6, precision=0)
+    tr.set_params(I.flatten(params, cfg))
+    for max_len, beam in [(4, 16), (1, 5), (6, 3)]:
+        ids, lens, score = tr.beam_decode(src, sl, max_len, beam=beam, length_penalty=0.6, eos_id=3)
+        oids, olens, oscore, margins = O.beam_decode(cfg, params, src, sl, max_len, beam, 0.6, bos_id=2, eos_id=3)
+        for b in range(2):
+            if margins[b] > 1e-3:
+                assert np.array_equal(ids[b], oids[b]) and lens[b] == olens[b], (max_len, beam, b, ids[b], oids[b])
+                assert abs(score[b] - oscore[b]) <= 1e-4 * max(1.0, abs(oscore[b]))
+    for kw in [dict(beam=0), dict(beam=17), dict(beam=21, max_len=2), dict(length_penalty=-1.0), dict(max_len=7), dict(eos_id=8)]:
+        args = dict(max_len=4, beam=4, length_penalty=0.6, eos_id=3); args.update(kw)
+        with pytest.raises(binding.CmtError) as e:
+            tr.beam_decode(src, sl, **args)
+        assert e.value.code == binding.CMT_EINVAL
+    tr.close()
+
+
 def test_greedy_decode_arguments_are_checked():
     from paper_1802_07170_amd import binding
     cfg = dict(src_vocab=104, tgt_vocab=136, emb=24, hidden=32, layers=1)
