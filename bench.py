@@ -27,6 +27,8 @@ HBM_PEAK_GBS = 8000.0
 # profiles/ gives the commands and the figures.  Known only for the workload it was measured on.
 MEASURED_TRAFFIC_BYTES = {"medium": 21703680}
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+# the paper's training-speed table, its own system, source tokens/s on its Quadro M4000 (context only)
+PAPER_SPEED_TABLE = {"paper_512x2": 4725, "paper_512x4": 3751, "paper_1024x2": 2571, "paper_1024x4": 1906}
 MFMA_FP32_PEAK_TFLOPS = 157.3
 
 
@@ -69,6 +71,8 @@ def main():
     ap.add_argument("--workload", default="medium", choices=list(I.CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sentences", type=int, default=64)
+    ap.add_argument("--no-paper-shapes", action="store_true",
+                    help="skip the four networks of the paper's training-speed table")
     ap.add_argument("--no-beam", action="store_true", help="skip the beam-search timing (it allocates a second, larger workspace)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run three plain 256 MiB device copies (the known-size kernel that the "
@@ -184,6 +188,36 @@ def main():
         tr.sgd_update(0.0)
     torch.cuda.synchronize()
     out["sgd_update_ms"] = (time.perf_counter() - t0) / 3 * 1e3
+    tr.close()
+    # the four networks of the paper's training-speed table, the step as the paper trains it (dropout
+    # 0.2, label smoothing 0.1), in the paper's unit (source tokens/s).  The paper's own figures were
+    # measured on a Quadro M4000 with real data and an unstated batch size: context, not a baseline.
+    if not args.no_paper_shapes:
+        shapes = {}
+        for name in I.PAPER_SHAPES:
+            pc = I.CONFIGS[name]
+            pcfg = I.model_cfg(pc)
+            pb = I.make_batch(pc)
+            tp = binding.Trainer(pcfg, pb[0].shape[0], pb[0].shape[1], pb[2].shape[1], precision=pc["precision"])
+            tp.init_params(pc["seed"], 0.1)
+            pdev = tp.upload_batch(*pb)
+            for i in range(2):
+                tp.set_regularization(0.2, 0.1, i)
+                tp.train_step_async(pdev)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(5):
+                tp.set_regularization(0.2, 0.1, 2 + i)
+                tp.train_step_async(pdev)
+                tp.sgd_update(1.0e-3)
+            torch.cuda.synchronize()
+            pdt = (time.perf_counter() - t0) / 5
+            tp.fetch_loss()
+            shapes[name] = {"ms_per_step_incl_sgd": pdt * 1e3, "source_tokens_per_s": float(pb[1].sum() / pdt),
+                            "target_tokens_per_s": float(pb[3].sum() / pdt),
+                            "paper_source_tokens_per_s_quadro_m4000": PAPER_SPEED_TABLE[name]}
+            tp.close()
+        out["paper_speed_table_shapes"] = shapes
     if args.calibration_copy:
         a = torch.zeros(64 << 20, dtype=torch.float32, device="cuda")
         b = torch.empty_like(a)
@@ -192,7 +226,6 @@ def main():
         torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(c, cfg, params, batch, args.cpu_sentences)
-    tr.close()
     print(json.dumps(out))
 
 

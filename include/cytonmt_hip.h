@@ -102,6 +102,18 @@ int cmt_train_step_async(cmt_handle* h, const int32_t* src_ids_dev, const int32_
                          int32_t B, int32_t S, int32_t T);
 int cmt_fetch_loss(cmt_handle* h, float* loss_host);
 
+/* The forward half of a step only (Eq. 1-7, no gradient): the development-set cross-entropy that
+ * the training procedure of the Settings section monitors.  Arguments as for cmt_train_step.
+ * Evaluation mode: no dropout and no label smoothing, whatever cmt_set_regularization says.
+ *   *loss_host  mean cross-entropy per valid target token of this batch,
+ *   *n_tok_host the number of valid target tokens (sum of tgt_len), so that a caller can average
+ *               over several batches; either may be NULL.
+ * Synchronises the stream.  Parameters and the gradient buffer are untouched; the intermediates of
+ * the last training step are overwritten.  Errors as for cmt_train_step. */
+int cmt_eval_loss(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* src_len_dev,
+                  const int32_t* tgt_ids_dev, const int32_t* tgt_len_dev,
+                  int32_t B, int32_t S, int32_t T, float* loss_host, float* n_tok_host);
+
 int cmt_get_grads(cmt_handle* h, float* host_dst);
 
 /* Regularisation of the training step (Settings section; hyperparameter table: dropout 0.2, label

@@ -495,7 +495,7 @@ void enqueue_encoder(cmt_handle* h, int S, const char** Hs_out, int* ldHs_out) {
 }
 
 int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, const int32_t* tgt_ids,
-                 const int32_t* tgt_len, int B, int S, int T) {
+                 const int32_t* tgt_len, int B, int S, int T, bool forward_only) {
   const cmt_config& c = h->cfg;
   if (!src_ids || !src_len || !tgt_ids || !tgt_len) return fail(h, CMT_EINVAL, "null input pointer");
   if (B < 1 || B > c.max_batch || S < 1 || S > c.max_src_len || T < 1 || T > c.max_tgt_len)
@@ -557,6 +557,28 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   // scatters) runs on the library's second stream and joins at the end of the step.
   const char* Ho = HoFeed + BP * esz;              // [T*Bp, H], row pitch PH
   const int np = ce_num_partials(V);
+  if (forward_only) {                              // Eq. 1 and the loss only: logits slab by slab, no gradient
+    int nslab;
+    const int rows = ce_slab_plan(Mt, &nslab);
+    int sl = 0;
+    for (int m0 = 0; m0 < Mt; ++sl) {
+      const int Mc = (sl == nslab - 1 || Mt - m0 < rows) ? Mt - m0 : rows;
+      launch_ce_fwd(p, Ho + (size_t)m0 * PH * esz, PH, h->Pw(h->off_Wo), P + h->off_Bo, h->labels + m0, Mc, V, H, h->dzTs,
+                    h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, h->ls_eps > 0.f ? h->psz + (size_t)m0 * np : nullptr,
+                    h->zy + m0, st);
+      launch_ce_rows(h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, h->psz + (size_t)m0 * np, h->zy + m0,
+                     h->mask_t + m0, Mc, np, h->ls_eps, V, h->lse + m0, h->nll + m0, st);
+      m0 += Mc;
+    }
+    launch_ce_loss(h->nll, Mt, h->loss, h->flags, st);
+    phase_mark(h, "end");
+    (void)hipMemcpyAsync(h->h_loss, h->loss, 2 * sizeof(float), hipMemcpyDeviceToHost, st);
+    (void)hipMemcpyAsync(h->h_flags, h->flags, sizeof(int), hipMemcpyDeviceToHost, st);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(h, e, "enqueue");
+    h->have_step = true;
+    return CMT_OK;
+  }
   hipStream_t sd = h->use_side ? h->side : st;
   const int ldHoT = Mt + Bp;
   const char* HoT = h->HoBufT + (size_t)Bp * esz;  // columns of H_o^{<0..T-1>}
@@ -907,7 +929,20 @@ int cmt_get_grads(cmt_handle* h, float* host_dst) {
 int cmt_train_step_async(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* src_len_dev,
                          const int32_t* tgt_ids_dev, const int32_t* tgt_len_dev, int32_t B, int32_t S, int32_t T) {
   if (!h) return CMT_EINVAL;
-  return enqueue_step(h, src_ids_dev, src_len_dev, tgt_ids_dev, tgt_len_dev, B, S, T);
+  return enqueue_step(h, src_ids_dev, src_len_dev, tgt_ids_dev, tgt_len_dev, B, S, T, false);
+}
+
+int cmt_eval_loss(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* src_len_dev, const int32_t* tgt_ids_dev,
+                  const int32_t* tgt_len_dev, int32_t B, int32_t S, int32_t T, float* loss_host, float* n_tok_host) {
+  if (!h) return CMT_EINVAL;
+  const float keep_p = h->drop_p, keep_eps = h->ls_eps;
+  h->drop_p = 0.f; h->ls_eps = 0.f;                 // evaluation: no masks, plain cross-entropy
+  int rc = enqueue_step(h, src_ids_dev, src_len_dev, tgt_ids_dev, tgt_len_dev, B, S, T, true);
+  h->drop_p = keep_p; h->ls_eps = keep_eps;
+  if (rc != CMT_OK) return rc;
+  rc = cmt_fetch_loss(h, loss_host);
+  if (n_tok_host) *n_tok_host = h->h_loss[1];
+  return rc;
 }
 
 int cmt_fetch_loss(cmt_handle* h, float* loss_host) {

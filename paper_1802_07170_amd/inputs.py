@@ -27,6 +27,14 @@ CONFIGS = {
     "attn":   dict(src_vocab=32000, tgt_vocab=32000, emb=512, hidden=512, layers=2, precision=1,
                    batch=32, len_range=(120, 120), ids="zipf", seed=4),
 }
+# The four networks of the paper's training-speed table (embedding = hidden size 512 or 1024, 2 or 4
+# layers on each side), with its vocabulary of about 37000.  The paper does not state its batch size:
+# 64 sentences here; lengths uniform in [5, 45] (mean 25, the corpus table's tokens per sentence).
+for _h in (512, 1024):
+    for _l in (2, 4):
+        CONFIGS[f"paper_{_h}x{_l}"] = dict(src_vocab=37000, tgt_vocab=37000, emb=_h, hidden=_h, layers=_l, precision=1,
+                                           batch=64, len_range=(5, 45), ids="zipf", seed=10 + _h // 512 + _l)
+PAPER_SHAPES = [k for k in CONFIGS if k.startswith("paper_")]
 
 
 def model_cfg(c):

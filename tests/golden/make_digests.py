@@ -2,7 +2,8 @@
 (medium, large, attn).  Calls only the CPU oracle (oracle/) on the seeded inputs; nothing here
 comes from the HIP path.
 
-    python tests/golden/make_digests.py [medium large attn medium:0.05 large:0.05 attn::reg medium:0.05:reg]
+    python tests/golden/make_digests.py [medium large attn medium:0.05 large:0.05 attn::reg medium:0.05:reg
+                                          paper_512x2:0.05:reg paper_1024x4:0.05:reg]
 
 A name with ":scale" draws the same parameters at uniform[-scale, scale) instead of the workload's
 [-0.1, 0.1): at hidden size 1024 the 0.1 initialisation makes the recurrences chaotic (rounding

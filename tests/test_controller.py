@@ -2,6 +2,8 @@
 Quality"), on hand-made entropy sequences."""
 import math
 
+import numpy as np
+
 import pytest
 
 from paper_1802_07170_amd import controller as C
@@ -42,3 +44,89 @@ def test_nan_never_improves_and_arguments_are_checked():
         C.LearningRateController(decay=1.0)
     with pytest.raises(ValueError):
         C.LearningRateController(patience=0)
+
+
+class _StubTrainer:
+    """Stands in for binding.Trainer: a parameter vector that each step moves towards a target, and a
+    development loss that is the squared distance to it (so the host loop has something to steer)."""
+
+    def __init__(self, n=6):
+        self.n_params = n
+        self.p = np.zeros(n, np.float32)
+        self.target = np.arange(n, dtype=np.float32)
+        self.reg = None
+        self.calls = []
+
+    def param_table(self):
+        return [("a", 2, 2, 0), ("b", 2, 1, 4)]
+
+    def get_params(self):
+        return self.p.copy()
+
+    def set_params(self, flat):
+        self.calls.append("set")
+        self.p = np.array(flat, np.float32)
+
+    def set_regularization(self, dropout, ls, seed):
+        self.reg = (dropout, ls, seed)
+
+    def train_step_async(self, batch):
+        self.calls.append(("step", batch, self.reg[2]))
+
+    def fetch_loss(self):
+        return 0.0
+
+    def sgd_update(self, lr):
+        self.p = (self.p + np.float32(0.5 * lr) * (self.target - self.p)).astype(np.float32)
+
+    def eval_loss(self, batch):
+        return float(((self.p - self.target) ** 2).sum()) + 0.25 * batch, 10.0 * (batch + 1)
+
+
+def test_host_loop_cycles_batches_seeds_masks_and_weights_the_dev_average():
+    from paper_1802_07170_amd import training as TR
+    t = _StubTrainer()
+    assert TR.dev_entropy(t, [0, 1]) == pytest.approx((55.0 * 10 + 55.25 * 20) / 30)
+    ctl = C.LearningRateController(patience=2)
+    hist = TR.fit(t, [0, 1, 2], [0, 1], ctl, eval_every=2, max_steps=7, dropout=0.2, label_smoothing=0.1, seed=40)
+    steps = [c for c in t.calls if c != "set"]
+    assert [b for _, b, _ in steps] == [0, 1, 2, 0, 1, 2, 0]          # batches cycled
+    assert [s for _, _, s in steps] == list(range(40, 47))             # one mask seed per step
+    assert [h[0] for h in hist] == [2, 4, 6, 7]                        # every 2 steps, and at the end
+    assert all(h[3] == C.NEW_BEST for h in hist)
+    assert t.reg[:2] == (0.2, 0.1)
+    with pytest.raises(ValueError):
+        TR.fit(t, [], [0], ctl, 1, 1)
+
+
+def test_host_loop_restores_the_best_parameters_on_decay_and_at_the_end():
+    from paper_1802_07170_amd import training as TR
+    t = _StubTrainer()
+    t.sgd_update = lambda lr: setattr(t, "p", (t.p + np.float32(1.0)).astype(np.float32))   # overshoots after a while
+    ctl = C.LearningRateController(patience=2)
+    hist = TR.fit(t, [0], [0], ctl, eval_every=1, max_steps=40)
+    best_step = min(hist, key=lambda h: h[1])
+    assert any(h[3] == C.DECAY_AND_RESTART for h in hist) and hist[-1][3] == C.STOP and ctl.stopped
+    assert t.eval_loss(0)[0] == pytest.approx(best_step[1])            # best parameters in place at the end
+    assert "set" in t.calls
+
+
+def test_checkpoint_round_trip_and_mismatch(tmp_path):
+    from paper_1802_07170_amd import training as TR
+    cfg = dict(src_vocab=8, tgt_vocab=9, emb=2, hidden=2, layers=1)
+    t = _StubTrainer()
+    t.p = np.array([0.1, -2.5, 3e-8, 7, 1e30, -0.0], np.float32)
+    ctl = C.LearningRateController(learning_rate=0.49, patience=5)
+    ctl.observe(3.25); ctl.observe(3.3)
+    path = tmp_path / "c.npz"
+    TR.save_checkpoint(path, t, cfg, ctl, step=123)
+    u = _StubTrainer()
+    ctl2 = C.LearningRateController()
+    assert TR.load_checkpoint(path, u, cfg, ctl2) == 123
+    assert u.p.tobytes() == t.p.tobytes()                               # bit for bit, the sign of zero included
+    assert vars(ctl2) == vars(ctl)
+    with pytest.raises(ValueError):
+        TR.load_checkpoint(path, u, dict(cfg, hidden=4))
+    u.param_table = lambda: [("a", 2, 2, 0), ("b", 1, 2, 4)]
+    with pytest.raises(ValueError):
+        TR.load_checkpoint(path, u, cfg)

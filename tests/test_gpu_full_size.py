@@ -3,8 +3,9 @@ times.  Expected values are digests written by tests/golden/make_digests.py, whi
 CPU oracle: loss, per-tensor gradient norms, a seeded sample of entries of every gradient tensor,
 embedding-gradient rows of frequent and never-seen ids, per-position nll.
 
-The attn workload and the medium shape (well-conditioned initialisation) are also run with the
-paper's regularisation (dropout 0.2, label smoothing 0.1) at the bar.
+The attn workload, the medium shape and two of the four networks of the paper's training-speed table
+(well-conditioned initialisation) are also run with the paper's regularisation (dropout 0.2, label
+smoothing 0.1) at the bar.
 
 Three kinds of case:
   * bf16 path, bar of the task (loss rel 2e-2; gradients relative L2 <= 2e-2 and
@@ -129,6 +130,13 @@ def test_attn_workload_bf16_with_dropout_and_label_smoothing_at_the_bar():
 
 def test_medium_shape_bf16_with_dropout_and_label_smoothing_at_the_bar():
     run_digest_case("medium", "0.05", 1, "bar", reg=True)
+
+
+@pytest.mark.parametrize("name", ["paper_512x2", "paper_1024x4"])
+def test_paper_speed_table_shapes_bf16_with_regularisation_at_the_bar(name):
+    """The smallest and the largest network of the paper's training-speed table (vocabulary 37000: 578
+    groups of 64 columns + 8), the step as the paper trains it (dropout 0.2, label smoothing 0.1)."""
+    run_digest_case(name, "0.05", 1, "bar", reg=True)
 
 
 @pytest.mark.parametrize("name", ["medium", "large"])

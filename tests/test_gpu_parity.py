@@ -386,6 +386,76 @@ def test_sgd_training_with_the_paper_s_regularisation_and_controller_learns():
     tr.close()
 
 
+@pytest.mark.parametrize("prec", [0, 1])
+@pytest.mark.parametrize("B,S,T,H,E,L,V", [(7, 6, 9, 32, 24, 2, 136), (70, 4, 17, 48, 16, 1, 328)])
+def test_eval_loss_is_the_oracle_s_forward_loss(prec, B, S, T, H, E, L, V):
+    """Forward-only evaluation: the oracle's loss without regularisation, whatever regularisation the
+    handle is set to; the token count; gradients left alone.  The second shape spans two slabs."""
+    from paper_1802_07170_amd import binding
+    cfg = dict(src_vocab=104, tgt_vocab=V, emb=E, hidden=H, layers=L)
+    rng = np.random.default_rng(17 + B)
+    params = I.make_params(cfg, seed=8, scale=0.3)
+    if prec == 1:
+        params = {k: bf16_round(v) for k, v in params.items()}
+    src, sl, tgt, tl = ragged_batch(rng, B, S, T, 104, V)
+    oloss, _ = O.train_step(cfg, params, src, sl, tgt, tl)[:2]
+    tr = binding.Trainer(cfg, B, S, T, precision=prec)
+    tr.set_params(I.flatten(params, cfg))
+    dev = tr.upload_batch(src, sl, tgt, tl)
+    step_loss = tr.train_step(dev)
+    g0 = tr.get_grads()
+    loss, ntok = tr.eval_loss(dev)
+    assert ntok == float(tl.sum())
+    assert loss == step_loss                               # the same forward kernels in the same order
+    tol = 1e-4 if prec == 0 else 2e-2
+    assert abs(loss - oloss) <= tol * abs(oloss), (loss, oloss)
+    tr.set_regularization(0.3, 0.2, 99)
+    loss_reg, _ = tr.eval_loss(dev)
+    assert loss_reg == loss                                # evaluation mode ignores dropout and smoothing
+    assert np.array_equal(tr.get_grads(), g0)
+    assert tr.train_step(dev) != step_loss                 # ... and leaves the setting in place
+    tr.close()
+
+
+def test_training_procedure_and_checkpoint_files(tmp_path):
+    """The host loop of the paper's training procedure on the device library: SGD with regularisation,
+    development entropy by forward-only evaluation over two batches, the learning-rate rule, best
+    parameters restored; a checkpoint file brings back parameters and controller state bit for bit."""
+    from paper_1802_07170_amd import binding, controller as C, training as TR
+    cfg = dict(src_vocab=104, tgt_vocab=136, emb=32, hidden=64, layers=2)
+    rng = np.random.default_rng(23)
+    tr = binding.Trainer(cfg, 24, 6, 7, precision=1)
+    tr.init_params(seed=5, scale=0.1)
+    # target tokens from 8 of the 136 entries: something a few dozen steps can learn, on unseen batches too
+    train = [tr.upload_batch(*ragged_batch(rng, 24, 6, 7, 104, 12)) for _ in range(3)]
+    devs = [train[0], tr.upload_batch(*ragged_batch(rng, 11, 5, 6, 104, 12))]
+    first = TR.dev_entropy(tr, devs)
+    l0, n0 = tr.eval_loss(devs[0]); l1, n1 = tr.eval_loss(devs[1])
+    assert first == pytest.approx((l0 * n0 + l1 * n1) / (n0 + n1), rel=1e-6)
+    ctl = C.LearningRateController(learning_rate=1.0, patience=2)
+    seen = []
+    hist = TR.fit(tr, train, devs, ctl, eval_every=10, max_steps=80, seed=500, on_check=lambda *a: seen.append(a))
+    assert hist == seen and len(hist) >= 2 and hist[0][0] == 10
+    assert all(a in (C.NEW_BEST, C.CONTINUE, C.DECAY_AND_RESTART, C.STOP) for _, _, _, a in hist)
+    assert ctl.best < 0.8 * first, (first, ctl.best)
+    assert ctl.best == min(e for _, e, _, a in hist if a == C.NEW_BEST)
+    assert TR.dev_entropy(tr, devs) == pytest.approx(ctl.best, rel=1e-6)    # the best parameters are back in place
+    path = tmp_path / "model.npz"
+    TR.save_checkpoint(path, tr, cfg, ctl, step=hist[-1][0])
+    kept = tr.get_params()
+    tr.init_params(seed=6, scale=0.1)
+    ctl2 = C.LearningRateController()
+    assert TR.load_checkpoint(path, tr, cfg, ctl2) == hist[-1][0]
+    assert np.array_equal(tr.get_params(), kept)
+    assert vars(ctl2) == vars(ctl)
+    tr.close()
+    other = dict(cfg, hidden=32)
+    tr2 = binding.Trainer(other, 4, 4, 4, precision=1)
+    with pytest.raises(ValueError):
+        TR.load_checkpoint(path, tr2, other)
+    tr2.close()
+
+
 def test_init_params_matches_the_counter_generator():
     from paper_1802_07170_amd import binding
     cfg = dict(src_vocab=104, tgt_vocab=136, emb=24, hidden=32, layers=2)
