@@ -598,7 +598,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   launch_transpose(p, h->Xt, E, h->XtT, Mt, Mt, E, sd);
   launch_transpose(p, h->Cs, PH, h->CsT, Mt, Mt, H, sd);
   {
-    // Slabs of <= CE_SLAB_ROWS rows, equal sizes, two slab buffer pairs.  Per slab the main stream
+    // Full slabs of CE_SLAB_ROWS rows and one remainder, two slab buffer pairs.  Per slab the main stream
     // takes forward (logits -> e, partials), lse / nll, e -> dz and dz^T, and dH_o = dz W_o (the
     // decoder needs it); the second stream takes dW_o += dz^T H_o and dB_o.
     int nslab;
