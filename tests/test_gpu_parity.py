@@ -141,6 +141,21 @@ def test_ragged_small_nets(prec, B, S, T, H, E, L):
 
 
 @pytest.mark.parametrize("prec", [0, 1])
+@pytest.mark.parametrize("B,S,T,H,E,L,Vs,Vt", [(1, 1, 1, 16, 8, 1, 8, 8), (2, 2, 3, 64, 2048, 1, 16, 24),
+                                               (200, 3, 3, 32, 16, 1, 104, 136), (130, 2, 2, 64, 16, 2, 40, 72)])
+def test_extreme_configurations(prec, B, S, T, H, E, L, Vs, Vt):
+    """The smallest model the library accepts (hidden 16, embedding 8, vocabularies of 8, one sentence of
+    one token each side), the widest embedding (2048), and batches of 200 and 130 sentences (more than
+    one 64-sentence block per weight tile, the last one ragged)."""
+    cfg = dict(src_vocab=Vs, tgt_vocab=Vt, emb=E, hidden=H, layers=L)
+    rng = np.random.default_rng(300 + B)
+    params = I.make_params(cfg, seed=40 + B, scale=0.3 if E <= 128 else 0.05)
+    batch = ragged_batch(rng, B, S, T, Vs, Vt)
+    loss, oloss, worst, tr = run_case(cfg, params, batch, prec)
+    tr.close()
+
+
+@pytest.mark.parametrize("prec", [0, 1])
 def test_output_layer_over_two_slabs(prec):
     """The output layer works through the target positions in slabs of <= 1024 rows.  1120 rows here:
     two slabs of unequal size, neither a multiple of the 256-row tile; a vocabulary that is not a
