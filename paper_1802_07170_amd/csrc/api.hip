@@ -859,12 +859,12 @@ int cmt_create(const cmt_config* cfg, void* params_dev, void* grads_dev, void* w
   h->ws_bytes = layout(h, h->ws);
   bind_params(h);
   hipError_t e = hipHostMalloc((void**)&h->h_loss, 256, hipHostMallocDefault);
-  if (e != hipSuccess) { delete h; return CMT_EHIP; }
+  if (e != hipSuccess) { cmt_destroy(h); return CMT_EHIP; }
   // second stream at the default priority, and a pool of events for the hand-offs between the two
-  if (hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking) != hipSuccess) { (void)hipHostFree(h->h_loss); delete h; return CMT_EHIP; }
-  h->ev.resize(512);
+  if (hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking) != hipSuccess) { cmt_destroy(h); return CMT_EHIP; }
+  h->ev.assign(512, nullptr);
   for (auto& ev : h->ev)
-    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) { delete h; return CMT_EHIP; }
+    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) { cmt_destroy(h); return CMT_EHIP; }
   h->h_flags = (int*)(h->h_loss + 8);
   h->h_loss[0] = 0.f; h->h_loss[1] = 0.f; *h->h_flags = 0;
   *out = h;
@@ -874,7 +874,9 @@ int cmt_create(const cmt_config* cfg, void* params_dev, void* grads_dev, void* w
 void cmt_destroy(cmt_handle* h) {
   if (!h) return;
   if (h->h_loss) (void)hipHostFree(h->h_loss);
+  if (h->side) (void)hipStreamSynchronize(h->side);
   for (auto ev : h->ev) if (ev) (void)hipEventDestroy(ev);
+  for (auto ev : h->phase_ev) if (ev) (void)hipEventDestroy(ev);
   if (h->side) (void)hipStreamDestroy(h->side);
   delete h;
 }

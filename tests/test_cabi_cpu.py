@@ -96,3 +96,42 @@ def test_workload_generators_follow_the_recipe():
     t = I.CONFIGS["tiny"]
     s2, sl2, _, _ = I.make_batch(t)
     assert s2.shape == (8, 10) and (sl2 == 10).all()
+
+
+C_PROGRAM = r"""
+#include <stdio.h>
+#include "cytonmt_hip.h"
+int main(void) {
+  cmt_config c;
+  size_t pb = 0, gb = 0, wb = 0;
+  c.src_vocab = 1000; c.tgt_vocab = 1000; c.emb_dim = 64; c.hidden = 64; c.layers = 1;
+  c.max_batch = 8; c.max_src_len = 10; c.max_tgt_len = 10; c.precision = 0; c.bos_id = 2; c.pad_id = 0;
+  if (cmt_query_sizes(&c, &pb, &gb, &wb) != CMT_OK) return 1;
+  c.hidden = 65;
+  if (cmt_query_sizes(&c, &pb, &gb, &wb) != CMT_EINVAL) return 2;
+  printf("%zu %zu %zu\n", pb, gb, wb);
+  return 0;
+}
+"""
+
+
+def test_header_is_plain_c_and_a_c_program_links_against_the_library(lib, tmp_path):
+    """The boundary is usable without Python or C++: the header compiles as C99 (pedantic) and as C++,
+    and a C program linked against the library calls a host-only entry point."""
+    import shutil
+    import subprocess
+    inc = os.path.join(ROOT, "include")
+    src = tmp_path / "prog.c"
+    src.write_text(C_PROGRAM)
+    exe = tmp_path / "prog"
+    libdir = os.path.dirname(binding.LIB_PATH)
+    rocm_lib = "/opt/rocm/lib"
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", inc, str(src), "-o", str(exe),
+                    "-L", libdir, "-lcytonmt_hip", f"-Wl,-rpath,{libdir}", f"-Wl,-rpath,{rocm_lib}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    cfg = I.model_cfg(I.CONFIGS["tiny"])
+    assert int(out[0]) == int(out[1]) == 4 * I.param_count(cfg) and int(out[2]) > 0
+    if shutil.which("g++"):
+        cpp = tmp_path / "prog.cpp"
+        cpp.write_text('#include "cytonmt_hip.h"\nint main() { return cmt_param_count(nullptr) == CMT_EINVAL ? 0 : 1; }\n')
+        subprocess.run(["g++", "-std=c++17", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, str(cpp)], check=True)
