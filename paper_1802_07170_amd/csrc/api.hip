@@ -243,6 +243,8 @@ size_t layout(cmt_handle* h, char* base) {
     bs.fin_par = (int32_t*)a.take((size_t)Bp * 4); bs.fin_tok = (int32_t*)a.take((size_t)Bp * 4);
     bs.hist_tok = (int32_t*)a.take(Mt * 4); bs.hist_par = (int32_t*)a.take(Mt * 4);
     bs.hist_ld = Bp;
+    bs.row_lse = (float*)a.take((size_t)Bp * 4);
+    bs.cand_z = (float*)a.take((size_t)Bp * 16 * 4); bs.cand_tok = (int32_t*)a.take((size_t)Bp * 16 * 4);
   }
   h->Cs = a.take(Mt * PH * esz); h->CsT = a.take(Mt * H * esz);
   h->att_a = (float*)a.take(Mt * Sm * 4); h->att_ds = (float*)a.take(Mt * Sm * 4);

@@ -1,9 +1,10 @@
 // Beam search bookkeeping on the device (hyperparameter table: beam size 10, length penalty 0.6;
 // the Settings section names the length normalisation of Wu et al. 2016).  The decoder runs on
 // R = B * K rows, row r = b * K + s holding live hypothesis s of sentence b.  Per step:
-//   beam_select_kernel  one workgroup per sentence: log-softmax of the live rows' logits, the K best
-//                       one-token extensions over all live hypotheses (equal scores: the lower
-//                       (slot, token) pair first), finished hypotheses split off, history written;
+//   beam_row_topk_kernel one workgroup per live row: log-sum-exp of its logits and its K best tokens;
+//   beam_merge_kernel   one workgroup per sentence: the K best one-token extensions over all live
+//                       hypotheses (equal scores: the lower (slot, token) pair first), finished
+//                       hypotheses split off, history written;
 //   beam_reorder_kernel the surviving hypotheses' decoder states and H_o move to their new rows.
 // After the last step beam_finish_kernel walks the back-pointers of each sentence's best finished
 // hypothesis.  Nothing returns to the host inside the loop.
@@ -54,94 +55,152 @@ void launch_beam_init(const BeamState& bs, int B, int Rp, int K, int bos, const 
 }
 
 constexpr int BEAM_MAX = 16;
+constexpr int BEAM_CAND_CAP = 2048;     // candidates a row's workgroup keeps in LDS
 
-// (value, flat index) ordering: larger value first, then lower index
+// (value, index) ordering: larger value first, then lower index
 __device__ __forceinline__ bool beam_better(float v, int f, float bv, int bf) { return v > bv || (v == bv && f < bf); }
 
-__global__ __launch_bounds__(1024) void beam_select_kernel(const float* __restrict__ z, int V, BeamState bs, int K, int j, int max_len,
-                                                           int eos, float alpha) {
-  __shared__ float s_red[16];
-  __shared__ int s_redi[16];
-  __shared__ int s_redo[16];
-  __shared__ float s_lse[BEAM_MAX];
+// Workgroup-wide best (value, index) pair of 256 threads; every thread gets the result.
+__device__ __forceinline__ void beam_block_best(float& v, int& f, float* s_v, int* s_f) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(v, o, 64);
+    const int of = __shfl_xor(f, o, 64);
+    if (beam_better(ov, of, v, f)) { v = ov; f = of; }
+  }
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  __syncthreads();                                       // the previous round's readers are done
+  if (lane == 0) { s_v[w] = v; s_f[w] = f; }
+  __syncthreads();
+  v = s_v[0]; f = s_f[0];
+#pragma unroll
+  for (int q = 1; q < 4; ++q)
+    if (beam_better(s_v[q], s_f[q], v, f)) { v = s_v[q]; f = s_f[q]; }
+}
+
+// One workgroup per hypothesis row: log-sum-exp of the row's logits and its K best tokens (larger
+// logit first, then lower token), written best first; entries beyond the row's candidates are
+// (-inf, INT_MAX).  The K best of a row contain every extension of it that can be among the K best
+// of its sentence (log-softmax is monotonic within a row).
+//   pass 1: every thread's best element; the K-th best of those 256 is a lower bound tau on the
+//           row's K-th best logit;
+//   pass 2: sum of exp(z - max), and the elements >= tau are appended to a list in LDS;
+//   then K rounds of a workgroup-wide arg-max over that list.  A list that overflows (many equal
+//   logits) falls back to K rounds over the row itself.
+__global__ __launch_bounds__(256) void beam_row_topk_kernel(const float* __restrict__ z, int V, BeamState bs, int K) {
+  __shared__ float s_v[4];
+  __shared__ int s_f[4];
+  __shared__ float s_sum[4];
+  __shared__ float s_cv[BEAM_CAND_CAP];
+  __shared__ int s_ci[BEAM_CAND_CAP];
+  __shared__ int s_n;
+  const int r = blockIdx.x, t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const int b = r / K, slot = r - b * K;
+  if (slot >= bs.nlive[b]) return;                       // dead row (uniform over the workgroup)
+  const float* zr = z + (size_t)r * V;
+  const int nv4 = V >> 2;                                // V is a multiple of 8
+  // ---- pass 1 ----------------------------------------------------------------------------------------
+  float tv = -INFINITY; int ti = 0x7fffffff;
+  for (int c = t; c < nv4; c += 256) {
+    const float4 q = *reinterpret_cast<const float4*>(zr + 4 * c);
+    if (beam_better(q.x, 4 * c, tv, ti)) { tv = q.x; ti = 4 * c; }
+    if (beam_better(q.y, 4 * c + 1, tv, ti)) { tv = q.y; ti = 4 * c + 1; }
+    if (beam_better(q.z, 4 * c + 2, tv, ti)) { tv = q.z; ti = 4 * c + 2; }
+    if (beam_better(q.w, 4 * c + 3, tv, ti)) { tv = q.w; ti = 4 * c + 3; }
+  }
+  float mx = -INFINITY, tau = -INFINITY;
+  {
+    bool taken = false;
+    for (int round = 0; round < K; ++round) {
+      float v = taken ? -INFINITY : tv;
+      int f = taken ? 0x7fffffff : ti;
+      beam_block_best(v, f, s_v, s_f);
+      if (round == 0) mx = v;
+      tau = v;                                           // -inf when fewer than K threads hold an element
+      if (!taken && f == ti) taken = true;
+    }
+  }
+  if (t == 0) s_n = 0;
+  __syncthreads();
+  // ---- pass 2 ----------------------------------------------------------------------------------------
+  float e = 0.f;
+  for (int c = t; c < nv4; c += 256) {
+    const float4 q = *reinterpret_cast<const float4*>(zr + 4 * c);
+    const float x[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      e += expf(x[i] - mx);
+      if (x[i] >= tau) {
+        const int pos = atomicAdd(&s_n, 1);
+        if (pos < BEAM_CAND_CAP) { s_cv[pos] = x[i]; s_ci[pos] = 4 * c + i; }
+      }
+    }
+  }
+  e = wave_sum(e);
+  if (lane == 0) s_sum[w] = e;
+  __syncthreads();
+  if (t == 0) bs.row_lse[r] = mx + logf((s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]));
+  const int n = s_n;
+  // ---- K rounds: the best element strictly after the previous winner in the (value, token) order ---------
+  float pv = INFINITY; int pi = -1;
+  for (int round = 0; round < K; ++round) {
+    float v = -INFINITY; int f = 0x7fffffff;
+    if (n <= BEAM_CAND_CAP) {
+      for (int q = t; q < n; q += 256) {
+        const float x = s_cv[q]; const int xi = s_ci[q];
+        if ((x < pv || (x == pv && xi > pi)) && beam_better(x, xi, v, f)) { v = x; f = xi; }
+      }
+    } else {
+      for (int c = t; c < nv4; c += 256) {
+        const float4 q = *reinterpret_cast<const float4*>(zr + 4 * c);
+        const float x[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int xi = 4 * c + i;
+          if ((x[i] < pv || (x[i] == pv && xi > pi)) && beam_better(x[i], xi, v, f)) { v = x[i]; f = xi; }
+        }
+      }
+    }
+    beam_block_best(v, f, s_v, s_f);
+    if (t == 0) { bs.cand_z[(size_t)r * BEAM_MAX + round] = v; bs.cand_tok[(size_t)r * BEAM_MAX + round] = f; }
+    pv = v; pi = f;
+  }
+}
+
+// One workgroup per sentence: the K best one-token extensions over the candidates of its live rows
+// (equal scores: the lower (slot, token) pair first), finished hypotheses split off, history written.
+__global__ __launch_bounds__(256) void beam_merge_kernel(int V, BeamState bs, int K, int j, int max_len, int eos, float alpha) {
+  __shared__ float s_v[4];
+  __shared__ int s_f[4];
   __shared__ float s_winv[BEAM_MAX];
   __shared__ int s_winf[BEAM_MAX];
-  __shared__ float s_b;
-  __shared__ int s_bi, s_bo;
-  const int b = blockIdx.x, t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const int b = blockIdx.x, t = threadIdx.x;
   const int nl = bs.nlive[b];
   const int row0 = b * K;
   if (nl == 0) {                                         // the sentence is done (uniform over the workgroup)
     if (t < K) { bs.parent[row0 + t] = -1; bs.new_cum[row0 + t] = -INFINITY; }
     return;
   }
-  // ---- log-sum-exp of every live row ---------------------------------------------------------------
-  for (int s = 0; s < nl; ++s) {
-    const float* zr = z + (size_t)(row0 + s) * V;
-    float mx = -INFINITY;
-    for (int v = t; v < V; v += 1024) mx = fmaxf(mx, zr[v]);
-    mx = wave_max(mx);
-    if (lane == 0) s_red[w] = mx;
-    __syncthreads();
-    mx = s_red[0];
-    for (int q = 1; q < 16; ++q) mx = fmaxf(mx, s_red[q]);
-    __syncthreads();
-    float e = 0.f;
-    for (int v = t; v < V; v += 1024) e += expf(zr[v] - mx);
-    e = wave_sum(e);
-    if (lane == 0) s_red[w] = e;
-    __syncthreads();
-    if (t == 0) {
-      float tot = 0.f;
-      for (int q = 0; q < 16; ++q) tot += s_red[q];
-      s_lse[s] = mx + logf(tot);
-    }
-    __syncthreads();
-  }
-  // ---- every thread's K best candidates, best first ---------------------------------------------------
-  float lv[BEAM_MAX];
-  int lf[BEAM_MAX];
-#pragma unroll
-  for (int q = 0; q < BEAM_MAX; ++q) { lv[q] = -INFINITY; lf[q] = 0x7fffffff; }
-  for (int s = 0; s < nl; ++s) {
-    const float base = bs.cum[row0 + s] - s_lse[s];
-    const float* zr = z + (size_t)(row0 + s) * V;
-    for (int v = t; v < V; v += 1024) {
-      const float val = base + zr[v];
-      const int f = s * V + v;
-      if (beam_better(val, f, lv[K - 1], lf[K - 1])) {   // insert, keeping the list sorted
-        int q = K - 1;
-        while (q > 0 && beam_better(val, f, lv[q - 1], lf[q - 1])) { lv[q] = lv[q - 1]; lf[q] = lf[q - 1]; --q; }
-        lv[q] = val; lf[q] = f;
-      }
+  // thread t holds candidate t % K of live row t / K (K * K <= 256)
+  float cv = -INFINITY; int cf = 0x7fffffff;
+  {
+    const int s = t / K, i = t - s * K;
+    if (s < nl) {
+      const int r = row0 + s;
+      const float zc = bs.cand_z[(size_t)r * BEAM_MAX + i];
+      const int tk = bs.cand_tok[(size_t)r * BEAM_MAX + i];
+      if (tk != 0x7fffffff) { cv = (bs.cum[r] - bs.row_lse[r]) + zc; cf = s * V + tk; }
     }
   }
-  // ---- K rounds: the best head over all threads wins, its owner moves to its next candidate -----------
-  int head = 0;
+  bool taken = false;
   for (int round = 0; round < K; ++round) {
-    float bv = head < K ? lv[head] : -INFINITY;
-    int bf = head < K ? lf[head] : 0x7fffffff;
-    int bo = t;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const float ov = __shfl_xor(bv, o, 64);
-      const int of = __shfl_xor(bf, o, 64);
-      const int oo = __shfl_xor(bo, o, 64);
-      if (beam_better(ov, of, bv, bf)) { bv = ov; bf = of; bo = oo; }
-    }
-    if (lane == 0) { s_red[w] = bv; s_redi[w] = bf; s_redo[w] = bo; }
-    __syncthreads();
-    if (t == 0) {
-      float v = s_red[0]; int f = s_redi[0], o = s_redo[0];
-      for (int q = 1; q < 16; ++q)
-        if (beam_better(s_red[q], s_redi[q], v, f)) { v = s_red[q]; f = s_redi[q]; o = s_redo[q]; }
-      s_b = v; s_bi = f; s_bo = o;
-      s_winv[round] = v; s_winf[round] = f;
-    }
-    __syncthreads();
-    if (t == s_bo) ++head;
-    __syncthreads();
+    float v = taken ? -INFINITY : cv;
+    int f = taken ? 0x7fffffff : cf;
+    beam_block_best(v, f, s_v, s_f);
+    if (t == 0) { s_winv[round] = v; s_winf[round] = f; }
+    if (!taken && f == cf && cf != 0x7fffffff) taken = true;
   }
+  __syncthreads();
   // ---- split the winners into finished and live hypotheses ---------------------------------------------
   if (t == 0) {
     int n_new = 0;
@@ -172,7 +231,8 @@ __global__ __launch_bounds__(1024) void beam_select_kernel(const float* __restri
 }
 void launch_beam_select(const float* z, int V, const BeamState& bs, int B, int K, int j, int max_len, int eos, float alpha,
                         hipStream_t st) {
-  hipLaunchKernelGGL(beam_select_kernel, dim3(B), dim3(1024), 0, st, z, V, bs, K, j, max_len, eos, alpha);
+  hipLaunchKernelGGL(beam_row_topk_kernel, dim3(B * K), dim3(256), 0, st, z, V, bs, K);
+  hipLaunchKernelGGL(beam_merge_kernel, dim3(B), dim3(256), 0, st, V, bs, K, j, max_len, eos, alpha);
 }
 
 // New row r takes the states of row parent[r] (or stays dead): per layer h (T) and c (fp32), and the

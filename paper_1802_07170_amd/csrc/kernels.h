@@ -187,6 +187,8 @@ struct BeamState {
   float* fin_score; int32_t* fin_step; int32_t* fin_par; int32_t* fin_tok;   // [B] best finished hypothesis
   int32_t* hist_tok; int32_t* hist_par;  // [steps, hist_ld] token / parent slot of every live hypothesis per step
   int hist_ld;
+  float* row_lse;                        // [Rp] log-sum-exp of the row's logits of the current step
+  float* cand_z; int32_t* cand_tok;      // [Rp, 16] the row's best logits / tokens of the current step, best first
 };
 struct BeamReorder {
   const void* h_src[8]; void* h_dst[8]; int ldh;     // per layer: states written by the step -> states the next step reads

@@ -230,7 +230,9 @@ void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh,
   const int nbt = (Bp + 15) / 16;
   // measured (bf16, hidden 1024): 64 sentences — 32 gate rows x 32 sentences per workgroup: 9.9 us against
   // 11.3 us for 16 rows x 64 sentences; more than 64 sentences — 32 rows x 64 sentences
-  if (how == 0) how = (Bp > 64) ? 2 : (prec && nbt == 4) ? 6 : 1;   // (32 sentences: 16 rows x 32 sentences is faster)
+  // (32 sentences: 16 rows x 32 sentences is faster; 640 sentences, as in beam search: 64 rows x 64 sentences,
+  // 65 us against 80 us; 128 sentences: 32 rows, 14.7 us against 19.7 us)
+  if (how == 0) how = (Bp >= 256) ? 4 : (Bp > 64) ? 2 : (prec && nbt == 4) ? 6 : 1;
   const int nsteps = (K / 8 + 3) / 4;
   if (prec) {
     if (how == 6) {

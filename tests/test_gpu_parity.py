@@ -142,11 +142,12 @@ def test_ragged_small_nets(prec, B, S, T, H, E, L):
 
 @pytest.mark.parametrize("prec", [0, 1])
 @pytest.mark.parametrize("B,S,T,H,E,L,Vs,Vt", [(1, 1, 1, 16, 8, 1, 8, 8), (2, 2, 3, 64, 2048, 1, 16, 24),
-                                               (200, 3, 3, 32, 16, 1, 104, 136), (130, 2, 2, 64, 16, 2, 40, 72)])
+                                               (200, 3, 3, 32, 16, 1, 104, 136), (130, 2, 2, 64, 16, 2, 40, 72),
+                                               (260, 3, 2, 48, 24, 3, 40, 72)])
 def test_extreme_configurations(prec, B, S, T, H, E, L, Vs, Vt):
     """The smallest model the library accepts (hidden 16, embedding 8, vocabularies of 8, one sentence of
     one token each side), the widest embedding (2048), and batches of 200 and 130 sentences (more than
-    one 64-sentence block per weight tile, the last one ragged)."""
+    one 64-sentence block per weight tile, the last one ragged; 260 sentences: five blocks)."""
     cfg = dict(src_vocab=Vs, tgt_vocab=Vt, emb=E, hidden=H, layers=L)
     rng = np.random.default_rng(300 + B)
     params = I.make_params(cfg, seed=40 + B, scale=0.3 if E <= 128 else 0.05)
@@ -294,6 +295,35 @@ def test_beam_search_matches_the_oracle(prec, B, S, H, E, L, max_len, beam):
     if beam == 1:
         gids, glens = tr.greedy_decode(src, sl, max_len, eos_id=3)
         assert np.array_equal(gids, ids) and np.array_equal(glens, lens)
+    tr.close()
+
+
+def test_beam_search_with_massively_tied_logits():
+    """W_o = 0: every row's logits are B_o, here five entries at 1.0, one (the end token) at 0.5 and 2050
+    exact zeros.  The candidate threshold of the per-row selection then admits the whole vocabulary
+    (more than its list holds), so the selection runs over the row itself; ties must resolve to the lower
+    (slot, token) pair exactly as in the oracle."""
+    from paper_1802_07170_amd import binding
+    cfg = dict(src_vocab=104, tgt_vocab=2056, emb=8, hidden=16, layers=1)
+    rng = np.random.default_rng(5)
+    params = I.make_params(cfg, seed=3, scale=0.5)
+    params["W_o"] = np.zeros_like(params["W_o"])
+    bo = np.zeros_like(params["B_o"])
+    bo[[100, 700, 701, 1500, 2055]] = 1.0
+    bo[3] = 0.5
+    params["B_o"] = bo
+    src, sl, _, _ = ragged_batch(rng, 3, 3, 4, 104, 2056)
+    tr = binding.Trainer(cfg, 3 * 8, 4, 6, precision=0)
+    tr.set_params(I.flatten(params, cfg))
+    for max_len, beam in [(5, 8), (3, 1), (4, 16)]:
+        if 3 * beam > 24:
+            tr.close()
+            tr = binding.Trainer(cfg, 3 * beam, 4, 6, precision=0)
+            tr.set_params(I.flatten(params, cfg))
+        ids, lens, score = tr.beam_decode(src, sl, max_len, beam=beam, length_penalty=0.6, eos_id=3)
+        oids, olens, oscore, _ = O.beam_decode(cfg, params, src, sl, max_len, beam, 0.6, bos_id=2, eos_id=3)
+        assert np.array_equal(ids, oids) and np.array_equal(lens, olens), (max_len, beam, ids, oids)
+        assert np.allclose(score, oscore, rtol=1e-5)
     tr.close()
 
 
