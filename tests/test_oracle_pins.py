@@ -474,6 +474,32 @@ def test_greedy_decode_end_token_and_length_cap():
     assert np.array_equal(one[0], ids[1]) and l1[0] == lens[1]
 
 
+def test_ties_go_to_the_lower_token_and_the_lower_slot():
+    """W_o = 0 makes every row's logits B_o, so ties are exact.  Greedy: the lowest index among equal
+    maxima.  Beam: with tokens 5, 7, 9 tied at the top every hypothesis of a step has the same score
+    per token; survivors are ordered by (slot, token), so the result is the sequence of all 5s, and
+    the beam's second and third rows descend from slot 0 as well."""
+    cfg = tiny_cfg(H=4, L=1)
+    p = rand_params(cfg, seed=45)
+    src, sl, _, _ = tiny_batch(cfg)
+    p["W_o"] = np.zeros_like(p["W_o"])
+    bo = np.full_like(p["B_o"], -1.0)
+    bo[[5, 7, 9]] = 2.0
+    p["B_o"] = bo
+    ids, lens, _ = O.greedy_decode(cfg, p, src, sl, 4, eos_id=3)
+    assert np.all(ids == 5) and np.all(lens == 4)
+    bids, blens, bscore, _ = O.beam_decode(cfg, p, src, sl, 4, beam=3, alpha=0.6, eos_id=3)
+    assert np.all(bids == 5) and np.all(blens == 4)
+    logp = 2.0 - np.log(3 * np.exp(2.0) + (bo.size - 3) * np.exp(-1.0))
+    np.testing.assert_allclose(bscore, 4 * logp / O.length_penalty(4, 0.6), rtol=1e-12)
+    # an end token tied with the best continuation: finishing (a lower token here: 3 < 5) comes first in the
+    # (slot, token) order, and a finished hypothesis of length 1 beats every longer one of equal per-token score
+    bo[3] = 2.0
+    p["B_o"] = bo
+    ids, lens, _ = O.greedy_decode(cfg, p, src, sl, 4, eos_id=3)
+    assert np.all(ids[:, 0] == 3) and np.all(lens == 1)
+
+
 def test_beam_of_one_is_greedy_and_length_penalty_closed_form():
     assert O.length_penalty(1, 0.6) == 1.0 and O.length_penalty(7, 1.0) == 2.0
     assert abs(O.length_penalty(19, 0.5) - 2.0) < 1e-15
