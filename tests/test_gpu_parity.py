@@ -125,13 +125,14 @@ def test_tiny_config_fp32():
 @pytest.mark.parametrize("prec", [0, 1])
 @pytest.mark.parametrize("B,S,T,H,E,L", [(5, 7, 9, 32, 24, 1), (19, 13, 11, 80, 40, 2), (3, 1, 1, 16, 8, 3),
                                          (70, 5, 4, 48, 16, 2), (3, 3, 2, 1024, 16, 2), (4, 6, 5, 32, 16, 8),
-                                         (64, 4, 3, 64, 32, 2), (1, 510, 3, 32, 16, 1), (2, 3, 70, 32, 16, 2)])
+                                         (64, 4, 3, 64, 32, 2), (1, 510, 3, 32, 16, 1), (2, 3, 70, 32, 16, 2),
+                                         (2, 3, 300, 16, 8, 1)])
 def test_ragged_small_nets(prec, B, S, T, H, E, L):
     """Odd batch (not a multiple of 16), ragged lengths incl. length 1, sizes that are not
     multiples of the kernels' tiles, a repeated token id, workspace larger than the batch; the deepest
     stack the library accepts (8 layers: seven layer-steps per wavefront launch); a batch of exactly 64
     (the 32-row x 32-sentence LSTM step kernel); a single sentence with the longest source the
-    library accepts (512 positions with the workspace margin); a long target."""
+    library accepts (512 positions with the workspace margin); long targets (70 and 300 positions)."""
     cfg = dict(src_vocab=104, tgt_vocab=136, emb=E, hidden=H, layers=L)
     rng = np.random.default_rng(100 + B)
     params = I.make_params(cfg, seed=B, scale=0.3 if H <= 128 else 0.05)
