@@ -8,7 +8,10 @@ import types
 
 import pytest
 
-from tests import test_oracle_pins as pins
+try:
+    from tests import test_oracle_pins as pins
+except ImportError:                       # pytest started with tests/ itself on the path
+    import test_oracle_pins as pins
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SOURCE = open(os.path.join(ROOT, "oracle", "nmt_oracle.py")).read()
