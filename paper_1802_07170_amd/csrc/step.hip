@@ -717,25 +717,34 @@ __global__ __launch_bounds__(256) void att_deferred_kernel(const float* __restri
                                                            const float* __restrict__ dCs, int lddc, const T* __restrict__ Ht,
                                                            int ldht, int S, int Tn, int Bp, int H, float* __restrict__ dHs,
                                                            T* __restrict__ dK) {
-  __shared__ float sa[32], sd[32];
+  constexpr int JB = 8;                              // decoder steps per pass: their loads are issued together
+  __shared__ float sa[JB][32], sd[JB][32];
   const int b = blockIdx.x, h = blockIdx.y * 256 + threadIdx.x, i0 = blockIdx.z * 32;
   float accC[32], accK[32];
 #pragma unroll
   for (int i = 0; i < 32; ++i) { accC[i] = 0.f; accK[i] = 0.f; }
-  for (int j = 0; j < Tn; ++j) {
+  for (int j0 = 0; j0 < Tn; j0 += JB) {
     __syncthreads();
-    if (threadIdx.x < 32) {
-      const int i = i0 + threadIdx.x;
-      sa[threadIdx.x] = i < S ? a[((size_t)j * Bp + b) * S + i] : 0.f;
-      sd[threadIdx.x] = i < S ? ds[((size_t)j * Bp + b) * S + i] : 0.f;
+    {
+      const int jj = threadIdx.x >> 5, i = i0 + (threadIdx.x & 31);        // 256 threads = JB x 32
+      const int j = j0 + jj;
+      const bool ok = j < Tn && i < S;
+      sa[jj][threadIdx.x & 31] = ok ? a[((size_t)j * Bp + b) * S + i] : 0.f;
+      sd[jj][threadIdx.x & 31] = ok ? ds[((size_t)j * Bp + b) * S + i] : 0.f;
     }
-    __syncthreads();
-    if (h < H) {
-      const float dc = dCs[((size_t)j * Bp + b) * lddc + h];
-      const float ht = to_f<T>(Ht[((size_t)j * Bp + b) * ldht + h]);
+    float dc[JB], ht[JB];
 #pragma unroll
-      for (int i = 0; i < 32; ++i) { accC[i] += sa[i] * dc; accK[i] += sd[i] * ht; }
+    for (int jj = 0; jj < JB; ++jj) {
+      const int j = j0 + jj;
+      const bool ok = h < H && j < Tn;
+      dc[jj] = ok ? dCs[((size_t)j * Bp + b) * lddc + h] : 0.f;
+      ht[jj] = ok ? to_f<T>(Ht[((size_t)j * Bp + b) * ldht + h]) : 0.f;
     }
+    __syncthreads();
+#pragma unroll
+    for (int jj = 0; jj < JB; ++jj)                  // ascending j: the same summation order as one step at a time
+#pragma unroll
+      for (int i = 0; i < 32; ++i) { accC[i] += sa[jj][i] * dc[jj]; accK[i] += sd[jj][i] * ht[jj]; }
   }
   if (h >= H) return;
 #pragma unroll
