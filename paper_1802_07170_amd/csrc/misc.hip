@@ -175,7 +175,13 @@ __global__ __launch_bounds__(256) void sum_parts_kernel(const float* __restrict_
   const size_t stride = (size_t)gridDim.x * 256;
   for (; i < n; i += stride) {
     float a = 0.f;
-    for (int p = 0; p < nparts; ++p) a += parts[(size_t)p * n + i];
+    for (int p0 = 0; p0 < nparts; p0 += 8) {       // eight loads in flight, added in ascending order
+      float v[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) v[q] = p0 + q < nparts ? parts[(size_t)(p0 + q) * n + i] : 0.f;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) a += v[q];
+    }
     out[i] = a;
   }
 }
