@@ -493,11 +493,13 @@ template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t* p, const floa
   *reinterpret_cast<uint2*>(p) = o;
 }
 
-// one thread per (sentence, 4 consecutive units)
+// one thread per (sentence, 4 consecutive units); single-wavefront workgroups, so that the 16 K threads
+// of a 64-sentence x 1024-unit step spread over all CUs
+constexpr int LSTM_BWD_POINT_THREADS = 64;
 template <typename T>
-__global__ __launch_bounds__(256) void lstm_bwd_point_kernel(LstmBwdPointArgs args, int Bp, int Hh) {
+__global__ __launch_bounds__(LSTM_BWD_POINT_THREADS) void lstm_bwd_point_kernel(LstmBwdPointArgs args, int Bp, int Hh) {
   const LstmBwdPoint& p = args.p[blockIdx.y];
-  const int idx4 = blockIdx.x * 256 + threadIdx.x;
+  const int idx4 = blockIdx.x * LSTM_BWD_POINT_THREADS + threadIdx.x;
   const int hq = Hh >> 2;
   if (idx4 >= Bp * hq) return;
   const int b = idx4 / hq, u = (idx4 - b * hq) * 4;
@@ -543,9 +545,9 @@ void launch_lstm_bwd_point_multi(int prec, const LstmBwdPoint* ps, int n, int Bp
   LstmBwdPointArgs a;
   for (int i = 0; i < STEP_MAX_INST; ++i) a.p[i] = ps[i < n ? i : 0];
   const int cnt = Bp * (Hh >> 2);
-  const dim3 grid((cnt + 255) / 256, n);
-  if (prec) hipLaunchKernelGGL(lstm_bwd_point_kernel<bf16_t>, grid, dim3(256), 0, st, a, Bp, Hh);
-  else hipLaunchKernelGGL(lstm_bwd_point_kernel<float>, grid, dim3(256), 0, st, a, Bp, Hh);
+  const dim3 grid((cnt + LSTM_BWD_POINT_THREADS - 1) / LSTM_BWD_POINT_THREADS, n);
+  if (prec) hipLaunchKernelGGL(lstm_bwd_point_kernel<bf16_t>, grid, dim3(LSTM_BWD_POINT_THREADS), 0, st, a, Bp, Hh);
+  else hipLaunchKernelGGL(lstm_bwd_point_kernel<float>, grid, dim3(LSTM_BWD_POINT_THREADS), 0, st, a, Bp, Hh);
 }
 void launch_lstm_bwd_point(int prec, const LstmBwdPoint& p, int Bp, int Hh, hipStream_t st) {
   launch_lstm_bwd_point_multi(prec, &p, 1, Bp, Hh, st);
@@ -787,9 +789,9 @@ template __global__ void tanh_planes_kernel<float>(Planes, float*, int, float*, 
 
 // dpre = (dHo_ce + feed) * (1 - Ho^2) -> T; feed arrives as planes (np = 0: none); 4 columns per thread
 template <typename T>
-__global__ __launch_bounds__(256) void tanh_bwd_kernel(const float* __restrict__ dce, Planes feed, const T* __restrict__ Ho,
-                                                       int ldho, T* __restrict__ dpre, int ldp, int Bp, int H, DropSpec drop) {
-  const int i4 = blockIdx.x * 256 + threadIdx.x;
+__global__ __launch_bounds__(64) void tanh_bwd_kernel(const float* __restrict__ dce, Planes feed, const T* __restrict__ Ho,
+                                                      int ldho, T* __restrict__ dpre, int ldp, int Bp, int H, DropSpec drop) {
+  const int i4 = blockIdx.x * 64 + threadIdx.x;        // single-wavefront workgroups: spread over all CUs
   const int hq = H >> 2;
   if (i4 >= Bp * hq) return;
   const int b = i4 / hq, h = (i4 - b * hq) * 4;
@@ -808,9 +810,9 @@ __global__ __launch_bounds__(256) void tanh_bwd_kernel(const float* __restrict__
 void launch_tanh_bwd(int prec, const float* dHo_ce, const Planes& feed, const void* Ho, int ldho, void* dpre, int ldp, int Bp, int H,
                      const DropSpec& drop, hipStream_t st) {
   const int n = Bp * (H >> 2);
-  if (prec) hipLaunchKernelGGL(tanh_bwd_kernel<bf16_t>, dim3((n + 255) / 256), dim3(256), 0, st, dHo_ce, feed,
+  if (prec) hipLaunchKernelGGL(tanh_bwd_kernel<bf16_t>, dim3((n + 63) / 64), dim3(64), 0, st, dHo_ce, feed,
                                (const bf16_t*)Ho, ldho, (bf16_t*)dpre, ldp, Bp, H, drop);
-  else hipLaunchKernelGGL(tanh_bwd_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, st, dHo_ce, feed,
+  else hipLaunchKernelGGL(tanh_bwd_kernel<float>, dim3((n + 63) / 64), dim3(64), 0, st, dHo_ce, feed,
                           (const float*)Ho, ldho, (float*)dpre, ldp, Bp, H, drop);
 }
 
