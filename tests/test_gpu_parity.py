@@ -18,7 +18,10 @@ def bf16_round(x):
     return u.astype(np.uint32).view(np.float32)
 
 
-def check_grads(g, og, prec, label=""):
+def check_grads(g, og, prec, label="", l2_override=None, elementwise=True):
+    """l2_override: {tensor: relative-L2 bound} replacing the bar for those tensors; elementwise=False
+    drops the per-entry bound.  Both are 'off' for every case the task names; the random sweep states
+    why it uses them."""
     worst = {}
     for k, v in og.items():
         a = g[k].astype(np.float64)
@@ -31,13 +34,15 @@ def check_grads(g, og, prec, label=""):
         else:
             tol_l2 = 2e-2
             bound = 2e-2 * np.abs(v) + 1e-3
+        if l2_override and k in l2_override:
+            tol_l2 = l2_override[k]
         assert rel <= tol_l2, f"{label}{k}: relative L2 {rel:.3e} > {tol_l2}"
         bad = np.abs(a - v) > bound
-        assert not bad.any(), f"{label}{k}: {bad.sum()} elements outside the elementwise bound"
+        assert not (elementwise and bad.any()), f"{label}{k}: {bad.sum()} elements outside the elementwise bound"
     return worst
 
 
-def run_case(cfg, params, batch, prec, max_shape=None, check_inter=True, reg=None):
+def run_case(cfg, params, batch, prec, max_shape=None, check_inter=True, reg=None, **grad_check):
     """reg: None or (dropout, label_smoothing, dropout_seed) — handed to both sides."""
     from paper_1802_07170_amd import binding
     src, sl, tgt, tl = batch
@@ -56,7 +61,7 @@ def run_case(cfg, params, batch, prec, max_shape=None, check_inter=True, reg=Non
         oloss, og, it = O.train_step(cfg, params, *batch, want_intermediates=True, **okw)
         tol = 1e-4 if prec == 0 else 2e-2
         assert abs(loss - oloss) <= tol * abs(oloss), (loss, oloss)
-        worst = check_grads(g, og, prec)
+        worst = check_grads(g, og, prec, **grad_check)
         if check_inter:
             Bp = tr.padded_batch()
             H, E = cfg["hidden"], cfg["emb"]
@@ -155,6 +160,39 @@ def test_extreme_configurations(prec, B, S, T, H, E, L, Vs, Vt):
     batch = ragged_batch(rng, B, S, T, Vs, Vt)
     loss, oloss, worst, tr = run_case(cfg, params, batch, prec)
     tr.close()
+
+
+def test_random_shapes_sweep():
+    """32 seeded random combinations of batch (1..90, around the 16- and 64-sentence tile edges), lengths,
+    hidden / embedding sizes, depth 1..4, vocabularies, precision, and regularisation on or off, each
+    against the oracle with intermediates.  Its purpose is indexing and tiling, where a mistake is an error
+    of order one.  fp32 cases: the full bar.  bf16 cases: loss and relative L2 of every gradient tensor at
+    the bar (2e-2), without the per-entry bound (on these small, strongly driven nets — parameters up to
+    0.3, dropout up to 0.5 — a handful of entries per run land just outside 2e-2 |g| + 1e-3), and with W_a
+    held to 6e-2: the softmax Jacobian a (da - sum a da) cancels heavily, and rounding the PARAMETERS to bf16
+    alone moves the oracle's exact W_a gradient by up to 3 % on such nets (measured on the CPU).  On the
+    task's configurations and in every other test the full bf16 bar applies, W_a included."""
+    rng = np.random.default_rng(1)
+    for it in range(32):
+        B = int(rng.choice([1, 2, 3, 7, 15, 16, 17, 31, 33, 48, 63, 64, 65, 90]))
+        S, T = int(rng.integers(1, 12)), int(rng.integers(1, 12))
+        H = int(rng.choice([16, 32, 48, 64, 96, 128, 160, 256]))
+        E = int(rng.choice([8, 16, 24, 40, 64, 128]))
+        L = int(rng.integers(1, 5))
+        Vs, Vt = int(rng.choice([8, 40, 104, 264])), int(rng.choice([8, 72, 136, 328, 1000]))
+        prec = int(rng.integers(0, 2))
+        reg = None if rng.random() < 0.5 else (float(rng.choice([0.1, 0.2, 0.5])), float(rng.choice([0.0, 0.1])),
+                                               int(rng.integers(0, 1 << 40)))
+        cfg = dict(src_vocab=Vs, tgt_vocab=Vt, emb=E, hidden=H, layers=L)
+        params = I.make_params(cfg, seed=it, scale=0.3 if H <= 128 else 0.1)
+        batch = ragged_batch(rng, B, S, T, Vs, Vt, repeat_id=min(5, Vs - 1, Vt - 1))
+        margin = (B + int(rng.integers(0, 4)), S + int(rng.integers(0, 3)), T + int(rng.integers(0, 3)))
+        relax = dict(l2_override={"W_a": 6e-2}, elementwise=False) if prec else {}
+        try:
+            loss, oloss, worst, tr = run_case(cfg, params, batch, prec, max_shape=margin, reg=reg, **relax)
+        except AssertionError as e:
+            raise AssertionError(f"case {it}: B={B} S={S} T={T} H={H} E={E} L={L} Vs={Vs} Vt={Vt} prec={prec} reg={reg}: {e}")
+        tr.close()
 
 
 @pytest.mark.parametrize("prec", [0, 1])
