@@ -170,7 +170,7 @@ def test_random_shapes_sweep():
     the bar (2e-2), without the per-entry bound (on these small, strongly driven nets — parameters up to
     0.3, dropout up to 0.5 — a handful of entries per run land just outside 2e-2 |g| + 1e-3), and with W_a
     held to 6e-2: the softmax Jacobian a (da - sum a da) cancels heavily, and rounding the PARAMETERS to bf16
-    alone moves the oracle's exact W_a gradient by up to 3 % on such nets (measured on the CPU).  On the
+    alone moves the oracle's exact W_a gradient by 2-10 % on such nets (measured on the CPU).  On the
     task's configurations and in every other test the full bf16 bar applies, W_a included."""
     rng = np.random.default_rng(1)
     for it in range(32):
