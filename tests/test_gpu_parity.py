@@ -337,6 +337,49 @@ def test_beam_search_matches_the_oracle(prec, B, S, H, E, L, max_len, beam):
     tr.close()
 
 
+def test_random_decode_sweep():
+    """24 seeded random shapes (batch, source length, step cap, widths, depth, vocabularies incl. one
+    larger than the per-row candidate list, beam 1..16), fp32 path: greedy tokens and beam-search
+    hypotheses, lengths and scores identical to the oracle's wherever its decision gap exceeds what fp32
+    resolves."""
+    from paper_1802_07170_amd import binding
+    rng = np.random.default_rng(1)
+    for it in range(24):
+        B = int(rng.choice([1, 2, 3, 5, 7, 9, 16, 17]))
+        S, max_len = int(rng.integers(1, 10)), int(rng.integers(1, 10))
+        H, E = int(rng.choice([16, 32, 48, 64, 96, 128])), int(rng.choice([8, 16, 24, 40, 64]))
+        L = int(rng.integers(1, 4))
+        Vs, Vt = int(rng.choice([8, 40, 104])), int(rng.choice([8, 72, 136, 328, 2056]))
+        beam = int(rng.choice([1, 2, 3, 5, 10, 16]))
+        cfg = dict(src_vocab=Vs, tgt_vocab=Vt, emb=E, hidden=H, layers=L)
+        params = I.make_params(cfg, seed=it + 100, scale=0.4)
+        params["W_o"] = params["W_o"] * 6.0
+        params["B_o"] = params["B_o"].copy()
+        params["B_o"][3] += float(rng.choice([0.0, 3.0, 5.0]))
+        src, sl, _, _ = ragged_batch(rng, B, S, 4, Vs, Vt, repeat_id=min(5, Vs - 1, Vt - 1))
+        what = f"case {it}: B={B} S={S} max_len={max_len} H={H} E={E} L={L} Vs={Vs} Vt={Vt} beam={beam}"
+        tr = binding.Trainer(cfg, B * beam + int(rng.integers(0, 3)), S + int(rng.integers(0, 2)),
+                             max(2, max_len + int(rng.integers(0, 2))), precision=0)
+        tr.set_params(I.flatten(params, cfg))
+        tol = 2e-5 * 2.0 * np.linalg.norm(params["W_o"], axis=1).max()
+        ids, lens = tr.greedy_decode(src, sl, max_len, eos_id=3)
+        oids, olens, gaps = O.greedy_decode(cfg, params, src, sl, max_len, bos_id=2, eos_id=3)
+        for b in range(B):
+            diff = np.nonzero(ids[b] != oids[b])[0]
+            if diff.size:
+                j = int(diff[0])
+                assert j < olens[b] and gaps[b, j] < tol, (what, "greedy", b, j, ids[b], oids[b])
+            else:
+                assert lens[b] == olens[b], (what, "greedy length", b)
+        bids, blens, bscore = tr.beam_decode(src, sl, max_len, beam=beam, length_penalty=0.6, eos_id=3)
+        obids, oblens, oscore, margins = O.beam_decode(cfg, params, src, sl, max_len, beam, 0.6, bos_id=2, eos_id=3)
+        for b in range(B):
+            if margins[b] > tol * max_len:
+                assert np.array_equal(bids[b], obids[b]) and blens[b] == oblens[b], (what, "beam", b, bids[b], obids[b])
+                assert abs(bscore[b] - oscore[b]) <= tol * max_len + 1e-4 * abs(oscore[b]), (what, "score", b)
+        tr.close()
+
+
 def test_beam_search_with_massively_tied_logits():
     """W_o = 0: every row's logits are B_o, here five entries at 1.0, one (the end token) at 0.5 and 2050
     exact zeros.  The candidate threshold of the per-row selection then admits the whole vocabulary
