@@ -65,6 +65,9 @@ int cmt_query_sizes(const cmt_config* cfg, size_t* param_bytes, size_t* grad_byt
  * alive until cmt_destroy.  Parameters are uninitialised until cmt_init_params / cmt_set_params. */
 int cmt_create(const cmt_config* cfg, void* params_dev, void* grads_dev, void* workspace_dev,
                void* hip_stream, cmt_handle** out);
+/* Releases the handle, its pinned host memory, its internal stream and events (it waits for the
+ * internal stream first).  The caller synchronises its own stream before freeing the device buffers
+ * that asynchronous calls may still be using.  NULL is accepted. */
 void cmt_destroy(cmt_handle* h);
 
 /* Parameter table.  Canonical order: E_src[Vs,E], E_tgt[Vt,E], enc.l0.fwd.W[4Hd,E+Hd], .b[4Hd],
