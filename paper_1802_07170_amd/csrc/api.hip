@@ -106,6 +106,9 @@ struct cmt_handle {
   float* dHt = nullptr; float* wcp = nullptr;
   float* dXt = nullptr; char* XtT = nullptr;
   float *pmax = nullptr, *psum = nullptr, *zy = nullptr, *lse = nullptr, *nll = nullptr, *rowscale = nullptr;
+  // the output layer works on the valid target positions only, numbered densely on the device
+  int32_t *ce_pos = nullptr, *ce_row = nullptr, *ce_nvalid = nullptr, *labels_c = nullptr;
+  char* Hoc = nullptr; char* HocT = nullptr;   // H_o (as the output layer sees it) of the valid positions, and its transpose
   float* loss = nullptr; int* flags = nullptr; float* colscr = nullptr;
   char* dzs = nullptr; char* dzTs = nullptr; float* dbo_parts = nullptr;
   float* gsplit = nullptr; size_t gsplit_floats = 0;
@@ -259,6 +262,9 @@ size_t layout(cmt_handle* h, char* base) {
   h->pmax = (float*)a.take(Mt * np * 4); h->psum = (float*)a.take(Mt * np * 4); h->psz = (float*)a.take(Mt * np * 4);
   h->zy = (float*)a.take(Mt * 4); h->lse = (float*)a.take(Mt * 4); h->nll = (float*)a.take(Mt * 4);
   h->rowscale = (float*)a.take(Mt * 4);
+  h->ce_pos = (int32_t*)a.take(Mt * 4); h->ce_row = (int32_t*)a.take(Mt * 4); h->labels_c = (int32_t*)a.take(Mt * 4);
+  h->ce_nvalid = (int32_t*)a.take(256);
+  h->Hoc = a.take(Mt * PH * esz); h->HocT = a.take(Mt * H * esz);
   h->loss = (float*)a.take(256); h->flags = (int*)a.take(256);
   h->colscr = (float*)a.take((size_t)16 * 4 * H * 4);
   h->dzs = a.take(ce_slab_elems(c.tgt_vocab) * esz); h->dzTs = a.take(ce_slab_elems(c.tgt_vocab) * esz);
@@ -524,7 +530,8 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
                 nullptr, h->len_s, h->flags, st);
   launch_gather(p, h->Pw(h->off_Etgt), c.tgt_vocab, E, tgt_ids, tgt_len, B, Bp, T, 1, c.bos_id, h->Xt, h->mask_t,
                 h->tok_t, h->labels, h->len_t, h->flags, st);
-  launch_ce_rowscale(h->mask_t, Mt, h->rowscale, h->loss, st);   // n_tok and mask / n_tok: the lengths give them
+  // valid target positions numbered densely, n_tok, 1 / n_tok: the lengths give them
+  launch_ce_compact(h->mask_t, h->labels, Mt, h->ce_pos, h->ce_row, h->labels_c, h->rowscale, h->ce_nvalid, h->loss, st);
 
   const char* Hs; int ldHs;                        // source-side top-layer states [S, Bp, H] and their row pitch
   enqueue_encoder(h, S, &Hs, &ldHs);
@@ -559,20 +566,25 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   // scatters) runs on the library's second stream and joins at the end of the step.
   const char* Ho = HoFeed + BP * esz;              // [T*Bp, H], row pitch PH
   const int np = ce_num_partials(V);
+  // The output layer sees the valid target positions only: their H_o rows are gathered into a dense
+  // matrix (the count is known to the device alone, so launches are sized for all T * Bp rows and the
+  // kernels stop at the count).
+  launch_ce_gather_rows(p, Ho, PH, h->ce_row, h->ce_nvalid, Mt, h->Hoc, PH, H, st);
   if (forward_only) {                              // Eq. 1 and the loss only: logits slab by slab, no gradient
     int nslab;
     const int rows = ce_slab_plan(Mt, &nslab);
     int sl = 0;
     for (int m0 = 0; m0 < Mt; ++sl) {
       const int Mc = (sl == nslab - 1 || Mt - m0 < rows) ? Mt - m0 : rows;
-      launch_ce_fwd(p, Ho + (size_t)m0 * PH * esz, PH, h->Pw(h->off_Wo), P + h->off_Bo, h->labels + m0, Mc, V, H, h->dzTs,
+      const RowLimit lim{h->ce_nvalid, m0};
+      launch_ce_fwd(p, h->Hoc + (size_t)m0 * PH * esz, PH, h->Pw(h->off_Wo), P + h->off_Bo, h->labels_c + m0, Mc, V, H, h->dzTs,
                     h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, h->ls_eps > 0.f ? h->psz + (size_t)m0 * np : nullptr,
-                    h->zy + m0, st);
+                    h->zy + m0, st, lim);
       launch_ce_rows(h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, h->psz + (size_t)m0 * np, h->zy + m0,
-                     h->mask_t + m0, Mc, np, h->ls_eps, V, h->lse + m0, h->nll + m0, st);
+                     nullptr, Mc, np, h->ls_eps, V, h->lse + m0, h->nll + m0, st, lim);
       m0 += Mc;
     }
-    launch_ce_loss(h->nll, Mt, h->loss, h->flags, st);
+    launch_ce_loss(h->nll, Mt, h->loss, h->flags, st, RowLimit{h->ce_nvalid, 0});
     phase_mark(h, "end");
     (void)hipMemcpyAsync(h->h_loss, h->loss, 2 * sizeof(float), hipMemcpyDeviceToHost, st);
     (void)hipMemcpyAsync(h->h_flags, h->flags, sizeof(int), hipMemcpyDeviceToHost, st);
@@ -583,11 +595,11 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   }
   hipStream_t sd = h->use_side ? h->side : st;
   const int ldHoT = Mt + Bp;
-  const char* HoT = h->HoBufT + (size_t)Bp * esz;  // columns of H_o^{<0..T-1>}
   auto transpose_states = [&](LD& d, int Lsteps) {
     launch_transpose(p, d.Hst, d.ph, d.HstT, (Lsteps + 1) * Bp, (Lsteps + 1) * Bp, d.Hh, sd);
   };
   stream_after(h, sd, st);
+  launch_transpose(p, h->Hoc, PH, h->HocT, Mt, Mt, H, sd);           // dense H_o rows, for dW_o
   launch_transpose(p, HoFeed, PH, h->HoBufT, ldHoT, Mt + Bp, H, sd);
   for (auto& d : h->enc) transpose_states(d, S);
   for (auto& d : h->dec) transpose_states(d, T);
@@ -600,8 +612,10 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   launch_transpose(p, h->Xt, E, h->XtT, Mt, Mt, E, sd);
   launch_transpose(p, h->Cs, PH, h->CsT, Mt, Mt, H, sd);
   {
-    // Full slabs of CE_SLAB_ROWS rows and one remainder, two slab buffer pairs.  Per slab the main stream
-    // takes forward (logits -> e, partials), lse / nll, e -> dz and dz^T, and dH_o = dz W_o (the
+    // Full slabs of CE_SLAB_ROWS rows and one remainder, two slab buffer pairs, over the dense rows of
+    // the valid target positions.  The host sizes the slabs for all T * Bp rows; every kernel gets the
+    // device's count and a slab that lies beyond it costs a few empty launches.  Per slab the main
+    // stream takes forward (logits -> e, partials), lse / nll, e -> dz and dz^T, and dH_o = dz W_o (the
     // decoder needs it); the second stream takes dW_o += dz^T H_o and dB_o.
     int nslab;
     const int rows = ce_slab_plan(Mt, &nslab);
@@ -610,22 +624,24 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     int sl = 0, n_dbo = 0;
     for (int m0 = 0; m0 < Mt; ++sl) {
       const int Mc = (sl == nslab - 1 || Mt - m0 < rows) ? Mt - m0 : rows;
+      const RowLimit lim{h->ce_nvalid, m0};
       char* dz = (sl & 1) ? h->dzs2 : h->dzs;
       char* dzT = (sl & 1) ? h->dzTs2 : h->dzTs;
       if (sl >= 2 && sd != st) (void)hipStreamWaitEvent(st, done[sl - 2], 0);
-      launch_ce_fwd(p, Ho + (size_t)m0 * PH * esz, PH, h->Pw(h->off_Wo), P + h->off_Bo, h->labels + m0, Mc, V, H, dzT,
+      launch_ce_fwd(p, h->Hoc + (size_t)m0 * PH * esz, PH, h->Pw(h->off_Wo), P + h->off_Bo, h->labels_c + m0, Mc, V, H, dzT,
                     h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, eps > 0.f ? h->psz + (size_t)m0 * np : nullptr,
-                    h->zy + m0, st);
+                    h->zy + m0, st, lim);
       launch_ce_rows(h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, h->psz + (size_t)m0 * np, h->zy + m0,
-                     h->mask_t + m0, Mc, np, eps, V, h->lse + m0, h->nll + m0, st);
-      launch_ce_scale(p, dzT, V, Mc, h->pmax + (size_t)m0 * np, h->lse + m0, h->labels + m0, h->rowscale + m0, eps, dz,
-                      h->dbo_parts + (size_t)n_dbo * V, st);
+                     nullptr, Mc, np, eps, V, h->lse + m0, h->nll + m0, st, lim);
+      launch_ce_scale(p, dzT, V, Mc, h->pmax + (size_t)m0 * np, h->lse + m0, h->labels_c + m0, h->rowscale + m0, eps, dz,
+                      h->dbo_parts + (size_t)n_dbo * V, st, lim);
       n_dbo += (Mc + 63) / 64;
       stream_after(h, sd, st);
       launch_gemm_nt(p, dz, V, h->WoT, V, Mc, H, V, h->dHoCE + (size_t)m0 * H, nullptr, H, nullptr, 0, st, h->gsplit,
-                     h->gsplit_floats);                                   // dH_o[slab] = dz W_o
-      launch_gemm_nt(p, dzT, CE_SLAB_ROWS, HoT + (size_t)m0 * esz, ldHoT, V, H, Mc, G + h->off_Wo, nullptr, H, nullptr, sl > 0,
-                     sd);                                                 // dW_o (+)= dz^T H_o[slab]
+                     h->gsplit_floats, lim, 1);                           // dH_o[slab] = dz W_o
+      // dW_o (+)= dz^T H_o[slab]; the first slab always holds a row, so W_o's gradient is always written
+      launch_gemm_nt(p, dzT, CE_SLAB_ROWS, h->HocT + (size_t)m0 * esz, Mt, V, H, Mc, G + h->off_Wo, nullptr, H, nullptr, sl > 0,
+                     sd, nullptr, 0, lim, 2);
       if (sd != st) {
         done[sl] = h->ev[h->ev_next++ % h->ev.size()];
         (void)hipEventRecord(done[sl], sd);
@@ -633,7 +649,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       m0 += Mc;
     }
     launch_sum_parts(h->dbo_parts, n_dbo, (size_t)V, G + h->off_Bo, st);
-    launch_ce_loss(h->nll, Mt, h->loss, h->flags, st);
+    launch_ce_loss(h->nll, Mt, h->loss, h->flags, st, RowLimit{h->ce_nvalid, 0});
   }
 
   phase_mark(h, "decoder backward loop");
@@ -645,7 +661,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     char* dpre = h->dPre + j * BP * esz;
     const bool last = j == T - 1;
     // dH_o = cross-entropy part + what step j+1's bottom layer sent back through the input feed
-    launch_tanh_bwd(p, h->dHoCE + j * BH, Planes{h->dec[0].bwdp, 2 * H, last ? 0 : kbd, pstr}, h->HoBuf + (j + 1) * BP * esz,
+    launch_tanh_bwd(p, h->dHoCE, h->ce_pos + (size_t)j * Bp, Planes{h->dec[0].bwdp, 2 * H, last ? 0 : kbd, pstr}, h->HoBuf + (j + 1) * BP * esz,
                     PH, dpre, PH, Bp, H, drop_spec(h, DROP_SITE_HO, j), st);
     const int kbw = step_kblocks(p, 2 * H, H, Bp, h->kb_wc);
     {   // [dC_s ; dH_t] = dpre W_c, as planes
@@ -1271,8 +1287,19 @@ int cmt_debug_fetch(cmt_handle* h, const char* name, float* host_dst, size_t byt
   else if (s == "h_o_drop") {
     src = (h->drop_p > 0.f ? h->HoDrop : h->HoBuf) + BP * h->esz; rows = T * Bp; cols = H; pitch = h->PH; isT = true;
   }
-  else if (s == "lse") { src = h->lse; rows = 1; cols = pitch = T * Bp; }
-  else if (s == "nll") { src = h->nll; rows = 1; cols = pitch = T * Bp; }
+  else if (s == "lse" || s == "nll") {
+    // kept per valid target position, densely numbered on the device: spread out to [T, Bp], zero elsewhere
+    const size_t n = T * Bp;
+    if (bytes != n * 4) return fail(h, CMT_EINVAL, "size mismatch for the requested intermediate");
+    hipError_t e = hipStreamSynchronize(h->st);
+    std::vector<int32_t> pos(n);
+    std::vector<float> dense(n);
+    if (e == hipSuccess) e = hipMemcpy(pos.data(), h->ce_pos, n * 4, hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(dense.data(), s == "lse" ? h->lse : h->nll, n * 4, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(h, e, "cmt_debug_fetch");
+    for (size_t i = 0; i < n; ++i) host_dst[i] = pos[i] >= 0 ? dense[pos[i]] : 0.f;
+    return CMT_OK;
+  }
   else return fail(h, CMT_EINVAL, "unknown intermediate name");
   const size_t n = rows * cols;
   if (bytes != n * 4) return fail(h, CMT_EINVAL, "size mismatch for the requested intermediate");

@@ -29,10 +29,12 @@ __global__ __launch_bounds__(CeG::NT) void ce_fwd_kernel(const T* __restrict__ H
                                                          const float* __restrict__ Bo, const int32_t* __restrict__ labels,
                                                          int M, int V, int H, T* __restrict__ ET, int ldet,
                                                          float* __restrict__ pmax, float* __restrict__ psum,
-                                                         float* __restrict__ psz, float* __restrict__ zy, int np, int ntn) {
+                                                         float* __restrict__ psz, float* __restrict__ zy, int np, RowLimit lim) {
   __shared__ __align__(16) char smem[CeG::SMEM_BYTES];
+  if (lim.n) M = min(M, max(*lim.n - lim.base, 0));       // rows that exist (uniform over the grid)
+  if (M <= 0) return;
   int v0, r0;                                             // tile: vocabulary rows v0.., target positions r0..
-  if (!gemm_tile_of_block((V + CeG::BM - 1) / CeG::BM, ntn, CeG::BM, CeG::BN, v0, r0)) return;
+  if (!gemm_tile_of_block((V + CeG::BM - 1) / CeG::BM, (M + CeG::BN - 1) / CeG::BN, CeG::BM, CeG::BN, v0, r0)) return;
   v16f acc[2][2];
   gemm_mainloop<T, 4, 4, 2, 2, 128>(Wo, H, Ho, ldho, V, M, H, v0, r0, acc, smem);
   float* sbo = reinterpret_cast<float*>(smem);            // the main loop ends with a barrier: LDS is free
@@ -80,16 +82,16 @@ __global__ __launch_bounds__(CeG::NT) void ce_fwd_kernel(const T* __restrict__ H
 }
 
 void launch_ce_fwd(int prec, const void* Ho, int ldho, const void* Wo, const float* Bo, const int32_t* labels,
-                   int M, int V, int H, void* ET, float* pmax, float* psum, float* psz, float* zy, hipStream_t st) {
+                   int M, int V, int H, void* ET, float* pmax, float* psum, float* psz, float* zy, hipStream_t st, RowLimit lim) {
   const int ntv = (V + CeG::BM - 1) / CeG::BM, ntr = (M + CeG::BN - 1) / CeG::BN;
   const int grid = ((ntv * ntr + 7) / 8) * 8;
   const int np = ce_num_partials(V);
   if (prec)
     hipLaunchKernelGGL(ce_fwd_kernel<bf16_t>, dim3(grid), dim3(CeG::NT), 0, st, (const bf16_t*)Ho, ldho, (const bf16_t*)Wo, Bo,
-                       labels, M, V, H, (bf16_t*)ET, CE_SLAB_ROWS, pmax, psum, psz, zy, np, ntr);
+                       labels, M, V, H, (bf16_t*)ET, CE_SLAB_ROWS, pmax, psum, psz, zy, np, lim);
   else
     hipLaunchKernelGGL(ce_fwd_kernel<float>, dim3(grid), dim3(CeG::NT), 0, st, (const float*)Ho, ldho, (const float*)Wo, Bo,
-                       labels, M, V, H, (float*)ET, CE_SLAB_ROWS, pmax, psum, psz, zy, np, ntr);
+                       labels, M, V, H, (float*)ET, CE_SLAB_ROWS, pmax, psum, psz, zy, np, lim);
 }
 
 // one wavefront per row: combine the partials.  Row loss against the smoothed target distribution
@@ -97,8 +99,9 @@ void launch_ce_fwd(int prec, const void* Ho, int ldho, const void* Wo, const flo
 __global__ __launch_bounds__(256) void ce_row_kernel(const float* __restrict__ pmax, const float* __restrict__ psum,
                                                      const float* __restrict__ psz, const float* __restrict__ zy,
                                                      const float* __restrict__ mask, int M, int np, float eps, int V,
-                                                     float* __restrict__ lse, float* __restrict__ nll) {
+                                                     float* __restrict__ lse, float* __restrict__ nll, RowLimit lim) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (lim.n) M = min(M, max(*lim.n - lim.base, 0));
   if (row >= M) return;
   float mx = -INFINITY;
   for (int p = lane; p < np; p += 64) mx = fmaxf(mx, pmax[(size_t)row * np + p]);
@@ -119,35 +122,73 @@ __global__ __launch_bounds__(256) void ce_row_kernel(const float* __restrict__ p
     lse[row] = l;
     float r = l - zy[row];
     if (eps > 0.f) r = (1.f - eps) * r + eps * (l - sz / (float)V);
-    nll[row] = mask[row] > 0.f ? r : 0.f;
+    nll[row] = !mask || mask[row] > 0.f ? r : 0.f;
   }
 }
 
-// single block: n_tok and the per-row scale mask / n_tok.  Needs only the lengths, so it runs before
-// the decoder and every slab's backward can follow its forward directly.
-__global__ __launch_bounds__(1024) void ce_rowscale_kernel(const float* __restrict__ mask, int M, float* __restrict__ rowscale,
-                                                           float* __restrict__ loss) {
-  __shared__ float s_cnt[1024];
+// single block: the valid target positions (mask > 0), taken in time-major order, get consecutive
+// indices, so that the output layer works on a dense row set: pos[r] = index of row r or -1,
+// row[c] = the row behind index c, labels_c / rowscale_c = label and 1 / n_tok per index,
+// *n_valid = loss[1] = n_tok.  Needs only the lengths, so it runs before the encoder.
+__global__ __launch_bounds__(1024) void ce_compact_kernel(const float* __restrict__ mask, const int32_t* __restrict__ labels, int M,
+                                                          int32_t* __restrict__ pos, int32_t* __restrict__ row,
+                                                          int32_t* __restrict__ labels_c, float* __restrict__ rowscale_c,
+                                                          int32_t* __restrict__ n_valid, float* __restrict__ loss) {
+  __shared__ int s_scan[2][1024];
   const int t = threadIdx.x;
-  float c = 0.f;
-  for (int r = t; r < M; r += 1024) c += mask[r];
-  s_cnt[t] = c;
+  const int per = (M + 1023) / 1024;
+  const int r0 = min(M, t * per), r1 = min(M, r0 + per);
+  int c = 0;
+  for (int r = r0; r < r1; ++r) c += mask[r] > 0.f;
+  s_scan[0][t] = c;
   __syncthreads();
-  for (int o = 512; o > 0; o >>= 1) {
-    if (t < o) s_cnt[t] += s_cnt[t + o];
+  int cur = 0;
+  for (int o = 1; o < 1024; o <<= 1) {                    // inclusive scan of the per-thread counts
+    s_scan[cur ^ 1][t] = s_scan[cur][t] + (t >= o ? s_scan[cur][t - o] : 0);
+    cur ^= 1;
     __syncthreads();
   }
-  const float ntok = s_cnt[0];
-  const float inv = ntok > 0.f ? 1.0f / ntok : 0.f;
-  for (int r = t; r < M; r += 1024) rowscale[r] = mask[r] * inv;
-  if (t == 0) loss[1] = ntok;
+  const int total = s_scan[cur][1023];
+  const float inv = total > 0 ? 1.0f / (float)total : 0.f;
+  int idx = s_scan[cur][t] - c;
+  for (int r = r0; r < r1; ++r) {
+    if (mask[r] > 0.f) {
+      pos[r] = idx; row[idx] = r; labels_c[idx] = labels[r]; rowscale_c[idx] = inv;
+      ++idx;
+    } else {
+      pos[r] = -1;
+    }
+  }
+  if (t == 0) { *n_valid = total; loss[1] = (float)total; }
+}
+
+// dst[c, :] = src[row[c], :] for c < *n_valid (cols * sizeof(T) and the pitches are multiples of 16 bytes)
+template <typename T>
+__global__ __launch_bounds__(128) void ce_gather_rows_kernel(const T* __restrict__ src, int lds, const int32_t* __restrict__ row,
+                                                             const int32_t* __restrict__ n_valid, T* __restrict__ dst, int ldd,
+                                                             int cols) {
+  const int c = blockIdx.x;
+  if (c >= *n_valid) return;
+  constexpr int VE = 16 / sizeof(T);
+  const T* s = src + (size_t)row[c] * lds;
+  T* d = dst + (size_t)c * ldd;
+  for (int k = threadIdx.x * VE; k < cols; k += 128 * VE) *reinterpret_cast<uint4*>(d + k) = *reinterpret_cast<const uint4*>(s + k);
+}
+void launch_ce_gather_rows(int prec, const void* src, int lds, const int32_t* row, const int32_t* n_valid, int max_rows, void* dst,
+                           int ldd, int cols, hipStream_t st) {
+  if (max_rows <= 0) return;
+  if (prec) hipLaunchKernelGGL(ce_gather_rows_kernel<bf16_t>, dim3(max_rows), dim3(128), 0, st, (const bf16_t*)src, lds, row, n_valid,
+                               (bf16_t*)dst, ldd, cols);
+  else hipLaunchKernelGGL(ce_gather_rows_kernel<float>, dim3(max_rows), dim3(128), 0, st, (const float*)src, lds, row, n_valid,
+                          (float*)dst, ldd, cols);
 }
 
 // single block: loss = sum nll / n_tok, summed in a fixed order
 __global__ __launch_bounds__(1024) void ce_loss_kernel(const float* __restrict__ nll, int M, float* __restrict__ loss,
-                                                       int* __restrict__ flags) {
+                                                       int* __restrict__ flags, RowLimit lim) {
   __shared__ float s_sum[1024];
   const int t = threadIdx.x;
+  if (lim.n) M = min(M, max(*lim.n - lim.base, 0));
   float a = 0.f;
   for (int r = t; r < M; r += 1024) a += nll[r];
   s_sum[t] = a;
@@ -164,15 +205,16 @@ __global__ __launch_bounds__(1024) void ce_loss_kernel(const float* __restrict__
   }
 }
 
-void launch_ce_rowscale(const float* mask, int M, float* rowscale, float* loss, hipStream_t st) {
-  hipLaunchKernelGGL(ce_rowscale_kernel, dim3(1), dim3(1024), 0, st, mask, M, rowscale, loss);
+void launch_ce_compact(const float* mask, const int32_t* labels, int M, int32_t* pos, int32_t* row, int32_t* labels_c,
+                       float* rowscale_c, int32_t* n_valid, float* loss, hipStream_t st) {
+  hipLaunchKernelGGL(ce_compact_kernel, dim3(1), dim3(1024), 0, st, mask, labels, M, pos, row, labels_c, rowscale_c, n_valid, loss);
 }
 void launch_ce_rows(const float* pmax, const float* psum, const float* psz, const float* zy, const float* mask, int M, int np,
-                    float eps, int V, float* lse, float* nll, hipStream_t st) {
-  hipLaunchKernelGGL(ce_row_kernel, dim3((M + 3) / 4), dim3(256), 0, st, pmax, psum, psz, zy, mask, M, np, eps, V, lse, nll);
+                    float eps, int V, float* lse, float* nll, hipStream_t st, RowLimit lim) {
+  hipLaunchKernelGGL(ce_row_kernel, dim3((M + 3) / 4), dim3(256), 0, st, pmax, psum, psz, zy, mask, M, np, eps, V, lse, nll, lim);
 }
-void launch_ce_loss(const float* nll, int M, float* loss, int* flags, hipStream_t st) {
-  hipLaunchKernelGGL(ce_loss_kernel, dim3(1), dim3(1024), 0, st, nll, M, loss, flags);
+void launch_ce_loss(const float* nll, int M, float* loss, int* flags, hipStream_t st, RowLimit lim) {
+  hipLaunchKernelGGL(ce_loss_kernel, dim3(1), dim3(1024), 0, st, nll, M, loss, flags, lim);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -186,7 +228,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void ce_scale_kernel(T* __restrict__ ET, int ldet, int V, int Mc, const float* __restrict__ pmax,
                                                        int np, const float* __restrict__ lse, const int32_t* __restrict__ labels,
                                                        const float* __restrict__ rowscale, float eps, T* __restrict__ dz,
-                                                       float* __restrict__ dbo_part) {
+                                                       float* __restrict__ dbo_part, RowLimit lim) {
   constexpr int VE = 16 / sizeof(T);                      // elements per 16-byte vector
   constexpr int NV = 16 / VE;                             // vectors per thread
   __shared__ __align__(16) T tile[64][64 + VE];           // [position][vocabulary entry]
@@ -194,6 +236,12 @@ __global__ __launch_bounds__(256) void ce_scale_kernel(T* __restrict__ ET, int l
   __shared__ int sy[64];
   const int v0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
   const int t = threadIdx.x;
+  if (lim.n) Mc = min(Mc, max(*lim.n - lim.base, 0));
+  if (r0 >= Mc) {                                         // a block of rows that does not exist: its share of dB_o is zero
+    const int v = v0 + (t >> 2);
+    if ((t & 3) == 0 && v < V) dbo_part[(size_t)blockIdx.y * V + v] = 0.f;
+    return;
+  }
   if (t < 64) {
     const int r = r0 + t;
     float f = 0.f, rs = 0.f;
@@ -243,15 +291,15 @@ __global__ __launch_bounds__(256) void ce_scale_kernel(T* __restrict__ ET, int l
 }
 
 void launch_ce_scale(int prec, void* ET, int V, int Mc, const float* pmax, const float* lse, const int32_t* labels,
-                     const float* rowscale, float eps, void* dz, float* dbo_part, hipStream_t st) {
+                     const float* rowscale, float eps, void* dz, float* dbo_part, hipStream_t st, RowLimit lim) {
   dim3 grid((V + 63) / 64, (Mc + 63) / 64);
   const int np = ce_num_partials(V);
   if (prec)
     hipLaunchKernelGGL(ce_scale_kernel<bf16_t>, grid, dim3(256), 0, st, (bf16_t*)ET, CE_SLAB_ROWS, V, Mc, pmax, np, lse, labels,
-                       rowscale, eps, (bf16_t*)dz, dbo_part);
+                       rowscale, eps, (bf16_t*)dz, dbo_part, lim);
   else
     hipLaunchKernelGGL(ce_scale_kernel<float>, grid, dim3(256), 0, st, (float*)ET, CE_SLAB_ROWS, V, Mc, pmax, np, lse, labels,
-                       rowscale, eps, (float*)dz, dbo_part);
+                       rowscale, eps, (float*)dz, dbo_part, lim);
 }
 
 }  // namespace cmt

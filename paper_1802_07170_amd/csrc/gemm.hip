@@ -26,13 +26,20 @@ template <typename T, int WM, int WN, int TA, int TB, int KB>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_kernel(const T* __restrict__ A, int lda, const T* __restrict__ B, int ldb,
                                                                int M, int N, int K, float* __restrict__ Cf, T* __restrict__ Ct,
                                                                int ldc, const float* __restrict__ bias, int accumulate, int ntn,
-                                                               int kchunk, size_t plane_stride) {
+                                                               int kchunk, size_t plane_stride, RowLimit lim, int lim_kind) {
   using G = GemmTile<WM, WN, TA, TB, KB>;
   __shared__ __align__(16) char smem[G::SMEM_BYTES];
+  if (lim.n) {                                     // a bound that only the device knows (uniform over the grid)
+    const int e = max(*lim.n - lim.base, 0);
+    if (lim_kind == 1) M = min(M, e);
+    else K = min(K, (e + 63) / 64 * 64);
+    if (M <= 0 || K <= 0) return;
+  }
   int m0, n0;
   if (!gemm_tile_of_block((M + G::BM - 1) / G::BM, ntn, G::BM, G::BN, m0, n0)) return;
   const int k0 = blockIdx.y * kchunk;
   const int klen = min(kchunk, K - k0);
+  if (klen <= 0 && gridDim.y == 1) return;
   v16f acc[TA][TB];
   gemm_mainloop<T, WM, WN, TA, TB, KB>(A + k0, lda, B + k0, ldb, M, N, klen, m0, n0, acc, smem);
   if (gridDim.y > 1) Cf += blockIdx.y * plane_stride;
@@ -62,7 +69,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_kernel(const T* __restri
 // out = sum of planes (+ bias per column) (+ previous out)
 __global__ __launch_bounds__(256) void gemm_planes_sum_kernel(const float* __restrict__ planes, int np, size_t stride,
                                                               float* __restrict__ out, int M, int N, int ldc,
-                                                              const float* __restrict__ bias, int accumulate) {
+                                                              const float* __restrict__ bias, int accumulate, RowLimit lim) {
+  if (lim.n) M = min(M, max(*lim.n - lim.base, 0));
   const size_t n = (size_t)M * N;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
     const size_t r = i / N, c = i - r * N;
@@ -75,21 +83,21 @@ __global__ __launch_bounds__(256) void gemm_planes_sum_kernel(const float* __res
 
 template <typename T, int WM, int WN, int TA, int TB>
 static void gemm_go(dim3 grid, hipStream_t st, const void* A, int lda, const void* B, int ldb, int M, int N, int K, float* out,
-                    void* Ct, int ldc, const float* bias, int acc, int ntn, int kchunk, size_t pstride) {
+                    void* Ct, int ldc, const float* bias, int acc, int ntn, int kchunk, size_t pstride, RowLimit lim, int lim_kind) {
   hipLaunchKernelGGL((gemm_nt_kernel<T, WM, WN, TA, TB, 128>), grid, dim3(64 * WM * WN), 0, st, (const T*)A, lda, (const T*)B, ldb,
-                     M, N, K, out, (T*)Ct, ldc, bias, acc, ntn, kchunk, pstride);
+                     M, N, K, out, (T*)Ct, ldc, bias, acc, ntn, kchunk, pstride, lim, lim_kind);
 }
 
 void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, int M, int N, int K,
                     float* Cf, void* Ct, int ldc, const float* bias, int accumulate, hipStream_t st,
-                    float* split_scratch, size_t split_scratch_floats) {
+                    float* split_scratch, size_t split_scratch_floats, RowLimit lim, int lim_kind) {
   if (M <= 0 || N <= 0) return;
   // enough 256 x 256 tiles to fill the chip: the big tile (half the L2 traffic per flop)
   const int ntm_b = (M + GemmBig::BM - 1) / GemmBig::BM, ntn_b = (N + GemmBig::BN - 1) / GemmBig::BN;
   if (ntm_b * ntn_b >= GEMM_BIG_MIN_TILES) {
     const int grid = ((ntm_b * ntn_b + 7) / 8) * 8;
-    if (prec) gemm_go<bf16_t, 4, 4, 2, 2>(dim3(grid, 1), st, A, lda, B, ldb, M, N, K, Cf, Ct, ldc, bias, accumulate, ntn_b, K, 0);
-    else gemm_go<float, 4, 4, 2, 2>(dim3(grid, 1), st, A, lda, B, ldb, M, N, K, Cf, Ct, ldc, bias, accumulate, ntn_b, K, 0);
+    if (prec) gemm_go<bf16_t, 4, 4, 2, 2>(dim3(grid, 1), st, A, lda, B, ldb, M, N, K, Cf, Ct, ldc, bias, accumulate, ntn_b, K, 0, lim, lim_kind);
+    else gemm_go<float, 4, 4, 2, 2>(dim3(grid, 1), st, A, lda, B, ldb, M, N, K, Cf, Ct, ldc, bias, accumulate, ntn_b, K, 0, lim, lim_kind);
     return;
   }
   using G = GemmSmall;
@@ -113,13 +121,13 @@ void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, in
   const int oldc = nks > 1 ? N : ldc;
   const float* obias = nks > 1 ? nullptr : bias;
   const int oacc = nks > 1 ? 0 : accumulate;
-  if (prec) gemm_go<bf16_t, 2, 2, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, out, Ct, oldc, obias, oacc, ntn, kchunk, pstride);
-  else gemm_go<float, 2, 2, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, out, Ct, oldc, obias, oacc, ntn, kchunk, pstride);
+  if (prec) gemm_go<bf16_t, 2, 2, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, out, Ct, oldc, obias, oacc, ntn, kchunk, pstride, lim, lim_kind);
+  else gemm_go<float, 2, 2, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, out, Ct, oldc, obias, oacc, ntn, kchunk, pstride, lim, lim_kind);
   if (nks > 1) {
     size_t g = (pstride + 255) / 256;
     if (g > 4096) g = 4096;
     hipLaunchKernelGGL(gemm_planes_sum_kernel, dim3((unsigned)g), dim3(256), 0, st, split_scratch, nks, pstride, Cf, M, N, ldc,
-                       bias, accumulate);
+                       bias, accumulate, lim_kind == 1 ? lim : RowLimit{});
   }
 }
 

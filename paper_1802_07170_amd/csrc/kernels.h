@@ -13,9 +13,16 @@ namespace cmt {
 // K, lda, ldb multiples of 8.
 // When split_scratch is given and the output has few tiles but K is long, k is split over workgroups
 // into fp32 planes in the scratch (at most 8 * M * N floats) that a second kernel sums.
+// A row count known only on the device (the number of valid target positions): the count a kernel
+// works on is clamp(*n - base, 0, the count the host passed).  n = null: the host's count.
+struct RowLimit { const int32_t* n = nullptr; int base = 0; };
+// limit_kind 1: `limit` bounds M (tiles beyond it exit; rows beyond it are not stored);
+// limit_kind 2: `limit` bounds K, rounded up to a multiple of 64 (the operands are zero there); a
+// workgroup whose contraction is empty exits without touching C.
 void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, int M, int N, int K,
                     float* Cf, void* Ct, int ldc, const float* bias, int accumulate, hipStream_t st,
-                    float* split_scratch = nullptr, size_t split_scratch_floats = 0);
+                    float* split_scratch = nullptr, size_t split_scratch_floats = 0, RowLimit limit = RowLimit{},
+                    int limit_kind = 0);
 // out[C,R] = in[R,C]^T for T matrices (ldin, ldout in elements).
 void launch_transpose(int prec, const void* in, int ldin, void* out, int ldout, int R, int C, hipStream_t st);
 
@@ -28,22 +35,32 @@ void launch_transpose(int prec, const void* in, int ldin, void* out, int ldout, 
 constexpr int CE_SLAB_ROWS = 1024;
 int ce_num_partials(int V);
 size_t ce_slab_elems(int V);                                 // elements of a slab buffer (E / dz, and dzT)
+// Every launcher below takes a RowLimit: the slab's row count as the device knows it (see
+// launch_ce_compact); rows beyond it are neither computed nor stored.
 void launch_ce_fwd(int prec, const void* Ho, int ldho, const void* Wo, const float* Bo, const int32_t* labels,
-                   int M, int V, int H, void* ET, float* pmax, float* psum, float* psz, float* zy, hipStream_t st);
-// rowscale[M] = mask / n_tok and loss[1] = n_tok (needs only the masks; M = all rows of the batch).
-void launch_ce_rowscale(const float* mask, int M, float* rowscale, float* loss, hipStream_t st);
-// lse[M] and the masked row loss nll[M] = (1 - eps) (lse - zy) + eps (lse - mean_v z_v) from the partials
-// (label smoothing eps of the hyperparameter table; eps = 0: plain negative log-likelihood).
+                   int M, int V, int H, void* ET, float* pmax, float* psum, float* psz, float* zy, hipStream_t st,
+                   RowLimit lim = RowLimit{});
+// The valid target positions of the batch (mask > 0, M = all rows, time-major) numbered consecutively:
+// pos[M] = index or -1, row[index] = row, labels_c / rowscale_c [index] = label and 1 / n_tok,
+// *n_valid = loss[1] = n_tok.  The output layer then runs on the dense rows [0, n_valid).
+void launch_ce_compact(const float* mask, const int32_t* labels, int M, int32_t* pos, int32_t* row, int32_t* labels_c,
+                       float* rowscale_c, int32_t* n_valid, float* loss, hipStream_t st);
+// dst[c, 0:cols] = src[row[c], 0:cols] for c < *n_valid (T rows; grid sized for max_rows)
+void launch_ce_gather_rows(int prec, const void* src, int lds, const int32_t* row, const int32_t* n_valid, int max_rows, void* dst,
+                           int ldd, int cols, hipStream_t st);
+// lse[M] and the row loss nll[M] = (1 - eps) (lse - zy) + eps (lse - mean_v z_v) from the partials
+// (label smoothing eps of the hyperparameter table; eps = 0: plain negative log-likelihood);
+// mask (may be null = all rows count) zeroes the loss of padded rows.
 void launch_ce_rows(const float* pmax, const float* psum, const float* psz, const float* zy, const float* mask, int M, int np,
-                    float eps, int V, float* lse, float* nll, hipStream_t st);
+                    float eps, int V, float* lse, float* nll, hipStream_t st, RowLimit lim = RowLimit{});
 // loss[0] = sum nll / loss[1]; flags |= 4 if it is not finite.  One block, deterministic order.
-void launch_ce_loss(const float* nll, int M, float* loss, int* flags, hipStream_t st);
+void launch_ce_loss(const float* nll, int M, float* loss, int* flags, hipStream_t st, RowLimit lim = RowLimit{});
 // Backward: ET -> dzT = (ET * exp(pmax - lse) - (1 - eps) onehot - eps / V) * rowscale in place
 // ([V, CE_SLAB_ROWS] T; columns >= Mc up to the next multiple of 64 are zero-filled) and dz [Mc, V] T.  The caller
 // then takes dH_o[rows] = dz W_o and dW_o += dz^T H_o[rows] with launch_gemm_nt.  dbo_part
 // [ceil(Mc / 64), V] fp32: column sums of dz over each block of 64 rows (dB_o = their sum over all slabs).
 void launch_ce_scale(int prec, void* ET, int V, int Mc, const float* pmax, const float* lse, const int32_t* labels,
-                     const float* rowscale, float eps, void* dz, float* dbo_part, hipStream_t st);
+                     const float* rowscale, float eps, void* dz, float* dbo_part, hipStream_t st, RowLimit lim = RowLimit{});
 
 // ---- step.hip ----------------------------------------------------------------------------------
 // A value delivered as `np` partial planes: v(b, c) = sum_k p[k * stride + b * ld + c]  (np = 0: zero).
@@ -139,8 +156,10 @@ void launch_att_deferred(int prec, const float* a, const float* ds, const float*
                          int S, int T, int Bp, int H, float* dHs, void* dK, hipStream_t st);
 // dpre = (dHo_ce + feed) * drop * (1 - Ho^2) -> T*   (Ho: before dropout; drop: the factors H_o's
 // consumers saw)
-void launch_tanh_bwd(int prec, const float* dHo_ce, const Planes& feed, const void* Ho, int ldho, void* dpre, int ldp,
-                     int Bp, int H, const DropSpec& drop, hipStream_t st);
+// dHo_ce: rows [Bp, H] of this step, or — with pos [Bp] given — a dense matrix [n, H] in which row pos[b]
+// belongs to sentence b (pos[b] < 0: no row, zero).
+void launch_tanh_bwd(int prec, const float* dHo_ce, const int32_t* pos, const Planes& feed, const void* Ho, int ldho, void* dpre,
+                     int ldp, int Bp, int H, const DropSpec& drop, hipStream_t st);
 
 // ---- misc.hip ----------------------------------------------------------------------------------
 // Embedding gather + masks + input validation (flags |= 1 bad id, |= 2 bad length).

@@ -789,14 +789,15 @@ template __global__ void tanh_planes_kernel<float>(Planes, float*, int, float*, 
 
 // dpre = (dHo_ce + feed) * (1 - Ho^2) -> T; feed arrives as planes (np = 0: none); 4 columns per thread
 template <typename T>
-__global__ __launch_bounds__(64) void tanh_bwd_kernel(const float* __restrict__ dce, Planes feed, const T* __restrict__ Ho,
-                                                      int ldho, T* __restrict__ dpre, int ldp, int Bp, int H, DropSpec drop) {
+__global__ __launch_bounds__(64) void tanh_bwd_kernel(const float* __restrict__ dce, const int32_t* __restrict__ pos, Planes feed,
+                                                      const T* __restrict__ Ho, int ldho, T* __restrict__ dpre, int ldp, int Bp,
+                                                      int H, DropSpec drop) {
   const int i4 = blockIdx.x * 64 + threadIdx.x;        // single-wavefront workgroups: spread over all CUs
   const int hq = H >> 2;
   if (i4 >= Bp * hq) return;
   const int b = i4 / hq, h = (i4 - b * hq) * 4;
-  const size_t i = (size_t)b * H + h;
-  const float4 d = *reinterpret_cast<const float4*>(dce + i);
+  const int c = pos ? pos[b] : b;                      // row of sentence b in dce
+  const float4 d = c >= 0 ? *reinterpret_cast<const float4*>(dce + (size_t)c * H + h) : make_float4(0.f, 0.f, 0.f, 0.f);
   const float4 f = planes_get4(feed, b, h);
   float o[4];
 #pragma unroll
@@ -807,12 +808,12 @@ __global__ __launch_bounds__(64) void tanh_bwd_kernel(const float* __restrict__ 
   store4<T>(dpre + (size_t)b * ldp + h, o);
 }
 
-void launch_tanh_bwd(int prec, const float* dHo_ce, const Planes& feed, const void* Ho, int ldho, void* dpre, int ldp, int Bp, int H,
-                     const DropSpec& drop, hipStream_t st) {
+void launch_tanh_bwd(int prec, const float* dHo_ce, const int32_t* pos, const Planes& feed, const void* Ho, int ldho, void* dpre,
+                     int ldp, int Bp, int H, const DropSpec& drop, hipStream_t st) {
   const int n = Bp * (H >> 2);
-  if (prec) hipLaunchKernelGGL(tanh_bwd_kernel<bf16_t>, dim3((n + 63) / 64), dim3(64), 0, st, dHo_ce, feed,
+  if (prec) hipLaunchKernelGGL(tanh_bwd_kernel<bf16_t>, dim3((n + 63) / 64), dim3(64), 0, st, dHo_ce, pos, feed,
                                (const bf16_t*)Ho, ldho, (bf16_t*)dpre, ldp, Bp, H, drop);
-  else hipLaunchKernelGGL(tanh_bwd_kernel<float>, dim3((n + 63) / 64), dim3(64), 0, st, dHo_ce, feed,
+  else hipLaunchKernelGGL(tanh_bwd_kernel<float>, dim3((n + 63) / 64), dim3(64), 0, st, dHo_ce, pos, feed,
                           (const float*)Ho, ldho, (float*)dpre, ldp, Bp, H, drop);
 }
 

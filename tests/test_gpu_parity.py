@@ -162,6 +162,38 @@ def test_extreme_configurations(prec, B, S, T, H, E, L, Vs, Vt):
     tr.close()
 
 
+@pytest.mark.parametrize("prec", [0, 1])
+def test_batches_of_different_shape_in_turn_on_one_handle(prec):
+    """A large batch, then a small one with far fewer valid target positions, then the large one again,
+    all on the same handle: nothing one step leaves in the workspace (rows beyond the valid positions of
+    the dense output-layer buffers, planes, padded slots) may reach the next.  Each result is checked
+    against the oracle, and the repeated batch must reproduce its first result bit for bit."""
+    from paper_1802_07170_amd import binding
+    cfg = dict(src_vocab=104, tgt_vocab=328, emb=24, hidden=48, layers=2)
+    rng = np.random.default_rng(77)
+    params = I.make_params(cfg, seed=12, scale=0.3)
+    big = ragged_batch(rng, 70, 9, 17, 104, 328)               # 1360 rows: two slabs
+    small = ragged_batch(rng, 5, 4, 3, 104, 328)
+    tr = binding.Trainer(cfg, 70, 9, 17, precision=prec)
+    tr.set_params(I.flatten(params, cfg))
+    tol = 1e-4 if prec == 0 else 2e-2
+    first = None
+    for name, batch in [("big", big), ("small", small), ("big", big), ("small", small)]:
+        loss = tr.train_step(tr.upload_batch(*batch))
+        flat = tr.get_grads()
+        oloss, og = O.train_step(cfg, params, *batch)[:2]
+        assert abs(loss - oloss) <= tol * abs(oloss), (name, loss, oloss)
+        check_grads(I.unflatten(flat, cfg), og, prec, label=name + " ")
+        ev, ntok = tr.eval_loss(tr.upload_batch(*batch))
+        assert ev == loss and ntok == float(batch[3].sum())
+        if name == "big":
+            if first is None:
+                first = (loss, flat)
+            else:
+                assert loss == first[0] and np.array_equal(flat, first[1])
+    tr.close()
+
+
 def test_random_shapes_sweep():
     """32 seeded random combinations of batch (1..90, around the 16- and 64-sentence tile edges), lengths,
     hidden / embedding sizes, depth 1..4, vocabularies, precision, and regularisation on or off, each
