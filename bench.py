@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the timed kernel from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE),
 # scaled by what the same counters read for a plain 256 MiB copy (x2 and x1): the summary under
 # profiles/ gives the commands and the figures.  Known only for the workload it was measured on.
-MEASURED_TRAFFIC_BYTES = {"medium": 21703680}
+MEASURED_TRAFFIC_BYTES = {"medium": 21700608}
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # the paper's training-speed table, its own system, source tokens/s on its Quadro M4000 (context only)
 PAPER_SPEED_TABLE = {"paper_512x2": 4725, "paper_512x4": 3751, "paper_1024x2": 2571, "paper_1024x4": 1906}
