@@ -712,27 +712,29 @@ void launch_att_bwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds
   }
 }
 
-// After the decoder loop: for a block (sentence b, 256 hidden columns, 32 source positions):
+// After the decoder loop: for a block (sentence b, 256 hidden columns, ATT_DEF_IB source positions):
 //   dHs[i,b,h] = sum_j a[j,b,i] dCs[j,b,h]        dK[i,b,h] = sum_j ds[j,b,i] Ht[j,b,h]
+constexpr int ATT_DEF_IB = 16;                       // source positions per workgroup
+constexpr int ATT_DEF_JB = 256 / ATT_DEF_IB;         // decoder steps per pass: their loads are issued together
 template <typename T>
 __global__ __launch_bounds__(256) void att_deferred_kernel(const float* __restrict__ a, const float* __restrict__ ds,
                                                            const float* __restrict__ dCs, int lddc, const T* __restrict__ Ht,
                                                            int ldht, int S, int Tn, int Bp, int H, float* __restrict__ dHs,
                                                            T* __restrict__ dK) {
-  constexpr int JB = 8;                              // decoder steps per pass: their loads are issued together
-  __shared__ float sa[JB][32], sd[JB][32];
-  const int b = blockIdx.x, h = blockIdx.y * 256 + threadIdx.x, i0 = blockIdx.z * 32;
-  float accC[32], accK[32];
+  constexpr int IB = ATT_DEF_IB, JB = ATT_DEF_JB;
+  __shared__ float sa[JB][IB], sd[JB][IB];
+  const int b = blockIdx.x, h = blockIdx.y * 256 + threadIdx.x, i0 = blockIdx.z * IB;
+  float accC[IB], accK[IB];
 #pragma unroll
-  for (int i = 0; i < 32; ++i) { accC[i] = 0.f; accK[i] = 0.f; }
+  for (int i = 0; i < IB; ++i) { accC[i] = 0.f; accK[i] = 0.f; }
   for (int j0 = 0; j0 < Tn; j0 += JB) {
     __syncthreads();
     {
-      const int jj = threadIdx.x >> 5, i = i0 + (threadIdx.x & 31);        // 256 threads = JB x 32
+      const int jj = threadIdx.x / IB, il = threadIdx.x % IB, i = i0 + il;   // 256 threads = JB x IB
       const int j = j0 + jj;
       const bool ok = j < Tn && i < S;
-      sa[jj][threadIdx.x & 31] = ok ? a[((size_t)j * Bp + b) * S + i] : 0.f;
-      sd[jj][threadIdx.x & 31] = ok ? ds[((size_t)j * Bp + b) * S + i] : 0.f;
+      sa[jj][il] = ok ? a[((size_t)j * Bp + b) * S + i] : 0.f;
+      sd[jj][il] = ok ? ds[((size_t)j * Bp + b) * S + i] : 0.f;
     }
     float dc[JB], ht[JB];
 #pragma unroll
@@ -746,11 +748,11 @@ __global__ __launch_bounds__(256) void att_deferred_kernel(const float* __restri
 #pragma unroll
     for (int jj = 0; jj < JB; ++jj)                  // ascending j: the same summation order as one step at a time
 #pragma unroll
-      for (int i = 0; i < 32; ++i) { accC[i] += sa[jj][i] * dc[jj]; accK[i] += sd[jj][i] * ht[jj]; }
+      for (int i = 0; i < IB; ++i) { accC[i] += sa[jj][i] * dc[jj]; accK[i] += sd[jj][i] * ht[jj]; }
   }
   if (h >= H) return;
 #pragma unroll
-  for (int i = 0; i < 32; ++i) {
+  for (int i = 0; i < IB; ++i) {
     if (i0 + i < S) {
       const size_t o = ((size_t)(i0 + i) * Bp + b) * H + h;
       dHs[o] = accC[i];
@@ -761,7 +763,7 @@ __global__ __launch_bounds__(256) void att_deferred_kernel(const float* __restri
 
 void launch_att_deferred(int prec, const float* a, const float* ds, const float* dCs, int lddc, const void* Ht, int ldht,
                          int S, int T, int Bp, int H, float* dHs, void* dK, hipStream_t st) {
-  dim3 grid(Bp, (H + 255) / 256, (S + 31) / 32);
+  dim3 grid(Bp, (H + 255) / 256, (S + ATT_DEF_IB - 1) / ATT_DEF_IB);
   if (prec) hipLaunchKernelGGL(att_deferred_kernel<bf16_t>, grid, dim3(256), 0, st, a, ds, dCs, lddc, (const bf16_t*)Ht, ldht, S, T,
                                Bp, H, dHs, (bf16_t*)dK);
   else hipLaunchKernelGGL(att_deferred_kernel<float>, grid, dim3(256), 0, st, a, ds, dCs, lddc, (const float*)Ht, ldht, S, T, Bp, H,
