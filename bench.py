@@ -83,7 +83,8 @@ def main():
         sys.exit(2)
 
     import torch
-    from paper_1802_07170_amd import binding
+    from paper_1802_07170_amd import binding, build
+    build.ensure_built()
 
     c = I.CONFIGS[args.workload]
     cfg = I.model_cfg(c)

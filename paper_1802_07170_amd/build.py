@@ -38,5 +38,11 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """For tests, the smoke run and the benchmark: the library as it was built, or a fresh build when
+    there is none.  (The binding itself never builds: without the library it raises.)"""
+    return LIB if os.path.exists(LIB) else build()
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

@@ -12,6 +12,12 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu on the GPU box)")
 
 
+def pytest_sessionstart(session):
+    # the tests load the library as it was built; only a tree with no library at all gets built here
+    from paper_1802_07170_amd import build
+    build.ensure_built()
+
+
 def _have_gpu():
     try:
         import torch
