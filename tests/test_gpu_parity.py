@@ -615,6 +615,27 @@ def test_training_procedure_and_checkpoint_files(tmp_path):
     tr2.close()
 
 
+def test_kernel_replay_timer_covers_its_kernels_and_leaves_results_alone():
+    """cmt_time_kernel (the benchmark's roofline probe) replays single kernels with the operands of the
+    last step: every name it documents works and reports positive time and work, an unknown name is an
+    error, and a training step afterwards still gives the result it gave before."""
+    from paper_1802_07170_amd import binding
+    cfg = dict(src_vocab=104, tgt_vocab=328, emb=32, hidden=64, layers=2)
+    rng = np.random.default_rng(31)
+    tr = binding.Trainer(cfg, 20, 7, 9, precision=1)
+    tr.init_params(seed=9, scale=0.2)
+    dev = tr.upload_batch(*ragged_batch(rng, 20, 7, 9, 104, 328))
+    loss = tr.train_step(dev)
+    g = tr.get_grads()
+    for name in ["lstm_fwd_dec", "step2d_bwd_dec", "att_fwd", "gemm_gx", "gemm_dw", "ce_fwd"]:
+        us, work = tr.time_kernel(name, 5)
+        assert us > 0 and work > 0, name
+    with pytest.raises(binding.CmtError):
+        tr.time_kernel("no_such_kernel", 1)
+    assert tr.train_step(dev) == loss and np.array_equal(tr.get_grads(), g)
+    tr.close()
+
+
 def test_init_params_matches_the_counter_generator():
     from paper_1802_07170_amd import binding
     cfg = dict(src_vocab=104, tgt_vocab=136, emb=24, hidden=32, layers=2)
