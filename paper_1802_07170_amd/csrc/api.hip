@@ -140,6 +140,13 @@ namespace {
 
 int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
+// jobs for launch_fill_multi / launch_copy2d_multi (units of 32-bit words; esz = bytes per T element)
+void add_fill(std::vector<FillJob>& v, void* p, size_t elems, size_t esz) { v.push_back(FillJob{p, elems * esz / 4}); }
+void add_copy(std::vector<CopyJob>& v, const void* s, int lds, void* d, int ldd, int rows, int cols, size_t esz) {
+  const int f = (int)(4 / esz);                    // elements per word: row pitches and widths are multiples of it
+  v.push_back(CopyJob{s, lds / f, d, ldd / f, rows, cols / f});
+}
+
 bool config_ok(const cmt_config* c, std::string* why) {
   auto bad = [&](const char* m) { if (why) *why = m; return false; };
   if (!c) return bad("null config");
@@ -420,8 +427,13 @@ void enqueue_encoder(cmt_handle* h, int S, const char** Hs_out, int* ldHs_out) {
   for (LD* d : {&ef, &eb})
     launch_gemm_nt(p, h->Xs, E, d->W, E + Hd, Ms, 4 * Hd, E, d->Gx, nullptr, 4 * Hd, P + d->b_off, 0, st);
   const size_t BHd = (size_t)Bp * Hd, BPd = (size_t)Bp * ef.ph;
-  launch_fill_T(p, ef.Hst, BPd, st); launch_fill_f32(ef.Cst, BHd, 0.f, st);
-  launch_fill_T(p, eb.Hst + (size_t)S * BPd * esz, BPd, st); launch_fill_f32(eb.Cst + (size_t)S * BHd, BHd, 0.f, st);
+  {   // initial states of every encoder LSTM: zero, in one launch
+    std::vector<FillJob> z;
+    add_fill(z, ef.Hst, BPd, esz); add_fill(z, ef.Cst, BHd, 4);
+    add_fill(z, eb.Hst + (size_t)S * BPd * esz, BPd, esz); add_fill(z, eb.Cst + (size_t)S * BHd, BHd, 4);
+    for (int l = 1; l < L; ++l) { add_fill(z, h->enc[l + 1].Hst, BP, esz); add_fill(z, h->enc[l + 1].Cst, BH, 4); }
+    launch_fill_multi(z.data(), (int)z.size(), st);
+  }
   for (int k = 0; k < S; ++k) {
     const int tf = k, tb = S - 1 - k;
     LstmFwdDir d[2];
@@ -452,7 +464,6 @@ void enqueue_encoder(cmt_handle* h, int S, const char** Hs_out, int* ldHs_out) {
   if (L > 1) {
     LD& e1 = h->enc[2];
     launch_gemm_nt(p, h->Y0, H, e1.W, 2 * H, Ms, 4 * H, H, e1.Gx, nullptr, 4 * H, P + e1.b_off, 0, st);
-    for (int l = 1; l < L; ++l) { launch_fill_T(p, h->enc[l + 1].Hst, BP, st); launch_fill_f32(h->enc[l + 1].Cst, BH, 0.f, st); }
     for (int dg = 0; dg < S + L - 2; ++dg) {
       LstmFwdDir dirs[STEP_MAX_INST];
       int n = 0;
@@ -490,15 +501,17 @@ void enqueue_encoder(cmt_handle* h, int S, const char** Hs_out, int* ldHs_out) {
   // ---- decoder initial state = encoder final state of the same depth ------------------------------
   {
     LD& d0 = h->dec[0];
-    launch_copy2d_T(p, ef.Hst + (size_t)S * BPd * esz, ef.ph, d0.Hst, d0.ph, Bp, Hd, st);
-    launch_copy2d_T(p, eb.Hst, eb.ph, d0.Hst + (size_t)Hd * esz, d0.ph, Bp, Hd, st);
-    launch_copy2d_f32(ef.Cst + (size_t)S * BHd, Hd, d0.Cst, H, Bp, Hd, st);
-    launch_copy2d_f32(eb.Cst, Hd, d0.Cst + Hd, H, Bp, Hd, st);
+    std::vector<CopyJob> cp;
+    add_copy(cp, ef.Hst + (size_t)S * BPd * esz, ef.ph, d0.Hst, d0.ph, Bp, Hd, esz);
+    add_copy(cp, eb.Hst, eb.ph, d0.Hst + (size_t)Hd * esz, d0.ph, Bp, Hd, esz);
+    add_copy(cp, ef.Cst + (size_t)S * BHd, Hd, d0.Cst, H, Bp, Hd, 4);
+    add_copy(cp, eb.Cst, Hd, d0.Cst + Hd, H, Bp, Hd, 4);
     for (int l = 1; l < L; ++l) {
       LD& e = h->enc[l + 1]; LD& d = h->dec[l];
-      launch_copy2d_T(p, e.Hst + (size_t)S * BP * esz, e.ph, d.Hst, d.ph, Bp, H, st);
-      launch_copy2d_f32(e.Cst + (size_t)S * BH, H, d.Cst, H, Bp, H, st);
+      add_copy(cp, e.Hst + (size_t)S * BP * esz, e.ph, d.Hst, d.ph, Bp, H, esz);
+      add_copy(cp, e.Cst + (size_t)S * BH, H, d.Cst, H, Bp, H, 4);
     }
+    launch_copy2d_multi(cp.data(), (int)cp.size(), st);
   }
 }
 
@@ -524,7 +537,14 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
 
   h->phase_n = 0;
   phase_mark(h, "gathers + encoder bottom layer");
-  launch_fill_f32((float*)h->flags, 1, 0.f, st);
+  {   // error flags, H_o^{<-1>} = 0, and the decoder's state gradients at the end of time = 0: one launch
+    std::vector<FillJob> z;
+    add_fill(z, h->flags, 1, 4);
+    add_fill(z, h->HoBuf, BP, esz);
+    if (drop) add_fill(z, h->HoDrop, BP, esz);
+    for (int l = 0; l < L; ++l) { add_fill(z, h->dec[l].dh, BH, 4); add_fill(z, h->dec[l].dc, BH, 4); }
+    launch_fill_multi(z.data(), (int)z.size(), st);
+  }
   // ---- embeddings, masks ------------------------------------------------------------------------
   launch_gather(p, h->Pw(h->off_Esrc), c.src_vocab, E, src_ids, src_len, B, Bp, S, 0, 0, h->Xs, h->mask_s, h->tok_s,
                 nullptr, h->len_s, h->flags, st);
@@ -541,8 +561,6 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   {
     LD& d0 = h->dec[0];
     launch_gemm_nt(p, h->Xt, E, d0.W, E + 2 * H, Mt, 4 * H, E, d0.Gx, nullptr, 4 * H, P + d0.b_off, 0, st);
-    launch_fill_T(p, h->HoBuf, BP, st);
-    if (drop) launch_fill_T(p, h->HoDrop, BP, st);
     phase_mark(h, "decoder forward loop");
     for (int j = 0; j < T; ++j) {
       for (int l = 0; l < L; ++l) dec_lstm_fwd(h, l, j);
@@ -654,7 +672,6 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
 
   phase_mark(h, "decoder backward loop");
   // ---- decoder loop backwards -----------------------------------------------------------------------
-  for (int l = 0; l < L; ++l) { launch_fill_f32(h->dec[l].dh, BH, 0.f, st); launch_fill_f32(h->dec[l].dc, BH, 0.f, st); }
   const int kbd = step_kblocks(p, 2 * H, 4 * H, Bp, h->kb_bwd);       // planes written by a decoder layer's backward GEMM
   const size_t pstr = (size_t)Bp * 2 * H;
   for (int j = T - 1; j >= 0; --j) {
@@ -788,8 +805,10 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   {   // bottom layer: the two directions run in the same launches
     const float* dY0 = L > 1 ? h->dYa : h->dHs;
     LD& d0 = h->dec[0];
-    launch_copy2d_f32(d0.dh, H, ef.dh, Hd, Bp, Hd, st); launch_copy2d_f32(d0.dh + Hd, H, eb.dh, Hd, Bp, Hd, st);
-    launch_copy2d_f32(d0.dc, H, ef.dc, Hd, Bp, Hd, st); launch_copy2d_f32(d0.dc + Hd, H, eb.dc, Hd, Bp, Hd, st);
+    std::vector<CopyJob> cp;
+    add_copy(cp, d0.dh, H, ef.dh, Hd, Bp, Hd, 4); add_copy(cp, d0.dh + Hd, H, eb.dh, Hd, Bp, Hd, 4);
+    add_copy(cp, d0.dc, H, ef.dc, Hd, Bp, Hd, 4); add_copy(cp, d0.dc + Hd, H, eb.dc, Hd, Bp, Hd, 4);
+    launch_copy2d_multi(cp.data(), (int)cp.size(), st);
     const int kb0 = step_kblocks(p, Hd, 4 * Hd, Bp, h->kb_bwd);
     const size_t pstr0 = (size_t)Bp * Hd;
     for (int k = 0; k < S; ++k) {

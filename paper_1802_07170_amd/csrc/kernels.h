@@ -176,6 +176,13 @@ void launch_fill_T(int prec, void* p, size_t n, hipStream_t st);      // zeros
 void launch_cast(int prec, const float* src, void* dst, size_t n, hipStream_t st);   // fp32 -> T
 // 2-D copies with pitches (elements): fp32 -> fp32, T -> T.
 void launch_copy2d_f32(const float* src, int lds, float* dst, int ldd, int rows, int cols, hipStream_t st);
+// Several small zero-fills / 2-D copies in one launch each (the state initialisations of a step), in units of
+// 32-bit words: a fill clears `words` words at p; a copy moves rows x cols words with row pitches lds / ldd.
+constexpr int MULTI_MAX_JOBS = 32;
+struct FillJob { void* p; size_t words; };
+struct CopyJob { const void* src; int lds; void* dst; int ldd; int rows; int cols; };
+void launch_fill_multi(const FillJob* jobs, int n, hipStream_t st);
+void launch_copy2d_multi(const CopyJob* jobs, int n, hipStream_t st);
 void launch_copy2d_T(int prec, const void* src, int lds, void* dst, int ldd, int rows, int cols, hipStream_t st);
 void launch_add_f32(float* dst, const float* src, size_t n, hipStream_t st);          // dst += src
 void launch_sum_parts(const float* parts, int nparts, size_t n, float* out, hipStream_t st);

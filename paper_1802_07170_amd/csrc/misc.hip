@@ -148,6 +148,50 @@ void launch_copy2d_T(int prec, const void* src, int lds, void* dst, int ldd, int
   else launch_copy2d_f32((const float*)src, lds, (float*)dst, ldd, rows, cols, st);
 }
 
+struct FillJobs { FillJob j[MULTI_MAX_JOBS]; };
+struct CopyJobs { CopyJob j[MULTI_MAX_JOBS]; };
+__global__ __launch_bounds__(256) void fill_multi_kernel(FillJobs jobs) {
+  const FillJob& job = jobs.j[blockIdx.y];
+  uint32_t* p = (uint32_t*)job.p;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < job.words; i += stride) p[i] = 0u;
+}
+__global__ __launch_bounds__(256) void copy2d_multi_kernel(CopyJobs jobs) {
+  const CopyJob& job = jobs.j[blockIdx.y];
+  const uint32_t* s = (const uint32_t*)job.src;
+  uint32_t* d = (uint32_t*)job.dst;
+  const size_t n = (size_t)job.rows * job.cols, stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+    const size_t r = i / job.cols, c = i - r * job.cols;
+    d[r * job.ldd + c] = s[r * job.lds + c];
+  }
+}
+void launch_fill_multi(const FillJob* jobs, int n, hipStream_t st) {
+  for (int base = 0; base < n; base += MULTI_MAX_JOBS) {
+    const int m = n - base < MULTI_MAX_JOBS ? n - base : MULTI_MAX_JOBS;
+    FillJobs a;
+    size_t most = 1;
+    for (int i = 0; i < MULTI_MAX_JOBS; ++i) {
+      a.j[i] = i < m ? jobs[base + i] : FillJob{nullptr, 0};
+      if (a.j[i].words > most) most = a.j[i].words;
+    }
+    hipLaunchKernelGGL(fill_multi_kernel, dim3(grid_for(most), m), dim3(256), 0, st, a);
+  }
+}
+void launch_copy2d_multi(const CopyJob* jobs, int n, hipStream_t st) {
+  for (int base = 0; base < n; base += MULTI_MAX_JOBS) {
+    const int m = n - base < MULTI_MAX_JOBS ? n - base : MULTI_MAX_JOBS;
+    CopyJobs a;
+    size_t most = 1;
+    for (int i = 0; i < MULTI_MAX_JOBS; ++i) {
+      a.j[i] = i < m ? jobs[base + i] : CopyJob{nullptr, 0, nullptr, 0, 0, 0};
+      const size_t cnt = (size_t)a.j[i].rows * a.j[i].cols;
+      if (cnt > most) most = cnt;
+    }
+    hipLaunchKernelGGL(copy2d_multi_kernel, dim3(grid_for(most), m), dim3(256), 0, st, a);
+  }
+}
+
 __global__ __launch_bounds__(256) void cast_bf16_kernel(const float* __restrict__ s, bf16_t* __restrict__ d, size_t n) {
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * 256;
