@@ -433,7 +433,7 @@ void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st) {
     const char* e = getenv("CMT_STEP_TANH");
     g_step_tanh = e ? atoi(e) : 1;
   }
-  if (g.mode == 0 && g_step_tanh) {
+  if (g.mode == 0 && g_step_tanh && Bp < 256) {       // (from 256 sentences on its 16-sentence tiles re-read W too often)
     StepGrid sg{(g.N + 15) / 16, 1, nbt};
     const dim3 grid(step_grid_blocks(sg));
     const int nsteps = ((g.K0 + g.K1) / 8 + 3) / 4;
