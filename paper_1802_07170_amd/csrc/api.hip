@@ -19,6 +19,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <functional>
 #include <string>
 #include <vector>
@@ -276,7 +277,12 @@ size_t layout(cmt_handle* h, char* base) {
   h->colscr = (float*)a.take((size_t)16 * 4 * H * 4);
   h->dzs = a.take(ce_slab_elems(c.tgt_vocab) * esz); h->dzTs = a.take(ce_slab_elems(c.tgt_vocab) * esz);
   h->dbo_parts = (float*)a.take((Mt / 64 + Mt / 256 + 4) * c.tgt_vocab * 4);
-  h->gsplit_floats = (size_t)8 * CE_SLAB_ROWS * 1024;
+  {   // split-k planes of the small-output GEMMs (dH_o of a slab, weight-gradient segments): room for 16 planes
+      // of the largest such output, at most 32 MB
+    const size_t slab_rows = Mt < (size_t)CE_SLAB_ROWS ? Mt : (size_t)CE_SLAB_ROWS;
+    const size_t out_max = std::max(slab_rows * H, (size_t)4 * H * std::max(E, H));
+    h->gsplit_floats = std::min((size_t)8 * CE_SLAB_ROWS * 1024, 16 * out_max);
+  }
   h->gsplit = (float*)a.take(h->gsplit_floats * 4);
   h->gsplit2 = (float*)a.take(h->gsplit_floats * 4);
   h->dzs2 = a.take(ce_slab_elems(c.tgt_vocab) * esz); h->dzTs2 = a.take(ce_slab_elems(c.tgt_vocab) * esz);

@@ -162,16 +162,24 @@ __global__ __launch_bounds__(1024) void ce_compact_kernel(const float* __restric
   if (t == 0) { *n_valid = total; loss[1] = (float)total; }
 }
 
-// dst[c, :] = src[row[c], :] for c < *n_valid (cols * sizeof(T) and the pitches are multiples of 16 bytes)
+// dst[c, :] = src[row[c], :] for c < *n_valid (cols * sizeof(T) and the pitches are multiples of 16 bytes).
+// Rows from *n_valid up to the next multiple of 64 are zero-filled: the weight-gradient contraction
+// dW_o = dz^T H_o runs over whole blocks of 64 rows, and its other operand is zero there, so these
+// rows must hold numbers, whatever the workspace held before.
 template <typename T>
 __global__ __launch_bounds__(128) void ce_gather_rows_kernel(const T* __restrict__ src, int lds, const int32_t* __restrict__ row,
                                                              const int32_t* __restrict__ n_valid, T* __restrict__ dst, int ldd,
                                                              int cols) {
   const int c = blockIdx.x;
-  if (c >= *n_valid) return;
+  const int n = *n_valid;
+  if (c >= (n + 63) / 64 * 64) return;
   constexpr int VE = 16 / sizeof(T);
-  const T* s = src + (size_t)row[c] * lds;
   T* d = dst + (size_t)c * ldd;
+  if (c >= n) {
+    for (int k = threadIdx.x * VE; k < cols; k += 128 * VE) *reinterpret_cast<uint4*>(d + k) = make_uint4(0, 0, 0, 0);
+    return;
+  }
+  const T* s = src + (size_t)row[c] * lds;
   for (int k = threadIdx.x * VE; k < cols; k += 128 * VE) *reinterpret_cast<uint4*>(d + k) = *reinterpret_cast<const uint4*>(s + k);
 }
 void launch_ce_gather_rows(int prec, const void* src, int lds, const int32_t* row, const int32_t* n_valid, int max_rows, void* dst,

@@ -17,7 +17,7 @@ namespace cmt {
 // works on is clamp(*n - base, 0, the count the host passed).  n = null: the host's count.
 struct RowLimit { const int32_t* n = nullptr; int base = 0; };
 // limit_kind 1: `limit` bounds M (tiles beyond it exit; rows beyond it are not stored);
-// limit_kind 2: `limit` bounds K, rounded up to a multiple of 64 (the operands are zero there); a
+// limit_kind 2: `limit` bounds K, rounded up to a multiple of 64 (the callers zero-fill both operands there); a
 // workgroup whose contraction is empty exits without touching C.
 void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, int M, int N, int K,
                     float* Cf, void* Ct, int ldc, const float* bias, int accumulate, hipStream_t st,
@@ -45,7 +45,7 @@ void launch_ce_fwd(int prec, const void* Ho, int ldho, const void* Wo, const flo
 // *n_valid = loss[1] = n_tok.  The output layer then runs on the dense rows [0, n_valid).
 void launch_ce_compact(const float* mask, const int32_t* labels, int M, int32_t* pos, int32_t* row, int32_t* labels_c,
                        float* rowscale_c, int32_t* n_valid, float* loss, hipStream_t st);
-// dst[c, 0:cols] = src[row[c], 0:cols] for c < *n_valid (T rows; grid sized for max_rows)
+// dst[c, 0:cols] = src[row[c], 0:cols] for c < *n_valid, zero rows up to the next multiple of 64 (T rows; grid sized for max_rows)
 void launch_ce_gather_rows(int prec, const void* src, int lds, const int32_t* row, const int32_t* n_valid, int max_rows, void* dst,
                            int ldd, int cols, hipStream_t st);
 // lse[M] and the row loss nll[M] = (1 - eps) (lse - zy) + eps (lse - mean_v z_v) from the partials
