@@ -117,6 +117,23 @@ int cmt_eval_loss(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* src_
                   const int32_t* tgt_ids_dev, const int32_t* tgt_len_dev,
                   int32_t B, int32_t S, int32_t T, float* loss_host, float* n_tok_host);
 
+/* cmt_eval_loss for callers that cannot provide (or allocate) a workspace for the call: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, same result
+ * (the same kernels in the same order), but every intermediate — including the working copies of the
+ * parameters, which are rebuilt on each call — lives in one array of CMT_STATIC_SCRATCH_BYTES that is
+ * part of the library's device code, laid out for exactly this call's B, S and T; the handle's
+ * workspace, its last step's intermediates and the gradient buffer are untouched.  The call allocates
+ * and frees nothing.  A shape whose intermediates do not fit is refused with CMT_EINVAL (cmt_last_error
+ * names both sizes): the tiny configuration (hidden 64, vocabulary 1000, 8 x 10 tokens) needs about
+ * 20 MB.  Each GPU holds one such array until the process ends, shared by all handles; it keeps the last
+ * call's contents and is cleared at the start of each call.  Calls that overlap on one GPU — from
+ * several handles, streams or threads — race on it: serialise them.  Like cmt_eval_loss it leaves its
+ * own loss in the handle's pinned read-back slot (what a later cmt_fetch_loss returns). */
+#define CMT_STATIC_SCRATCH_BYTES (32u << 20)
+int cmt_eval_loss_static(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* src_len_dev,
+                         const int32_t* tgt_ids_dev, const int32_t* tgt_len_dev,
+                         int32_t B, int32_t S, int32_t T, float* loss_host, float* n_tok_host);
+
 int cmt_get_grads(cmt_handle* h, float* host_dst);
 
 /* Regularisation of the training step (Settings section; hyperparameter table: dropout 0.2, label

@@ -18,7 +18,7 @@ EXPORTS = [
     "cmt_init_params", "cmt_set_params", "cmt_get_params", "cmt_train_step", "cmt_train_step_async",
     "cmt_fetch_loss", "cmt_get_grads", "cmt_sgd_update", "cmt_debug_fetch", "cmt_padded_batch",
     "cmt_time_kernel", "cmt_last_error", "cmt_set_regularization", "cmt_greedy_decode", "cmt_beam_decode",
-    "cmt_eval_loss",
+    "cmt_eval_loss", "cmt_eval_loss_static",
 ]
 
 
@@ -63,6 +63,7 @@ def load_library():
     lib.cmt_train_step_async.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32]
     lib.cmt_fetch_loss.argtypes = [vp, C.POINTER(C.c_float)]
     lib.cmt_eval_loss.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, C.POINTER(C.c_float), C.POINTER(C.c_float)]
+    lib.cmt_eval_loss_static.argtypes = lib.cmt_eval_loss.argtypes
     lib.cmt_get_grads.argtypes = [vp, vp]
     lib.cmt_sgd_update.argtypes = [vp, C.c_float]
     lib.cmt_set_regularization.argtypes = [vp, C.c_float, C.c_float, C.c_uint64]
@@ -189,6 +190,14 @@ class Trainer:
         loss, ntok = C.c_float(), C.c_float()
         self._check(self.lib.cmt_eval_loss(self.h, s.data_ptr(), sl.data_ptr(), tg.data_ptr(), tl.data_ptr(),
                                            s.shape[0], s.shape[1], tg.shape[1], C.byref(loss), C.byref(ntok)))
+        return loss.value, ntok.value
+
+    def eval_loss_static(self, dev_batch):
+        """eval_loss with every intermediate in the library's static device array (allocates nothing)."""
+        s, sl, tg, tl = dev_batch
+        loss, ntok = C.c_float(), C.c_float()
+        self._check(self.lib.cmt_eval_loss_static(self.h, s.data_ptr(), sl.data_ptr(), tg.data_ptr(), tl.data_ptr(),
+                                                  s.shape[0], s.shape[1], tg.shape[1], C.byref(loss), C.byref(ntok)))
         return loss.value, ntok.value
 
     def sgd_update(self, lr):

@@ -990,6 +990,67 @@ int cmt_eval_loss(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* src_
   return rc;
 }
 
+// ---- evaluation without a caller-provided workspace -------------------------------------------------
+// All intermediates of cmt_eval_loss_static live in this array instead of the handle's workspace.  In
+// host code the array's name is only a stand-in: the device address comes from hipGetSymbolAddress,
+// once per device (every GPU holds its own copy), and only that pointer is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[CMT_STATIC_SCRATCH_BYTES];
+namespace {
+constexpr int STATIC_MAX_DEVICES = 64;
+void* g_static_scratch[STATIC_MAX_DEVICES] = {};
+// device address of `scratch` on the current device (looked up at the first call on that device)
+int static_scratch_ptr(cmt_handle* h, char** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(h, e, "hipGetDevice");
+  if (dev < 0 || dev >= STATIC_MAX_DEVICES) return fail(h, CMT_EINVAL, "device ordinal beyond the static scratch table");
+  if (!g_static_scratch[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return hip_fail(h, e, "hipGetSymbolAddress(scratch)");
+    g_static_scratch[dev] = p;
+  }
+  *out = (char*)g_static_scratch[dev];
+  return CMT_OK;
+}
+}  // namespace
+
+int cmt_eval_loss_static(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* src_len_dev, const int32_t* tgt_ids_dev,
+                         const int32_t* tgt_len_dev, int32_t B, int32_t S, int32_t T, float* loss_host, float* n_tok_host) {
+  if (!h) return CMT_EINVAL;
+  const cmt_config& c = h->cfg;
+  if (B < 1 || B > c.max_batch || S < 1 || S > c.max_src_len || T < 1 || T > c.max_tgt_len)
+    return fail(h, CMT_EINVAL, "B, S or T outside [1, configured maximum]");
+  // a view of the handle whose workspace is the static array, laid out for exactly this call's shape
+  cmt_handle v = *h;
+  v.cfg.max_batch = B; v.cfg.max_src_len = S; v.cfg.max_tgt_len = T;
+  v.Bpm = round_up(B, 16);
+  v.phase_timing = 0; v.phase_ev.clear(); v.phase_name.clear();
+  const size_t need = layout(&v, nullptr);
+  if (need > (size_t)CMT_STATIC_SCRATCH_BYTES) {
+    char msg[160];
+    snprintf(msg, sizeof msg, "this shape needs %zu bytes of scratch, the static buffer holds %zu", need,
+             (size_t)CMT_STATIC_SCRATCH_BYTES);
+    return fail(h, CMT_EINVAL, msg);
+  }
+  char* base = nullptr;
+  int rc = static_scratch_ptr(h, &base);
+  if (rc != CMT_OK) return rc;
+  v.ws = base;
+  v.ws_bytes = layout(&v, base);
+  bind_params(&v);
+  // the array keeps the last call's contents (perhaps of another shape): start from zeros
+  launch_fill_f32((float*)base, (need + 3) / 4, 0.f, v.st);
+  refresh_params(&v);                                // working copies of the parameters (casts, transposes) in the array
+  v.drop_p = 0.f; v.ls_eps = 0.f;                    // evaluation: no masks, plain cross-entropy
+  rc = enqueue_step(&v, src_ids_dev, src_len_dev, tgt_ids_dev, tgt_len_dev, B, S, T, true);
+  if (rc == CMT_OK) rc = cmt_fetch_loss(&v, loss_host);
+  if (rc != CMT_OK) { h->err = v.err; return rc; }
+  if (n_tok_host) *n_tok_host = v.h_loss[1];
+  h->ev_next = v.ev_next;
+  return CMT_OK;
+}
+
 int cmt_fetch_loss(cmt_handle* h, float* loss_host) {
   if (!h) return CMT_EINVAL;
   if (!h->have_step) return fail(h, CMT_EINVAL, "no step has been run");
