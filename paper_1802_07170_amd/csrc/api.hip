@@ -118,6 +118,11 @@ struct cmt_handle {
   int use_side = 1;
   char* dzs2 = nullptr; char* dzTs2 = nullptr; float* gsplit2 = nullptr;
   int kb_bwd = 0, kb_wc = 0;            // caps on the k blocks of the backward step GEMMs (0 = default)
+  // backward loops that use the whole-k step GEMM with the consumer in its epilogue (env CMT_BWD_FUSED, a bit
+  // mask): 1 = decoder, 2 = upper encoder layers, 4 = bottom encoder layer.  The upper encoder layers keep the
+  // k-split GEMM + pointwise pair: their launches carry up to L - 1 layer-steps, and three rounds of
+  // 1024-thread workgroups per CU take longer (45 us per diagonal) than the pair (34 us).
+  int bwd_fused = 5;
   // phase timing of a step on the caller's stream (measurement aid, env CMT_PHASE_TIMING=1)
   int phase_timing = 0;
   std::vector<hipEvent_t> phase_ev; std::vector<const char*> phase_name; size_t phase_n = 0;
@@ -385,6 +390,58 @@ DropSpec drop_spec(const cmt_handle* h, int site, int t) {
     d.key0 = h->drop_seed + ((unsigned long long)site << 48) + (unsigned long long)t * (unsigned long long)h->B * H;
   }
   return d;
+}
+
+// the cell backward of decoder layer l at step j; dy / dhrec are filled in by the caller
+LstmBwdPoint dec_cell(cmt_handle* h, int l, int j) {
+  const int H = h->cfg.hidden, Bp = h->Bp;
+  const size_t BH = (size_t)Bp * H;
+  LD& e = h->dec[l];
+  LstmBwdPoint q;
+  q.dy = Planes{nullptr, 0, 0, 0}; q.dy_col = 0; q.dhrec = Planes{nullptr, 0, 0, 0}; q.dhrec_col = 0;
+  q.dh = e.dh; q.dc = e.dc;
+  q.gsave = e.Gs + (size_t)j * Bp * 4 * H;
+  q.cprev = e.Cst + j * BH; q.cnext = e.Cst + (j + 1) * BH;
+  q.mask = h->mask_t + (size_t)j * Bp;
+  q.dg = e.dG + (size_t)j * Bp * e.pg * h->esz; q.lddg = e.pg;
+  return q;
+}
+
+// Backward step GEMM of decoder layer l at step j in its fused form: [dx; dh_prev] = dgates [W_x; W_h] with the
+// whole contraction inside the workgroup.  The dx half feeds the cell backward of the layer below in the
+// epilogue (bottom layer: the tanh backward of the previous step's H_o, which received it through the input
+// feed); the dh_prev half is stored (one fp32 matrix per layer, the first Bp * H floats of bwdp) for that
+// layer's next step.
+StepBwd dec_bwd_gemm(cmt_handle* h, int l, int j) {
+  const cmt_config& c = h->cfg;
+  const int E = c.emb_dim, H = c.hidden, Bp = h->Bp, PH = h->PH;
+  const size_t esz = h->esz, BP = (size_t)Bp * PH;
+  const bool last = j == h->T - 1;
+  LD& e = h->dec[l];
+  StepBwd g{};
+  g.dg = e.dG + (size_t)j * Bp * e.pg * esz; g.lddg = e.pg; g.K = 4 * H; g.ldw = 4 * H;
+  BwdEpi store{};
+  store.kind = BWD_EPI_STORE; store.ncols = H; store.hh = H; store.out = e.bwdp; store.ldout = H;
+  if (l > 0) {
+    g.Wt = e.Wt;
+    BwdEpi& c0 = g.part[0];
+    c0.kind = BWD_EPI_CELL_DY; c0.ncols = H; c0.hh = H;
+    c0.cell = dec_cell(h, l - 1, j);
+    c0.cell.drop_dy = drop_spec(h, DROP_SITE_DEC + l - 1, j);
+    c0.cell.dhrec = Planes{h->dec[l - 1].bwdp, H, last ? 0 : 1, 0};
+    g.part[1] = store;
+  } else if (j > 0) {
+    g.Wt = e.Wt + (size_t)E * 4 * H * esz;                       // rows [feed; h] of the bottom layer's W^T
+    BwdEpi& t0 = g.part[0];
+    t0.kind = BWD_EPI_TANH; t0.ncols = H; t0.hh = H;
+    t0.dce = h->dHoCE; t0.pos = h->ce_pos + (size_t)(j - 1) * Bp; t0.Ho = h->HoBuf + j * BP * esz; t0.ldho = PH;
+    t0.dpre = h->dPre + (j - 1) * BP * esz; t0.ldp = PH; t0.drop = drop_spec(h, DROP_SITE_HO, j - 1);
+    g.part[1] = store;
+  } else {
+    g.Wt = e.Wt + (size_t)(E + H) * 4 * H * esz;                 // H_o^{<-1>} is a constant: only dh_prev
+    g.part[0] = store;
+  }
+  return g;
 }
 
 // forward step j of decoder layer l (layer 0 takes [H_o^{<j-1>}; h] per step, its embedding part is pre-batched)
@@ -680,6 +737,37 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   // ---- decoder loop backwards -----------------------------------------------------------------------
   const int kbd = step_kblocks(p, 2 * H, 4 * H, Bp, h->kb_bwd);       // planes written by a decoder layer's backward GEMM
   const size_t pstr = (size_t)Bp * 2 * H;
+  const Planes no_planes{nullptr, 0, 0, 0};
+  if (h->bwd_fused & 1) {
+    // one launch per layer and step (dec_bwd_gemm): no pointwise launches, no planes
+    for (int j = T - 1; j >= 0; --j) {
+      char* dpre = h->dPre + j * BP * esz;
+      const bool last = j == T - 1;
+      if (last)
+        launch_tanh_bwd(p, h->dHoCE, h->ce_pos + (size_t)j * Bp, no_planes, h->HoBuf + (j + 1) * BP * esz, PH, dpre, PH, Bp, H,
+                        drop_spec(h, DROP_SITE_HO, j), st);
+      const int kbw = step_kblocks(p, 2 * H, H, Bp, h->kb_wc);
+      {   // [dC_s ; dH_t] = dpre W_c, as planes
+        StepGemm g{};
+        g.a0 = dpre; g.lda0 = PH; g.K0 = H; g.w0_off = 0; g.K1 = 0;
+        g.W = h->WcT; g.ldw = H; g.N = 2 * H; g.mode = 1; g.max_kb = h->kb_wc;
+        g.out = h->wcp; g.ldout = 2 * H; g.plane_stride = pstr;
+        launch_step_gemm(p, g, Bp, st);
+      }
+      // attention backward; the gradient it sends to the top layer's output stays in registers and that
+      // layer's cell backward runs in the same launch
+      LstmBwdPoint top = dec_cell(h, L - 1, j);
+      top.dhrec = Planes{h->dec[L - 1].bwdp, H, last ? 0 : 1, 0};
+      launch_att_bwd(p, h->Kmat, H, Hs, ldHs, Planes{h->wcp, 2 * H, kbw, pstr}, h->dCs + j * BH, h->att_a + (size_t)j * Bp * S,
+                     h->len_s, S, Bp, H, h->dots, h->att_ds + (size_t)j * Bp * S, h->dHt, st, &top);
+      for (int l = L - 1; l >= 0; --l) {
+        const StepBwd g = dec_bwd_gemm(h, l, j);
+        launch_step_bwd_fused(p, &g, 1, Bp, st);
+      }
+    }
+    for (int l = 0; l < L; ++l)
+      launch_planes_add(h->dec[l].dh, h->dec[l].dh, Planes{h->dec[l].bwdp, H, 1, 0}, 0, Bp, H, st);
+  } else {
   for (int j = T - 1; j >= 0; --j) {
     char* dpre = h->dPre + j * BP * esz;
     const bool last = j == T - 1;
@@ -720,6 +808,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   // gradient of the decoder's initial state: pass-through part + the last GEMM's recurrent part
   for (int l = 0; l < L; ++l)
     launch_planes_add(h->dec[l].dh, h->dec[l].dh, Planes{h->dec[l].bwdp, 2 * H, kbd, pstr}, H, Bp, H, st);
+  }
 
   phase_mark(h, "deferred attention gradients");
   // ---- second stream: everything that only needed the decoder's dgates and dpre -----------------------
@@ -762,7 +851,65 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   // ---- encoder backwards ------------------------------------------------------------------------------
   // Upper layers: the same wavefront, top layer first.  Per diagonal one pointwise launch (cell
   // backward of every active layer-step) and one step-GEMM launch ([dx; dh_prev] = dgates [W_x; W_h]).
-  if (L > 1) {
+  if (L > 1 && (h->bwd_fused & 2)) {
+    // Fused form: one launch per diagonal.  The step GEMM of (layer l, position t) keeps its dh_prev half in
+    // registers and runs the cell backward of (l, t - 1) in its epilogue; its dx half is stored for the layer
+    // below (two alternating slots of bwdp per layer, Bp * H floats each).  Layer l at position t - 1 needs the
+    // dx of layer l + 1 at t - 1 from an earlier launch, so a layer runs two diagonals behind the one above:
+    // (l, t) sits on diagonal (S - 1 - t) + 2 (L - 1 - l).  The first position of a layer has no GEMM
+    // before it: its cell backward is a pointwise launch just ahead of the layer's first diagonal.
+    const size_t slot = (size_t)Bp * H;
+    auto enc_cell = [&](int l, int t) {
+      LD& e = h->enc[l + 1];
+      LstmBwdPoint q;
+      if (l == L - 1) q.dy = Planes{h->dHs + (size_t)t * Bp * H, H, 1, 0};
+      else { q.dy = Planes{h->enc[l + 2].bwdp + (size_t)(t & 1) * slot, H, 1, 0}; q.drop_dy = drop_spec(h, DROP_SITE_ENC + l, t); }
+      q.dy_col = 0;
+      q.dhrec = Planes{nullptr, 0, 0, 0}; q.dhrec_col = 0;
+      q.dh = h->dec[l].dh; q.dc = h->dec[l].dc;      // gradient of the final state = gradient of the decoder's initial state
+      q.gsave = e.Gs + (size_t)t * Bp * 4 * H;
+      q.cprev = e.Cst + t * BH; q.cnext = e.Cst + (t + 1) * BH;
+      q.mask = h->mask_s + (size_t)t * Bp;
+      q.dg = e.dG + (size_t)t * Bp * e.pg * esz; q.lddg = e.pg;
+      return q;
+    };
+    for (int dg = 0; dg <= (S - 1) + 2 * (L - 2); ++dg) {
+      StepBwd gs[STEP_MAX_INST];
+      int ng = 0;
+      for (int l = L - 1; l >= 1; --l) {
+        const int k = dg - 2 * (L - 1 - l);
+        if (k < 0 || k >= S) continue;
+        const int t = S - 1 - k;
+        LD& e = h->enc[l + 1];
+        if (k == 0) launch_lstm_bwd_point(p, enc_cell(l, t), Bp, H, st);
+        if (l == 1 && t == 0) continue;              // the initial state is a constant, and layer 1's dx is batched below
+        StepBwd& g = gs[ng++];
+        g = StepBwd{};
+        g.dg = e.dG + (size_t)t * Bp * e.pg * esz; g.lddg = e.pg; g.K = 4 * H; g.ldw = 4 * H;
+        int np = 0;
+        if (l > 1) {
+          g.Wt = e.Wt;
+          BwdEpi& d = g.part[np++];
+          d.kind = BWD_EPI_STORE; d.ncols = H; d.hh = H; d.out = e.bwdp + (size_t)(t & 1) * slot; d.ldout = H;
+        } else {
+          g.Wt = e.Wt + (size_t)H * 4 * H * esz;
+        }
+        if (t > 0) {
+          BwdEpi& r = g.part[np++];
+          r.kind = BWD_EPI_CELL_REC; r.ncols = H; r.hh = H; r.cell = enc_cell(l, t - 1);
+        }
+      }
+      if (ng) launch_step_bwd_fused(p, gs, ng, Bp, st);
+    }
+    LD& e1 = h->enc[2];
+    launch_gemm_nt(p, e1.dG, e1.pg, e1.Wt, 4 * H, Ms, H, 4 * H, h->dYa, nullptr, H, nullptr, 0, st);   // layer 0's dY = dG_1 W_x
+    stream_after(h, sd, st);
+    for (int l = L - 1; l >= 1; --l) {
+      LD& e = h->enc[l + 1];
+      int ld; const char* XT = encYT(l - 1, &ld);
+      weight_grads(h, e, S, {{XT, ld}, {e.HstT, (S + 1) * Bp}}, {H, H}, sd);
+    }
+  } else if (L > 1) {
     const int Nplan = L > 2 ? 2 * H : H;
     const int kbE = step_kblocks(p, Nplan, 4 * H, Bp, h->kb_bwd);
     const size_t pstrE = (size_t)Bp * 2 * H;
@@ -817,6 +964,41 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     launch_copy2d_multi(cp.data(), (int)cp.size(), st);
     const int kb0 = step_kblocks(p, Hd, 4 * Hd, Bp, h->kb_bwd);
     const size_t pstr0 = (size_t)Bp * Hd;
+    // cell backward of direction i at position t (its dy is a slice of the batched dY of the layer above)
+    auto enc0_cell = [&](int i, int t) {
+      LD& e = i ? eb : ef;
+      const int slot_prev = i ? t + 1 : t, slot_next = i ? t : t + 1;
+      LstmBwdPoint q;
+      q.dy = Planes{dY0 + (size_t)t * Bp * H, H, 1, 0}; q.dy_col = i ? Hd : 0;
+      if (L > 1) q.drop_dy = drop_spec(h, DROP_SITE_ENC + 0, t);
+      q.dhrec = Planes{nullptr, 0, 0, 0}; q.dhrec_col = 0;
+      q.dh = e.dh; q.dc = e.dc;
+      q.gsave = e.Gs + (size_t)t * Bp * 4 * Hd;
+      q.cprev = e.Cst + (size_t)slot_prev * BHd; q.cnext = e.Cst + (size_t)slot_next * BHd;
+      q.mask = h->mask_s + (size_t)t * Bp;
+      q.dg = e.dG + (size_t)t * Bp * e.pg * esz; q.lddg = e.pg;
+      return q;
+    };
+    if (h->bwd_fused & 4) {
+      // one launch per position: dh_prev = dgates W_h of both directions, the cell backward of each
+      // direction's next position in the epilogue; only the very first position is a pointwise launch
+      LstmBwdPoint first[2] = {enc0_cell(0, S - 1), enc0_cell(1, 0)};
+      launch_lstm_bwd_point_multi(p, first, 2, Bp, Hd, st);
+      for (int k = 0; k + 1 < S; ++k) {
+        StepBwd gs[2];
+        for (int i = 0; i < 2; ++i) {
+          LD& e = i ? eb : ef;
+          const int t = i ? k : S - 1 - k, tn = i ? k + 1 : S - 2 - k;
+          StepBwd& g = gs[i];
+          g = StepBwd{};
+          g.dg = e.dG + (size_t)t * Bp * e.pg * esz; g.lddg = e.pg; g.K = 4 * Hd;
+          g.Wt = e.Wt + (size_t)E * 4 * Hd * esz; g.ldw = 4 * Hd;
+          BwdEpi& r = g.part[0];
+          r.kind = BWD_EPI_CELL_REC; r.ncols = Hd; r.hh = Hd; r.cell = enc0_cell(i, tn);
+        }
+        launch_step_bwd_fused(p, gs, 2, Bp, st);
+      }
+    } else
     for (int k = 0; k < S; ++k) {
       LstmBwdPoint pts[2];
       StepGemm gs[2];
@@ -897,6 +1079,7 @@ int cmt_create(const cmt_config* cfg, void* params_dev, void* grads_dev, void* w
     const char* k2 = getenv("CMT_KB_WC"); h->kb_wc = k2 ? atoi(k2) : 2;
     const char* k3 = getenv("CMT_SIDE_STREAM"); h->use_side = k3 ? atoi(k3) : 1;
     const char* k4 = getenv("CMT_PHASE_TIMING"); h->phase_timing = k4 ? atoi(k4) : 0;
+    const char* k5 = getenv("CMT_BWD_FUSED"); h->bwd_fused = k5 ? atoi(k5) : 5;
   }
   build_table(h->cfg, h->table, h->nparams);
   h->ws_bytes = layout(h, h->ws);
@@ -1293,6 +1476,16 @@ int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_la
       g.N = 2 * H; g.mode = 1; g.max_kb = h->kb_bwd;
       g.out = e.bwdp; g.ldout = 2 * H; g.plane_stride = (size_t)Bp * 2 * H;
       launch_step_gemm(p, g, Bp, st);
+    };
+  } else if (s == "step_bwd_fused_dec") {
+    // the same product with the whole contraction inside the workgroup and the cell backward of the layer below
+    // in the epilogue (the form the decoder's backward loop runs): weights and dgates read once, dh_prev stored,
+    // and the pointwise operands of the fused cell backward (gates, c, dc, dh in and out, dgates out)
+    *algo_work = 4.0 * H * 2 * H * esz + (double)Bp * 4 * H * esz + (double)Bp * H * 4
+               + (double)Bp * H * (4 * 4 + 2 * 4 + 2 * 4 + 2 * 4 + 4) + (double)Bp * 4 * H * esz;
+    launch = [=](int i) {
+      const StepBwd g = dec_bwd_gemm(h, L > 1 ? 1 + i % (L - 1) : 0, j);
+      launch_step_bwd_fused(p, &g, 1, Bp, st);
     };
   } else if (s == "att_fwd") {
     // scores + softmax + context of one decoder step: the keys and H_s of every sentence once

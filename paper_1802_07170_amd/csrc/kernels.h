@@ -135,6 +135,36 @@ struct LstmBwdPoint {
 };
 void launch_lstm_bwd_point(int prec, const LstmBwdPoint& p, int Bp, int Hh, hipStream_t st);
 void launch_lstm_bwd_point_multi(int prec, const LstmBwdPoint* ps, int n, int Bp, int Hh, hipStream_t st);
+// Backward step GEMM with the whole contraction inside the workgroup and the consumer of its result fused
+// into the epilogue: out[Bp, N] = dg[Bp, K] * Wt[N, K]^T, where the N output columns come in two parts
+// (part 0 first), each with its own epilogue:
+//   BWD_EPI_STORE     the values are stored as fp32 to out [Bp, ncols] (row pitch ldout);
+//   BWD_EPI_CELL_DY   the values are the gradient arriving at the output of the LSTM step `cell` (the layer
+//                     below, same time step: dx of this layer), added to cell.dy; the cell backward runs
+//                     in-register and writes that step's dgates;
+//   BWD_EPI_CELL_REC  the values are the recurrent part of the state gradient of the LSTM step `cell` (this
+//                     layer, the next step of the backward loop: dh_prev), added to cell.dhrec;
+//   BWD_EPI_TANH      the values are the input-feed gradient of H_o of the previous decoder step:
+//                     dpre = (dce[pos[b]] + value) * drop * (1 - Ho^2), as launch_tanh_bwd computes it.
+// ncols of part 0 is a multiple of 16; both are multiples of 4.  hh = hidden width of `cell` (CELL_*) or the
+// row width of dce (TANH).
+enum { BWD_EPI_STORE = 0, BWD_EPI_CELL_DY = 1, BWD_EPI_CELL_REC = 2, BWD_EPI_TANH = 3 };
+struct BwdEpi {
+  int kind = BWD_EPI_STORE; int ncols = 0; int hh = 0;
+  float* out = nullptr; int ldout = 0;
+  LstmBwdPoint cell{};
+  const float* dce = nullptr; const int32_t* pos = nullptr; const void* Ho = nullptr; int ldho = 0;
+  void* dpre = nullptr; int ldp = 0; DropSpec drop{};
+};
+struct StepBwd {
+  const void* dg; int lddg; int K;     // T* [Bp, K]
+  const void* Wt; int ldw;             // T* [N, K]: row n = output column n
+  BwdEpi part[2];
+};
+constexpr int STEP_BWD_MAX_INST = 4;
+// n independent instances in one launch (more than STEP_BWD_MAX_INST are spread over several launches)
+void launch_step_bwd_fused(int prec, const StepBwd* gs, int n, int Bp, hipStream_t st);
+
 // out[Bp, cols] = base (or 0) + planes columns col0 + [0, cols)
 void launch_planes_add(float* out, const float* base, const Planes& p, int col0, int Bp, int cols, hipStream_t st);
 
@@ -148,9 +178,11 @@ void launch_att_fwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds
 // columns [0,H) = dC_s, [H,2H) = the part of dH_t that came through the concatenation.
 // da_i = dC_s . H_s^i, ds = a (da - sum a da), dHt = dCst[:, H:] + sum ds_i K_i;
 // dCs_sum [Bp,H] receives the summed dC_s (kept for the deferred gradients).
+// With `cell` (the top decoder layer's step, hidden width H) the cell backward of that step runs in the same
+// launch with dHt as the gradient at its output (added to cell->dy), and dHt itself is not stored.
 void launch_att_bwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds, const Planes& dCst, float* dCs_sum, const float* a,
                     const int32_t* src_len, int S, int Bp, int H, float* dots, float* ds /*[Bp,S]*/,
-                    float* dHt /*[Bp,H]*/, hipStream_t st);
+                    float* dHt /*[Bp,H]*/, hipStream_t st, const LstmBwdPoint* cell = nullptr);
 // After the decoder loop: dHs_ctx[i,b,:] = sum_j a[j,b,i] dCs[j,b,:], dK[i,b,:] = sum_j ds[j,b,i] Ht[j,b,:].
 void launch_att_deferred(int prec, const float* a, const float* ds, const float* dCs, int lddc, const void* Ht, int ldht,
                          int S, int T, int Bp, int H, float* dHs, void* dK, hipStream_t st);

@@ -16,6 +16,8 @@
 // and meet in one L2.
 #include <stdlib.h>
 
+#include <algorithm>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -23,7 +25,7 @@ namespace cmt {
 
 constexpr int STEP_MAXBT = 4;          // batch tiles (of 16 sentences) per workgroup
 
-struct StepGrid { int nx, kb, nz; };
+struct StepGrid { int nx, kb, nz; int krot = 0; };
 struct StepGemmArgs { StepGemm g[STEP_MAX_INST]; };
 struct LstmBwdPointArgs { LstmBwdPoint p[STEP_MAX_INST]; };
 __device__ __forceinline__ bool decode_block(const StepGrid& g, int& x, int& kb, int& z) {
@@ -44,7 +46,8 @@ static inline int step_grid_blocks(const StepGrid& g) { return ((g.nx + 7) / 8) 
 // t % KS.  red must hold KS * RT * STEP_MAXBT * 256 floats.
 template <typename T, int RT, int KS, int U, int BT = STEP_MAXBT>
 __device__ __forceinline__ void step_contract(const T* const (&wrow)[RT], int w0_off, int w1_off, const T* a0, int lda0,
-                                              int K0, const T* a1, int lda1, int K1, int Bp, int bt0, int nbt, float* red) {
+                                              int K0, const T* a1, int lda1, int K1, int Bp, int bt0, int nbt, float* red,
+                                              int rot = 0) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int nc0 = K0 >> 3, nc = (K0 + K1) >> 3;
   const int nsteps = (nc + 3) >> 2;
@@ -58,8 +61,14 @@ __device__ __forceinline__ void step_contract(const T* const (&wrow)[RT], int w0
     Frag<T> fw[U][RT], fx[U][BT];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int chunk = 4 * (s0 + w + KS * u) + (lane >> 4);
-      if (chunk < nc) {
+      // workgroups start at different points of the k axis (rot), so that the ones that share an
+      // activation slab do not ask the same L2 lines at the same time
+      int ks = s0 + w + KS * u;
+      const bool in_range = ks < nsteps;
+      ks += rot;
+      if (ks >= nsteps) ks -= nsteps;
+      const int chunk = 4 * ks + (lane >> 4);
+      if (in_range && chunk < nc) {
         const bool first = chunk < nc0;
         const int kk = first ? chunk * 8 : (chunk - nc0) * 8;
         const int wo = (first ? w0_off : w1_off) + kk;
@@ -188,8 +197,13 @@ __global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(LstmFwdArgs args, int
     have0 = bt < nbt && u < Hh && b < Bp;
     if (have0) in0 = cell_load(d, b, u, Hh, sizeof(T) == 2);
   }
+  int rot = 0;
+  if (sg.krot) {
+    const int nsteps = (((d.Kx + Hh) >> 3) + 3) >> 2;
+    rot = (int)(((long long)(blockIdx.x >> 3) * nsteps) / max(1, (int)(gridDim.x >> 3)));
+  }
   step_contract<T, RT, KS, U, BT>(wrow, d.wx_off, d.wh_off, (const T*)d.x, d.ldx, d.Kx, (const T*)d.hprev, d.ldh, Hh, Bp, bt0,
-                              nbt, red);
+                              nbt, red, rot);
   for (int t = w; t < RT * BT; t += KS) {
     const int rt = t / BT, bt = t - rt * BT;
     if (bt >= nbt) continue;
@@ -203,10 +217,11 @@ __global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(LstmFwdArgs args, int
   }
 }
 
+static int g_step_krot = 0;            // env CMT_KROT (experiment): rotate the k order per workgroup
 template <typename T, int RT, int KS, int U, int BT = STEP_MAXBT>
 static void lstm_fwd_go(const LstmFwdArgs& a, int Bp, int Hh, int ndir, hipStream_t st) {
   const int nbt = (Bp + 15) / 16;
-  StepGrid sg{((Hh + 4 * RT - 1) / (4 * RT)) * ndir, 1, (nbt + BT - 1) / BT};
+  StepGrid sg{((Hh + 4 * RT - 1) / (4 * RT)) * ndir, 1, (nbt + BT - 1) / BT, g_step_krot};
   hipLaunchKernelGGL((lstm_fwd_kernel<T, RT, KS, U, BT>), dim3(step_grid_blocks(sg)), dim3(64 * KS), 0, st, a, Bp, Hh, sg, ndir);
 }
 
@@ -219,6 +234,8 @@ void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh,
   if (g_lstm_fwd_how < 0) {
     const char* e = getenv("CMT_LSTM_FWD");
     g_lstm_fwd_how = e ? atoi(e) : 0;
+    const char* r = getenv("CMT_KROT");
+    g_step_krot = r ? atoi(r) : 0;
   }
   LstmFwdArgs a;
   int K = 0;
@@ -235,7 +252,9 @@ void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh,
   if (how == 0) how = (Bp >= 256) ? 4 : (Bp > 64) ? 2 : (prec && nbt == 4) ? 6 : 1;
   const int nsteps = (K / 8 + 3) / 4;
   if (prec) {
-    if (how == 6) {
+    if (how == 7) lstm_fwd_go<bf16_t, 2, 8, 8, 2>(a, Bp, Hh, ndir, st);
+    else if (how == 8) lstm_fwd_go<bf16_t, 2, 16, 4, 2>(a, Bp, Hh, ndir, st);
+    else if (how == 6) {
       if (nsteps > 32) lstm_fwd_go<bf16_t, 2, 8, 4, 2>(a, Bp, Hh, ndir, st);
       else if (nsteps > 16) lstm_fwd_go<bf16_t, 2, 8, 2, 2>(a, Bp, Hh, ndir, st);
       else lstm_fwd_go<bf16_t, 2, 4, 2, 2>(a, Bp, Hh, ndir, st);
@@ -493,6 +512,58 @@ template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t* p, const floa
   *reinterpret_cast<uint2*>(p) = o;
 }
 
+// Cell backward of 4 consecutive units u..u+3 of sentence b.  The gradient arriving at the step's output is
+// dy = p.dy planes + dy_x, the recurrent part of the state gradient is p.dhrec planes + rec_x (the _x parts are
+// what a fused caller holds in registers); everything else comes from p.
+struct CellBwdIn { float4 i, f, g, o, cp, cn, dc, dhp, dy, rec; float mask; };
+__device__ __forceinline__ CellBwdIn cell_bwd_load(const LstmBwdPoint& p, int b, int u, int Hh) {
+  CellBwdIn in;
+  const size_t idx = (size_t)b * Hh + u;
+  in.mask = p.mask[b];
+  in.rec = planes_get4(p.dhrec, b, p.dhrec_col + u);
+  in.dhp = *reinterpret_cast<const float4*>(p.dh + idx);
+  in.dy = planes_get4(p.dy, b, p.dy_col + u);
+  in.dc = *reinterpret_cast<const float4*>(p.dc + idx);
+  const float* gs = p.gsave + (size_t)b * 4 * Hh + u;
+  in.i = *reinterpret_cast<const float4*>(gs); in.f = *reinterpret_cast<const float4*>(gs + Hh);
+  in.g = *reinterpret_cast<const float4*>(gs + 2 * Hh); in.o = *reinterpret_cast<const float4*>(gs + 3 * Hh);
+  in.cp = *reinterpret_cast<const float4*>(p.cprev + idx); in.cn = *reinterpret_cast<const float4*>(p.cnext + idx);
+  return in;
+}
+template <typename T>
+__device__ __forceinline__ void cell_bwd_finish(const LstmBwdPoint& p, int b, int u, int Hh, const CellBwdIn& in, const float (&dy_x)[4],
+                                                const float (&rec_x)[4]) {
+  const size_t idx = (size_t)b * Hh + u;
+  const float dh_state[4] = {in.dhp.x + (in.rec.x + rec_x[0]), in.dhp.y + (in.rec.y + rec_x[1]), in.dhp.z + (in.rec.z + rec_x[2]),
+                             in.dhp.w + (in.rec.w + rec_x[3])};
+  T* dg = (T*)p.dg + (size_t)b * p.lddg + u;
+  const float zero[4] = {0.f, 0.f, 0.f, 0.f};
+  if (!(in.mask > 0.f)) {                          // masked step: state passes through, no gate gradient
+#pragma unroll
+    for (int g = 0; g < 4; ++g) store4<T>(dg + g * Hh, zero);
+    store4<float>(p.dh + idx, dh_state);           // (an output of a masked step is the constant 0: dy is dropped)
+    return;
+  }
+  float di[4], df[4], dgg[4], dout[4], dcn[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float ig = (&in.i.x)[e], fg = (&in.f.x)[e], gg = (&in.g.x)[e], og = (&in.o.x)[e];
+    const float cp = (&in.cp.x)[e], cn = (&in.cn.x)[e];
+    const float tc = tanhf(cn);
+    const float dh = dh_state[e] + ((&in.dy.x)[e] + dy_x[e]) * drop_factor(p.drop_dy, b, p.dy_col + u + e);
+    const float dog = dh * tc;
+    const float dc = (&in.dc.x)[e] + dh * og * (1.f - tc * tc);
+    di[e] = dc * gg * ig * (1.f - ig);
+    df[e] = dc * cp * fg * (1.f - fg);
+    dgg[e] = dc * ig * (1.f - gg * gg);
+    dout[e] = dog * og * (1.f - og);
+    dcn[e] = dc * fg;
+  }
+  store4<T>(dg, di); store4<T>(dg + Hh, df); store4<T>(dg + 2 * Hh, dgg); store4<T>(dg + 3 * Hh, dout);
+  store4<float>(p.dc + idx, dcn);
+  store4<float>(p.dh + idx, zero);                 // the recurrent part arrives with the next step's GEMM
+}
+
 // one thread per (sentence, 4 consecutive units); single-wavefront workgroups, so that the 16 K threads
 // of a 64-sentence x 1024-unit step spread over all CUs
 constexpr int LSTM_BWD_POINT_THREADS = 64;
@@ -503,42 +574,8 @@ __global__ __launch_bounds__(LSTM_BWD_POINT_THREADS) void lstm_bwd_point_kernel(
   const int hq = Hh >> 2;
   if (idx4 >= Bp * hq) return;
   const int b = idx4 / hq, u = (idx4 - b * hq) * 4;
-  const size_t idx = (size_t)b * Hh + u;
-  const float4 rec = planes_get4(p.dhrec, b, p.dhrec_col + u);
-  const float4 dhp = *reinterpret_cast<const float4*>(p.dh + idx);
-  const float dh_state[4] = {dhp.x + rec.x, dhp.y + rec.y, dhp.z + rec.z, dhp.w + rec.w};
-  T* dg = (T*)p.dg + (size_t)b * p.lddg + u;
   const float zero[4] = {0.f, 0.f, 0.f, 0.f};
-  if (!(p.mask[b] > 0.f)) {                       // masked step: state passes through, no gate gradient
-#pragma unroll
-    for (int g = 0; g < 4; ++g) store4<T>(dg + g * Hh, zero);
-    store4<float>(p.dh + idx, dh_state);           // (an output of a masked step is the constant 0: dy is dropped)
-    return;
-  }
-  const float4 dy4 = planes_get4(p.dy, b, p.dy_col + u);
-  const float4 dc4 = *reinterpret_cast<const float4*>(p.dc + idx);
-  const float* gs = p.gsave + (size_t)b * 4 * Hh + u;
-  const float4 i4 = *reinterpret_cast<const float4*>(gs), f4 = *reinterpret_cast<const float4*>(gs + Hh);
-  const float4 g4 = *reinterpret_cast<const float4*>(gs + 2 * Hh), o4 = *reinterpret_cast<const float4*>(gs + 3 * Hh);
-  const float4 cp4 = *reinterpret_cast<const float4*>(p.cprev + idx), cn4 = *reinterpret_cast<const float4*>(p.cnext + idx);
-  float di[4], df[4], dgg[4], dout[4], dcn[4];
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const float ig = (&i4.x)[e], fg = (&f4.x)[e], gg = (&g4.x)[e], og = (&o4.x)[e];
-    const float cp = (&cp4.x)[e], cn = (&cn4.x)[e];
-    const float tc = tanhf(cn);
-    const float dh = dh_state[e] + (&dy4.x)[e] * drop_factor(p.drop_dy, b, p.dy_col + u + e);
-    const float dog = dh * tc;
-    const float dc = (&dc4.x)[e] + dh * og * (1.f - tc * tc);
-    di[e] = dc * gg * ig * (1.f - ig);
-    df[e] = dc * cp * fg * (1.f - fg);
-    dgg[e] = dc * ig * (1.f - gg * gg);
-    dout[e] = dog * og * (1.f - og);
-    dcn[e] = dc * fg;
-  }
-  store4<T>(dg, di); store4<T>(dg + Hh, df); store4<T>(dg + 2 * Hh, dgg); store4<T>(dg + 3 * Hh, dout);
-  store4<float>(p.dc + idx, dcn);
-  store4<float>(p.dh + idx, zero);                 // the recurrent part arrives as planes of the step GEMM
+  cell_bwd_finish<T>(p, b, u, Hh, cell_bwd_load(p, b, u, Hh), zero, zero);
 }
 
 void launch_lstm_bwd_point_multi(int prec, const LstmBwdPoint* ps, int n, int Bp, int Hh, hipStream_t st) {
@@ -551,6 +588,107 @@ void launch_lstm_bwd_point_multi(int prec, const LstmBwdPoint* ps, int n, int Bp
 }
 void launch_lstm_bwd_point(int prec, const LstmBwdPoint& p, int Bp, int Hh, hipStream_t st) {
   launch_lstm_bwd_point_multi(prec, &p, 1, Bp, Hh, st);
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward step GEMM, whole k range per workgroup, consumer fused into the epilogue
+// ------------------------------------------------------------------------------------------------
+// A workgroup owns 16 output columns x BT tiles of 16 sentences; its wavefronts split the k range and
+// meet in LDS as in the forward kernel.  After the reduction a lane holds 4 consecutive output columns
+// of one sentence — for the cell backward that is 4 consecutive hidden units, the same unit of work a
+// thread of the pointwise kernel has — so the consumer runs in registers and neither the planes nor a
+// second launch exist.  The epilogue's operands are fetched before the contraction starts.
+struct StepBwdArgs { StepBwd g[STEP_BWD_MAX_INST]; };
+
+template <typename T, int KS, int U, int BT>
+__global__ __launch_bounds__(64 * KS) void step_bwd_fused_kernel(StepBwdArgs args, int Bp, StepGrid sg) {
+  __shared__ __align__(16) float red[KS * BT * 256];
+  const StepBwd& g = args.g[blockIdx.y];
+  int x, kb, z;
+  if (!decode_block(sg, x, kb, z)) return;
+  const int N = g.part[0].ncols + g.part[1].ncols;
+  const int n0 = x * 16;
+  if (n0 >= N) return;                              // instances of one launch may differ in N
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int which = n0 >= g.part[0].ncols ? 1 : 0;
+  const BwdEpi& e = g.part[which];
+  const int c0 = n0 - (which ? g.part[0].ncols : 0);
+  const int bt0 = z * BT;
+  const int nbt = min(BT, (Bp + 15) / 16 - bt0);
+  const T* wrow[1] = {(const T*)g.Wt + (size_t)min(n0 + (lane & 15), N - 1) * g.ldw};
+  // the tile this wavefront will finish: fetch what its epilogue reads now
+  const int c = c0 + 4 * (lane >> 4);
+  const int b = 16 * (bt0 + w) + (lane & 15);
+  const bool mine = w < nbt && b < Bp && c < e.ncols;
+  const bool is_cell = e.kind == BWD_EPI_CELL_DY || e.kind == BWD_EPI_CELL_REC;
+  CellBwdIn cin;
+  float4 tce = make_float4(0.f, 0.f, 0.f, 0.f);
+  float tho[4] = {0.f, 0.f, 0.f, 0.f};
+  if (mine) {
+    if (is_cell) cin = cell_bwd_load(e.cell, b, c, e.hh);
+    else if (e.kind == BWD_EPI_TANH) {
+      const int r = e.pos ? e.pos[b] : b;
+      if (r >= 0) tce = *reinterpret_cast<const float4*>(e.dce + (size_t)r * e.hh + c);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) tho[i] = to_f<T>(((const T*)e.Ho)[(size_t)b * e.ldho + c + i]);
+    }
+  }
+  int rot = 0;
+  if (sg.krot) {
+    const int nsteps = ((g.K >> 3) + 3) >> 2;
+    rot = (int)(((long long)(blockIdx.x >> 3) * nsteps) / max(1, (int)(gridDim.x >> 3)));
+  }
+  step_contract<T, 1, KS, U, BT>(wrow, 0, 0, (const T*)g.dg, g.lddg, g.K, (const T*)nullptr, 0, 0, Bp, bt0, nbt, red, rot);
+  if (!mine) return;                                // KS >= BT: wavefront w finishes sentence tile w
+  const v4f r = step_tile_sum<1, KS, BT>(red, 0, w);
+  const float v[4] = {r[0], r[1], r[2], r[3]};
+  const float zero[4] = {0.f, 0.f, 0.f, 0.f};
+  if (e.kind == BWD_EPI_STORE) {
+    store4<float>(e.out + (size_t)b * e.ldout + c, v);
+  } else if (e.kind == BWD_EPI_CELL_DY) {
+    cell_bwd_finish<T>(e.cell, b, c, e.hh, cin, v, zero);
+  } else if (e.kind == BWD_EPI_CELL_REC) {
+    cell_bwd_finish<T>(e.cell, b, c, e.hh, cin, zero, v);
+  } else {
+    float o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = ((&tce.x)[i] + v[i]) * drop_factor(e.drop, b, c + i) * (1.f - tho[i] * tho[i]);
+    store4<T>((T*)e.dpre + (size_t)b * e.ldp + c, o);
+  }
+}
+
+template <typename T, int KS, int U, int BT>
+static void step_bwd_go(const StepBwdArgs& a, int n, int Nmax, int Bp, hipStream_t st) {
+  const int nbt = (Bp + 15) / 16;
+  StepGrid sg{(Nmax + 15) / 16, 1, (nbt + BT - 1) / BT, g_step_krot};
+  hipLaunchKernelGGL((step_bwd_fused_kernel<T, KS, U, BT>), dim3(step_grid_blocks(sg), n), dim3(64 * KS), 0, st, a, Bp, sg);
+}
+
+void launch_step_bwd_fused(int prec, const StepBwd* gs, int n, int Bp, hipStream_t st) {
+  for (int base = 0; base < n; base += STEP_BWD_MAX_INST) {
+    const int m = n - base < STEP_BWD_MAX_INST ? n - base : STEP_BWD_MAX_INST;
+    StepBwdArgs a;
+    int Nmax = 0, Kmax = 0;
+    for (int i = 0; i < STEP_BWD_MAX_INST; ++i) {
+      a.g[i] = gs[base + (i < m ? i : 0)];
+      if (i < m) {
+        Nmax = std::max(Nmax, a.g[i].part[0].ncols + a.g[i].part[1].ncols);
+        Kmax = std::max(Kmax, a.g[i].K);
+      }
+    }
+    int nsteps = (Kmax / 8 + 3) / 4;
+    static const int cfg_ks8 = getenv("CMT_BWD_KS8") ? atoi(getenv("CMT_BWD_KS8")) : 0;     // experiments
+    static const int cfg_bt4 = getenv("CMT_BWD_BT4") ? atoi(getenv("CMT_BWD_BT4")) : 0;
+    if (cfg_ks8 && nsteps > 64) nsteps = 64;
+    const bool wide = Bp > 64 || cfg_bt4;           // 64 sentences per workgroup from 65 sentences on
+#define GO(TT, KS, UU) do { if (wide) step_bwd_go<TT, KS, UU, 4>(a, m, Nmax, Bp, st); else step_bwd_go<TT, KS, UU, 2>(a, m, Nmax, Bp, st); } while (0)
+    if (prec) {
+      if (nsteps > 64) GO(bf16_t, 16, 4); else if (nsteps > 32) GO(bf16_t, 8, 4); else if (nsteps > 16) GO(bf16_t, 8, 2); else GO(bf16_t, 4, 2);
+    } else {
+      if (nsteps > 32) GO(float, 16, 2); else if (nsteps > 16) GO(float, 8, 2); else GO(float, 4, 2);
+    }
+#undef GO
+  }
 }
 
 // out[b, c] = base[b, c] + sum of planes (plain fp32 [Bp, cols])
@@ -626,11 +764,19 @@ template <typename T, int MODE>
 __global__ __launch_bounds__(256) void att_mix_kernel(const T* __restrict__ Mat, int ldm, int ldo, const float* __restrict__ dots,
                                                       const float* __restrict__ a_in, const int32_t* __restrict__ len,
                                                       int S, int Bp, int H, float* __restrict__ coef_out,
-                                                      void* __restrict__ out, Planes add, int add_col) {
+                                                      void* __restrict__ out, Planes add, int add_col, LstmBwdPoint cell,
+                                                      int fuse_cell) {
   __shared__ float sc[ATT_MAXS];
   __shared__ float part[32][65];
   const int b = blockIdx.y, t = threadIdx.x;
   const int n = min(len[b], S);
+  // MODE 1 with fuse_cell: the result is the gradient at the top decoder layer's output, and the cell
+  // backward of that layer's step runs here (lanes 0..15 take 4 consecutive units each) instead of in
+  // a launch of its own; its operands are fetched now
+  const int u4 = blockIdx.x * 64 + 4 * t;
+  const bool do_cell = MODE == 1 && fuse_cell && t < 16 && u4 < H;
+  CellBwdIn cin;
+  if (do_cell) cin = cell_bwd_load(cell, b, u4, H);
   if (t < 64) {
     if (MODE == 0) {
       float mx = -INFINITY;
@@ -676,12 +822,22 @@ __global__ __launch_bounds__(256) void att_mix_kernel(const T* __restrict__ Mat,
   __syncthreads();
   if (t < 64) {
     const int h = blockIdx.x * 64 + t;
+    float s = 0.f;
     if (h < H) {
-      float s = 0.f;
 #pragma unroll
       for (int g = 0; g < 32; ++g) s += part[g][t];
       if (MODE == 0) ((T*)out)[(size_t)b * ldo + h] = from_f<T>(s);
-      else ((float*)out)[(size_t)b * H + h] = s + planes_get(add, b, add_col + h);
+      else {
+        s += planes_get(add, b, add_col + h);
+        if (!fuse_cell) ((float*)out)[(size_t)b * H + h] = s;
+      }
+    }
+    if (MODE == 1 && fuse_cell) {
+      float dyx[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) dyx[e] = __shfl(s, 4 * (t & 15) + e, 64);
+      const float zero[4] = {0.f, 0.f, 0.f, 0.f};
+      if (do_cell) cell_bwd_finish<T>(cell, b, u4, H, cin, dyx, zero);
     }
   }
 }
@@ -692,23 +848,26 @@ void launch_att_fwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds
   const Planes none{nullptr, 0, 0, 0};
   if (prec) {
     hipLaunchKernelGGL((att_dots_kernel<bf16_t, false>), gd, dim3(256), 0, st, (const bf16_t*)Kmat, ldk, (const bf16_t*)Ht, ldt, none, nullptr, src_len, S, Bp, H, dots);
-    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 0>), gm, dim3(256), 0, st, (const bf16_t*)Hs, lds, ldcs, dots, nullptr, src_len, S, Bp, H, a, Cs, none, 0);
+    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 0>), gm, dim3(256), 0, st, (const bf16_t*)Hs, lds, ldcs, dots, nullptr, src_len, S, Bp, H, a, Cs, none, 0, LstmBwdPoint{}, 0);
   } else {
     hipLaunchKernelGGL((att_dots_kernel<float, false>), gd, dim3(256), 0, st, (const float*)Kmat, ldk, (const float*)Ht, ldt, none, nullptr, src_len, S, Bp, H, dots);
-    hipLaunchKernelGGL((att_mix_kernel<float, 0>), gm, dim3(256), 0, st, (const float*)Hs, lds, ldcs, dots, nullptr, src_len, S, Bp, H, a, Cs, none, 0);
+    hipLaunchKernelGGL((att_mix_kernel<float, 0>), gm, dim3(256), 0, st, (const float*)Hs, lds, ldcs, dots, nullptr, src_len, S, Bp, H, a, Cs, none, 0, LstmBwdPoint{}, 0);
   }
 }
 
 void launch_att_bwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds, const Planes& dCst, float* dCs_sum, const float* a,
-                    const int32_t* src_len, int S, int Bp, int H, float* dots, float* ds, float* dHt, hipStream_t st) {
+                    const int32_t* src_len, int S, int Bp, int H, float* dots, float* ds, float* dHt, hipStream_t st,
+                    const LstmBwdPoint* cell) {
+  const LstmBwdPoint cl = cell ? *cell : LstmBwdPoint{};
+  const int fuse = cell ? 1 : 0;
   // dCst planes [.., Bp, 2H]: columns [0,H) = dC_s, columns [H,2H) = the direct part of dH_t
   dim3 gd((S + 3) / 4, Bp), gm((H + 63) / 64, Bp);
   if (prec) {
     hipLaunchKernelGGL((att_dots_kernel<bf16_t, true>), gd, dim3(256), 0, st, (const bf16_t*)Hs, lds, nullptr, 0, dCst, dCs_sum, src_len, S, Bp, H, dots);
-    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 1>), gm, dim3(256), 0, st, (const bf16_t*)Kmat, ldk, 0, dots, a, src_len, S, Bp, H, ds, dHt, dCst, H);
+    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 1>), gm, dim3(256), 0, st, (const bf16_t*)Kmat, ldk, 0, dots, a, src_len, S, Bp, H, ds, dHt, dCst, H, cl, fuse);
   } else {
     hipLaunchKernelGGL((att_dots_kernel<float, true>), gd, dim3(256), 0, st, (const float*)Hs, lds, nullptr, 0, dCst, dCs_sum, src_len, S, Bp, H, dots);
-    hipLaunchKernelGGL((att_mix_kernel<float, 1>), gm, dim3(256), 0, st, (const float*)Kmat, ldk, 0, dots, a, src_len, S, Bp, H, ds, dHt, dCst, H);
+    hipLaunchKernelGGL((att_mix_kernel<float, 1>), gm, dim3(256), 0, st, (const float*)Kmat, ldk, 0, dots, a, src_len, S, Bp, H, ds, dHt, dCst, H, cl, fuse);
   }
 }
 
