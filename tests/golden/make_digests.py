@@ -1,52 +1,63 @@
-"""Writes the expected values for the full-size parity tests of the three bf16 workloads
-(medium, large, attn).  Calls only the CPU oracle (oracle/) on the seeded inputs; nothing here
-comes from the HIP path.
+"""Writes the expected values for the full-size parity tests.  Calls only the CPU oracle (oracle/) on
+the seeded inputs; nothing here comes from the HIP path.
 
-    python tests/golden/make_digests.py [medium large attn medium:0.05 large:0.05 attn::reg medium:0.05:reg
-                                          paper_512x2:0.05:reg paper_1024x4:0.05:reg]
+    python tests/golden/make_digests.py [medium::sens large::sens attn medium:0.05 large:0.05 attn::reg
+                                          medium:0.05:reg paper_512x2:0.05:reg paper_1024x4:0.05:reg]
 
-A name with ":scale" draws the same parameters at uniform[-scale, scale) instead of the workload's
-[-0.1, 0.1): at hidden size 1024 the 0.1 initialisation makes the recurrences chaotic (rounding
-the weights to bf16 alone moves the exact gradient by 15-30 %), so the bf16 path is also checked
-at the full shapes with a well-conditioned initialisation.  A third field "reg" runs the step with
-the paper's regularisation: dropout 0.2, label smoothing 0.1 (mask seed REG_SEED).
+A spec is name[:scale][:flags].  ":scale" draws the same parameters at uniform[-scale, scale) instead
+of the workload's [-0.1, 0.1): at hidden size 1024 the 0.1 initialisation makes the recurrences
+chaotic (rounding the weights to bf16 alone moves the exact gradient by 15-30 %), so the bf16 path is
+also checked at the full shapes with a well-conditioned initialisation.  Flags (comma separated):
+  reg   the step with the paper's regularisation: dropout 0.2, label smoothing 0.1 (mask seed REG_SEED);
+  sens  a second oracle run with every parameter rounded to bfloat16 (round to nearest even), from
+        which the digest also gets, per gradient tensor, the sensitivity
+        s = |g(bf16 W) - g(W)| / |g(W)| (L2 over the whole tensor), the cosine between the two, and
+        the kept entries of g(bf16 W).
 
 Per workload a compressed .npz with: the loss, the per-tensor L2 norm and max|g| of every gradient,
-a seeded sample of 4096 entries per gradient tensor (all entries of tensors up to 65536 elements),
-the embedding rows of the 16 most frequent and of 16 never-seen token ids, and per-position nll.
-Runs for a few minutes on 8 cores (the large workload needs ~20 GB of memory)."""
+the entries tests/golden/digest_index.py selects (a seeded sample of 4096 entries per tensor, all
+entries of tensors up to 65536 elements, boundary rows and one 256 x 256 block of every large
+matrix), the embedding rows of the 16 most frequent and of 16 never-seen token ids, the per-position
+nll, and the first positions of the forward intermediates (h_s at source positions 0..4; h_t, att_a,
+att_cs, h_o at target positions 0..2).
+Runs for a few minutes per workload on 8 cores (the large workload needs ~20 GB of memory)."""
 import os
 import sys
 import time
 
 import numpy as np
 
-ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(os.path.dirname(HERE))
 sys.path.insert(0, ROOT)
+sys.path.insert(0, HERE)
 
+import digest_index as DI  # noqa: E402
 from oracle import nmt_oracle as O  # noqa: E402
 from paper_1802_07170_amd import inputs as I  # noqa: E402
 
-HERE = os.path.dirname(os.path.abspath(__file__))
-SAMPLE = 4096
-SMALL = 65536
 REG = dict(dropout=0.2, label_smoothing=0.1, dropout_seed=20180207)
+PREFIX_SRC, PREFIX_TGT = 5, 3
 
 
-def sample_index(name, n):
-    """The same seeded sample positions are drawn by the test."""
-    if n <= SMALL:
-        return np.arange(n)
-    seed = int.from_bytes(name.encode(), "little") % (2 ** 31)
-    return np.sort(np.random.default_rng(seed).choice(n, size=SAMPLE, replace=False))
+def bf16_round(x):
+    """float32 -> nearest bfloat16 value (ties to even), returned as float32."""
+    u = np.ascontiguousarray(x, np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(np.shape(x))
+
+
+def digest_path(name, sc, reg):
+    return os.path.join(HERE, f"digest_{name}" + (f"_s{sc}" if sc else "") + ("_reg" if reg else "") + ".npz")
 
 
 def main():
-    names = sys.argv[1:] or ["medium", "large", "attn", "medium:0.05", "large:0.05"]
+    names = sys.argv[1:] or ["medium::sens", "large::sens", "attn", "medium:0.05", "large:0.05"]
     for spec in names:
-        name, sc, reg = (spec.split(":") + ["", ""])[:3]
+        name, sc, fl = (spec.split(":") + ["", ""])[:3]
+        flags = set(f for f in fl.split(",") if f)
         scale = float(sc) if sc else 0.1
-        kw = REG if reg == "reg" else {}
+        kw = REG if "reg" in flags else {}
         c = I.CONFIGS[name]
         cfg = I.model_cfg(c)
         params = I.make_params(cfg, c["seed"], scale)
@@ -55,11 +66,17 @@ def main():
         loss, g, it = O.train_step(cfg, params, *batch, want_intermediates=True, **kw)
         out = {"loss": np.float64(loss), "oracle_seconds": np.float64(time.time() - t0),
                "nll": it["nll"].astype(np.float32)}
+        out["prefix/h_s"] = it["h_s"][:PREFIX_SRC].astype(np.float32)
+        for key in ("h_t", "att_a", "att_cs", "h_o"):
+            out[f"prefix/{key}"] = it[key][:PREFIX_TGT].astype(np.float32)
+        del it
         for k, v in g.items():
             flat = v.reshape(-1)
             out[f"norm/{k}"] = np.float64(np.linalg.norm(flat))
             out[f"max/{k}"] = np.float64(np.abs(flat).max())
-            out[f"sample/{k}"] = flat[sample_index(k, flat.size)].astype(np.float64)
+            out[f"sample/{k}"] = flat[DI.sample_index(k, flat.size)].astype(np.float64)
+            for pn, piece in DI.pieces(v.shape).items():
+                out[f"piece/{pn}/{k}"] = DI.take(v, v.shape, piece).astype(np.float32)
         for side, ids in (("E_src", batch[0]), ("E_tgt", batch[2])):
             cnt = np.bincount(ids.reshape(-1), minlength=cfg["src_vocab"])
             top = np.argsort(-cnt)[:16]
@@ -68,9 +85,23 @@ def main():
             rows = np.concatenate([top, unseen])
             out[f"rows_idx/{side}"] = rows.astype(np.int64)
             out[f"rows/{side}"] = g[side][rows].astype(np.float64)
-        path = os.path.join(HERE, f"digest_{name}" + (f"_s{sc}" if sc else "") + ("_reg" if kw else "") + ".npz")
+        if "sens" in flags:
+            t1 = time.time()
+            loss_bf, gb, _ = O.train_step(cfg, {k: bf16_round(v) for k, v in params.items()}, *batch, **kw)
+            out["loss_bf"] = np.float64(loss_bf)
+            for k, v in g.items():
+                a, b = v.reshape(-1), gb[k].reshape(-1)
+                na, nb = np.linalg.norm(a), np.linalg.norm(b)
+                out[f"sens/{k}"] = np.float64(np.linalg.norm(b - a) / na)
+                out[f"cos_bf/{k}"] = np.float64(a @ b / (na * nb))
+                out[f"sample_bf/{k}"] = b[DI.sample_index(k, b.size)].astype(np.float64)
+            print(f"{name}: bf16-rounded parameters: loss {loss_bf:.6f}, {time.time() - t1:.1f} s; sensitivity "
+                  + ", ".join(f"{k} {float(out[f'sens/{k}']):.3f}" for k in g), flush=True)
+            del gb
+        path = digest_path(name, sc, bool(kw))
         np.savez_compressed(path, **out)
         print(f"{name}: loss {loss:.6f}, {time.time() - t0:.1f} s -> {path} ({os.path.getsize(path) / 1e6:.1f} MB)", flush=True)
+        del g, out
 
 
 if __name__ == "__main__":

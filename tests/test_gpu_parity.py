@@ -194,18 +194,11 @@ def test_batches_of_different_shape_in_turn_on_one_handle(prec):
     tr.close()
 
 
-def test_random_shapes_sweep():
-    """32 seeded random combinations of batch (1..90, around the 16- and 64-sentence tile edges), lengths,
-    hidden / embedding sizes, depth 1..4, vocabularies, precision, and regularisation on or off, each
-    against the oracle with intermediates.  Its purpose is indexing and tiling, where a mistake is an error
-    of order one.  fp32 cases: the full bar.  bf16 cases: loss and relative L2 of every gradient tensor at
-    the bar (2e-2), without the per-entry bound (on these small, strongly driven nets — parameters up to
-    0.3, dropout up to 0.5 — a handful of entries per run land just outside 2e-2 |g| + 1e-3), and with W_a
-    held to 6e-2: the softmax Jacobian a (da - sum a da) cancels heavily, and rounding the PARAMETERS to bf16
-    alone moves the oracle's exact W_a gradient by 2-10 % on such nets (measured on the CPU).  On the
-    task's configurations and in every other test the full bf16 bar applies, W_a included."""
-    rng = np.random.default_rng(1)
-    for it in range(32):
+def sweep_cases(seed, n):
+    """The random shape sweep's cases (also replayed on the CPU by tests/test_oracle_conditioning.py):
+    yields (index, cfg, params, batch, prec, reg, max_shape)."""
+    rng = np.random.default_rng(seed)
+    for it in range(n):
         B = int(rng.choice([1, 2, 3, 7, 15, 16, 17, 31, 33, 48, 63, 64, 65, 90]))
         S, T = int(rng.integers(1, 12)), int(rng.integers(1, 12))
         H = int(rng.choice([16, 32, 48, 64, 96, 128, 160, 256]))
@@ -219,11 +212,52 @@ def test_random_shapes_sweep():
         params = I.make_params(cfg, seed=it, scale=0.3 if H <= 128 else 0.1)
         batch = ragged_batch(rng, B, S, T, Vs, Vt, repeat_id=min(5, Vs - 1, Vt - 1))
         margin = (B + int(rng.integers(0, 4)), S + int(rng.integers(0, 3)), T + int(rng.integers(0, 3)))
-        relax = dict(l2_override={"W_a": 6e-2}, elementwise=False) if prec else {}
+        yield it, cfg, params, batch, prec, reg, margin
+
+
+SWEEP_SENS_C = 2.0
+# (generator seed, case) of bf16 cases whose exact W_a gradient moves by about 2e-2 or more when the
+# parameters are rounded to bf16 (found and pinned by tests/test_oracle_conditioning.py, oracle only)
+SWEEP_ILL_CONDITIONED = [(2, 44), (2, 57), (2, 71), (3, 40), (3, 92), (3, 97)]
+
+
+def oracle_sensitivity(cfg, params, batch, reg):
+    """Per gradient tensor s = |g(bf16 W) - g(W)| / |g(W)|, from two oracle runs: how far rounding the
+    parameters to bfloat16 alone moves the exact gradient."""
+    kw = dict(dropout=reg[0], label_smoothing=reg[1], dropout_seed=reg[2]) if reg else {}
+    g0 = O.train_step(cfg, params, *batch, **kw)[1]
+    g1 = O.train_step(cfg, {k: bf16_round(v) for k, v in params.items()}, *batch, **kw)[1]
+    return {k: float(np.linalg.norm(g1[k] - g0[k]) / (np.linalg.norm(g0[k]) + 1e-300)) for k in g0}
+
+
+def test_random_shapes_sweep():
+    """32 seeded random combinations of batch (1..90, around the 16- and 64-sentence tile edges), lengths,
+    hidden / embedding sizes, depth 1..4, vocabularies, precision, and regularisation on or off, each
+    against the oracle with intermediates.  Its purpose is indexing and tiling, where a mistake is an error
+    of order one.  fp32 cases: the full bar.  bf16 cases: loss at the bar; every gradient tensor's relative
+    L2 error at max(2e-2, SWEEP_SENS_C * s), where s is that tensor's sensitivity in this very case —
+    how far rounding the PARAMETERS to bf16 moves the oracle's exact gradient (two oracle runs, no HIP
+    value involved).  On these small, strongly driven nets (parameters up to 0.3, dropout up to 0.5) s
+    stays below 1e-2 for almost every tensor, so the plain bar applies; the exception is W_a, whose
+    gradient goes through the softmax Jacobian a (da - sum a da) and cancels heavily when a sentence's
+    source states resemble each other (s up to 0.1: tests/test_oracle_conditioning.py pins that on the
+    CPU, and the six worst of 200 further cases of the same generator are added to the 32 here).  The per-entry bound is dropped for bf16 cases here (a handful of entries per run land just
+    outside 2e-2 |g| + 1e-3); on the task's configurations and in every other test the full bf16 bar
+    applies to every tensor."""
+    cases = list(sweep_cases(1, 32))
+    for seed in sorted({sd for sd, _ in SWEEP_ILL_CONDITIONED}):
+        want = {i for sd, i in SWEEP_ILL_CONDITIONED if sd == seed}
+        cases += [c for c in sweep_cases(seed, max(want) + 1) if c[0] in want]
+    for it, cfg, params, batch, prec, reg, margin in cases:
+        relax = {}
+        if prec:
+            sens = oracle_sensitivity(cfg, params, batch, reg)
+            relax = dict(l2_override={k: max(2e-2, SWEEP_SENS_C * v) for k, v in sens.items()}, elementwise=False)
         try:
             loss, oloss, worst, tr = run_case(cfg, params, batch, prec, max_shape=margin, reg=reg, **relax)
         except AssertionError as e:
-            raise AssertionError(f"case {it}: B={B} S={S} T={T} H={H} E={E} L={L} Vs={Vs} Vt={Vt} prec={prec} reg={reg}: {e}")
+            raise AssertionError(f"case {it}: {cfg} B={batch[0].shape[0]} S={batch[0].shape[1]} T={batch[2].shape[1]} "
+                                 f"prec={prec} reg={reg}: {e}")
         tr.close()
 
 
