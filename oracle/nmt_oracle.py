@@ -45,9 +45,13 @@ inputs, torch.log_softmax, a torch-autograd restatement of the full model, padde
 per-sentence brute force, attention rows summing to one, loss == log V for a zero output layer;
 dropout and label smoothing: finite differences with the masks held fixed, the same torch
 restatement with masks and torch's own label-smoothed cross-entropy, SplitMix64's published first
-outputs, keep rate and values of the masks.  No function here is unpinned.
+outputs, keep rate and values of the masks; the optional operand-rounding model: identity hook ==
+plain result bit for bit, bf16_round against hand-computed values, a one-step product against the
+same product of hand-rounded inputs.  No function here is unpinned.
 """
 from __future__ import annotations
+
+import contextlib
 
 import numpy as np
 
@@ -74,6 +78,42 @@ def param_shapes(cfg):
     return out
 
 
+# ----------------------------------------------------------------------------------------------
+# optional precision model (off by default: every contraction below is exact fp64)
+# ----------------------------------------------------------------------------------------------
+# The bf16 path of the library under test stores every matrix-product operand (weights, embeddings,
+# LSTM states, attention keys, context, H_o, gate / logit gradients) as bfloat16 and accumulates in
+# fp32.  `operand_rounding(fn)` turns this oracle into the matching precision model: while it is
+# active, fn is applied to the matrix operands of every contraction (matrix product or attention
+# einsum), forward and backward; the softmax coefficients and the fp32-resident gradient vectors
+# (a, ds, dC_s), every sum and all pointwise arithmetic stay exact.  Tests use it with bf16_round to
+# ask how far ANY bf16-operand method can be from the exact gradient on a given input (the
+# conditioning of that gradient); nothing else uses it.
+_operand_fn = None
+
+
+def _op(x):
+    return x if _operand_fn is None else _operand_fn(x)
+
+
+@contextlib.contextmanager
+def operand_rounding(fn):
+    global _operand_fn
+    prev, _operand_fn = _operand_fn, fn
+    try:
+        yield
+    finally:
+        _operand_fn = prev
+
+
+def bf16_round(x):
+    """Nearest bfloat16 value (ties to even) of every element, returned as float64."""
+    x32 = np.ascontiguousarray(x, np.float32)
+    u = x32.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(x32.shape).astype(F64)
+
+
 def sigmoid(x):
     # identical to 1/(1+exp(-x)); this form cannot overflow
     return 0.5 * (1.0 + np.tanh(0.5 * x))
@@ -86,7 +126,7 @@ def cell_forward(x, h_prev, c_prev, W, b):
     """x [B,K], h_prev/c_prev [B,h], W [4h, K+h] (rows: i,f,g,o blocks; columns: [x; h]), b [4h]."""
     h = h_prev.shape[1]
     xh = np.concatenate([x, h_prev], axis=1)
-    pre = xh @ W.T + b
+    pre = _op(xh) @ _op(W).T + b
     i = sigmoid(pre[:, 0 * h:1 * h])
     f = sigmoid(pre[:, 1 * h:2 * h])
     g = np.tanh(pre[:, 2 * h:3 * h])
@@ -110,9 +150,9 @@ def cell_backward(dh_new, dc_new, cache, W):
     dg = dc * i
     dc_prev = dc * f
     dpre = np.concatenate([di * i * (1 - i), df * f * (1 - f), dg * (1 - g * g), do * o * (1 - o)], axis=1)
-    dxh = dpre @ W
+    dxh = _op(dpre) @ _op(W)
     K = xh.shape[1] - h
-    dW = dpre.T @ xh
+    dW = _op(dpre).T @ _op(xh)
     db = dpre.sum(axis=0)
     return dxh[:, :K], dxh[:, K:], dc_prev, dW, db
 
@@ -178,17 +218,17 @@ def lstm_backward(dY, dh_final, dc_final, saved, W):
 # ----------------------------------------------------------------------------------------------
 def attention_forward(Hs, src_mask, Ht, W_a, W_c):
     """Hs [S,B,H], src_mask [S,B] (1 = valid), Ht [B,H].  Returns H_o [B,H] and a cache."""
-    q = Ht @ W_a.T                                   # W_a H_t  (linearHt in the paper's listing)
-    s = np.einsum("ibh,bh->bi", Hs, q)               # F_a = H_s^T (W_a H_t), Eq. 4
+    q = _op(Ht) @ _op(W_a).T                                   # W_a H_t  (linearHt in the paper's listing)
+    s = np.einsum("ibh,bh->bi", _op(Hs), _op(q))               # F_a = H_s^T (W_a H_t), Eq. 4
     valid = src_mask.T > 0                           # [B,S]
     s = np.where(valid, s, -np.inf)
     smax = s.max(axis=1, keepdims=True)
     e = np.where(valid, np.exp(s - smax), 0.0)
     a = e / e.sum(axis=1, keepdims=True)             # Eq. 3
-    Cs = np.einsum("bi,ibh->bh", a, Hs)              # Eq. 5
+    Cs = np.einsum("bi,ibh->bh", a, _op(Hs))              # Eq. 5
     Cst = np.concatenate([Cs, Ht], axis=1)           # Eq. 6
-    Ho = np.tanh(Cst @ W_c.T)                        # Eq. 7
-    return Ho, dict(q=q, a=a, Cs=Cs, Cst=Cst, Ho=Ho, Ht=Ht)
+    Ho = np.tanh(_op(Cst) @ _op(W_c).T)                        # Eq. 7
+    return Ho, dict(q=q, s=s, a=a, Cs=Cs, Cst=Cst, Ho=Ho, Ht=Ht)
 
 
 def attention_backward(dHo, cache, Hs, W_a, W_c):
@@ -196,16 +236,16 @@ def attention_backward(dHo, cache, Hs, W_a, W_c):
     a, q, Cst, Ho, Ht = cache["a"], cache["q"], cache["Cst"], cache["Ho"], cache["Ht"]
     H = Ht.shape[1]
     dpre = dHo * (1.0 - Ho * Ho)
-    dW_c = dpre.T @ Cst
-    dCst = dpre @ W_c
+    dW_c = _op(dpre).T @ _op(Cst)
+    dCst = _op(dpre) @ _op(W_c)
     dCs, dHt = dCst[:, :H], dCst[:, H:].copy()       # the second consumer of H_t (DuplicateLayer)
-    da = np.einsum("ibh,bh->bi", Hs, dCs)
+    da = np.einsum("ibh,bh->bi", _op(Hs), dCs)
     dHs = np.einsum("bi,bh->ibh", a, dCs)
     ds = a * (da - (a * da).sum(axis=1, keepdims=True))
-    dq = np.einsum("bi,ibh->bh", ds, Hs)
+    dq = np.einsum("bi,ibh->bh", ds, _op(Hs))
     dHs += np.einsum("bi,bh->ibh", ds, q)
-    dW_a = dq.T @ Ht
-    dHt += dq @ W_a
+    dW_a = _op(dq).T @ _op(Ht)
+    dHt += _op(dq) @ _op(W_a)
     return dHt, dHs, dW_a, dW_c
 
 
@@ -215,7 +255,7 @@ def attention_backward(dHo, cache, Hs, W_a, W_c):
 def output_forward(Ho, labels, W_o, B_o, logit_tanh=False, label_smoothing=0.0):
     """Returns lse [B], the per-row loss [B] (unmasked), cache.  The row loss is the cross-entropy
     against the target distribution q = (1 - eps) onehot(label) + eps / V (eps = 0: plain nll)."""
-    u = Ho @ W_o.T + B_o
+    u = _op(Ho) @ _op(W_o).T + B_o
     z = np.tanh(u) if logit_tanh else u
     zmax = z.max(axis=1, keepdims=True)
     lse = (zmax + np.log(np.exp(z - zmax).sum(axis=1, keepdims=True)))[:, 0]
@@ -235,7 +275,7 @@ def output_backward(w, cache, W_o):
     dz *= w[:, None]
     if cache["logit_tanh"]:
         dz = dz * (1.0 - z * z)
-    return dz @ W_o, dz.T @ Ho, dz.sum(axis=0)
+    return _op(dz) @ _op(W_o), _op(dz).T @ _op(Ho), dz.sum(axis=0)
 
 
 # ----------------------------------------------------------------------------------------------
@@ -319,7 +359,7 @@ def train_step(cfg, params, src_ids, src_len, tgt_ids, tgt_len, bos_id=2, logit_
     h = [enc_fin[l][0] for l in range(L)]
     c = [enc_fin[l][1] for l in range(L)]
     Ho_prev = z_h
-    dec_caches, att_caches, out_caches = [], [], []
+    dec_caches, att_caches, out_caches, dec_states = [], [], [], []
     nll_all = np.zeros((T, B), F64)
     lse_all = np.zeros((T, B), F64)
     for j in range(T):
@@ -335,6 +375,7 @@ def train_step(cfg, params, src_ids, src_len, tgt_ids, tgt_len, bos_id=2, logit_
         lse, nll, ocache = output_forward(Ho_d, tgt_ids[:, j], p["W_o"], p["B_o"], logit_tanh, label_smoothing)
         nll_all[j], lse_all[j] = nll, lse
         dec_caches.append(step_caches)
+        dec_states.append(([hl.copy() for hl in h], [cl.copy() for cl in c]))
         att_caches.append(acache)
         out_caches.append(ocache)
         Ho_prev = Ho_d
@@ -400,7 +441,16 @@ def train_step(cfg, params, src_ids, src_len, tgt_ids, tgt_len, bos_id=2, logit_
             h_o_drop=np.stack([ac["Ho"] for ac in att_caches]) * D_ho,
             lse=lse_all, nll=nll_all * tgt_mask,
             enc_y=enc_Y, enc_final=enc_fin,
+            att_s=np.stack([ac["s"] for ac in att_caches]),          # [T,B,S] scores of Eq. 4, -inf on padding
         )
+        # per LSTM (layer, direction): state after every step (h, c) and the gate activations [i, f, g, o]
+        gates = lambda caches: np.stack([np.concatenate([ch["i"], ch["f"], ch["g"], ch["o"]], axis=1) for ch in caches])
+        for name, sv in [("enc.l0.fwd", enc_sv[0][0]), ("enc.l0.bwd", enc_sv[0][1])] + [(f"enc.l{l}", enc_sv[l]) for l in range(1, L)]:
+            inter[name + ".h"], inter[name + ".c"], inter[name + ".gates"] = sv["Hst"], sv["Cst"], gates(sv["caches"])
+        for l in range(L):
+            inter[f"dec.l{l}.h"] = np.stack([st[0][l] for st in dec_states])
+            inter[f"dec.l{l}.c"] = np.stack([st[1][l] for st in dec_states])
+            inter[f"dec.l{l}.gates"] = gates([dec_caches[j][l] for j in range(T)])
     return loss, g, inter
 
 

@@ -49,13 +49,14 @@ def test_bf16_rounding_helper_is_round_to_nearest_even():
 
 def test_w_a_gradient_is_the_ill_conditioned_one_on_the_random_sweep_nets():
     """The GPU tests' random shape sweep (tests/test_gpu_parity.py) holds bf16 cases to
-    max(2e-2, 2 s) per tensor, s = how far bf16-rounding the parameters moves the exact gradient.
-    This replays 200 cases of the sweep's generator with the oracle alone and pins what that bound
-    amounts to: W_a is the tensor that needs it (its gradient goes through the softmax Jacobian
-    a (da - sum a da), which cancels almost completely when the source states of a sentence
-    resemble each other: short sources, deep encoders): a tenth of the bf16 cases move it by more
-    than 1e-2, the worst by 1e-1, while no other tensor of any case moves by 2e-2.  The cases the GPU
-    sweep adds to its 32 (SWEEP_ILL_CONDITIONED) are the ones found here."""
+    max(2e-2, 2 s) per tensor, s = how far the oracle's exact gradient moves under its own bf16
+    precision model (parameters and contraction operands rounded to bfloat16).  This replays 200
+    cases of the sweep's generator with the oracle alone and pins what that bound amounts to: W_a is
+    the tensor that needs it (its gradient goes through the softmax Jacobian a (da - sum a da),
+    which cancels almost completely when the source states of a sentence resemble each other:
+    short sources, deep encoders): a third of the bf16 cases move it by more than 1e-2, the worst
+    by 0.16, while no other tensor of any case moves by 2e-2.  The cases the GPU sweep adds to its
+    32 (SWEEP_ILL_CONDITIONED) are the ones found here."""
     import test_gpu_parity as P
     worst_wa, over, worst_other, found = 0.0, 0, 0.0, set()
     for seed in (2, 3):
@@ -65,9 +66,9 @@ def test_w_a_gradient_is_the_ill_conditioned_one_on_the_random_sweep_nets():
             s = P.oracle_sensitivity(cfg, params, batch, reg)
             worst_wa = max(worst_wa, s["W_a"])
             over += s["W_a"] > 1e-2                  # 2 s beyond the plain bar
-            if s["W_a"] > 1.8e-2:
+            if s["W_a"] > 2e-2:
                 found.add((seed, it))
             worst_other = max(worst_other, max(v for k, v in s.items() if k != "W_a"))
-    assert over >= 10 and 5e-2 < worst_wa < 0.2, (over, worst_wa)
+    assert over >= 25 and 0.1 < worst_wa < 0.3, (over, worst_wa)
     assert worst_other < 2e-2, worst_other
     assert found == set(P.SWEEP_ILL_CONDITIONED), found

@@ -24,16 +24,16 @@ MUTATIONS = [
      "g = np.tanh(pre[:, 2 * h:3 * h])\n    o = sigmoid(pre[:, 3 * h:4 * h])",
      "g = np.tanh(pre[:, 3 * h:4 * h])\n    o = sigmoid(pre[:, 2 * h:3 * h])"),
     ("cell: weight columns taken as [h; x]", "xh = np.concatenate([x, h_prev], axis=1)", "xh = np.concatenate([h_prev, x], axis=1)"),
-    ("cell: bias dropped", "pre = xh @ W.T + b", "pre = xh @ W.T"),
+    ("cell: bias dropped", "pre = _op(xh) @ _op(W).T + b", "pre = _op(xh) @ _op(W).T"),
     ("mask: padded step emits its state", "y = m * h_new", "y = h"),
     ("mask: padded step updates the state", "h = m * h_new + (1 - m) * h_prev", "h = h_new"),
     ("mask: padded step updates the cell", "c = m * c_new + (1 - m) * c_prev", "c = c_new"),
     ("encoder: reverse direction runs forwards", "order = range(T - 1, -1, -1) if reverse else range(T)", "order = range(T)"),
-    ("attention: W_a transposed", "q = Ht @ W_a.T", "q = Ht @ W_a"),
+    ("attention: W_a transposed", "q = _op(Ht) @ _op(W_a).T", "q = _op(Ht) @ _op(W_a)"),
     ("attention: padding takes part in the softmax", "valid = src_mask.T > 0  ", "valid = src_mask.T > -1 "),
     ("attention: [H_t; C_s] instead of [C_s; H_t]", "Cst = np.concatenate([Cs, Ht], axis=1)", "Cst = np.concatenate([Ht, Cs], axis=1)"),
-    ("attention: tanh of Eq. 7 dropped", "Ho = np.tanh(Cst @ W_c.T)", "Ho = Cst @ W_c.T"),
-    ("output: bias dropped", "u = Ho @ W_o.T + B_o", "u = Ho @ W_o.T"),
+    ("attention: tanh of Eq. 7 dropped", "Ho = np.tanh(_op(Cst) @ _op(W_c).T)", "Ho = _op(Cst) @ _op(W_c).T"),
+    ("output: bias dropped", "u = _op(Ho) @ _op(W_o).T + B_o", "u = _op(Ho) @ _op(W_o).T"),
     ("output: smoothing term dropped", "row = (1.0 - eps) * nll + eps * (lse - z.mean(axis=1))", "row = (1.0 - eps) * nll"),
     ("step: decoder input not shifted",
      "dec_in = np.concatenate([np.full((B, 1), bos_id, tgt_ids.dtype), tgt_ids[:, :T - 1]], axis=1)", "dec_in = tgt_ids"),
@@ -44,11 +44,11 @@ MUTATIONS = [
     ("backward: cell-state path dropped", "dc = dc_new + dh_new * o * (1.0 - tc * tc)", "dc = dh_new * o * (1.0 - tc * tc)"),
     ("backward: forget gate sees the new cell", "df = dc * c_prev", "df = dc * c_new"),
     ("backward: bias gradient averaged", "db = dpre.sum(axis=0)", "db = dpre.mean(axis=0)"),
-    ("backward: weight gradient transposed operand", "dW = dpre.T @ xh", "dW = (xh.T @ dpre).T * 1.0 if False else dpre.T @ xh[:, ::-1]"),
+    ("backward: weight gradient transposed operand", "dW = _op(dpre).T @ _op(xh)", "dW = _op(dpre).T @ _op(xh)[:, ::-1]"),
     ("backward: masked step drops the state gradient", "dh_prev = dh_prev + (1 - m) * dh_state", "dh_prev = dh_prev + 0.0"),
     ("backward: softmax Jacobian without the mean term", "ds = a * (da - (a * da).sum(axis=1, keepdims=True))", "ds = a * da"),
     ("backward: H_s gradient through the scores dropped", 'dHs += np.einsum("bi,bh->ibh", ds, q)', "dHs += 0.0"),
-    ("backward: W_a transposed in dH_t", "dHt += dq @ W_a", "dHt += dq @ W_a.T"),
+    ("backward: W_a transposed in dH_t", "dHt += _op(dq) @ _op(W_a)", "dHt += _op(dq) @ _op(W_a).T"),
     ("backward: second consumer of H_t forgotten", "dCs, dHt = dCst[:, :H], dCst[:, H:].copy()", "dCs, dHt = dCst[:, :H], 0.0 * dCst[:, H:]"),
     ("backward: smoothed target taken as one-hot", "dz[np.arange(z.shape[0]), labels] -= 1.0 - eps", "dz[np.arange(z.shape[0]), labels] -= 1.0"),
     ("backward: input-feed gradient dropped", "dHo = (dHo + dHo_feed) * D_ho[j]", "dHo = dHo * D_ho[j]"),

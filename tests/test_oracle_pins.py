@@ -589,3 +589,36 @@ def test_param_tables_agree():
     for c in I.CONFIGS.values():
         cfg = I.model_cfg(c)
         assert O.param_shapes(cfg) == I.param_table(cfg)
+
+
+def test_operand_rounding_model_is_off_by_default_and_rounds_only_contraction_operands():
+    """The optional precision model of the oracle: (a) without it, and with an identity hook, the step
+    is the plain step bit for bit; (b) bf16_round gives the nearest bfloat16 value, ties to even, on
+    hand-computed cases; (c) under operand_rounding(bf16_round) one cell step equals the plain cell step
+    of hand-rounded inputs and weights (the bias and the pointwise arithmetic stay exact), and the whole
+    step moves the gradient of a small well-conditioned net by a bf16-sized amount, not more."""
+    cfg = dict(src_vocab=11, tgt_vocab=13, emb=3, hidden=4, layers=2)
+    rng = np.random.default_rng(5)
+    params = {k: rng.uniform(-0.3, 0.3, size=shp) for k, shp in O.param_shapes(cfg)}
+    batch = (rng.integers(4, 11, size=(3, 4)), np.array([4, 2, 3]), rng.integers(4, 13, size=(3, 5)), np.array([5, 3, 1]))
+    loss0, g0, _ = O.train_step(cfg, params, *batch)
+    with O.operand_rounding(lambda x: x):
+        loss1, g1, _ = O.train_step(cfg, params, *batch)
+    assert loss1 == loss0 and all(np.array_equal(g0[k], g1[k]) for k in g0)
+    x = np.array([1.0, 1.00390625, 1.0078125 + 2.0 ** -8, -3.1415927, 0.1], np.float64)
+    r = O.bf16_round(x)
+    assert r.dtype == np.float64 and r[0] == 1.0 and r[1] == 1.0 and r[2] == 1.015625
+    assert r[3] == -3.140625 and r[4] == 0.10009765625          # 0x4049 and 0x3DCD as bfloat16
+    xs, hp, cp = rng.normal(size=(2, 3)), rng.normal(size=(2, 4)), rng.normal(size=(2, 4))
+    W, b = rng.normal(size=(16, 7)), rng.normal(size=16)
+    with O.operand_rounding(O.bf16_round):
+        h_r, c_r, _ = O.cell_forward(xs, hp, cp, W, b)
+        loss2, g2, _ = O.train_step(cfg, params, *batch)
+    h_m, c_m, _ = O.cell_forward(O.bf16_round(xs), O.bf16_round(hp), cp, O.bf16_round(W), b)
+    assert np.array_equal(h_r, h_m) and np.array_equal(c_r, c_m)
+    assert loss2 != loss0 and abs(loss2 - loss0) < 1e-2 * loss0
+    for k in g0:
+        rel = np.linalg.norm(g2[k] - g0[k]) / np.linalg.norm(g0[k])
+        assert 0 < rel < 3e-2, (k, rel)
+    loss3, g3, _ = O.train_step(cfg, params, *batch)              # the hook is gone again
+    assert loss3 == loss0 and all(np.array_equal(g0[k], g3[k]) for k in g0)
