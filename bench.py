@@ -24,8 +24,18 @@ from paper_1802_07170_amd import inputs as I  # noqa: E402
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the timed kernel from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE),
 # scaled by what the same counters read for a plain 256 MiB copy (x2 and x1): the summary under
-# profiles/ gives the commands and the figures.  Known only for the workload it was measured on.
-MEASURED_TRAFFIC_BYTES = {"medium": 21700608}
+# profiles/ gives the commands and the figures.  Valid for the workload and the kernel source it was
+# measured with: (workload, first 12 hex digits of the sha256 of csrc/step.hip + csrc/common.h) -> bytes;
+# with another source the figure is stale and reported as null.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def step_kernel_source_tag():
+    import hashlib
+    h = hashlib.sha256()
+    for f in ("step.hip", "common.h"):
+        h.update(open(os.path.join(ROOT, "paper_1802_07170_amd", "csrc", f), "rb").read())
+    return h.hexdigest()[:12]
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # the paper's training-speed table, its own system, source tokens/s on its Quadro M4000 (context only)
 PAPER_SPEED_TABLE = {"paper_512x2": 4725, "paper_512x4": 3751, "paper_1024x2": 2571, "paper_1024x4": 1906}
@@ -58,7 +68,11 @@ def cpu_baseline(c, cfg, params, batch, budget_sentences):
         O.train_step(cfg, params, *sub)
         steps += 1
     dt = time.time() - t0
-    cores = int(os.environ["OMP_NUM_THREADS"]) if os.environ.get("OMP_NUM_THREADS") else int(os.cpu_count())
+    try:                                             # the thread count numpy's BLAS actually runs with
+        from threadpoolctl import threadpool_info
+        cores = max([int(p.get("num_threads", 1)) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
+    except Exception:
+        cores = int(os.environ["OMP_NUM_THREADS"]) if os.environ.get("OMP_NUM_THREADS") else int(os.cpu_count())
     return dict(value=float(steps * tl[:n].sum() / dt), unit="tokens/s", cores=cores, kind="oracle",
                 sample=f"first {n} sentences of the batch ({int(tl[:n].sum())} target tokens), {steps} step(s), {dt:.1f} s")
 
@@ -73,6 +87,7 @@ def main():
     ap.add_argument("--cpu-sentences", type=int, default=64)
     ap.add_argument("--no-paper-shapes", action="store_true",
                     help="skip the four networks of the paper's training-speed table")
+    ap.add_argument("--no-per-workload", action="store_true", help="skip the timing of the other four workloads")
     ap.add_argument("--no-beam", action="store_true", help="skip the beam-search timing (it allocates a second, larger workspace)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run three plain 256 MiB device copies (the known-size kernel that the "
@@ -101,11 +116,18 @@ def main():
     for _ in range(args.warmup):
         tr.train_step_async(dev)
     torch.cuda.synchronize()
+    # exactly `steps` steps between two synchronisations (the headline figure), each also bracketed by HIP
+    # events on the stream the library works on (torch's current stream; the library's second stream joins
+    # it before a step ends)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    ev[0].record()
+    for i in range(args.steps):
         tr.train_step_async(dev)
+        ev[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    step_ms = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps))
     loss = tr.fetch_loss()
     ms = dt / args.steps * 1e3
     flops = gemm_flops_per_step(cfg, B, S, T)
@@ -120,6 +142,8 @@ def main():
         "source_tokens_per_s": n_src / (dt / args.steps),
         "gemm_tflops_padded": flops / (dt / args.steps) / 1e12,
         "mfma_peak_frac_whole_step": flops / (dt / args.steps) / 1e12 / (MFMA_BF16_PEAK_TFLOPS if c["precision"] else MFMA_FP32_PEAK_TFLOPS),
+        "ms_per_step_event_median": step_ms[len(step_ms) // 2], "ms_per_step_event_min": step_ms[0],
+        "ms_per_step_event_max": step_ms[-1],
     }
     # the same step with the paper's regularisation (hyperparameter table: dropout 0.2, label
     # smoothing 0.1), a new mask seed per step; reported beside the headline figure, not as it
@@ -143,7 +167,8 @@ def main():
     achieved = nbytes / (us * 1e-6) / 1e9
     out["roofline"] = {"kernel": "lstm_fwd_kernel (decoder layer step: gate GEMM + fused cell)", "bound": "hbm",
                        "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                       "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "us_per_launch": us, "algorithmic_bytes_per_launch": nbytes}
+                       "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, step_kernel_source_tag())), "us_per_launch": us,
+                       "algorithmic_bytes_per_launch": nbytes, "kernel_source_tag": step_kernel_source_tag()}
     # forward-only greedy translation of the same source batch (not part of the headline metric)
     max_len = T
     tr.greedy_decode(src, sl, max_len)
@@ -169,8 +194,8 @@ def main():
     # the other kernel classes of the step, each replayed alone (no second stream active)
     peak_mfma = MFMA_BF16_PEAK_TFLOPS if c["precision"] else MFMA_FP32_PEAK_TFLOPS
     kernels = {}
-    for name, kind, iters in [("step2d_bwd_dec", "hbm", 400), ("att_fwd", "hbm", 400), ("gemm_gx", "mfma", 50),
-                              ("gemm_dw", "mfma", 50), ("ce_fwd", "mfma", 20)]:
+    for name, kind, iters in [("step_bwd_fused_dec", "hbm", 400), ("step2d_bwd_dec", "hbm", 400), ("att_fwd", "hbm", 400),
+                              ("gemm_gx", "mfma", 50), ("gemm_dw", "mfma", 50), ("ce_fwd", "mfma", 20)]:
         kus, work = tr.time_kernel(name, iters)
         if kind == "hbm":
             a = work / (kus * 1e-6) / 1e9
@@ -181,6 +206,12 @@ def main():
             kernels[name] = {"bound": "mfma", "us_per_launch": kus, "achieved": a, "unit": "TFLOP/s", "peak": peak_mfma,
                              "frac": a / peak_mfma}
     out["other_kernels"] = kernels
+    if c["precision"]:
+        # what the matrix cores reach with nothing but bf16 MFMA instructions in flight, beside the nominal peak
+        kus, work = tr.time_kernel("mfma_rate", 5)
+        out["mfma_rate_measured_tflops"] = work / (kus * 1e-6) / 1e12
+        out["mfma_peak_nominal_tflops"] = MFMA_BF16_PEAK_TFLOPS
+        out["gemm_kernels_mfma_frac"] = {k: kernels[k]["frac"] for k in ("gemm_gx", "gemm_dw", "ce_fwd")}
     # SGD update of all parameters incl. the refresh of the kernels' working copies (not part of a step)
     tr.sgd_update(0.0)
     torch.cuda.synchronize()
@@ -219,6 +250,38 @@ def main():
                             "paper_source_tokens_per_s_quadro_m4000": PAPER_SPEED_TABLE[name]}
             tp.close()
         out["paper_speed_table_shapes"] = shapes
+    # the other four workloads of the benchmark spec, each timed the same way (median of event-timed steps); the parity
+    # tests check them against the oracle, here they give the per-workload figures
+    if not args.no_per_workload:
+        per = {args.workload: {"ms_per_step": out["ms_per_step_event_median"], "target_tokens_per_s": n_tok / (out["ms_per_step_event_median"] * 1e-3),
+                               "gemm_tflops_padded": flops / (out["ms_per_step_event_median"] * 1e-3) / 1e12}}
+        for name in ("tiny", "small", "medium", "large", "attn"):
+            if name in per:
+                continue
+            wc = I.CONFIGS[name]
+            wcfg = I.model_cfg(wc)
+            wb = I.make_batch(wc)
+            wB, wS, wT = wb[0].shape[0], wb[0].shape[1], wb[2].shape[1]
+            tw = binding.Trainer(wcfg, wB, wS, wT, precision=wc["precision"])
+            tw.init_params(wc["seed"], 0.1)
+            wdev = tw.upload_batch(*wb)
+            nst = 10
+            for _ in range(2):
+                tw.train_step_async(wdev)
+            torch.cuda.synchronize()
+            wev = [torch.cuda.Event(enable_timing=True) for _ in range(nst + 1)]
+            wev[0].record()
+            for i in range(nst):
+                tw.train_step_async(wdev)
+                wev[i + 1].record()
+            torch.cuda.synchronize()
+            wms = sorted(wev[i].elapsed_time(wev[i + 1]) for i in range(nst))[nst // 2]
+            tw.fetch_loss()
+            wfl = gemm_flops_per_step(wcfg, wB, wS, wT)
+            per[name] = {"ms_per_step": wms, "target_tokens_per_s": float(wb[3].sum() / (wms * 1e-3)),
+                         "gemm_tflops_padded": wfl / (wms * 1e-3) / 1e12, "dtype": "bf16" if wc["precision"] else "f32"}
+            tw.close()
+        out["per_workload"] = per
     if args.calibration_copy:
         a = torch.zeros(64 << 20, dtype=torch.float32, device="cuda")
         b = torch.empty_like(a)

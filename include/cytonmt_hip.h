@@ -98,8 +98,11 @@ int cmt_get_params(cmt_handle* h, float* host_dst);
 int cmt_train_step(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* src_len_dev,
                    const int32_t* tgt_ids_dev, const int32_t* tgt_len_dev,
                    int32_t B, int32_t S, int32_t T, float* loss_host);
-/* Same work, but only enqueues it: no synchronisation, no error-flag or loss read-back.  The loss
- * and flag of the last enqueued step are fetched (with a synchronisation) by cmt_fetch_loss. */
+/* Same work, but only enqueues it: no synchronisation, no error-flag or loss read-back.  The loss of
+ * the last enqueued step is fetched (with a synchronisation) by cmt_fetch_loss.  The error flags are
+ * sticky: cmt_fetch_loss reports CMT_ERANGE / CMT_ENONFINITE if ANY step enqueued since the previous
+ * read-back raised one, and clears them; until then cmt_sgd_update applies nothing (the gradients of
+ * a failed step are undefined), so parameters stay as they were before the failed step. */
 int cmt_train_step_async(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* src_len_dev,
                          const int32_t* tgt_ids_dev, const int32_t* tgt_len_dev,
                          int32_t B, int32_t S, int32_t T);
@@ -183,13 +186,19 @@ int cmt_beam_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* sr
                     int32_t* out_len_dev, float* out_score_dev);
 
 /* Plain SGD (hyperparameter table: optimizer SGD, learning rate 1.0): p <- p - lr * g on the flat
- * fp32 master vector, then refreshes the kernels' working copies (bf16 casts, transposes). */
+ * fp32 master vector, then refreshes the kernels' working copies (bf16 casts, transposes).  The
+ * update is skipped on the device while an error flag of an earlier step is pending (see
+ * cmt_train_step_async). */
 int cmt_sgd_update(cmt_handle* h, float lr);
 
 /* Copies a named intermediate of the last step to host memory as fp32, for per-kernel parity
  * tests.  Names: "x_src" [S,Bp,E], "x_tgt" [T,Bp,E], "mask_src" [S,Bp], "mask_tgt" [T,Bp],
  * "h_s" [S,Bp,H], "h_t" [T,Bp,H], "att_a" [T,Bp,S], "att_cs" [T,Bp,H], "h_o" [T,Bp,H] (before
- * dropout), "h_o_drop" [T,Bp,H] (after), "lse" [T,Bp], "nll" [T,Bp] (the per-token loss); Bp = B rounded up to a multiple of 16 (extra rows are padding).
+ * dropout), "h_o_drop" [T,Bp,H] (after), "lse" [T,Bp], "nll" [T,Bp] (the per-token loss), "att_s" [T,Bp,S]
+ * (the scores F_a of Eq. 4 before the softmax; training step only), and per LSTM "enc.l0.fwd", "enc.l0.bwd"
+ * (width H/2), "enc.l<k>" (k >= 1), "dec.l<k>": "<lstm>.h" and "<lstm>.c" [len,Bp,width] (the state after every
+ * step, a padded step carrying the previous state) and "<lstm>.gates" [len,Bp,4 width] (gate activations
+ * i, f, g, o of every step), len = S or T; Bp = B rounded up to a multiple of 16 (extra rows are padding).
  * bytes must equal the tensor's size; values at masked positions are unspecified except for
  * the masks, "att_a" (exactly 0 on padded source positions) and "nll" (0 on padded targets). */
 int cmt_debug_fetch(cmt_handle* h, const char* name, float* host_dst, size_t bytes);
@@ -207,7 +216,12 @@ int cmt_padded_batch(const cmt_handle* h);
  *   "gemm_gx"        time-batched input-side GEMM [T Bp, E] x [E, 4H]                      flops
  *   "gemm_dw"        time-batched weight-gradient GEMM [4H, T Bp] x [T Bp, H]              flops
  *   "ce_fwd"         vocabulary projection + log-sum-exp partials of the first slab of rows flops
- * Synchronises the stream. */
+ *   "step_bwd_fused_dec" the same product as step2d_bwd_dec in the form the decoder's backward loop runs:
+ *                    whole contraction per workgroup, cell backward of the layer below in the epilogue bytes
+ *   "mfma_rate"      matrix-core instructions alone (bf16 32x32x16 on registers): the rate the chip's
+ *                    matrix cores reach, to be read beside the nominal peak                 flops
+ * The replays of the backward kernels leave the in-place state gradients of the last step in whatever
+ * state they reach; the next step re-initialises them.  Synchronises the stream. */
 int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_launch, double* algo_work);
 
 const char* cmt_last_error(const cmt_handle* h);

@@ -102,6 +102,7 @@ struct cmt_handle {
   char* Xt = nullptr; float* mask_t = nullptr; int32_t* tok_t = nullptr; int32_t* labels = nullptr; int32_t* len_t = nullptr;
   char* HoBuf = nullptr; char* HoBufT = nullptr; char* Cs = nullptr; char* CsT = nullptr;
   float* att_a = nullptr; float* att_ds = nullptr; float* dCs = nullptr; float* dots = nullptr;
+  float* att_s = nullptr;               // [Tmax, Bp, Smax] attention scores of every step of the last training step
   char* dPre = nullptr; char* dPreT = nullptr;
   float* dHoCE = nullptr;
   float* dHt = nullptr; float* wcp = nullptr;
@@ -119,9 +120,11 @@ struct cmt_handle {
   char* dzs2 = nullptr; char* dzTs2 = nullptr; float* gsplit2 = nullptr;
   int kb_bwd = 0, kb_wc = 0;            // caps on the k blocks of the backward step GEMMs (0 = default)
   // backward loops that use the whole-k step GEMM with the consumer in its epilogue (env CMT_BWD_FUSED, a bit
-  // mask): 1 = decoder, 2 = upper encoder layers, 4 = bottom encoder layer.  The upper encoder layers keep the
-  // k-split GEMM + pointwise pair: their launches carry up to L - 1 layer-steps, and three rounds of
-  // 1024-thread workgroups per CU take longer (45 us per diagonal) than the pair (34 us).
+  // mask): 1 = decoder (up to 64 sentences; at 128 every workgroup's re-read of the step's dgates makes it
+  // slower than the k-split GEMM + pointwise pair: 9.5 against 8.7 ms for the large workload's backward loop),
+  // 2 = upper encoder layers, 4 = bottom encoder layer.  The upper encoder layers keep the pair: their launches
+  // carry up to L - 1 layer-steps, and three rounds of 1024-thread workgroups per CU take longer (45 us per
+  // diagonal) than the pair (34 us).
   int bwd_fused = 5;
   // phase timing of a step on the caller's stream (measurement aid, env CMT_PHASE_TIMING=1)
   int phase_timing = 0;
@@ -266,6 +269,7 @@ size_t layout(cmt_handle* h, char* base) {
   h->att_a = (float*)a.take(Mt * Sm * 4); h->att_ds = (float*)a.take(Mt * Sm * 4);
   h->dCs = (float*)a.take(Mt * H * 4);
   h->dots = (float*)a.take((size_t)Bp * Sm * 4);
+  h->att_s = (float*)a.take(Mt * Sm * 4);
   h->dPre = a.take(Mt * PH * esz); h->dPreT = a.take(Mt * H * esz);
   h->dHoCE = (float*)a.take(Mt * H * 4);
   h->dHt = (float*)a.take((size_t)Bp * H * 4);
@@ -600,9 +604,9 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
 
   h->phase_n = 0;
   phase_mark(h, "gathers + encoder bottom layer");
-  {   // error flags, H_o^{<-1>} = 0, and the decoder's state gradients at the end of time = 0: one launch
+  {   // H_o^{<-1>} = 0, and the decoder's state gradients at the end of time = 0: one launch.  (The error flags
+      // are not cleared here: they accumulate over the steps enqueued since the last read-back.)
     std::vector<FillJob> z;
-    add_fill(z, h->flags, 1, 4);
     add_fill(z, h->HoBuf, BP, esz);
     if (drop) add_fill(z, h->HoDrop, BP, esz);
     for (int l = 0; l < L; ++l) { add_fill(z, h->dec[l].dh, BH, 4); add_fill(z, h->dec[l].dc, BH, 4); }
@@ -628,8 +632,8 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     for (int j = 0; j < T; ++j) {
       for (int l = 0; l < L; ++l) dec_lstm_fwd(h, l, j);
       const char* Ht = h->dec[L - 1].Hst + (j + 1) * BP * esz;
-      launch_att_fwd(p, h->Kmat, H, Hs, ldHs, Ht, PH, h->len_s, S, Bp, H, h->dots, h->att_a + (size_t)j * Bp * S,
-                     h->Cs + j * BP * esz, PH, st);
+      launch_att_fwd(p, h->Kmat, H, Hs, ldHs, Ht, PH, h->len_s, S, Bp, H, h->att_s + (size_t)j * Bp * S,
+                     h->att_a + (size_t)j * Bp * S, h->Cs + j * BP * esz, PH, st);
       StepGemm g{};
       g.a0 = h->Cs + j * BP * esz; g.lda0 = PH; g.K0 = H; g.w0_off = 0;
       g.a1 = Ht; g.lda1 = PH; g.K1 = H; g.w1_off = H;
@@ -738,7 +742,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   const int kbd = step_kblocks(p, 2 * H, 4 * H, Bp, h->kb_bwd);       // planes written by a decoder layer's backward GEMM
   const size_t pstr = (size_t)Bp * 2 * H;
   const Planes no_planes{nullptr, 0, 0, 0};
-  if (h->bwd_fused & 1) {
+  if ((h->bwd_fused & 1) && Bp <= 64) {
     // one launch per layer and step (dec_bwd_gemm): no pointwise launches, no planes
     for (int j = T - 1; j >= 0; --j) {
       char* dpre = h->dPre + j * BP * esz;
@@ -1093,6 +1097,7 @@ int cmt_create(const cmt_config* cfg, void* params_dev, void* grads_dev, void* w
     if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) { cmt_destroy(h); return CMT_EHIP; }
   h->h_flags = (int*)(h->h_loss + 8);
   h->h_loss[0] = 0.f; h->h_loss[1] = 0.f; *h->h_flags = 0;
+  launch_fill_f32((float*)h->flags, 1, 0.f, h->st);  // the workspace may hold anything
   *out = h;
   return CMT_OK;
 }
@@ -1251,6 +1256,10 @@ int cmt_fetch_loss(cmt_handle* h, float* loss_host) {
   }
   const int flags = *h->h_flags;
   if (loss_host) *loss_host = h->h_loss[0];
+  if (flags) {                                       // reported once: clear the device word for the steps to come
+    *h->h_flags = 0;
+    launch_fill_f32((float*)h->flags, 1, 0.f, h->st);
+  }
   if (flags & 3) return fail(h, CMT_ERANGE, (flags & 1) ? "a token id is outside its vocabulary" : "a length is outside [1, padded length]");
   if (flags & 4) return fail(h, CMT_ENONFINITE, "the loss is not finite");
   return CMT_OK;
@@ -1422,7 +1431,7 @@ int cmt_beam_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* sr
 int cmt_sgd_update(cmt_handle* h, float lr) {
   if (!h) return CMT_EINVAL;
   if (!isfinite(lr)) return fail(h, CMT_EINVAL, "learning rate is not finite");
-  launch_sgd(h->params, h->grads, h->nparams, lr, h->st);
+  launch_sgd(h->params, h->grads, h->nparams, lr, h->flags, h->st);
   refresh_params(h);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(h, e, "cmt_sgd_update");
@@ -1459,7 +1468,7 @@ int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_la
     const int K = 2 * H;                                // per-step contraction (layer 0: [feed; h], others: [x; h])
     *algo_work = 4.0 * H * K * esz                      // weights, read once
                + (double)Bp * K * esz                   // [x; h_prev]
-               + (double)Bp * 4 * H * 4                 // bias / pre-batched input part
+               + (double)4 * H * 4                      // bias (the layers timed here have no pre-batched input part)
                + (double)Bp * H * 4                     // c_prev
                + (double)Bp * H * (esz + 4)             // h, c out
                + (double)Bp * 4 * H * 4;                // gate activations kept for backward
@@ -1522,6 +1531,12 @@ int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_la
       launch_ce_fwd(p, Ho, PH, h->Pw(h->off_Wo), h->params + h->off_Bo, h->labels, Mc, V, H, h->dzTs2, h->pmax, h->psum, nullptr,
                     h->zy, st);
     };
+  } else if (s == "mfma_rate") {
+    // matrix cores alone: 4096 workgroups x 4 wavefronts x 2048 x 4 bf16 32x32x16 MFMAs on registers  (flops)
+    const int blocks = 4096, it = 2048;
+    if ((size_t)blocks * 256 > h->gsplit_floats) return fail(h, CMT_EINVAL, "workspace too small for the probe");
+    *algo_work = (double)blocks * 4 * it * 4.0 * (2.0 * 32 * 32 * 16);
+    launch = [=](int) { (void)launch_mfma_rate(h->gsplit, blocks, it, st); };
   } else {
     return fail(h, CMT_EINVAL, "unknown kernel name");
   }
@@ -1561,6 +1576,29 @@ int cmt_debug_fetch(cmt_handle* h, const char* name, float* host_dst, size_t byt
   }
   else if (s == "h_t") { src = h->dec[L - 1].Hst + BP * h->esz; rows = T * Bp; cols = H; pitch = h->PH; isT = true; }
   else if (s == "att_a") { src = h->att_a; rows = 1; cols = pitch = T * Bp * S; }
+  else if (s == "att_s") { src = h->att_s; rows = 1; cols = pitch = T * Bp * S; }
+  else if ((s.rfind("enc.l", 0) == 0 || s.rfind("dec.l", 0) == 0) && s.size() >= 8) {
+    // "<enc|dec>.l<k>[.fwd|.bwd].<h|c|gates>": states after every step and gate activations of one LSTM
+    const bool enc = s[0] == 'e';
+    size_t pos = 5;
+    int l = 0;
+    while (pos < s.size() && s[pos] >= '0' && s[pos] <= '9') l = l * 10 + (s[pos++] - '0');
+    int dir = -1;
+    if (s.compare(pos, 5, ".fwd.") == 0) { dir = 0; pos += 4; }
+    else if (s.compare(pos, 5, ".bwd.") == 0) { dir = 1; pos += 4; }
+    const std::string what = pos < s.size() ? s.substr(pos + 1) : "";
+    if (l >= L || (what != "h" && what != "c" && what != "gates") || (dir >= 0) != (enc && l == 0))
+      return fail(h, CMT_EINVAL, "unknown intermediate name");
+    const LD& d = enc ? h->enc[l == 0 ? dir : l + 1] : h->dec[l];
+    const size_t steps = enc ? S : T;
+    // slot 0 of Hst / Cst holds the initial state (the reverse direction: slot S), slot t + 1 (reverse: t)
+    // the state after the step at position t
+    const size_t first = (enc && l == 0 && dir == 1) ? 0 : 1;
+    rows = steps * Bp;
+    if (what == "h") { src = d.Hst + first * Bp * d.ph * h->esz; cols = d.Hh; pitch = d.ph; isT = true; }
+    else if (what == "c") { src = d.Cst + first * Bp * d.Hh; cols = pitch = d.Hh; }
+    else { src = d.Gs; cols = pitch = 4 * (size_t)d.Hh; }
+  }
   else if (s == "att_cs") { src = h->Cs; rows = T * Bp; cols = H; pitch = h->PH; isT = true; }
   else if (s == "h_o") { src = h->HoBuf + BP * h->esz; rows = T * Bp; cols = H; pitch = h->PH; isT = true; }
   else if (s == "h_o_drop") {

@@ -30,7 +30,7 @@ __global__ __launch_bounds__(CeG::NT) void ce_fwd_kernel(const T* __restrict__ H
                                                          int M, int V, int H, T* __restrict__ ET, int ldet,
                                                          float* __restrict__ pmax, float* __restrict__ psum,
                                                          float* __restrict__ psz, float* __restrict__ zy, int np, RowLimit lim) {
-  __shared__ __align__(16) char smem[CeG::SMEM_BYTES];
+  __shared__ __align__(16) char smem[CeG::SMEM_BYTES + 1024];   // main-loop stages; afterwards 1 KB of bias + the staged e tile
   if (lim.n) M = min(M, max(*lim.n - lim.base, 0));       // rows that exist (uniform over the grid)
   if (M <= 0) return;
   int v0, r0;                                             // tile: vocabulary rows v0.., target positions r0..
@@ -43,6 +43,13 @@ __global__ __launch_bounds__(CeG::NT) void ce_fwd_kernel(const T* __restrict__ H
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int wm = w >> 2, wn = w & 3;
   const int pidx = (v0 >> 6) + wm;                        // this wavefront's group of 64 vocabulary entries
+  // e leaves through LDS: every wavefront stages its 64 vocabulary entries x 64 (fp32: 32) target positions
+  // and writes them out as whole rows of E^T — 128 contiguous bytes per row instead of the 64-byte pieces of
+  // the accumulator layout
+  constexpr int NTS = sizeof(T) == 2 ? 2 : 1;             // 32-position halves staged together
+  constexpr int SROW = 32 * NTS * (int)sizeof(T) + 16;    // staged row pitch in bytes (padded against bank conflicts)
+  char* stage = smem + 1024 + w * (64 * SROW);
+  static_assert(1024 + 16 * 64 * SROW <= CeG::SMEM_BYTES + 1024, "staging area exceeds the kernel's LDS");
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
     const int r = r0 + wn * 64 + nt * 32 + (lane & 31);
@@ -66,11 +73,27 @@ __global__ __launch_bounds__(CeG::NT) void ce_fwd_kernel(const T* __restrict__ H
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const int v = v0 + wm * 64 + mt * 32 + acc32_row(lane, i);
+        const int vl = mt * 32 + acc32_row(lane, i);
         const float ev = mx > -INFINITY ? expf(z[mt][i] - mx) : 0.f;      // exp(-inf) = 0 past the vocabulary
         e += ev;
-        if (r < M && v < V) ET[(size_t)v * ldet + r] = from_f<T>(ev);
+        *reinterpret_cast<T*>(stage + vl * SROW + ((nt % NTS) * 32 + (lane & 31)) * sizeof(T)) = from_f<T>(ev);
       }
+    if (nt % NTS == NTS - 1) {                            // a staged block is complete: 64 rows of 32 * NTS positions
+      __syncthreads();
+      constexpr int CPR = 32 * NTS * (int)sizeof(T) / 16; // 16-byte chunks per staged row
+      constexpr int RPP = 64 / CPR;                       // rows per pass
+      const int rbase = r0 + wn * 64 + (nt / NTS) * 32 * NTS;
+#pragma unroll
+      for (int ps = 0; ps < 64 / RPP; ++ps) {
+        const int vl = ps * RPP + lane / CPR, ch = lane % CPR;
+        const int v = v0 + wm * 64 + vl;
+        // rows past M (inside the slab buffer, pitch ldet >= the tile's extent) hold values nobody reads
+        if (v < V)
+          *reinterpret_cast<uint4*>(ET + (size_t)v * ldet + rbase + ch * (16 / (int)sizeof(T))) =
+              *reinterpret_cast<const uint4*>(stage + vl * SROW + ch * 16);
+      }
+      if (nt + 1 < 2) __syncthreads();                    // the staging area is reused by the next half
+    }
     e += __shfl_xor(e, 32, 64);
     if (psz) sz += __shfl_xor(sz, 32, 64);                // label smoothing needs the mean logit of the row
     if (lane < 32 && r < M) {

@@ -131,6 +131,34 @@ void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, in
   }
 }
 
+// Measurement aid: nothing but matrix-core instructions (4 independent 32x32x16 bf16 accumulator chains per
+// wavefront, operands in registers), to read the rate the matrix cores reach on this chip beside the
+// nominal peak.  out receives one value per lane so that the loop cannot be dropped.
+__global__ __launch_bounds__(256) void mfma_rate_kernel(float* __restrict__ out, int iters) {
+  Frag<bf16_t> a, b;
+  a.v = make_uint4(0x3f803f80u + threadIdx.x, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
+  b.v = make_uint4(0x3f803f80u, 0x3f803f80u + blockIdx.x, 0x3f803f80u, 0x3f803f80u);
+  v16f acc[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[q][i] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) mma32(acc[q], a, b);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += acc[q][i];
+  out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+double launch_mfma_rate(float* out, int blocks, int iters, hipStream_t st) {
+  hipLaunchKernelGGL(mfma_rate_kernel, dim3(blocks), dim3(256), 0, st, out, iters);
+  return (double)blocks * 4 /*wavefronts*/ * iters * 4.0 * (2.0 * 32 * 32 * 16);
+}
+
 // 64x64 tiles through LDS; reads and writes are both row-contiguous.
 template <typename T>
 __global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ in, int ldin, T* __restrict__ out, int ldout,

@@ -23,6 +23,9 @@ void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, in
                     float* Cf, void* Ct, int ldc, const float* bias, int accumulate, hipStream_t st,
                     float* split_scratch = nullptr, size_t split_scratch_floats = 0, RowLimit limit = RowLimit{},
                     int limit_kind = 0);
+// Matrix-core issue-rate probe: `blocks` workgroups of 4 wavefronts, each `iters` x 4 bf16 32x32x16 MFMAs on
+// registers; out needs blocks * 256 floats.  Returns the flops of the launch.
+double launch_mfma_rate(float* out, int blocks, int iters, hipStream_t st);
 // out[C,R] = in[R,C]^T for T matrices (ldin, ldout in elements).
 void launch_transpose(int prec, const void* in, int ldin, void* out, int ldout, int R, int C, hipStream_t st);
 
@@ -220,7 +223,8 @@ void launch_add_f32(float* dst, const float* src, size_t n, hipStream_t st);    
 void launch_sum_parts(const float* parts, int nparts, size_t n, float* out, hipStream_t st);
 // db[n] = sum_m dG[m, n] over M rows of a T matrix [M, N].
 void launch_colsum(int prec, const void* dG, int ld, int M, int N, float* scratch /*[16*N]*/, float* db, hipStream_t st);
-void launch_sgd(float* p, const float* g, size_t n, float lr, hipStream_t st);
+// p <- p - lr g; skipped entirely while *flags != 0 (flags may be null)
+void launch_sgd(float* p, const float* g, size_t n, float lr, const int* flags, hipStream_t st);
 void launch_init_uniform(float* p, size_t n, uint64_t seed, float scale, hipStream_t st);
 
 // ---- greedy decoding (misc.hip) -------------------------------------------------------------------

@@ -256,14 +256,17 @@ void launch_colsum(int prec, const void* dG, int ld, int M, int N, float* scratc
   launch_sum_parts(scratch, COLSUM_SPLITS, (size_t)N, db, st);
 }
 
-__global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ p, const float* __restrict__ g, size_t n, float lr) {
+// nothing is updated while an error flag of an earlier step is pending (its gradients are undefined)
+__global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ p, const float* __restrict__ g, size_t n, float lr,
+                                                  const int* __restrict__ flags) {
+  if (flags && *flags) return;
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * 256;
   for (; i < n; i += stride) p[i] = p[i] - lr * g[i];
 }
-void launch_sgd(float* p, const float* g, size_t n, float lr, hipStream_t st) {
+void launch_sgd(float* p, const float* g, size_t n, float lr, const int* flags, hipStream_t st) {
   if (n == 0) return;
-  hipLaunchKernelGGL(sgd_kernel, dim3(grid_for(n)), dim3(256), 0, st, p, g, n, lr);
+  hipLaunchKernelGGL(sgd_kernel, dim3(grid_for(n)), dim3(256), 0, st, p, g, n, lr, flags);
 }
 
 // SplitMix64 of (seed + element index); top 24 bits -> uniform [-scale, scale)

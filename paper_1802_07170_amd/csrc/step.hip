@@ -676,12 +676,10 @@ void launch_step_bwd_fused(int prec, const StepBwd* gs, int n, int Bp, hipStream
         Kmax = std::max(Kmax, a.g[i].K);
       }
     }
-    int nsteps = (Kmax / 8 + 3) / 4;
-    static const int cfg_ks8 = getenv("CMT_BWD_KS8") ? atoi(getenv("CMT_BWD_KS8")) : 0;     // experiments
-    static const int cfg_bt4 = getenv("CMT_BWD_BT4") ? atoi(getenv("CMT_BWD_BT4")) : 0;
-    if (cfg_ks8 && nsteps > 64) nsteps = 64;
-    const bool wide = Bp > 64 || cfg_bt4;           // 64 sentences per workgroup from 65 sentences on
-#define GO(TT, KS, UU) do { if (wide) step_bwd_go<TT, KS, UU, 4>(a, m, Nmax, Bp, st); else step_bwd_go<TT, KS, UU, 2>(a, m, Nmax, Bp, st); } while (0)
+    const int nsteps = (Kmax / 8 + 3) / 4;
+    // 16 columns x 32 sentences per workgroup.  (64 sentences per workgroup halves the number of workgroups
+    // and was measured at twice the time: 25.6 against 12.9 us for 64 sentences, 26.2 against 21.8 us for 128.)
+#define GO(TT, KS, UU) step_bwd_go<TT, KS, UU, 2>(a, m, Nmax, Bp, st)
     if (prec) {
       if (nsteps > 64) GO(bf16_t, 16, 4); else if (nsteps > 32) GO(bf16_t, 8, 4); else if (nsteps > 16) GO(bf16_t, 8, 2); else GO(bf16_t, 4, 2);
     } else {
@@ -873,7 +871,7 @@ void launch_att_bwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds
 
 // After the decoder loop: for a block (sentence b, 256 hidden columns, ATT_DEF_IB source positions):
 //   dHs[i,b,h] = sum_j a[j,b,i] dCs[j,b,h]        dK[i,b,h] = sum_j ds[j,b,i] Ht[j,b,h]
-constexpr int ATT_DEF_IB = 16;                       // source positions per workgroup
+constexpr int ATT_DEF_IB = 32;                       // source positions per workgroup (each re-reads the step data once)
 constexpr int ATT_DEF_JB = 256 / ATT_DEF_IB;         // decoder steps per pass: their loads are issued together
 template <typename T>
 __global__ __launch_bounds__(256) void att_deferred_kernel(const float* __restrict__ a, const float* __restrict__ ds,

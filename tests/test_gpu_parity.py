@@ -100,6 +100,27 @@ def run_case(cfg, params, batch, prec, max_shape=None, check_inter=True, reg=Non
             nll = tr.debug_fetch("nll", (T, Bp))[:, :B]
             assert np.abs(nll - it["nll"]).max() <= (1e-4 if prec == 0 else 5e-2) * np.abs(it["nll"]).max()
             assert not nll[~vt].any()
+            # per kernel: scores of Eq. 4, and states / gate activations of every LSTM, in forward order, so
+            # that a failure names the first kernel that diverges (valid positions only)
+            # (cases that drop the per-entry bound on the gradients hold these in relative L2 instead)
+            per_entry = grad_check.get("elementwise", True)
+
+            def close(got, ref, what):
+                if per_entry:
+                    assert np.abs(got - ref).max() <= atol * max(1.0, np.abs(ref).max()), what
+                else:
+                    assert np.linalg.norm(got - ref) <= atol * np.linalg.norm(ref), what
+            sc = tr.debug_fetch("att_s", (T, Bp, S))[:, :B]
+            ok = vt[:, :, None] & vs.T[None, :, :]
+            close(sc[ok], it["att_s"][ok], "att_s")
+            L = cfg["layers"]
+            lstms = [("enc.l0.fwd", S, H // 2, vs), ("enc.l0.bwd", S, H // 2, vs)] + [(f"enc.l{l}", S, H, vs) for l in range(1, L)] \
+                + [(f"dec.l{l}", T, H, vt) for l in range(L)]
+            for nm, n, w, m in lstms:
+                for what, width in (("gates", 4 * w), ("c", w), ("h", w)):
+                    got = tr.debug_fetch(f"{nm}.{what}", (n, Bp, width))[:, :B]
+                    ref = it[f"{nm}.{what}"]
+                    close(got[m], ref[m], f"{nm}.{what}")
         return loss, oloss, worst, tr
     except Exception:
         tr.close()
@@ -216,17 +237,19 @@ def sweep_cases(seed, n):
 
 
 SWEEP_SENS_C = 2.0
-# (generator seed, case) of bf16 cases whose exact W_a gradient moves by about 2e-2 or more when the
-# parameters are rounded to bf16 (found and pinned by tests/test_oracle_conditioning.py, oracle only)
-SWEEP_ILL_CONDITIONED = [(2, 44), (2, 57), (2, 71), (3, 40), (3, 92), (3, 97)]
+# (generator seed, case) of bf16 cases whose exact W_a gradient moves by more than 2e-2 under the oracle's
+# bf16 precision model (found and pinned by tests/test_oracle_conditioning.py, oracle only)
+SWEEP_ILL_CONDITIONED = [(2, 14), (2, 23), (2, 44), (2, 57), (2, 71), (2, 80), (2, 91), (3, 92), (3, 97)]
 
 
 def oracle_sensitivity(cfg, params, batch, reg):
-    """Per gradient tensor s = |g(bf16 W) - g(W)| / |g(W)|, from two oracle runs: how far rounding the
-    parameters to bfloat16 alone moves the exact gradient."""
+    """Per gradient tensor s = |g_bf16 - g| / |g| from two oracle runs: g the exact fp64 gradient, g_bf16
+    the oracle's gradient under its bf16 precision model (parameters and every contraction operand rounded
+    to bfloat16, sums exact): how far any bf16-operand method can be expected to land from g on this input."""
     kw = dict(dropout=reg[0], label_smoothing=reg[1], dropout_seed=reg[2]) if reg else {}
     g0 = O.train_step(cfg, params, *batch, **kw)[1]
-    g1 = O.train_step(cfg, {k: bf16_round(v) for k, v in params.items()}, *batch, **kw)[1]
+    with O.operand_rounding(O.bf16_round):
+        g1 = O.train_step(cfg, {k: O.bf16_round(v) for k, v in params.items()}, *batch, **kw)[1]
     return {k: float(np.linalg.norm(g1[k] - g0[k]) / (np.linalg.norm(g0[k]) + 1e-300)) for k in g0}
 
 
@@ -236,12 +259,12 @@ def test_random_shapes_sweep():
     against the oracle with intermediates.  Its purpose is indexing and tiling, where a mistake is an error
     of order one.  fp32 cases: the full bar.  bf16 cases: loss at the bar; every gradient tensor's relative
     L2 error at max(2e-2, SWEEP_SENS_C * s), where s is that tensor's sensitivity in this very case —
-    how far rounding the PARAMETERS to bf16 moves the oracle's exact gradient (two oracle runs, no HIP
-    value involved).  On these small, strongly driven nets (parameters up to 0.3, dropout up to 0.5) s
+    how far the oracle's own gradient moves when its parameters and contraction operands are rounded to
+    bf16 (two oracle runs, no HIP value involved).  On these small, strongly driven nets (parameters up to 0.3, dropout up to 0.5) s
     stays below 1e-2 for almost every tensor, so the plain bar applies; the exception is W_a, whose
     gradient goes through the softmax Jacobian a (da - sum a da) and cancels heavily when a sentence's
-    source states resemble each other (s up to 0.1: tests/test_oracle_conditioning.py pins that on the
-    CPU, and the six worst of 200 further cases of the same generator are added to the 32 here).  The per-entry bound is dropped for bf16 cases here (a handful of entries per run land just
+    source states resemble each other (s up to 0.16: tests/test_oracle_conditioning.py pins that on the
+    CPU, and the nine worst of 200 further cases of the same generator are added to the 32 here).  The per-entry bound is dropped for bf16 cases here (a handful of entries per run land just
     outside 2e-2 |g| + 1e-3); on the task's configurations and in every other test the full bf16 bar
     applies to every tensor."""
     cases = list(sweep_cases(1, 32))
@@ -705,6 +728,92 @@ def test_errors_are_reported_not_fatal():
     assert np.array_equal(tr.get_params(), p0)            # parameters untouched
     assert np.isfinite(tr.train_step(tr.upload_batch(src, sl, tgt, tl)))
     tr.close()
+
+
+@pytest.mark.parametrize("prec", [0, 1])
+def test_non_finite_loss_is_reported_and_parameters_stay_untouched(prec):
+    """An Inf in W_o makes the loss of Eq. 1 non-finite: the step must return CMT_ENONFINITE, a following
+    SGD update must not touch the parameters, and after good parameters are set the handle works again."""
+    from paper_1802_07170_amd import binding
+    cfg = dict(src_vocab=104, tgt_vocab=136, emb=24, hidden=32, layers=2)
+    tr = binding.Trainer(cfg, 4, 6, 6, precision=prec)
+    rng = np.random.default_rng(1)
+    batch = ragged_batch(rng, 4, 6, 6, 104, 136)
+    params = I.make_params(cfg, seed=2, scale=0.1)
+    good = I.flatten(params, cfg)
+    bad = dict(params)
+    bad["W_o"] = params["W_o"].copy()
+    bad["W_o"][int(batch[2][0, 0]), 3] = np.inf            # a row the first label uses
+    tr.set_params(I.flatten(bad, cfg))
+    dev = tr.upload_batch(*batch)
+    p0 = tr.get_params()
+    with pytest.raises(binding.CmtError) as e:
+        tr.train_step(dev)
+    assert e.value.code == binding.CMT_ENONFINITE
+    assert np.array_equal(tr.get_params(), p0, equal_nan=True)
+    tr.set_params(good)
+    loss = tr.train_step(dev)
+    oloss = O.train_step(cfg, params, *batch)[0]
+    assert abs(loss - oloss) <= (1e-4 if prec == 0 else 2e-2) * oloss
+    tr.close()
+
+
+def test_error_flags_are_sticky_over_asynchronous_steps_and_block_the_update():
+    """A failing step in the middle of a run of asynchronous steps (nothing fetched in between) must still be
+    reported by the next cmt_fetch_loss, and no SGD update enqueued after it may change the parameters:
+    they stay as the last good update left them.  After the report the handle trains on."""
+    from paper_1802_07170_amd import binding
+    cfg = dict(src_vocab=104, tgt_vocab=136, emb=24, hidden=32, layers=1)
+    tr = binding.Trainer(cfg, 4, 6, 6, precision=0)
+    tr.init_params(0, 0.1)
+    rng = np.random.default_rng(0)
+    src, sl, tgt, tl = ragged_batch(rng, 4, 6, 6, 104, 136)
+    good = tr.upload_batch(src, sl, tgt, tl)
+    bad_ids = tgt.copy(); bad_ids[0, 0] = 136                # label == vocabulary size
+    bad = tr.upload_batch(src, sl, bad_ids, tl)
+    tr.train_step_async(good); tr.sgd_update(0.5)
+    tr.torch.cuda.synchronize()
+    p_after_good = tr.get_params()
+    tr.train_step_async(bad); tr.sgd_update(0.5)             # must not be applied
+    tr.train_step_async(good); tr.sgd_update(0.5)            # flag still pending: not applied either
+    with pytest.raises(binding.CmtError) as e:
+        tr.fetch_loss()
+    assert e.value.code == binding.CMT_ERANGE
+    assert np.array_equal(tr.get_params(), p_after_good)
+    tr.train_step_async(good); tr.sgd_update(0.5)            # reported and cleared: training goes on
+    assert np.isfinite(tr.fetch_loss())
+    assert not np.array_equal(tr.get_params(), p_after_good)
+    tr.close()
+
+
+@pytest.mark.parametrize("prec", [0, 1])
+def test_a_workspace_full_of_garbage_changes_nothing(prec):
+    """The library must not rely on the caller's workspace being zeroed: with every byte set to 0xFF (NaN
+    patterns in both operand types) before the parameters are set, a step gives bit for bit the loss and
+    gradients of a step on a zeroed workspace.  Vocabulary and row counts that leave ragged tails in the
+    output layer's 64-row blocks."""
+    from paper_1802_07170_amd import binding
+    cfg = dict(src_vocab=104, tgt_vocab=328, emb=16, hidden=48, layers=2)
+    rng = np.random.default_rng(5)
+    params = I.flatten(I.make_params(cfg, seed=4, scale=0.2), cfg)
+    batch = ragged_batch(rng, 7, 5, 9, cfg["src_vocab"], cfg["tgt_vocab"])
+    results = []
+    for fill in (0, 0xFF):
+        tr = binding.Trainer(cfg, 7, 5, 9, precision=prec)
+        tr.workspace.fill_(fill)
+        tr.grads.fill_(float("nan"))
+        tr.torch.cuda.synchronize()
+        tr.lib.cmt_destroy(tr.h)                              # bind again, so that creation sees the filled workspace
+        h = binding.C.c_void_p()
+        assert tr.lib.cmt_create(binding.C.byref(tr.ccfg), tr.params.data_ptr(), tr.grads.data_ptr(), tr.workspace.data_ptr(),
+                                 tr.stream.cuda_stream, binding.C.byref(h)) == binding.CMT_OK
+        tr.h = h
+        tr.set_params(params)
+        dev = tr.upload_batch(*batch)
+        results.append((tr.train_step(dev), tr.get_grads(), tr.eval_loss(dev)))
+        tr.close()
+    assert results[0][0] == results[1][0] and results[0][2] == results[1][2]
+    assert np.isfinite(results[1][1]).all() and np.array_equal(results[0][1], results[1][1])
 
 
 def test_small_config_fp32_full_size():
