@@ -218,6 +218,9 @@ int cmt_padded_batch(const cmt_handle* h);
  *   "ce_fwd"         vocabulary projection + log-sum-exp partials of the first slab of rows flops
  *   "step_bwd_fused_dec" the same product as step2d_bwd_dec in the form the decoder's backward loop runs:
  *                    whole contraction per workgroup, cell backward of the layer below in the epilogue bytes
+ *   "grid_barrier", "grid_barrier_nofence"  100 chip-wide barriers between 256 resident workgroups, with /
+ *                    without device-scope fences (bounded polling; what a persistent recurrence would pay
+ *                    per time step); work = the number of barriers
  *   "mfma_rate"      matrix-core instructions alone (bf16 32x32x16 on registers): the rate the chip's
  *                    matrix cores reach, to be read beside the nominal peak                 flops
  * The replays of the backward kernels leave the in-place state gradients of the last step in whatever

@@ -1463,6 +1463,7 @@ int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_la
   const std::string s(name);
   const int j = T / 2;                                  // the middle target position
   std::function<void(int)> launch;
+  const int* probe_flag = nullptr;                      // set by a probe whose bounded wait may give up
   if (s == "lstm_fwd_dec") {
     // decoder LSTM forward step, cycling over the layers like the real loop (weights not L2-resident)
     const int K = 2 * H;                                // per-step contraction (layer 0: [feed; h], others: [x; h])
@@ -1531,6 +1532,17 @@ int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_la
       launch_ce_fwd(p, Ho, PH, h->Pw(h->off_Wo), h->params + h->off_Bo, h->labels, Mc, V, H, h->dzTs2, h->pmax, h->psum, nullptr,
                     h->zy, st);
     };
+  } else if (s == "grid_barrier" || s == "grid_barrier_nofence") {
+    // 100 chip-wide barriers between 256 resident workgroups (bounded polling); work = the number of barriers
+    const int rounds = 100, fences = s == "grid_barrier" ? 1 : 0;
+    unsigned* counter = (unsigned*)h->gsplit;
+    int* gave_up = (int*)h->gsplit + 64;
+    *algo_work = rounds;
+    launch = [=](int) {
+      launch_fill_f32(h->gsplit, 128, 0.f, st);
+      launch_grid_barrier_probe(counter, gave_up, 256, rounds, fences, 1 << 16, st);
+    };
+    probe_flag = gave_up;
   } else if (s == "mfma_rate") {
     // matrix cores alone: 4096 workgroups x 4 wavefronts x 2048 x 4 bf16 32x32x16 MFMAs on registers  (flops)
     const int blocks = 4096, it = 2048;
@@ -1553,6 +1565,12 @@ int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_la
   (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
   if (e != hipSuccess) return hip_fail(h, e, "cmt_time_kernel");
   *us_per_launch = ms * 1e3f / iters;
+  if (probe_flag) {
+    int gave = 0;
+    e = hipMemcpy(&gave, probe_flag, sizeof(int), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(h, e, "cmt_time_kernel");
+    if (gave) return fail(h, CMT_EHIP, "the barrier probe gave up waiting (its workgroups were not all resident)");
+  }
   return CMT_OK;
 }
 

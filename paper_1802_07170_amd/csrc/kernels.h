@@ -227,6 +227,11 @@ void launch_colsum(int prec, const void* dG, int ld, int M, int N, float* scratc
 void launch_sgd(float* p, const float* g, size_t n, float lr, const int* flags, hipStream_t st);
 void launch_init_uniform(float* p, size_t n, uint64_t seed, float scale, hipStream_t st);
 
+// Chip-wide barrier probe: `blocks` workgroups (they must all be resident: at most one per CU) pass `rounds`
+// barriers on *counter (zero before the launch); a workgroup that polls max_spin times without success sets
+// *gave_up and leaves.  fences: device-scope fences around each barrier.
+void launch_grid_barrier_probe(unsigned* counter, int* gave_up, int blocks, int rounds, int fences, int max_spin, hipStream_t st);
+
 // ---- greedy decoding (misc.hip) -------------------------------------------------------------------
 // x[b, 0:E] = table[tok[b]] (T, row pitch ldx) for b < B; zero rows for b in [B, Bp).
 void launch_dec_embed(int prec, const void* table, int E, const int32_t* tok, int B, int Bp, void* x, int ldx, hipStream_t st);

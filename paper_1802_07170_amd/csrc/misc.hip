@@ -288,6 +288,39 @@ void launch_init_uniform(float* p, size_t n, uint64_t seed, float scale, hipStre
 }
 
 // ------------------------------------------------------------------------------------------------
+// Measurement aid: what a chip-wide barrier between resident workgroups costs — the price a persistent,
+// weight-stationary recurrence would pay per time step instead of a kernel boundary.  Every workgroup
+// arrives with one device-scope atomic increment and polls the counter until all have arrived; with
+// `fences` the arrival is preceded and the departure followed by a device-scope fence, as an exchange of
+// data between the workgroups needs (each XCD has its own L2).  The wait is bounded: after max_spin polls a
+// workgroup gives up, raises *gave_up and leaves, so the kernel ends whatever happens (e.g. when not all
+// workgroups are resident at once).
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void grid_barrier_probe_kernel(unsigned* __restrict__ counter, int rounds, int fences, int max_spin,
+                                                                 int* __restrict__ gave_up) {
+  __shared__ int s_stop;
+  const unsigned n = gridDim.x;
+  for (int r = 0; r < rounds; ++r) {
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      if (fences) __threadfence();
+      atomicAdd(counter, 1u);
+      const unsigned target = (unsigned)(r + 1) * n;
+      int spin = 0;
+      while (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target && spin < max_spin) ++spin;
+      s_stop = spin >= max_spin;
+      if (s_stop) atomicOr(gave_up, 1);
+      if (fences) __threadfence();
+    }
+    __syncthreads();
+    if (s_stop) break;
+  }
+}
+void launch_grid_barrier_probe(unsigned* counter, int* gave_up, int blocks, int rounds, int fences, int max_spin, hipStream_t st) {
+  hipLaunchKernelGGL(grid_barrier_probe_kernel, dim3(blocks), dim3(256), 0, st, counter, rounds, fences, max_spin, gave_up);
+}
+
+// ------------------------------------------------------------------------------------------------
 // greedy decoding helpers
 // ------------------------------------------------------------------------------------------------
 // x[b, 0:E] = table[tok[b]] for b < B, zero rows for the batch padding

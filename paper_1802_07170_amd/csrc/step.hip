@@ -25,7 +25,7 @@ namespace cmt {
 
 constexpr int STEP_MAXBT = 4;          // batch tiles (of 16 sentences) per workgroup
 
-struct StepGrid { int nx, kb, nz; int krot = 0; };
+struct StepGrid { int nx, kb, nz; };
 struct StepGemmArgs { StepGemm g[STEP_MAX_INST]; };
 struct LstmBwdPointArgs { LstmBwdPoint p[STEP_MAX_INST]; };
 __device__ __forceinline__ bool decode_block(const StepGrid& g, int& x, int& kb, int& z) {
@@ -46,8 +46,7 @@ static inline int step_grid_blocks(const StepGrid& g) { return ((g.nx + 7) / 8) 
 // t % KS.  red must hold KS * RT * STEP_MAXBT * 256 floats.
 template <typename T, int RT, int KS, int U, int BT = STEP_MAXBT>
 __device__ __forceinline__ void step_contract(const T* const (&wrow)[RT], int w0_off, int w1_off, const T* a0, int lda0,
-                                              int K0, const T* a1, int lda1, int K1, int Bp, int bt0, int nbt, float* red,
-                                              int rot = 0) {
+                                              int K0, const T* a1, int lda1, int K1, int Bp, int bt0, int nbt, float* red) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int nc0 = K0 >> 3, nc = (K0 + K1) >> 3;
   const int nsteps = (nc + 3) >> 2;
@@ -61,14 +60,8 @@ __device__ __forceinline__ void step_contract(const T* const (&wrow)[RT], int w0
     Frag<T> fw[U][RT], fx[U][BT];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      // workgroups start at different points of the k axis (rot), so that the ones that share an
-      // activation slab do not ask the same L2 lines at the same time
-      int ks = s0 + w + KS * u;
-      const bool in_range = ks < nsteps;
-      ks += rot;
-      if (ks >= nsteps) ks -= nsteps;
-      const int chunk = 4 * ks + (lane >> 4);
-      if (in_range && chunk < nc) {
+      const int chunk = 4 * (s0 + w + KS * u) + (lane >> 4);
+      if (chunk < nc) {
         const bool first = chunk < nc0;
         const int kk = first ? chunk * 8 : (chunk - nc0) * 8;
         const int wo = (first ? w0_off : w1_off) + kk;
@@ -197,13 +190,8 @@ __global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(LstmFwdArgs args, int
     have0 = bt < nbt && u < Hh && b < Bp;
     if (have0) in0 = cell_load(d, b, u, Hh, sizeof(T) == 2);
   }
-  int rot = 0;
-  if (sg.krot) {
-    const int nsteps = (((d.Kx + Hh) >> 3) + 3) >> 2;
-    rot = (int)(((long long)(blockIdx.x >> 3) * nsteps) / max(1, (int)(gridDim.x >> 3)));
-  }
   step_contract<T, RT, KS, U, BT>(wrow, d.wx_off, d.wh_off, (const T*)d.x, d.ldx, d.Kx, (const T*)d.hprev, d.ldh, Hh, Bp, bt0,
-                              nbt, red, rot);
+                              nbt, red);
   for (int t = w; t < RT * BT; t += KS) {
     const int rt = t / BT, bt = t - rt * BT;
     if (bt >= nbt) continue;
@@ -217,11 +205,10 @@ __global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(LstmFwdArgs args, int
   }
 }
 
-static int g_step_krot = 0;            // env CMT_KROT (experiment): rotate the k order per workgroup
 template <typename T, int RT, int KS, int U, int BT = STEP_MAXBT>
 static void lstm_fwd_go(const LstmFwdArgs& a, int Bp, int Hh, int ndir, hipStream_t st) {
   const int nbt = (Bp + 15) / 16;
-  StepGrid sg{((Hh + 4 * RT - 1) / (4 * RT)) * ndir, 1, (nbt + BT - 1) / BT, g_step_krot};
+  StepGrid sg{((Hh + 4 * RT - 1) / (4 * RT)) * ndir, 1, (nbt + BT - 1) / BT};
   hipLaunchKernelGGL((lstm_fwd_kernel<T, RT, KS, U, BT>), dim3(step_grid_blocks(sg)), dim3(64 * KS), 0, st, a, Bp, Hh, sg, ndir);
 }
 
@@ -234,8 +221,6 @@ void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh,
   if (g_lstm_fwd_how < 0) {
     const char* e = getenv("CMT_LSTM_FWD");
     g_lstm_fwd_how = e ? atoi(e) : 0;
-    const char* r = getenv("CMT_KROT");
-    g_step_krot = r ? atoi(r) : 0;
   }
   LstmFwdArgs a;
   int K = 0;
@@ -252,9 +237,7 @@ void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh,
   if (how == 0) how = (Bp >= 256) ? 4 : (Bp > 64) ? 2 : (prec && nbt == 4) ? 6 : 1;
   const int nsteps = (K / 8 + 3) / 4;
   if (prec) {
-    if (how == 7) lstm_fwd_go<bf16_t, 2, 8, 8, 2>(a, Bp, Hh, ndir, st);
-    else if (how == 8) lstm_fwd_go<bf16_t, 2, 16, 4, 2>(a, Bp, Hh, ndir, st);
-    else if (how == 6) {
+    if (how == 6) {
       if (nsteps > 32) lstm_fwd_go<bf16_t, 2, 8, 4, 2>(a, Bp, Hh, ndir, st);
       else if (nsteps > 16) lstm_fwd_go<bf16_t, 2, 8, 2, 2>(a, Bp, Hh, ndir, st);
       else lstm_fwd_go<bf16_t, 2, 4, 2, 2>(a, Bp, Hh, ndir, st);
@@ -633,12 +616,7 @@ __global__ __launch_bounds__(64 * KS) void step_bwd_fused_kernel(StepBwdArgs arg
       for (int i = 0; i < 4; ++i) tho[i] = to_f<T>(((const T*)e.Ho)[(size_t)b * e.ldho + c + i]);
     }
   }
-  int rot = 0;
-  if (sg.krot) {
-    const int nsteps = ((g.K >> 3) + 3) >> 2;
-    rot = (int)(((long long)(blockIdx.x >> 3) * nsteps) / max(1, (int)(gridDim.x >> 3)));
-  }
-  step_contract<T, 1, KS, U, BT>(wrow, 0, 0, (const T*)g.dg, g.lddg, g.K, (const T*)nullptr, 0, 0, Bp, bt0, nbt, red, rot);
+  step_contract<T, 1, KS, U, BT>(wrow, 0, 0, (const T*)g.dg, g.lddg, g.K, (const T*)nullptr, 0, 0, Bp, bt0, nbt, red);
   if (!mine) return;                                // KS >= BT: wavefront w finishes sentence tile w
   const v4f r = step_tile_sum<1, KS, BT>(red, 0, w);
   const float v[4] = {r[0], r[1], r[2], r[3]};
@@ -660,7 +638,7 @@ __global__ __launch_bounds__(64 * KS) void step_bwd_fused_kernel(StepBwdArgs arg
 template <typename T, int KS, int U, int BT>
 static void step_bwd_go(const StepBwdArgs& a, int n, int Nmax, int Bp, hipStream_t st) {
   const int nbt = (Bp + 15) / 16;
-  StepGrid sg{(Nmax + 15) / 16, 1, (nbt + BT - 1) / BT, g_step_krot};
+  StepGrid sg{(Nmax + 15) / 16, 1, (nbt + BT - 1) / BT};
   hipLaunchKernelGGL((step_bwd_fused_kernel<T, KS, U, BT>), dim3(step_grid_blocks(sg), n), dim3(64 * KS), 0, st, a, Bp, sg);
 }
 
