@@ -276,7 +276,11 @@ size_t layout(cmt_handle* h, char* base) {
   h->wcp = (float*)a.take((size_t)8 * Bp * 2 * H * 4);
   h->dXt = (float*)a.take(Mt * E * 4);
   const int np = ce_num_partials(c.tgt_vocab);
-  h->pmax = (float*)a.take(Mt * np * 4); h->psum = (float*)a.take(Mt * np * 4); h->psz = (float*)a.take(Mt * np * 4);
+  {   // per slab of CE_SLAB_ROWS positions a [np, CE_SLAB_ROWS] block of partials (slab sl starts at sl * CE_SLAB_ROWS * np)
+    const size_t slabs = (Mt + CE_SLAB_ROWS - 1) / CE_SLAB_ROWS;
+    const size_t bytes = slabs * CE_SLAB_ROWS * np * 4;
+    h->pmax = (float*)a.take(bytes); h->psum = (float*)a.take(bytes); h->psz = (float*)a.take(bytes);
+  }
   h->zy = (float*)a.take(Mt * 4); h->lse = (float*)a.take(Mt * 4); h->nll = (float*)a.take(Mt * 4);
   h->rowscale = (float*)a.take(Mt * 4);
   h->ce_pos = (int32_t*)a.take(Mt * 4); h->ce_row = (int32_t*)a.take(Mt * 4); h->labels_c = (int32_t*)a.take(Mt * 4);
@@ -1544,9 +1548,10 @@ int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_la
     };
     probe_flag = gave_up;
   } else if (s == "mfma_rate") {
-    // matrix cores alone: 4096 workgroups x 4 wavefronts x 2048 x 4 bf16 32x32x16 MFMAs on registers  (flops)
-    const int blocks = 4096, it = 2048;
-    if ((size_t)blocks * 256 > h->gsplit_floats) return fail(h, CMT_EINVAL, "workspace too small for the probe");
+    // matrix cores alone: up to 4096 workgroups x 4 wavefronts x 2048 x 4 bf16 32x32x16 MFMAs on registers  (flops)
+    const int it = 2048;
+    const int blocks = (int)std::min<size_t>(4096, h->gsplit_floats / 256);   // one float per lane lands in the split-k scratch
+    if (blocks < 1) return fail(h, CMT_EINVAL, "workspace too small for the probe");
     *algo_work = (double)blocks * 4 * it * 4.0 * (2.0 * 32 * 32 * 16);
     launch = [=](int) { (void)launch_mfma_rate(h->gsplit, blocks, it, st); };
   } else {

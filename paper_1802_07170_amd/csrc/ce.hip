@@ -96,10 +96,10 @@ __global__ __launch_bounds__(CeG::NT) void ce_fwd_kernel(const T* __restrict__ H
     }
     e += __shfl_xor(e, 32, 64);
     if (psz) sz += __shfl_xor(sz, 32, 64);                // label smoothing needs the mean logit of the row
-    if (lane < 32 && r < M) {
-      pmax[(size_t)r * np + pidx] = mx;
-      psum[(size_t)r * np + pidx] = e;
-      if (psz) psz[(size_t)r * np + pidx] = sz;
+    if (lane < 32 && r < M) {                             // partials are kept [group][position]: 32 lanes, 128 bytes
+      pmax[(size_t)pidx * CE_SLAB_ROWS + r] = mx;
+      psum[(size_t)pidx * CE_SLAB_ROWS + r] = e;
+      if (psz) psz[(size_t)pidx * CE_SLAB_ROWS + r] = sz;
     }
   }
 }
@@ -117,30 +117,50 @@ void launch_ce_fwd(int prec, const void* Ho, int ldho, const void* Wo, const flo
                        labels, M, V, H, (float*)ET, CE_SLAB_ROWS, pmax, psum, psz, zy, np, lim);
 }
 
-// one wavefront per row: combine the partials.  Row loss against the smoothed target distribution
-// (1 - eps) onehot(y) + eps / V:  (1 - eps) (lse - z_y) + eps (lse - mean_v z_v); eps = 0: plain nll.
-__global__ __launch_bounds__(256) void ce_row_kernel(const float* __restrict__ pmax, const float* __restrict__ psum,
-                                                     const float* __restrict__ psz, const float* __restrict__ zy,
-                                                     const float* __restrict__ mask, int M, int np, float eps, int V,
-                                                     float* __restrict__ lse, float* __restrict__ nll, RowLimit lim) {
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+// Combines the partials (kept [group][position], pitch CE_SLAB_ROWS) of 32 target positions per workgroup: thread
+// t takes position t % 32 and every 32nd group from t / 32 on, so that a half-wavefront reads 32 consecutive
+// positions of one group; the 32 group strands of a position meet in LDS, in a fixed order.  Row loss
+// against the smoothed target distribution (1 - eps) onehot(y) + eps / V:
+// (1 - eps) (lse - z_y) + eps (lse - mean_v z_v); eps = 0: plain nll.
+constexpr int CE_ROW_STRANDS = 32, CE_ROW_ROWS = 32;
+__device__ __forceinline__ float ce_row_meet(float (&red)[CE_ROW_STRANDS][CE_ROW_ROWS], int pg, int rl, float v, bool take_max) {
+  red[pg][rl] = v;
+  __syncthreads();
+  float r = red[0][rl];
+#pragma unroll
+  for (int k = 1; k < CE_ROW_STRANDS; ++k) r = take_max ? fmaxf(r, red[k][rl]) : r + red[k][rl];
+  __syncthreads();
+  return r;
+}
+__global__ __launch_bounds__(CE_ROW_ROWS * CE_ROW_STRANDS) void ce_row_kernel(const float* __restrict__ pmax, const float* __restrict__ psum,
+                                                                    const float* __restrict__ psz, const float* __restrict__ zy,
+                                                                    const float* __restrict__ mask, int M, int np, float eps, int V,
+                                                                    float* __restrict__ lse, float* __restrict__ nll, RowLimit lim) {
+  __shared__ float red[CE_ROW_STRANDS][CE_ROW_ROWS];
+  const int rl = threadIdx.x % CE_ROW_ROWS, pg = threadIdx.x / CE_ROW_ROWS;
+  const int row = blockIdx.x * CE_ROW_ROWS + rl;
   if (lim.n) M = min(M, max(*lim.n - lim.base, 0));
-  if (row >= M) return;
+  if (blockIdx.x * CE_ROW_ROWS >= M) return;
+  const bool ok = row < M;
   float mx = -INFINITY;
-  for (int p = lane; p < np; p += 64) mx = fmaxf(mx, pmax[(size_t)row * np + p]);
-  mx = wave_max(mx);
-  float s = 0.f;
-  for (int p = lane; p < np; p += 64) {
-    const float pm = pmax[(size_t)row * np + p];
-    if (pm > -INFINITY) s += psum[(size_t)row * np + p] * expf(pm - mx);
+  if (ok) {
+#pragma unroll 4
+    for (int p = pg; p < np; p += CE_ROW_STRANDS) mx = fmaxf(mx, pmax[(size_t)p * CE_SLAB_ROWS + row]);
   }
-  s = wave_sum(s);
-  float sz = 0.f;
-  if (eps > 0.f) {
-    for (int p = lane; p < np; p += 64) sz += psz[(size_t)row * np + p];
-    sz = wave_sum(sz);
+  mx = ce_row_meet(red, pg, rl, mx, true);
+  float s = 0.f, sz = 0.f;
+  if (ok) {
+#pragma unroll 4
+    for (int p = pg; p < np; p += CE_ROW_STRANDS) {
+      const float pm = pmax[(size_t)p * CE_SLAB_ROWS + row];
+      const float ps = psum[(size_t)p * CE_SLAB_ROWS + row];
+      if (pm > -INFINITY) s += ps * expf(pm - mx);
+      if (eps > 0.f) sz += psz[(size_t)p * CE_SLAB_ROWS + row];
+    }
   }
-  if (lane == 0) {
+  s = ce_row_meet(red, pg, rl, s, false);
+  if (eps > 0.f) sz = ce_row_meet(red, pg, rl, sz, false);
+  if (pg == 0 && ok) {
     const float l = mx + logf(s);
     lse[row] = l;
     float r = l - zy[row];
@@ -242,7 +262,7 @@ void launch_ce_compact(const float* mask, const int32_t* labels, int M, int32_t*
 }
 void launch_ce_rows(const float* pmax, const float* psum, const float* psz, const float* zy, const float* mask, int M, int np,
                     float eps, int V, float* lse, float* nll, hipStream_t st, RowLimit lim) {
-  hipLaunchKernelGGL(ce_row_kernel, dim3((M + 3) / 4), dim3(256), 0, st, pmax, psum, psz, zy, mask, M, np, eps, V, lse, nll, lim);
+  hipLaunchKernelGGL(ce_row_kernel, dim3((M + CE_ROW_ROWS - 1) / CE_ROW_ROWS), dim3(CE_ROW_ROWS * CE_ROW_STRANDS), 0, st, pmax, psum, psz, zy, mask, M, np, eps, V, lse, nll, lim);
 }
 void launch_ce_loss(const float* nll, int M, float* loss, int* flags, hipStream_t st, RowLimit lim) {
   hipLaunchKernelGGL(ce_loss_kernel, dim3(1), dim3(1024), 0, st, nll, M, loss, flags, lim);
@@ -278,7 +298,7 @@ __global__ __launch_bounds__(256) void ce_scale_kernel(T* __restrict__ ET, int l
     float f = 0.f, rs = 0.f;
     int y = -1;
     if (r < Mc) {
-      const float pm = pmax[(size_t)r * np + blockIdx.x];
+      const float pm = pmax[(size_t)blockIdx.x * CE_SLAB_ROWS + r];
       f = pm > -INFINITY ? expf(pm - lse[r]) : 0.f;
       rs = rowscale[r];
       y = labels[r];

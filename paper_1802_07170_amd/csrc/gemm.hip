@@ -163,7 +163,7 @@ double launch_mfma_rate(float* out, int blocks, int iters, hipStream_t st) {
 template <typename T>
 __global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ in, int ldin, T* __restrict__ out, int ldout,
                                                         int R, int C) {
-  __shared__ T tile[64][65];
+  __shared__ T tile[64][64 + 4 / sizeof(T)];             // row pitch of an odd number of 32-bit words: no bank conflicts in either pass
   const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
 #pragma unroll

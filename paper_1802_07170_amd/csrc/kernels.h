@@ -32,9 +32,9 @@ void launch_transpose(int prec, const void* in, int ldin, void* out, int ldout, 
 // ---- ce.hip ------------------------------------------------------------------------------------
 // Eq. 1 for a slab of M <= CE_SLAB_ROWS rows (all row pointers at the slab's first row).
 // Forward: Ho [M,H] T, Wo [V,H] T, Bo [V] fp32, labels [M] int32.  Per row and group of 64
-// vocabulary columns: pmax = max z, psum = sum exp(z - pmax) ([M, np] fp32, np = ce_num_partials(V));
+// vocabulary columns: pmax = max z, psum = sum exp(z - pmax) ([np, CE_SLAB_ROWS] fp32: group-major, np = ce_num_partials(V));
 // zy [M] = the label's logit; ET [V, CE_SLAB_ROWS] T = exp(z - pmax of its group), transposed;
-// psz [M, np] = sum of z over the group (null unless label smoothing needs the row's mean logit).
+// psz (same layout) = sum of z over the group (null unless label smoothing needs the row's mean logit).
 constexpr int CE_SLAB_ROWS = 1024;
 int ce_num_partials(int V);
 size_t ce_slab_elems(int V);                                 // elements of a slab buffer (E / dz, and dzT)

@@ -58,16 +58,17 @@ void launch_gather(int prec, const void* table, int vocab, int E, const int32_t*
                           shift, bos, (float*)out, mask, tok, labels, len_p, flags);
 }
 
-// One workgroup per (position p, block of 256 columns).  If no earlier position holds the same id,
-// this workgroup sums the gradient rows of every occurrence q >= p in ascending q and stores its
-// part of the row; otherwise it exits.  Rows are fetched 8 at a time so their loads overlap.
+// One workgroup per position p.  If no earlier position holds the same id, this workgroup sums the gradient
+// rows of every occurrence q >= p in ascending q and stores the whole row (each thread owns up to two groups of
+// four consecutive columns, E <= 2048); otherwise it exits.  The occurrence scan is done once per position, and
+// rows are fetched sixteen at a time as 16-byte vectors so their loads overlap.
+constexpr int EMBED_SCATTER_MAX_E = 2048;
 __global__ __launch_bounds__(256) void embed_scatter_kernel(const float* __restrict__ dX, const int32_t* __restrict__ tok,
                                                             int n, int E, float* __restrict__ dE) {
   __shared__ int s_found;
   __shared__ int s_list[256];
   __shared__ int s_wcnt[4];
   const int p = blockIdx.x, t = threadIdx.x, lane = t & 63, w = t >> 6;
-  const int col = blockIdx.y * 256 + t;
   const int id = tok[p];
   if (id < 0) return;
   if (t == 0) s_found = 0;
@@ -76,7 +77,8 @@ __global__ __launch_bounds__(256) void embed_scatter_kernel(const float* __restr
     if (tok[q] == id) s_found = 1;
   __syncthreads();
   if (s_found) return;
-  float acc = 0.f;
+  const int eq = E >> 2;                                  // float4 groups per row
+  float4 acc[2] = {make_float4(0.f, 0.f, 0.f, 0.f), make_float4(0.f, 0.f, 0.f, 0.f)};
   for (int base = p; base < n; base += 256) {
     const int q = base + t;
     const bool match = q < n && tok[q] == id;
@@ -88,18 +90,27 @@ __global__ __launch_bounds__(256) void embed_scatter_kernel(const float* __restr
     const int total = s_wcnt[0] + s_wcnt[1] + s_wcnt[2] + s_wcnt[3];
     if (match) s_list[off + __popcll(bal & ((1ull << lane) - 1ull))] = q;
     __syncthreads();
-    if (col < E) {
-      for (int k = 0; k < total; k += 8) {
-        float v[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = k + j < total ? dX[(size_t)s_list[k + j] * E + col] : 0.f;
+    for (int g = 0; g < 2; ++g) {
+      const int c4 = t + 256 * g;
+      if (c4 < eq) {
+        for (int k = 0; k < total; k += 16) {             // 16 rows in flight: a frequent id's chain is latency-bound
+          float4 v[16];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc += v[j];
+          for (int j = 0; j < 16; ++j)
+            v[j] = k + j < total ? reinterpret_cast<const float4*>(dX + (size_t)s_list[k + j] * E)[c4] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+          for (int j = 0; j < 16; ++j) { acc[g].x += v[j].x; acc[g].y += v[j].y; acc[g].z += v[j].z; acc[g].w += v[j].w; }
+        }
       }
     }
     __syncthreads();
   }
-  if (col < E) dE[(size_t)id * E + col] = acc;
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    const int c4 = t + 256 * g;
+    if (c4 < eq) reinterpret_cast<float4*>(dE + (size_t)id * E)[c4] = acc[g];
+  }
 }
 
 __global__ __launch_bounds__(256) void fill_f32_kernel(float* __restrict__ p, size_t n, float v) {
@@ -123,7 +134,7 @@ void launch_fill_T(int prec, void* p, size_t n, hipStream_t st) {
 
 void launch_embed_scatter(const float* dX, const int32_t* tok, int n, int V, int E, float* dE, hipStream_t st) {
   launch_fill_f32(dE, (size_t)V * E, 0.f, st);
-  hipLaunchKernelGGL(embed_scatter_kernel, dim3(n, (E + 255) / 256), dim3(256), 0, st, dX, tok, n, E, dE);
+  hipLaunchKernelGGL(embed_scatter_kernel, dim3(n), dim3(256), 0, st, dX, tok, n, E, dE);   // E <= EMBED_SCATTER_MAX_E (checked with the configuration)
 }
 
 template <typename T>
