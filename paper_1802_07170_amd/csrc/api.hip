@@ -688,6 +688,14 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     launch_transpose(p, d.Hst, d.ph, d.HstT, (Lsteps + 1) * Bp, (Lsteps + 1) * Bp, d.Hh, sd);
   };
   stream_after(h, sd, st);
+  // the dense embedding gradients start from zero: cleared now, while the second stream has little to do
+  launch_fill_f32(G + h->off_Esrc, (size_t)c.src_vocab * E, 0.f, sd);
+  launch_fill_f32(G + h->off_Etgt, (size_t)c.tgt_vocab * E, 0.f, sd);
+  hipEvent_t esrc_cleared = nullptr;               // the source table's scatter runs on the caller's stream at the end
+  if (sd != st) {
+    esrc_cleared = h->ev[h->ev_next++ % h->ev.size()];
+    (void)hipEventRecord(esrc_cleared, sd);
+  }
   launch_transpose(p, h->Hoc, PH, h->HocT, Mt, Mt, H, sd);           // dense H_o rows, for dW_o
   launch_transpose(p, HoFeed, PH, h->HoBufT, ldHoT, Mt + Bp, H, sd);
   for (auto& d : h->enc) transpose_states(d, S);
@@ -842,7 +850,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
                              {e.HstT, (T + 1) * Bp}}, {H, H}, sd);
   }
   launch_gemm_nt(p, h->dec[0].dG, h->dec[0].pg, h->dec[0].Wt, 4 * H, Mt, E, 4 * H, h->dXt, nullptr, E, nullptr, 0, sd);
-  launch_embed_scatter(h->dXt, h->tok_t, Mt, c.tgt_vocab, E, G + h->off_Etgt, sd);
+  launch_embed_scatter(h->dXt, h->tok_t, Mt, c.tgt_vocab, E, G + h->off_Etgt, sd, false);
 
   // ---- attention gradients that do not feed the decoder recurrence, batched over all steps ---------
   const char* HtAll = h->dec[L - 1].Hst + BP * esz;      // H_t^{<0..T-1>}
@@ -1033,12 +1041,15 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       launch_lstm_bwd_point_multi(p, pts, 2, Bp, Hd, st);
       if (k + 1 < S) launch_step_gemm_multi(p, gs, 2, Hd, Bp, st);          // the initial state is a constant
     }
+    // What is left after the last recurrent kernel is shared between the two streams: the weight gradients of
+    // both directions on the second one, the source-embedding gradient (dX_s, then the scatter) on the caller's.
     stream_after(h, sd, st);
     weight_grads(h, ef, S, {{h->XsT, Ms}, {ef.HstT, (S + 1) * Bp}}, {E, Hd}, sd);
     weight_grads(h, eb, S, {{h->XsT, Ms}, {eb.HstT + (size_t)Bp * esz, (S + 1) * Bp}}, {E, Hd}, sd);
-    launch_gemm_nt(p, ef.dG, ef.pg, ef.Wt, 4 * Hd, Ms, E, 4 * Hd, h->dXs, nullptr, E, nullptr, 0, sd);
-    launch_gemm_nt(p, eb.dG, eb.pg, eb.Wt, 4 * Hd, Ms, E, 4 * Hd, h->dXs, nullptr, E, nullptr, 1, sd);
-    launch_embed_scatter(h->dXs, h->tok_s, Ms, c.src_vocab, E, G + h->off_Esrc, sd);
+    launch_gemm_nt(p, ef.dG, ef.pg, ef.Wt, 4 * Hd, Ms, E, 4 * Hd, h->dXs, nullptr, E, nullptr, 0, st);
+    launch_gemm_nt(p, eb.dG, eb.pg, eb.Wt, 4 * Hd, Ms, E, 4 * Hd, h->dXs, nullptr, E, nullptr, 1, st);
+    if (esrc_cleared) (void)hipStreamWaitEvent(st, esrc_cleared, 0);
+    launch_embed_scatter(h->dXs, h->tok_s, Ms, c.src_vocab, E, G + h->off_Esrc, st, false);
   }
   phase_mark(h, "wait for the second stream");
   stream_after(h, st, sd);                         // join: the step is complete on the caller's stream

@@ -205,7 +205,8 @@ void launch_gather(int prec, const void* table, int vocab, int E, const int32_t*
                    int32_t* labels, int32_t* len_p, int* flags, hipStream_t st);
 // Dense embedding gradient: dE[V,E] = 0, then row id gets the sum of dX rows of its occurrences,
 // added in ascending position order by the block of the first occurrence (no atomics).
-void launch_embed_scatter(const float* dX, const int32_t* tok, int n, int V, int E, float* dE, hipStream_t st);
+// zero_first = false: the caller has already cleared dE (e.g. earlier in the step, off the critical path).
+void launch_embed_scatter(const float* dX, const int32_t* tok, int n, int V, int E, float* dE, hipStream_t st, bool zero_first = true);
 void launch_fill_f32(float* p, size_t n, float v, hipStream_t st);
 void launch_fill_T(int prec, void* p, size_t n, hipStream_t st);      // zeros
 void launch_cast(int prec, const float* src, void* dst, size_t n, hipStream_t st);   // fp32 -> T

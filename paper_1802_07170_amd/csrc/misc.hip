@@ -132,8 +132,8 @@ void launch_fill_T(int prec, void* p, size_t n, hipStream_t st) {
   launch_fill_f32((float*)p, words, 0.f, st);
 }
 
-void launch_embed_scatter(const float* dX, const int32_t* tok, int n, int V, int E, float* dE, hipStream_t st) {
-  launch_fill_f32(dE, (size_t)V * E, 0.f, st);
+void launch_embed_scatter(const float* dX, const int32_t* tok, int n, int V, int E, float* dE, hipStream_t st, bool zero_first) {
+  if (zero_first) launch_fill_f32(dE, (size_t)V * E, 0.f, st);
   hipLaunchKernelGGL(embed_scatter_kernel, dim3(n), dim3(256), 0, st, dX, tok, n, E, dE);   // E <= EMBED_SCATTER_MAX_E (checked with the configuration)
 }
 

@@ -857,7 +857,7 @@ __global__ __launch_bounds__(256) void att_deferred_kernel(const float* __restri
                                                            int ldht, int S, int Tn, int Bp, int H, float* __restrict__ dHs,
                                                            T* __restrict__ dK) {
   constexpr int IB = ATT_DEF_IB, JB = ATT_DEF_JB;
-  __shared__ float sa[JB][IB], sd[JB][IB];
+  __shared__ __align__(16) float sa[JB][IB], sd[JB][IB];
   const int b = blockIdx.x, h = blockIdx.y * 256 + threadIdx.x, i0 = blockIdx.z * IB;
   float accC[IB], accK[IB];
 #pragma unroll
@@ -883,7 +883,12 @@ __global__ __launch_bounds__(256) void att_deferred_kernel(const float* __restri
 #pragma unroll
     for (int jj = 0; jj < JB; ++jj)                  // ascending j: the same summation order as one step at a time
 #pragma unroll
-      for (int i = 0; i < IB; ++i) { accC[i] += sa[jj][i] * dc[jj]; accK[i] += sd[jj][i] * ht[jj]; }
+      for (int i = 0; i < IB; i += 4) {              // coefficients as 16-byte LDS reads (same address in every lane)
+        const float4 ca = *reinterpret_cast<const float4*>(&sa[jj][i]);
+        const float4 cd = *reinterpret_cast<const float4*>(&sd[jj][i]);
+        accC[i] += ca.x * dc[jj]; accC[i + 1] += ca.y * dc[jj]; accC[i + 2] += ca.z * dc[jj]; accC[i + 3] += ca.w * dc[jj];
+        accK[i] += cd.x * ht[jj]; accK[i + 1] += cd.y * ht[jj]; accK[i + 2] += cd.z * ht[jj]; accK[i + 3] += cd.w * ht[jj];
+      }
   }
   if (h >= H) return;
 #pragma unroll
