@@ -30,43 +30,53 @@ __global__ __launch_bounds__(CeG::NT) void ce_fwd_kernel(const T* __restrict__ H
                                                          int M, int V, int H, T* __restrict__ ET, int ldet,
                                                          float* __restrict__ pmax, float* __restrict__ psum,
                                                          float* __restrict__ psz, float* __restrict__ zy, int np, RowLimit lim) {
-  __shared__ __align__(16) char smem[CeG::SMEM_BYTES + 1024];   // main-loop stages; afterwards 1 KB of bias + the staged e tile
+  __shared__ __align__(16) char smem[CeG::SMEM_BYTES];    // main-loop stages; afterwards the staged e tile
   if (lim.n) M = min(M, max(*lim.n - lim.base, 0));       // rows that exist (uniform over the grid)
   if (M <= 0) return;
   int v0, r0;                                             // tile: vocabulary rows v0.., target positions r0..
   if (!gemm_tile_of_block((V + CeG::BM - 1) / CeG::BM, (M + CeG::BN - 1) / CeG::BN, CeG::BM, CeG::BN, v0, r0)) return;
-  v16f acc[2][2];
-  gemm_mainloop<T, 4, 4, 2, 2, 128>(Wo, H, Ho, ldho, V, M, H, v0, r0, acc, smem);
-  float* sbo = reinterpret_cast<float*>(smem);            // the main loop ends with a barrier: LDS is free
-  if (threadIdx.x < CeG::BM) sbo[threadIdx.x] = v0 + (int)threadIdx.x < V ? Bo[v0 + threadIdx.x] : 0.f;
-  __syncthreads();
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int wm = w >> 2, wn = w & 3;
+  // the accumulators start from the bias of their vocabulary entries, so the main loop leaves the logits
+  v16f acc[2][2];
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int v = v0 + wm * 64 + mt * 32 + acc32_row(lane, i);
+      const float bv = v < V ? Bo[v] : 0.f;
+      acc[mt][0][i] = bv; acc[mt][1][i] = bv;
+    }
+  gemm_mainloop<T, 4, 4, 2, 2, 128, false>(Wo, H, Ho, ldho, V, M, H, v0, r0, acc, smem);   // ends with a barrier: LDS is free
   const int pidx = (v0 >> 6) + wm;                        // this wavefront's group of 64 vocabulary entries
   // e leaves through LDS: every wavefront stages its 64 vocabulary entries x 64 (fp32: 32) target positions
   // and writes them out as whole rows of E^T — 128 contiguous bytes per row instead of the 64-byte pieces of
   // the accumulator layout
   constexpr int NTS = sizeof(T) == 2 ? 2 : 1;             // 32-position halves staged together
   constexpr int SROW = 32 * NTS * (int)sizeof(T) + 16;    // staged row pitch in bytes (padded against bank conflicts)
-  char* stage = smem + 1024 + w * (64 * SROW);
-  static_assert(1024 + 16 * 64 * SROW <= CeG::SMEM_BYTES + 1024, "staging area exceeds the kernel's LDS");
+  char* stage = smem + w * (64 * SROW);
+  static_assert(16 * 64 * SROW <= CeG::SMEM_BYTES, "staging area exceeds the kernel's LDS");
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
     const int r = r0 + wn * 64 + nt * 32 + (lane & 31);
     const int y = r < M ? labels[r] : -1;
-    float z[2][16];
-    float mx = -INFINITY, sz = 0.f;
+    // the logits overwrite the accumulators of this half (nothing else needs them): no second register array
+    float mx = -INFINITY, sz = 0.f, zlab = 0.f;
+    const int yl = y - v0 - wm * 64;                      // the label's place among this wavefront's 64 entries, if any
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int vl = wm * 64 + mt * 32 + acc32_row(lane, i);
         const bool in = v0 + vl < V;
-        z[mt][i] = in ? acc[mt][nt][i] + sbo[vl] : -INFINITY;
-        if (in) sz += z[mt][i];
-        if (v0 + vl == y) zy[r] = z[mt][i];
-        mx = fmaxf(mx, z[mt][i]);
+        const float zv = in ? acc[mt][nt][i] : -INFINITY;
+        acc[mt][nt][i] = zv;
+        sz += in ? zv : 0.f;
+        zlab = (mt * 32 + acc32_row(lane, i) == yl) ? zv : zlab;
+        mx = fmaxf(mx, zv);
       }
+    // one of the two lanes that share position r holds the label's entry: rows 8 (i / 4) + 4 (lane / 32) + i % 4
+    if (y >= 0 && yl >= 0 && yl < 64 && ((yl >> 2) & 1) == (lane >> 5)) zy[r] = zlab;
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     float e = 0.f;
 #pragma unroll
@@ -74,7 +84,7 @@ __global__ __launch_bounds__(CeG::NT) void ce_fwd_kernel(const T* __restrict__ H
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int vl = mt * 32 + acc32_row(lane, i);
-        const float ev = mx > -INFINITY ? expf(z[mt][i] - mx) : 0.f;      // exp(-inf) = 0 past the vocabulary
+        const float ev = mx > -INFINITY ? expf(acc[mt][nt][i] - mx) : 0.f;   // exp(-inf) = 0 past the vocabulary
         e += ev;
         *reinterpret_cast<T*>(stage + vl * SROW + ((nt % NTS) * 32 + (lane & 31)) * sizeof(T)) = from_f<T>(ev);
       }
@@ -83,7 +93,7 @@ __global__ __launch_bounds__(CeG::NT) void ce_fwd_kernel(const T* __restrict__ H
       constexpr int CPR = 32 * NTS * (int)sizeof(T) / 16; // 16-byte chunks per staged row
       constexpr int RPP = 64 / CPR;                       // rows per pass
       const int rbase = r0 + wn * 64 + (nt / NTS) * 32 * NTS;
-#pragma unroll
+#pragma unroll 2
       for (int ps = 0; ps < 64 / RPP; ++ps) {
         const int vl = ps * RPP + lane / CPR, ch = lane % CPR;
         const int v = v0 + wm * 64 + vl;

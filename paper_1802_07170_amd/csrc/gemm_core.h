@@ -73,7 +73,8 @@ __device__ __forceinline__ void gemm_store_tile(char* tile, const uint4 (&regs)[
 
 // With w = wavefront index, wm = w / WN, wn = w % WN:
 // acc[a][b]: rows m0 + (wm*TA + a)*32 + acc32_row(lane,i), cols n0 + (wn*TB + b)*32 + lane%32
-template <typename T, int WM, int WN, int TA, int TB, int KB>
+// ZERO = false: the accumulators come in initialised by the caller (e.g. with a bias) and are added to.
+template <typename T, int WM, int WN, int TA, int TB, int KB, bool ZERO = true>
 __device__ __forceinline__ void gemm_mainloop(const T* __restrict__ A, int lda, const T* __restrict__ B, int ldb,
                                               int M, int N, int K, int m0, int n0, v16f (&acc)[TA][TB], char* smem) {
   using G = GemmTile<WM, WN, TA, TB, KB>;
@@ -82,12 +83,14 @@ __device__ __forceinline__ void gemm_mainloop(const T* __restrict__ A, int lda, 
   constexpr int GEMM_ROWB = G::ROWB;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int wm = w / WN, wn = w % WN;
+  if (ZERO) {
 #pragma unroll
-  for (int a = 0; a < TA; ++a)
+    for (int a = 0; a < TA; ++a)
 #pragma unroll
-    for (int b = 0; b < TB; ++b)
+      for (int b = 0; b < TB; ++b)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+        for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+  }
 
   uint4 ra[G::BM * KB / 16 / NT], rb[G::BN * KB / 16 / NT];
   gemm_load_tile<T, NT, G::BM, KB>(A, lda, M, K, m0, 0, ra);
