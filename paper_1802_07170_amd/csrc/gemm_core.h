@@ -46,19 +46,33 @@ __device__ __forceinline__ bool gemm_tile_of_block(int ntm, int ntn, int bm, int
   return true;
 }
 
+// Global -> register half of a tile copy.  The rows a thread fetches do not change from one k tile to the next, so
+// their offsets from the tile's first element (32-bit, element units; rows beyond `rows` are clamped to the last
+// one — they are never stored) are computed once (gemm_tile_offsets) and every load is "uniform base + 32-bit
+// thread offset": no 64-bit per-thread addresses are kept across the main loop.
 template <typename T, int NT, int ROWS, int KB>
-__device__ __forceinline__ void gemm_load_tile(const T* __restrict__ P, int ld, int rows, int K, int r0, int k0,
-                                               uint4 (&regs)[ROWS * KB / 16 / NT]) {
+__device__ __forceinline__ void gemm_tile_offsets(int ld, int rows, int r0, unsigned (&off)[ROWS * KB / 16 / NT]) {
   constexpr int EPC = 16 / sizeof(T);                     // elements per 16-byte chunk
   constexpr int CPR = KB / 16;                            // chunks per row
   constexpr int RPP = NT / CPR;                           // rows per pass
   const int t = threadIdx.x;
-  const int kc = k0 + (t % CPR) * EPC;
 #pragma unroll
   for (int p = 0; p < ROWS / RPP; ++p) {
     int r = r0 + (t / CPR) + RPP * p;
-    r = r < rows ? r : rows - 1;                          // clamped rows are never stored
-    if (kc < K) regs[p] = *reinterpret_cast<const uint4*>(P + (size_t)r * ld + kc);
+    r = r < rows ? r : rows - 1;
+    off[p] = (unsigned)(r - r0) * (unsigned)ld + (unsigned)((t % CPR) * EPC);
+  }
+}
+// base = first element of the tile row r0 at the k tile's first column (uniform); kleft = K - k0.
+template <typename T, int NT, int ROWS, int KB>
+__device__ __forceinline__ void gemm_load_tile(const T* __restrict__ base, const unsigned (&off)[ROWS * KB / 16 / NT], int kleft,
+                                               uint4 (&regs)[ROWS * KB / 16 / NT]) {
+  constexpr int EPC = 16 / sizeof(T);
+  constexpr int CPR = KB / 16;
+  const bool in = (int)((threadIdx.x % CPR) * EPC) < kleft;
+#pragma unroll
+  for (int p = 0; p < ROWS * KB / 16 / NT; ++p) {
+    if (in) regs[p] = *reinterpret_cast<const uint4*>(base + off[p]);
     else regs[p] = make_uint4(0, 0, 0, 0);
   }
 }
@@ -93,8 +107,13 @@ __device__ __forceinline__ void gemm_mainloop(const T* __restrict__ A, int lda, 
   }
 
   uint4 ra[G::BM * KB / 16 / NT], rb[G::BN * KB / 16 / NT];
-  gemm_load_tile<T, NT, G::BM, KB>(A, lda, M, K, m0, 0, ra);
-  gemm_load_tile<T, NT, G::BN, KB>(B, ldb, N, K, n0, 0, rb);
+  unsigned oa[G::BM * KB / 16 / NT], ob[G::BN * KB / 16 / NT];
+  gemm_tile_offsets<T, NT, G::BM, KB>(lda, M, m0, oa);
+  gemm_tile_offsets<T, NT, G::BN, KB>(ldb, N, n0, ob);
+  const T* __restrict__ pa = A + (size_t)m0 * lda;        // uniform: first row of the tile
+  const T* __restrict__ pb = B + (size_t)n0 * ldb;
+  gemm_load_tile<T, NT, G::BM, KB>(pa, oa, K, ra);
+  gemm_load_tile<T, NT, G::BN, KB>(pb, ob, K, rb);
   gemm_store_tile<NT, G::BM, KB>(smem, ra);
   gemm_store_tile<NT, G::BN, KB>(smem + G::A_BYTES, rb);
   __syncthreads();
@@ -104,8 +123,8 @@ __device__ __forceinline__ void gemm_mainloop(const T* __restrict__ A, int lda, 
     char* nxt = smem + ((kt + 1) & 1) * G::STAGE_BYTES;
     const bool more = kt + 1 < nk;
     if (more) {
-      gemm_load_tile<T, NT, G::BM, KB>(A, lda, M, K, m0, (kt + 1) * BK, ra);
-      gemm_load_tile<T, NT, G::BN, KB>(B, ldb, N, K, n0, (kt + 1) * BK, rb);
+      gemm_load_tile<T, NT, G::BM, KB>(pa + (kt + 1) * BK, oa, K - (kt + 1) * BK, ra);
+      gemm_load_tile<T, NT, G::BN, KB>(pb + (kt + 1) * BK, ob, K - (kt + 1) * BK, rb);
     }
     const char* ta = cur + (wm * 32 * TA + (lane & 31)) * GEMM_ROWB + (lane >> 5) * 8 * sizeof(T);
     const char* tb = cur + G::A_BYTES + (wn * 32 * TB + (lane & 31)) * GEMM_ROWB + (lane >> 5) * 8 * sizeof(T);
