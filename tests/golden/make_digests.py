@@ -6,7 +6,7 @@ the seeded inputs; nothing here comes from the HIP path.
 
 A spec is name[:scale][:flags].  ":scale" draws the same parameters at uniform[-scale, scale) instead
 of the workload's [-0.1, 0.1): at hidden size 1024 the 0.1 initialisation makes the recurrences
-chaotic (rounding the weights to bf16 alone moves the exact gradient by 15-30 %), so the bf16 path is
+chaotic (rounding the operands to bf16 moves the exact gradient by 9-22 % and more), so the bf16 path is
 also checked at the full shapes with a well-conditioned initialisation.  Flags (comma separated):
   reg   the step with the paper's regularisation: dropout 0.2, label smoothing 0.1 (mask seed REG_SEED);
   sens  a second oracle run under the oracle's bf16 precision model (every parameter and every

@@ -16,10 +16,11 @@ Three kinds of case:
   * fp32 path on the medium workload exactly as specified (uniform[-0.1, 0.1)): bar 1e-4.  This
     pins the schedule, indexing and tiling at the benchmark's shapes.
   * bf16 path on medium / large exactly as specified ("sens" mode).  At hidden size 1024 the
-    [-0.1, 0.1) initialisation makes the recurrences chaotic: rounding the weights to bf16 alone
-    moves the EXACT gradient by s = |g(bf16 W) - g(W)| / |g(W)| = 10-19 % per tensor at the medium
-    workload and by about 100 % at the large one's 80 steps (tests/test_oracle_conditioning.py shows
-    the effect on the CPU; the digest stores s per tensor, computed by the oracle alone).  No method
+    [-0.1, 0.1) initialisation makes the recurrences chaotic: under the oracle's bf16 precision model
+    (parameters and every contraction operand rounded to bfloat16, sums exact) the EXACT gradient moves
+    by s = |g_bf16 - g| / |g| = 9-22 % per tensor at the medium workload and by about 100 % at the
+    large one's 80 steps (tests/test_oracle_conditioning.py shows the effect on the CPU; the digest
+    stores s per tensor, computed by the oracle alone).  No method
     whose operands are bf16 can be closer to g(W) than that, so here every gradient tensor is held to
     a bound RELATIVE TO ITS OWN SENSITIVITY: relative L2 error over the kept entries
     <= max(2e-2, SENS_C * s), and cosine with the oracle's entries >= 1 - (SENS_C * s)^2 / 2 - 1e-3

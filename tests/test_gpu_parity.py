@@ -184,6 +184,32 @@ def test_extreme_configurations(prec, B, S, T, H, E, L, Vs, Vt):
 
 
 @pytest.mark.parametrize("prec", [0, 1])
+@pytest.mark.parametrize("forms", [0, 2, 7])
+@pytest.mark.parametrize("B,S,T,H,E,L", [(19, 9, 8, 80, 40, 3), (64, 6, 7, 256, 64, 2), (70, 5, 4, 48, 16, 2)])
+def test_every_form_of_the_backward_loops(prec, forms, B, S, T, H, E, L, monkeypatch):
+    """The three backward loops (decoder, upper encoder layers, bottom encoder layer) each exist as a
+    step GEMM with its consumer in the epilogue and as a k-split GEMM followed by a pointwise kernel; the
+    library picks per loop and batch width.  CMT_BWD_FUSED (read when the handle is created) forces the
+    choice: all three pointwise (0), the upper encoder fused alone (2), all three fused (7, the decoder
+    only up to 64 sentences).  Every form meets the same bars against the oracle, and the gradients of the
+    forms agree with each other to rounding order (same products, different summation order)."""
+    cfg = dict(src_vocab=104, tgt_vocab=136, emb=E, hidden=H, layers=L)
+    rng = np.random.default_rng(700 + B)
+    params = I.make_params(cfg, seed=B + 1, scale=0.3 if H <= 128 else 0.05)
+    batch = ragged_batch(rng, B, S, T, cfg["src_vocab"], cfg["tgt_vocab"])
+    monkeypatch.setenv("CMT_BWD_FUSED", str(forms))
+    loss, oloss, worst, tr = run_case(cfg, params, batch, prec)
+    g = tr.get_grads().copy()
+    tr.close()
+    monkeypatch.delenv("CMT_BWD_FUSED")
+    loss0, _, _, tr0 = run_case(cfg, params, batch, prec, check_inter=False)
+    g0 = tr0.get_grads().copy()
+    tr0.close()
+    assert loss == loss0                                       # the forward pass does not depend on the form
+    assert np.linalg.norm(g - g0) <= (1e-5 if prec == 0 else 1e-2) * np.linalg.norm(g0)
+
+
+@pytest.mark.parametrize("prec", [0, 1])
 def test_batches_of_different_shape_in_turn_on_one_handle(prec):
     """A large batch, then a small one with far fewer valid target positions, then the large one again,
     all on the same handle: nothing one step leaves in the workspace (rows beyond the valid positions of
