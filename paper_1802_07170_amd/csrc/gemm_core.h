@@ -9,7 +9,10 @@
 //     Half the L2 traffic per flop: 1.1 PFLOP/s on large problems, and faster than the small tile
 //     whenever there are about 200 or more tiles.
 // Tiles of KB bytes of k per row are double-buffered in LDS; the next tile's global loads are in
-// flight while the current one feeds the matrix cores.
+// flight while the current one feeds the matrix cores.  16-bit operands go from global memory straight
+// into LDS (global_load_lds_dwordx4, no staging registers): rows of 128 bytes without padding, the
+// 16-byte chunks of a row XOR-swizzled by the row number so that fragment reads stay free of bank
+// conflicts (gemm_swz).  32-bit operands are staged through registers into rows padded by 16 bytes.
 #pragma once
 #include "common.h"
 
@@ -85,12 +88,123 @@ __device__ __forceinline__ void gemm_store_tile(char* tile, const uint4 (&regs)[
     *reinterpret_cast<uint4*>(tile + ((t / CPR) + RPP * p) * (KB + 16) + (t % CPR) * 16) = regs[p];
 }
 
+// ---- 16-bit operands: global -> LDS without staging registers ----
+// LDS image of a tile: row r (128 bytes = 64 elements of k) at r * 128; the 16-byte chunk c of the row sits at
+// position c ^ gemm_swz(r).  A load instruction of wavefront w writes 64 consecutive 16-byte slots (the hardware
+// adds lane * 16 to the base in M0), so slot (p * NT + thread) holds row slot / 8, position slot % 8, and the
+// thread fetches the chunk that belongs there.
+__device__ __forceinline__ int gemm_swz(int r) { return (r ^ (r >> 3)) & 7; }
+
+// byte offsets from the tile's first row at the k tile's first column; rows beyond `rows` clamped (never stored)
+template <int NT, int ROWS>
+__device__ __forceinline__ void gemm_dl_offsets(int ld, int rows, int r0, unsigned (&off)[ROWS * 8 / NT]) {
+  static_assert((ROWS * 8) % NT == 0, "tile rows must fill whole passes of the workgroup");
+#pragma unroll
+  for (int p = 0; p < ROWS * 8 / NT; ++p) {
+    const int slot = p * NT + threadIdx.x, r = slot >> 3, c = (slot & 7) ^ gemm_swz(r);
+    const int row = min(r0 + r, rows - 1) - r0;
+    off[p] = ((unsigned)row * (unsigned)ld + (unsigned)(c * 8)) * 2u;
+  }
+}
+__device__ __forceinline__ unsigned gemm_lds_address(const char* p) {
+  return (unsigned)(size_t)(__attribute__((address_space(3))) const char*)p;
+}
+// Asynchronous: completion is awaited with gemm_dl_wait() before the barrier that publishes the stage.
+// The instruction is written out because the compiler, when it knows a load writes LDS, waits for every
+// outstanding one before the next LDS read of any address — which would serialise the two stages.
+template <int NT, int ROWS>
+__device__ __forceinline__ void gemm_dl_issue(const bf16_t* __restrict__ base, const unsigned (&off)[ROWS * 8 / NT], char* tile, int w) {
+#pragma unroll
+  for (int p = 0; p < ROWS * 8 / NT; ++p) {
+    const unsigned dst = gemm_lds_address(tile) + (unsigned)((p * NT + w * 64) * 16);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(off[p]), "s"(base) : "memory");
+  }
+}
+__device__ __forceinline__ void gemm_dl_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// A k tile with fewer than 64 valid columns (the last one of a K that is no multiple of 64): through registers,
+// chunks beyond K as zeros, into the same LDS image.
+template <int NT, int ROWS>
+__device__ __forceinline__ void gemm_dl_fill_tail(const bf16_t* __restrict__ base, const unsigned (&off)[ROWS * 8 / NT], int kleft, char* tile) {
+#pragma unroll
+  for (int p = 0; p < ROWS * 8 / NT; ++p) {
+    const int slot = p * NT + threadIdx.x, r = slot >> 3, c = (slot & 7) ^ gemm_swz(r);
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (c * 8 < kleft) v = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(base) + off[p]);
+    *reinterpret_cast<uint4*>(tile + slot * 16) = v;
+  }
+}
+
+template <int WM, int WN, int TA, int TB, bool ZERO>
+__device__ __forceinline__ void gemm_mainloop_dl(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B, int ldb,
+                                                 int M, int N, int K, int m0, int n0, v16f (&acc)[TA][TB], char* smem) {
+  constexpr int NT = 64 * WM * WN, BM = 32 * TA * WM, BN = 32 * TB * WN;
+  constexpr int A_BYTES = BM * 128, STAGE = (BM + BN) * 128;
+  static_assert(2 * STAGE <= GemmTile<WM, WN, TA, TB, 128>::SMEM_BYTES, "LDS image larger than the tile's allocation");
+  const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = w / WN, wn = w % WN;
+  if (ZERO) {
+#pragma unroll
+    for (int a = 0; a < TA; ++a)
+#pragma unroll
+      for (int b = 0; b < TB; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+  }
+  unsigned oa[BM * 8 / NT], ob[BN * 8 / NT];
+  gemm_dl_offsets<NT, BM>(lda, M, m0, oa);
+  gemm_dl_offsets<NT, BN>(ldb, N, n0, ob);
+  const bf16_t* __restrict__ pa = A + (size_t)m0 * lda;    // uniform: first row of the tile
+  const bf16_t* __restrict__ pb = B + (size_t)n0 * ldb;
+  auto fill = [&](char* stage, int k0) {
+    if (K - k0 >= 64) {
+      gemm_dl_issue<NT, BM>(pa + k0, oa, stage, w);
+      gemm_dl_issue<NT, BN>(pb + k0, ob, stage + A_BYTES, w);
+    } else {
+      gemm_dl_fill_tail<NT, BM>(pa + k0, oa, K - k0, stage);
+      gemm_dl_fill_tail<NT, BN>(pb + k0, ob, K - k0, stage + A_BYTES);
+    }
+  };
+  fill(smem, 0);
+  gemm_dl_wait();
+  __syncthreads();
+  // fragment of row r at k step ks: chunk 2 ks + lane / 32, at position chunk ^ gemm_swz(r)
+  int fa_row[TA], fa_s[TA], fb_row[TB], fb_s[TB];
+#pragma unroll
+  for (int x = 0; x < TA; ++x) { const int r = (wm * TA + x) * 32 + (lane & 31); fa_row[x] = r * 128; fa_s[x] = gemm_swz(r) ^ (lane >> 5); }
+#pragma unroll
+  for (int x = 0; x < TB; ++x) { const int r = (wn * TB + x) * 32 + (lane & 31); fb_row[x] = A_BYTES + r * 128; fb_s[x] = gemm_swz(r) ^ (lane >> 5); }
+  const int nk = (K + 63) / 64;
+  for (int kt = 0; kt < nk; ++kt) {
+    char* cur = smem + (kt & 1) * STAGE;
+    char* nxt = smem + ((kt + 1) & 1) * STAGE;
+    if (kt + 1 < nk) fill(nxt, (kt + 1) * 64);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      Frag<bf16_t> fa[TA], fb[TB];
+#pragma unroll
+      for (int x = 0; x < TA; ++x) fa[x].load(reinterpret_cast<const bf16_t*>(cur + fa_row[x] + ((fa_s[x] ^ (2 * ks)) << 4)));
+#pragma unroll
+      for (int x = 0; x < TB; ++x) fb[x].load(reinterpret_cast<const bf16_t*>(cur + fb_row[x] + ((fb_s[x] ^ (2 * ks)) << 4)));
+#pragma unroll
+      for (int a = 0; a < TA; ++a)
+#pragma unroll
+        for (int b = 0; b < TB; ++b) mma32(acc[a][b], fa[a], fb[b]);
+    }
+    gemm_dl_wait();
+    __syncthreads();
+  }
+}
+
 // With w = wavefront index, wm = w / WN, wn = w % WN:
 // acc[a][b]: rows m0 + (wm*TA + a)*32 + acc32_row(lane,i), cols n0 + (wn*TB + b)*32 + lane%32
 // ZERO = false: the accumulators come in initialised by the caller (e.g. with a bias) and are added to.
 template <typename T, int WM, int WN, int TA, int TB, int KB, bool ZERO = true>
 __device__ __forceinline__ void gemm_mainloop(const T* __restrict__ A, int lda, const T* __restrict__ B, int ldb,
                                               int M, int N, int K, int m0, int n0, v16f (&acc)[TA][TB], char* smem) {
+  if constexpr (sizeof(T) == 2 && KB == 128) {
+    gemm_mainloop_dl<WM, WN, TA, TB, ZERO>(A, lda, B, ldb, M, N, K, m0, n0, acc, smem);
+    return;
+  }
   using G = GemmTile<WM, WN, TA, TB, KB>;
   constexpr int NT = G::NT;
   constexpr int BK = KB / sizeof(T);
