@@ -66,18 +66,35 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_kernel(const T* __restri
   }
 }
 
-// out = sum of planes (+ bias per column) (+ previous out)
+// out = sum of planes (+ bias per column) (+ previous out).  VEC = 4: four consecutive columns per thread as one
+// 16-byte access per plane (N, ldc and the plane stride multiples of 4, all bases 16-byte aligned).
+template <int VEC>
 __global__ __launch_bounds__(256) void gemm_planes_sum_kernel(const float* __restrict__ planes, int np, size_t stride,
                                                               float* __restrict__ out, int M, int N, int ldc,
                                                               const float* __restrict__ bias, int accumulate, RowLimit lim) {
   if (lim.n) M = min(M, max(*lim.n - lim.base, 0));
-  const size_t n = (size_t)M * N;
+  const unsigned nq = (unsigned)N / VEC;                  // column groups per row
+  const size_t n = (size_t)M * nq;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
-    const size_t r = i / N, c = i - r * N;
-    float v = bias ? bias[c] : 0.f;
-    for (int p = 0; p < np; ++p) v += planes[(size_t)p * stride + i];
-    float* o = out + r * ldc + c;
-    *o = accumulate ? *o + v : v;
+    const unsigned r = (unsigned)(i / nq), c = ((unsigned)i - r * nq) * VEC;
+    const float* src = planes + (size_t)r * N + c;
+    float* o = out + (size_t)r * ldc + c;
+    if (VEC == 4) {
+      float4 v = bias ? *reinterpret_cast<const float4*>(bias + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int p = 0; p < np; ++p) {
+        const float4 a = *reinterpret_cast<const float4*>(src + (size_t)p * stride);
+        v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
+      }
+      if (accumulate) {
+        const float4 a = *reinterpret_cast<const float4*>(o);
+        v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
+      }
+      *reinterpret_cast<float4*>(o) = v;
+    } else {
+      float v = bias ? bias[c] : 0.f;
+      for (int p = 0; p < np; ++p) v += src[(size_t)p * stride];
+      *o = accumulate ? *o + v : v;
+    }
   }
 }
 
@@ -124,10 +141,16 @@ void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, in
   if (prec) gemm_go<bf16_t, 2, 2, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, out, Ct, oldc, obias, oacc, ntn, kchunk, pstride, lim, lim_kind);
   else gemm_go<float, 2, 2, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, out, Ct, oldc, obias, oacc, ntn, kchunk, pstride, lim, lim_kind);
   if (nks > 1) {
-    size_t g = (pstride + 255) / 256;
+    const bool vec = N % 4 == 0 && ldc % 4 == 0 && pstride % 4 == 0 && ((size_t)Cf | (size_t)split_scratch | (size_t)bias) % 16 == 0;
+    size_t g = (pstride / (vec ? 4 : 1) + 255) / 256;
     if (g > 4096) g = 4096;
-    hipLaunchKernelGGL(gemm_planes_sum_kernel, dim3((unsigned)g), dim3(256), 0, st, split_scratch, nks, pstride, Cf, M, N, ldc,
-                       bias, accumulate, lim_kind == 1 ? lim : RowLimit{});
+    const RowLimit rl = lim_kind == 1 ? lim : RowLimit{};
+    if (vec)
+      hipLaunchKernelGGL(gemm_planes_sum_kernel<4>, dim3((unsigned)g), dim3(256), 0, st, split_scratch, nks, pstride, Cf, M, N, ldc,
+                         bias, accumulate, rl);
+    else
+      hipLaunchKernelGGL(gemm_planes_sum_kernel<1>, dim3((unsigned)g), dim3(256), 0, st, split_scratch, nks, pstride, Cf, M, N, ldc,
+                         bias, accumulate, rl);
   }
 }
 
