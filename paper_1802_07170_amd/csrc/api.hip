@@ -59,6 +59,14 @@ struct LD {
 // padding with 64 elements instead: 11.6 us against 9.8 us, 32 / 72 / 136 elements: 10.0 - 10.2 us).
 constexpr int ACT_PAD = 8;
 
+// Row capacity of an output-layer slab: CE_SLAB_MAX_ROWS unless CMT_CE_SLAB_ROWS asks for less (a multiple of 256
+// from 256 up; read whenever a handle or a size query is set up, so both see the same value).
+static int ce_cap_env() {
+  const char* e = getenv("CMT_CE_SLAB_ROWS");
+  const int v = e ? atoi(e) / 256 * 256 : 0;
+  return v >= 256 ? std::min(CE_SLAB_MAX_ROWS, v) : CE_SLAB_MAX_ROWS;
+}
+
 struct Bump {
   char* base; size_t off = 0;
   explicit Bump(char* b) : base(b) {}
@@ -114,6 +122,8 @@ struct cmt_handle {
   char* Hoc = nullptr; char* HocT = nullptr;   // H_o (as the output layer sees it) of the valid positions, and its transpose
   float* loss = nullptr; int* flags = nullptr; float* colscr = nullptr;
   char* dzs = nullptr; char* dzTs = nullptr; float* dbo_parts = nullptr;
+  int ce_rows = 0, ce_pitch = 0;        // row capacity of an output-layer slab and the row pitch of its buffers
+  int ce_cap = ce_cap_env();            // upper bound of ce_rows
   float* gsplit = nullptr; size_t gsplit_floats = 0;
   hipStream_t side = nullptr;           // library-owned second stream for work off the recurrences' critical path
   std::vector<hipEvent_t> ev; size_t ev_next = 0;
@@ -277,9 +287,13 @@ size_t layout(cmt_handle* h, char* base) {
   h->wcp = (float*)a.take((size_t)8 * Bp * 2 * H * 4);
   h->dXt = (float*)a.take(Mt * E * 4);
   const int np = ce_num_partials(c.tgt_vocab);
-  {   // per slab of CE_SLAB_ROWS positions a [np, CE_SLAB_ROWS] block of partials (slab sl starts at sl * CE_SLAB_ROWS * np)
-    const size_t slabs = (Mt + CE_SLAB_ROWS - 1) / CE_SLAB_ROWS;
-    const size_t bytes = slabs * CE_SLAB_ROWS * np * 4;
+  // output-layer slabs: one slab for the whole batch up to the cap, else full slabs of the cap and a remainder
+  h->ce_rows = (int)std::min<size_t>((size_t)h->ce_cap, (Mt + 255) / 256 * 256);
+  h->ce_pitch = ce_slab_pitch(h->ce_rows);
+  const size_t ce_slabs = (Mt + h->ce_rows - 1) / h->ce_rows;
+  const size_t slab_elems = (size_t)h->ce_pitch * c.tgt_vocab;      // elements of a slab buffer (e / dz, and dz^T)
+  {   // per slab a [np, pitch] block of partials (slab sl starts at sl * np * pitch)
+    const size_t bytes = ce_slabs * h->ce_pitch * np * 4;
     h->pmax = (float*)a.take(bytes); h->psum = (float*)a.take(bytes); h->psz = (float*)a.take(bytes);
   }
   h->zy = (float*)a.take(Mt * 4); h->lse = (float*)a.take(Mt * 4); h->nll = (float*)a.take(Mt * 4);
@@ -289,17 +303,21 @@ size_t layout(cmt_handle* h, char* base) {
   h->Hoc = a.take(Mt * PH * esz); h->HocT = a.take(Mt * H * esz);
   h->loss = (float*)a.take(256); h->flags = (int*)a.take(256);
   h->colscr = (float*)a.take((size_t)16 * 4 * H * 4);
-  h->dzs = a.take(ce_slab_elems(c.tgt_vocab) * esz); h->dzTs = a.take(ce_slab_elems(c.tgt_vocab) * esz);
+  h->dzs = a.take(slab_elems * esz); h->dzTs = a.take(slab_elems * esz);
   h->dbo_parts = (float*)a.take((Mt / 64 + Mt / 256 + 4) * c.tgt_vocab * 4);
   {   // split-k planes of the small-output GEMMs (dH_o of a slab, weight-gradient segments): room for 16 planes
       // of the largest such output, at most 32 MB
-    const size_t slab_rows = Mt < (size_t)CE_SLAB_ROWS ? Mt : (size_t)CE_SLAB_ROWS;
+    const size_t slab_rows = std::min<size_t>(Mt, (size_t)h->ce_rows);
     const size_t out_max = std::max(slab_rows * H, (size_t)4 * H * std::max(E, H));
-    h->gsplit_floats = std::min((size_t)8 * CE_SLAB_ROWS * 1024, 16 * out_max);
+    h->gsplit_floats = std::min((size_t)8 << 20, 16 * out_max);
   }
   h->gsplit = (float*)a.take(h->gsplit_floats * 4);
   h->gsplit2 = (float*)a.take(h->gsplit_floats * 4);
-  h->dzs2 = a.take(ce_slab_elems(c.tgt_vocab) * esz); h->dzTs2 = a.take(ce_slab_elems(c.tgt_vocab) * esz);
+  if (ce_slabs > 1) {                             // a second pair, so that slab s + 1 starts while dW_o of slab s still runs
+    h->dzs2 = a.take(slab_elems * esz); h->dzTs2 = a.take(slab_elems * esz);
+  } else {
+    h->dzs2 = h->dzs; h->dzTs2 = h->dzTs;
+  }
   return (a.off + 255) & ~(size_t)255;
 }
 
@@ -379,13 +397,11 @@ void phase_mark(cmt_handle* h, const char* name) {
   (void)hipEventRecord(h->phase_ev[h->phase_n++], h->st);
 }
 
-// The output layer's slabs: full slabs of CE_SLAB_ROWS rows and one remainder.  With 256 x 256 logit
-// tiles a full slab gives (V / 256) * 4 tiles, close to a whole number of rounds over the 256 CUs for
-// the vocabulary sizes of interest (32000: 500 tiles = 1.95 rounds), which equal-sized smaller slabs
-// do not (768 rows: 375 tiles = 1.46 rounds).  Returns the rows of all slabs but the last.
-int ce_slab_plan(int Mt, int* nslab_out) {
-  *nslab_out = (Mt + CE_SLAB_ROWS - 1) / CE_SLAB_ROWS;
-  return CE_SLAB_ROWS;
+// The output layer's slabs: full slabs of the handle's slab capacity and one remainder (a single slab whenever
+// the batch fits).  Returns the rows of all slabs but the last.
+int ce_slab_plan(const cmt_handle* h, int Mt, int* nslab_out) {
+  *nslab_out = (Mt + h->ce_rows - 1) / h->ce_rows;
+  return h->ce_rows;
 }
 
 // dropout sites (the oracle and the tests use the same numbering): encoder layer l output, decoder
@@ -662,16 +678,16 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   launch_ce_gather_rows(p, Ho, PH, h->ce_row, h->ce_nvalid, Mt, h->Hoc, PH, H, st);
   if (forward_only) {                              // Eq. 1 and the loss only: logits slab by slab, no gradient
     int nslab;
-    const int rows = ce_slab_plan(Mt, &nslab);
+    const int rows = ce_slab_plan(h, Mt, &nslab);
     int sl = 0;
     for (int m0 = 0; m0 < Mt; ++sl) {
       const int Mc = (sl == nslab - 1 || Mt - m0 < rows) ? Mt - m0 : rows;
       const RowLimit lim{h->ce_nvalid, m0};
+      const size_t po = (size_t)sl * np * h->ce_pitch;       // this slab's block of partials
       launch_ce_fwd(p, h->Hoc + (size_t)m0 * PH * esz, PH, h->Pw(h->off_Wo), P + h->off_Bo, h->labels_c + m0, Mc, V, H, h->dzTs,
-                    h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, h->ls_eps > 0.f ? h->psz + (size_t)m0 * np : nullptr,
-                    h->zy + m0, st, lim);
-      launch_ce_rows(h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, h->psz + (size_t)m0 * np, h->zy + m0,
-                     nullptr, Mc, np, h->ls_eps, V, h->lse + m0, h->nll + m0, st, lim);
+                    h->ce_pitch, h->pmax + po, h->psum + po, h->ls_eps > 0.f ? h->psz + po : nullptr, h->zy + m0, st, lim);
+      launch_ce_rows(h->pmax + po, h->psum + po, h->psz + po, h->zy + m0, nullptr, Mc, np, h->ce_pitch, h->ls_eps, V,
+                     h->lse + m0, h->nll + m0, st, lim);
       m0 += Mc;
     }
     launch_ce_loss(h->nll, Mt, h->loss, h->flags, st, RowLimit{h->ce_nvalid, 0});
@@ -710,13 +726,13 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   launch_transpose(p, h->Xt, E, h->XtT, Mt, Mt, E, sd);
   launch_transpose(p, h->Cs, PH, h->CsT, Mt, Mt, H, sd);
   {
-    // Full slabs of CE_SLAB_ROWS rows and one remainder, two slab buffer pairs, over the dense rows of
+    // Full slabs of the slab capacity and one remainder (one slab whenever the batch fits), two slab buffer pairs, over the dense rows of
     // the valid target positions.  The host sizes the slabs for all T * Bp rows; every kernel gets the
     // device's count and a slab that lies beyond it costs a few empty launches.  Per slab the main
     // stream takes forward (logits -> e, partials), lse / nll, e -> dz and dz^T, and dH_o = dz W_o (the
     // decoder needs it); the second stream takes dW_o += dz^T H_o and dB_o.
     int nslab;
-    const int rows = ce_slab_plan(Mt, &nslab);
+    const int rows = ce_slab_plan(h, Mt, &nslab);
     std::vector<hipEvent_t> done(nslab, nullptr);
     const float eps = h->ls_eps;
     int sl = 0, n_dbo = 0;
@@ -726,19 +742,19 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       char* dz = (sl & 1) ? h->dzs2 : h->dzs;
       char* dzT = (sl & 1) ? h->dzTs2 : h->dzTs;
       if (sl >= 2 && sd != st) (void)hipStreamWaitEvent(st, done[sl - 2], 0);
+      const size_t po = (size_t)sl * np * h->ce_pitch;       // this slab's block of partials
       launch_ce_fwd(p, h->Hoc + (size_t)m0 * PH * esz, PH, h->Pw(h->off_Wo), P + h->off_Bo, h->labels_c + m0, Mc, V, H, dzT,
-                    h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, eps > 0.f ? h->psz + (size_t)m0 * np : nullptr,
-                    h->zy + m0, st, lim);
-      launch_ce_rows(h->pmax + (size_t)m0 * np, h->psum + (size_t)m0 * np, h->psz + (size_t)m0 * np, h->zy + m0,
-                     nullptr, Mc, np, eps, V, h->lse + m0, h->nll + m0, st, lim);
-      launch_ce_scale(p, dzT, V, Mc, h->pmax + (size_t)m0 * np, h->lse + m0, h->labels_c + m0, h->rowscale + m0, eps, dz,
+                    h->ce_pitch, h->pmax + po, h->psum + po, eps > 0.f ? h->psz + po : nullptr, h->zy + m0, st, lim);
+      launch_ce_rows(h->pmax + po, h->psum + po, h->psz + po, h->zy + m0, nullptr, Mc, np, h->ce_pitch, eps, V, h->lse + m0,
+                     h->nll + m0, st, lim);
+      launch_ce_scale(p, dzT, h->ce_pitch, V, Mc, h->pmax + po, h->lse + m0, h->labels_c + m0, h->rowscale + m0, eps, dz,
                       h->dbo_parts + (size_t)n_dbo * V, st, lim);
       n_dbo += (Mc + 63) / 64;
       stream_after(h, sd, st);
       launch_gemm_nt(p, dz, V, h->WoT, V, Mc, H, V, h->dHoCE + (size_t)m0 * H, nullptr, H, nullptr, 0, st, h->gsplit,
                      h->gsplit_floats, lim, 1);                           // dH_o[slab] = dz W_o
       // dW_o (+)= dz^T H_o[slab]; the first slab always holds a row, so W_o's gradient is always written
-      launch_gemm_nt(p, dzT, CE_SLAB_ROWS, h->HocT + (size_t)m0 * esz, Mt, V, H, Mc, G + h->off_Wo, nullptr, H, nullptr, sl > 0,
+      launch_gemm_nt(p, dzT, h->ce_pitch, h->HocT + (size_t)m0 * esz, Mt, V, H, Mc, G + h->off_Wo, nullptr, H, nullptr, sl > 0,
                      sd, nullptr, 0, lim, 2);
       if (sd != st) {
         done[sl] = h->ev[h->ev_next++ % h->ev.size()];
@@ -1540,13 +1556,13 @@ int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_la
   } else if (s == "ce_fwd") {
     // vocabulary projection of one slab of rows with the partial log-sum-exp statistics  (flops)
     int nslab;
-    const int rows = ce_slab_plan(Mt, &nslab);
+    const int rows = ce_slab_plan(h, Mt, &nslab);
     const int Mc = nslab == 1 ? Mt : rows;              // the first slab
     *algo_work = 2.0 * Mc * (double)V * H;
     const char* Ho = (h->drop_p > 0.f ? h->HoDrop : h->HoBuf) + BP * es;
     launch = [=](int) {
-      launch_ce_fwd(p, Ho, PH, h->Pw(h->off_Wo), h->params + h->off_Bo, h->labels, Mc, V, H, h->dzTs2, h->pmax, h->psum, nullptr,
-                    h->zy, st);
+      launch_ce_fwd(p, Ho, PH, h->Pw(h->off_Wo), h->params + h->off_Bo, h->labels, Mc, V, H, h->dzTs, h->ce_pitch, h->pmax,
+                    h->psum, nullptr, h->zy, st);
     };
   } else if (s == "grid_barrier" || s == "grid_barrier_nofence") {
     // 100 chip-wide barriers between 256 resident workgroups (bounded polling); work = the number of barriers

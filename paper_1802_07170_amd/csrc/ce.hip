@@ -1,6 +1,6 @@
-// Vocabulary projection + log-softmax + cross-entropy (Eq. 1), forward and backward, one slab of at
-// most CE_SLAB_ROWS target positions at a time; the full [rows, vocabulary] matrix never exists and
-// the logits are contracted exactly once:
+// Vocabulary projection + log-softmax + cross-entropy (Eq. 1), forward and backward, one slab of target
+// positions at a time (the whole batch up to CE_SLAB_MAX_ROWS positions, larger batches in several slabs,
+// so the slab buffers stop growing with the batch); the logits are contracted exactly once:
 //   ce_fwd_kernel : logits of a 256 x 256 tile on the matrix cores; per target position and group of
 //                   64 vocabulary entries the maximum m, the sum of e = exp(z - m) and the label's
 //                   logit are kept, and e itself is stored (transposed, [V, slab rows]) in the
@@ -18,7 +18,6 @@ namespace cmt {
 
 using CeG = GemmBig;                                      // 256 x 256 logit tile, 16 wavefronts of 64 x 64
 int ce_num_partials(int V) { return 4 * ((V + CeG::BN - 1) / CeG::BN); }
-size_t ce_slab_elems(int V) { return (size_t)CE_SLAB_ROWS * V; }
 
 // The tile is computed transposed — vocabulary rows on the matrix cores' row side, target positions
 // on the column side — so that in the accumulator layout a lane holds 32 vocabulary entries of ONE
@@ -107,27 +106,28 @@ __global__ __launch_bounds__(CeG::NT) void ce_fwd_kernel(const T* __restrict__ H
     e += __shfl_xor(e, 32, 64);
     if (psz) sz += __shfl_xor(sz, 32, 64);                // label smoothing needs the mean logit of the row
     if (lane < 32 && r < M) {                             // partials are kept [group][position]: 32 lanes, 128 bytes
-      pmax[(size_t)pidx * CE_SLAB_ROWS + r] = mx;
-      psum[(size_t)pidx * CE_SLAB_ROWS + r] = e;
-      if (psz) psz[(size_t)pidx * CE_SLAB_ROWS + r] = sz;
+      pmax[(size_t)pidx * ldet + r] = mx;
+      psum[(size_t)pidx * ldet + r] = e;
+      if (psz) psz[(size_t)pidx * ldet + r] = sz;
     }
   }
 }
 
 void launch_ce_fwd(int prec, const void* Ho, int ldho, const void* Wo, const float* Bo, const int32_t* labels,
-                   int M, int V, int H, void* ET, float* pmax, float* psum, float* psz, float* zy, hipStream_t st, RowLimit lim) {
+                   int M, int V, int H, void* ET, int pitch, float* pmax, float* psum, float* psz, float* zy, hipStream_t st,
+                   RowLimit lim) {
   const int ntv = (V + CeG::BM - 1) / CeG::BM, ntr = (M + CeG::BN - 1) / CeG::BN;
   const int grid = ((ntv * ntr + 7) / 8) * 8;
   const int np = ce_num_partials(V);
   if (prec)
     hipLaunchKernelGGL(ce_fwd_kernel<bf16_t>, dim3(grid), dim3(CeG::NT), 0, st, (const bf16_t*)Ho, ldho, (const bf16_t*)Wo, Bo,
-                       labels, M, V, H, (bf16_t*)ET, CE_SLAB_ROWS, pmax, psum, psz, zy, np, lim);
+                       labels, M, V, H, (bf16_t*)ET, pitch, pmax, psum, psz, zy, np, lim);
   else
     hipLaunchKernelGGL(ce_fwd_kernel<float>, dim3(grid), dim3(CeG::NT), 0, st, (const float*)Ho, ldho, (const float*)Wo, Bo,
-                       labels, M, V, H, (float*)ET, CE_SLAB_ROWS, pmax, psum, psz, zy, np, lim);
+                       labels, M, V, H, (float*)ET, pitch, pmax, psum, psz, zy, np, lim);
 }
 
-// Combines the partials (kept [group][position], pitch CE_SLAB_ROWS) of 32 target positions per workgroup: thread
+// Combines the partials (kept [group][position], row pitch `pitch`) of 32 target positions per workgroup: thread
 // t takes position t % 32 and every 32nd group from t / 32 on, so that a half-wavefront reads 32 consecutive
 // positions of one group; the 32 group strands of a position meet in LDS, in a fixed order.  Row loss
 // against the smoothed target distribution (1 - eps) onehot(y) + eps / V:
@@ -144,7 +144,7 @@ __device__ __forceinline__ float ce_row_meet(float (&red)[CE_ROW_STRANDS][CE_ROW
 }
 __global__ __launch_bounds__(CE_ROW_ROWS * CE_ROW_STRANDS) void ce_row_kernel(const float* __restrict__ pmax, const float* __restrict__ psum,
                                                                     const float* __restrict__ psz, const float* __restrict__ zy,
-                                                                    const float* __restrict__ mask, int M, int np, float eps, int V,
+                                                                    const float* __restrict__ mask, int M, int np, int pitch, float eps, int V,
                                                                     float* __restrict__ lse, float* __restrict__ nll, RowLimit lim) {
   __shared__ float red[CE_ROW_STRANDS][CE_ROW_ROWS];
   const int rl = threadIdx.x % CE_ROW_ROWS, pg = threadIdx.x / CE_ROW_ROWS;
@@ -155,17 +155,17 @@ __global__ __launch_bounds__(CE_ROW_ROWS * CE_ROW_STRANDS) void ce_row_kernel(co
   float mx = -INFINITY;
   if (ok) {
 #pragma unroll 4
-    for (int p = pg; p < np; p += CE_ROW_STRANDS) mx = fmaxf(mx, pmax[(size_t)p * CE_SLAB_ROWS + row]);
+    for (int p = pg; p < np; p += CE_ROW_STRANDS) mx = fmaxf(mx, pmax[(size_t)p * pitch + row]);
   }
   mx = ce_row_meet(red, pg, rl, mx, true);
   float s = 0.f, sz = 0.f;
   if (ok) {
 #pragma unroll 4
     for (int p = pg; p < np; p += CE_ROW_STRANDS) {
-      const float pm = pmax[(size_t)p * CE_SLAB_ROWS + row];
-      const float ps = psum[(size_t)p * CE_SLAB_ROWS + row];
+      const float pm = pmax[(size_t)p * pitch + row];
+      const float ps = psum[(size_t)p * pitch + row];
       if (pm > -INFINITY) s += ps * expf(pm - mx);
-      if (eps > 0.f) sz += psz[(size_t)p * CE_SLAB_ROWS + row];
+      if (eps > 0.f) sz += psz[(size_t)p * pitch + row];
     }
   }
   s = ce_row_meet(red, pg, rl, s, false);
@@ -271,8 +271,9 @@ void launch_ce_compact(const float* mask, const int32_t* labels, int M, int32_t*
   hipLaunchKernelGGL(ce_compact_kernel, dim3(1), dim3(1024), 0, st, mask, labels, M, pos, row, labels_c, rowscale_c, n_valid, loss);
 }
 void launch_ce_rows(const float* pmax, const float* psum, const float* psz, const float* zy, const float* mask, int M, int np,
-                    float eps, int V, float* lse, float* nll, hipStream_t st, RowLimit lim) {
-  hipLaunchKernelGGL(ce_row_kernel, dim3((M + CE_ROW_ROWS - 1) / CE_ROW_ROWS), dim3(CE_ROW_ROWS * CE_ROW_STRANDS), 0, st, pmax, psum, psz, zy, mask, M, np, eps, V, lse, nll, lim);
+                    int pitch, float eps, int V, float* lse, float* nll, hipStream_t st, RowLimit lim) {
+  hipLaunchKernelGGL(ce_row_kernel, dim3((M + CE_ROW_ROWS - 1) / CE_ROW_ROWS), dim3(CE_ROW_ROWS * CE_ROW_STRANDS), 0, st, pmax, psum,
+                     psz, zy, mask, M, np, pitch, eps, V, lse, nll, lim);
 }
 void launch_ce_loss(const float* nll, int M, float* loss, int* flags, hipStream_t st, RowLimit lim) {
   hipLaunchKernelGGL(ce_loss_kernel, dim3(1), dim3(1024), 0, st, nll, M, loss, flags, lim);
@@ -308,7 +309,7 @@ __global__ __launch_bounds__(256) void ce_scale_kernel(T* __restrict__ ET, int l
     float f = 0.f, rs = 0.f;
     int y = -1;
     if (r < Mc) {
-      const float pm = pmax[(size_t)blockIdx.x * CE_SLAB_ROWS + r];
+      const float pm = pmax[(size_t)blockIdx.x * ldet + r];
       f = pm > -INFINITY ? expf(pm - lse[r]) : 0.f;
       rs = rowscale[r];
       y = labels[r];
@@ -351,15 +352,15 @@ __global__ __launch_bounds__(256) void ce_scale_kernel(T* __restrict__ ET, int l
   }
 }
 
-void launch_ce_scale(int prec, void* ET, int V, int Mc, const float* pmax, const float* lse, const int32_t* labels,
+void launch_ce_scale(int prec, void* ET, int pitch, int V, int Mc, const float* pmax, const float* lse, const int32_t* labels,
                      const float* rowscale, float eps, void* dz, float* dbo_part, hipStream_t st, RowLimit lim) {
   dim3 grid((V + 63) / 64, (Mc + 63) / 64);
   const int np = ce_num_partials(V);
   if (prec)
-    hipLaunchKernelGGL(ce_scale_kernel<bf16_t>, grid, dim3(256), 0, st, (bf16_t*)ET, CE_SLAB_ROWS, V, Mc, pmax, np, lse, labels,
+    hipLaunchKernelGGL(ce_scale_kernel<bf16_t>, grid, dim3(256), 0, st, (bf16_t*)ET, pitch, V, Mc, pmax, np, lse, labels,
                        rowscale, eps, (bf16_t*)dz, dbo_part, lim);
   else
-    hipLaunchKernelGGL(ce_scale_kernel<float>, grid, dim3(256), 0, st, (float*)ET, CE_SLAB_ROWS, V, Mc, pmax, np, lse, labels,
+    hipLaunchKernelGGL(ce_scale_kernel<float>, grid, dim3(256), 0, st, (float*)ET, pitch, V, Mc, pmax, np, lse, labels,
                        rowscale, eps, (float*)dz, dbo_part, lim);
 }
 

@@ -34,12 +34,15 @@ using GemmBig = GemmTile<4, 4, 2, 2, 128>;                 // 256 x 256, 1024 th
 // its own L2), so XCD x is given the contiguous range of tile numbers [x * per, (x + 1) * per); tile
 // numbers run down groups of GROUP_M tile rows column by column, so that the ~32 tiles an XCD works
 // on at a time form a block of GROUP_M x 8 tiles that share their A and B panels in that L2 (a strip
-// of 1 x 32 tiles would pull 33 panels through L2 instead of 12).  Returns false for padding ids.
+// of 1 x 32 tiles would pull 33 panels through L2 instead of 12).  Returns false for padding ids.  The
+// launched grid must hold at least 8 * ceil(ntm * ntn / 8) workgroups.
 constexpr int GEMM_GROUP_M = 4;
 __device__ __forceinline__ bool gemm_tile_of_block(int ntm, int ntn, int bm, int bn, int& m0, int& n0) {
-  const int per = gridDim.x >> 3;
-  const int id = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
-  if (id >= ntm * ntn) return false;
+  // `per` comes from the tiles that exist, not from the launched grid: a launch sized for more rows than the
+  // device-side count leaves (ids beyond the last tile exit) still spreads its tiles evenly over the XCDs
+  const int nt = ntm * ntn, per = (nt + 7) >> 3, j = blockIdx.x >> 3;
+  const int id = (blockIdx.x & 7) * per + j;
+  if (j >= per || id >= nt) return false;
   const int gsz = GEMM_GROUP_M * ntn;
   const int grp = id / gsz, rem = id - grp * gsz;
   const int first = grp * GEMM_GROUP_M;

@@ -30,18 +30,22 @@ double launch_mfma_rate(float* out, int blocks, int iters, hipStream_t st);
 void launch_transpose(int prec, const void* in, int ldin, void* out, int ldout, int R, int C, hipStream_t st);
 
 // ---- ce.hip ------------------------------------------------------------------------------------
-// Eq. 1 for a slab of M <= CE_SLAB_ROWS rows (all row pointers at the slab's first row).
+// Eq. 1 for a slab of M <= pitch rows (all row pointers at the slab's first row; pitch = row capacity of the
+// slab buffers, a multiple of 64).
 // Forward: Ho [M,H] T, Wo [V,H] T, Bo [V] fp32, labels [M] int32.  Per row and group of 64
-// vocabulary columns: pmax = max z, psum = sum exp(z - pmax) ([np, CE_SLAB_ROWS] fp32: group-major, np = ce_num_partials(V));
-// zy [M] = the label's logit; ET [V, CE_SLAB_ROWS] T = exp(z - pmax of its group), transposed;
+// vocabulary columns: pmax = max z, psum = sum exp(z - pmax) ([np, pitch] fp32: group-major, np = ce_num_partials(V));
+// zy [M] = the label's logit; ET [V, pitch] T = exp(z - pmax of its group), transposed;
 // psz (same layout) = sum of z over the group (null unless label smoothing needs the row's mean logit).
-constexpr int CE_SLAB_ROWS = 1024;
+// A slab holds up to CE_SLAB_MAX_ROWS target positions (fewer when the handle is created for fewer): the whole
+// batch is one slab up to that size, which measured faster than several smaller ones (one pass over W_o and one
+// read-modify-write of its gradient per slab).  The pitch adds 64 to the capacity so that it is never a power of two.
+constexpr int CE_SLAB_MAX_ROWS = 16384;
 int ce_num_partials(int V);
-size_t ce_slab_elems(int V);                                 // elements of a slab buffer (E / dz, and dzT)
+inline int ce_slab_pitch(int rows) { return rows + 64; }
 // Every launcher below takes a RowLimit: the slab's row count as the device knows it (see
 // launch_ce_compact); rows beyond it are neither computed nor stored.
 void launch_ce_fwd(int prec, const void* Ho, int ldho, const void* Wo, const float* Bo, const int32_t* labels,
-                   int M, int V, int H, void* ET, float* pmax, float* psum, float* psz, float* zy, hipStream_t st,
+                   int M, int V, int H, void* ET, int pitch, float* pmax, float* psum, float* psz, float* zy, hipStream_t st,
                    RowLimit lim = RowLimit{});
 // The valid target positions of the batch (mask > 0, M = all rows, time-major) numbered consecutively:
 // pos[M] = index or -1, row[index] = row, labels_c / rowscale_c [index] = label and 1 / n_tok,
@@ -55,14 +59,14 @@ void launch_ce_gather_rows(int prec, const void* src, int lds, const int32_t* ro
 // (label smoothing eps of the hyperparameter table; eps = 0: plain negative log-likelihood);
 // mask (may be null = all rows count) zeroes the loss of padded rows.
 void launch_ce_rows(const float* pmax, const float* psum, const float* psz, const float* zy, const float* mask, int M, int np,
-                    float eps, int V, float* lse, float* nll, hipStream_t st, RowLimit lim = RowLimit{});
+                    int pitch, float eps, int V, float* lse, float* nll, hipStream_t st, RowLimit lim = RowLimit{});
 // loss[0] = sum nll / loss[1]; flags |= 4 if it is not finite.  One block, deterministic order.
 void launch_ce_loss(const float* nll, int M, float* loss, int* flags, hipStream_t st, RowLimit lim = RowLimit{});
 // Backward: ET -> dzT = (ET * exp(pmax - lse) - (1 - eps) onehot - eps / V) * rowscale in place
-// ([V, CE_SLAB_ROWS] T; columns >= Mc up to the next multiple of 64 are zero-filled) and dz [Mc, V] T.  The caller
+// ([V, pitch] T; columns >= Mc up to the next multiple of 64 are zero-filled) and dz [Mc, V] T.  The caller
 // then takes dH_o[rows] = dz W_o and dW_o += dz^T H_o[rows] with launch_gemm_nt.  dbo_part
 // [ceil(Mc / 64), V] fp32: column sums of dz over each block of 64 rows (dB_o = their sum over all slabs).
-void launch_ce_scale(int prec, void* ET, int V, int Mc, const float* pmax, const float* lse, const int32_t* labels,
+void launch_ce_scale(int prec, void* ET, int pitch, int V, int Mc, const float* pmax, const float* lse, const int32_t* labels,
                      const float* rowscale, float eps, void* dz, float* dbo_part, hipStream_t st, RowLimit lim = RowLimit{});
 
 // ---- step.hip ----------------------------------------------------------------------------------

@@ -210,16 +210,20 @@ def test_every_form_of_the_backward_loops(prec, forms, B, S, T, H, E, L, monkeyp
 
 
 @pytest.mark.parametrize("prec", [0, 1])
-def test_batches_of_different_shape_in_turn_on_one_handle(prec):
+@pytest.mark.parametrize("slab_rows", [0, 1024])
+def test_batches_of_different_shape_in_turn_on_one_handle(prec, slab_rows, monkeypatch):
     """A large batch, then a small one with far fewer valid target positions, then the large one again,
     all on the same handle: nothing one step leaves in the workspace (rows beyond the valid positions of
     the dense output-layer buffers, planes, padded slots) may reach the next.  Each result is checked
-    against the oracle, and the repeated batch must reproduce its first result bit for bit."""
+    against the oracle, and the repeated batch must reproduce its first result bit for bit.  With the
+    output layer's slab capacity at its default (one slab) and lowered to 1024 rows (two slabs)."""
     from paper_1802_07170_amd import binding
+    if slab_rows:
+        monkeypatch.setenv("CMT_CE_SLAB_ROWS", str(slab_rows))
     cfg = dict(src_vocab=104, tgt_vocab=328, emb=24, hidden=48, layers=2)
     rng = np.random.default_rng(77)
     params = I.make_params(cfg, seed=12, scale=0.3)
-    big = ragged_batch(rng, 70, 9, 17, 104, 328)               # 1360 rows: two slabs
+    big = ragged_batch(rng, 70, 9, 17, 104, 328)               # 1360 rows
     small = ragged_batch(rng, 5, 4, 3, 104, 328)
     tr = binding.Trainer(cfg, 70, 9, 17, precision=prec)
     tr.set_params(I.flatten(params, cfg))
@@ -311,15 +315,26 @@ def test_random_shapes_sweep():
 
 
 @pytest.mark.parametrize("prec", [0, 1])
-def test_output_layer_over_two_slabs(prec):
-    """The output layer works through the target positions in slabs of <= 1024 rows.  1120 rows here:
-    two slabs of unequal size, neither a multiple of the 256-row tile; a vocabulary that is not a
-    multiple of any tile (328 = 5 groups of 64 columns + 8)."""
+@pytest.mark.parametrize("slab_rows", [0, 256, 512, 768])
+def test_output_layer_over_several_slabs(prec, slab_rows, monkeypatch):
+    """The output layer works through the valid target positions in slabs: one slab for the whole batch up to
+    the library's slab capacity, several beyond it.  CMT_CE_SLAB_ROWS (read when the handle is created) lowers
+    the capacity so that small shapes reach the multi-slab path: 1120 padded rows (a ragged part of them valid) here, as
+    one slab (the default), as 256-row slabs (the last ones beyond the valid rows: empty launches), as 512 +
+    remainder, as 768 + remainder (neither a multiple of the 256-row tile of the logit kernel); a vocabulary that
+    is not a multiple of any tile (328 = 5 groups of 64 columns + 8); with and without label smoothing (the mean
+    logit partials) and an evaluation pass over the same slabs."""
     cfg = dict(src_vocab=104, tgt_vocab=328, emb=16, hidden=48, layers=1)
     rng = np.random.default_rng(7)
     params = I.make_params(cfg, seed=3, scale=0.3)
     batch = ragged_batch(rng, 70, 4, 14, cfg["src_vocab"], cfg["tgt_vocab"])
+    if slab_rows:
+        monkeypatch.setenv("CMT_CE_SLAB_ROWS", str(slab_rows))
     loss, oloss, worst, tr = run_case(cfg, params, batch, prec, check_inter=False)
+    ev, ntok = tr.eval_loss(tr.upload_batch(*batch))
+    assert ev == loss and ntok == float(batch[3].sum())
+    tr.close()
+    loss, oloss, worst, tr = run_case(cfg, params, batch, prec, check_inter=False, reg=(0.0, 0.1, 5))
     tr.close()
 
 
@@ -630,10 +645,12 @@ def test_sgd_training_with_the_paper_s_regularisation_and_controller_learns():
 
 @pytest.mark.parametrize("prec", [0, 1])
 @pytest.mark.parametrize("B,S,T,H,E,L,V", [(7, 6, 9, 32, 24, 2, 136), (70, 4, 17, 48, 16, 1, 328)])
-def test_eval_loss_is_the_oracle_s_forward_loss(prec, B, S, T, H, E, L, V):
+def test_eval_loss_is_the_oracle_s_forward_loss(prec, B, S, T, H, E, L, V, monkeypatch):
     """Forward-only evaluation: the oracle's loss without regularisation, whatever regularisation the
-    handle is set to; the token count; gradients left alone.  The second shape spans two slabs."""
+    handle is set to; the token count; gradients left alone.  The second shape spans two slabs of the
+    output layer (slab capacity lowered to 1024 rows)."""
     from paper_1802_07170_amd import binding
+    monkeypatch.setenv("CMT_CE_SLAB_ROWS", "1024")
     cfg = dict(src_vocab=104, tgt_vocab=V, emb=E, hidden=H, layers=L)
     rng = np.random.default_rng(17 + B)
     params = I.make_params(cfg, seed=8, scale=0.3)
