@@ -124,7 +124,7 @@ struct cmt_handle {
   char* dzs = nullptr; char* dzTs = nullptr; float* dbo_parts = nullptr;
   int ce_rows = 0, ce_pitch = 0;        // row capacity of an output-layer slab and the row pitch of its buffers
   int ce_cap = ce_cap_env();            // upper bound of ce_rows
-  float* gsplit = nullptr; size_t gsplit_floats = 0;
+  float* gsplit = nullptr; size_t gsplit_floats = 0, gsplit_main_floats = 0;
   hipStream_t side = nullptr;           // library-owned second stream for work off the recurrences' critical path
   std::vector<hipEvent_t> ev; size_t ev_next = 0;
   int use_side = 1;
@@ -305,13 +305,14 @@ size_t layout(cmt_handle* h, char* base) {
   h->colscr = (float*)a.take((size_t)16 * 4 * H * 4);
   h->dzs = a.take(slab_elems * esz); h->dzTs = a.take(slab_elems * esz);
   h->dbo_parts = (float*)a.take((Mt / 64 + Mt / 256 + 4) * c.tgt_vocab * 4);
-  {   // split-k planes of the small-output GEMMs (dH_o of a slab, weight-gradient segments): room for 16 planes
-      // of the largest such output, at most 32 MB
+  {   // split-k planes.  Second stream (weight-gradient segments): room for 16 planes of the largest such output, at
+      // most 32 MB.  Caller's stream (dH_o of a slab, k = the vocabulary): 16 planes of a slab's dH_o, at most 256 MB.
     const size_t slab_rows = std::min<size_t>(Mt, (size_t)h->ce_rows);
-    const size_t out_max = std::max(slab_rows * H, (size_t)4 * H * std::max(E, H));
-    h->gsplit_floats = std::min((size_t)8 << 20, 16 * out_max);
+    const size_t out_w = (size_t)4 * H * std::max(E, H);
+    h->gsplit_floats = std::min((size_t)8 << 20, 16 * std::max(out_w, std::min(slab_rows, (size_t)1024) * H));
+    h->gsplit_main_floats = std::max(h->gsplit_floats, std::min((size_t)64 << 20, 16 * slab_rows * H));
   }
-  h->gsplit = (float*)a.take(h->gsplit_floats * 4);
+  h->gsplit = (float*)a.take(h->gsplit_main_floats * 4);
   h->gsplit2 = (float*)a.take(h->gsplit_floats * 4);
   if (ce_slabs > 1) {                             // a second pair, so that slab s + 1 starts while dW_o of slab s still runs
     h->dzs2 = a.take(slab_elems * esz); h->dzTs2 = a.take(slab_elems * esz);
@@ -752,7 +753,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       n_dbo += (Mc + 63) / 64;
       stream_after(h, sd, st);
       launch_gemm_nt(p, dz, V, h->WoT, V, Mc, H, V, h->dHoCE + (size_t)m0 * H, nullptr, H, nullptr, 0, st, h->gsplit,
-                     h->gsplit_floats, lim, 1);                           // dH_o[slab] = dz W_o
+                     h->gsplit_main_floats, lim, 1);                           // dH_o[slab] = dz W_o
       // dW_o (+)= dz^T H_o[slab]; the first slab always holds a row, so W_o's gradient is always written
       launch_gemm_nt(p, dzT, h->ce_pitch, h->HocT + (size_t)m0 * esz, Mt, V, H, Mc, G + h->off_Wo, nullptr, H, nullptr, sl > 0,
                      sd, nullptr, 0, lim, 2);

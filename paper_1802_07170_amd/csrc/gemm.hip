@@ -18,7 +18,19 @@ static const int GEMM_BIG_MIN_TILES = env_int("CMT_GEMM_BIG_MIN_TILES", 192);
 static const int GEMM_SPLIT_BELOW = env_int("CMT_GEMM_SPLIT_BELOW", 129);
 static const int GEMM_SPLIT_TARGET = env_int("CMT_GEMM_SPLIT_TARGET", 512);
 static const int GEMM_SPLIT_MAX = env_int("CMT_GEMM_SPLIT_MAX", 16);
+static const int GEMM_BIGSPLIT_MIN_K = env_int("CMT_GEMM_BIGSPLIT_MIN_K", 8192);
+// beyond this many big tiles (by the host's row count) the small tile without a split measured faster (large
+// workload: 160 tiles, 3.15 against 3.57 ms for the output layer)
+static const int GEMM_BIGSPLIT_MAX_TILES = env_int("CMT_GEMM_BIGSPLIT_MAX_TILES", 96);
 
+
+// Number of k splits when the row count is known to the device alone: as many as make one round of workgroups
+// over the chip's 256 CUs out of the tiles that exist, at most the launched number.  The kernel and the plane
+// sum both derive it from the same count.
+__host__ __device__ inline int gemm_dyn_splits(int tiles, int launched) {
+  const int ns = 256 / (tiles > 0 ? tiles : 1);
+  return ns < 1 ? 1 : (ns > launched ? launched : ns);
+}
 
 // blockIdx.y = k split index: each split contracts kchunk elements of k and, when there is more
 // than one, writes its own fp32 plane Cf + split * plane_stride (summed afterwards, fixed order).
@@ -26,7 +38,8 @@ template <typename T, int WM, int WN, int TA, int TB, int KB>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_kernel(const T* __restrict__ A, int lda, const T* __restrict__ B, int ldb,
                                                                int M, int N, int K, float* __restrict__ Cf, T* __restrict__ Ct,
                                                                int ldc, const float* __restrict__ bias, int accumulate, int ntn,
-                                                               int kchunk, size_t plane_stride, RowLimit lim, int lim_kind) {
+                                                               int kchunk, size_t plane_stride, RowLimit lim, int lim_kind,
+                                                               int dyn_split) {
   using G = GemmTile<WM, WN, TA, TB, KB>;
   __shared__ __align__(16) char smem[G::SMEM_BYTES];
   if (lim.n) {                                     // a bound that only the device knows (uniform over the grid)
@@ -37,6 +50,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_kernel(const T* __restri
   }
   int m0, n0;
   if (!gemm_tile_of_block((M + G::BM - 1) / G::BM, ntn, G::BM, G::BN, m0, n0)) return;
+  if (dyn_split) {                                 // the number of k splits follows the tiles that exist: one round of workgroups
+    const int ns = gemm_dyn_splits((M + G::BM - 1) / G::BM * ntn, gridDim.y);
+    if ((int)blockIdx.y >= ns) return;
+    kchunk = ((K + ns - 1) / ns + 63) / 64 * 64;
+  }
   const int k0 = blockIdx.y * kchunk;
   const int klen = min(kchunk, K - k0);
   if (klen <= 0 && gridDim.y == 1) return;
@@ -71,8 +89,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_kernel(const T* __restri
 template <int VEC>
 __global__ __launch_bounds__(256) void gemm_planes_sum_kernel(const float* __restrict__ planes, int np, size_t stride,
                                                               float* __restrict__ out, int M, int N, int ldc,
-                                                              const float* __restrict__ bias, int accumulate, RowLimit lim) {
+                                                              const float* __restrict__ bias, int accumulate, RowLimit lim,
+                                                              int dyn_bm, int dyn_ntn) {
   if (lim.n) M = min(M, max(*lim.n - lim.base, 0));
+  if (dyn_bm) np = gemm_dyn_splits((M + dyn_bm - 1) / dyn_bm * dyn_ntn, np);   // the planes the GEMM wrote
   const unsigned nq = (unsigned)N / VEC;                  // column groups per row
   const size_t n = (size_t)M * nq;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
@@ -98,11 +118,25 @@ __global__ __launch_bounds__(256) void gemm_planes_sum_kernel(const float* __res
   }
 }
 
+static void launch_planes_sum(const float* planes, int nks, size_t pstride, float* Cf, int M, int N, int ldc, const float* bias,
+                              int accumulate, RowLimit rl, hipStream_t st, int dyn_bm = 0, int dyn_ntn = 0) {
+  const bool vec = N % 4 == 0 && ldc % 4 == 0 && pstride % 4 == 0 && ((size_t)Cf | (size_t)planes | (size_t)bias) % 16 == 0;
+  size_t g = (pstride / (vec ? 4 : 1) + 255) / 256;
+  if (g > 4096) g = 4096;
+  if (vec)
+    hipLaunchKernelGGL(gemm_planes_sum_kernel<4>, dim3((unsigned)g), dim3(256), 0, st, planes, nks, pstride, Cf, M, N, ldc, bias,
+                       accumulate, rl, dyn_bm, dyn_ntn);
+  else
+    hipLaunchKernelGGL(gemm_planes_sum_kernel<1>, dim3((unsigned)g), dim3(256), 0, st, planes, nks, pstride, Cf, M, N, ldc, bias,
+                       accumulate, rl, dyn_bm, dyn_ntn);
+}
+
 template <typename T, int WM, int WN, int TA, int TB>
 static void gemm_go(dim3 grid, hipStream_t st, const void* A, int lda, const void* B, int ldb, int M, int N, int K, float* out,
-                    void* Ct, int ldc, const float* bias, int acc, int ntn, int kchunk, size_t pstride, RowLimit lim, int lim_kind) {
+                    void* Ct, int ldc, const float* bias, int acc, int ntn, int kchunk, size_t pstride, RowLimit lim, int lim_kind,
+                    int dyn_split = 0) {
   hipLaunchKernelGGL((gemm_nt_kernel<T, WM, WN, TA, TB, 128>), grid, dim3(64 * WM * WN), 0, st, (const T*)A, lda, (const T*)B, ldb,
-                     M, N, K, out, (T*)Ct, ldc, bias, acc, ntn, kchunk, pstride, lim, lim_kind);
+                     M, N, K, out, (T*)Ct, ldc, bias, acc, ntn, kchunk, pstride, lim, lim_kind, dyn_split);
 }
 
 void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, int M, int N, int K,
@@ -116,6 +150,26 @@ void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, in
     if (prec) gemm_go<bf16_t, 4, 4, 2, 2>(dim3(grid, 1), st, A, lda, B, ldb, M, N, K, Cf, Ct, ldc, bias, accumulate, ntn_b, K, 0, lim, lim_kind);
     else gemm_go<float, 4, 4, 2, 2>(dim3(grid, 1), st, A, lda, B, ldb, M, N, K, Cf, Ct, ldc, bias, accumulate, ntn_b, K, 0, lim, lim_kind);
     return;
+  }
+  // a long contraction over few output tiles (dH_o = dz W_o: k = the vocabulary): big tiles with k split into
+  // planes.  With a device-side row limit the kernel picks the number of splits itself (gemm_dyn_splits) out of
+  // the launched maximum; otherwise the host aims at about one and a half rounds of workgroups.
+  if (split_scratch && Cf && !Ct && K >= GEMM_BIGSPLIT_MIN_K && ntm_b * ntn_b <= GEMM_BIGSPLIT_MAX_TILES) {
+    const bool dyn = lim.n && lim_kind == 1;
+    int ks = dyn ? GEMM_SPLIT_MAX : (384 + ntm_b * ntn_b - 1) / (ntm_b * ntn_b);
+    if (ks > GEMM_SPLIT_MAX) ks = GEMM_SPLIT_MAX;
+    while (ks > 1 && ((size_t)ks * M * N > split_scratch_floats || K / ks < 2048)) --ks;
+    if (ks > 1 && (dyn || ks * ntm_b * ntn_b >= GEMM_BIG_MIN_TILES)) {     // else the small tile fills the chip better
+      const int kchunk = ((K + ks - 1) / ks + 63) / 64 * 64;
+      const int nks = dyn ? ks : (K + kchunk - 1) / kchunk;
+      const size_t pstride = (size_t)M * N;
+      const int grid = ((ntm_b * ntn_b + 7) / 8) * 8;
+      if (prec) gemm_go<bf16_t, 4, 4, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, split_scratch, nullptr, N, nullptr, 0, ntn_b, kchunk, pstride, lim, lim_kind, dyn);
+      else gemm_go<float, 4, 4, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, split_scratch, nullptr, N, nullptr, 0, ntn_b, kchunk, pstride, lim, lim_kind, dyn);
+      launch_planes_sum(split_scratch, nks, pstride, Cf, M, N, ldc, bias, accumulate, lim_kind == 1 ? lim : RowLimit{}, st,
+                        dyn ? GemmBig::BM : 0, ntn_b);
+      return;
+    }
   }
   using G = GemmSmall;
   const int ntm = (M + G::BM - 1) / G::BM, ntn = (N + G::BN - 1) / G::BN;
@@ -140,18 +194,7 @@ void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, in
   const int oacc = nks > 1 ? 0 : accumulate;
   if (prec) gemm_go<bf16_t, 2, 2, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, out, Ct, oldc, obias, oacc, ntn, kchunk, pstride, lim, lim_kind);
   else gemm_go<float, 2, 2, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, out, Ct, oldc, obias, oacc, ntn, kchunk, pstride, lim, lim_kind);
-  if (nks > 1) {
-    const bool vec = N % 4 == 0 && ldc % 4 == 0 && pstride % 4 == 0 && ((size_t)Cf | (size_t)split_scratch | (size_t)bias) % 16 == 0;
-    size_t g = (pstride / (vec ? 4 : 1) + 255) / 256;
-    if (g > 4096) g = 4096;
-    const RowLimit rl = lim_kind == 1 ? lim : RowLimit{};
-    if (vec)
-      hipLaunchKernelGGL(gemm_planes_sum_kernel<4>, dim3((unsigned)g), dim3(256), 0, st, split_scratch, nks, pstride, Cf, M, N, ldc,
-                         bias, accumulate, rl);
-    else
-      hipLaunchKernelGGL(gemm_planes_sum_kernel<1>, dim3((unsigned)g), dim3(256), 0, st, split_scratch, nks, pstride, Cf, M, N, ldc,
-                         bias, accumulate, rl);
-  }
+  if (nks > 1) launch_planes_sum(split_scratch, nks, pstride, Cf, M, N, ldc, bias, accumulate, lim_kind == 1 ? lim : RowLimit{}, st);
 }
 
 // Measurement aid: nothing but matrix-core instructions (4 independent 32x32x16 bf16 accumulator chains per
