@@ -114,7 +114,9 @@ __device__ __forceinline__ unsigned gemm_lds_address(const char* p) {
 }
 // Asynchronous: completion is awaited with gemm_dl_wait() before the barrier that publishes the stage.
 // The instruction is written out because the compiler, when it knows a load writes LDS, waits for every
-// outstanding one before the next LDS read of any address — which would serialise the two stages.
+// outstanding one before the next LDS read of any address — which would serialise the two stages.  M0 (the LDS
+// base of the transfer) is a register the compiler reserves and loads directly before each use of its own, so
+// setting it here disturbs nothing (it cannot be named as a clobber).
 template <int NT, int ROWS>
 __device__ __forceinline__ void gemm_dl_issue(const bf16_t* __restrict__ base, const unsigned (&off)[ROWS * 8 / NT], char* tile, int w) {
 #pragma unroll
