@@ -122,13 +122,15 @@ struct cmt_handle {
   char* Hoc = nullptr; char* HocT = nullptr;   // H_o (as the output layer sees it) of the valid positions, and its transpose
   float* loss = nullptr; int* flags = nullptr; float* colscr = nullptr;
   char* dzs = nullptr; char* dzTs = nullptr; float* dbo_parts = nullptr;
+  std::vector<GemmProb> dw_group;       // weight-gradient GEMMs collected for one grouped launch (flush_dw_group)
   int ce_rows = 0, ce_pitch = 0;        // row capacity of an output-layer slab and the row pitch of its buffers
   int ce_cap = ce_cap_env();            // upper bound of ce_rows
-  float* gsplit = nullptr; size_t gsplit_floats = 0, gsplit_main_floats = 0;
+  float* gsplit = nullptr; size_t gsplit_floats = 0;   // split-k planes of dH_o = dz W_o (also the probes' scratch)
+  float* gsplit2 = nullptr; size_t gsplit2_floats = 0; // split-k planes of the second stream's GEMMs (fp32 path)
   hipStream_t side = nullptr;           // library-owned second stream for work off the recurrences' critical path
   std::vector<hipEvent_t> ev; size_t ev_next = 0;
   int use_side = 1;
-  char* dzs2 = nullptr; char* dzTs2 = nullptr; float* gsplit2 = nullptr;
+  char* dzs2 = nullptr; char* dzTs2 = nullptr;
   int kb_bwd = 0, kb_wc = 0;            // caps on the k blocks of the backward step GEMMs (0 = default)
   // backward loops that use the whole-k step GEMM with the consumer in its epilogue (env CMT_BWD_FUSED, a bit
   // mask): 1 = decoder (up to 64 sentences; at 128 every workgroup's re-read of the step's dgates makes it
@@ -305,15 +307,13 @@ size_t layout(cmt_handle* h, char* base) {
   h->colscr = (float*)a.take((size_t)16 * 4 * H * 4);
   h->dzs = a.take(slab_elems * esz); h->dzTs = a.take(slab_elems * esz);
   h->dbo_parts = (float*)a.take((Mt / 64 + Mt / 256 + 4) * c.tgt_vocab * 4);
-  {   // split-k planes.  Second stream (weight-gradient segments): room for 16 planes of the largest such output, at
-      // most 32 MB.  Caller's stream (dH_o of a slab, k = the vocabulary): 16 planes of a slab's dH_o, at most 256 MB.
+  {   // split-k planes of dH_o = dz W_o of a slab (k = the vocabulary): 16 planes, at most 256 MB, at least 1 MB
     const size_t slab_rows = std::min<size_t>(Mt, (size_t)h->ce_rows);
-    const size_t out_w = (size_t)4 * H * std::max(E, H);
-    h->gsplit_floats = std::min((size_t)8 << 20, 16 * std::max(out_w, std::min(slab_rows, (size_t)1024) * H));
-    h->gsplit_main_floats = std::max(h->gsplit_floats, std::min((size_t)64 << 20, 16 * slab_rows * H));
+    h->gsplit_floats = std::max((size_t)1 << 18, std::min((size_t)64 << 20, 16 * slab_rows * H));
   }
-  h->gsplit = (float*)a.take(h->gsplit_main_floats * 4);
-  h->gsplit2 = (float*)a.take(h->gsplit_floats * 4);
+  h->gsplit = (float*)a.take(h->gsplit_floats * 4);
+  h->gsplit2_floats = c.precision ? 0 : std::min((size_t)8 << 20, (size_t)16 * 4 * H * std::max(E, H));
+  h->gsplit2 = (float*)a.take(h->gsplit2_floats * 4);
   if (ce_slabs > 1) {                             // a second pair, so that slab s + 1 starts while dW_o of slab s still runs
     h->dzs2 = a.take(slab_elems * esz); h->dzTs2 = a.take(slab_elems * esz);
   } else {
@@ -379,11 +379,15 @@ void weight_grads(cmt_handle* h, LD& d, int Lsteps, const std::vector<std::pair<
   float* dW = h->grads + d.w_off;
   int col = 0;
   for (size_t i = 0; i < segs.size(); ++i) {
-    launch_gemm_nt(p, d.dGT, M, segs[i].first, segs[i].second, 4 * Hh, seg_k[i], M, dW + col, nullptr, d.Kin + Hh, nullptr, 0, st,
-                   h->gsplit2, h->gsplit_floats);
+    h->dw_group.push_back(GemmProb{d.dGT, segs[i].first, dW + col, M, segs[i].second, d.Kin + Hh, 4 * Hh, seg_k[i], M, 0});
     col += seg_k[i];
   }
   launch_colsum(p, d.dG, d.pg, M, 4 * Hh, h->colscr, h->grads + d.b_off, st);
+}
+// launches what weight_grads (and the callers that add W_c / W_a problems) have collected, as one queue of tiles
+void flush_dw_group(cmt_handle* h, hipStream_t st) {
+  launch_gemm_nt_group(h->prec, h->dw_group.data(), (int)h->dw_group.size(), st, h->gsplit2, h->gsplit2_floats);
+  h->dw_group.clear();
 }
 
 // marks the start of a phase of the step on the caller's stream (only when phase timing is on)
@@ -753,7 +757,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       n_dbo += (Mc + 63) / 64;
       stream_after(h, sd, st);
       launch_gemm_nt(p, dz, V, h->WoT, V, Mc, H, V, h->dHoCE + (size_t)m0 * H, nullptr, H, nullptr, 0, st, h->gsplit,
-                     h->gsplit_main_floats, lim, 1);                           // dH_o[slab] = dz W_o
+                     h->gsplit_floats, lim, 1);                           // dH_o[slab] = dz W_o
       // dW_o (+)= dz^T H_o[slab]; the first slab always holds a row, so W_o's gradient is always written
       launch_gemm_nt(p, dzT, h->ce_pitch, h->HocT + (size_t)m0 * esz, Mt, V, H, Mc, G + h->off_Wo, nullptr, H, nullptr, sl > 0,
                      sd, nullptr, 0, lim, 2);
@@ -855,9 +859,8 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     *ld = (S + 1) * Bp; return h->enc[l + 1].HstT + (size_t)Bp * esz;
   };
   // dW_c = dpre^T [C_s ; H_t]
-  launch_gemm_nt(p, h->dPreT, Mt, h->CsT, Mt, H, H, Mt, G + h->off_Wc, nullptr, 2 * H, nullptr, 0, sd, h->gsplit2, h->gsplit_floats);
-  launch_gemm_nt(p, h->dPreT, Mt, h->dec[L - 1].HstT + (size_t)Bp * esz, (T + 1) * Bp, H, H, Mt, G + h->off_Wc + H, nullptr,
-                 2 * H, nullptr, 0, sd, h->gsplit2, h->gsplit_floats);
+  h->dw_group.push_back(GemmProb{h->dPreT, h->CsT, G + h->off_Wc, Mt, Mt, 2 * H, H, H, Mt, 0});
+  h->dw_group.push_back(GemmProb{h->dPreT, h->dec[L - 1].HstT + (size_t)Bp * esz, G + h->off_Wc + H, Mt, (T + 1) * Bp, 2 * H, H, H, Mt, 0});
   for (int l = 0; l < L; ++l) {
     LD& e = h->dec[l];
     if (l == 0)
@@ -867,6 +870,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
                                   : std::pair<const char*, int>{h->dec[l - 1].HstT + (size_t)Bp * esz, (T + 1) * Bp},
                              {e.HstT, (T + 1) * Bp}}, {H, H}, sd);
   }
+  flush_dw_group(h, sd);                           // W_c and every decoder layer's weight gradient: one launch
   launch_gemm_nt(p, h->dec[0].dG, h->dec[0].pg, h->dec[0].Wt, 4 * H, Mt, E, 4 * H, h->dXt, nullptr, E, nullptr, 0, sd);
   launch_embed_scatter(h->dXt, h->tok_t, Mt, c.tgt_vocab, E, G + h->off_Etgt, sd, false);
 
@@ -878,7 +882,8 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   launch_transpose(p, h->dK, H, h->dKT, Ms, Ms, H, sd);
   {   // dW_a[r,c] = sum_i H_s[i,r] dK[i,c]
     int ld; const char* HsT = encYT(L - 1, &ld);
-    launch_gemm_nt(p, HsT, ld, h->dKT, Ms, H, H, Ms, G + h->off_Wa, nullptr, H, nullptr, 0, sd, h->gsplit2, h->gsplit_floats);
+    h->dw_group.push_back(GemmProb{HsT, h->dKT, G + h->off_Wa, ld, Ms, H, H, H, Ms, 0});
+    flush_dw_group(h, sd);
   }
 
   phase_mark(h, "encoder upper layers backward");
@@ -943,6 +948,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       int ld; const char* XT = encYT(l - 1, &ld);
       weight_grads(h, e, S, {{XT, ld}, {e.HstT, (S + 1) * Bp}}, {H, H}, sd);
     }
+    flush_dw_group(h, sd);
   } else if (L > 1) {
     const int Nplan = L > 2 ? 2 * H : H;
     const int kbE = step_kblocks(p, Nplan, 4 * H, Bp, h->kb_bwd);
@@ -987,6 +993,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       int ld; const char* XT = encYT(l - 1, &ld);
       weight_grads(h, e, S, {{XT, ld}, {e.HstT, (S + 1) * Bp}}, {H, H}, sd);
     }
+    flush_dw_group(h, sd);
   }
   phase_mark(h, "encoder bottom layer backward");
   {   // bottom layer: the two directions run in the same launches
@@ -1064,6 +1071,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     stream_after(h, sd, st);
     weight_grads(h, ef, S, {{h->XsT, Ms}, {ef.HstT, (S + 1) * Bp}}, {E, Hd}, sd);
     weight_grads(h, eb, S, {{h->XsT, Ms}, {eb.HstT + (size_t)Bp * esz, (S + 1) * Bp}}, {E, Hd}, sd);
+    flush_dw_group(h, sd);
     launch_gemm_nt(p, ef.dG, ef.pg, ef.Wt, 4 * Hd, Ms, E, 4 * Hd, h->dXs, nullptr, E, nullptr, 0, st);
     launch_gemm_nt(p, eb.dG, eb.pg, eb.Wt, 4 * Hd, Ms, E, 4 * Hd, h->dXs, nullptr, E, nullptr, 1, st);
     if (esrc_cleared) (void)hipStreamWaitEvent(st, esrc_cleared, 0);
@@ -1547,13 +1555,28 @@ int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_la
       launch_gemm_nt(p, h->Xt, E, d0.W, E + 2 * H, Mt, 4 * H, E, d0.Gx, nullptr, 4 * H, h->params + d0.b_off, 0, st);
     };
   } else if (s == "gemm_dw") {
-    // weight gradient of a decoder layer's recurrent block: dG^T [4H, T Bp] x H^T [H, T Bp]^T  (flops)
-    *algo_work = 2.0 * 4 * H * H * Mt;
-    launch = [=](int) {
-      LD& e = h->dec[L - 1];
-      launch_gemm_nt(p, e.dGT, Mt, e.HstT, (T + 1) * Bp, 4 * H, H, Mt, h->grads + e.w_off + e.Kin, nullptr, e.Kin + H, nullptr, 0,
-                     st, h->gsplit2, h->gsplit_floats);
-    };
+    // the decoder's weight gradients as the step launches them: W_c (two segments) and every layer's segments,
+    // dG^T [4H, T Bp] x X^T [width, T Bp]^T each, one grouped launch  (flops)
+    std::vector<GemmProb> probs;
+    probs.push_back(GemmProb{h->dPreT, h->CsT, h->grads + h->off_Wc, Mt, Mt, 2 * H, H, H, Mt, 0});
+    probs.push_back(GemmProb{h->dPreT, h->dec[L - 1].HstT + (size_t)Bp * es, h->grads + h->off_Wc + H, Mt, (T + 1) * Bp, 2 * H, H, H, Mt, 0});
+    for (int l = 0; l < L; ++l) {
+      LD& e = h->dec[l];
+      float* dW = h->grads + e.w_off;
+      if (l == 0) {
+        probs.push_back(GemmProb{e.dGT, h->XtT, dW, Mt, Mt, e.Kin + H, 4 * H, E, Mt, 0});
+        probs.push_back(GemmProb{e.dGT, h->HoBufT, dW + E, Mt, Mt + Bp, e.Kin + H, 4 * H, H, Mt, 0});
+        probs.push_back(GemmProb{e.dGT, e.HstT, dW + E + H, Mt, (T + 1) * Bp, e.Kin + H, 4 * H, H, Mt, 0});
+      } else {
+        if (h->drop_p > 0.f) probs.push_back(GemmProb{e.dGT, h->dec[l - 1].YdT, dW, Mt, Mt, e.Kin + H, 4 * H, H, Mt, 0});
+        else probs.push_back(GemmProb{e.dGT, h->dec[l - 1].HstT + (size_t)Bp * es, dW, Mt, (T + 1) * Bp, e.Kin + H, 4 * H, H, Mt, 0});
+        probs.push_back(GemmProb{e.dGT, e.HstT, dW + H, Mt, (T + 1) * Bp, e.Kin + H, 4 * H, H, Mt, 0});
+      }
+    }
+    double fl = 0;
+    for (const GemmProb& q : probs) fl += 2.0 * q.M * q.N * q.K;
+    *algo_work = fl;
+    launch = [=](int) { launch_gemm_nt_group(p, probs.data(), (int)probs.size(), st, h->gsplit2, h->gsplit2_floats); };
   } else if (s == "ce_fwd") {
     // vocabulary projection of one slab of rows with the partial log-sum-exp statistics  (flops)
     int nslab;

@@ -37,18 +37,27 @@ using GemmBig = GemmTile<4, 4, 2, 2, 128>;                 // 256 x 256, 1024 th
 // of 1 x 32 tiles would pull 33 panels through L2 instead of 12).  Returns false for padding ids.  The
 // launched grid must hold at least 8 * ceil(ntm * ntn / 8) workgroups.
 constexpr int GEMM_GROUP_M = 4;
-__device__ __forceinline__ bool gemm_tile_of_block(int ntm, int ntn, int bm, int bn, int& m0, int& n0) {
-  // `per` comes from the tiles that exist, not from the launched grid: a launch sized for more rows than the
-  // device-side count leaves (ids beyond the last tile exit) still spreads its tiles evenly over the XCDs
-  const int nt = ntm * ntn, per = (nt + 7) >> 3, j = blockIdx.x >> 3;
-  const int id = (blockIdx.x & 7) * per + j;
-  if (j >= per || id >= nt) return false;
+// tile number (in the grouped order described above) -> first row and column of the tile
+__device__ __forceinline__ void gemm_tile_from_index(int id, int ntm, int ntn, int bm, int bn, int& m0, int& n0) {
   const int gsz = GEMM_GROUP_M * ntn;
   const int grp = id / gsz, rem = id - grp * gsz;
   const int first = grp * GEMM_GROUP_M;
   const int gm = min(GEMM_GROUP_M, ntm - first);
   m0 = (first + rem % gm) * bm;
   n0 = (rem / gm) * bn;
+}
+// workgroup id -> tile number for a launch of at least 8 * ceil(nt / 8) workgroups over nt tiles; -1 for padding ids.
+// `per` comes from the tiles that exist, not from the launched grid: a launch sized for more rows than the
+// device-side count leaves (ids beyond the last tile exit) still spreads its tiles evenly over the XCDs.
+__device__ __forceinline__ int gemm_tile_index(int nt) {
+  const int per = (nt + 7) >> 3, j = blockIdx.x >> 3;
+  const int id = (blockIdx.x & 7) * per + j;
+  return (j >= per || id >= nt) ? -1 : id;
+}
+__device__ __forceinline__ bool gemm_tile_of_block(int ntm, int ntn, int bm, int bn, int& m0, int& n0) {
+  const int id = gemm_tile_index(ntm * ntn);
+  if (id < 0) return false;
+  gemm_tile_from_index(id, ntm, ntn, bm, bn, m0, n0);
   return true;
 }
 

@@ -25,6 +25,12 @@ void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, in
                     int limit_kind = 0);
 // Matrix-core issue-rate probe: `blocks` workgroups of 4 wavefronts, each `iters` x 4 bf16 32x32x16 MFMAs on
 // registers; out needs blocks * 256 floats.  Returns the flops of the launch.
+// Several independent C (+)= A * B^T problems (fp32 C, no bias) as one launch: the tiles of all problems form one
+// queue spread over the chip, so that small problems fill each other's partial rounds and there are no gaps between
+// them (the weight-gradient GEMMs of the step, the paper's calculateGradient with beta = 1 batched over time).
+struct GemmProb { const void* A; const void* B; float* C; int lda, ldb, ldc, M, N, K, accumulate; };
+// split_scratch: planes for the fp32 path, which launches the problems one by one (see launch_gemm_nt).
+void launch_gemm_nt_group(int prec, const GemmProb* probs, int n, hipStream_t st, float* split_scratch, size_t split_scratch_floats);
 double launch_mfma_rate(float* out, int blocks, int iters, hipStream_t st);
 // out[C,R] = in[R,C]^T for T matrices (ldin, ldout in elements).
 void launch_transpose(int prec, const void* in, int ldin, void* out, int ldout, int R, int C, hipStream_t st);
