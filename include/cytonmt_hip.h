@@ -214,7 +214,7 @@ int cmt_padded_batch(const cmt_handle* h);
  *   "step2d_bwd_dec" [dx; dh] = dgates [W_x; W_h] of a decoder layer's backward step       bytes
  *   "att_fwd"        attention scores + softmax + context of one decoder step              bytes
  *   "gemm_gx"        time-batched input-side GEMM [T Bp, E] x [E, 4H]                      flops
- *   "gemm_dw"        time-batched weight-gradient GEMM [4H, T Bp] x [T Bp, H]              flops
+ *   "gemm_dw"        the decoder's weight-gradient GEMMs (W_c and every layer, k = T Bp), one grouped launch  flops
  *   "ce_fwd"         vocabulary projection + log-sum-exp partials of the first slab of rows flops
  *   "step_bwd_fused_dec" the same product as step2d_bwd_dec in the form the decoder's backward loop runs:
  *                    whole contraction per workgroup, cell backward of the layer below in the epilogue bytes
