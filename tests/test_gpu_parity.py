@@ -184,6 +184,20 @@ def test_extreme_configurations(prec, B, S, T, H, E, L, Vs, Vt):
 
 
 @pytest.mark.parametrize("prec", [0, 1])
+@pytest.mark.parametrize("B,T,V", [(5, 6, 8200), (40, 9, 16520)])
+def test_vocabulary_long_enough_for_the_k_split_of_the_output_gradient(prec, B, T, V):
+    """dH_o = dz W_o contracts over the vocabulary; from 8192 entries on it runs on 256 x 256 tiles with the k
+    range split into planes, the number of splits chosen on the device from the valid row count.  Vocabularies
+    just over the threshold and not a multiple of the 64-entry k tile, with one row tile (few rows) and with two."""
+    cfg = dict(src_vocab=40, tgt_vocab=V, emb=16, hidden=64, layers=1)
+    rng = np.random.default_rng(V)
+    params = I.make_params(cfg, seed=V % 97, scale=0.3)
+    batch = ragged_batch(rng, B, 4, T, cfg["src_vocab"], cfg["tgt_vocab"])
+    loss, oloss, worst, tr = run_case(cfg, params, batch, prec, check_inter=False)
+    tr.close()
+
+
+@pytest.mark.parametrize("prec", [0, 1])
 @pytest.mark.parametrize("forms", [0, 2, 7])
 @pytest.mark.parametrize("B,S,T,H,E,L", [(19, 9, 8, 80, 40, 3), (64, 6, 7, 256, 64, 2), (70, 5, 4, 48, 16, 2)])
 def test_every_form_of_the_backward_loops(prec, forms, B, S, T, H, E, L, monkeypatch):
