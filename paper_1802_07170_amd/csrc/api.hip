@@ -338,11 +338,11 @@ void bind_params(cmt_handle* h) {
 }
 
 // refresh the kernels' working copies of the parameters: operand-type cast, transposes
-void refresh_params(cmt_handle* h) {
+void refresh_params(cmt_handle* h, bool cast = true) {
   const cmt_config& c = h->cfg;
   const int H = c.hidden, p = h->prec;
   hipStream_t st = h->st;
-  if (p) launch_cast(1, h->params, h->Pc, h->nparams, st);
+  if (p && cast) launch_cast(1, h->params, h->Pc, h->nparams, st);
   auto tr = [&](LD& d) { launch_transpose(p, d.W, d.Kin + d.Hh, d.Wt, 4 * d.Hh, 4 * d.Hh, d.Kin + d.Hh, st); };
   for (auto& d : h->enc) tr(d);
   for (auto& d : h->dec) tr(d);
@@ -1472,8 +1472,8 @@ int cmt_beam_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* sr
 int cmt_sgd_update(cmt_handle* h, float lr) {
   if (!h) return CMT_EINVAL;
   if (!isfinite(lr)) return fail(h, CMT_EINVAL, "learning rate is not finite");
-  launch_sgd(h->params, h->grads, h->nparams, lr, h->flags, h->st);
-  refresh_params(h);
+  launch_sgd(h->params, h->grads, h->nparams, lr, h->flags, h->prec ? h->Pc : nullptr, h->st);
+  refresh_params(h, false);                        // the update wrote the bf16 copy itself: only the transposes are left
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(h, e, "cmt_sgd_update");
   return CMT_OK;

@@ -235,7 +235,8 @@ void launch_sum_parts(const float* parts, int nparts, size_t n, float* out, hipS
 // db[n] = sum_m dG[m, n] over M rows of a T matrix [M, N].
 void launch_colsum(int prec, const void* dG, int ld, int M, int N, float* scratch /*[16*N]*/, float* db, hipStream_t st);
 // p <- p - lr g; skipped entirely while *flags != 0 (flags may be null)
-void launch_sgd(float* p, const float* g, size_t n, float lr, const int* flags, hipStream_t st);
+// bf16_copy (may be null): the bf16 working copy of p, rewritten in the same pass
+void launch_sgd(float* p, const float* g, size_t n, float lr, const int* flags, void* bf16_copy, hipStream_t st);
 void launch_init_uniform(float* p, size_t n, uint64_t seed, float scale, hipStream_t st);
 
 // Chip-wide barrier probe: `blocks` workgroups (they must all be resident: at most one per CU) pass `rounds`

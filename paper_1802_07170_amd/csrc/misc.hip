@@ -267,17 +267,35 @@ void launch_colsum(int prec, const void* dG, int ld, int M, int N, float* scratc
   launch_sum_parts(scratch, COLSUM_SPLITS, (size_t)N, db, st);
 }
 
-// nothing is updated while an error flag of an earlier step is pending (its gradients are undefined)
+// p <- p - lr g, four elements per thread and pass; with pc the bf16 working copy of the parameters is written in
+// the same pass (one read of p less than a separate cast).  Nothing is updated while an error flag of an earlier
+// step is pending (its gradients are undefined); the working copy then stays valid as it is.
 __global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ p, const float* __restrict__ g, size_t n, float lr,
-                                                  const int* __restrict__ flags) {
+                                                  const int* __restrict__ flags, bf16_t* __restrict__ pc) {
   if (flags && *flags) return;
-  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t n4 = n >> 2;
   const size_t stride = (size_t)gridDim.x * 256;
-  for (; i < n; i += stride) p[i] = p[i] - lr * g[i];
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
+    float4 a = reinterpret_cast<const float4*>(p)[i];
+    const float4 b = reinterpret_cast<const float4*>(g)[i];
+    a.x -= lr * b.x; a.y -= lr * b.y; a.z -= lr * b.z; a.w -= lr * b.w;
+    reinterpret_cast<float4*>(p)[i] = a;
+    if (pc) {
+      uint2 o;
+      o.x = (uint32_t)f2bf(a.x) | ((uint32_t)f2bf(a.y) << 16);
+      o.y = (uint32_t)f2bf(a.z) | ((uint32_t)f2bf(a.w) << 16);
+      reinterpret_cast<uint2*>(pc)[i] = o;
+    }
+  }
+  for (size_t i = (n4 << 2) + (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+    const float v = p[i] - lr * g[i];
+    p[i] = v;
+    if (pc) pc[i] = f2bf(v);
+  }
 }
-void launch_sgd(float* p, const float* g, size_t n, float lr, const int* flags, hipStream_t st) {
+void launch_sgd(float* p, const float* g, size_t n, float lr, const int* flags, void* bf16_copy, hipStream_t st) {
   if (n == 0) return;
-  hipLaunchKernelGGL(sgd_kernel, dim3(grid_for(n)), dim3(256), 0, st, p, g, n, lr, flags);
+  hipLaunchKernelGGL(sgd_kernel, dim3(grid_for((n + 3) / 4)), dim3(256), 0, st, p, g, n, lr, flags, (bf16_t*)bf16_copy);
 }
 
 // SplitMix64 of (seed + element index); top 24 bits -> uniform [-scale, scale)

@@ -624,6 +624,38 @@ def test_two_steps_are_bit_identical_and_sgd_matches_oracle():
     tr.close()
 
 
+def test_sgd_update_keeps_the_bf16_working_copies_in_step_with_the_parameters():
+    """bf16 path: the update rewrites the kernels' bf16 copy of the parameters (and their transposes) in the
+    same pass as the fp32 master.  After an update with a learning rate that is no power of two, the next step on
+    this handle must equal, bit for bit, the step of a fresh handle that is given the updated fp32 parameters;
+    the master itself is p - lr g (one rounding or two: the device may contract the multiply-add).  An odd
+    parameter count (vocabulary of 8 x 13 entries, hidden 48) exercises the tail of the vectorised kernel."""
+    from paper_1802_07170_amd import binding
+    cfg = dict(src_vocab=104, tgt_vocab=136, emb=24, hidden=48, layers=2)
+    rng = np.random.default_rng(5)
+    params = I.make_params(cfg, seed=9, scale=0.3)
+    batch = ragged_batch(rng, 19, 7, 6, 104, 136)
+    tr = binding.Trainer(cfg, 19, 7, 6, precision=1)
+    p0 = I.flatten(params, cfg)
+    tr.set_params(p0)
+    dev = tr.upload_batch(*batch)
+    tr.train_step(dev)
+    g = tr.get_grads()
+    lr = 0.37
+    tr.sgd_update(lr)
+    p1 = tr.get_params()
+    exact = p0.astype(np.float64) - np.float64(np.float32(lr)) * g.astype(np.float64)
+    assert np.abs(p1 - exact).max() <= 2.0 ** -23 * np.abs(exact).max()
+    l_same = tr.train_step(dev)
+    g_same = tr.get_grads()
+    tr.close()
+    fresh = binding.Trainer(cfg, 19, 7, 6, precision=1)
+    fresh.set_params(p1)
+    l_fresh = fresh.train_step(fresh.upload_batch(*batch))
+    assert l_same == l_fresh and np.array_equal(g_same, fresh.get_grads())
+    fresh.close()
+
+
 def test_sgd_training_with_the_paper_s_regularisation_and_controller_learns():
     """End to end on the device: 60 SGD steps on one small batch with dropout 0.2 / label smoothing
     0.1 (a new mask seed per step), the development entropy (same batch, regularisation off) checked
