@@ -382,9 +382,22 @@ __global__ __launch_bounds__(1024) void dec_argmax_kernel(const float* __restric
   const int b = blockIdx.x, t = threadIdx.x;
   float best = -INFINITY;
   int bi = 0x7fffffff;
-  for (int v = t; v < V; v += 1024) {                    // ascending v: '>' keeps the lowest index of equal values
-    const float x = z[(size_t)b * ldz + v] + bias[v];
-    if (x > best || (x == best && v < bi)) { best = x; bi = v; }
+  // equal values: the lowest index wins, whatever order the candidates come in
+  const float* zr = z + (size_t)b * ldz;
+  if ((V & 3) == 0 && (ldz & 3) == 0 && (((size_t)z | (size_t)bias) & 15) == 0) {
+    for (int v = 4 * t; v < V; v += 4096) {              // 16-byte loads: four candidates per thread and pass
+      const float4 a = *reinterpret_cast<const float4*>(zr + v);
+      const float4 c = *reinterpret_cast<const float4*>(bias + v);
+      const float x[4] = {a.x + c.x, a.y + c.y, a.z + c.z, a.w + c.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (x[q] > best || (x[q] == best && v + q < bi)) { best = x[q]; bi = v + q; }
+    }
+  } else {
+    for (int v = t; v < V; v += 1024) {
+      const float x = zr[v] + bias[v];
+      if (x > best || (x == best && v < bi)) { best = x; bi = v; }
+    }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
