@@ -3,11 +3,12 @@
 // this form).  WM x WN wavefronts; each wavefront owns TA x TB MFMA 32x32 tiles, so the workgroup
 // tile is (32 TA WM) x (32 TB WN).  Two shapes are used:
 //   * 2x2 wavefronts, 2x2 tiles each: 128 x 128, 256 threads, 72 KB of LDS, two workgroups per CU
-//     hiding each other's barriers.  Reads 32 KB from L2 per 2 x 128 x 128 x 64 flops: at the
-//     800 TFLOP/s it reaches, L2 -> CU traffic is 12 TB/s, which is what bounds it.
+//     hiding each other's barriers.  Needs 32 KB from L2 per 2 x 128 x 128 x 64 flops.
 //   * 4x4 wavefronts, 2x2 tiles each: 256 x 256, 1024 threads, 144 KB of LDS, one workgroup per CU.
-//     Half the L2 traffic per flop: 1.1 PFLOP/s on large problems, and faster than the small tile
-//     whenever there are about 200 or more tiles.
+//     Half the L2 traffic per flop (64 KB per k tile): 1.3 PFLOP/s on large problems, and faster than the
+//     small tile whenever there are about 200 or more tiles.
+// What bounds both is the rate at which a CU takes data from L2: about 49 GB/s per CU measured with the main
+// loop's loads alone (12.6 TB/s over the chip), i.e. at most 1.6 PFLOP/s for the big tile and 0.8 for the small.
 // Tiles of KB bytes of k per row are double-buffered in LDS; the next tile's global loads are in
 // flight while the current one feeds the matrix cores.  16-bit operands go from global memory straight
 // into LDS (global_load_lds_dwordx4, no staging registers): rows of 128 bytes without padding, the
