@@ -51,6 +51,12 @@ struct LD {
   char* YdT = nullptr;               // ... and its transpose [Hh, L*Bp]; used only while dropout is on
   float* dh = nullptr; float* dc = nullptr;   // [Bp, Hh]
   float* bwdp = nullptr;             // [8][Bp][2Hh] backward step-GEMM planes
+  // fragment-major copies read by the per-step kernels (bf16 path, Hh a multiple of 32; see fm_offset)
+  int Kstep = 0;                     // width of the per-step input segment: the x columns [Kin - Kstep, Kin) of W
+  char* Wfm = nullptr;               // gate rows of W, columns [Kin - Kstep, Kin + Hh)
+  char* HstF = nullptr;              // [(Lmax+1)] slots of [Bp, Hh]
+  char* YdF = nullptr;               // [Lmax] slots of [Bp, Hh] (the layer's output after dropout)
+  bool fm = false;
 };
 
 // Row pitch padding of the per-step activation operands.  The step kernels read 16 sentences x 64
@@ -131,6 +137,7 @@ struct cmt_handle {
   std::vector<hipEvent_t> ev; size_t ev_next = 0;
   int use_side = 1;
   char* dzs2 = nullptr; char* dzTs2 = nullptr;
+  char* HoFeedF = nullptr;              // fragment-major copy of the H_o rows fed to the decoder's bottom layer, [(Tmax+1)] slots of [Bp, H]
   int kb_bwd = 0, kb_wc = 0;            // caps on the k blocks of the backward step GEMMs (0 = default)
   // backward loops that use the whole-k step GEMM with the consumer in its epilogue (env CMT_BWD_FUSED, a bit
   // mask): 1 = decoder (up to 64 sentences; at 128 every workgroup's re-read of the step's dgates makes it
@@ -219,9 +226,16 @@ size_t layout(cmt_handle* h, char* base) {
   h->PH = H + ACT_PAD;
   const size_t PH = h->PH;
   h->Pc = c.precision ? a.take(h->nparams * esz) : (char*)h->params;
-  auto ld_alloc = [&](LD& d, int Kin, int Hh, int Lm, bool gx) {
+  auto ld_alloc = [&](LD& d, int Kin, int Hh, int Lm, bool gx, int Kstep) {
     d.Kin = Kin; d.Hh = Hh; d.ph = Hh + ACT_PAD; d.pg = 4 * Hh + ACT_PAD;
     const size_t M = (size_t)Lm * Bp;
+    d.Kstep = Kstep;
+    d.fm = c.precision && Hh % 32 == 0 && Kstep % 32 == 0;
+    if (d.fm) {
+      d.Wfm = a.take((size_t)4 * Hh * (Kstep + Hh) * esz);
+      d.HstF = a.take((M + Bp) * Hh * esz);
+      d.YdF = a.take(M * Hh * esz);
+    }
     d.Wt = a.take((size_t)(Kin + Hh) * 4 * Hh * esz);
     d.Hst = a.take((M + Bp) * d.ph * esz);
     d.Cst = (float*)a.take((M + Bp) * Hh * 4);
@@ -238,11 +252,14 @@ size_t layout(cmt_handle* h, char* base) {
   };
   h->enc.assign(L + 1, LD());
   h->dec.assign(L, LD());
-  ld_alloc(h->enc[0], E, Hd, Sm, true);
-  ld_alloc(h->enc[1], E, Hd, Sm, true);
-  for (int l = 1; l < L; ++l) ld_alloc(h->enc[l + 1], H, H, Sm, true);
-  ld_alloc(h->dec[0], E + H, H, Tm, true);
-  for (int l = 1; l < L; ++l) ld_alloc(h->dec[l], H, H, Tm, false);
+  // per-step input segment: none for the layers whose input part is batched over time (bottom encoder layers,
+  // encoder layer 1), the fed H_o for the decoder's bottom layer, the layer below's state for the others
+  ld_alloc(h->enc[0], E, Hd, Sm, true, 0);
+  ld_alloc(h->enc[1], E, Hd, Sm, true, 0);
+  for (int l = 1; l < L; ++l) ld_alloc(h->enc[l + 1], H, H, Sm, true, l == 1 ? 0 : H);
+  ld_alloc(h->dec[0], E + H, H, Tm, true, H);
+  for (int l = 1; l < L; ++l) ld_alloc(h->dec[l], H, H, Tm, false, H);
+  if (c.precision && H % 32 == 0) h->HoFeedF = a.take((Mt + Bp) * H * esz);
   h->WaT = a.take((size_t)H * H * esz);
   h->WcT = a.take((size_t)2 * H * H * esz);
   h->WoT = a.take((size_t)H * c.tgt_vocab * esz);
@@ -343,7 +360,10 @@ void refresh_params(cmt_handle* h, bool cast = true) {
   const int H = c.hidden, p = h->prec;
   hipStream_t st = h->st;
   if (p && cast) launch_cast(1, h->params, h->Pc, h->nparams, st);
-  auto tr = [&](LD& d) { launch_transpose(p, d.W, d.Kin + d.Hh, d.Wt, 4 * d.Hh, 4 * d.Hh, d.Kin + d.Hh, st); };
+  auto tr = [&](LD& d) {
+    launch_transpose(p, d.W, d.Kin + d.Hh, d.Wt, 4 * d.Hh, 4 * d.Hh, d.Kin + d.Hh, st);
+    if (d.fm) launch_fm_pack_lstm_weights(d.W, d.Kin + d.Hh, d.Kin - d.Kstep, d.Kstep + d.Hh, d.Hh, d.Wfm, st);
+  };
   for (auto& d : h->enc) tr(d);
   for (auto& d : h->dec) tr(d);
   launch_transpose(p, h->Pw(h->off_Wa), H, h->WaT, H, H, H, st);
@@ -497,6 +517,13 @@ void dec_lstm_fwd(cmt_handle* h, int l, int j) {
   if (drop && l + 1 < c.layers) {                  // what the layer above reads
     d.ycat = e.Yd + j * BP * esz; d.ldy = e.ph; d.drop = drop_spec(h, DROP_SITE_DEC + l, j); d.drop_col0 = 0;
   }
+  if (e.fm) {                                      // the contraction's operands in fragment-major form
+    d.W_fm = e.Wfm;
+    d.x_fm = l == 0 ? h->HoFeedF + j * BH * esz
+                    : (drop ? h->dec[l - 1].YdF + j * BH * esz : h->dec[l - 1].HstF + (j + 1) * BH * esz);
+    d.hprev_fm = e.HstF + j * BH * esz; d.hnext_fm = e.HstF + (j + 1) * BH * esz;
+    if (d.ycat) d.ycat_fm = e.YdF + j * BH * esz;
+  }
   launch_lstm_fwd(h->prec, &d, 1, Bp, H, h->st);
 }
 
@@ -524,7 +551,11 @@ void enqueue_encoder(cmt_handle* h, int S, const char** Hs_out, int* ldHs_out) {
     std::vector<FillJob> z;
     add_fill(z, ef.Hst, BPd, esz); add_fill(z, ef.Cst, BHd, 4);
     add_fill(z, eb.Hst + (size_t)S * BPd * esz, BPd, esz); add_fill(z, eb.Cst + (size_t)S * BHd, BHd, 4);
-    for (int l = 1; l < L; ++l) { add_fill(z, h->enc[l + 1].Hst, BP, esz); add_fill(z, h->enc[l + 1].Cst, BH, 4); }
+    if (ef.fm) { add_fill(z, ef.HstF, BHd, esz); add_fill(z, eb.HstF + (size_t)S * BHd * esz, BHd, esz); }
+    for (int l = 1; l < L; ++l) {
+      add_fill(z, h->enc[l + 1].Hst, BP, esz); add_fill(z, h->enc[l + 1].Cst, BH, 4);
+      if (h->enc[l + 1].fm) add_fill(z, h->enc[l + 1].HstF, BH, esz);
+    }
     launch_fill_multi(z.data(), (int)z.size(), st);
   }
   for (int k = 0; k < S; ++k) {
@@ -543,6 +574,9 @@ void enqueue_encoder(cmt_handle* h, int S, const char** Hs_out, int* ldHs_out) {
       d[i].gsave = e.Gs + (size_t)t * Bp * 4 * Hd;
       d[i].ycat = h->Y0 + ((size_t)t * BH + (i ? Hd : 0)) * esz; d[i].ldy = H;
       if (L > 1) { d[i].drop = drop_spec(h, DROP_SITE_ENC + 0, t); d[i].drop_col0 = i ? Hd : 0; }
+      if (e.fm) {
+        d[i].W_fm = e.Wfm; d[i].hprev_fm = e.HstF + sp * BHd * esz; d[i].hnext_fm = e.HstF + sn * BHd * esz;
+      }
     }
     launch_lstm_fwd(p, d, 2, Bp, Hd, st);
   }
@@ -579,6 +613,11 @@ void enqueue_encoder(cmt_handle* h, int S, const char** Hs_out, int* ldHs_out) {
         if (drop && l + 1 < L) {
           d.ycat = e.Yd + t * BP * esz; d.ldy = e.ph; d.drop = drop_spec(h, DROP_SITE_ENC + l, t); d.drop_col0 = 0;
         }
+        if (e.fm) {
+          d.W_fm = e.Wfm; d.hprev_fm = e.HstF + t * BH * esz; d.hnext_fm = e.HstF + (t + 1) * BH * esz;
+          if (l > 1) d.x_fm = drop ? h->enc[l].YdF + t * BH * esz : h->enc[l].HstF + (t + 1) * BH * esz;
+          if (d.ycat) d.ycat_fm = e.YdF + t * BH * esz;
+        }
       }
       launch_lstm_fwd(p, dirs, n, Bp, H, st);
     }
@@ -605,6 +644,8 @@ void enqueue_encoder(cmt_handle* h, int S, const char** Hs_out, int* ldHs_out) {
       add_copy(cp, e.Cst + (size_t)S * BH, H, d.Cst, H, Bp, H, 4);
     }
     launch_copy2d_multi(cp.data(), (int)cp.size(), st);
+    for (int l = 0; l < L; ++l)                     // fragment-major copies of the initial states
+      if (h->dec[l].fm) launch_fm_pack(h->dec[l].Hst, h->dec[l].ph, Bp, H, h->dec[l].HstF, st);
   }
 }
 
@@ -635,6 +676,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     std::vector<FillJob> z;
     add_fill(z, h->HoBuf, BP, esz);
     if (drop) add_fill(z, h->HoDrop, BP, esz);
+    if (h->HoFeedF) add_fill(z, h->HoFeedF, BH, esz);
     for (int l = 0; l < L; ++l) { add_fill(z, h->dec[l].dh, BH, 4); add_fill(z, h->dec[l].dc, BH, 4); }
     launch_fill_multi(z.data(), (int)z.size(), st);
   }
@@ -667,6 +709,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       g.outT = h->HoBuf + (j + 1) * BP * esz; g.ldo = PH;
       if (drop) { g.outD = h->HoDrop + (j + 1) * BP * esz; g.ldod = PH; g.drop = drop_spec(h, DROP_SITE_HO, j); }
       g.out = h->wcp; g.ldout = H; g.plane_stride = BH;
+      if (h->HoFeedF) g.outF = h->HoFeedF + (j + 1) * BH * esz;
       launch_step_gemm(p, g, Bp, st);
     }
   }

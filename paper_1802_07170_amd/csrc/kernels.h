@@ -107,7 +107,25 @@ struct LstmFwdDir {
   void* ycat; int ldy;                  // optional second copy of h (T*, row pitch ldy), or null:
   DropSpec drop{}; int drop_col0 = 0;   //   the layer's output as the layer above sees it, i.e. after
                                         //   dropout (columns drop_col0 + [0, Hh) of the site)
+  // Fragment-major copies (16-bit operands, see fm_offset; null = not used).  With W_fm set the contraction reads
+  // W_fm (the columns [wh_off - Kx, wh_off + Hh) of W), x_fm (if Kx > 0) and hprev_fm instead of W, x and hprev;
+  // hnext_fm / ycat_fm receive a second copy of what goes to hnext / ycat.  Needs Kx and Hh multiples of 32.
+  const void* W_fm = nullptr; const void* x_fm = nullptr; const void* hprev_fm = nullptr;
+  void* hnext_fm = nullptr; void* ycat_fm = nullptr;
 };
+// Fragment-major storage of a 16-bit matrix [rows, K] that a step kernel reads as a matrix-core operand: 1 KB blocks
+// [row / 16][k / 32][lane][8 elements] with lane = row % 16 + 16 * ((k % 32) / 8) — the register image of the
+// 16x16x32 MFMA operand, so that a wavefront's fragment load is one contiguous kilobyte instead of 16 pieces of
+// 64 bytes from 16 rows (measured on the decoder layer step: 2.3 times the rate from L2).  nsteps = K / 32.
+inline __host__ __device__ size_t fm_offset(int row, int k, int nsteps) {
+  return ((((size_t)(row >> 4) * nsteps + (k >> 5)) * 64 + (row & 15) + 16 * ((k & 31) >> 3)) << 3) + (k & 7);
+}
+// dst (fragment-major, nsteps = cols / 32) <- src [rows, cols] row-major with pitch ld (16-bit elements; rows a
+// multiple of 16, cols a multiple of 32)
+void launch_fm_pack(const void* src, int ld, int rows, int cols, void* dst, hipStream_t st);
+// the same for the gate rows of an LSTM weight matrix: tile T holds units 4T .. 4T+3, row m of the tile is gate m % 4
+// of unit 4T + m / 4 (rows of W are gate-major: gate * Hh + unit); columns [col0, col0 + K) of W
+void launch_fm_pack_lstm_weights(const void* W, int ldw, int col0, int K, int Hh, void* dst, hipStream_t st);
 // ndir <= STEP_MAX_INST instances of equal hidden width Hh in one launch.
 void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh, hipStream_t st);
 
@@ -125,6 +143,8 @@ struct StepGemm {
   void* outT; int ldo;
   void* outD = nullptr; int ldod = 0;  // mode 0: optional copy of outT after dropout `drop`
   DropSpec drop{};
+  void* outF = nullptr;                // mode 0, 16-bit types: optional fragment-major copy (fm_offset, N / 32 k steps) of
+                                       //   what the next step is fed: outD's values if outD is set, else outT's
   float* out; int ldout; size_t plane_stride;
   int max_kb;          // cap on the number of k blocks (planes); 0 = default (8)
 };

@@ -104,6 +104,56 @@ __device__ __forceinline__ v4f step_tile_sum(const float* red, int rt, int bt) {
   return r;
 }
 
+// The same contraction on fragment-major operands (bf16): wt[rt] = first block of row tile rt (its k steps follow
+// each other), a0 / a1 = fragment-major activation segments of ns0 / ns1 k steps (batch tile bt at bt * ns blocks).
+template <int RT, int KS, int U, int BT>
+__device__ __forceinline__ void step_contract_fm(const bf16_t* const (&wt)[RT], const bf16_t* a0, int ns0, const bf16_t* a1, int ns1,
+                                                 int bt0, int nbt, float* red) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int nsteps = ns0 + ns1;
+  v4f acc[RT][BT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int b = 0; b < BT; ++b) acc[rt][b] = v4f{0.f, 0.f, 0.f, 0.f};
+  for (int s0 = 0; s0 < nsteps; s0 += KS * U) {
+    Frag<bf16_t> fw[U][RT], fx[U][BT];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int s = s0 + w + KS * u;
+      if (s < nsteps) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) fw[u][rt].load(wt[rt] + ((size_t)s * 64 + lane) * 8);
+        const bool first = s < ns0;
+        const bf16_t* a = first ? a0 : a1;
+        const int ns = first ? ns0 : ns1, sl = first ? s : s - ns0;
+#pragma unroll
+        for (int b = 0; b < BT; ++b) {
+          if (b < nbt) fx[u][b].load(a + (((size_t)(bt0 + b) * ns + sl) * 64 + lane) * 8);
+          else fx[u][b].zero();
+        }
+      } else {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) fw[u][rt].zero();
+#pragma unroll
+        for (int b = 0; b < BT; ++b) fx[u][b].zero();
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int b = 0; b < BT; ++b) mma16(acc[rt][b], fw[u][rt], fx[u][b]);
+  }
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int b = 0; b < BT; ++b)
+      *reinterpret_cast<v4f*>(red + (((w * RT + rt) * BT + b) * 64 + lane) * 4) = acc[rt][b];
+  __syncthreads();
+}
+
 // keep-and-rescale factor of element (b, col) of a dropout slice (see DropSpec)
 __device__ __forceinline__ float drop_factor(const DropSpec& d, int b, int col) {
   if (!d.on) return 1.f;
@@ -119,6 +169,48 @@ __device__ __forceinline__ float planes_get(const Planes& p, int b, int c) {
   float v = 0.f;
   for (int k = 0; k < p.np; ++k) v += p.p[(size_t)k * p.stride + (size_t)b * p.ld + c];
   return v;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Row-major -> fragment-major copies (16-bit elements)
+// ------------------------------------------------------------------------------------------------
+// one thread per 16-byte chunk of the destination: block (row tile, k step), lane, 8 elements
+__global__ __launch_bounds__(256) void fm_pack_kernel(const bf16_t* __restrict__ src, int ld, int rows, int nsteps, bf16_t* __restrict__ dst) {
+  const size_t n = (size_t)(rows >> 4) * nsteps * 64;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const int lane = (int)(i & 63);
+    const size_t blk = i >> 6;
+    const int s = (int)(blk % nsteps), rt = (int)(blk / nsteps);
+    const int row = rt * 16 + (lane & 15), k = s * 32 + (lane >> 4) * 8;
+    *reinterpret_cast<uint4*>(dst + i * 8) = *reinterpret_cast<const uint4*>(src + (size_t)row * ld + k);
+  }
+}
+void launch_fm_pack(const void* src, int ld, int rows, int cols, void* dst, hipStream_t st) {
+  const size_t n = (size_t)(rows >> 4) * (cols >> 5) * 64;
+  if (n == 0) return;
+  size_t g = (n + 255) / 256;
+  if (g > 65535) g = 65535;
+  hipLaunchKernelGGL(fm_pack_kernel, dim3((unsigned)g), dim3(256), 0, st, (const bf16_t*)src, ld, rows, cols >> 5, (bf16_t*)dst);
+}
+__global__ __launch_bounds__(256) void fm_pack_lstm_weights_kernel(const bf16_t* __restrict__ W, int ldw, int col0, int nsteps, int Hh,
+                                                                   bf16_t* __restrict__ dst) {
+  const size_t n = (size_t)(Hh >> 2) * nsteps * 64;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const int lane = (int)(i & 63);
+    const size_t blk = i >> 6;
+    const int s = (int)(blk % nsteps), tile = (int)(blk / nsteps);
+    const int m = lane & 15;
+    const int row = (m & 3) * Hh + 4 * tile + (m >> 2), k = col0 + s * 32 + (lane >> 4) * 8;
+    *reinterpret_cast<uint4*>(dst + i * 8) = *reinterpret_cast<const uint4*>(W + (size_t)row * ldw + k);
+  }
+}
+void launch_fm_pack_lstm_weights(const void* W, int ldw, int col0, int K, int Hh, void* dst, hipStream_t st) {
+  const size_t n = (size_t)(Hh >> 2) * (K >> 5) * 64;
+  if (n == 0) return;
+  size_t g = (n + 255) / 256;
+  if (g > 65535) g = 65535;
+  hipLaunchKernelGGL(fm_pack_lstm_weights_kernel, dim3((unsigned)g), dim3(256), 0, st, (const bf16_t*)W, ldw, col0, K >> 5, Hh,
+                     (bf16_t*)dst);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -153,6 +245,8 @@ __device__ __forceinline__ void cell_finish(const LstmFwdDir& d, int b, int u, i
   if (is_bf16) {
     ((bf16_t*)d.hnext)[(size_t)b * d.ldhn + u] = f2bf(hv);   // a carried state is already a bf16 value: exact
     if (d.ycat) ((bf16_t*)d.ycat)[(size_t)b * d.ldy + u] = f2bf(yv);
+    if (d.hnext_fm) ((bf16_t*)d.hnext_fm)[fm_offset(b, u, Hh >> 5)] = f2bf(hv);
+    if (d.ycat_fm) ((bf16_t*)d.ycat_fm)[fm_offset(b, u, Hh >> 5)] = f2bf(yv);
   } else {
     ((float*)d.hnext)[(size_t)b * d.ldhn + u] = hv;
     if (d.ycat) ((float*)d.ycat)[(size_t)b * d.ldy + u] = yv;
@@ -163,7 +257,7 @@ __device__ __forceinline__ void cell_finish(const LstmFwdDir& d, int b, int u, i
 // whole k range inside the workgroup.  Per workgroup RT weight slabs and BT activation slabs cross L2:
 // for 64 sentences RT = BT = 2 moves the fewest bytes (each weight slab is then read by two workgroups,
 // which the XCD-aware numbering puts on the same L2).
-template <typename T, int RT, int KS, int U, int BT>
+template <typename T, int RT, int KS, int U, int BT, bool FM = false>
 __global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(LstmFwdArgs args, int Bp, int Hh, StepGrid sg, int ndir) {
   __shared__ __align__(16) float red[KS * RT * BT * 256];
   int x, kb, z;
@@ -190,8 +284,16 @@ __global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(LstmFwdArgs args, int
     have0 = bt < nbt && u < Hh && b < Bp;
     if (have0) in0 = cell_load(d, b, u, Hh, sizeof(T) == 2);
   }
-  step_contract<T, RT, KS, U, BT>(wrow, d.wx_off, d.wh_off, (const T*)d.x, d.ldx, d.Kx, (const T*)d.hprev, d.ldh, Hh, Bp, bt0,
-                              nbt, red);
+  if constexpr (FM) {
+    const int ns0 = d.Kx >> 5, ns1 = Hh >> 5;
+    const bf16_t* wt[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) wt[rt] = (const bf16_t*)d.W_fm + (size_t)((u0 >> 2) + rt) * (ns0 + ns1) * 512;
+    step_contract_fm<RT, KS, U, BT>(wt, (const bf16_t*)d.x_fm, ns0, (const bf16_t*)d.hprev_fm, ns1, bt0, nbt, red);
+  } else {
+    step_contract<T, RT, KS, U, BT>(wrow, d.wx_off, d.wh_off, (const T*)d.x, d.ldx, d.Kx, (const T*)d.hprev, d.ldh, Hh, Bp, bt0,
+                                    nbt, red);
+  }
   for (int t = w; t < RT * BT; t += KS) {
     const int rt = t / BT, bt = t - rt * BT;
     if (bt >= nbt) continue;
@@ -206,9 +308,15 @@ __global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(LstmFwdArgs args, int
 }
 
 template <typename T, int RT, int KS, int U, int BT = STEP_MAXBT>
-static void lstm_fwd_go(const LstmFwdArgs& a, int Bp, int Hh, int ndir, hipStream_t st) {
+static void lstm_fwd_go(const LstmFwdArgs& a, int Bp, int Hh, int ndir, hipStream_t st, bool fm = false) {
   const int nbt = (Bp + 15) / 16;
   StepGrid sg{((Hh + 4 * RT - 1) / (4 * RT)) * ndir, 1, (nbt + BT - 1) / BT};
+  if constexpr (sizeof(T) == 2) {
+    if (fm) {
+      hipLaunchKernelGGL((lstm_fwd_kernel<T, RT, KS, U, BT, true>), dim3(step_grid_blocks(sg)), dim3(64 * KS), 0, st, a, Bp, Hh, sg, ndir);
+      return;
+    }
+  }
   hipLaunchKernelGGL((lstm_fwd_kernel<T, RT, KS, U, BT>), dim3(step_grid_blocks(sg)), dim3(64 * KS), 0, st, a, Bp, Hh, sg, ndir);
 }
 
@@ -228,6 +336,8 @@ void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh,
     a.d[i] = dirs[i < ndir ? i : 0];
     if (i < ndir && dirs[i].Kx + Hh > K) K = dirs[i].Kx + Hh;      // instances may differ in their input width
   }
+  bool fm = prec != 0;                              // fragment-major operands: every instance must bring them
+  for (int i = 0; i < ndir; ++i) fm = fm && dirs[i].W_fm != nullptr;
   int how = g_lstm_fwd_how;
   const int nbt = (Bp + 15) / 16;
   // measured (bf16, hidden 1024): 64 sentences — 32 gate rows x 32 sentences per workgroup: 9.9 us against
@@ -238,16 +348,16 @@ void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh,
   const int nsteps = (K / 8 + 3) / 4;
   if (prec) {
     if (how == 6) {
-      if (nsteps > 32) lstm_fwd_go<bf16_t, 2, 8, 4, 2>(a, Bp, Hh, ndir, st);
-      else if (nsteps > 16) lstm_fwd_go<bf16_t, 2, 8, 2, 2>(a, Bp, Hh, ndir, st);
-      else lstm_fwd_go<bf16_t, 2, 4, 2, 2>(a, Bp, Hh, ndir, st);
+      if (nsteps > 32) lstm_fwd_go<bf16_t, 2, 8, 4, 2>(a, Bp, Hh, ndir, st, fm);
+      else if (nsteps > 16) lstm_fwd_go<bf16_t, 2, 8, 2, 2>(a, Bp, Hh, ndir, st, fm);
+      else lstm_fwd_go<bf16_t, 2, 4, 2, 2>(a, Bp, Hh, ndir, st, fm);
     }
-    else if (how == 4) lstm_fwd_go<bf16_t, 4, 8, 4>(a, Bp, Hh, ndir, st);
-    else if (how == 2) lstm_fwd_go<bf16_t, 2, 8, 4>(a, Bp, Hh, ndir, st);
-    else if (nsteps > 32) lstm_fwd_go<bf16_t, 1, 16, 4>(a, Bp, Hh, ndir, st);
-    else if (nsteps > 16) lstm_fwd_go<bf16_t, 1, 16, 2>(a, Bp, Hh, ndir, st);
-    else if (nsteps > 8) lstm_fwd_go<bf16_t, 1, 8, 2>(a, Bp, Hh, ndir, st);
-    else lstm_fwd_go<bf16_t, 1, 4, 2>(a, Bp, Hh, ndir, st);
+    else if (how == 4) lstm_fwd_go<bf16_t, 4, 8, 4>(a, Bp, Hh, ndir, st, fm);
+    else if (how == 2) lstm_fwd_go<bf16_t, 2, 8, 4>(a, Bp, Hh, ndir, st, fm);
+    else if (nsteps > 32) lstm_fwd_go<bf16_t, 1, 16, 4>(a, Bp, Hh, ndir, st, fm);
+    else if (nsteps > 16) lstm_fwd_go<bf16_t, 1, 16, 2>(a, Bp, Hh, ndir, st, fm);
+    else if (nsteps > 8) lstm_fwd_go<bf16_t, 1, 8, 2>(a, Bp, Hh, ndir, st, fm);
+    else lstm_fwd_go<bf16_t, 1, 4, 2>(a, Bp, Hh, ndir, st, fm);
   } else {
     if (how == 4) lstm_fwd_go<float, 4, 8, 2>(a, Bp, Hh, ndir, st);
     else if (how == 2) lstm_fwd_go<float, 2, 8, 2>(a, Bp, Hh, ndir, st);
@@ -402,8 +512,10 @@ __global__ __launch_bounds__(64 * KS) void step_tanh_kernel(StepGemm g, int Bp, 
   for (int i = 0; i < 4; ++i)
     if (n + i < g.N) {
       const float hv = tanhf(r[i]);
+      const float hd = g.outD ? hv * drop_factor(g.drop, b, n + i) : hv;
       ((T*)g.outT)[(size_t)b * g.ldo + n + i] = from_f<T>(hv);
-      if (g.outD) ((T*)g.outD)[(size_t)b * g.ldod + n + i] = from_f<T>(hv * drop_factor(g.drop, b, n + i));
+      if (g.outD) ((T*)g.outD)[(size_t)b * g.ldod + n + i] = from_f<T>(hd);
+      if (sizeof(T) == 2 && g.outF) ((T*)g.outF)[fm_offset(b, n + i, g.N >> 5)] = from_f<T>(hd);
     }
 }
 
@@ -445,6 +557,8 @@ void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st) {
 #undef GO
     return;
   }
+  // the other forms do not write the fragment-major copy themselves
+  const bool pack_after = g.mode == 0 && prec && g.outF;
   const Step2dPlan pl = plan2d(prec, g.N, g.K0 + g.K1, Bp, g.max_kb);
   StepGrid sg{(g.N + 63) / 64, pl.kb, (nbt + STEP_MAXBT - 1) / STEP_MAXBT};
   const dim3 grid(step_grid_blocks(sg));
@@ -462,6 +576,7 @@ void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st) {
     else hipLaunchKernelGGL(tanh_planes_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, st, p, (float*)g.outT, g.ldo,
                             (float*)g.outD, g.ldod, g.drop, Bp, g.N);
   }
+  if (pack_after) launch_fm_pack(g.outD ? g.outD : g.outT, g.outD ? g.ldod : g.ldo, Bp, g.N, g.outF, st);
 }
 
 // ------------------------------------------------------------------------------------------------
