@@ -57,6 +57,9 @@ struct LD {
   char* HstF = nullptr;              // [(Lmax+1)] slots of [Bp, Hh]
   char* YdF = nullptr;               // [Lmax] slots of [Bp, Hh] (the layer's output after dropout)
   bool fm = false;
+  char* WtF = nullptr;               // W^T [Kin+Hh, 4Hh] (backward step GEMMs; needs Kin a multiple of 16)
+  char* dGF = nullptr;               // [Lmax] slots of [Bp, 4Hh]
+  bool fmb = false;
 };
 
 // Row pitch padding of the per-step activation operands.  The step kernels read 16 sentences x 64
@@ -236,6 +239,11 @@ size_t layout(cmt_handle* h, char* base) {
       d.HstF = a.take((M + Bp) * Hh * esz);
       d.YdF = a.take(M * Hh * esz);
     }
+    d.fmb = c.precision && Hh % 32 == 0 && Kin % 16 == 0;
+    if (d.fmb) {
+      d.WtF = a.take((size_t)(Kin + Hh) * 4 * Hh * esz);
+      d.dGF = a.take(M * 4 * Hh * esz);
+    }
     d.Wt = a.take((size_t)(Kin + Hh) * 4 * Hh * esz);
     d.Hst = a.take((M + Bp) * d.ph * esz);
     d.Cst = (float*)a.take((M + Bp) * Hh * 4);
@@ -363,6 +371,7 @@ void refresh_params(cmt_handle* h, bool cast = true) {
   auto tr = [&](LD& d) {
     launch_transpose(p, d.W, d.Kin + d.Hh, d.Wt, 4 * d.Hh, 4 * d.Hh, d.Kin + d.Hh, st);
     if (d.fm) launch_fm_pack_lstm_weights(d.W, d.Kin + d.Hh, d.Kin - d.Kstep, d.Kstep + d.Hh, d.Hh, d.Wfm, st);
+    if (d.fmb) launch_fm_pack(d.Wt, 4 * d.Hh, d.Kin + d.Hh, 4 * d.Hh, d.WtF, st);
   };
   for (auto& d : h->enc) tr(d);
   for (auto& d : h->dec) tr(d);
@@ -454,6 +463,7 @@ LstmBwdPoint dec_cell(cmt_handle* h, int l, int j) {
   q.cprev = e.Cst + j * BH; q.cnext = e.Cst + (j + 1) * BH;
   q.mask = h->mask_t + (size_t)j * Bp;
   q.dg = e.dG + (size_t)j * Bp * e.pg * h->esz; q.lddg = e.pg;
+  if (e.fmb) q.dg_fm = e.dGF + (size_t)j * Bp * 4 * H * h->esz;
   return q;
 }
 
@@ -490,6 +500,10 @@ StepBwd dec_bwd_gemm(cmt_handle* h, int l, int j) {
   } else {
     g.Wt = e.Wt + (size_t)(E + H) * 4 * H * esz;                 // H_o^{<-1>} is a constant: only dh_prev
     g.part[0] = store;
+  }
+  if (e.fmb) {                                                   // the same operands in fragment-major form
+    g.dg_fm = e.dGF + (size_t)j * Bp * 4 * H * esz; g.Wt_fm = e.WtF;
+    g.wt_tile0 = (l > 0 ? 0 : j > 0 ? E : E + H) / 16;
   }
   return g;
 }
@@ -1061,6 +1075,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       q.cprev = e.Cst + (size_t)slot_prev * BHd; q.cnext = e.Cst + (size_t)slot_next * BHd;
       q.mask = h->mask_s + (size_t)t * Bp;
       q.dg = e.dG + (size_t)t * Bp * e.pg * esz; q.lddg = e.pg;
+      if (e.fmb) q.dg_fm = e.dGF + (size_t)t * Bp * 4 * Hd * esz;
       return q;
     };
     if (h->bwd_fused & 4) {
@@ -1077,6 +1092,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
           g = StepBwd{};
           g.dg = e.dG + (size_t)t * Bp * e.pg * esz; g.lddg = e.pg; g.K = 4 * Hd;
           g.Wt = e.Wt + (size_t)E * 4 * Hd * esz; g.ldw = 4 * Hd;
+          if (e.fmb) { g.dg_fm = e.dGF + (size_t)t * Bp * 4 * Hd * esz; g.Wt_fm = e.WtF; g.wt_tile0 = E / 16; }
           BwdEpi& r = g.part[0];
           r.kind = BWD_EPI_CELL_REC; r.ncols = Hd; r.hh = Hd; r.cell = enc0_cell(i, tn);
         }

@@ -165,6 +165,7 @@ struct LstmBwdPoint {
   const float* cprev; const float* cnext;  // [Bp,Hh]
   const float* mask;                   // [Bp]
   void* dg; int lddg;                  // T* [Bp,4Hh], row pitch lddg
+  void* dg_fm = nullptr;               // optional fragment-major copy of dg (16-bit types; 4Hh / 32 k steps)
 };
 void launch_lstm_bwd_point(int prec, const LstmBwdPoint& p, int Bp, int Hh, hipStream_t st);
 void launch_lstm_bwd_point_multi(int prec, const LstmBwdPoint* ps, int n, int Bp, int Hh, hipStream_t st);
@@ -188,11 +189,15 @@ struct BwdEpi {
   LstmBwdPoint cell{};
   const float* dce = nullptr; const int32_t* pos = nullptr; const void* Ho = nullptr; int ldho = 0;
   void* dpre = nullptr; int ldp = 0; DropSpec drop{};
+  void* dpre_fm = nullptr;             // TANH: optional fragment-major copy of dpre (hh / 32 k steps)
 };
 struct StepBwd {
   const void* dg; int lddg; int K;     // T* [Bp, K]
   const void* Wt; int ldw;             // T* [N, K]: row n = output column n
   BwdEpi part[2];
+  // fragment-major operands (16-bit types; both or none): dg_fm = the same [Bp, K]; Wt_fm = the whole transposed
+  // weight matrix, of which this instance's rows start at row tile wt_tile0 (16 rows per tile)
+  const void* dg_fm = nullptr; const void* Wt_fm = nullptr; int wt_tile0 = 0;
 };
 constexpr int STEP_BWD_MAX_INST = 4;
 // n independent instances in one launch (more than STEP_BWD_MAX_INST are spread over several launches)

@@ -636,9 +636,14 @@ __device__ __forceinline__ void cell_bwd_finish(const LstmBwdPoint& p, int b, in
                              in.dhp.w + (in.rec.w + rec_x[3])};
   T* dg = (T*)p.dg + (size_t)b * p.lddg + u;
   const float zero[4] = {0.f, 0.f, 0.f, 0.f};
+  T* dgf[4] = {nullptr, nullptr, nullptr, nullptr};  // the same four values per gate in the fragment-major copy (u % 4 == 0)
+  if (sizeof(T) == 2 && p.dg_fm) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) dgf[g] = (T*)p.dg_fm + fm_offset(b, g * Hh + u, (4 * Hh) >> 5);
+  }
   if (!(in.mask > 0.f)) {                          // masked step: state passes through, no gate gradient
 #pragma unroll
-    for (int g = 0; g < 4; ++g) store4<T>(dg + g * Hh, zero);
+    for (int g = 0; g < 4; ++g) { store4<T>(dg + g * Hh, zero); if (dgf[g]) store4<T>(dgf[g], zero); }
     store4<float>(p.dh + idx, dh_state);           // (an output of a masked step is the constant 0: dy is dropped)
     return;
   }
@@ -658,6 +663,7 @@ __device__ __forceinline__ void cell_bwd_finish(const LstmBwdPoint& p, int b, in
     dcn[e] = dc * fg;
   }
   store4<T>(dg, di); store4<T>(dg + Hh, df); store4<T>(dg + 2 * Hh, dgg); store4<T>(dg + 3 * Hh, dout);
+  if (dgf[0]) { store4<T>(dgf[0], di); store4<T>(dgf[1], df); store4<T>(dgf[2], dgg); store4<T>(dgf[3], dout); }
   store4<float>(p.dc + idx, dcn);
   store4<float>(p.dh + idx, zero);                 // the recurrent part arrives with the next step's GEMM
 }
@@ -698,7 +704,7 @@ void launch_lstm_bwd_point(int prec, const LstmBwdPoint& p, int Bp, int Hh, hipS
 // second launch exist.  The epilogue's operands are fetched before the contraction starts.
 struct StepBwdArgs { StepBwd g[STEP_BWD_MAX_INST]; };
 
-template <typename T, int KS, int U, int BT>
+template <typename T, int KS, int U, int BT, bool FM = false>
 __global__ __launch_bounds__(64 * KS) void step_bwd_fused_kernel(StepBwdArgs args, int Bp, StepGrid sg) {
   __shared__ __align__(16) float red[KS * BT * 256];
   const StepBwd& g = args.g[blockIdx.y];
@@ -731,7 +737,13 @@ __global__ __launch_bounds__(64 * KS) void step_bwd_fused_kernel(StepBwdArgs arg
       for (int i = 0; i < 4; ++i) tho[i] = to_f<T>(((const T*)e.Ho)[(size_t)b * e.ldho + c + i]);
     }
   }
-  step_contract<T, 1, KS, U, BT>(wrow, 0, 0, (const T*)g.dg, g.lddg, g.K, (const T*)nullptr, 0, 0, Bp, bt0, nbt, red);
+  if constexpr (FM) {
+    const int ns = g.K >> 5;
+    const bf16_t* wt[1] = {(const bf16_t*)g.Wt_fm + (size_t)(g.wt_tile0 + x) * ns * 512};
+    step_contract_fm<1, KS, U, BT>(wt, (const bf16_t*)g.dg_fm, ns, nullptr, 0, bt0, nbt, red);
+  } else {
+    step_contract<T, 1, KS, U, BT>(wrow, 0, 0, (const T*)g.dg, g.lddg, g.K, (const T*)nullptr, 0, 0, Bp, bt0, nbt, red);
+  }
   if (!mine) return;                                // KS >= BT: wavefront w finishes sentence tile w
   const v4f r = step_tile_sum<1, KS, BT>(red, 0, w);
   const float v[4] = {r[0], r[1], r[2], r[3]};
@@ -747,13 +759,20 @@ __global__ __launch_bounds__(64 * KS) void step_bwd_fused_kernel(StepBwdArgs arg
 #pragma unroll
     for (int i = 0; i < 4; ++i) o[i] = ((&tce.x)[i] + v[i]) * drop_factor(e.drop, b, c + i) * (1.f - tho[i] * tho[i]);
     store4<T>((T*)e.dpre + (size_t)b * e.ldp + c, o);
+    if (sizeof(T) == 2 && e.dpre_fm) store4<T>((T*)e.dpre_fm + fm_offset(b, c, e.hh >> 5), o);
   }
 }
 
 template <typename T, int KS, int U, int BT>
-static void step_bwd_go(const StepBwdArgs& a, int n, int Nmax, int Bp, hipStream_t st) {
+static void step_bwd_go(const StepBwdArgs& a, int n, int Nmax, int Bp, hipStream_t st, bool fm) {
   const int nbt = (Bp + 15) / 16;
   StepGrid sg{(Nmax + 15) / 16, 1, (nbt + BT - 1) / BT};
+  if constexpr (sizeof(T) == 2) {
+    if (fm) {
+      hipLaunchKernelGGL((step_bwd_fused_kernel<T, KS, U, BT, true>), dim3(step_grid_blocks(sg), n), dim3(64 * KS), 0, st, a, Bp, sg);
+      return;
+    }
+  }
   hipLaunchKernelGGL((step_bwd_fused_kernel<T, KS, U, BT>), dim3(step_grid_blocks(sg), n), dim3(64 * KS), 0, st, a, Bp, sg);
 }
 
@@ -762,9 +781,11 @@ void launch_step_bwd_fused(int prec, const StepBwd* gs, int n, int Bp, hipStream
     const int m = n - base < STEP_BWD_MAX_INST ? n - base : STEP_BWD_MAX_INST;
     StepBwdArgs a;
     int Nmax = 0, Kmax = 0;
+    bool fm = prec != 0;                           // fragment-major operands: every instance must bring them
     for (int i = 0; i < STEP_BWD_MAX_INST; ++i) {
       a.g[i] = gs[base + (i < m ? i : 0)];
       if (i < m) {
+        fm = fm && a.g[i].dg_fm && a.g[i].Wt_fm;
         Nmax = std::max(Nmax, a.g[i].part[0].ncols + a.g[i].part[1].ncols);
         Kmax = std::max(Kmax, a.g[i].K);
       }
@@ -772,7 +793,7 @@ void launch_step_bwd_fused(int prec, const StepBwd* gs, int n, int Bp, hipStream
     const int nsteps = (Kmax / 8 + 3) / 4;
     // 16 columns x 32 sentences per workgroup.  (64 sentences per workgroup halves the number of workgroups
     // and was measured at twice the time: 25.6 against 12.9 us for 64 sentences, 26.2 against 21.8 us for 128.)
-#define GO(TT, KS, UU) step_bwd_go<TT, KS, UU, 2>(a, m, Nmax, Bp, st)
+#define GO(TT, KS, UU) step_bwd_go<TT, KS, UU, 2>(a, m, Nmax, Bp, st, fm)
     if (prec) {
       if (nsteps > 64) GO(bf16_t, 16, 4); else if (nsteps > 32) GO(bf16_t, 8, 4); else if (nsteps > 16) GO(bf16_t, 8, 2); else GO(bf16_t, 4, 2);
     } else {
