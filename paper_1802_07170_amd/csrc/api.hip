@@ -140,6 +140,8 @@ struct cmt_handle {
   std::vector<hipEvent_t> ev; size_t ev_next = 0;
   int use_side = 1;
   char* dzs2 = nullptr; char* dzTs2 = nullptr;
+  char* WcF = nullptr; char* WcTF = nullptr;  // fragment-major W_c [H, 2H] and W_c^T [2H, H]
+  char* CsF = nullptr; char* dPreF = nullptr; // fragment-major copies of the contexts and of dpre, [Tmax] slots of [Bp, H]
   char* HoFeedF = nullptr;              // fragment-major copy of the H_o rows fed to the decoder's bottom layer, [(Tmax+1)] slots of [Bp, H]
   int kb_bwd = 0, kb_wc = 0;            // caps on the k blocks of the backward step GEMMs (0 = default)
   // backward loops that use the whole-k step GEMM with the consumer in its epilogue (env CMT_BWD_FUSED, a bit
@@ -267,7 +269,11 @@ size_t layout(cmt_handle* h, char* base) {
   for (int l = 1; l < L; ++l) ld_alloc(h->enc[l + 1], H, H, Sm, true, l == 1 ? 0 : H);
   ld_alloc(h->dec[0], E + H, H, Tm, true, H);
   for (int l = 1; l < L; ++l) ld_alloc(h->dec[l], H, H, Tm, false, H);
-  if (c.precision && H % 32 == 0) h->HoFeedF = a.take((Mt + Bp) * H * esz);
+  if (c.precision && H % 32 == 0) {
+    h->HoFeedF = a.take((Mt + Bp) * H * esz);
+    h->WcF = a.take((size_t)2 * H * H * esz); h->WcTF = a.take((size_t)2 * H * H * esz);
+    h->CsF = a.take(Mt * H * esz); h->dPreF = a.take(Mt * H * esz);
+  }
   h->WaT = a.take((size_t)H * H * esz);
   h->WcT = a.take((size_t)2 * H * H * esz);
   h->WoT = a.take((size_t)H * c.tgt_vocab * esz);
@@ -377,6 +383,10 @@ void refresh_params(cmt_handle* h, bool cast = true) {
   for (auto& d : h->dec) tr(d);
   launch_transpose(p, h->Pw(h->off_Wa), H, h->WaT, H, H, H, st);
   launch_transpose(p, h->Pw(h->off_Wc), 2 * H, h->WcT, H, H, 2 * H, st);
+  if (h->WcF) {
+    launch_fm_pack(h->Pw(h->off_Wc), 2 * H, H, 2 * H, h->WcF, st);
+    launch_fm_pack(h->WcT, H, 2 * H, H, h->WcTF, st);
+  }
   launch_transpose(p, h->Pw(h->off_Wo), H, h->WoT, c.tgt_vocab, c.tgt_vocab, H, st);
 }
 
@@ -496,6 +506,7 @@ StepBwd dec_bwd_gemm(cmt_handle* h, int l, int j) {
     t0.kind = BWD_EPI_TANH; t0.ncols = H; t0.hh = H;
     t0.dce = h->dHoCE; t0.pos = h->ce_pos + (size_t)(j - 1) * Bp; t0.Ho = h->HoBuf + j * BP * esz; t0.ldho = PH;
     t0.dpre = h->dPre + (j - 1) * BP * esz; t0.ldp = PH; t0.drop = drop_spec(h, DROP_SITE_HO, j - 1);
+    if (h->dPreF) t0.dpre_fm = h->dPreF + (size_t)(j - 1) * Bp * H * esz;
     g.part[1] = store;
   } else {
     g.Wt = e.Wt + (size_t)(E + H) * 4 * H * esz;                 // H_o^{<-1>} is a constant: only dh_prev
@@ -715,7 +726,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       for (int l = 0; l < L; ++l) dec_lstm_fwd(h, l, j);
       const char* Ht = h->dec[L - 1].Hst + (j + 1) * BP * esz;
       launch_att_fwd(p, h->Kmat, H, Hs, ldHs, Ht, PH, h->len_s, S, Bp, H, h->att_s + (size_t)j * Bp * S,
-                     h->att_a + (size_t)j * Bp * S, h->Cs + j * BP * esz, PH, st);
+                     h->att_a + (size_t)j * Bp * S, h->Cs + j * BP * esz, PH, st, h->CsF ? h->CsF + j * BH * esz : nullptr);
       StepGemm g{};
       g.a0 = h->Cs + j * BP * esz; g.lda0 = PH; g.K0 = H; g.w0_off = 0;
       g.a1 = Ht; g.lda1 = PH; g.K1 = H; g.w1_off = H;
@@ -723,7 +734,10 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       g.outT = h->HoBuf + (j + 1) * BP * esz; g.ldo = PH;
       if (drop) { g.outD = h->HoDrop + (j + 1) * BP * esz; g.ldod = PH; g.drop = drop_spec(h, DROP_SITE_HO, j); }
       g.out = h->wcp; g.ldout = H; g.plane_stride = BH;
-      if (h->HoFeedF) g.outF = h->HoFeedF + (j + 1) * BH * esz;
+      if (h->HoFeedF) {
+        g.outF = h->HoFeedF + (j + 1) * BH * esz;
+        g.W_fm = h->WcF; g.a0_fm = h->CsF + j * BH * esz; g.a1_fm = h->dec[L - 1].HstF + (j + 1) * BH * esz;
+      }
       launch_step_gemm(p, g, Bp, st);
     }
   }
@@ -838,15 +852,17 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     for (int j = T - 1; j >= 0; --j) {
       char* dpre = h->dPre + j * BP * esz;
       const bool last = j == T - 1;
+      char* dpreF = h->dPreF ? h->dPreF + j * BH * esz : nullptr;
       if (last)
         launch_tanh_bwd(p, h->dHoCE, h->ce_pos + (size_t)j * Bp, no_planes, h->HoBuf + (j + 1) * BP * esz, PH, dpre, PH, Bp, H,
-                        drop_spec(h, DROP_SITE_HO, j), st);
+                        drop_spec(h, DROP_SITE_HO, j), st, dpreF);
       const int kbw = step_kblocks(p, 2 * H, H, Bp, h->kb_wc);
       {   // [dC_s ; dH_t] = dpre W_c, as planes
         StepGemm g{};
         g.a0 = dpre; g.lda0 = PH; g.K0 = H; g.w0_off = 0; g.K1 = 0;
         g.W = h->WcT; g.ldw = H; g.N = 2 * H; g.mode = 1; g.max_kb = h->kb_wc;
         g.out = h->wcp; g.ldout = 2 * H; g.plane_stride = pstr;
+        g.W_fm = h->WcTF; g.a0_fm = dpreF;
         launch_step_gemm(p, g, Bp, st);
       }
       // attention backward; the gradient it sends to the top layer's output stays in registers and that
@@ -867,14 +883,16 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
     char* dpre = h->dPre + j * BP * esz;
     const bool last = j == T - 1;
     // dH_o = cross-entropy part + what step j+1's bottom layer sent back through the input feed
+    char* dpreF = h->dPreF ? h->dPreF + j * BH * esz : nullptr;
     launch_tanh_bwd(p, h->dHoCE, h->ce_pos + (size_t)j * Bp, Planes{h->dec[0].bwdp, 2 * H, last ? 0 : kbd, pstr}, h->HoBuf + (j + 1) * BP * esz,
-                    PH, dpre, PH, Bp, H, drop_spec(h, DROP_SITE_HO, j), st);
+                    PH, dpre, PH, Bp, H, drop_spec(h, DROP_SITE_HO, j), st, dpreF);
     const int kbw = step_kblocks(p, 2 * H, H, Bp, h->kb_wc);
     {   // [dC_s ; dH_t] = dpre W_c, as planes
       StepGemm g{};
       g.a0 = dpre; g.lda0 = PH; g.K0 = H; g.w0_off = 0; g.K1 = 0;
       g.W = h->WcT; g.ldw = H; g.N = 2 * H; g.mode = 1; g.max_kb = h->kb_wc;
       g.out = h->wcp; g.ldout = 2 * H; g.plane_stride = pstr;
+      g.W_fm = h->WcTF; g.a0_fm = dpreF;
       launch_step_gemm(p, g, Bp, st);
     }
     launch_att_bwd(p, h->Kmat, H, Hs, ldHs, Planes{h->wcp, 2 * H, kbw, pstr}, h->dCs + j * BH, h->att_a + (size_t)j * Bp * S,
@@ -891,10 +909,12 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       q.cprev = e.Cst + j * BH; q.cnext = e.Cst + (j + 1) * BH;
       q.mask = h->mask_t + (size_t)j * Bp;
       q.dg = e.dG + (size_t)j * Bp * e.pg * esz; q.lddg = e.pg;
+      if (e.fmb) q.dg_fm = e.dGF + (size_t)j * Bp * 4 * H * esz;
       launch_lstm_bwd_point(p, q, Bp, H, st);
       StepGemm g{};                                  // [dx ; dh_prev] = dgates [W_x ; W_h] (bottom layer: [feed ; h])
       g.a0 = q.dg; g.lda0 = e.pg; g.K0 = 4 * H; g.w0_off = 0; g.K1 = 0;
       g.W = e.Wt + (size_t)(l == 0 ? E : 0) * 4 * H * esz; g.ldw = 4 * H;
+      if (e.fmb) { g.W_fm = e.WtF; g.w_tile0 = (l == 0 ? E : 0) / 16; g.a0_fm = q.dg_fm; }
       g.N = 2 * H; g.mode = 1; g.max_kb = h->kb_bwd;
       g.out = e.bwdp; g.ldout = 2 * H; g.plane_stride = pstr;
       launch_step_gemm(p, g, Bp, st);
@@ -967,6 +987,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       q.cprev = e.Cst + t * BH; q.cnext = e.Cst + (t + 1) * BH;
       q.mask = h->mask_s + (size_t)t * Bp;
       q.dg = e.dG + (size_t)t * Bp * e.pg * esz; q.lddg = e.pg;
+      if (e.fmb) q.dg_fm = e.dGF + (size_t)t * Bp * 4 * H * esz;
       return q;
     };
     for (int dg = 0; dg <= (S - 1) + 2 * (L - 2); ++dg) {
@@ -990,6 +1011,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
         } else {
           g.Wt = e.Wt + (size_t)H * 4 * H * esz;
         }
+        if (e.fmb) { g.dg_fm = e.dGF + (size_t)t * Bp * 4 * H * esz; g.Wt_fm = e.WtF; g.wt_tile0 = (l > 1 ? 0 : H) / 16; }
         if (t > 0) {
           BwdEpi& r = g.part[np++];
           r.kind = BWD_EPI_CELL_REC; r.ncols = H; r.hh = H; r.cell = enc_cell(l, t - 1);
@@ -1031,11 +1053,13 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
         q.cprev = e.Cst + t * BH; q.cnext = e.Cst + (t + 1) * BH;
         q.mask = h->mask_s + (size_t)t * Bp;
         q.dg = e.dG + (size_t)t * Bp * e.pg * esz; q.lddg = e.pg;
+        if (e.fmb) q.dg_fm = e.dGF + (size_t)t * Bp * 4 * H * esz;
         if (l == 1 && k == S - 1) continue;                                 // the initial state is a constant
         StepGemm& g = gs[ng++];
         g = StepGemm{};
         g.a0 = q.dg; g.lda0 = e.pg; g.K0 = 4 * H; g.w0_off = 0; g.K1 = 0;
         g.W = e.Wt + (size_t)(l == 1 ? H : 0) * 4 * H * esz; g.ldw = 4 * H;
+        if (e.fmb) { g.W_fm = e.WtF; g.w_tile0 = (l == 1 ? H : 0) / 16; g.a0_fm = q.dg_fm; }
         g.N = (l == 1) ? H : 2 * H; g.mode = 1; g.max_kb = h->kb_bwd;
         g.out = e.bwdp; g.ldout = 2 * H; g.plane_stride = pstrE;
       }
@@ -1585,6 +1609,7 @@ int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_la
       g.W = e.Wt + (size_t)(&e == &h->dec[0] ? E : 0) * 4 * H * es; g.ldw = 4 * H;
       g.N = 2 * H; g.mode = 1; g.max_kb = h->kb_bwd;
       g.out = e.bwdp; g.ldout = 2 * H; g.plane_stride = (size_t)Bp * 2 * H;
+      if (e.fmb) { g.W_fm = e.WtF; g.w_tile0 = (&e == &h->dec[0] ? E : 0) / 16; g.a0_fm = e.dGF + (size_t)j * Bp * 4 * H * es; }
       launch_step_gemm(p, g, Bp, st);
     };
   } else if (s == "step_bwd_fused_dec") {

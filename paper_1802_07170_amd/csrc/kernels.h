@@ -143,6 +143,9 @@ struct StepGemm {
   void* outT; int ldo;
   void* outD = nullptr; int ldod = 0;  // mode 0: optional copy of outT after dropout `drop`
   DropSpec drop{};
+  // fragment-major operands (16-bit types; all that apply or none; K0, K1 multiples of 32, N of 16): W_fm = rows
+  // [w_tile0 * 16, ...) of a packed matrix whose k axis is this GEMM's [segment 0; segment 1]; a0_fm, a1_fm
+  const void* W_fm = nullptr; int w_tile0 = 0; const void* a0_fm = nullptr; const void* a1_fm = nullptr;
   void* outF = nullptr;                // mode 0, 16-bit types: optional fragment-major copy (fm_offset, N / 32 k steps) of
                                        //   what the next step is fed: outD's values if outD is set, else outT's
   float* out; int ldout; size_t plane_stride;
@@ -211,7 +214,7 @@ void launch_planes_add(float* out, const float* base, const Planes& p, int col0,
 // ldk / lds / ldt / ldcs: row pitches (elements) of Kmat, Hs, Ht and Cs.
 void launch_att_fwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds, const void* Ht, int ldt,
                     const int32_t* src_len, int S, int Bp, int H, float* dots, float* a /*[Bp,S]*/,
-                    void* Cs /*T* [Bp,ldcs]*/, int ldcs, hipStream_t st);
+                    void* Cs /*T* [Bp,ldcs]*/, int ldcs, hipStream_t st, void* Cs_fm = nullptr /* fragment-major copy */);
 // Attention backward for one step.  dCst: planes [.., Bp, 2H] fp32 from the step GEMM dpre W_c:
 // columns [0,H) = dC_s, [H,2H) = the part of dH_t that came through the concatenation.
 // da_i = dC_s . H_s^i, ds = a (da - sum a da), dHt = dCst[:, H:] + sum ds_i K_i;
@@ -229,7 +232,7 @@ void launch_att_deferred(int prec, const float* a, const float* ds, const float*
 // dHo_ce: rows [Bp, H] of this step, or — with pos [Bp] given — a dense matrix [n, H] in which row pos[b]
 // belongs to sentence b (pos[b] < 0: no row, zero).
 void launch_tanh_bwd(int prec, const float* dHo_ce, const int32_t* pos, const Planes& feed, const void* Ho, int ldho, void* dpre,
-                     int ldp, int Bp, int H, const DropSpec& drop, hipStream_t st);
+                     int ldp, int Bp, int H, const DropSpec& drop, hipStream_t st, void* dpre_fm = nullptr /* fragment-major copy */);
 
 // ---- misc.hip ----------------------------------------------------------------------------------
 // Embedding gather + masks + input validation (flags |= 1 bad id, |= 2 bad length).

@@ -106,17 +106,18 @@ __device__ __forceinline__ v4f step_tile_sum(const float* red, int rt, int bt) {
 
 // The same contraction on fragment-major operands (bf16): wt[rt] = first block of row tile rt (its k steps follow
 // each other), a0 / a1 = fragment-major activation segments of ns0 / ns1 k steps (batch tile bt at bt * ns blocks).
+// [s_begin, s_end) = the k steps this workgroup contracts (default: all).
 template <int RT, int KS, int U, int BT>
 __device__ __forceinline__ void step_contract_fm(const bf16_t* const (&wt)[RT], const bf16_t* a0, int ns0, const bf16_t* a1, int ns1,
-                                                 int bt0, int nbt, float* red) {
+                                                 int bt0, int nbt, float* red, int s_begin = 0, int s_end = 1 << 30) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int nsteps = ns0 + ns1;
+  const int nsteps = min(ns0 + ns1, s_end);
   v4f acc[RT][BT];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
     for (int b = 0; b < BT; ++b) acc[rt][b] = v4f{0.f, 0.f, 0.f, 0.f};
-  for (int s0 = 0; s0 < nsteps; s0 += KS * U) {
+  for (int s0 = s_begin; s0 < nsteps; s0 += KS * U) {
     Frag<bf16_t> fw[U][RT], fx[U][BT];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -395,7 +396,7 @@ static Step2dPlan plan2d(int prec, int N, int K, int Bp, int max_kb) {
 }
 int step_kblocks(int prec, int N, int K, int Bp, int max_kb) { return plan2d(prec, N, K, Bp, max_kb).kb; }
 
-template <typename T, int U>
+template <typename T, int U, bool FM = false>
 __global__ __launch_bounds__(256) void step2d_kernel(StepGemmArgs args, int Bp, StepGrid sg, int spb) {
   __shared__ __align__(16) float red[4 * 16 * 64 * 4];
   const StepGemm& g = args.g[blockIdx.y];
@@ -419,6 +420,14 @@ __global__ __launch_bounds__(256) void step2d_kernel(StepGemmArgs args, int Bp, 
 #pragma unroll
     for (int b = 0; b < STEP_MAXBT; ++b) acc[rt][b] = v4f{0.f, 0.f, 0.f, 0.f};
   const int s_begin = kb * spb, s_end = s_begin + spb;
+  if constexpr (FM) {
+    const int ns0 = g.K0 >> 5, ns1 = g.K1 >> 5, ntile = g.N >> 4;
+    const bf16_t* wt[4];
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt)   // row tiles past N read the last one (their results are dropped)
+      wt[rt] = (const bf16_t*)g.W_fm + (size_t)(g.w_tile0 + min((n0 >> 4) + rt, ntile - 1)) * (ns0 + ns1) * 512;
+    step_contract_fm<4, 4, U, STEP_MAXBT>(wt, (const bf16_t*)g.a0_fm, ns0, (const bf16_t*)g.a1_fm, ns1, bt0, nbt, red, s_begin, s_end);
+  } else {
   for (int s0 = s_begin; s0 < s_end; s0 += 4 * U) {
     Frag<T> fw[U][4], fx[U][STEP_MAXBT];
 #pragma unroll
@@ -458,6 +467,7 @@ __global__ __launch_bounds__(256) void step2d_kernel(StepGemmArgs args, int Bp, 
     for (int b = 0; b < STEP_MAXBT; ++b)
       *reinterpret_cast<v4f*>(red + (((w * 4 + rt) * STEP_MAXBT + b) * 64 + lane) * 4) = acc[rt][b];
   __syncthreads();
+  }
   // wavefront w finishes row tile w for all batch tiles
   const int n = n0 + 16 * w + 4 * (lane >> 4);
 #pragma unroll
@@ -495,7 +505,7 @@ __global__ __launch_bounds__(256) void tanh_planes_kernel(Planes p, T* __restric
 // (split over its wavefronts, combined through LDS), tanh and the optional dropped copy in the
 // epilogue.  No planes, no second kernel; each weight slab is read by the batch's 16-sentence groups
 // from the same L2.
-template <typename T, int KS, int U>
+template <typename T, int KS, int U, bool FM = false>
 __global__ __launch_bounds__(64 * KS) void step_tanh_kernel(StepGemm g, int Bp, StepGrid sg) {
   __shared__ __align__(16) float red[KS * 256];
   int x, kb, z;
@@ -503,7 +513,13 @@ __global__ __launch_bounds__(64 * KS) void step_tanh_kernel(StepGemm g, int Bp, 
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int n0 = x * 16;
   const T* wrow[1] = {(const T*)g.W + (size_t)min(n0 + (lane & 15), g.N - 1) * g.ldw};
-  step_contract<T, 1, KS, U, 1>(wrow, g.w0_off, g.w1_off, (const T*)g.a0, g.lda0, g.K0, (const T*)g.a1, g.lda1, g.K1, Bp, z, 1, red);
+  if constexpr (FM) {
+    const int ns0 = g.K0 >> 5, ns1 = g.K1 >> 5;
+    const bf16_t* wt[1] = {(const bf16_t*)g.W_fm + (size_t)(g.w_tile0 + x) * (ns0 + ns1) * 512};
+    step_contract_fm<1, KS, U, 1>(wt, (const bf16_t*)g.a0_fm, ns0, (const bf16_t*)g.a1_fm, ns1, z, 1, red);
+  } else {
+    step_contract<T, 1, KS, U, 1>(wrow, g.w0_off, g.w1_off, (const T*)g.a0, g.lda0, g.K0, (const T*)g.a1, g.lda1, g.K1, Bp, z, 1, red);
+  }
   if (w != 0) return;
   const v4f r = step_tile_sum<1, KS, 1>(red, 0, 0);
   const int n = n0 + 4 * (lane >> 4), b = 16 * z + (lane & 15);
@@ -517,6 +533,10 @@ __global__ __launch_bounds__(64 * KS) void step_tanh_kernel(StepGemm g, int Bp, 
       if (g.outD) ((T*)g.outD)[(size_t)b * g.ldod + n + i] = from_f<T>(hd);
       if (sizeof(T) == 2 && g.outF) ((T*)g.outF)[fm_offset(b, n + i, g.N >> 5)] = from_f<T>(hd);
     }
+}
+
+static bool step_gemm_has_fm(const StepGemm& g) {
+  return g.W_fm && (g.K0 == 0 || g.a0_fm) && (g.K1 == 0 || g.a1_fm) && g.K0 % 32 == 0 && g.K1 % 32 == 0 && g.N % 16 == 0;
 }
 
 // n instances in one launch (blockIdx.y); they share the contraction length and the k-block plan,
@@ -534,10 +554,15 @@ void launch_step_gemm_multi(int prec, const StepGemm* gs, int n, int n_plan, int
   const Step2dPlan pl = plan2d(prec, Nmax, g.K0 + g.K1, Bp, g.max_kb);
   StepGrid sg{(Nmax + 63) / 64, pl.kb, (nbt + STEP_MAXBT - 1) / STEP_MAXBT};
   const dim3 grid(step_grid_blocks(sg), n);
+  bool fm = prec != 0;                              // fragment-major operands: every instance must bring them
+  for (int i = 0; i < n; ++i) fm = fm && step_gemm_has_fm(gs[i]);
 #define GO(TT, UU) hipLaunchKernelGGL((step2d_kernel<TT, UU>), grid, dim3(256), 0, st, a, Bp, sg, pl.steps_per_block)
-  if (prec) { if (pl.u == 4) GO(bf16_t, 4); else if (pl.u == 2) GO(bf16_t, 2); else GO(bf16_t, 1); }
+#define GOF(UU) hipLaunchKernelGGL((step2d_kernel<bf16_t, UU, true>), grid, dim3(256), 0, st, a, Bp, sg, pl.steps_per_block)
+  if (fm) { if (pl.u == 4) GOF(4); else if (pl.u == 2) GOF(2); else GOF(1); }
+  else if (prec) { if (pl.u == 4) GO(bf16_t, 4); else if (pl.u == 2) GO(bf16_t, 2); else GO(bf16_t, 1); }
   else { if (pl.u == 2) GO(float, 2); else GO(float, 1); }
 #undef GO
+#undef GOF
 }
 
 static int g_step_tanh = -1;
@@ -552,9 +577,12 @@ void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st) {
     const dim3 grid(step_grid_blocks(sg));
     const int nsteps = ((g.K0 + g.K1) / 8 + 3) / 4;
 #define GO(TT, KS, UU) hipLaunchKernelGGL((step_tanh_kernel<TT, KS, UU>), grid, dim3(64 * KS), 0, st, g, Bp, sg)
-    if (prec) { if (nsteps > 32) GO(bf16_t, 16, 4); else if (nsteps > 16) GO(bf16_t, 16, 2); else GO(bf16_t, 8, 2); }
+#define GOF(KS, UU) hipLaunchKernelGGL((step_tanh_kernel<bf16_t, KS, UU, true>), grid, dim3(64 * KS), 0, st, g, Bp, sg)
+    if (prec && step_gemm_has_fm(g)) { if (nsteps > 32) GOF(16, 4); else if (nsteps > 16) GOF(16, 2); else GOF(8, 2); }
+    else if (prec) { if (nsteps > 32) GO(bf16_t, 16, 4); else if (nsteps > 16) GO(bf16_t, 16, 2); else GO(bf16_t, 8, 2); }
     else { if (nsteps > 16) GO(float, 16, 2); else GO(float, 8, 2); }
 #undef GO
+#undef GOF
     return;
   }
   // the other forms do not write the fragment-major copy themselves
@@ -565,9 +593,12 @@ void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st) {
   StepGemmArgs a;
   for (int i = 0; i < STEP_MAX_INST; ++i) a.g[i] = g;
 #define GO(TT, UU) hipLaunchKernelGGL((step2d_kernel<TT, UU>), grid, dim3(256), 0, st, a, Bp, sg, pl.steps_per_block)
-  if (prec) { if (pl.u == 4) GO(bf16_t, 4); else if (pl.u == 2) GO(bf16_t, 2); else GO(bf16_t, 1); }
+#define GOF(UU) hipLaunchKernelGGL((step2d_kernel<bf16_t, UU, true>), grid, dim3(256), 0, st, a, Bp, sg, pl.steps_per_block)
+  if (prec && step_gemm_has_fm(g)) { if (pl.u == 4) GOF(4); else if (pl.u == 2) GOF(2); else GOF(1); }
+  else if (prec) { if (pl.u == 4) GO(bf16_t, 4); else if (pl.u == 2) GO(bf16_t, 2); else GO(bf16_t, 1); }
   else { if (pl.u == 2) GO(float, 2); else GO(float, 1); }
 #undef GO
+#undef GOF
   if (g.mode == 0 && pl.kb > 1) {
     Planes p{g.out, g.ldout, pl.kb, g.plane_stride};
     const int n = Bp * (g.N >> 2);
@@ -877,7 +908,7 @@ __global__ __launch_bounds__(256) void att_mix_kernel(const T* __restrict__ Mat,
                                                       const float* __restrict__ a_in, const int32_t* __restrict__ len,
                                                       int S, int Bp, int H, float* __restrict__ coef_out,
                                                       void* __restrict__ out, Planes add, int add_col, LstmBwdPoint cell,
-                                                      int fuse_cell) {
+                                                      int fuse_cell, void* __restrict__ out_fm) {
   __shared__ float sc[ATT_MAXS];
   __shared__ float part[32][65];
   const int b = blockIdx.y, t = threadIdx.x;
@@ -938,7 +969,10 @@ __global__ __launch_bounds__(256) void att_mix_kernel(const T* __restrict__ Mat,
     if (h < H) {
 #pragma unroll
       for (int g = 0; g < 32; ++g) s += part[g][t];
-      if (MODE == 0) ((T*)out)[(size_t)b * ldo + h] = from_f<T>(s);
+      if (MODE == 0) {
+        ((T*)out)[(size_t)b * ldo + h] = from_f<T>(s);
+        if (sizeof(T) == 2 && out_fm) ((T*)out_fm)[fm_offset(b, h, H >> 5)] = from_f<T>(s);
+      }
       else {
         s += planes_get(add, b, add_col + h);
         if (!fuse_cell) ((float*)out)[(size_t)b * H + h] = s;
@@ -955,15 +989,16 @@ __global__ __launch_bounds__(256) void att_mix_kernel(const T* __restrict__ Mat,
 }
 
 void launch_att_fwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds, const void* Ht, int ldt,
-                    const int32_t* src_len, int S, int Bp, int H, float* dots, float* a, void* Cs, int ldcs, hipStream_t st) {
+                    const int32_t* src_len, int S, int Bp, int H, float* dots, float* a, void* Cs, int ldcs, hipStream_t st,
+                    void* Cs_fm) {
   dim3 gd((S + 3) / 4, Bp), gm((H + 63) / 64, Bp);
   const Planes none{nullptr, 0, 0, 0};
   if (prec) {
     hipLaunchKernelGGL((att_dots_kernel<bf16_t, false>), gd, dim3(256), 0, st, (const bf16_t*)Kmat, ldk, (const bf16_t*)Ht, ldt, none, nullptr, src_len, S, Bp, H, dots);
-    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 0>), gm, dim3(256), 0, st, (const bf16_t*)Hs, lds, ldcs, dots, nullptr, src_len, S, Bp, H, a, Cs, none, 0, LstmBwdPoint{}, 0);
+    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 0>), gm, dim3(256), 0, st, (const bf16_t*)Hs, lds, ldcs, dots, nullptr, src_len, S, Bp, H, a, Cs, none, 0, LstmBwdPoint{}, 0, Cs_fm);
   } else {
     hipLaunchKernelGGL((att_dots_kernel<float, false>), gd, dim3(256), 0, st, (const float*)Kmat, ldk, (const float*)Ht, ldt, none, nullptr, src_len, S, Bp, H, dots);
-    hipLaunchKernelGGL((att_mix_kernel<float, 0>), gm, dim3(256), 0, st, (const float*)Hs, lds, ldcs, dots, nullptr, src_len, S, Bp, H, a, Cs, none, 0, LstmBwdPoint{}, 0);
+    hipLaunchKernelGGL((att_mix_kernel<float, 0>), gm, dim3(256), 0, st, (const float*)Hs, lds, ldcs, dots, nullptr, src_len, S, Bp, H, a, Cs, none, 0, LstmBwdPoint{}, 0, nullptr);
   }
 }
 
@@ -976,10 +1011,10 @@ void launch_att_bwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds
   dim3 gd((S + 3) / 4, Bp), gm((H + 63) / 64, Bp);
   if (prec) {
     hipLaunchKernelGGL((att_dots_kernel<bf16_t, true>), gd, dim3(256), 0, st, (const bf16_t*)Hs, lds, nullptr, 0, dCst, dCs_sum, src_len, S, Bp, H, dots);
-    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 1>), gm, dim3(256), 0, st, (const bf16_t*)Kmat, ldk, 0, dots, a, src_len, S, Bp, H, ds, dHt, dCst, H, cl, fuse);
+    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 1>), gm, dim3(256), 0, st, (const bf16_t*)Kmat, ldk, 0, dots, a, src_len, S, Bp, H, ds, dHt, dCst, H, cl, fuse, nullptr);
   } else {
     hipLaunchKernelGGL((att_dots_kernel<float, true>), gd, dim3(256), 0, st, (const float*)Hs, lds, nullptr, 0, dCst, dCs_sum, src_len, S, Bp, H, dots);
-    hipLaunchKernelGGL((att_mix_kernel<float, 1>), gm, dim3(256), 0, st, (const float*)Kmat, ldk, 0, dots, a, src_len, S, Bp, H, ds, dHt, dCst, H, cl, fuse);
+    hipLaunchKernelGGL((att_mix_kernel<float, 1>), gm, dim3(256), 0, st, (const float*)Kmat, ldk, 0, dots, a, src_len, S, Bp, H, ds, dHt, dCst, H, cl, fuse, nullptr);
   }
 }
 
@@ -1069,7 +1104,7 @@ template __global__ void tanh_planes_kernel<float>(Planes, float*, int, float*, 
 template <typename T>
 __global__ __launch_bounds__(64) void tanh_bwd_kernel(const float* __restrict__ dce, const int32_t* __restrict__ pos, Planes feed,
                                                       const T* __restrict__ Ho, int ldho, T* __restrict__ dpre, int ldp, int Bp,
-                                                      int H, DropSpec drop) {
+                                                      int H, DropSpec drop, T* __restrict__ dpre_fm) {
   const int i4 = blockIdx.x * 64 + threadIdx.x;        // single-wavefront workgroups: spread over all CUs
   const int hq = H >> 2;
   if (i4 >= Bp * hq) return;
@@ -1084,15 +1119,16 @@ __global__ __launch_bounds__(64) void tanh_bwd_kernel(const float* __restrict__ 
     o[e] = ((&d.x)[e] + (&f.x)[e]) * drop_factor(drop, b, h + e) * (1.f - ho * ho);
   }
   store4<T>(dpre + (size_t)b * ldp + h, o);
+  if (sizeof(T) == 2 && dpre_fm) store4<T>(dpre_fm + fm_offset(b, h, H >> 5), o);
 }
 
 void launch_tanh_bwd(int prec, const float* dHo_ce, const int32_t* pos, const Planes& feed, const void* Ho, int ldho, void* dpre,
-                     int ldp, int Bp, int H, const DropSpec& drop, hipStream_t st) {
+                     int ldp, int Bp, int H, const DropSpec& drop, hipStream_t st, void* dpre_fm) {
   const int n = Bp * (H >> 2);
   if (prec) hipLaunchKernelGGL(tanh_bwd_kernel<bf16_t>, dim3((n + 63) / 64), dim3(64), 0, st, dHo_ce, pos, feed,
-                               (const bf16_t*)Ho, ldho, (bf16_t*)dpre, ldp, Bp, H, drop);
+                               (const bf16_t*)Ho, ldho, (bf16_t*)dpre, ldp, Bp, H, drop, (bf16_t*)dpre_fm);
   else hipLaunchKernelGGL(tanh_bwd_kernel<float>, dim3((n + 63) / 64), dim3(64), 0, st, dHo_ce, pos, feed,
-                          (const float*)Ho, ldho, (float*)dpre, ldp, Bp, H, drop);
+                          (const float*)Ho, ldho, (float*)dpre, ldp, Bp, H, drop, (float*)nullptr);
 }
 
 }  // namespace cmt
