@@ -145,11 +145,10 @@ struct cmt_handle {
   char* HoFeedF = nullptr;              // fragment-major copy of the H_o rows fed to the decoder's bottom layer, [(Tmax+1)] slots of [Bp, H]
   int kb_bwd = 0, kb_wc = 0;            // caps on the k blocks of the backward step GEMMs (0 = default)
   // backward loops that use the whole-k step GEMM with the consumer in its epilogue (env CMT_BWD_FUSED, a bit
-  // mask): 1 = decoder (up to 64 sentences; at 128 every workgroup's re-read of the step's dgates makes it
-  // slower than the k-split GEMM + pointwise pair: 9.5 against 8.7 ms for the large workload's backward loop),
-  // 2 = upper encoder layers, 4 = bottom encoder layer.  The upper encoder layers keep the pair: their launches
-  // carry up to L - 1 layer-steps, and three rounds of 1024-thread workgroups per CU take longer (45 us per
-  // diagonal) than the pair (34 us).
+  // mask): 1 = decoder (up to 128 sentences: 8.1 against 8.7 ms for the large workload's backward loop; wider
+  // batches keep the k-split GEMM + pointwise pair), 2 = upper encoder layers, 4 = bottom encoder layer.  The upper
+  // encoder layers keep the pair: their launches carry up to L - 1 layer-steps, and the two forms take the same
+  // time there (1.62 against 1.64 ms at the medium workload).
   int bwd_fused = 5;
   // phase timing of a step on the caller's stream (measurement aid, env CMT_PHASE_TIMING=1)
   int phase_timing = 0;
@@ -847,7 +846,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   const int kbd = step_kblocks(p, 2 * H, 4 * H, Bp, h->kb_bwd);       // planes written by a decoder layer's backward GEMM
   const size_t pstr = (size_t)Bp * 2 * H;
   const Planes no_planes{nullptr, 0, 0, 0};
-  if ((h->bwd_fused & 1) && Bp <= 64) {
+  if ((h->bwd_fused & 1) && Bp <= 128) {            // (measured at 128 sentences: 8.1 against 8.7 ms for the k-split form)
     // one launch per layer and step (dec_bwd_gemm): no pointwise launches, no planes
     for (int j = T - 1; j >= 0; --j) {
       char* dpre = h->dPre + j * BP * esz;
