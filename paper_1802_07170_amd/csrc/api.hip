@@ -141,6 +141,7 @@ struct cmt_handle {
   int use_side = 1;
   char* dzs2 = nullptr; char* dzTs2 = nullptr;
   char* WcF = nullptr; char* WcTF = nullptr;  // fragment-major W_c [H, 2H] and W_c^T [2H, H]
+  char* WoF = nullptr;                        // fragment-major W_o [V, H] (greedy decoding's logits; V a multiple of 16)
   char* CsF = nullptr; char* dPreF = nullptr; // fragment-major copies of the contexts and of dpre, [Tmax] slots of [Bp, H]
   char* HoFeedF = nullptr;              // fragment-major copy of the H_o rows fed to the decoder's bottom layer, [(Tmax+1)] slots of [Bp, H]
   int kb_bwd = 0, kb_wc = 0;            // caps on the k blocks of the backward step GEMMs (0 = default)
@@ -272,6 +273,7 @@ size_t layout(cmt_handle* h, char* base) {
     h->HoFeedF = a.take((Mt + Bp) * H * esz);
     h->WcF = a.take((size_t)2 * H * H * esz); h->WcTF = a.take((size_t)2 * H * H * esz);
     h->CsF = a.take(Mt * H * esz); h->dPreF = a.take(Mt * H * esz);
+    if (c.tgt_vocab % 16 == 0) h->WoF = a.take((size_t)c.tgt_vocab * H * esz);
   }
   h->WaT = a.take((size_t)H * H * esz);
   h->WcT = a.take((size_t)2 * H * H * esz);
@@ -385,6 +387,7 @@ void refresh_params(cmt_handle* h, bool cast = true) {
   if (h->WcF) {
     launch_fm_pack(h->Pw(h->off_Wc), 2 * H, H, 2 * H, h->WcF, st);
     launch_fm_pack(h->WcT, H, 2 * H, H, h->WcTF, st);
+    if (h->WoF) launch_fm_pack(h->Pw(h->off_Wo), H, c.tgt_vocab, H, h->WoF, st);
   }
   launch_transpose(p, h->Pw(h->off_Wo), H, h->WoT, c.tgt_vocab, c.tgt_vocab, H, st);
 }
@@ -1433,21 +1436,34 @@ int cmt_greedy_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* 
       d.cprev = e.Cst + j * BH; d.mask = h->dec_mask;
       d.hnext = e.Hst + (j + 1) * BP * esz; d.ldhn = e.ph; d.cnext = e.Cst + (j + 1) * BH;
       d.gsave = e.Gs + (size_t)j * Bp * 4 * H; d.ycat = nullptr; d.ldy = 0;
+      if (e.fm) {
+        // fragment-major states for the layers above (and the attentional layer); the bottom layer's own input
+        // [embedding; H_o] has no fragment-major form here, so it reads row-major operands
+        d.hnext_fm = e.HstF + (j + 1) * BH * esz;
+        if (l > 0 && h->dec[l - 1].fm) {
+          d.W_fm = e.Wfm; d.x_fm = h->dec[l - 1].HstF + (j + 1) * BH * esz; d.hprev_fm = e.HstF + j * BH * esz;
+        }
+      }
       launch_lstm_fwd(p, &d, 1, Bp, H, st);
     }
     const char* Ht = h->dec[L - 1].Hst + (j + 1) * BP * esz;
     launch_att_fwd(p, h->Kmat, H, Hs, ldHs, Ht, PH, h->len_s, S, Bp, H, h->dots, h->att_a + (size_t)j * Bp * S, h->Cs + j * BP * esz,
-                   PH, st);
+                   PH, st, h->CsF ? h->CsF + j * BH * esz : nullptr);
     StepGemm g{};                                   // H_o = tanh(W_c [C_s; H_t]) straight into the next step's input
     g.a0 = h->Cs + j * BP * esz; g.lda0 = PH; g.K0 = H; g.w0_off = 0;
     g.a1 = Ht; g.lda1 = PH; g.K1 = H; g.w1_off = H;
     g.W = h->Pw(h->off_Wc); g.ldw = 2 * H; g.N = H; g.mode = 0;
     g.outT = h->xcat + (size_t)E * esz; g.ldo = h->ldxcat;
     g.out = h->wcp; g.ldout = H; g.plane_stride = BH;
+    if (h->HoFeedF && h->dec[L - 1].fm) {
+      g.W_fm = h->WcF; g.a0_fm = h->CsF + j * BH * esz; g.a1_fm = h->dec[L - 1].HstF + (j + 1) * BH * esz;
+      g.outF = h->HoFeedF;                          // H_o of this step, for the logits
+    }
     launch_step_gemm(p, g, Bp, st);
     StepGemm z{};                                   // logits (without the bias) = H_o W_o^T
     z.a0 = h->xcat + (size_t)E * esz; z.lda0 = h->ldxcat; z.K0 = H; z.w0_off = 0; z.K1 = 0;
     z.W = h->Pw(h->off_Wo); z.ldw = H; z.N = V; z.mode = 1; z.max_kb = 1;
+    if (g.outF && h->WoF) { z.W_fm = h->WoF; z.a0_fm = h->HoFeedF; }
     z.out = h->logits; z.ldout = V; z.plane_stride = (size_t)Bp * V;
     launch_step_gemm(p, z, Bp, st);
     launch_dec_argmax(h->logits, V, h->params + h->off_Bo, V, B, j, max_len, eos_id, h->dec_tok, h->dec_done, out_ids_dev,
