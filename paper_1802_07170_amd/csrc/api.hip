@@ -1516,10 +1516,12 @@ int cmt_beam_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* sr
   launch_beam_expand((int)esz, Hs, ldHs, BpE, h->Hs_exp, H, S, R, Rp, K, H, st);
   launch_beam_expand((int)esz, h->Kmat, H, BpE, h->K_exp, H, S, R, Rp, K, H, st);
   const size_t slotT = (size_t)Rp * PH * esz, slotC = (size_t)Rp * H * 4;   // state slots of Rp rows: 1 = read, 2 = written
+  const size_t slotF = (size_t)Rp * H * esz;                                // the same slots of the fragment-major copies
   for (int l = 0; l < L; ++l) {
     LD& e = h->dec[l];
     launch_beam_expand((int)esz, e.Hst, e.ph, BpE, e.Hst + slotT, e.ph, 1, R, Rp, K, H, st);
     launch_beam_expand(4, e.Cst, H, BpE, (char*)e.Cst + slotC, H, 1, R, Rp, K, H, st);
+    if (e.fm) launch_fm_pack(e.Hst + slotT, e.ph, Rp, H, e.HstF + slotF, st);   // fragment-major copy of the expanded states
   }
   launch_fill_T(p, h->xcat, (size_t)Rp * h->ldxcat, st);               // H_o^{<-1>} = 0
   BeamReorder ro{};
@@ -1527,6 +1529,7 @@ int cmt_beam_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* sr
     LD& e = h->dec[l];
     ro.h_src[l] = e.Hst + 2 * slotT; ro.h_dst[l] = e.Hst + slotT;
     ro.c_src[l] = (const float*)((char*)e.Cst + 2 * slotC); ro.c_dst[l] = (float*)((char*)e.Cst + slotC);
+    if (e.fm) ro.h_dst_fm[l] = e.HstF + slotF;
   }
   ro.ldh = PH;
   ro.ho_src = h->HoBuf; ro.ldho_src = PH; ro.ho_dst = h->xcat + (size_t)E * esz; ro.ldho_dst = h->ldxcat;
@@ -1542,16 +1545,21 @@ int cmt_beam_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* sr
       d.cprev = (const float*)((char*)e.Cst + slotC); d.mask = bs.mask;
       d.hnext = e.Hst + 2 * slotT; d.ldhn = e.ph; d.cnext = (float*)((char*)e.Cst + 2 * slotC);
       d.gsave = e.Gs; d.ycat = nullptr; d.ldy = 0;
+      if (e.fm) {                                    // as in greedy decoding: the layers above the bottom one
+        d.hnext_fm = e.HstF + 2 * slotF;
+        if (l > 0 && h->dec[l - 1].fm) { d.W_fm = e.Wfm; d.x_fm = h->dec[l - 1].HstF + 2 * slotF; d.hprev_fm = e.HstF + slotF; }
+      }
       launch_lstm_fwd(p, &d, 1, Rp, H, st);
     }
     const char* Ht = h->dec[L - 1].Hst + 2 * slotT;
-    launch_att_fwd(p, h->K_exp, H, h->Hs_exp, H, Ht, PH, h->len_exp, S, Rp, H, h->dots, h->att_a, h->Cs, PH, st);
+    launch_att_fwd(p, h->K_exp, H, h->Hs_exp, H, Ht, PH, h->len_exp, S, Rp, H, h->dots, h->att_a, h->Cs, PH, st, h->CsF);
     StepGemm g{};
     g.a0 = h->Cs; g.lda0 = PH; g.K0 = H; g.w0_off = 0;
     g.a1 = Ht; g.lda1 = PH; g.K1 = H; g.w1_off = H;
     g.W = h->Pw(h->off_Wc); g.ldw = 2 * H; g.N = H; g.mode = 0;
     g.outT = h->HoBuf; g.ldo = PH;
     g.out = h->wcp; g.ldout = H; g.plane_stride = (size_t)Rp * H;
+    if (h->CsF && h->dec[L - 1].fm) { g.W_fm = h->WcF; g.a0_fm = h->CsF; g.a1_fm = h->dec[L - 1].HstF + 2 * slotF; }
     launch_step_gemm(p, g, Rp, st);
     launch_gemm_nt(p, h->HoBuf, PH, h->Pw(h->off_Wo), H, Rp, V, H, h->logits, nullptr, V, h->params + h->off_Bo, 0, st);
     launch_beam_select(h->logits, V, bs, B, K, j, max_len, eos_id, length_penalty, st);

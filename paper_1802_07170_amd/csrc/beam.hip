@@ -251,7 +251,12 @@ __global__ __launch_bounds__(256) void beam_reorder_kernel(BeamReorder ro, BeamS
   for (int l = 0; l < L; ++l) {
     const T* hs = (const T*)ro.h_src[l] + (size_t)pr * ro.ldh;
     T* hd = (T*)ro.h_dst[l] + (size_t)r * ro.ldh;
-    for (int c = t * VE; c < H; c += 256 * VE) *reinterpret_cast<uint4*>(hd + c) = *reinterpret_cast<const uint4*>(hs + c);
+    T* hf = (T*)ro.h_dst_fm[l];
+    for (int c = t * VE; c < H; c += 256 * VE) {
+      const uint4 v = *reinterpret_cast<const uint4*>(hs + c);
+      *reinterpret_cast<uint4*>(hd + c) = v;
+      if (sizeof(T) == 2 && hf) *reinterpret_cast<uint4*>(hf + fm_offset(r, c, H >> 5)) = v;   // 8 elements of one k chunk
+    }
     const float* cs = ro.c_src[l] + (size_t)pr * H;
     float* cd = ro.c_dst[l] + (size_t)r * H;
     for (int c = t * 4; c < H; c += 256 * 4) *reinterpret_cast<float4*>(cd + c) = *reinterpret_cast<const float4*>(cs + c);

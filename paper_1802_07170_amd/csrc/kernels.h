@@ -299,6 +299,7 @@ struct BeamState {
 };
 struct BeamReorder {
   const void* h_src[8]; void* h_dst[8]; int ldh;     // per layer: states written by the step -> states the next step reads
+  void* h_dst_fm[8] = {};                            // optional fragment-major copies of h_dst (16-bit types, H / 32 k steps)
   const float* c_src[8]; float* c_dst[8];
   const void* ho_src; int ldho_src; void* ho_dst; int ldho_dst;   // H_o of the step -> input feed of the next
 };
