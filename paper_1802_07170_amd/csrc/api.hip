@@ -144,6 +144,9 @@ struct cmt_handle {
   char* WoF = nullptr;                        // fragment-major W_o [V, H] (greedy decoding's logits; V a multiple of 16)
   char* CsF = nullptr; char* dPreF = nullptr; // fragment-major copies of the contexts and of dpre, [Tmax] slots of [Bp, H]
   char* HoFeedF = nullptr;              // fragment-major copy of the H_o rows fed to the decoder's bottom layer, [(Tmax+1)] slots of [Bp, H]
+  // decoding (greedy, beam): the bottom decoder layer contracts [embedding; H_o; h] in one step, so it needs the gate
+  // rows of all E + 2H columns of its weights and its input [Bp, E + H] in fragment-major form
+  char* Wdec0F = nullptr; char* xcatF = nullptr;
   int kb_bwd = 0, kb_wc = 0;            // caps on the k blocks of the backward step GEMMs (0 = default)
   // backward loops that use the whole-k step GEMM with the consumer in its epilogue (env CMT_BWD_FUSED, a bit
   // mask): 1 = decoder (up to 128 sentences: 8.1 against 8.7 ms for the large workload's backward loop; wider
@@ -274,6 +277,7 @@ size_t layout(cmt_handle* h, char* base) {
     h->WcF = a.take((size_t)2 * H * H * esz); h->WcTF = a.take((size_t)2 * H * H * esz);
     h->CsF = a.take(Mt * H * esz); h->dPreF = a.take(Mt * H * esz);
     if (c.tgt_vocab % 16 == 0) h->WoF = a.take((size_t)c.tgt_vocab * H * esz);
+    if (E % 32 == 0) { h->Wdec0F = a.take((size_t)4 * H * (E + 2 * H) * esz); h->xcatF = a.take((size_t)Bp * (E + H) * esz); }
   }
   h->WaT = a.take((size_t)H * H * esz);
   h->WcT = a.take((size_t)2 * H * H * esz);
@@ -388,6 +392,7 @@ void refresh_params(cmt_handle* h, bool cast = true) {
     launch_fm_pack(h->Pw(h->off_Wc), 2 * H, H, 2 * H, h->WcF, st);
     launch_fm_pack(h->WcT, H, 2 * H, H, h->WcTF, st);
     if (h->WoF) launch_fm_pack(h->Pw(h->off_Wo), H, c.tgt_vocab, H, h->WoF, st);
+    if (h->Wdec0F) launch_fm_pack_lstm_weights(h->dec[0].W, c.emb_dim + 2 * H, 0, c.emb_dim + 2 * H, H, h->Wdec0F, st);
   }
   launch_transpose(p, h->Pw(h->off_Wo), H, h->WoT, c.tgt_vocab, c.tgt_vocab, H, st);
 }
@@ -1424,8 +1429,10 @@ int cmt_greedy_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* 
   enqueue_encoder(h, S, &Hs, &ldHs);
   launch_dec_init(B, Bp, max_len, c.bos_id, c.pad_id, h->dec_tok, h->dec_done, out_ids_dev, out_len_dev, h->dec_mask, st);
   launch_fill_T(p, h->xcat, (size_t)Bp * h->ldxcat, st);              // H_o^{<-1>} = 0
+  const bool fm0 = h->xcatF && h->dec[0].fm;                          // bottom layer on fragment-major operands
+  if (fm0) launch_fill_T(p, h->xcatF, (size_t)Bp * (E + H), st);
   for (int j = 0; j < max_len; ++j) {
-    launch_dec_embed(p, h->Pw(h->off_Etgt), E, h->dec_tok, B, Bp, h->xcat, h->ldxcat, st);
+    launch_dec_embed(p, h->Pw(h->off_Etgt), E, h->dec_tok, B, Bp, h->xcat, h->ldxcat, st, fm0 ? h->xcatF : nullptr, (E + H) >> 5);
     for (int l = 0; l < L; ++l) {
       LD& e = h->dec[l];
       LstmFwdDir d;
@@ -1437,11 +1444,11 @@ int cmt_greedy_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* 
       d.hnext = e.Hst + (j + 1) * BP * esz; d.ldhn = e.ph; d.cnext = e.Cst + (j + 1) * BH;
       d.gsave = e.Gs + (size_t)j * Bp * 4 * H; d.ycat = nullptr; d.ldy = 0;
       if (e.fm) {
-        // fragment-major states for the layers above (and the attentional layer); the bottom layer's own input
-        // [embedding; H_o] has no fragment-major form here, so it reads row-major operands
         d.hnext_fm = e.HstF + (j + 1) * BH * esz;
         if (l > 0 && h->dec[l - 1].fm) {
           d.W_fm = e.Wfm; d.x_fm = h->dec[l - 1].HstF + (j + 1) * BH * esz; d.hprev_fm = e.HstF + j * BH * esz;
+        } else if (l == 0 && fm0) {
+          d.W_fm = h->Wdec0F; d.x_fm = h->xcatF; d.hprev_fm = e.HstF + j * BH * esz;
         }
       }
       launch_lstm_fwd(p, &d, 1, Bp, H, st);
@@ -1458,6 +1465,7 @@ int cmt_greedy_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* 
     if (h->HoFeedF && h->dec[L - 1].fm) {
       g.W_fm = h->WcF; g.a0_fm = h->CsF + j * BH * esz; g.a1_fm = h->dec[L - 1].HstF + (j + 1) * BH * esz;
       g.outF = h->HoFeedF;                          // H_o of this step, for the logits
+      if (fm0) { g.outF2 = h->xcatF; g.outF2_nsteps = (E + H) >> 5; g.outF2_k0 = E; }   // and for the next step's bottom layer
     }
     launch_step_gemm(p, g, Bp, st);
     StepGemm z{};                                   // logits (without the bias) = H_o W_o^T
@@ -1524,6 +1532,8 @@ int cmt_beam_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* sr
     if (e.fm) launch_fm_pack(e.Hst + slotT, e.ph, Rp, H, e.HstF + slotF, st);   // fragment-major copy of the expanded states
   }
   launch_fill_T(p, h->xcat, (size_t)Rp * h->ldxcat, st);               // H_o^{<-1>} = 0
+  const bool fm0 = h->xcatF && h->dec[0].fm;                           // bottom layer on fragment-major operands
+  if (fm0) launch_fill_T(p, h->xcatF, (size_t)Rp * (E + H), st);
   BeamReorder ro{};
   for (int l = 0; l < L; ++l) {
     LD& e = h->dec[l];
@@ -1533,8 +1543,9 @@ int cmt_beam_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* sr
   }
   ro.ldh = PH;
   ro.ho_src = h->HoBuf; ro.ldho_src = PH; ro.ho_dst = h->xcat + (size_t)E * esz; ro.ldho_dst = h->ldxcat;
+  if (fm0) { ro.ho_dst_fm = h->xcatF; ro.ho_fm_nsteps = (E + H) >> 5; ro.ho_fm_k0 = E; }
   for (int j = 0; j < max_len; ++j) {
-    launch_dec_embed(p, h->Pw(h->off_Etgt), E, bs.tok, R, Rp, h->xcat, h->ldxcat, st);
+    launch_dec_embed(p, h->Pw(h->off_Etgt), E, bs.tok, R, Rp, h->xcat, h->ldxcat, st, fm0 ? h->xcatF : nullptr, (E + H) >> 5);
     for (int l = 0; l < L; ++l) {
       LD& e = h->dec[l];
       LstmFwdDir d;
@@ -1548,6 +1559,7 @@ int cmt_beam_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* sr
       if (e.fm) {                                    // as in greedy decoding: the layers above the bottom one
         d.hnext_fm = e.HstF + 2 * slotF;
         if (l > 0 && h->dec[l - 1].fm) { d.W_fm = e.Wfm; d.x_fm = h->dec[l - 1].HstF + 2 * slotF; d.hprev_fm = e.HstF + slotF; }
+        else if (l == 0 && fm0) { d.W_fm = h->Wdec0F; d.x_fm = h->xcatF; d.hprev_fm = e.HstF + slotF; }
       }
       launch_lstm_fwd(p, &d, 1, Rp, H, st);
     }

@@ -263,7 +263,12 @@ __global__ __launch_bounds__(256) void beam_reorder_kernel(BeamReorder ro, BeamS
   }
   const T* os = (const T*)ro.ho_src + (size_t)pr * ro.ldho_src;
   T* od = (T*)ro.ho_dst + (size_t)r * ro.ldho_dst;
-  for (int c = t * VE; c < H; c += 256 * VE) *reinterpret_cast<uint4*>(od + c) = *reinterpret_cast<const uint4*>(os + c);
+  T* of = (T*)ro.ho_dst_fm;
+  for (int c = t * VE; c < H; c += 256 * VE) {
+    const uint4 v = *reinterpret_cast<const uint4*>(os + c);
+    *reinterpret_cast<uint4*>(od + c) = v;
+    if (sizeof(T) == 2 && of) *reinterpret_cast<uint4*>(of + fm_offset(r, ro.ho_fm_k0 + c, ro.ho_fm_nsteps)) = v;
+  }
 }
 void launch_beam_reorder(int prec, const BeamReorder& ro, const BeamState& bs, int R, int H, int L, hipStream_t st) {
   if (prec) hipLaunchKernelGGL(beam_reorder_kernel<bf16_t>, dim3(R), dim3(256), 0, st, ro, bs, H, L);

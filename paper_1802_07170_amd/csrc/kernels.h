@@ -121,8 +121,9 @@ inline __host__ __device__ size_t fm_offset(int row, int k, int nsteps) {
   return ((((size_t)(row >> 4) * nsteps + (k >> 5)) * 64 + (row & 15) + 16 * ((k & 31) >> 3)) << 3) + (k & 7);
 }
 // dst (fragment-major, nsteps = cols / 32) <- src [rows, cols] row-major with pitch ld (16-bit elements; rows a
-// multiple of 16, cols a multiple of 32)
-void launch_fm_pack(const void* src, int ld, int rows, int cols, void* dst, hipStream_t st);
+// multiple of 16, cols a multiple of 32).  With dst_nsteps > 0 the destination is a wider matrix of dst_nsteps
+// k steps per row tile and the copy lands at its columns [32 * dst_step0, 32 * dst_step0 + cols).
+void launch_fm_pack(const void* src, int ld, int rows, int cols, void* dst, hipStream_t st, int dst_nsteps = 0, int dst_step0 = 0);
 // the same for the gate rows of an LSTM weight matrix: tile T holds units 4T .. 4T+3, row m of the tile is gate m % 4
 // of unit 4T + m / 4 (rows of W are gate-major: gate * Hh + unit); columns [col0, col0 + K) of W
 void launch_fm_pack_lstm_weights(const void* W, int ldw, int col0, int K, int Hh, void* dst, hipStream_t st);
@@ -148,6 +149,8 @@ struct StepGemm {
   const void* W_fm = nullptr; int w_tile0 = 0; const void* a0_fm = nullptr; const void* a1_fm = nullptr;
   void* outF = nullptr;                // mode 0, 16-bit types: optional fragment-major copy (fm_offset, N / 32 k steps) of
                                        //   what the next step is fed: outD's values if outD is set, else outT's
+  void* outF2 = nullptr;               // one more such copy, into the columns [outF2_k0, outF2_k0 + N) of a fragment-major
+  int outF2_nsteps = 0, outF2_k0 = 0;  //   matrix of outF2_nsteps k steps (k0 a multiple of 32)
   float* out; int ldout; size_t plane_stride;
   int max_kb;          // cap on the number of k blocks (planes); 0 = default (8)
 };
@@ -274,7 +277,9 @@ void launch_grid_barrier_probe(unsigned* counter, int* gave_up, int blocks, int 
 
 // ---- greedy decoding (misc.hip) -------------------------------------------------------------------
 // x[b, 0:E] = table[tok[b]] (T, row pitch ldx) for b < B; zero rows for b in [B, Bp).
-void launch_dec_embed(int prec, const void* table, int E, const int32_t* tok, int B, int Bp, void* x, int ldx, hipStream_t st);
+// x_fm (16-bit types, optional): the same rows into the columns [0, E) of a fragment-major matrix of nsteps_fm k steps.
+void launch_dec_embed(int prec, const void* table, int E, const int32_t* tok, int B, int Bp, void* x, int ldx, hipStream_t st,
+                      void* x_fm = nullptr, int nsteps_fm = 0);
 // tok[b] = argmax_v (z[b, v] + bias[v]) (lowest index on ties); unfinished sentences record it at
 // out_ids[b, j] and end on eos or at j = max_len - 1 (done[b] = 1, out_len[b] = j + 1).
 void launch_dec_argmax(const float* z, int ldz, const float* bias, int V, int B, int j, int max_len, int eos, int32_t* tok,
@@ -302,6 +307,8 @@ struct BeamReorder {
   void* h_dst_fm[8] = {};                            // optional fragment-major copies of h_dst (16-bit types, H / 32 k steps)
   const float* c_src[8]; float* c_dst[8];
   const void* ho_src; int ldho_src; void* ho_dst; int ldho_dst;   // H_o of the step -> input feed of the next
+  void* ho_dst_fm = nullptr; int ho_fm_nsteps = 0, ho_fm_k0 = 0;  // optional fragment-major copy: columns [k0, k0 + H) of a
+                                                                  //   matrix of ho_fm_nsteps k steps (16-bit types)
 };
 // dst[i, r, 0:cols] = src[i, r / K, 0:cols] (r < R), zero rows up to Rp; elem_bytes 2 or 4.
 void launch_beam_expand(int elem_bytes, const void* src, int ld_src, int rows_src, void* dst, int ld_dst, int n_outer, int R, int Rp,

@@ -355,7 +355,7 @@ void launch_grid_barrier_probe(unsigned* counter, int* gave_up, int blocks, int 
 // x[b, 0:E] = table[tok[b]] for b < B, zero rows for the batch padding
 template <typename T>
 __global__ __launch_bounds__(128) void dec_embed_kernel(const T* __restrict__ table, int E, const int32_t* __restrict__ tok, int B,
-                                                        T* __restrict__ x, int ldx) {
+                                                        T* __restrict__ x, int ldx, T* __restrict__ x_fm, int nsteps_fm) {
   const int b = blockIdx.x;
   const T* src = b < B ? table + (size_t)tok[b] * E : nullptr;
   for (int c = threadIdx.x * 8; c < E; c += 128 * 8) {
@@ -363,11 +363,15 @@ __global__ __launch_bounds__(128) void dec_embed_kernel(const T* __restrict__ ta
     if (src) for (int q = 0; q < (int)(sizeof(T) / 2); ++q) v[q] = reinterpret_cast<const uint4*>(src + c)[q];
     else for (int q = 0; q < (int)(sizeof(T) / 2); ++q) v[q] = make_uint4(0, 0, 0, 0);
     for (int q = 0; q < (int)(sizeof(T) / 2); ++q) reinterpret_cast<uint4*>(x + (size_t)b * ldx + c)[q] = v[q];
+    if (sizeof(T) == 2 && x_fm) *reinterpret_cast<uint4*>(x_fm + fm_offset(b, c, nsteps_fm)) = v[0];   // 8 elements of one k chunk
   }
 }
-void launch_dec_embed(int prec, const void* table, int E, const int32_t* tok, int B, int Bp, void* x, int ldx, hipStream_t st) {
-  if (prec) hipLaunchKernelGGL(dec_embed_kernel<bf16_t>, dim3(Bp), dim3(128), 0, st, (const bf16_t*)table, E, tok, B, (bf16_t*)x, ldx);
-  else hipLaunchKernelGGL(dec_embed_kernel<float>, dim3(Bp), dim3(128), 0, st, (const float*)table, E, tok, B, (float*)x, ldx);
+void launch_dec_embed(int prec, const void* table, int E, const int32_t* tok, int B, int Bp, void* x, int ldx, hipStream_t st,
+                      void* x_fm, int nsteps_fm) {
+  if (prec) hipLaunchKernelGGL(dec_embed_kernel<bf16_t>, dim3(Bp), dim3(128), 0, st, (const bf16_t*)table, E, tok, B, (bf16_t*)x, ldx,
+                               (bf16_t*)x_fm, nsteps_fm);
+  else hipLaunchKernelGGL(dec_embed_kernel<float>, dim3(Bp), dim3(128), 0, st, (const float*)table, E, tok, B, (float*)x, ldx,
+                          (float*)nullptr, 0);
 }
 
 // One workgroup per sentence: token = argmax_v (z[b, v] + bias[v]), the lowest index winning a tie.

@@ -176,22 +176,26 @@ __device__ __forceinline__ float planes_get(const Planes& p, int b, int c) {
 // Row-major -> fragment-major copies (16-bit elements)
 // ------------------------------------------------------------------------------------------------
 // one thread per 16-byte chunk of the destination: block (row tile, k step), lane, 8 elements
-__global__ __launch_bounds__(256) void fm_pack_kernel(const bf16_t* __restrict__ src, int ld, int rows, int nsteps, bf16_t* __restrict__ dst) {
+__global__ __launch_bounds__(256) void fm_pack_kernel(const bf16_t* __restrict__ src, int ld, int rows, int nsteps, bf16_t* __restrict__ dst,
+                                                      int dst_nsteps, int dst_step0) {
   const size_t n = (size_t)(rows >> 4) * nsteps * 64;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
     const int lane = (int)(i & 63);
     const size_t blk = i >> 6;
     const int s = (int)(blk % nsteps), rt = (int)(blk / nsteps);
     const int row = rt * 16 + (lane & 15), k = s * 32 + (lane >> 4) * 8;
-    *reinterpret_cast<uint4*>(dst + i * 8) = *reinterpret_cast<const uint4*>(src + (size_t)row * ld + k);
+    const size_t o = (((size_t)rt * dst_nsteps + dst_step0 + s) * 64 + lane) * 8;
+    *reinterpret_cast<uint4*>(dst + o) = *reinterpret_cast<const uint4*>(src + (size_t)row * ld + k);
   }
 }
-void launch_fm_pack(const void* src, int ld, int rows, int cols, void* dst, hipStream_t st) {
+void launch_fm_pack(const void* src, int ld, int rows, int cols, void* dst, hipStream_t st, int dst_nsteps, int dst_step0) {
   const size_t n = (size_t)(rows >> 4) * (cols >> 5) * 64;
   if (n == 0) return;
   size_t g = (n + 255) / 256;
   if (g > 65535) g = 65535;
-  hipLaunchKernelGGL(fm_pack_kernel, dim3((unsigned)g), dim3(256), 0, st, (const bf16_t*)src, ld, rows, cols >> 5, (bf16_t*)dst);
+  if (dst_nsteps <= 0) { dst_nsteps = cols >> 5; dst_step0 = 0; }
+  hipLaunchKernelGGL(fm_pack_kernel, dim3((unsigned)g), dim3(256), 0, st, (const bf16_t*)src, ld, rows, cols >> 5, (bf16_t*)dst, dst_nsteps,
+                     dst_step0);
 }
 __global__ __launch_bounds__(256) void fm_pack_lstm_weights_kernel(const bf16_t* __restrict__ W, int ldw, int col0, int nsteps, int Hh,
                                                                    bf16_t* __restrict__ dst) {
@@ -532,6 +536,7 @@ __global__ __launch_bounds__(64 * KS) void step_tanh_kernel(StepGemm g, int Bp, 
       ((T*)g.outT)[(size_t)b * g.ldo + n + i] = from_f<T>(hv);
       if (g.outD) ((T*)g.outD)[(size_t)b * g.ldod + n + i] = from_f<T>(hd);
       if (sizeof(T) == 2 && g.outF) ((T*)g.outF)[fm_offset(b, n + i, g.N >> 5)] = from_f<T>(hd);
+      if (sizeof(T) == 2 && g.outF2) ((T*)g.outF2)[fm_offset(b, g.outF2_k0 + n + i, g.outF2_nsteps)] = from_f<T>(hd);
     }
 }
 
@@ -586,7 +591,7 @@ void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st) {
     return;
   }
   // the other forms do not write the fragment-major copy themselves
-  const bool pack_after = g.mode == 0 && prec && g.outF;
+  const bool pack_after = g.mode == 0 && prec && (g.outF || g.outF2);
   const Step2dPlan pl = plan2d(prec, g.N, g.K0 + g.K1, Bp, g.max_kb);
   StepGrid sg{(g.N + 63) / 64, pl.kb, (nbt + STEP_MAXBT - 1) / STEP_MAXBT};
   const dim3 grid(step_grid_blocks(sg));
@@ -607,7 +612,9 @@ void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st) {
     else hipLaunchKernelGGL(tanh_planes_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, st, p, (float*)g.outT, g.ldo,
                             (float*)g.outD, g.ldod, g.drop, Bp, g.N);
   }
-  if (pack_after) launch_fm_pack(g.outD ? g.outD : g.outT, g.outD ? g.ldod : g.ldo, Bp, g.N, g.outF, st);
+  if (pack_after && g.outF) launch_fm_pack(g.outD ? g.outD : g.outT, g.outD ? g.ldod : g.ldo, Bp, g.N, g.outF, st);
+  if (pack_after && g.outF2)
+    launch_fm_pack(g.outD ? g.outD : g.outT, g.outD ? g.ldod : g.ldo, Bp, g.N, g.outF2, st, g.outF2_nsteps, g.outF2_k0 >> 5);
 }
 
 // ------------------------------------------------------------------------------------------------
