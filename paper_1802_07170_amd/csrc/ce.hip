@@ -55,38 +55,72 @@ __global__ __launch_bounds__(CeG::NT) void ce_fwd_kernel(const T* __restrict__ H
   constexpr int SROW = 32 * NTS * (int)sizeof(T) + 16;    // staged row pitch in bytes (padded against bank conflicts)
   char* stage = smem + w * (64 * SROW);
   static_assert(16 * 64 * SROW <= CeG::SMEM_BYTES, "staging area exceeds the kernel's LDS");
+  // The epilogue handles 64 logits per lane with a handful of vector instructions each (it is bound by their
+  // count, not by memory): the vocabulary bound is tested only in the tile that contains it, the label's logit is
+  // picked outside the loops, and the 16-bit path uses the hardware exponential and the packed bf16 conversion.
+  const bool ragged = v0 + CeG::BM > V;                   // uniform: the tile reaches past the vocabulary
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
     const int r = r0 + wn * 64 + nt * 32 + (lane & 31);
     const int y = r < M ? labels[r] : -1;
-    // the logits overwrite the accumulators of this half (nothing else needs them): no second register array
-    float mx = -INFINITY, sz = 0.f, zlab = 0.f;
-    const int yl = y - v0 - wm * 64;                      // the label's place among this wavefront's 64 entries, if any
+    float mx = -INFINITY, sz = 0.f;
+    if (ragged) {                                         // entries past the vocabulary: logit -inf, e = 0
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (v0 + wm * 64 + mt * 32 + acc32_row(lane, i) >= V) acc[mt][nt][i] = -INFINITY;
+    }
+    if (psz) {                                            // label smoothing needs the mean logit of the row
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sz += acc[mt][nt][i] > -INFINITY ? acc[mt][nt][i] : 0.f;
+    }
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int vl = wm * 64 + mt * 32 + acc32_row(lane, i);
-        const bool in = v0 + vl < V;
-        const float zv = in ? acc[mt][nt][i] : -INFINITY;
-        acc[mt][nt][i] = zv;
-        sz += in ? zv : 0.f;
-        zlab = (mt * 32 + acc32_row(lane, i) == yl) ? zv : zlab;
-        mx = fmaxf(mx, zv);
-      }
-    // one of the two lanes that share position r holds the label's entry: rows 8 (i / 4) + 4 (lane / 32) + i % 4
-    if (y >= 0 && yl >= 0 && yl < 64 && ((yl >> 2) & 1) == (lane >> 5)) zy[r] = zlab;
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[mt][nt][i]);
+    // the label's logit: entry yl of this wavefront's 64 sits in register (yl / 32, 4 (yl % 32 / 8) + yl % 4) of the
+    // one of the two lanes sharing position r whose half (lane / 32) equals (yl / 4) % 2
+    const int yl = y - v0 - wm * 64;
+    if (y >= 0 && yl >= 0 && yl < 64 && ((yl >> 2) & 1) == (lane >> 5)) {
+      const int want = (yl >> 5) * 16 + ((yl & 31) >> 3) * 4 + (yl & 3);
+      float zlab = 0.f;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) zlab = (mt * 16 + i == want) ? acc[mt][nt][i] : zlab;
+      zy[r] = zlab;
+    }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float ms = mx > -INFINITY ? mx : 0.f;           // a group wholly past the vocabulary: exp(-inf - 0) = 0
     float e = 0.f;
+    char* srow = stage + ((nt % NTS) * 32 + (lane & 31)) * sizeof(T);
+    if constexpr (sizeof(T) == 2) {
+      typedef float f32x2 __attribute__((ext_vector_type(2)));
+      typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+      for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int vl = mt * 32 + acc32_row(lane, i);
-        const float ev = mx > -INFINITY ? expf(acc[mt][nt][i] - mx) : 0.f;   // exp(-inf) = 0 past the vocabulary
-        e += ev;
-        *reinterpret_cast<T*>(stage + vl * SROW + ((nt % NTS) * 32 + (lane & 31)) * sizeof(T)) = from_f<T>(ev);
-      }
+        for (int i = 0; i < 16; i += 2) {
+          const f32x2 ev = {__expf(acc[mt][nt][i] - ms), __expf(acc[mt][nt][i + 1] - ms)};
+          e += ev[0] + ev[1];
+          const bf16x2 eb = __builtin_convertvector(ev, bf16x2);   // round to nearest even, one instruction per pair
+          const int vl = mt * 32 + acc32_row(lane, i);             // i even: entries i and i + 1 are rows vl and vl + 1
+          *reinterpret_cast<__bf16*>(srow + vl * SROW) = eb[0];
+          *reinterpret_cast<__bf16*>(srow + (vl + 1) * SROW) = eb[1];
+        }
+    } else {
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float ev = expf(acc[mt][nt][i] - ms);
+          e += ev;
+          *reinterpret_cast<float*>(srow + (mt * 32 + acc32_row(lane, i)) * SROW) = ev;
+        }
+    }
     if (nt % NTS == NTS - 1) {                            // a staged block is complete: 64 rows of 32 * NTS positions
       __syncthreads();
       constexpr int CPR = 32 * NTS * (int)sizeof(T) / 16; // 16-byte chunks per staged row
@@ -104,7 +138,7 @@ __global__ __launch_bounds__(CeG::NT) void ce_fwd_kernel(const T* __restrict__ H
       if (nt + 1 < 2) __syncthreads();                    // the staging area is reused by the next half
     }
     e += __shfl_xor(e, 32, 64);
-    if (psz) sz += __shfl_xor(sz, 32, 64);                // label smoothing needs the mean logit of the row
+    if (psz) sz += __shfl_xor(sz, 32, 64);
     if (lane < 32 && r < M) {                             // partials are kept [group][position]: 32 lanes, 128 bytes
       pmax[(size_t)pidx * ldet + r] = mx;
       psum[(size_t)pidx * ldet + r] = e;
