@@ -328,8 +328,8 @@ __global__ __launch_bounds__(256) void ce_scale_kernel(T* __restrict__ ET, int l
   constexpr int VE = 16 / sizeof(T);                      // elements per 16-byte vector
   constexpr int NV = 16 / VE;                             // vectors per thread
   __shared__ __align__(16) T tile[64][64 + VE];           // [position][vocabulary entry]
-  __shared__ float sf[64], srs[64];
-  __shared__ int sy[64];
+  __shared__ __align__(16) float sf[64], srs[64];
+  __shared__ __align__(16) int sy[64];
   const int v0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
   const int t = threadIdx.x;
   if (lim.n) Mc = min(Mc, max(*lim.n - lim.base, 0));
@@ -338,6 +338,10 @@ __global__ __launch_bounds__(256) void ce_scale_kernel(T* __restrict__ ET, int l
     if ((t & 3) == 0 && v < V) dbo_part[(size_t)blockIdx.y * V + v] = 0.f;
     return;
   }
+  // dz = (e * f - q) * rs with f = exp(m - lse), q = (1 - eps) onehot + eps / V, rs = mask / n_tok, as one
+  // multiply-add per element: dz = e * sa - (sb + [label] * sc), sa = f rs, sb = eps / V rs, sc = (1 - eps) rs
+  // (rows that do not exist: all three zero)
+  const float epsv = eps / (float)V;
   if (t < 64) {
     const int r = r0 + t;
     float f = 0.f, rs = 0.f;
@@ -348,25 +352,51 @@ __global__ __launch_bounds__(256) void ce_scale_kernel(T* __restrict__ ET, int l
       rs = rowscale[r];
       y = labels[r];
     }
-    sf[t] = f; srs[t] = rs; sy[t] = y;
+    sf[t] = f * rs; srs[t] = rs; sy[t] = y;
   }
   __syncthreads();
-  const float epsv = eps / (float)V;                      // target distribution (1 - eps) onehot + eps / V
   {
     const int vl = t >> 2, v = v0 + vl, rb = (t & 3) * 16;
+    const bool edge = r0 + 64 > Mc;                       // uniform: the block holds rows that do not exist
     float cs = 0.f;                                       // this block's share of dB_o[v]: 64 positions in fixed order
 #pragma unroll
     for (int q = 0; q < NV; ++q) {
       T x[VE];
       if (v < V) *reinterpret_cast<uint4*>(x) = *reinterpret_cast<const uint4*>(ET + (size_t)v * ldet + r0 + rb + q * VE);
       else *reinterpret_cast<uint4*>(x) = make_uint4(0, 0, 0, 0);
+      float a[VE], rs[VE];
+      int y[VE];
+      *reinterpret_cast<uint4*>(a) = *reinterpret_cast<const uint4*>(&sf[rb + q * VE]);
+      *reinterpret_cast<uint4*>(rs) = *reinterpret_cast<const uint4*>(&srs[rb + q * VE]);
+      *reinterpret_cast<uint4*>(y) = *reinterpret_cast<const uint4*>(&sy[rb + q * VE]);
+      if constexpr (VE == 8) {
+        *reinterpret_cast<uint4*>(a + 4) = *reinterpret_cast<const uint4*>(&sf[rb + q * VE + 4]);
+        *reinterpret_cast<uint4*>(rs + 4) = *reinterpret_cast<const uint4*>(&srs[rb + q * VE + 4]);
+        *reinterpret_cast<uint4*>(y + 4) = *reinterpret_cast<const uint4*>(&sy[rb + q * VE + 4]);
+      }
+      float d[VE];
 #pragma unroll
       for (int j = 0; j < VE; ++j) {
-        const int rl = rb + q * VE + j;
-        const float d = v < V && r0 + rl < Mc ? (to_f<T>(x[j]) * sf[rl] - (sy[rl] == v ? 1.f - eps : 0.f) - epsv) * srs[rl] : 0.f;
-        x[j] = from_f<T>(d);
+        const float e = edge && r0 + rb + q * VE + j >= Mc ? 0.f : to_f<T>(x[j]);   // (what such rows hold is anything)
+        d[j] = v < V ? fmaf(e, a[j], -(epsv * rs[j] + (y[j] == v ? (1.f - eps) * rs[j] : 0.f))) : 0.f;
+      }
+      if constexpr (sizeof(T) == 2) {
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+        for (int j = 0; j < VE; j += 2) {                 // round to nearest even, one instruction per pair
+          const f32x2 dv = {d[j], d[j + 1]};
+          const bf16x2 db = __builtin_convertvector(dv, bf16x2);
+          *reinterpret_cast<bf16x2*>(&x[j]) = db;
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < VE; ++j) x[j] = from_f<T>(d[j]);
+      }
+#pragma unroll
+      for (int j = 0; j < VE; ++j) {
         cs += to_f<T>(x[j]);
-        tile[rl][vl] = x[j];
+        tile[rb + q * VE + j][vl] = x[j];
       }
       if (v < V) *reinterpret_cast<uint4*>(ET + (size_t)v * ldet + r0 + rb + q * VE) = *reinterpret_cast<const uint4*>(x);
     }
