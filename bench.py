@@ -195,6 +195,7 @@ def main():
     peak_mfma = MFMA_BF16_PEAK_TFLOPS if c["precision"] else MFMA_FP32_PEAK_TFLOPS
     kernels = {}
     for name, kind, iters in [("step_bwd_fused_dec", "hbm", 400), ("step2d_bwd_dec", "hbm", 400), ("att_fwd", "hbm", 400),
+                              ("att_bwd", "hbm", 400),
                               ("gemm_gx", "mfma", 50), ("gemm_dw", "mfma", 50), ("ce_fwd", "mfma", 20)]:
         kus, work = tr.time_kernel(name, iters)
         if kind == "hbm":

@@ -213,6 +213,7 @@ int cmt_padded_batch(const cmt_handle* h);
  *   "lstm_fwd_dec"   fused decoder LSTM step (gate GEMM + cell), cycling over the layers   bytes
  *   "step2d_bwd_dec" [dx; dh] = dgates [W_x; W_h] of a decoder layer's backward step       bytes
  *   "att_fwd"        attention scores + softmax + context of one decoder step              bytes
+ *   "att_bwd"        attention backward of one decoder step (with the top layer's cell)   bytes
  *   "gemm_gx"        time-batched input-side GEMM [T Bp, E] x [E, 4H]                      flops
  *   "gemm_dw"        the decoder's weight-gradient GEMMs (W_c and every layer, k = T Bp), one grouped launch  flops
  *   "ce_fwd"         vocabulary projection + log-sum-exp partials of the first slab of rows flops

@@ -1666,6 +1666,20 @@ int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_la
       launch_att_fwd(p, h->Kmat, H, Hs, ldHs, h->dec[L - 1].Hst + (j + 1) * BP * es, PH, h->len_s, S, Bp, H, h->dots,
                      h->att_a + (size_t)j * Bp * S, h->Cs + j * BP * es, PH, st);
     };
+  } else if (s == "att_bwd") {
+    // attention backward of one decoder step as the step launches it (score gradients, the gradient sent to the
+    // top layer's output, that layer's cell backward in the same launch): H_s and the keys of every sentence once
+    *algo_work = 2.0 * Bp * S * H * esz;
+    const char* Hs = L > 1 ? h->enc[L].Hst + BP * es : h->Y0;
+    const int ldHs = L > 1 ? PH : H;
+    const int kbw = step_kblocks(p, 2 * H, H, Bp, h->kb_wc);
+    const size_t pstr = (size_t)Bp * 2 * H;
+    launch = [=](int) {
+      LstmBwdPoint top = dec_cell(h, L - 1, j);
+      top.dhrec = Planes{h->dec[L - 1].bwdp, H, 1, 0};
+      launch_att_bwd(p, h->Kmat, H, Hs, ldHs, Planes{h->wcp, 2 * H, kbw, pstr}, h->dCs + j * BH, h->att_a + (size_t)j * Bp * S,
+                     h->len_s, S, Bp, H, h->dots, h->att_ds + (size_t)j * Bp * S, h->dHt, st, &top);
+    };
   } else if (s == "gemm_gx") {
     // time-batched input-side GEMM of the decoder's bottom layer: [T Bp, E] x [E, 4H]  (flops)
     *algo_work = 2.0 * Mt * 4 * H * E;
