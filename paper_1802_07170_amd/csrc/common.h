@@ -88,8 +88,19 @@ __device__ __forceinline__ void mma32(v16f& acc, const Frag<float>& a, const Fra
 }
 __device__ __forceinline__ int acc32_row(int lane, int i) { return 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); }
 
-// full-accuracy exp / tanh: the pointwise work is negligible next to the weight streaming
+// Gate nonlinearities.  The fp32 path takes the full-accuracy library routines.  On the 16-bit path (FAST) the
+// results are rounded to 8 significant bits or meet operands that were, so the hardware exponential and
+// reciprocal (about 1e-6 relative) are as good, at a tenth of the instructions — the cell epilogues of the
+// per-step kernels run on one or two wavefronts per workgroup and wait for these.
 __device__ __forceinline__ float sigm(float x) { return 1.0f / (1.0f + expf(-x)); }
+template <bool FAST> __device__ __forceinline__ float sigm_of(float x) {
+  if (FAST) return __builtin_amdgcn_rcpf(1.0f + __expf(-x));
+  return sigm(x);
+}
+template <bool FAST> __device__ __forceinline__ float tanh_of(float x) {
+  if (FAST) return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(2.0f * x));   // exp = inf -> 1, exp = 0 -> -1
+  return tanhf(x);
+}
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

@@ -237,10 +237,17 @@ __device__ __forceinline__ CellIn cell_load(const LstmFwdDir& d, int b, int u, i
 }
 __device__ __forceinline__ void cell_finish(const LstmFwdDir& d, int b, int u, int Hh, const float (&pre)[4], const CellIn& in,
                                             bool is_bf16) {
-  const float ig = sigm(pre[0] + in.add[0]), fg = sigm(pre[1] + in.add[1]);
-  const float gg = tanhf(pre[2] + in.add[2]), og = sigm(pre[3] + in.add[3]);
+  float ig, fg, gg, og, tcn;
+  if (is_bf16) {
+    ig = sigm_of<true>(pre[0] + in.add[0]); fg = sigm_of<true>(pre[1] + in.add[1]);
+    gg = tanh_of<true>(pre[2] + in.add[2]); og = sigm_of<true>(pre[3] + in.add[3]);
+  } else {
+    ig = sigm_of<false>(pre[0] + in.add[0]); fg = sigm_of<false>(pre[1] + in.add[1]);
+    gg = tanh_of<false>(pre[2] + in.add[2]); og = sigm_of<false>(pre[3] + in.add[3]);
+  }
   const float cn = fg * in.cp + ig * gg;
-  const float hn = og * tanhf(cn);
+  tcn = is_bf16 ? tanh_of<true>(cn) : tanh_of<false>(cn);
+  const float hn = og * tcn;
   const bool valid = in.mask > 0.f;
   d.cnext[(size_t)b * Hh + u] = valid ? cn : in.cp;
   float* gs = d.gsave + (size_t)b * 4 * Hh + u;
@@ -486,7 +493,7 @@ __global__ __launch_bounds__(256) void step2d_kernel(StepGemmArgs args, int Bp, 
 #pragma unroll
       for (int i = 0; i < 4; ++i)
         if (n + i < g.N) {
-          const float hv = tanhf(r[i]);
+          const float hv = tanh_of<sizeof(T) == 2>(r[i]);
           ((T*)g.outT)[(size_t)b * g.ldo + n + i] = from_f<T>(hv);
           if (g.outD) ((T*)g.outD)[(size_t)b * g.ldod + n + i] = from_f<T>(hv * drop_factor(g.drop, b, n + i));
         }
@@ -531,7 +538,7 @@ __global__ __launch_bounds__(64 * KS) void step_tanh_kernel(StepGemm g, int Bp, 
 #pragma unroll
   for (int i = 0; i < 4; ++i)
     if (n + i < g.N) {
-      const float hv = tanhf(r[i]);
+      const float hv = tanh_of<sizeof(T) == 2>(r[i]);
       const float hd = g.outD ? hv * drop_factor(g.drop, b, n + i) : hv;
       ((T*)g.outT)[(size_t)b * g.ldo + n + i] = from_f<T>(hv);
       if (g.outD) ((T*)g.outD)[(size_t)b * g.ldod + n + i] = from_f<T>(hd);
@@ -690,7 +697,7 @@ __device__ __forceinline__ void cell_bwd_finish(const LstmBwdPoint& p, int b, in
   for (int e = 0; e < 4; ++e) {
     const float ig = (&in.i.x)[e], fg = (&in.f.x)[e], gg = (&in.g.x)[e], og = (&in.o.x)[e];
     const float cp = (&in.cp.x)[e], cn = (&in.cn.x)[e];
-    const float tc = tanhf(cn);
+    const float tc = tanh_of<sizeof(T) == 2>(cn);
     const float dh = dh_state[e] + ((&in.dy.x)[e] + dy_x[e]) * drop_factor(p.drop_dy, b, p.dy_col + u + e);
     const float dog = dh * tc;
     const float dc = (&in.dc.x)[e] + dh * og * (1.f - tc * tc);
@@ -1148,7 +1155,8 @@ __global__ __launch_bounds__(256) void tanh_planes_kernel(Planes p, T* __restric
   if (i4 >= Bp * nq) return;
   const int b = i4 / nq, n = (i4 - b * nq) * 4;
   const float4 v = planes_get4(p, b, n);
-  const float o[4] = {tanhf(v.x), tanhf(v.y), tanhf(v.z), tanhf(v.w)};
+  constexpr bool FAST = sizeof(T) == 2;
+  const float o[4] = {tanh_of<FAST>(v.x), tanh_of<FAST>(v.y), tanh_of<FAST>(v.z), tanh_of<FAST>(v.w)};
   store4<T>(out + (size_t)b * ldo + n, o);
   if (outD) {
     const float od[4] = {o[0] * drop_factor(drop, b, n), o[1] * drop_factor(drop, b, n + 1), o[2] * drop_factor(drop, b, n + 2),
