@@ -88,6 +88,12 @@ __device__ __forceinline__ void mma32(v16f& acc, const Frag<float>& a, const Fra
 }
 __device__ __forceinline__ int acc32_row(int lane, int i) { return 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); }
 
+// Keeps a wavefront-uniform value (a kernel argument, a field of an argument structure picked by a uniform index)
+// in a scalar register from this point on.  Without it the compiler fetches such a value where it is first used;
+// in an epilogue behind a barrier that is one scalar load and one wait after the other, each a trip to the
+// scalar cache, on the critical path of a kernel that lasts a few microseconds.
+#define CMT_PIN_UNIFORM(x) asm volatile("" : "+s"(x))
+
 // Gate nonlinearities.  The fp32 path takes the full-accuracy library routines.  On the 16-bit path (FAST) the
 // results are rounded to 8 significant bits or meet operands that were, so the hardware exponential and
 // reciprocal (about 1e-6 relative) are as good, at a tenth of the instructions — the cell epilogues of the

@@ -276,7 +276,13 @@ __global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(LstmFwdArgs args, int
   if (!decode_block(sg, x, kb, z)) return;
   const int nxd = sg.nx / ndir;                    // unit blocks per direction
   const int dir = x / nxd;
-  const LstmFwdDir& d = args.d[dir];
+  LstmFwdDir d = args.d[dir];
+  // what the epilogue needs is fetched now, not behind the barrier
+  CMT_PIN_UNIFORM(d.cnext); CMT_PIN_UNIFORM(d.gsave); CMT_PIN_UNIFORM(d.hnext); CMT_PIN_UNIFORM(d.ldhn);
+  CMT_PIN_UNIFORM(d.ycat); CMT_PIN_UNIFORM(d.ldy); CMT_PIN_UNIFORM(d.hnext_fm); CMT_PIN_UNIFORM(d.ycat_fm);
+  CMT_PIN_UNIFORM(d.drop.on); CMT_PIN_UNIFORM(d.drop_col0);
+  CMT_PIN_UNIFORM(d.gx); CMT_PIN_UNIFORM(d.ldgx); CMT_PIN_UNIFORM(d.bias); CMT_PIN_UNIFORM(d.cprev); CMT_PIN_UNIFORM(d.mask);
+  CMT_PIN_UNIFORM(d.hprev); CMT_PIN_UNIFORM(d.ldh);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int u0 = (x - dir * nxd) * 4 * RT;
   const int bt0 = z * BT;
@@ -410,10 +416,13 @@ int step_kblocks(int prec, int N, int K, int Bp, int max_kb) { return plan2d(pre
 template <typename T, int U, bool FM = false>
 __global__ __launch_bounds__(256) void step2d_kernel(StepGemmArgs args, int Bp, StepGrid sg, int spb) {
   __shared__ __align__(16) float red[4 * 16 * 64 * 4];
-  const StepGemm& g = args.g[blockIdx.y];
+  StepGemm g = args.g[blockIdx.y];
   int x, kb, z;
   if (!decode_block(sg, x, kb, z)) return;
   if (x * 64 >= g.N) return;                       // instances of one launch may differ in N
+  // what the epilogue needs is fetched now, not behind the barrier
+  CMT_PIN_UNIFORM(g.N); CMT_PIN_UNIFORM(g.mode); CMT_PIN_UNIFORM(g.out); CMT_PIN_UNIFORM(g.ldout); CMT_PIN_UNIFORM(g.plane_stride);
+  CMT_PIN_UNIFORM(g.outT); CMT_PIN_UNIFORM(g.ldo); CMT_PIN_UNIFORM(g.outD); CMT_PIN_UNIFORM(g.ldod); CMT_PIN_UNIFORM(g.drop.on);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int n0 = x * 64;
   const int bt0 = z * STEP_MAXBT;
@@ -523,6 +532,10 @@ __global__ __launch_bounds__(64 * KS) void step_tanh_kernel(StepGemm g, int Bp, 
   if (!decode_block(sg, x, kb, z)) return;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int n0 = x * 16;
+  // what the epilogue needs is fetched now, not behind the barrier
+  CMT_PIN_UNIFORM(g.outT); CMT_PIN_UNIFORM(g.ldo); CMT_PIN_UNIFORM(g.outD); CMT_PIN_UNIFORM(g.ldod); CMT_PIN_UNIFORM(g.outF);
+  CMT_PIN_UNIFORM(g.outF2); CMT_PIN_UNIFORM(g.outF2_nsteps); CMT_PIN_UNIFORM(g.outF2_k0); CMT_PIN_UNIFORM(g.N);
+  CMT_PIN_UNIFORM(g.drop.on);
   const T* wrow[1] = {(const T*)g.W + (size_t)min(n0 + (lane & 15), g.N - 1) * g.ldw};
   if constexpr (FM) {
     const int ns0 = g.K0 >> 5, ns1 = g.K1 >> 5;
@@ -760,7 +773,12 @@ __global__ __launch_bounds__(64 * KS) void step_bwd_fused_kernel(StepBwdArgs arg
   if (n0 >= N) return;                              // instances of one launch may differ in N
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int which = n0 >= g.part[0].ncols ? 1 : 0;
-  const BwdEpi& e = g.part[which];
+  BwdEpi e = g.part[which];
+  // what the epilogue needs is fetched now, not behind the barrier
+  CMT_PIN_UNIFORM(e.kind); CMT_PIN_UNIFORM(e.ncols); CMT_PIN_UNIFORM(e.hh); CMT_PIN_UNIFORM(e.out); CMT_PIN_UNIFORM(e.ldout);
+  CMT_PIN_UNIFORM(e.dpre); CMT_PIN_UNIFORM(e.ldp); CMT_PIN_UNIFORM(e.dpre_fm); CMT_PIN_UNIFORM(e.drop.on);
+  CMT_PIN_UNIFORM(e.cell.dg); CMT_PIN_UNIFORM(e.cell.lddg); CMT_PIN_UNIFORM(e.cell.dg_fm); CMT_PIN_UNIFORM(e.cell.dc);
+  CMT_PIN_UNIFORM(e.cell.dh); CMT_PIN_UNIFORM(e.cell.drop_dy.on); CMT_PIN_UNIFORM(e.cell.dy_col);
   const int c0 = n0 - (which ? g.part[0].ncols : 0);
   const int bt0 = z * BT;
   const int nbt = min(BT, (Bp + 15) / 16 - bt0);
