@@ -148,6 +148,7 @@ struct cmt_handle {
   // rows of all E + 2H columns of its weights and its input [Bp, E + H] in fragment-major form
   char* Wdec0F = nullptr; char* xcatF = nullptr;
   int kb_bwd = 0, kb_wc = 0;            // caps on the k blocks of the backward step GEMMs (0 = default)
+  int wc_whole_k = 1;                   // fused decoder loop: dpre W_c with the whole k range per workgroup (env CMT_WC_WHOLE_K)
   // backward loops that use the whole-k step GEMM with the consumer in its epilogue (env CMT_BWD_FUSED, a bit
   // mask): 1 = decoder (up to 128 sentences: 8.1 against 8.7 ms for the large workload's backward loop; wider
   // batches keep the k-split GEMM + pointwise pair), 2 = upper encoder layers, 4 = bottom encoder layer.  The upper
@@ -863,8 +864,15 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       if (last)
         launch_tanh_bwd(p, h->dHoCE, h->ce_pos + (size_t)j * Bp, no_planes, h->HoBuf + (j + 1) * BP * esz, PH, dpre, PH, Bp, H,
                         drop_spec(h, DROP_SITE_HO, j), st, dpreF);
-      const int kbw = step_kblocks(p, 2 * H, H, Bp, h->kb_wc);
-      {   // [dC_s ; dH_t] = dpre W_c, as planes
+      int kbw = step_kblocks(p, 2 * H, H, Bp, h->kb_wc);
+      if (h->wc_whole_k) {   // [dC_s ; dH_t] = dpre W_c with the whole (short) k range per workgroup: one plane
+        StepBwd g{};
+        g.dg = dpre; g.lddg = PH; g.K = H; g.Wt = h->WcT; g.ldw = H;
+        g.part[0].kind = BWD_EPI_STORE; g.part[0].ncols = 2 * H; g.part[0].out = h->wcp; g.part[0].ldout = 2 * H;
+        g.dg_fm = dpreF; g.Wt_fm = dpreF ? h->WcTF : nullptr; g.wt_tile0 = 0;
+        launch_step_bwd_fused(p, &g, 1, Bp, st);
+        kbw = 1;
+      } else {   // the same as k blocks into planes
         StepGemm g{};
         g.a0 = dpre; g.lda0 = PH; g.K0 = H; g.w0_off = 0; g.K1 = 0;
         g.W = h->WcT; g.ldw = H; g.N = 2 * H; g.mode = 1; g.max_kb = h->kb_wc;
@@ -1212,6 +1220,7 @@ int cmt_create(const cmt_config* cfg, void* params_dev, void* grads_dev, void* w
   {
     const char* k1 = getenv("CMT_KB_BWD"); h->kb_bwd = k1 ? atoi(k1) : 0;
     const char* k2 = getenv("CMT_KB_WC"); h->kb_wc = k2 ? atoi(k2) : 2;
+    const char* kw = getenv("CMT_WC_WHOLE_K"); h->wc_whole_k = kw ? atoi(kw) : 1;
     const char* k3 = getenv("CMT_SIDE_STREAM"); h->use_side = k3 ? atoi(k3) : 1;
     const char* k4 = getenv("CMT_PHASE_TIMING"); h->phase_timing = k4 ? atoi(k4) : 0;
     const char* k5 = getenv("CMT_BWD_FUSED"); h->bwd_fused = k5 ? atoi(k5) : 5;
