@@ -151,10 +151,14 @@ struct cmt_handle {
   int wc_whole_k = 1;                   // fused decoder loop: dpre W_c with the whole k range per workgroup (env CMT_WC_WHOLE_K)
   // backward loops that use the whole-k step GEMM with the consumer in its epilogue (env CMT_BWD_FUSED, a bit
   // mask): 1 = decoder (up to 128 sentences: 8.1 against 8.7 ms for the large workload's backward loop; wider
-  // batches keep the k-split GEMM + pointwise pair), 2 = upper encoder layers, 4 = bottom encoder layer.  The upper
-  // encoder layers keep the pair: their launches carry up to L - 1 layer-steps, and the two forms take the same
-  // time there (1.62 against 1.64 ms at the medium workload).
+  // batches keep the k-split GEMM + pointwise pair), 2 = upper encoder layers, 4 = bottom encoder layer.  Without
+  // the switch (bwd_fused_auto) bits 1 and 4 are set and the upper encoder layers choose per step: their launches
+  // carry up to L - 1 layer-steps, each re-reading all gate gradients from L2 in the fused form, so it wins while
+  // (L - 1) * Bp * H^2 is small (step time fused / pair, ms: 512 x 2 layers 5.07 / 5.22, 512 x 4 6.89 / 7.09,
+  // 1024 x 2 6.30 / 6.45, 512 x 2 at 32 sentences x 120 positions 11.77 / 12.13; 1024 x 4 at 64 sentences
+  // 9.43 / 9.41; at 128 sentences 26.4 / 25.3): fused up to 2^27.
   int bwd_fused = 5;
+  bool bwd_fused_auto = true;
   // phase timing of a step on the caller's stream (measurement aid, env CMT_PHASE_TIMING=1)
   int phase_timing = 0;
   std::vector<hipEvent_t> phase_ev; std::vector<const char*> phase_name; size_t phase_n = 0;
@@ -982,7 +986,8 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   // ---- encoder backwards ------------------------------------------------------------------------------
   // Upper layers: the same wavefront, top layer first.  Per diagonal one pointwise launch (cell
   // backward of every active layer-step) and one step-GEMM launch ([dx; dh_prev] = dgates [W_x; W_h]).
-  if (L > 1 && (h->bwd_fused & 2)) {
+  const bool upper_fused = h->bwd_fused_auto ? (double)(L - 1) * Bp * H * H <= 134217728.0 : (h->bwd_fused & 2) != 0;
+  if (L > 1 && upper_fused) {
     // Fused form: one launch per diagonal.  The step GEMM of (layer l, position t) keeps its dh_prev half in
     // registers and runs the cell backward of (l, t - 1) in its epilogue; its dx half is stored for the layer
     // below (two alternating slots of bwdp per layer, Bp * H floats each).  Layer l at position t - 1 needs the
@@ -1223,7 +1228,7 @@ int cmt_create(const cmt_config* cfg, void* params_dev, void* grads_dev, void* w
     const char* kw = getenv("CMT_WC_WHOLE_K"); h->wc_whole_k = kw ? atoi(kw) : 1;
     const char* k3 = getenv("CMT_SIDE_STREAM"); h->use_side = k3 ? atoi(k3) : 1;
     const char* k4 = getenv("CMT_PHASE_TIMING"); h->phase_timing = k4 ? atoi(k4) : 0;
-    const char* k5 = getenv("CMT_BWD_FUSED"); h->bwd_fused = k5 ? atoi(k5) : 5;
+    const char* k5 = getenv("CMT_BWD_FUSED"); h->bwd_fused = k5 ? atoi(k5) : 5; h->bwd_fused_auto = k5 == nullptr;
   }
   build_table(h->cfg, h->table, h->nparams);
   h->ws_bytes = layout(h, h->ws);
