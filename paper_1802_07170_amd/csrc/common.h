@@ -92,6 +92,12 @@ __device__ __forceinline__ int acc32_row(int lane, int i) { return 8 * (i >> 2) 
 // scalar cache, on the critical path of a kernel that lasts a few microseconds.
 #define CMT_PIN_UNIFORM(x) asm volatile("" : "+s"(x))
 
+// i / d and i % d for a wavefront-uniform divisor: a shift when d is a power of two (the usual case for widths)
+__device__ __forceinline__ void divmod_uniform(int i, int d, int& q, int& r) {
+  if ((d & (d - 1)) == 0) { q = i >> __builtin_ctz(d); r = i & (d - 1); }
+  else { q = i / d; r = i - q * d; }
+}
+
 // Gate nonlinearities.  The fp32 path takes the full-accuracy library routines.  On the 16-bit path (FAST) the
 // results are rounded to 8 significant bits or meet operands that were, so the hardware exponential and
 // reciprocal (about 1e-6 relative) are as good, at a tenth of the instructions — the cell epilogues of the

@@ -32,8 +32,14 @@ __device__ __forceinline__ bool decode_block(const StepGrid& g, int& x, int& kb,
   const int L = blockIdx.x;
   const int xcd = L & 7;
   int r = L >> 3;
-  z = r % g.nz; r /= g.nz;
-  kb = r % g.kb; r /= g.kb;
+  // (an integer division costs some twenty instructions at the head of a kernel that lasts microseconds: the
+  // common counts, one and powers of two, go without)
+  if (g.nz == 1) z = 0;
+  else if ((g.nz & (g.nz - 1)) == 0) { z = r & (g.nz - 1); r >>= __builtin_ctz(g.nz); }
+  else { z = r % g.nz; r /= g.nz; }
+  if (g.kb == 1) kb = 0;
+  else if ((g.kb & (g.kb - 1)) == 0) { kb = r & (g.kb - 1); r >>= __builtin_ctz(g.kb); }
+  else { kb = r % g.kb; r /= g.kb; }
   x = xcd + 8 * r;
   return x < g.nx;
 }
@@ -275,7 +281,7 @@ __global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(LstmFwdArgs args, int
   int x, kb, z;
   if (!decode_block(sg, x, kb, z)) return;
   const int nxd = sg.nx / ndir;                    // unit blocks per direction
-  const int dir = x / nxd;
+  const int dir = ndir == 1 ? 0 : x / nxd;
   LstmFwdDir d = args.d[dir];
   // what the epilogue needs is fetched now, not behind the barrier
   CMT_PIN_UNIFORM(d.cnext); CMT_PIN_UNIFORM(d.gsave); CMT_PIN_UNIFORM(d.hnext); CMT_PIN_UNIFORM(d.ldhn);
@@ -735,7 +741,9 @@ __global__ __launch_bounds__(LSTM_BWD_POINT_THREADS) void lstm_bwd_point_kernel(
   const int idx4 = blockIdx.x * LSTM_BWD_POINT_THREADS + threadIdx.x;
   const int hq = Hh >> 2;
   if (idx4 >= Bp * hq) return;
-  const int b = idx4 / hq, u = (idx4 - b * hq) * 4;
+  int b, u;
+  divmod_uniform(idx4, hq, b, u);
+  u *= 4;
   const float zero[4] = {0.f, 0.f, 0.f, 0.f};
   cell_bwd_finish<T>(p, b, u, Hh, cell_bwd_load(p, b, u, Hh), zero, zero);
 }
@@ -871,7 +879,8 @@ __global__ __launch_bounds__(256) void planes_add_kernel(float* __restrict__ out
                                                          int col0, int Bp, int cols) {
   const int idx = blockIdx.x * 256 + threadIdx.x;
   if (idx >= Bp * cols) return;
-  const int b = idx / cols, c = idx - b * cols;
+  int b, c;
+  divmod_uniform(idx, cols, b, c);
   out[idx] = (base ? base[idx] : 0.f) + planes_get(p, b, col0 + c);
 }
 void launch_planes_add(float* out, const float* base, const Planes& p, int col0, int Bp, int cols, hipStream_t st) {
@@ -1171,7 +1180,9 @@ __global__ __launch_bounds__(256) void tanh_planes_kernel(Planes p, T* __restric
   const int i4 = blockIdx.x * 256 + threadIdx.x;
   const int nq = N >> 2;
   if (i4 >= Bp * nq) return;
-  const int b = i4 / nq, n = (i4 - b * nq) * 4;
+  int b, n;
+  divmod_uniform(i4, nq, b, n);
+  n *= 4;
   const float4 v = planes_get4(p, b, n);
   constexpr bool FAST = sizeof(T) == 2;
   const float o[4] = {tanh_of<FAST>(v.x), tanh_of<FAST>(v.y), tanh_of<FAST>(v.z), tanh_of<FAST>(v.w)};
@@ -1193,7 +1204,9 @@ __global__ __launch_bounds__(64) void tanh_bwd_kernel(const float* __restrict__ 
   const int i4 = blockIdx.x * 64 + threadIdx.x;        // single-wavefront workgroups: spread over all CUs
   const int hq = H >> 2;
   if (i4 >= Bp * hq) return;
-  const int b = i4 / hq, h = (i4 - b * hq) * 4;
+  int b, h;
+  divmod_uniform(i4, hq, b, h);
+  h *= 4;
   const int c = pos ? pos[b] : b;                      // row of sentence b in dce
   const float4 d = c >= 0 ? *reinterpret_cast<const float4*>(dce + (size_t)c * H + h) : make_float4(0.f, 0.f, 0.f, 0.f);
   const float4 f = planes_get4(feed, b, h);
