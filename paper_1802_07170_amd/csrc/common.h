@@ -91,6 +91,15 @@ __device__ __forceinline__ int acc32_row(int lane, int i) { return 8 * (i >> 2) 
 // in an epilogue behind a barrier that is one scalar load and one wait after the other, each a trip to the
 // scalar cache, on the critical path of a kernel that lasts a few microseconds.
 #define CMT_PIN_UNIFORM(x) asm volatile("" : "+s"(x))
+// The same for a pointer to device memory.  The value passes through the global address space, so that what
+// is reached through it afterwards is still known to be global memory (an opaque generic pointer would turn
+// every access into a flat one).
+#define CMT_PIN_UNIFORM_PTR(p)                                                                  \
+  do {                                                                                          \
+    auto cmt_gp_ = (__attribute__((address_space(1))) char*)(p);                                \
+    asm volatile("" : "+s"(cmt_gp_));                                                           \
+    (p) = (decltype(p))(char*)cmt_gp_;                                                          \
+  } while (0)
 
 // i / d and i % d for a wavefront-uniform divisor: a shift when d is a power of two (the usual case for widths)
 __device__ __forceinline__ void divmod_uniform(int i, int d, int& q, int& r) {

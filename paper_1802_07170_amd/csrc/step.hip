@@ -284,11 +284,11 @@ __global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(LstmFwdArgs args, int
   const int dir = ndir == 1 ? 0 : x / nxd;
   LstmFwdDir d = args.d[dir];
   // what the epilogue needs is fetched now, not behind the barrier
-  CMT_PIN_UNIFORM(d.cnext); CMT_PIN_UNIFORM(d.gsave); CMT_PIN_UNIFORM(d.hnext); CMT_PIN_UNIFORM(d.ldhn);
-  CMT_PIN_UNIFORM(d.ycat); CMT_PIN_UNIFORM(d.ldy); CMT_PIN_UNIFORM(d.hnext_fm); CMT_PIN_UNIFORM(d.ycat_fm);
+  CMT_PIN_UNIFORM_PTR(d.cnext); CMT_PIN_UNIFORM_PTR(d.gsave); CMT_PIN_UNIFORM_PTR(d.hnext); CMT_PIN_UNIFORM(d.ldhn);
+  CMT_PIN_UNIFORM_PTR(d.ycat); CMT_PIN_UNIFORM(d.ldy); CMT_PIN_UNIFORM_PTR(d.hnext_fm); CMT_PIN_UNIFORM_PTR(d.ycat_fm);
   CMT_PIN_UNIFORM(d.drop.on); CMT_PIN_UNIFORM(d.drop_col0);
-  CMT_PIN_UNIFORM(d.gx); CMT_PIN_UNIFORM(d.ldgx); CMT_PIN_UNIFORM(d.bias); CMT_PIN_UNIFORM(d.cprev); CMT_PIN_UNIFORM(d.mask);
-  CMT_PIN_UNIFORM(d.hprev); CMT_PIN_UNIFORM(d.ldh);
+  CMT_PIN_UNIFORM_PTR(d.gx); CMT_PIN_UNIFORM(d.ldgx); CMT_PIN_UNIFORM_PTR(d.bias); CMT_PIN_UNIFORM_PTR(d.cprev); CMT_PIN_UNIFORM_PTR(d.mask);
+  CMT_PIN_UNIFORM_PTR(d.hprev); CMT_PIN_UNIFORM(d.ldh);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int u0 = (x - dir * nxd) * 4 * RT;
   const int bt0 = z * BT;
@@ -427,8 +427,8 @@ __global__ __launch_bounds__(256) void step2d_kernel(StepGemmArgs args, int Bp, 
   if (!decode_block(sg, x, kb, z)) return;
   if (x * 64 >= g.N) return;                       // instances of one launch may differ in N
   // what the epilogue needs is fetched now, not behind the barrier
-  CMT_PIN_UNIFORM(g.N); CMT_PIN_UNIFORM(g.mode); CMT_PIN_UNIFORM(g.out); CMT_PIN_UNIFORM(g.ldout); CMT_PIN_UNIFORM(g.plane_stride);
-  CMT_PIN_UNIFORM(g.outT); CMT_PIN_UNIFORM(g.ldo); CMT_PIN_UNIFORM(g.outD); CMT_PIN_UNIFORM(g.ldod); CMT_PIN_UNIFORM(g.drop.on);
+  CMT_PIN_UNIFORM(g.N); CMT_PIN_UNIFORM(g.mode); CMT_PIN_UNIFORM_PTR(g.out); CMT_PIN_UNIFORM(g.ldout); CMT_PIN_UNIFORM(g.plane_stride);
+  CMT_PIN_UNIFORM_PTR(g.outT); CMT_PIN_UNIFORM(g.ldo); CMT_PIN_UNIFORM_PTR(g.outD); CMT_PIN_UNIFORM(g.ldod); CMT_PIN_UNIFORM(g.drop.on);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int n0 = x * 64;
   const int bt0 = z * STEP_MAXBT;
@@ -539,8 +539,8 @@ __global__ __launch_bounds__(64 * KS) void step_tanh_kernel(StepGemm g, int Bp, 
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int n0 = x * 16;
   // what the epilogue needs is fetched now, not behind the barrier
-  CMT_PIN_UNIFORM(g.outT); CMT_PIN_UNIFORM(g.ldo); CMT_PIN_UNIFORM(g.outD); CMT_PIN_UNIFORM(g.ldod); CMT_PIN_UNIFORM(g.outF);
-  CMT_PIN_UNIFORM(g.outF2); CMT_PIN_UNIFORM(g.outF2_nsteps); CMT_PIN_UNIFORM(g.outF2_k0); CMT_PIN_UNIFORM(g.N);
+  CMT_PIN_UNIFORM_PTR(g.outT); CMT_PIN_UNIFORM(g.ldo); CMT_PIN_UNIFORM_PTR(g.outD); CMT_PIN_UNIFORM(g.ldod); CMT_PIN_UNIFORM_PTR(g.outF);
+  CMT_PIN_UNIFORM_PTR(g.outF2); CMT_PIN_UNIFORM(g.outF2_nsteps); CMT_PIN_UNIFORM(g.outF2_k0); CMT_PIN_UNIFORM(g.N);
   CMT_PIN_UNIFORM(g.drop.on);
   const T* wrow[1] = {(const T*)g.W + (size_t)min(n0 + (lane & 15), g.N - 1) * g.ldw};
   if constexpr (FM) {
@@ -700,14 +700,15 @@ __device__ __forceinline__ void cell_bwd_finish(const LstmBwdPoint& p, int b, in
                              in.dhp.w + (in.rec.w + rec_x[3])};
   T* dg = (T*)p.dg + (size_t)b * p.lddg + u;
   const float zero[4] = {0.f, 0.f, 0.f, 0.f};
-  T* dgf[4] = {nullptr, nullptr, nullptr, nullptr};  // the same four values per gate in the fragment-major copy (u % 4 == 0)
-  if (sizeof(T) == 2 && p.dg_fm) {
+  // the same four values per gate go to the fragment-major copy (u % 4 == 0: four consecutive elements there too)
+  const bool fm_copy = sizeof(T) == 2 && p.dg_fm != nullptr;
+  T* const dgf = (T*)p.dg_fm;
+  size_t fo[4];
 #pragma unroll
-    for (int g = 0; g < 4; ++g) dgf[g] = (T*)p.dg_fm + fm_offset(b, g * Hh + u, (4 * Hh) >> 5);
-  }
+  for (int g = 0; g < 4; ++g) fo[g] = fm_offset(b, g * Hh + u, (4 * Hh) >> 5);
   if (!(in.mask > 0.f)) {                          // masked step: state passes through, no gate gradient
 #pragma unroll
-    for (int g = 0; g < 4; ++g) { store4<T>(dg + g * Hh, zero); if (dgf[g]) store4<T>(dgf[g], zero); }
+    for (int g = 0; g < 4; ++g) { store4<T>(dg + g * Hh, zero); if (fm_copy) store4<T>(dgf + fo[g], zero); }
     store4<float>(p.dh + idx, dh_state);           // (an output of a masked step is the constant 0: dy is dropped)
     return;
   }
@@ -727,7 +728,7 @@ __device__ __forceinline__ void cell_bwd_finish(const LstmBwdPoint& p, int b, in
     dcn[e] = dc * fg;
   }
   store4<T>(dg, di); store4<T>(dg + Hh, df); store4<T>(dg + 2 * Hh, dgg); store4<T>(dg + 3 * Hh, dout);
-  if (dgf[0]) { store4<T>(dgf[0], di); store4<T>(dgf[1], df); store4<T>(dgf[2], dgg); store4<T>(dgf[3], dout); }
+  if (fm_copy) { store4<T>(dgf + fo[0], di); store4<T>(dgf + fo[1], df); store4<T>(dgf + fo[2], dgg); store4<T>(dgf + fo[3], dout); }
   store4<float>(p.dc + idx, dcn);
   store4<float>(p.dh + idx, zero);                 // the recurrent part arrives with the next step's GEMM
 }
@@ -783,10 +784,10 @@ __global__ __launch_bounds__(64 * KS) void step_bwd_fused_kernel(StepBwdArgs arg
   const int which = n0 >= g.part[0].ncols ? 1 : 0;
   BwdEpi e = g.part[which];
   // what the epilogue needs is fetched now, not behind the barrier
-  CMT_PIN_UNIFORM(e.kind); CMT_PIN_UNIFORM(e.ncols); CMT_PIN_UNIFORM(e.hh); CMT_PIN_UNIFORM(e.out); CMT_PIN_UNIFORM(e.ldout);
-  CMT_PIN_UNIFORM(e.dpre); CMT_PIN_UNIFORM(e.ldp); CMT_PIN_UNIFORM(e.dpre_fm); CMT_PIN_UNIFORM(e.drop.on);
-  CMT_PIN_UNIFORM(e.cell.dg); CMT_PIN_UNIFORM(e.cell.lddg); CMT_PIN_UNIFORM(e.cell.dg_fm); CMT_PIN_UNIFORM(e.cell.dc);
-  CMT_PIN_UNIFORM(e.cell.dh); CMT_PIN_UNIFORM(e.cell.drop_dy.on); CMT_PIN_UNIFORM(e.cell.dy_col);
+  CMT_PIN_UNIFORM(e.kind); CMT_PIN_UNIFORM(e.ncols); CMT_PIN_UNIFORM(e.hh); CMT_PIN_UNIFORM_PTR(e.out); CMT_PIN_UNIFORM(e.ldout);
+  CMT_PIN_UNIFORM_PTR(e.dpre); CMT_PIN_UNIFORM(e.ldp); CMT_PIN_UNIFORM_PTR(e.dpre_fm); CMT_PIN_UNIFORM(e.drop.on);
+  CMT_PIN_UNIFORM_PTR(e.cell.dg); CMT_PIN_UNIFORM(e.cell.lddg); CMT_PIN_UNIFORM_PTR(e.cell.dg_fm); CMT_PIN_UNIFORM_PTR(e.cell.dc);
+  CMT_PIN_UNIFORM_PTR(e.cell.dh); CMT_PIN_UNIFORM(e.cell.drop_dy.on); CMT_PIN_UNIFORM(e.cell.dy_col);
   const int c0 = n0 - (which ? g.part[0].ncols : 0);
   const int bt0 = z * BT;
   const int nbt = min(BT, (Bp + 15) / 16 - bt0);
