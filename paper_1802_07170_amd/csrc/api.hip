@@ -148,6 +148,13 @@ struct cmt_handle {
   // rows of all E + 2H columns of its weights and its input [Bp, E + H] in fragment-major form
   char* Wdec0F = nullptr; char* xcatF = nullptr;
   int kb_bwd = 0, kb_wc = 0;            // caps on the k blocks of the backward step GEMMs (0 = default)
+  // Workgroup caps of the second stream's GEMMs (weight gradients; dW_o), 0 = none, -1 = by batch width: with all
+  // 256 CUs taken by 256 x 256 tiles for tens of microseconds at a time, the recurrences' kernels on the caller's
+  // stream queue behind them; capped at 128 workgroups the GEMMs take twice as long (still hidden) and leave half the
+  // chip free.  Step time capped / uncapped, ms: medium 9.83 / 9.96, attn 11.03 / 11.12, small (fp32) 10.57 / 10.90;
+  // at 128 sentences (large) 24.82 / 24.73, so the caps apply up to 64 sentences.  Env CMT_SIDE_WGS, CMT_SIDE_WGS_WO.
+  int side_wgs = -1, side_wgs_wo = -1;
+  int side_cap(int v) const { return v >= 0 ? v : (Bp <= 64 ? 128 : 0); }
   int wc_whole_k = 1;                   // fused decoder loop: dpre W_c with the whole k range per workgroup (env CMT_WC_WHOLE_K)
   // backward loops that use the whole-k step GEMM with the consumer in its epilogue (env CMT_BWD_FUSED, a bit
   // mask): 1 = decoder (up to 128 sentences: 8.1 against 8.7 ms for the large workload's backward loop; wider
@@ -437,7 +444,8 @@ void weight_grads(cmt_handle* h, LD& d, int Lsteps, const std::vector<std::pair<
 }
 // launches what weight_grads (and the callers that add W_c / W_a problems) have collected, as one queue of tiles
 void flush_dw_group(cmt_handle* h, hipStream_t st) {
-  launch_gemm_nt_group(h->prec, h->dw_group.data(), (int)h->dw_group.size(), st, h->gsplit2, h->gsplit2_floats);
+  launch_gemm_nt_group(h->prec, h->dw_group.data(), (int)h->dw_group.size(), st, h->gsplit2, h->gsplit2_floats,
+                       st != h->st ? h->side_cap(h->side_wgs) : 0);
   h->dw_group.clear();
 }
 
@@ -843,7 +851,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
                      h->gsplit_floats, lim, 1);                           // dH_o[slab] = dz W_o
       // dW_o (+)= dz^T H_o[slab]; the first slab always holds a row, so W_o's gradient is always written
       launch_gemm_nt(p, dzT, h->ce_pitch, h->HocT + (size_t)m0 * esz, Mt, V, H, Mc, G + h->off_Wo, nullptr, H, nullptr, sl > 0,
-                     sd, nullptr, 0, lim, 2);
+                     sd, nullptr, 0, lim, 2, sd != st ? h->side_cap(h->side_wgs_wo) : 0);
       if (sd != st) {
         done[sl] = h->ev[h->ev_next++ % h->ev.size()];
         (void)hipEventRecord(done[sl], sd);
@@ -1225,6 +1233,8 @@ int cmt_create(const cmt_config* cfg, void* params_dev, void* grads_dev, void* w
   {
     const char* k1 = getenv("CMT_KB_BWD"); h->kb_bwd = k1 ? atoi(k1) : 0;
     const char* k2 = getenv("CMT_KB_WC"); h->kb_wc = k2 ? atoi(k2) : 2;
+    const char* ks1 = getenv("CMT_SIDE_WGS"); h->side_wgs = ks1 ? atoi(ks1) : -1;
+    const char* ks2 = getenv("CMT_SIDE_WGS_WO"); h->side_wgs_wo = ks2 ? atoi(ks2) : -1;
     const char* kw = getenv("CMT_WC_WHOLE_K"); h->wc_whole_k = kw ? atoi(kw) : 1;
     const char* k3 = getenv("CMT_SIDE_STREAM"); h->use_side = k3 ? atoi(k3) : 1;
     const char* k4 = getenv("CMT_PHASE_TIMING"); h->phase_timing = k4 ? atoi(k4) : 0;

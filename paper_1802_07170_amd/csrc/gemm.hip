@@ -38,7 +38,7 @@ __host__ __device__ inline int gemm_dyn_splits(int tiles, int launched) {
 // than one, writes its own fp32 plane Cf + split * plane_stride (summed afterwards, fixed order).
 template <typename T, int WM, int WN, int TA, int TB, int KB>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_kernel(const T* __restrict__ A, int lda, const T* __restrict__ B, int ldb,
-                                                               int M, int N, int K, float* __restrict__ Cf, T* __restrict__ Ct,
+                                                               int M, int N, int K, float* __restrict__ Cf0, T* __restrict__ Ct,
                                                                int ldc, const float* __restrict__ bias, int accumulate, int ntn,
                                                                int kchunk, size_t plane_stride, RowLimit lim, int lim_kind,
                                                                int dyn_split) {
@@ -50,8 +50,12 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_kernel(const T* __restri
     else K = min(K, (e + 63) / 64 * 64);
     if (M <= 0 || K <= 0) return;
   }
+  // a grid smaller than the tile count (a launch that is to leave part of the chip to other streams): the
+  // workgroups walk the tiles, virtual id = blockIdx.x + a multiple of the grid
+  const int ntiles8 = (((M + G::BM - 1) / G::BM * ntn + 7) >> 3) << 3;
+  for (int vb = blockIdx.x; vb < ntiles8; vb += gridDim.x) {
   int m0, n0;
-  if (!gemm_tile_of_block((M + G::BM - 1) / G::BM, ntn, G::BM, G::BN, m0, n0)) return;
+  if (!gemm_tile_of_block((M + G::BM - 1) / G::BM, ntn, G::BM, G::BN, m0, n0, vb)) continue;
   if (dyn_split) {                                 // the number of k splits follows the tiles that exist: one round of workgroups
     const int ns = gemm_dyn_splits((M + G::BM - 1) / G::BM * ntn, gridDim.y);
     if ((int)blockIdx.y >= ns) return;
@@ -62,7 +66,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_kernel(const T* __restri
   if (klen <= 0 && gridDim.y == 1) return;
   v16f acc[TA][TB];
   gemm_mainloop<T, WM, WN, TA, TB, KB>(A + k0, lda, B + k0, ldb, M, N, klen, m0, n0, acc, smem);
-  if (gridDim.y > 1) Cf += blockIdx.y * plane_stride;
+  __syncthreads();                                 // (the next tile of a walking workgroup refills the LDS)
+  float* const Cf = gridDim.y > 1 ? Cf0 + blockIdx.y * plane_stride : Cf0;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int wm = w / WN, wn = w % WN;
 #pragma unroll
@@ -83,6 +88,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_kernel(const T* __restri
         if (Ct) Ct[o] = from_f<T>(v);
       }
     }
+  }
   }
 }
 
@@ -136,21 +142,22 @@ static void launch_planes_sum(const float* planes, int nks, size_t pstride, floa
 template <typename T, int WM, int WN, int TA, int TB>
 static void gemm_go(dim3 grid, hipStream_t st, const void* A, int lda, const void* B, int ldb, int M, int N, int K, float* out,
                     void* Ct, int ldc, const float* bias, int acc, int ntn, int kchunk, size_t pstride, RowLimit lim, int lim_kind,
-                    int dyn_split = 0) {
+                    int dyn_split = 0, int wg_cap = 0) {
+  if (wg_cap > 0 && (int)grid.x > (wg_cap + 7) / 8 * 8) grid.x = (wg_cap + 7) / 8 * 8;
   hipLaunchKernelGGL((gemm_nt_kernel<T, WM, WN, TA, TB, 128>), grid, dim3(64 * WM * WN), 0, st, (const T*)A, lda, (const T*)B, ldb,
                      M, N, K, out, (T*)Ct, ldc, bias, acc, ntn, kchunk, pstride, lim, lim_kind, dyn_split);
 }
 
 void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, int M, int N, int K,
                     float* Cf, void* Ct, int ldc, const float* bias, int accumulate, hipStream_t st,
-                    float* split_scratch, size_t split_scratch_floats, RowLimit lim, int lim_kind) {
+                    float* split_scratch, size_t split_scratch_floats, RowLimit lim, int lim_kind, int wg_cap) {
   if (M <= 0 || N <= 0) return;
   // enough 256 x 256 tiles to fill the chip: the big tile (half the L2 traffic per flop)
   const int ntm_b = (M + GemmBig::BM - 1) / GemmBig::BM, ntn_b = (N + GemmBig::BN - 1) / GemmBig::BN;
   if (ntm_b * ntn_b >= GEMM_BIG_MIN_TILES) {
     const int grid = ((ntm_b * ntn_b + 7) / 8) * 8;
-    if (prec) gemm_go<bf16_t, 4, 4, 2, 2>(dim3(grid, 1), st, A, lda, B, ldb, M, N, K, Cf, Ct, ldc, bias, accumulate, ntn_b, K, 0, lim, lim_kind);
-    else gemm_go<float, 4, 4, 2, 2>(dim3(grid, 1), st, A, lda, B, ldb, M, N, K, Cf, Ct, ldc, bias, accumulate, ntn_b, K, 0, lim, lim_kind);
+    if (prec) gemm_go<bf16_t, 4, 4, 2, 2>(dim3(grid, 1), st, A, lda, B, ldb, M, N, K, Cf, Ct, ldc, bias, accumulate, ntn_b, K, 0, lim, lim_kind, 0, wg_cap);
+    else gemm_go<float, 4, 4, 2, 2>(dim3(grid, 1), st, A, lda, B, ldb, M, N, K, Cf, Ct, ldc, bias, accumulate, ntn_b, K, 0, lim, lim_kind, 0, wg_cap);
     return;
   }
   // a long contraction over few output tiles (dH_o = dz W_o: k = the vocabulary): big tiles with k split into
@@ -166,8 +173,8 @@ void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, in
       const int nks = dyn ? ks : (K + kchunk - 1) / kchunk;
       const size_t pstride = (size_t)M * N;
       const int grid = ((ntm_b * ntn_b + 7) / 8) * 8;
-      if (prec) gemm_go<bf16_t, 4, 4, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, split_scratch, nullptr, N, nullptr, 0, ntn_b, kchunk, pstride, lim, lim_kind, dyn);
-      else gemm_go<float, 4, 4, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, split_scratch, nullptr, N, nullptr, 0, ntn_b, kchunk, pstride, lim, lim_kind, dyn);
+      if (prec) gemm_go<bf16_t, 4, 4, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, split_scratch, nullptr, N, nullptr, 0, ntn_b, kchunk, pstride, lim, lim_kind, dyn, wg_cap);
+      else gemm_go<float, 4, 4, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, split_scratch, nullptr, N, nullptr, 0, ntn_b, kchunk, pstride, lim, lim_kind, dyn, wg_cap);
       launch_planes_sum(split_scratch, nks, pstride, Cf, M, N, ldc, bias, accumulate, lim_kind == 1 ? lim : RowLimit{}, st,
                         dyn ? GemmBig::BM : 0, ntn_b);
       return;
@@ -194,8 +201,8 @@ void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, in
   const int oldc = nks > 1 ? N : ldc;
   const float* obias = nks > 1 ? nullptr : bias;
   const int oacc = nks > 1 ? 0 : accumulate;
-  if (prec) gemm_go<bf16_t, 2, 2, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, out, Ct, oldc, obias, oacc, ntn, kchunk, pstride, lim, lim_kind);
-  else gemm_go<float, 2, 2, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, out, Ct, oldc, obias, oacc, ntn, kchunk, pstride, lim, lim_kind);
+  if (prec) gemm_go<bf16_t, 2, 2, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, out, Ct, oldc, obias, oacc, ntn, kchunk, pstride, lim, lim_kind, 0, wg_cap);
+  else gemm_go<float, 2, 2, 2, 2>(dim3(grid, nks), st, A, lda, B, ldb, M, N, K, out, Ct, oldc, obias, oacc, ntn, kchunk, pstride, lim, lim_kind, 0, wg_cap);
   if (nks > 1) launch_planes_sum(split_scratch, nks, pstride, Cf, M, N, ldc, bias, accumulate, lim_kind == 1 ? lim : RowLimit{}, st);
 }
 
@@ -206,8 +213,13 @@ template <typename T, int WM, int WN, int TA, int TB>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_group_kernel(GemmGroupArgs g) {
   using G = GemmTile<WM, WN, TA, TB, 128>;
   __shared__ __align__(16) char smem[G::SMEM_BYTES];
-  const int id = gemm_tile_index(g.tile_start[g.n]);
-  if (id < 0) return;
+  // the workgroups walk the tile queue: workgroup v takes the tiles of the virtual ids v, v + grid, v + 2 grid, ...
+  // (the grid is a multiple of 8, so a workgroup stays with the tile range of its XCD); a grid as large as the
+  // queue is the plain one-tile-per-workgroup launch
+  const int nt_all = g.tile_start[g.n], per = (nt_all + 7) >> 3;
+  for (int vb = blockIdx.x; (vb >> 3) < per; vb += gridDim.x) {
+  const int id = (vb & 7) * per + (vb >> 3);
+  if (id >= nt_all) continue;
   int q = 0;
   while (q + 1 < g.n && id >= g.tile_start[q + 1]) ++q;   // uniform over the workgroup
   const GemmProb& pr = g.p[q];
@@ -216,6 +228,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_group_kernel(GemmGroupAr
   gemm_tile_from_index(id - g.tile_start[q], (M + G::BM - 1) / G::BM, (N + G::BN - 1) / G::BN, G::BM, G::BN, m0, n0);
   v16f acc[TA][TB];
   gemm_mainloop<T, WM, WN, TA, TB, 128>((const T*)pr.A, pr.lda, (const T*)pr.B, pr.ldb, M, N, pr.K, m0, n0, acc, smem);
+  __syncthreads();                                        // (the next tile of a walking workgroup refills the LDS)
   float* __restrict__ C = pr.C;
   const int accumulate = pr.accumulate;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -235,10 +248,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_group_kernel(GemmGroupAr
       }
     }
   }
+  }
 }
 
 template <typename T, int WM, int WN, int TA, int TB>
-static void gemm_group_go(const GemmProb* probs, int n, hipStream_t st) {
+static void gemm_group_go(const GemmProb* probs, int n, hipStream_t st, int wg_cap) {
   using G = GemmTile<WM, WN, TA, TB, 128>;
   for (int c0 = 0; c0 < n; c0 += GEMM_GROUP_MAX) {
     GemmGroupArgs g{};
@@ -251,18 +265,21 @@ static void gemm_group_go(const GemmProb* probs, int n, hipStream_t st) {
     }
     g.tile_start[g.n] = nt;
     if (nt == 0) continue;
-    hipLaunchKernelGGL((gemm_nt_group_kernel<T, WM, WN, TA, TB>), dim3(((nt + 7) / 8) * 8), dim3(64 * WM * WN), 0, st, g);
+    int grid = ((nt + 7) / 8) * 8;
+    if (wg_cap > 0 && grid > (wg_cap + 7) / 8 * 8) grid = (wg_cap + 7) / 8 * 8;
+    hipLaunchKernelGGL((gemm_nt_group_kernel<T, WM, WN, TA, TB>), dim3(grid), dim3(64 * WM * WN), 0, st, g);
   }
 }
 
-void launch_gemm_nt_group(int prec, const GemmProb* probs, int n, hipStream_t st, float* split_scratch, size_t split_scratch_floats) {
+void launch_gemm_nt_group(int prec, const GemmProb* probs, int n, hipStream_t st, float* split_scratch, size_t split_scratch_floats,
+                          int wg_cap) {
   if (!prec) {
     // fp32 operands: one launch per problem, k split over workgroups where there are few tiles.  These GEMMs are
     // matrix-core bound either way, and the shorter workgroups of the split form leave the CUs sooner to the
     // recurrences' kernels running beside them (small workload: 11.2 against 11.4 ms per step).
     for (int i = 0; i < n; ++i)
       launch_gemm_nt(prec, probs[i].A, probs[i].lda, probs[i].B, probs[i].ldb, probs[i].M, probs[i].N, probs[i].K, probs[i].C, nullptr,
-                     probs[i].ldc, nullptr, probs[i].accumulate, st, split_scratch, split_scratch_floats);
+                     probs[i].ldc, nullptr, probs[i].accumulate, st, split_scratch, split_scratch_floats, RowLimit{}, 0, wg_cap);
     return;
   }
   std::vector<GemmProb> live;
@@ -274,8 +291,8 @@ void launch_gemm_nt_group(int prec, const GemmProb* probs, int n, hipStream_t st
   }
   if (live.empty()) return;
   // enough 256 x 256 tiles over the whole group to fill the chip: the big tile, else the small one
-  if (big >= GEMM_BIG_MIN_TILES) gemm_group_go<bf16_t, 4, 4, 2, 2>(live.data(), (int)live.size(), st);
-  else gemm_group_go<bf16_t, 2, 2, 2, 2>(live.data(), (int)live.size(), st);
+  if (big >= GEMM_BIG_MIN_TILES) gemm_group_go<bf16_t, 4, 4, 2, 2>(live.data(), (int)live.size(), st, wg_cap);
+  else gemm_group_go<bf16_t, 2, 2, 2, 2>(live.data(), (int)live.size(), st, wg_cap);
 }
 
 // Measurement aid: nothing but matrix-core instructions (4 independent 32x32x16 bf16 accumulator chains per

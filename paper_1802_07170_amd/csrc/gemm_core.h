@@ -50,13 +50,16 @@ __device__ __forceinline__ void gemm_tile_from_index(int id, int ntm, int ntn, i
 // workgroup id -> tile number for a launch of at least 8 * ceil(nt / 8) workgroups over nt tiles; -1 for padding ids.
 // `per` comes from the tiles that exist, not from the launched grid: a launch sized for more rows than the
 // device-side count leaves (ids beyond the last tile exit) still spreads its tiles evenly over the XCDs.
-__device__ __forceinline__ int gemm_tile_index(int nt) {
-  const int per = (nt + 7) >> 3, j = blockIdx.x >> 3;
-  const int id = (blockIdx.x & 7) * per + j;
+// `vb` = the (virtual) workgroup id: blockIdx.x, or blockIdx.x + a multiple of the grid for a workgroup that walks
+// several tiles (the grid is a multiple of 8, so it stays with the tile range of its XCD).
+__device__ __forceinline__ int gemm_tile_index(int nt, int vb) {
+  const int per = (nt + 7) >> 3, j = vb >> 3;
+  const int id = (vb & 7) * per + j;
   return (j >= per || id >= nt) ? -1 : id;
 }
-__device__ __forceinline__ bool gemm_tile_of_block(int ntm, int ntn, int bm, int bn, int& m0, int& n0) {
-  const int id = gemm_tile_index(ntm * ntn);
+__device__ __forceinline__ int gemm_tile_index(int nt) { return gemm_tile_index(nt, (int)blockIdx.x); }
+__device__ __forceinline__ bool gemm_tile_of_block(int ntm, int ntn, int bm, int bn, int& m0, int& n0, int vb = -1) {
+  const int id = gemm_tile_index(ntm * ntn, vb < 0 ? (int)blockIdx.x : vb);
   if (id < 0) return false;
   gemm_tile_from_index(id, ntm, ntn, bm, bn, m0, n0);
   return true;

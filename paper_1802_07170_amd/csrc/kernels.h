@@ -22,7 +22,9 @@ struct RowLimit { const int32_t* n = nullptr; int base = 0; };
 void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, int M, int N, int K,
                     float* Cf, void* Ct, int ldc, const float* bias, int accumulate, hipStream_t st,
                     float* split_scratch = nullptr, size_t split_scratch_floats = 0, RowLimit limit = RowLimit{},
-                    int limit_kind = 0);
+                    int limit_kind = 0, int wg_cap = 0);
+// wg_cap > 0: at most that many workgroups (rounded up to a multiple of 8) walk the tiles — for a GEMM on a second
+// stream that is to leave part of the chip to the kernels of the first.
 // Matrix-core issue-rate probe: `blocks` workgroups of 4 wavefronts, each `iters` x 4 bf16 32x32x16 MFMAs on
 // registers; out needs blocks * 256 floats.  Returns the flops of the launch.
 // Several independent C (+)= A * B^T problems (fp32 C, no bias) as one launch: the tiles of all problems form one
@@ -30,7 +32,8 @@ void launch_gemm_nt(int prec, const void* A, int lda, const void* B, int ldb, in
 // them (the weight-gradient GEMMs of the step, the paper's calculateGradient with beta = 1 batched over time).
 struct GemmProb { const void* A; const void* B; float* C; int lda, ldb, ldc, M, N, K, accumulate; };
 // split_scratch: planes for the fp32 path, which launches the problems one by one (see launch_gemm_nt).
-void launch_gemm_nt_group(int prec, const GemmProb* probs, int n, hipStream_t st, float* split_scratch, size_t split_scratch_floats);
+void launch_gemm_nt_group(int prec, const GemmProb* probs, int n, hipStream_t st, float* split_scratch, size_t split_scratch_floats,
+                          int wg_cap = 0);
 double launch_mfma_rate(float* out, int blocks, int iters, hipStream_t st);
 // out[C,R] = in[R,C]^T for T matrices (ldin, ldout in elements).
 void launch_transpose(int prec, const void* in, int ldin, void* out, int ldout, int R, int C, hipStream_t st);

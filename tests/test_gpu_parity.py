@@ -229,6 +229,30 @@ def test_every_form_of_the_backward_loops(prec, forms, B, S, T, H, E, L, monkeyp
 
 
 @pytest.mark.parametrize("prec", [0, 1])
+def test_second_stream_gemms_walking_their_tiles(prec, monkeypatch):
+    """The weight-gradient GEMMs of the second stream may be launched with fewer workgroups than tiles
+    (CMT_SIDE_WGS, CMT_SIDE_WGS_WO: a cap that leaves part of the chip to the recurrences' kernels); each
+    workgroup then walks several tiles.  With the caps at 8 workgroups every such GEMM of this case walks
+    (W_o's gradient alone has 5 x 2 tiles of 128 x 128): the gradients meet the bars against the oracle and
+    are bit-identical to those of the uncapped launches (same tiles, same arithmetic)."""
+    cfg = dict(src_vocab=104, tgt_vocab=520, emb=136, hidden=160, layers=2)
+    rng = np.random.default_rng(4242)
+    params = I.make_params(cfg, seed=31, scale=0.2)
+    batch = ragged_batch(rng, 37, 11, 13, cfg["src_vocab"], cfg["tgt_vocab"])
+    monkeypatch.setenv("CMT_SIDE_WGS", "8")
+    monkeypatch.setenv("CMT_SIDE_WGS_WO", "8")
+    loss, oloss, worst, tr = run_case(cfg, params, batch, prec)
+    g = tr.get_grads().copy()
+    tr.close()
+    monkeypatch.setenv("CMT_SIDE_WGS", "0")
+    monkeypatch.setenv("CMT_SIDE_WGS_WO", "0")
+    loss0, _, _, tr0 = run_case(cfg, params, batch, prec, check_inter=False)
+    g0 = tr0.get_grads().copy()
+    tr0.close()
+    assert loss == loss0 and np.array_equal(g, g0)
+
+
+@pytest.mark.parametrize("prec", [0, 1])
 @pytest.mark.parametrize("slab_rows", [0, 1024])
 def test_batches_of_different_shape_in_turn_on_one_handle(prec, slab_rows, monkeypatch):
     """A large batch, then a small one with far fewer valid target positions, then the large one again,
