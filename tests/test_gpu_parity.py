@@ -198,7 +198,7 @@ def test_vocabulary_long_enough_for_the_k_split_of_the_output_gradient(prec, B, 
 
 
 @pytest.mark.parametrize("prec", [0, 1])
-@pytest.mark.parametrize("forms", ["0", "2", "7", "7 k-split W_c"])
+@pytest.mark.parametrize("forms", ["0", "0 uncapped k blocks", "2", "7", "7 k-split W_c"])
 @pytest.mark.parametrize("B,S,T,H,E,L", [(19, 9, 8, 80, 40, 3), (64, 6, 7, 256, 64, 2), (70, 5, 4, 48, 16, 2), (130, 3, 4, 64, 32, 2)])
 def test_every_form_of_the_backward_loops(prec, forms, B, S, T, H, E, L, monkeypatch):
     """The three backward loops (decoder, upper encoder layers, bottom encoder layer) each exist as a
@@ -206,7 +206,8 @@ def test_every_form_of_the_backward_loops(prec, forms, B, S, T, H, E, L, monkeyp
     library picks per loop and batch width.  CMT_BWD_FUSED (read when the handle is created) forces the
     choice: all three pointwise (0), the upper encoder fused alone (2), all three fused (7, the decoder
     only up to 128 sentences).  Inside the fused decoder loop the product dpre W_c runs with the whole k
-    range per workgroup by default and as k blocks into planes with CMT_WC_WHOLE_K=0.  Every form meets the
+    range per workgroup by default and as k blocks into planes with CMT_WC_WHOLE_K=0; the k-split GEMMs write
+    two planes by default and up to eight with CMT_KB_BWD=0.  Every form meets the
     same bars against the oracle, and the gradients of the forms agree with each other to rounding order
     (same products, different summation order)."""
     cfg = dict(src_vocab=104, tgt_vocab=136, emb=E, hidden=H, layers=L)
@@ -216,11 +217,14 @@ def test_every_form_of_the_backward_loops(prec, forms, B, S, T, H, E, L, monkeyp
     monkeypatch.setenv("CMT_BWD_FUSED", forms.split()[0])
     if "k-split W_c" in forms:
         monkeypatch.setenv("CMT_WC_WHOLE_K", "0")
+    if "uncapped k blocks" in forms:
+        monkeypatch.setenv("CMT_KB_BWD", "0")
     loss, oloss, worst, tr = run_case(cfg, params, batch, prec)
     g = tr.get_grads().copy()
     tr.close()
     monkeypatch.delenv("CMT_BWD_FUSED")
     monkeypatch.delenv("CMT_WC_WHOLE_K", raising=False)
+    monkeypatch.delenv("CMT_KB_BWD", raising=False)
     loss0, _, _, tr0 = run_case(cfg, params, batch, prec, check_inter=False)
     g0 = tr0.get_grads().copy()
     tr0.close()
