@@ -148,6 +148,7 @@ struct cmt_handle {
   // rows of all E + 2H columns of its weights and its input [Bp, E + H] in fragment-major form
   char* Wdec0F = nullptr; char* xcatF = nullptr;
   int kb_bwd = 0, kb_wc = 0;            // caps on the k blocks of the backward step GEMMs (0 = default)
+  int kb_bwd_dec = 0;                   // the same for the decoder's k-split form (one instance per launch)
   // Workgroup caps of the second stream's GEMMs (weight gradients; dW_o), 0 = none, -1 = by batch width: with all
   // 256 CUs taken by 256 x 256 tiles for tens of microseconds at a time, the recurrences' kernels on the caller's
   // stream queue behind them; capped at 128 workgroups the GEMMs take twice as long (still hidden) and leave half the
@@ -864,7 +865,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
 
   phase_mark(h, "decoder backward loop");
   // ---- decoder loop backwards -----------------------------------------------------------------------
-  const int kbd = step_kblocks(p, 2 * H, 4 * H, Bp, h->kb_bwd);       // planes written by a decoder layer's backward GEMM
+  const int kbd = step_kblocks(p, 2 * H, 4 * H, Bp, h->kb_bwd_dec);       // planes written by a decoder layer's backward GEMM
   const size_t pstr = (size_t)Bp * 2 * H;
   const Planes no_planes{nullptr, 0, 0, 0};
   if ((h->bwd_fused & 1) && Bp <= 128) {            // (measured at 128 sentences: 8.1 against 8.7 ms for the k-split form)
@@ -942,7 +943,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
       g.a0 = q.dg; g.lda0 = e.pg; g.K0 = 4 * H; g.w0_off = 0; g.K1 = 0;
       g.W = e.Wt + (size_t)(l == 0 ? E : 0) * 4 * H * esz; g.ldw = 4 * H;
       if (e.fmb) { g.W_fm = e.WtF; g.w_tile0 = (l == 0 ? E : 0) / 16; g.a0_fm = q.dg_fm; }
-      g.N = 2 * H; g.mode = 1; g.max_kb = h->kb_bwd;
+      g.N = 2 * H; g.mode = 1; g.max_kb = h->kb_bwd_dec;
       g.out = e.bwdp; g.ldout = 2 * H; g.plane_stride = pstr;
       launch_step_gemm(p, g, Bp, st);
     }
@@ -1231,10 +1232,12 @@ int cmt_create(const cmt_config* cfg, void* params_dev, void* grads_dev, void* w
   h->params = (float*)params_dev; h->grads = (float*)grads_dev; h->ws = (char*)workspace_dev;
   h->Bpm = round_up(cfg->max_batch, 16);
   {
-    // k blocks of the k-split backward step GEMMs: 2 (medium 9.72 ms per step against 9.75 with 4, 9.86 with 8 and
-    // 9.96 with 1; large 24.59 / 24.69 / 24.71 / 24.74): fewer planes for the consumer to sum weigh more than the
-    // extra workgroups, now that the operands stream fragment-major
+    // k blocks of the encoder's k-split backward step GEMMs (up to L - 1 instances per launch): 2 (medium 9.72 ms
+    // per step against 9.75 with 4, 9.86 with 8 and 9.96 with 1; large 24.59 / 24.69 / 24.71 / 24.74): fewer planes
+    // for the consumer to sum weigh more than the extra workgroups, now that the operands stream fragment-major.
+    // The decoder's k-split form launches one instance at a time and keeps as many blocks as fill the chip.
     const char* k1 = getenv("CMT_KB_BWD"); h->kb_bwd = k1 ? atoi(k1) : 2;
+    const char* k1d = getenv("CMT_KB_BWD_DEC"); h->kb_bwd_dec = k1d ? atoi(k1d) : 0;
     const char* k2 = getenv("CMT_KB_WC"); h->kb_wc = k2 ? atoi(k2) : 2;
     const char* ks1 = getenv("CMT_SIDE_WGS"); h->side_wgs = ks1 ? atoi(ks1) : -1;
     const char* ks2 = getenv("CMT_SIDE_WGS_WO"); h->side_wgs_wo = ks2 ? atoi(ks2) : -1;
@@ -1662,14 +1665,14 @@ int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_la
     launch = [=](int i) { dec_lstm_fwd(h, L > 1 ? 1 + i % (L - 1) : 0, j); };
   } else if (s == "step2d_bwd_dec") {
     // [dx; dh_prev] = dgates [W_x; W_h] of a decoder layer, written as planes
-    const int kb = step_kblocks(p, 2 * H, 4 * H, Bp, h->kb_bwd);
+    const int kb = step_kblocks(p, 2 * H, 4 * H, Bp, h->kb_bwd_dec);
     *algo_work = 4.0 * H * 2 * H * esz + (double)Bp * 4 * H * esz + (double)kb * Bp * 2 * H * 4;
     launch = [=](int i) {
       LD& e = h->dec[L > 1 ? 1 + i % (L - 1) : 0];
       StepGemm g{};
       g.a0 = e.dG + (size_t)j * Bp * e.pg * es; g.lda0 = e.pg; g.K0 = 4 * H; g.w0_off = 0; g.K1 = 0;
       g.W = e.Wt + (size_t)(&e == &h->dec[0] ? E : 0) * 4 * H * es; g.ldw = 4 * H;
-      g.N = 2 * H; g.mode = 1; g.max_kb = h->kb_bwd;
+      g.N = 2 * H; g.mode = 1; g.max_kb = h->kb_bwd_dec;
       g.out = e.bwdp; g.ldout = 2 * H; g.plane_stride = (size_t)Bp * 2 * H;
       if (e.fmb) { g.W_fm = e.WtF; g.w_tile0 = (&e == &h->dec[0] ? E : 0) / 16; g.a0_fm = e.dGF + (size_t)j * Bp * 4 * H * es; }
       launch_step_gemm(p, g, Bp, st);
