@@ -863,10 +863,15 @@ void launch_step_bwd_fused(int prec, const StepBwd* gs, int n, int Bp, hipStream
       }
     }
     const int nsteps = (Kmax / 8 + 3) / 4;
+    const int wgs = ((Nmax + 15) / 16) * (((Bp + 15) / 16 + 1) / 2) * m;
     // 16 columns x 32 sentences per workgroup.  (64 sentences per workgroup halves the number of workgroups
     // and was measured at twice the time: 25.6 against 12.9 us for 64 sentences, 26.2 against 21.8 us for 128.)
 #define GO(TT, KS, UU) step_bwd_go<TT, KS, UU, 2>(a, m, Nmax, Bp, st, fm)
     if (prec) {
+      // a long k range is split over 16 wavefronts while the launch is one round of workgroups; with more than 256
+      // workgroups (128 sentences) 8 wavefronts, so that two workgroups share a CU instead of taking turns
+      // (decoder layer at 128 sentences: 12.4 against 14.5 us; at 64 sentences: 10.2 against 9.1 us)
+      if (nsteps > 64 && wgs > 256) GO(bf16_t, 8, 2); else
       if (nsteps > 64) GO(bf16_t, 16, 4); else if (nsteps > 32) GO(bf16_t, 8, 4); else if (nsteps > 16) GO(bf16_t, 8, 2); else GO(bf16_t, 4, 2);
     } else {
       if (nsteps > 32) GO(float, 16, 2); else if (nsteps > 16) GO(float, 8, 2); else GO(float, 4, 2);
