@@ -373,8 +373,8 @@ void launch_lstm_fwd(int prec, const LstmFwdDir* dirs, int ndir, int Bp, int Hh,
   if (prec) {
     if (how == 6) {
       if (nsteps > 32) lstm_fwd_go<bf16_t, 2, 8, 4, 2>(a, Bp, Hh, ndir, st, fm);
-      else lstm_fwd_go<bf16_t, 2, 8, 2, 2>(a, Bp, Hh, ndir, st, fm);   // (also for <= 16 k steps: 0.44 against 0.46 ms for
-                                                                      //  the bottom encoder layer's 50 launches with 4 wavefronts)
+      else if (nsteps > 16) lstm_fwd_go<bf16_t, 2, 8, 2, 2>(a, Bp, Hh, ndir, st, fm);
+      else lstm_fwd_go<bf16_t, 2, 4, 2, 2>(a, Bp, Hh, ndir, st, fm);
     }
     else if (how == 4) lstm_fwd_go<bf16_t, 4, 8, 4>(a, Bp, Hh, ndir, st, fm);
     else if (how == 2) lstm_fwd_go<bf16_t, 2, 8, 4>(a, Bp, Hh, ndir, st, fm);
