@@ -1461,8 +1461,9 @@ int cmt_greedy_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* 
   launch_fill_T(p, h->xcat, (size_t)Bp * h->ldxcat, st);              // H_o^{<-1>} = 0
   const bool fm0 = h->xcatF && h->dec[0].fm;                          // bottom layer on fragment-major operands
   if (fm0) launch_fill_T(p, h->xcatF, (size_t)Bp * (E + H), st);
+  // the first step's input embedding; every later one is written by the arg-max kernel of the step before
+  launch_dec_embed(p, h->Pw(h->off_Etgt), E, h->dec_tok, B, Bp, h->xcat, h->ldxcat, st, fm0 ? h->xcatF : nullptr, (E + H) >> 5);
   for (int j = 0; j < max_len; ++j) {
-    launch_dec_embed(p, h->Pw(h->off_Etgt), E, h->dec_tok, B, Bp, h->xcat, h->ldxcat, st, fm0 ? h->xcatF : nullptr, (E + H) >> 5);
     for (int l = 0; l < L; ++l) {
       LD& e = h->dec[l];
       LstmFwdDir d;
@@ -1505,7 +1506,7 @@ int cmt_greedy_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* 
     z.out = h->logits; z.ldout = V; z.plane_stride = (size_t)Bp * V;
     launch_step_gemm(p, z, Bp, st);
     launch_dec_argmax(h->logits, V, h->params + h->off_Bo, V, B, j, max_len, eos_id, h->dec_tok, h->dec_done, out_ids_dev,
-                      out_len_dev, st);
+                      out_len_dev, st, p, h->Pw(h->off_Etgt), E, h->xcat, h->ldxcat, fm0 ? h->xcatF : nullptr, (E + H) >> 5);
   }
   h->drop_p = keep_p;
   (void)hipMemcpyAsync(h->h_flags, h->flags, sizeof(int), hipMemcpyDeviceToHost, st);

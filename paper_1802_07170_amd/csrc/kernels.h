@@ -285,8 +285,11 @@ void launch_dec_embed(int prec, const void* table, int E, const int32_t* tok, in
                       void* x_fm = nullptr, int nsteps_fm = 0);
 // tok[b] = argmax_v (z[b, v] + bias[v]) (lowest index on ties); unfinished sentences record it at
 // out_ids[b, j] and end on eos or at j = max_len - 1 (done[b] = 1, out_len[b] = j + 1).
+// With `table` (T [V, E]) the kernel also writes the token's embedding row to x[b, 0:E] (T, row pitch ldx) and, for
+// 16-bit types, to the fragment-major x_fm (nsteps_fm k steps): the next step's input, for b < B.
 void launch_dec_argmax(const float* z, int ldz, const float* bias, int V, int B, int j, int max_len, int eos, int32_t* tok,
-                       int32_t* done, int32_t* out_ids, int32_t* out_len, hipStream_t st);
+                       int32_t* done, int32_t* out_ids, int32_t* out_len, hipStream_t st, int prec = 0, const void* table = nullptr,
+                       int E = 0, void* x = nullptr, int ldx = 0, void* x_fm = nullptr, int nsteps_fm = 0);
 // tok = bos, done = 0, out_ids = pad, out_len = 0, mask[b] = (b < B).
 void launch_dec_init(int B, int Bp, int max_len, int bos, int pad, int32_t* tok, int32_t* done, int32_t* out_ids, int32_t* out_len,
                      float* mask, hipStream_t st);

@@ -377,12 +377,17 @@ void launch_dec_embed(int prec, const void* table, int E, const int32_t* tok, in
 // One workgroup per sentence: token = argmax_v (z[b, v] + bias[v]), the lowest index winning a tie.
 // A sentence that has not ended records the token at out_ids[b, j]; it ends when the token is eos or
 // j is the last step.  tok[b] (the next step's input) is always updated.
+// With a table the workgroup then copies the token's embedding row into the next step's input x[b, 0:E] (and its
+// fragment-major copy): the lookup needs no launch of its own in the chain of dependent kernels.
+template <typename T>
 __global__ __launch_bounds__(1024) void dec_argmax_kernel(const float* __restrict__ z, int ldz, const float* __restrict__ bias, int V,
                                                           int j, int max_len, int eos, int32_t* __restrict__ tok,
                                                           int32_t* __restrict__ done, int32_t* __restrict__ out_ids,
-                                                          int32_t* __restrict__ out_len) {
+                                                          int32_t* __restrict__ out_len, const T* __restrict__ table, int E,
+                                                          T* __restrict__ x, int ldx, T* __restrict__ x_fm, int nsteps_fm) {
   __shared__ float smax[16];
   __shared__ int sidx[16];
+  __shared__ int s_tok;
   const int b = blockIdx.x, t = threadIdx.x;
   float best = -INFINITY;
   int bi = 0x7fffffff;
@@ -416,15 +421,31 @@ __global__ __launch_bounds__(1024) void dec_argmax_kernel(const float* __restric
       if (smax[w] > best || (smax[w] == best && sidx[w] < bi)) { best = smax[w]; bi = sidx[w]; }
     if (bi == 0x7fffffff) bi = 0;                        // a row of NaNs: keep the token in range
     tok[b] = bi;
+    s_tok = bi;
     if (!done[b]) {
       out_ids[(size_t)b * max_len + j] = bi;
       if (bi == eos || j == max_len - 1) { done[b] = 1; out_len[b] = j + 1; }
     }
   }
+  if (!table) return;
+  __syncthreads();
+  const T* src = table + (size_t)s_tok * E;
+  constexpr int EPC = 16 / sizeof(T);                     // elements per 16-byte chunk
+  for (int c = t * EPC; c < E; c += 1024 * EPC) {
+    const uint4 v = *reinterpret_cast<const uint4*>(src + c);
+    *reinterpret_cast<uint4*>(x + (size_t)b * ldx + c) = v;
+    if (sizeof(T) == 2 && x_fm) *reinterpret_cast<uint4*>(x_fm + fm_offset(b, c, nsteps_fm)) = v;
+  }
 }
 void launch_dec_argmax(const float* z, int ldz, const float* bias, int V, int B, int j, int max_len, int eos, int32_t* tok,
-                       int32_t* done, int32_t* out_ids, int32_t* out_len, hipStream_t st) {
-  hipLaunchKernelGGL(dec_argmax_kernel, dim3(B), dim3(1024), 0, st, z, ldz, bias, V, j, max_len, eos, tok, done, out_ids, out_len);
+                       int32_t* done, int32_t* out_ids, int32_t* out_len, hipStream_t st, int prec, const void* table, int E, void* x,
+                       int ldx, void* x_fm, int nsteps_fm) {
+  if (prec)
+    hipLaunchKernelGGL(dec_argmax_kernel<bf16_t>, dim3(B), dim3(1024), 0, st, z, ldz, bias, V, j, max_len, eos, tok, done, out_ids, out_len,
+                       (const bf16_t*)table, E, (bf16_t*)x, ldx, (bf16_t*)x_fm, nsteps_fm);
+  else
+    hipLaunchKernelGGL(dec_argmax_kernel<float>, dim3(B), dim3(1024), 0, st, z, ldz, bias, V, j, max_len, eos, tok, done, out_ids, out_len,
+                       (const float*)table, E, (float*)x, ldx, (float*)nullptr, 0);
 }
 
 // start of a decode: tok = bos, done = 0, out_ids = pad, out_len = 0, mask = 1 for b < B else 0
