@@ -1703,7 +1703,8 @@ int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_la
     *algo_work = 2.0 * Bp * S * H * esz;
     const char* Hs = L > 1 ? h->enc[L].Hst + BP * es : h->Y0;
     const int ldHs = L > 1 ? PH : H;
-    const int kbw = step_kblocks(p, 2 * H, H, Bp, h->kb_wc);
+    // (the planes the step's dpre W_c wrote: one in the fused loop's whole-k form)
+    const int kbw = (h->wc_whole_k && (h->bwd_fused & 1) && Bp <= 128) ? 1 : step_kblocks(p, 2 * H, H, Bp, h->kb_wc);
     const size_t pstr = (size_t)Bp * 2 * H;
     launch = [=](int) {
       LstmBwdPoint top = dec_cell(h, L - 1, j);
