@@ -206,8 +206,9 @@ int cmt_debug_fetch(cmt_handle* h, const char* name, float* host_dst, size_t byt
 int cmt_padded_batch(const cmt_handle* h);
 
 /* Measurement aid: launches one kernel of the last step `iters` times back to back on the handle's
- * stream, with the operands that step used (results are rewritten with identical values), timed
- * by HIP events.  Returns the mean microseconds per launch and the algorithmic work of one launch:
+ * stream, with the operands that step used, timed by HIP events (the forward kernels rewrite their results
+ * with identical values; the backward replays update the state gradients they find in place, which changes
+ * those values, not the timing: run a step before using gradients again).  Returns the mean microseconds per launch and the algorithmic work of one launch:
  * bytes (operands read once, outputs written once) for the bandwidth-bound kernels, flops
  * (2 per multiply-add) for the matrix-core-bound ones.  Names:
  *   "lstm_fwd_dec"   fused decoder LSTM step (gate GEMM + cell), cycling over the layers   bytes
