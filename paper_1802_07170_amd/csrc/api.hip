@@ -1501,12 +1501,16 @@ int cmt_greedy_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* 
     launch_step_gemm(p, g, Bp, st);
     StepGemm z{};                                   // logits (without the bias) = H_o W_o^T
     z.a0 = h->xcat + (size_t)E * esz; z.lda0 = h->ldxcat; z.K0 = H; z.w0_off = 0; z.K1 = 0;
-    z.W = h->Pw(h->off_Wo); z.ldw = H; z.N = V; z.mode = 1; z.max_kb = 1;
+    // ... of which only the largest per sentence is wanted: every workgroup of the product keeps the best of its 64
+    // vocabulary entries (bias included), and the arg-max kernel picks among those
+    const int nblk = (V + 63) / 64;
+    float* part_v = h->logits; int32_t* part_i = (int32_t*)(h->logits + (size_t)nblk * Bp);
+    z.W = h->Pw(h->off_Wo); z.ldw = H; z.N = V; z.mode = 2; z.max_kb = 1;
     if (g.outF && h->WoF) { z.W_fm = h->WoF; z.a0_fm = h->HoFeedF; }
-    z.out = h->logits; z.ldout = V; z.plane_stride = (size_t)Bp * V;
+    z.out = part_v; z.best_idx = part_i; z.bias = h->params + h->off_Bo; z.ldout = V; z.plane_stride = (size_t)Bp * V;
     launch_step_gemm(p, z, Bp, st);
-    launch_dec_argmax(h->logits, V, h->params + h->off_Bo, V, B, j, max_len, eos_id, h->dec_tok, h->dec_done, out_ids_dev,
-                      out_len_dev, st, p, h->Pw(h->off_Etgt), E, h->xcat, h->ldxcat, fm0 ? h->xcatF : nullptr, (E + H) >> 5);
+    launch_dec_argmax(part_v, Bp, nullptr, nblk, B, j, max_len, eos_id, h->dec_tok, h->dec_done, out_ids_dev,
+                      out_len_dev, st, p, h->Pw(h->off_Etgt), E, h->xcat, h->ldxcat, fm0 ? h->xcatF : nullptr, (E + H) >> 5, part_i);
   }
   h->drop_p = keep_p;
   (void)hipMemcpyAsync(h->h_flags, h->flags, sizeof(int), hipMemcpyDeviceToHost, st);

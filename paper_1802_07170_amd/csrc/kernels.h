@@ -144,6 +144,9 @@ struct StepGemm {
                        //    `out` is scratch for the planes when the k range is split
                        // 1: partial planes out[kb][b][n] (fp32, row pitch ldout, plane pitch plane_stride),
                        //    kb < step_kblocks(prec, K0 + K1); the consumer sums them
+                       // 2: (max_kb = 1) per block of 64 output columns and sentence the largest value of
+                       //    sum + bias[n] and its column, the lower column on equal values:
+                       //    out[blk * Bp + b] and best_idx[blk * Bp + b], blk < ceil(N / 64); nothing else is stored
   void* outT; int ldo;
   void* outD = nullptr; int ldod = 0;  // mode 0: optional copy of outT after dropout `drop`
   DropSpec drop{};
@@ -156,6 +159,7 @@ struct StepGemm {
   int outF2_nsteps = 0, outF2_k0 = 0;  //   matrix of outF2_nsteps k steps (k0 a multiple of 32)
   float* out; int ldout; size_t plane_stride;
   int max_kb;          // cap on the number of k blocks (planes); 0 = default (8)
+  const float* bias = nullptr; int32_t* best_idx = nullptr;   // mode 2
 };
 void launch_step_gemm(int prec, const StepGemm& g, int Bp, hipStream_t st);
 // n <= STEP_MAX_INST instances in one launch (mode 1 only): same K0 + K1 and max_kb, N may differ; the
@@ -287,9 +291,12 @@ void launch_dec_embed(int prec, const void* table, int E, const int32_t* tok, in
 // out_ids[b, j] and end on eos or at j = max_len - 1 (done[b] = 1, out_len[b] = j + 1).
 // With `table` (T [V, E]) the kernel also writes the token's embedding row to x[b, 0:E] (T, row pitch ldx) and, for
 // 16-bit types, to the fragment-major x_fm (nsteps_fm k steps): the next step's input, for b < B.
+// With part_idx the candidates are not logits but per-sentence partial results: z[k * ldz + b] and part_idx[k * ldz + b],
+// k < V, hold a value (bias included) and its token; `bias` is not used.
 void launch_dec_argmax(const float* z, int ldz, const float* bias, int V, int B, int j, int max_len, int eos, int32_t* tok,
                        int32_t* done, int32_t* out_ids, int32_t* out_len, hipStream_t st, int prec = 0, const void* table = nullptr,
-                       int E = 0, void* x = nullptr, int ldx = 0, void* x_fm = nullptr, int nsteps_fm = 0);
+                       int E = 0, void* x = nullptr, int ldx = 0, void* x_fm = nullptr, int nsteps_fm = 0,
+                       const int32_t* part_idx = nullptr);
 // tok = bos, done = 0, out_ids = pad, out_len = 0, mask[b] = (b < B).
 void launch_dec_init(int B, int Bp, int max_len, int bos, int pad, int32_t* tok, int32_t* done, int32_t* out_ids, int32_t* out_len,
                      float* mask, hipStream_t st);

@@ -384,7 +384,8 @@ __global__ __launch_bounds__(1024) void dec_argmax_kernel(const float* __restric
                                                           int j, int max_len, int eos, int32_t* __restrict__ tok,
                                                           int32_t* __restrict__ done, int32_t* __restrict__ out_ids,
                                                           int32_t* __restrict__ out_len, const T* __restrict__ table, int E,
-                                                          T* __restrict__ x, int ldx, T* __restrict__ x_fm, int nsteps_fm) {
+                                                          T* __restrict__ x, int ldx, T* __restrict__ x_fm, int nsteps_fm,
+                                                          const int32_t* __restrict__ part_idx) {
   __shared__ float smax[16];
   __shared__ int sidx[16];
   __shared__ int s_tok;
@@ -393,6 +394,13 @@ __global__ __launch_bounds__(1024) void dec_argmax_kernel(const float* __restric
   int bi = 0x7fffffff;
   // equal values: the lowest index wins, whatever order the candidates come in
   const float* zr = z + (size_t)b * ldz;
+  if (part_idx) {                                        // partial results [k][sentence]: value and token
+    for (int k = t; k < V; k += 1024) {
+      const float xv = z[(size_t)k * ldz + b];
+      const int xi = part_idx[(size_t)k * ldz + b];
+      if (xv > best || (xv == best && xi < bi)) { best = xv; bi = xi; }
+    }
+  } else
   if ((V & 3) == 0 && (ldz & 3) == 0 && (((size_t)z | (size_t)bias) & 15) == 0) {
     for (int v = 4 * t; v < V; v += 4096) {              // 16-byte loads: four candidates per thread and pass
       const float4 a = *reinterpret_cast<const float4*>(zr + v);
@@ -439,13 +447,13 @@ __global__ __launch_bounds__(1024) void dec_argmax_kernel(const float* __restric
 }
 void launch_dec_argmax(const float* z, int ldz, const float* bias, int V, int B, int j, int max_len, int eos, int32_t* tok,
                        int32_t* done, int32_t* out_ids, int32_t* out_len, hipStream_t st, int prec, const void* table, int E, void* x,
-                       int ldx, void* x_fm, int nsteps_fm) {
+                       int ldx, void* x_fm, int nsteps_fm, const int32_t* part_idx) {
   if (prec)
     hipLaunchKernelGGL(dec_argmax_kernel<bf16_t>, dim3(B), dim3(1024), 0, st, z, ldz, bias, V, j, max_len, eos, tok, done, out_ids, out_len,
-                       (const bf16_t*)table, E, (bf16_t*)x, ldx, (bf16_t*)x_fm, nsteps_fm);
+                       (const bf16_t*)table, E, (bf16_t*)x, ldx, (bf16_t*)x_fm, nsteps_fm, part_idx);
   else
     hipLaunchKernelGGL(dec_argmax_kernel<float>, dim3(B), dim3(1024), 0, st, z, ldz, bias, V, j, max_len, eos, tok, done, out_ids, out_len,
-                       (const float*)table, E, (float*)x, ldx, (float*)nullptr, 0);
+                       (const float*)table, E, (float*)x, ldx, (float*)nullptr, 0, part_idx);
 }
 
 // start of a decode: tok = bos, done = 0, out_ids = pad, out_len = 0, mask = 1 for b < B else 0

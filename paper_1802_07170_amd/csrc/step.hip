@@ -427,6 +427,7 @@ __global__ __launch_bounds__(256) void step2d_kernel(StepGemmArgs args, int Bp, 
   if (!decode_block(sg, x, kb, z)) return;
   if (x * 64 >= g.N) return;                       // instances of one launch may differ in N
   // what the epilogue needs is fetched now, not behind the barrier
+  CMT_PIN_UNIFORM_PTR(g.bias); CMT_PIN_UNIFORM_PTR(g.best_idx);
   CMT_PIN_UNIFORM(g.N); CMT_PIN_UNIFORM(g.mode); CMT_PIN_UNIFORM_PTR(g.out); CMT_PIN_UNIFORM(g.ldout); CMT_PIN_UNIFORM(g.plane_stride);
   CMT_PIN_UNIFORM_PTR(g.outT); CMT_PIN_UNIFORM(g.ldo); CMT_PIN_UNIFORM_PTR(g.outD); CMT_PIN_UNIFORM(g.ldod); CMT_PIN_UNIFORM(g.drop.on);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -496,6 +497,45 @@ __global__ __launch_bounds__(256) void step2d_kernel(StepGemmArgs args, int Bp, 
   }
   // wavefront w finishes row tile w for all batch tiles
   const int n = n0 + 16 * w + 4 * (lane >> 4);
+  if (g.mode == 2) {
+    // arg-max over this workgroup's 64 columns per sentence: a lane's 4 columns, then the 4 lane groups of the
+    // wavefront's row tile, then the 4 wavefronts through LDS ((value, column) order: larger value, lower column)
+    __shared__ float sbv[4][16 * STEP_MAXBT];
+    __shared__ int sbi[4][16 * STEP_MAXBT];
+#pragma unroll
+    for (int bt = 0; bt < STEP_MAXBT; ++bt) {
+      float bv = -INFINITY; int bi = 0x7fffffff;
+      if (bt < nbt) {
+        v4f r = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) r += *reinterpret_cast<const v4f*>(red + (((k * 4 + w) * STEP_MAXBT + bt) * 64 + lane) * 4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (n + i < g.N) {
+            const float v = r[i] + g.bias[n + i];
+            if (v > bv) { bv = v; bi = n + i; }              // ascending columns: the first of equal values stays
+          }
+      }
+#pragma unroll
+      for (int o = 16; o <= 32; o <<= 1) {
+        const float ov = __shfl_xor(bv, o, 64);
+        const int oi = __shfl_xor(bi, o, 64);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+      }
+      if (lane < 16) { sbv[w][16 * bt + lane] = bv; sbi[w][16 * bt + lane] = bi; }
+    }
+    __syncthreads();
+    const int t = threadIdx.x;
+    if (t < 16 * STEP_MAXBT) {
+      const int b = 16 * bt0 + t;
+      float bv = sbv[0][t]; int bi = sbi[0][t];
+#pragma unroll
+      for (int k = 1; k < 4; ++k)
+        if (sbv[k][t] > bv || (sbv[k][t] == bv && sbi[k][t] < bi)) { bv = sbv[k][t]; bi = sbi[k][t]; }
+      if (b < Bp) { g.out[(size_t)x * Bp + b] = bv; g.best_idx[(size_t)x * Bp + b] = bi; }
+    }
+    return;
+  }
 #pragma unroll
   for (int bt = 0; bt < STEP_MAXBT; ++bt) {
     if (bt >= nbt) break;
