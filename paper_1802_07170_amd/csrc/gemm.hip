@@ -34,28 +34,15 @@ __host__ __device__ inline int gemm_dyn_splits(int tiles, int launched) {
   return ns < 1 ? 1 : (ns > launched ? launched : ns);
 }
 
-// blockIdx.y = k split index: each split contracts kchunk elements of k and, when there is more
-// than one, writes its own fp32 plane Cf + split * plane_stride (summed afterwards, fixed order).
+// One output tile (the one of virtual workgroup id vb) of C (+)= A B^T (+ bias): main loop and store.
 template <typename T, int WM, int WN, int TA, int TB, int KB>
-__global__ __launch_bounds__(64 * WM * WN) void gemm_nt_kernel(const T* __restrict__ A, int lda, const T* __restrict__ B, int ldb,
-                                                               int M, int N, int K, float* __restrict__ Cf0, T* __restrict__ Ct,
-                                                               int ldc, const float* __restrict__ bias, int accumulate, int ntn,
-                                                               int kchunk, size_t plane_stride, RowLimit lim, int lim_kind,
-                                                               int dyn_split) {
+__device__ __forceinline__ void gemm_nt_tile(const T* __restrict__ A, int lda, const T* __restrict__ B, int ldb, int M, int N, int K,
+                                             float* __restrict__ Cf0, T* __restrict__ Ct, int ldc, const float* __restrict__ bias,
+                                             int accumulate, int ntn, int kchunk, size_t plane_stride, int dyn_split, int vb,
+                                             char* smem) {
   using G = GemmTile<WM, WN, TA, TB, KB>;
-  __shared__ __align__(16) char smem[G::SMEM_BYTES];
-  if (lim.n) {                                     // a bound that only the device knows (uniform over the grid)
-    const int e = max(*lim.n - lim.base, 0);
-    if (lim_kind == 1) M = min(M, e);
-    else K = min(K, (e + 63) / 64 * 64);
-    if (M <= 0 || K <= 0) return;
-  }
-  // a grid smaller than the tile count (a launch that is to leave part of the chip to other streams): the
-  // workgroups walk the tiles, virtual id = blockIdx.x + a multiple of the grid
-  const int ntiles8 = (((M + G::BM - 1) / G::BM * ntn + 7) >> 3) << 3;
-  for (int vb = blockIdx.x; vb < ntiles8; vb += gridDim.x) {
   int m0, n0;
-  if (!gemm_tile_of_block((M + G::BM - 1) / G::BM, ntn, G::BM, G::BN, m0, n0, vb)) continue;
+  if (!gemm_tile_of_block((M + G::BM - 1) / G::BM, ntn, G::BM, G::BN, m0, n0, vb)) return;
   if (dyn_split) {                                 // the number of k splits follows the tiles that exist: one round of workgroups
     const int ns = gemm_dyn_splits((M + G::BM - 1) / G::BM * ntn, gridDim.y);
     if ((int)blockIdx.y >= ns) return;
@@ -66,7 +53,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_kernel(const T* __restri
   if (klen <= 0 && gridDim.y == 1) return;
   v16f acc[TA][TB];
   gemm_mainloop<T, WM, WN, TA, TB, KB>(A + k0, lda, B + k0, ldb, M, N, klen, m0, n0, acc, smem);
-  __syncthreads();                                 // (the next tile of a walking workgroup refills the LDS)
   float* const Cf = gridDim.y > 1 ? Cf0 + blockIdx.y * plane_stride : Cf0;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int wm = w / WN, wn = w % WN;
@@ -89,6 +75,37 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_nt_kernel(const T* __restri
       }
     }
   }
+}
+
+// blockIdx.y = k split index: each split contracts kchunk elements of k and, when there is more
+// than one, writes its own fp32 plane Cf + split * plane_stride (summed afterwards, fixed order).
+// WALK: the launch has fewer workgroups than tiles (it is to leave part of the chip to other streams) and every
+// workgroup walks the tiles of the virtual ids blockIdx.x, blockIdx.x + grid, ...  It is a variant of its own because
+// the loop costs the one-tile-per-workgroup kernel a spilled register.
+template <typename T, int WM, int WN, int TA, int TB, int KB, bool WALK = false>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_nt_kernel(const T* __restrict__ A, int lda, const T* __restrict__ B, int ldb,
+                                                               int M, int N, int K, float* __restrict__ Cf0, T* __restrict__ Ct,
+                                                               int ldc, const float* __restrict__ bias, int accumulate, int ntn,
+                                                               int kchunk, size_t plane_stride, RowLimit lim, int lim_kind,
+                                                               int dyn_split) {
+  using G = GemmTile<WM, WN, TA, TB, KB>;
+  __shared__ __align__(16) char smem[G::SMEM_BYTES];
+  if (lim.n) {                                     // a bound that only the device knows (uniform over the grid)
+    const int e = max(*lim.n - lim.base, 0);
+    if (lim_kind == 1) M = min(M, e);
+    else K = min(K, (e + 63) / 64 * 64);
+    if (M <= 0 || K <= 0) return;
+  }
+  if constexpr (WALK) {
+    const int ntiles8 = (((M + G::BM - 1) / G::BM * ntn + 7) >> 3) << 3;
+    for (int vb = blockIdx.x; vb < ntiles8; vb += gridDim.x) {
+      gemm_nt_tile<T, WM, WN, TA, TB, KB>(A, lda, B, ldb, M, N, K, Cf0, Ct, ldc, bias, accumulate, ntn, kchunk, plane_stride, dyn_split,
+                                          vb, smem);
+      __syncthreads();                             // (the next tile refills the LDS)
+    }
+  } else {
+    gemm_nt_tile<T, WM, WN, TA, TB, KB>(A, lda, B, ldb, M, N, K, Cf0, Ct, ldc, bias, accumulate, ntn, kchunk, plane_stride, dyn_split,
+                                        (int)blockIdx.x, smem);
   }
 }
 
@@ -143,7 +160,12 @@ template <typename T, int WM, int WN, int TA, int TB>
 static void gemm_go(dim3 grid, hipStream_t st, const void* A, int lda, const void* B, int ldb, int M, int N, int K, float* out,
                     void* Ct, int ldc, const float* bias, int acc, int ntn, int kchunk, size_t pstride, RowLimit lim, int lim_kind,
                     int dyn_split = 0, int wg_cap = 0) {
-  if (wg_cap > 0 && (int)grid.x > (wg_cap + 7) / 8 * 8) grid.x = (wg_cap + 7) / 8 * 8;
+  if (wg_cap > 0 && (int)grid.x > (wg_cap + 7) / 8 * 8) {
+    grid.x = (wg_cap + 7) / 8 * 8;
+    hipLaunchKernelGGL((gemm_nt_kernel<T, WM, WN, TA, TB, 128, true>), grid, dim3(64 * WM * WN), 0, st, (const T*)A, lda, (const T*)B, ldb,
+                       M, N, K, out, (T*)Ct, ldc, bias, acc, ntn, kchunk, pstride, lim, lim_kind, dyn_split);
+    return;
+  }
   hipLaunchKernelGGL((gemm_nt_kernel<T, WM, WN, TA, TB, 128>), grid, dim3(64 * WM * WN), 0, st, (const T*)A, lda, (const T*)B, ldb,
                      M, N, K, out, (T*)Ct, ldc, bias, acc, ntn, kchunk, pstride, lim, lim_kind, dyn_split);
 }
