@@ -213,8 +213,12 @@ int cmt_padded_batch(const cmt_handle* h);
  * (2 per multiply-add) for the matrix-core-bound ones.  Names:
  *   "lstm_fwd_dec"   fused decoder LSTM step (gate GEMM + cell), cycling over the layers   bytes
  *   "step2d_bwd_dec" [dx; dh] = dgates [W_x; W_h] of a decoder layer's backward step       bytes
- *   "att_fwd"        attention scores + softmax + context of one decoder step              bytes
- *   "att_bwd"        attention backward of one decoder step (with the top layer's cell)   bytes
+ *   "att_fwd"        attention forward of one decoder step as the step runs it: below 256 sentences the scores
+ *                    (with the H_t half of the attentional layer's product in the same launch), then softmax,
+ *                    mix of the projected source rows and tanh -> H_o; else scores + softmax + context     bytes
+ *   "att_bwd"        attention backward of one decoder step as the step runs it (with the top layer's cell; in
+ *                    the fused loop below 256 sentences also the product dpre W_c, whose launch carries the
+ *                    score gradients)                                                      bytes
  *   "gemm_gx"        time-batched input-side GEMM [T Bp, E] x [E, 4H]                      flops
  *   "gemm_dw"        the decoder's weight-gradient GEMMs (W_c and every layer, k = T Bp), one grouped launch  flops
  *   "ce_fwd"         vocabulary projection + log-sum-exp partials of the first slab of rows flops

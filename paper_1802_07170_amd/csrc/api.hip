@@ -114,6 +114,9 @@ struct cmt_handle {
   // source side
   char* Xs = nullptr; float* mask_s = nullptr; int32_t* tok_s = nullptr; int32_t* len_s = nullptr;
   char* Y0 = nullptr; char* Y0T = nullptr; char* Kmat = nullptr;
+  float* Pmat = nullptr; char* PmatT = nullptr;   // the source states through the context half of W_c, [S * Bp, H] in fp32 and in
+                                        // the operand type (Eq. 7 regrouped)
+  int att_proj = 1;                     // the training step's attention runs on Pmat (see enqueue_step)
   float* dHs = nullptr; char* dK = nullptr; char* dKT = nullptr;
   float* dYa = nullptr; float* dXs = nullptr; char* XsT = nullptr;
   // target side
@@ -299,6 +302,7 @@ size_t layout(cmt_handle* h, char* base) {
   h->Xs = a.take(Ms * E * esz); h->XsT = a.take(Ms * E * esz);
   h->mask_s = (float*)a.take(Ms * 4); h->tok_s = (int32_t*)a.take(Ms * 4); h->len_s = (int32_t*)a.take((size_t)Bp * 4);
   h->Y0 = a.take(Ms * H * esz); h->Y0T = a.take(Ms * H * esz); h->Kmat = a.take(Ms * H * esz);
+  h->Pmat = (float*)a.take(Ms * H * 4); h->PmatT = a.take(Ms * H * esz);
   h->dHs = (float*)a.take(Ms * H * 4); h->dK = a.take(Ms * H * esz); h->dKT = a.take(Ms * H * esz);
   h->dYa = (float*)a.take(Ms * H * 4);
   h->dXs = (float*)a.take(Ms * E * 4);
@@ -577,6 +581,47 @@ void dec_lstm_fwd(cmt_handle* h, int l, int j) {
 // (gather done by the caller): bottom layer (both directions per launch), upper layers as a
 // wavefront, attention keys, and the decoder's initial states.  Returns H_s (top-layer states) and
 // its row pitch.
+// Attention and attentional layer of decoder step j on the projected source rows P_i = W_c1 H_s^i (Eq. 3-7
+// regrouped: W_c [C_s; H_t] = sum_i a_i P_i + W_c2 H_t), two dependent launches: the scores together with the sums
+// W_c2 H_t (both wait for the top layer's state alone), then softmax, mix, tanh -> H_o and its copies.
+void dec_att_fwd_proj(cmt_handle* h, int j, int S, float* scores) {
+  const int p = h->prec, H = h->cfg.hidden, L = h->cfg.layers, Bp = h->Bp, PH = h->PH;
+  const size_t esz = h->esz, BH = (size_t)Bp * H, BP = (size_t)Bp * PH;
+  const char* Ht = h->dec[L - 1].Hst + (j + 1) * BP * esz;
+  StepGemm g{};
+  g.a0 = nullptr; g.lda0 = PH; g.K0 = H; g.w0_off = 0; g.skip0 = 1;
+  g.a1 = Ht; g.lda1 = PH; g.K1 = H; g.w1_off = H;
+  g.W = h->Pw(h->off_Wc); g.ldw = 2 * H; g.N = H; g.mode = 3;
+  g.out = h->wcp; g.ldout = H; g.plane_stride = BH;
+  if (h->HoFeedF) { g.W_fm = h->WcF; g.a1_fm = h->dec[L - 1].HstF + (j + 1) * BH * esz; g.a0_fm = g.a1_fm; }
+  AttOut o{};
+  o.outT = h->HoBuf + (j + 1) * BP * esz; o.ldo = PH;
+  if (h->drop_p > 0.f) { o.outD = h->HoDrop + (j + 1) * BP * esz; o.ldod = PH; o.drop = drop_spec(h, DROP_SITE_HO, j); }
+  if (h->HoFeedF) o.outF = h->HoFeedF + (j + 1) * BH * esz;
+  launch_att_fwd_proj(p, h->Kmat, H, h->PmatT, H, Ht, PH, g, o, h->len_s, S, Bp, H, scores, h->att_a + (size_t)j * Bp * S, h->st);
+}
+// The backward of the same on the projected rows, two dependent launches: the score gradients da_i = dC_s . H_s^i
+// are dpre . P_i (fp32 rows), so they need dpre alone and ride in the launch of [dC_s ; dH_t] = dpre W_c, whose halves
+// go where their readers want them (dC_s to its slot for the deferred gradients, the dH_t half beside it); then
+// the softmax Jacobian, the gradient sent to the top layer's output and that layer's cell backward.
+void dec_att_bwd_proj(cmt_handle* h, int j, int S, bool last) {
+  const int p = h->prec, H = h->cfg.hidden, L = h->cfg.layers, Bp = h->Bp, PH = h->PH;
+  const size_t esz = h->esz, BH = (size_t)Bp * H, BP = (size_t)Bp * PH;
+  char* dpre = h->dPre + j * BP * esz;
+  char* dpreF = h->dPreF ? h->dPreF + j * BH * esz : nullptr;
+  StepBwd g{};
+  g.dg = dpre; g.lddg = PH; g.K = H; g.Wt = h->WcT; g.ldw = H;
+  g.part[0].kind = BWD_EPI_STORE; g.part[0].ncols = H; g.part[0].out = h->dCs + j * BH; g.part[0].ldout = H;
+  g.part[1].kind = BWD_EPI_STORE; g.part[1].ncols = H; g.part[1].out = h->wcp; g.part[1].ldout = H;
+  g.dg_fm = dpreF; g.Wt_fm = dpreF ? h->WcTF : nullptr; g.wt_tile0 = 0;
+  const AttScores sc{h->Pmat, H, dpre, PH, h->len_s, S, H, h->dots, 1};
+  launch_step_bwd_fused(p, &g, 1, Bp, h->st, &sc);
+  LstmBwdPoint top = dec_cell(h, L - 1, j);
+  top.dhrec = Planes{h->dec[L - 1].bwdp, H, last ? 0 : 1, 0};
+  launch_att_bwd_mix(p, h->Kmat, H, Planes{h->wcp, H, 1, 0}, 0, h->att_a + (size_t)j * Bp * S, h->len_s, S, Bp, H, h->dots,
+                     h->att_ds + (size_t)j * Bp * S, h->dHt, h->st, &top);
+}
+
 void enqueue_encoder(cmt_handle* h, int S, const char** Hs_out, int* ldHs_out) {
   const cmt_config& c = h->cfg;
   const int p = h->prec, E = c.emb_dim, H = c.hidden, Hd = H / 2, L = c.layers, Bp = h->Bp;
@@ -739,22 +784,29 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   LD& ef = h->enc[0]; LD& eb = h->enc[1];
   const size_t BHd = (size_t)Bp * Hd;
   // ---- decoder time loop --------------------------------------------------------------------------
+  // The attentional layer's pre-activation W_c [C_s; H_t] (Eq. 7) is sum_i a_i (W_c1 H_s^i) + W_c2 H_t: with the rows
+  // W_c1 H_s^i made once per batch, a step needs no context before its H_o, and the W_c2 H_t sums share a launch
+  // with the scores (both wait for the top layer's state alone) — two dependent launches per step instead of three.
+  // The contexts themselves (the weight gradient of W_c needs them) are made for all steps at once afterwards.
+  const bool proj = h->att_proj && Bp < 256;
   {
     LD& d0 = h->dec[0];
     launch_gemm_nt(p, h->Xt, E, d0.W, E + 2 * H, Mt, 4 * H, E, d0.Gx, nullptr, 4 * H, P + d0.b_off, 0, st);
+    if (proj) launch_gemm_nt(p, Hs, ldHs, h->Pw(h->off_Wc), 2 * H, Ms, H, H, h->Pmat, h->PmatT, H, nullptr, 0, st);
     phase_mark(h, "decoder forward loop");
     for (int j = 0; j < T; ++j) {
       for (int l = 0; l < L; ++l) dec_lstm_fwd(h, l, j);
       const char* Ht = h->dec[L - 1].Hst + (j + 1) * BP * esz;
-      launch_att_fwd(p, h->Kmat, H, Hs, ldHs, Ht, PH, h->len_s, S, Bp, H, h->att_s + (size_t)j * Bp * S,
-                     h->att_a + (size_t)j * Bp * S, h->Cs + j * BP * esz, PH, st, h->CsF ? h->CsF + j * BH * esz : nullptr);
+      if (proj) { dec_att_fwd_proj(h, j, S, h->att_s + (size_t)j * Bp * S); continue; }
       StepGemm g{};
       g.a0 = h->Cs + j * BP * esz; g.lda0 = PH; g.K0 = H; g.w0_off = 0;
       g.a1 = Ht; g.lda1 = PH; g.K1 = H; g.w1_off = H;
       g.W = h->Pw(h->off_Wc); g.ldw = 2 * H; g.N = H; g.mode = 0;
+      g.out = h->wcp; g.ldout = H; g.plane_stride = BH;
+      launch_att_fwd(p, h->Kmat, H, Hs, ldHs, Ht, PH, h->len_s, S, Bp, H, h->att_s + (size_t)j * Bp * S,
+                     h->att_a + (size_t)j * Bp * S, h->Cs + j * BP * esz, PH, st, h->CsF ? h->CsF + j * BH * esz : nullptr);
       g.outT = h->HoBuf + (j + 1) * BP * esz; g.ldo = PH;
       if (drop) { g.outD = h->HoDrop + (j + 1) * BP * esz; g.ldod = PH; g.drop = drop_spec(h, DROP_SITE_HO, j); }
-      g.out = h->wcp; g.ldout = H; g.plane_stride = BH;
       if (h->HoFeedF) {
         g.outF = h->HoFeedF + (j + 1) * BH * esz;
         g.W_fm = h->WcF; g.a0_fm = h->CsF + j * BH * esz; g.a1_fm = h->dec[L - 1].HstF + (j + 1) * BH * esz;
@@ -774,6 +826,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   // kernels stop at the count).
   launch_ce_gather_rows(p, Ho, PH, h->ce_row, h->ce_nvalid, Mt, h->Hoc, PH, H, st);
   if (forward_only) {                              // Eq. 1 and the loss only: logits slab by slab, no gradient
+    if (proj) launch_att_context(p, Hs, ldHs, h->att_a, h->len_s, S, T, Bp, H, h->Cs, PH, st);   // (for the read-back by name)
     int nslab;
     const int rows = ce_slab_plan(h, Mt, &nslab);
     int sl = 0;
@@ -821,6 +874,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
   launch_transpose(p, h->Y0, H, h->Y0T, Ms, Ms, H, sd);
   launch_transpose(p, h->Xs, E, h->XsT, Ms, Ms, E, sd);
   launch_transpose(p, h->Xt, E, h->XtT, Mt, Mt, E, sd);
+  if (proj) launch_att_context(p, Hs, ldHs, h->att_a, h->len_s, S, T, Bp, H, h->Cs, PH, sd);
   launch_transpose(p, h->Cs, PH, h->CsT, Mt, Mt, H, sd);
   {
     // Full slabs of the slab capacity and one remainder (one slab whenever the batch fits), two slab buffer pairs, over the dense rows of
@@ -878,6 +932,14 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
         launch_tanh_bwd(p, h->dHoCE, h->ce_pos + (size_t)j * Bp, no_planes, h->HoBuf + (j + 1) * BP * esz, PH, dpre, PH, Bp, H,
                         drop_spec(h, DROP_SITE_HO, j), st, dpreF);
       int kbw = step_kblocks(p, 2 * H, H, Bp, h->kb_wc);
+      if (proj && h->wc_whole_k) {
+        dec_att_bwd_proj(h, j, S, last);
+        for (int l = L - 1; l >= 0; --l) {
+          const StepBwd gl = dec_bwd_gemm(h, l, j);
+          launch_step_bwd_fused(p, &gl, 1, Bp, st);
+        }
+        continue;
+      }
       if (h->wc_whole_k) {   // [dC_s ; dH_t] = dpre W_c with the whole (short) k range per workgroup: one plane
         StepBwd g{};
         g.dg = dpre; g.lddg = PH; g.K = H; g.Wt = h->WcT; g.ldw = H;
@@ -1243,6 +1305,7 @@ int cmt_create(const cmt_config* cfg, void* params_dev, void* grads_dev, void* w
     const char* ks2 = getenv("CMT_SIDE_WGS_WO"); h->side_wgs_wo = ks2 ? atoi(ks2) : -1;
     const char* kw = getenv("CMT_WC_WHOLE_K"); h->wc_whole_k = kw ? atoi(kw) : 1;
     const char* k3 = getenv("CMT_SIDE_STREAM"); h->use_side = k3 ? atoi(k3) : 1;
+    const char* k3p = getenv("CMT_ATT_PROJ"); h->att_proj = k3p ? atoi(k3p) : 1;
     const char* k4 = getenv("CMT_PHASE_TIMING"); h->phase_timing = k4 ? atoi(k4) : 0;
     const char* k5 = getenv("CMT_BWD_FUSED"); h->bwd_fused = k5 ? atoi(k5) : 5; h->bwd_fused_auto = k5 == nullptr;
   }
@@ -1457,6 +1520,8 @@ int cmt_greedy_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* 
                 nullptr, h->len_s, h->flags, st);
   const char* Hs; int ldHs;
   enqueue_encoder(h, S, &Hs, &ldHs);
+  const bool proj = h->att_proj && Bp < 256;
+  if (proj) launch_gemm_nt(p, Hs, ldHs, h->Pw(h->off_Wc), 2 * H, S * Bp, H, H, nullptr, h->PmatT, H, nullptr, 0, st);
   launch_dec_init(B, Bp, max_len, c.bos_id, c.pad_id, h->dec_tok, h->dec_done, out_ids_dev, out_len_dev, h->dec_mask, st);
   launch_fill_T(p, h->xcat, (size_t)Bp * h->ldxcat, st);              // H_o^{<-1>} = 0
   const bool fm0 = h->xcatF && h->dec[0].fm;                          // bottom layer on fragment-major operands
@@ -1485,8 +1550,6 @@ int cmt_greedy_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* 
       launch_lstm_fwd(p, &d, 1, Bp, H, st);
     }
     const char* Ht = h->dec[L - 1].Hst + (j + 1) * BP * esz;
-    launch_att_fwd(p, h->Kmat, H, Hs, ldHs, Ht, PH, h->len_s, S, Bp, H, h->dots, h->att_a + (size_t)j * Bp * S, h->Cs + j * BP * esz,
-                   PH, st, h->CsF ? h->CsF + j * BH * esz : nullptr);
     StepGemm g{};                                   // H_o = tanh(W_c [C_s; H_t]) straight into the next step's input
     g.a0 = h->Cs + j * BP * esz; g.lda0 = PH; g.K0 = H; g.w0_off = 0;
     g.a1 = Ht; g.lda1 = PH; g.K1 = H; g.w1_off = H;
@@ -1498,7 +1561,16 @@ int cmt_greedy_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* 
       g.outF = h->HoFeedF;                          // H_o of this step, for the logits
       if (fm0) { g.outF2 = h->xcatF; g.outF2_nsteps = (E + H) >> 5; g.outF2_k0 = E; }   // and for the next step's bottom layer
     }
-    launch_step_gemm(p, g, Bp, st);
+    if (proj) {                                     // on the projected source rows, as in the training step
+      AttOut o{};
+      o.outT = g.outT; o.ldo = g.ldo; o.outF = g.outF; o.outF2 = g.outF2; o.outF2_nsteps = g.outF2_nsteps; o.outF2_k0 = g.outF2_k0;
+      g.mode = 3; g.skip0 = 1; g.a0_fm = g.a1_fm;
+      launch_att_fwd_proj(p, h->Kmat, H, h->PmatT, H, Ht, PH, g, o, h->len_s, S, Bp, H, h->dots, h->att_a + (size_t)j * Bp * S, st);
+    } else {
+      launch_att_fwd(p, h->Kmat, H, Hs, ldHs, Ht, PH, h->len_s, S, Bp, H, h->dots, h->att_a + (size_t)j * Bp * S,
+                     h->Cs + j * BP * esz, PH, st, h->CsF ? h->CsF + j * BH * esz : nullptr);
+      launch_step_gemm(p, g, Bp, st);
+    }
     StepGemm z{};                                   // logits (without the bias) = H_o W_o^T
     z.a0 = h->xcat + (size_t)E * esz; z.lda0 = h->ldxcat; z.K0 = H; z.w0_off = 0; z.K1 = 0;
     // ... of which only the largest per sentence is wanted: every workgroup of the product keeps the best of its 64
@@ -1556,7 +1628,15 @@ int cmt_beam_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* sr
   BeamState& bs = h->beam;
   bs.hist_ld = Rp;
   launch_beam_init(bs, B, Rp, K, c.bos_id, h->len_s, h->len_exp, st);
-  launch_beam_expand((int)esz, Hs, ldHs, BpE, h->Hs_exp, H, S, R, Rp, K, H, st);
+  // (below 256 rows the attention runs on the projected source rows, as in the training step: those are expanded
+  // in the place of the source states)
+  const bool proj = h->att_proj && Rp < 256;
+  if (proj) {
+    launch_gemm_nt(p, Hs, ldHs, h->Pw(h->off_Wc), 2 * H, S * BpE, H, H, nullptr, h->PmatT, H, nullptr, 0, st);
+    launch_beam_expand((int)esz, h->PmatT, H, BpE, h->Hs_exp, H, S, R, Rp, K, H, st);
+  } else {
+    launch_beam_expand((int)esz, Hs, ldHs, BpE, h->Hs_exp, H, S, R, Rp, K, H, st);
+  }
   launch_beam_expand((int)esz, h->Kmat, H, BpE, h->K_exp, H, S, R, Rp, K, H, st);
   const size_t slotT = (size_t)Rp * PH * esz, slotC = (size_t)Rp * H * 4;   // state slots of Rp rows: 1 = read, 2 = written
   const size_t slotF = (size_t)Rp * H * esz;                                // the same slots of the fragment-major copies
@@ -1599,7 +1679,6 @@ int cmt_beam_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* sr
       launch_lstm_fwd(p, &d, 1, Rp, H, st);
     }
     const char* Ht = h->dec[L - 1].Hst + 2 * slotT;
-    launch_att_fwd(p, h->K_exp, H, h->Hs_exp, H, Ht, PH, h->len_exp, S, Rp, H, h->dots, h->att_a, h->Cs, PH, st, h->CsF);
     StepGemm g{};
     g.a0 = h->Cs; g.lda0 = PH; g.K0 = H; g.w0_off = 0;
     g.a1 = Ht; g.lda1 = PH; g.K1 = H; g.w1_off = H;
@@ -1607,7 +1686,15 @@ int cmt_beam_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* sr
     g.outT = h->HoBuf; g.ldo = PH;
     g.out = h->wcp; g.ldout = H; g.plane_stride = (size_t)Rp * H;
     if (h->CsF && h->dec[L - 1].fm) { g.W_fm = h->WcF; g.a0_fm = h->CsF; g.a1_fm = h->dec[L - 1].HstF + 2 * slotF; }
-    launch_step_gemm(p, g, Rp, st);
+    if (proj) {
+      AttOut o{};
+      o.outT = g.outT; o.ldo = g.ldo;
+      g.mode = 3; g.skip0 = 1; g.a0_fm = g.a1_fm;
+      launch_att_fwd_proj(p, h->K_exp, H, h->Hs_exp, H, Ht, PH, g, o, h->len_exp, S, Rp, H, h->dots, h->att_a, st);
+    } else {
+      launch_att_fwd(p, h->K_exp, H, h->Hs_exp, H, Ht, PH, h->len_exp, S, Rp, H, h->dots, h->att_a, h->Cs, PH, st, h->CsF);
+      launch_step_gemm(p, g, Rp, st);
+    }
     launch_gemm_nt(p, h->HoBuf, PH, h->Pw(h->off_Wo), H, Rp, V, H, h->logits, nullptr, V, h->params + h->off_Bo, 0, st);
     launch_beam_select(h->logits, V, bs, B, K, j, max_len, eos_id, length_penalty, st);
     launch_beam_reorder(p, ro, bs, R, H, L, st);
@@ -1693,24 +1780,33 @@ int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_la
       launch_step_bwd_fused(p, &g, 1, Bp, st);
     };
   } else if (s == "att_fwd") {
-    // scores + softmax + context of one decoder step: the keys and H_s of every sentence once
-    *algo_work = 2.0 * Bp * S * H * esz;
+    // attention forward of one decoder step as the step launches it.  On the projected rows: scores (with the sums
+    // W_c2 H_t in the same launch), softmax, mix and tanh -> H_o: the keys and the projected rows of every sentence
+    // once and the H_t half of W_c.  Else scores + softmax + context: the keys and H_s of every sentence once.
+    const bool proj = h->att_proj && Bp < 256;
+    *algo_work = 2.0 * Bp * S * H * esz + (proj ? (double)H * H * esz : 0.0);
     const char* Hs = L > 1 ? h->enc[L].Hst + BP * es : h->Y0;
     const int ldHs = L > 1 ? PH : H;
     launch = [=](int) {
-      launch_att_fwd(p, h->Kmat, H, Hs, ldHs, h->dec[L - 1].Hst + (j + 1) * BP * es, PH, h->len_s, S, Bp, H, h->dots,
-                     h->att_a + (size_t)j * Bp * S, h->Cs + j * BP * es, PH, st);
+      if (proj) dec_att_fwd_proj(h, j, S, h->dots);
+      else launch_att_fwd(p, h->Kmat, H, Hs, ldHs, h->dec[L - 1].Hst + (j + 1) * BP * es, PH, h->len_s, S, Bp, H, h->dots,
+                          h->att_a + (size_t)j * Bp * S, h->Cs + j * BP * es, PH, st);
     };
   } else if (s == "att_bwd") {
     // attention backward of one decoder step as the step launches it (score gradients, the gradient sent to the
-    // top layer's output, that layer's cell backward in the same launch): H_s and the keys of every sentence once
-    *algo_work = 2.0 * Bp * S * H * esz;
+    // top layer's output, that layer's cell backward in the same launch).  On the projected rows the launch of
+    // dpre W_c is part of it: the fp32 projected rows and the keys of every sentence once, and W_c.  Else H_s and the
+    // keys of every sentence once.
+    const bool fused = (h->bwd_fused & 1) && Bp <= 128;
+    const bool proj = h->att_proj && Bp < 256 && fused && h->wc_whole_k;
+    *algo_work = proj ? (double)Bp * S * H * (4 + esz) + 2.0 * H * H * esz : 2.0 * Bp * S * H * esz;
     const char* Hs = L > 1 ? h->enc[L].Hst + BP * es : h->Y0;
     const int ldHs = L > 1 ? PH : H;
     // (the planes the step's dpre W_c wrote: one in the fused loop's whole-k form)
-    const int kbw = (h->wc_whole_k && (h->bwd_fused & 1) && Bp <= 128) ? 1 : step_kblocks(p, 2 * H, H, Bp, h->kb_wc);
+    const int kbw = (h->wc_whole_k && fused) ? 1 : step_kblocks(p, 2 * H, H, Bp, h->kb_wc);
     const size_t pstr = (size_t)Bp * 2 * H;
     launch = [=](int) {
+      if (proj) { dec_att_bwd_proj(h, j, S, false); return; }
       LstmBwdPoint top = dec_cell(h, L - 1, j);
       top.dhrec = Planes{h->dec[L - 1].bwdp, H, 1, 0};
       launch_att_bwd(p, h->Kmat, H, Hs, ldHs, Planes{h->wcp, 2 * H, kbw, pstr}, h->dCs + j * BH, h->att_a + (size_t)j * Bp * S,

@@ -147,6 +147,8 @@ struct StepGemm {
                        // 2: (max_kb = 1) per block of 64 output columns and sentence the largest value of
                        //    sum + bias[n] and its column, the lower column on equal values:
                        //    out[blk * Bp + b] and best_idx[blk * Bp + b], blk < ceil(N / 64); nothing else is stored
+                       // 3: (whole k range in the workgroup) the plain sums out[b * ldout + n] (fp32), nothing else
+  int skip0 = 0;       // contract segment 1 only (segment 0 keeps its place in the weight rows and in W_fm)
   void* outT; int ldo;
   void* outD = nullptr; int ldod = 0;  // mode 0: optional copy of outT after dropout `drop`
   DropSpec drop{};
@@ -213,8 +215,13 @@ struct StepBwd {
   const void* dg_fm = nullptr; const void* Wt_fm = nullptr; int wt_tile0 = 0;
 };
 constexpr int STEP_BWD_MAX_INST = 4;
-// n independent instances in one launch (more than STEP_BWD_MAX_INST are spread over several launches)
-void launch_step_bwd_fused(int prec, const StepBwd* gs, int n, int Bp, hipStream_t st);
+// Attention scores that ride in a step GEMM's launch: dots[b, i] = vec[b, :] . Mat[i, b, :] for i < len[b]
+// (Mat rows [S * Bp, ldm]: T*, or float* with mat_f32 set; vec rows [Bp, ldv]: T*; dots fp32 [Bp, S])
+struct AttScores { const void* Mat; int ldm; const void* vec; int ldv; const int32_t* len; int S, H; float* dots; int mat_f32; };
+// n independent instances in one launch (more than STEP_BWD_MAX_INST are spread over several launches).
+// With `scores` (n = 1) further workgroups of the launch compute those scores; they must depend on nothing the
+// instance writes.
+void launch_step_bwd_fused(int prec, const StepBwd* gs, int n, int Bp, hipStream_t st, const AttScores* scores = nullptr);
 
 // out[Bp, cols] = base (or 0) + planes columns col0 + [0, cols)
 void launch_planes_add(float* out, const float* base, const Planes& p, int col0, int Bp, int cols, hipStream_t st);
@@ -225,6 +232,26 @@ void launch_planes_add(float* out, const float* base, const Planes& p, int col0,
 void launch_att_fwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds, const void* Ht, int ldt,
                     const int32_t* src_len, int S, int Bp, int H, float* dots, float* a /*[Bp,S]*/,
                     void* Cs /*T* [Bp,ldcs]*/, int ldcs, hipStream_t st, void* Cs_fm = nullptr /* fragment-major copy */);
+// The same step with the context half of the attentional layer hoisted out of the loop (Eq. 5-7):
+// W_c [C_s; H_t] = sum_i a_i (W_c1 H_s^i) + W_c2 H_t, where the rows P_i = W_c1 H_s^i (Pmat: T* [S * Bp, ldp], like Kmat)
+// are made once per batch.  Two launches: (1) the scores s_i = K_i . H_t and, in other workgroups of the same launch, the plain
+// sums u = W_c2 H_t (fp32 [Bp, H] at `u.out`; `u` is a StepGemm of mode 3 with skip0 set, below 256 sentences);
+// (2) softmax, sum a_i P_i + u, tanh -> H_o with the copies a mode-0 StepGemm writes (described by `o`).
+// C_s itself is not made here: launch_att_context makes it for all steps at once.
+struct AttOut {
+  void* outT; int ldo;                 // H_o rows [Bp, ldo]
+  void* outD = nullptr; int ldod = 0;  // optional copy after dropout `drop`
+  DropSpec drop{};
+  void* outF = nullptr;                // 16-bit types: optional fragment-major copy (H / 32 k steps) of outD's values, else outT's
+  void* outF2 = nullptr;               // one more such copy, into the columns [outF2_k0, outF2_k0 + H) of a fragment-major
+  int outF2_nsteps = 0, outF2_k0 = 0;  //   matrix of outF2_nsteps k steps (k0 a multiple of 32)
+};
+void launch_att_fwd_proj(int prec, const void* Kmat, int ldk, const void* Pmat, int ldp, const void* Ht, int ldt,
+                         const StepGemm& u, const AttOut& o, const int32_t* src_len, int S, int Bp, int H, float* dots,
+                         float* a /*[Bp,S]*/, hipStream_t st);
+// C_s[j, b, :] = sum_i a[j, b, i] H_s^i[b, :] for all T steps (Eq. 5); a [T, Bp, S], Cs rows [T * Bp, ldcs]
+void launch_att_context(int prec, const void* Hs, int lds, const float* a, const int32_t* src_len, int S, int T, int Bp, int H,
+                        void* Cs, int ldcs, hipStream_t st);
 // Attention backward for one step.  dCst: planes [.., Bp, 2H] fp32 from the step GEMM dpre W_c:
 // columns [0,H) = dC_s, [H,2H) = the part of dH_t that came through the concatenation.
 // da_i = dC_s . H_s^i, ds = a (da - sum a da), dHt = dCst[:, H:] + sum ds_i K_i;
@@ -234,6 +261,11 @@ void launch_att_fwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds
 void launch_att_bwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds, const Planes& dCst, float* dCs_sum, const float* a,
                     const int32_t* src_len, int S, int Bp, int H, float* dots, float* ds /*[Bp,S]*/,
                     float* dHt /*[Bp,H]*/, hipStream_t st, const LstmBwdPoint* cell = nullptr);
+// The second half of that step when the scores da_i are already in `dots` (with the projected rows P_i = W_c1 H_s^i,
+// da_i = dpre . P_i needs no dC_s): ds, dHt = add[:, add_col + [0, H)] + sum ds_i K_i, and the fused cell backward.
+void launch_att_bwd_mix(int prec, const void* Kmat, int ldk, const Planes& add, int add_col, const float* a, const int32_t* src_len,
+                        int S, int Bp, int H, const float* dots, float* ds /*[Bp,S]*/, float* dHt /*[Bp,H]*/, hipStream_t st,
+                        const LstmBwdPoint* cell = nullptr);
 // After the decoder loop: dHs_ctx[i,b,:] = sum_j a[j,b,i] dCs[j,b,:], dK[i,b,:] = sum_j ds[j,b,i] Ht[j,b,:].
 void launch_att_deferred(int prec, const float* a, const float* ds, const float* dCs, int lddc, const void* Ht, int ldht,
                          int S, int T, int Bp, int H, float* dHs, void* dK, hipStream_t st);

@@ -161,6 +161,26 @@ __device__ __forceinline__ void step_contract_fm(const bf16_t* const (&wt)[RT], 
   __syncthreads();
 }
 
+// dots[b, i] = vec[b, :] . Mat[i, b, :] for position i < len[b] of sentence b, by one wavefront
+template <typename MT, typename T>
+__device__ __forceinline__ void att_dots_row(const MT* __restrict__ Mat, int ldm, const T* __restrict__ vec, int ldv,
+                                             const int32_t* __restrict__ len, int S, int Bp, int H, float* __restrict__ dots, int i, int b) {
+  const int lane = threadIdx.x & 63;
+  if (i >= S || i >= len[b]) return;
+  const MT* row = Mat + ((size_t)i * Bp + b) * ldm;
+  float a = 0.f;
+  for (int c = lane; c < (H >> 3); c += 64) {
+    Frag<T> fv;
+    Frag<MT> f;
+    fv.load(vec + (size_t)b * ldv + 8 * c);
+    f.load(row + 8 * c);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a += f.get(e) * fv.get(e);
+  }
+  a = wave_sum(a);
+  if (lane == 0) dots[(size_t)b * S + i] = a;
+}
+
 // keep-and-rescale factor of element (b, col) of a dropout slice (see DropSpec)
 __device__ __forceinline__ float drop_factor(const DropSpec& d, int b, int col) {
   if (!d.on) return 1.f;
@@ -571,29 +591,40 @@ __global__ __launch_bounds__(256) void tanh_planes_kernel(Planes p, T* __restric
 // (split over its wavefronts, combined through LDS), tanh and the optional dropped copy in the
 // epilogue.  No planes, no second kernel; each weight slab is read by the batch's 16-sentence groups
 // from the same L2.
-template <typename T, int KS, int U, bool FM = false>
-__global__ __launch_bounds__(64 * KS) void step_tanh_kernel(StepGemm g, int Bp, StepGrid sg) {
-  __shared__ __align__(16) float red[KS * 256];
+template <typename T, int KS, int U, bool FM, bool RAW>
+__device__ __forceinline__ void step_tanh_body(StepGemm& g, int Bp, const StepGrid& sg, float* red) {
   int x, kb, z;
   if (!decode_block(sg, x, kb, z)) return;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int n0 = x * 16;
   // what the epilogue needs is fetched now, not behind the barrier
-  CMT_PIN_UNIFORM_PTR(g.outT); CMT_PIN_UNIFORM(g.ldo); CMT_PIN_UNIFORM_PTR(g.outD); CMT_PIN_UNIFORM(g.ldod); CMT_PIN_UNIFORM_PTR(g.outF);
-  CMT_PIN_UNIFORM_PTR(g.outF2); CMT_PIN_UNIFORM(g.outF2_nsteps); CMT_PIN_UNIFORM(g.outF2_k0); CMT_PIN_UNIFORM(g.N);
-  CMT_PIN_UNIFORM(g.drop.on);
+  if constexpr (RAW) {
+    CMT_PIN_UNIFORM_PTR(g.out); CMT_PIN_UNIFORM(g.ldout); CMT_PIN_UNIFORM(g.N);
+  } else {
+    CMT_PIN_UNIFORM_PTR(g.outT); CMT_PIN_UNIFORM(g.ldo); CMT_PIN_UNIFORM_PTR(g.outD); CMT_PIN_UNIFORM(g.ldod); CMT_PIN_UNIFORM_PTR(g.outF);
+    CMT_PIN_UNIFORM_PTR(g.outF2); CMT_PIN_UNIFORM(g.outF2_nsteps); CMT_PIN_UNIFORM(g.outF2_k0); CMT_PIN_UNIFORM(g.N);
+    CMT_PIN_UNIFORM(g.drop.on);
+  }
+  const bool skip0 = RAW && g.skip0;                 // (mode 3 only) segment 1 alone
   const T* wrow[1] = {(const T*)g.W + (size_t)min(n0 + (lane & 15), g.N - 1) * g.ldw};
   if constexpr (FM) {
     const int ns0 = g.K0 >> 5, ns1 = g.K1 >> 5;
     const bf16_t* wt[1] = {(const bf16_t*)g.W_fm + (size_t)(g.w_tile0 + x) * (ns0 + ns1) * 512};
-    step_contract_fm<1, KS, U, 1>(wt, (const bf16_t*)g.a0_fm, ns0, (const bf16_t*)g.a1_fm, ns1, z, 1, red);
+    step_contract_fm<1, KS, U, 1>(wt, (const bf16_t*)g.a0_fm, ns0, (const bf16_t*)g.a1_fm, ns1, z, 1, red, skip0 ? ns0 : 0);
   } else {
-    step_contract<T, 1, KS, U, 1>(wrow, g.w0_off, g.w1_off, (const T*)g.a0, g.lda0, g.K0, (const T*)g.a1, g.lda1, g.K1, Bp, z, 1, red);
+    step_contract<T, 1, KS, U, 1>(wrow, g.w0_off, g.w1_off, (const T*)g.a0, g.lda0, skip0 ? 0 : g.K0, (const T*)g.a1, g.lda1, g.K1, Bp,
+                                  z, 1, red);
   }
   if (w != 0) return;
   const v4f r = step_tile_sum<1, KS, 1>(red, 0, 0);
   const int n = n0 + 4 * (lane >> 4), b = 16 * z + (lane & 15);
   if (b >= Bp) return;
+  if constexpr (RAW) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (n + i < g.N) g.out[(size_t)b * g.ldout + n + i] = r[i];
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < 4; ++i)
     if (n + i < g.N) {
@@ -604,6 +635,11 @@ __global__ __launch_bounds__(64 * KS) void step_tanh_kernel(StepGemm g, int Bp, 
       if (sizeof(T) == 2 && g.outF) ((T*)g.outF)[fm_offset(b, n + i, g.N >> 5)] = from_f<T>(hd);
       if (sizeof(T) == 2 && g.outF2) ((T*)g.outF2)[fm_offset(b, g.outF2_k0 + n + i, g.outF2_nsteps)] = from_f<T>(hd);
     }
+}
+template <typename T, int KS, int U, bool FM = false>
+__global__ __launch_bounds__(64 * KS) void step_tanh_kernel(StepGemm g, int Bp, StepGrid sg) {
+  __shared__ __align__(16) float red[KS * 256];
+  step_tanh_body<T, KS, U, FM, false>(g, Bp, sg, red);
 }
 
 static bool step_gemm_has_fm(const StepGemm& g) {
@@ -811,10 +847,8 @@ void launch_lstm_bwd_point(int prec, const LstmBwdPoint& p, int Bp, int Hh, hipS
 // second launch exist.  The epilogue's operands are fetched before the contraction starts.
 struct StepBwdArgs { StepBwd g[STEP_BWD_MAX_INST]; };
 
-template <typename T, int KS, int U, int BT, bool FM = false>
-__global__ __launch_bounds__(64 * KS) void step_bwd_fused_kernel(StepBwdArgs args, int Bp, StepGrid sg) {
-  __shared__ __align__(16) float red[KS * BT * 256];
-  const StepBwd& g = args.g[blockIdx.y];
+template <typename T, int KS, int U, int BT, bool FM>
+__device__ __forceinline__ void step_bwd_body(const StepBwd& g, int Bp, const StepGrid& sg, float* red) {
   int x, kb, z;
   if (!decode_block(sg, x, kb, z)) return;
   const int N = g.part[0].ncols + g.part[1].ncols;
@@ -874,11 +908,43 @@ __global__ __launch_bounds__(64 * KS) void step_bwd_fused_kernel(StepBwdArgs arg
     if (sizeof(T) == 2 && e.dpre_fm) store4<T>((T*)e.dpre_fm + fm_offset(b, c, e.hh >> 5), o);
   }
 }
+template <typename T, int KS, int U, int BT, bool FM = false>
+__global__ __launch_bounds__(64 * KS) void step_bwd_fused_kernel(StepBwdArgs args, int Bp, StepGrid sg) {
+  __shared__ __align__(16) float red[KS * BT * 256];
+  step_bwd_body<T, KS, U, BT, FM>(args.g[blockIdx.y], Bp, sg, red);
+}
+// One instance and, in further workgroups of the same launch, attention scores that depend on the same input
+// alone (block n_gemm + ig * Bp + b: positions ig * KS + wavefront of sentence b).
+template <typename T, int KS, int U, int BT, bool FM = false>
+__global__ __launch_bounds__(64 * KS) void step_bwd_scores_kernel(StepBwd g, int Bp, StepGrid sg, int n_gemm, AttScores d) {
+  __shared__ __align__(16) float red[KS * BT * 256];
+  if ((int)blockIdx.x >= n_gemm) {
+    int ig, b;
+    divmod_uniform((int)blockIdx.x - n_gemm, Bp, ig, b);
+    const int i = ig * KS + (threadIdx.x >> 6);
+    if (d.mat_f32) att_dots_row<float, T>((const float*)d.Mat, d.ldm, (const T*)d.vec, d.ldv, d.len, d.S, Bp, d.H, d.dots, i, b);
+    else att_dots_row<T, T>((const T*)d.Mat, d.ldm, (const T*)d.vec, d.ldv, d.len, d.S, Bp, d.H, d.dots, i, b);
+    return;
+  }
+  step_bwd_body<T, KS, U, BT, FM>(g, Bp, sg, red);
+}
 
 template <typename T, int KS, int U, int BT>
-static void step_bwd_go(const StepBwdArgs& a, int n, int Nmax, int Bp, hipStream_t st, bool fm) {
+static void step_bwd_go(const StepBwdArgs& a, int n, int Nmax, int Bp, hipStream_t st, bool fm, const AttScores* sc) {
   const int nbt = (Bp + 15) / 16;
   StepGrid sg{(Nmax + 15) / 16, 1, (nbt + BT - 1) / BT};
+  if (sc) {                                        // (one instance) the scores ride in the same launch
+    const int n_gemm = step_grid_blocks(sg);
+    const dim3 grid(n_gemm + ((sc->S + KS - 1) / KS) * Bp);
+    if constexpr (sizeof(T) == 2) {
+      if (fm) {
+        hipLaunchKernelGGL((step_bwd_scores_kernel<T, KS, U, BT, true>), grid, dim3(64 * KS), 0, st, a.g[0], Bp, sg, n_gemm, *sc);
+        return;
+      }
+    }
+    hipLaunchKernelGGL((step_bwd_scores_kernel<T, KS, U, BT>), grid, dim3(64 * KS), 0, st, a.g[0], Bp, sg, n_gemm, *sc);
+    return;
+  }
   if constexpr (sizeof(T) == 2) {
     if (fm) {
       hipLaunchKernelGGL((step_bwd_fused_kernel<T, KS, U, BT, true>), dim3(step_grid_blocks(sg), n), dim3(64 * KS), 0, st, a, Bp, sg);
@@ -888,7 +954,8 @@ static void step_bwd_go(const StepBwdArgs& a, int n, int Nmax, int Bp, hipStream
   hipLaunchKernelGGL((step_bwd_fused_kernel<T, KS, U, BT>), dim3(step_grid_blocks(sg), n), dim3(64 * KS), 0, st, a, Bp, sg);
 }
 
-void launch_step_bwd_fused(int prec, const StepBwd* gs, int n, int Bp, hipStream_t st) {
+void launch_step_bwd_fused(int prec, const StepBwd* gs, int n, int Bp, hipStream_t st, const AttScores* scores) {
+  if (scores && n != 1) scores = nullptr;            // (callers pass one instance with scores)
   for (int base = 0; base < n; base += STEP_BWD_MAX_INST) {
     const int m = n - base < STEP_BWD_MAX_INST ? n - base : STEP_BWD_MAX_INST;
     StepBwdArgs a;
@@ -906,7 +973,7 @@ void launch_step_bwd_fused(int prec, const StepBwd* gs, int n, int Bp, hipStream
     const int wgs = ((Nmax + 15) / 16) * (((Bp + 15) / 16 + 1) / 2) * m;
     // 16 columns x 32 sentences per workgroup.  (64 sentences per workgroup halves the number of workgroups
     // and was measured at twice the time: 25.6 against 12.9 us for 64 sentences, 26.2 against 21.8 us for 128.)
-#define GO(TT, KS, UU) step_bwd_go<TT, KS, UU, 2>(a, m, Nmax, Bp, st, fm)
+#define GO(TT, KS, UU) step_bwd_go<TT, KS, UU, 2>(a, m, Nmax, Bp, st, fm, scores)
     if (prec) {
       // a long k range is split over 16 wavefronts while the launch is one round of workgroups; with more than 256
       // workgroups (128 sentences) 8 wavefronts, so that two workgroups share a CU instead of taking turns
@@ -941,20 +1008,22 @@ void launch_planes_add(float* out, const float* base, const Planes& p, int col0,
 template <typename T>
 __global__ __launch_bounds__(256) void att_dots_kernel(const T* __restrict__ Mat, int ldm, const T* __restrict__ vec, int ldv,
                                                        const int32_t* __restrict__ len, int S, int Bp, int H, float* __restrict__ dots) {
-  const int lane = threadIdx.x & 63;
-  const int i = blockIdx.x * 4 + (threadIdx.x >> 6), b = blockIdx.y;
-  if (i >= S || i >= len[b]) return;
-  const T* row = Mat + ((size_t)i * Bp + b) * ldm;
-  float a = 0.f;
-  for (int c = lane; c < (H >> 3); c += 64) {
-    Frag<T> fv, f;
-    fv.load(vec + (size_t)b * ldv + 8 * c);
-    f.load(row + 8 * c);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) a += f.get(e) * fv.get(e);
+  att_dots_row<T, T>(Mat, ldm, vec, ldv, len, S, Bp, H, dots, blockIdx.x * 4 + (threadIdx.x >> 6), blockIdx.y);
+}
+
+// The scores of a step and, in other workgroups of the same launch, the plain sums of a mode-3 step GEMM (the
+// attentional layer's H_t half): both depend on the top layer's new state alone, so neither waits for the other.
+// Blocks [0, n_gemm) are the GEMM's; block n_gemm + ig * Bp + b takes positions ig * KS + wavefront of sentence b.
+template <typename T, int KS, int U, bool FM>
+__global__ __launch_bounds__(64 * KS) void att_dots_pre_kernel(StepGemm g, int Bp, StepGrid sg, int n_gemm, AttScores d) {
+  __shared__ __align__(16) float red[KS * 256];
+  if ((int)blockIdx.x >= n_gemm) {
+    int ig, b;
+    divmod_uniform((int)blockIdx.x - n_gemm, Bp, ig, b);
+    att_dots_row<T, T>((const T*)d.Mat, d.ldm, (const T*)d.vec, d.ldv, d.len, d.S, Bp, d.H, d.dots, ig * KS + (threadIdx.x >> 6), b);
+    return;
   }
-  a = wave_sum(a);
-  if (lane == 0) dots[(size_t)b * S + i] = a;
+  step_tanh_body<T, KS, U, FM, true>(g, Bp, sg, red);
 }
 
 // The same with the vector given as the sum of fp32 planes (backward: dC_s from the step GEMM).  The planes are
@@ -1018,17 +1087,20 @@ __global__ __launch_bounds__(256) void att_dots_planes_kernel(const T* __restric
 }
 
 constexpr int ATT_MAXS = 512;
+struct AttDropped { void* outD; int ldod; DropSpec drop; void* outF2; int outF2_nsteps, outF2_k0; };   // MODE 2: optional copies
 // MODE 0 (forward, Eq. 3 and 5): a = softmax(dots) over i < len, written by the h-chunk 0 block;
 //                                out = sum_i a_i Mat[i,b,:]  -> T
 // MODE 1 (backward): ds = a (dots - sum a dots), written by the h-chunk 0 block;
 //                    out = add[b,:] + sum_i ds_i Mat[i,b,:]  -> fp32
+// MODE 2 (forward, Eq. 3-7 with Mat = the projected rows W_c1 H_s^i): a as in mode 0;
+//                    out = tanh(add[b,:] + sum_i a_i Mat[i,b,:]) -> T, its dropped copy and fragment-major copy
 // grid (H / 64 column chunks, Bp); 256 threads = 8 column-octets x 32 position groups
 template <typename T, int MODE>
 __global__ __launch_bounds__(256) void att_mix_kernel(const T* __restrict__ Mat, int ldm, int ldo, const float* __restrict__ dots,
                                                       const float* __restrict__ a_in, const int32_t* __restrict__ len,
                                                       int S, int Bp, int H, float* __restrict__ coef_out,
                                                       void* __restrict__ out, Planes add, int add_col, LstmBwdPoint cell,
-                                                      int fuse_cell, void* __restrict__ out_fm) {
+                                                      int fuse_cell, void* __restrict__ out_fm, AttDropped dropped) {
   __shared__ float sc[ATT_MAXS];
   __shared__ float part[32][65];
   const int b = blockIdx.y, t = threadIdx.x;
@@ -1051,9 +1123,9 @@ __global__ __launch_bounds__(256) void att_mix_kernel(const T* __restrict__ Mat,
     else pre[q].zero();
   }
   float addv = 0.f;
-  if (MODE == 1 && t < 64 && blockIdx.x * 64 + t < H) addv = planes_get(add, b, add_col + blockIdx.x * 64 + t);
+  if (MODE != 0 && t < 64 && blockIdx.x * 64 + t < H) addv = planes_get(add, b, add_col + blockIdx.x * 64 + t);
   if (t < 64) {
-    if (MODE == 0) {
+    if (MODE != 1) {
       float mx = -INFINITY;
       for (int i = t; i < n; i += 64) mx = fmaxf(mx, dots[(size_t)b * S + i]);
       mx = wave_max(mx);
@@ -1109,6 +1181,15 @@ __global__ __launch_bounds__(256) void att_mix_kernel(const T* __restrict__ Mat,
         ((T*)out)[(size_t)b * ldo + h] = from_f<T>(s);
         if (sizeof(T) == 2 && out_fm) ((T*)out_fm)[fm_offset(b, h, H >> 5)] = from_f<T>(s);
       }
+      else if (MODE == 2) {                                  // Eq. 7 on the projected rows: s + u is the pre-activation
+        const float hv = tanh_of<sizeof(T) == 2>(s + addv);
+        const float hd = dropped.outD ? hv * drop_factor(dropped.drop, b, h) : hv;
+        ((T*)out)[(size_t)b * ldo + h] = from_f<T>(hv);
+        if (dropped.outD) ((T*)dropped.outD)[(size_t)b * dropped.ldod + h] = from_f<T>(hd);
+        if (sizeof(T) == 2 && out_fm) ((T*)out_fm)[fm_offset(b, h, H >> 5)] = from_f<T>(hd);
+        if (sizeof(T) == 2 && dropped.outF2)
+          ((T*)dropped.outF2)[fm_offset(b, dropped.outF2_k0 + h, dropped.outF2_nsteps)] = from_f<T>(hd);
+      }
       else {
         s += addv;
         if (!fuse_cell) ((float*)out)[(size_t)b * H + h] = s;
@@ -1131,11 +1212,86 @@ void launch_att_fwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds
   const Planes none{nullptr, 0, 0, 0};
   if (prec) {
     hipLaunchKernelGGL(att_dots_kernel<bf16_t>, gd, dim3(256), 0, st, (const bf16_t*)Kmat, ldk, (const bf16_t*)Ht, ldt, src_len, S, Bp, H, dots);
-    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 0>), gm, dim3(256), 0, st, (const bf16_t*)Hs, lds, ldcs, dots, nullptr, src_len, S, Bp, H, a, Cs, none, 0, LstmBwdPoint{}, 0, Cs_fm);
+    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 0>), gm, dim3(256), 0, st, (const bf16_t*)Hs, lds, ldcs, dots, nullptr, src_len, S, Bp, H, a, Cs, none, 0, LstmBwdPoint{}, 0, Cs_fm, AttDropped{});
   } else {
     hipLaunchKernelGGL(att_dots_kernel<float>, gd, dim3(256), 0, st, (const float*)Kmat, ldk, (const float*)Ht, ldt, src_len, S, Bp, H, dots);
-    hipLaunchKernelGGL((att_mix_kernel<float, 0>), gm, dim3(256), 0, st, (const float*)Hs, lds, ldcs, dots, nullptr, src_len, S, Bp, H, a, Cs, none, 0, LstmBwdPoint{}, 0, nullptr);
+    hipLaunchKernelGGL((att_mix_kernel<float, 0>), gm, dim3(256), 0, st, (const float*)Hs, lds, ldcs, dots, nullptr, src_len, S, Bp, H, a, Cs, none, 0, LstmBwdPoint{}, 0, nullptr, AttDropped{});
   }
+}
+
+void launch_att_fwd_proj(int prec, const void* Kmat, int ldk, const void* Pmat, int ldp, const void* Ht, int ldt,
+                         const StepGemm& u, const AttOut& o, const int32_t* src_len, int S, int Bp, int H, float* dots, float* a,
+                         hipStream_t st) {
+  const int nbt = (Bp + 15) / 16;
+  StepGrid sg{(u.N + 15) / 16, 1, nbt};
+  const int n_gemm = step_grid_blocks(sg);
+  const int nsteps = (u.K1 / 8 + 3) / 4;              // k steps of the contracted segment
+  const int ks = nsteps > 16 ? 16 : 8;
+  const dim3 grid(n_gemm + ((S + ks - 1) / ks) * Bp);
+  const AttScores d{Kmat, ldk, Ht, ldt, src_len, S, H, dots, 0};
+#define GO(TT, KS, FM) hipLaunchKernelGGL((att_dots_pre_kernel<TT, KS, 2, FM>), grid, dim3(64 * KS), 0, st, u, Bp, sg, n_gemm, d)
+  if (prec && step_gemm_has_fm(u)) { if (ks == 16) GO(bf16_t, 16, true); else GO(bf16_t, 8, true); }
+  else if (prec) { if (ks == 16) GO(bf16_t, 16, false); else GO(bf16_t, 8, false); }
+  else { if (ks == 16) GO(float, 16, false); else GO(float, 8, false); }
+#undef GO
+  const dim3 gm((H + 63) / 64, Bp);
+  const Planes up{u.out, u.ldout, 1, 0};
+  const AttDropped dr{o.outD, o.ldod, o.drop, o.outF2, o.outF2_nsteps, o.outF2_k0};
+  if (prec)
+    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 2>), gm, dim3(256), 0, st, (const bf16_t*)Pmat, ldp, o.ldo, dots, nullptr, src_len, S, Bp,
+                       H, a, o.outT, up, 0, LstmBwdPoint{}, 0, o.outF, dr);
+  else
+    hipLaunchKernelGGL((att_mix_kernel<float, 2>), gm, dim3(256), 0, st, (const float*)Pmat, ldp, o.ldo, dots, nullptr, src_len, S, Bp,
+                       H, a, o.outT, up, 0, LstmBwdPoint{}, 0, nullptr, dr);
+}
+
+// One workgroup: 64 columns of one sentence for 16 steps; the rows H_s^i pass through LDS 64 positions at a time.
+template <typename T>
+__global__ __launch_bounds__(256) void att_context_kernel(const T* __restrict__ Hs, int lds, const float* __restrict__ a,
+                                                          const int32_t* __restrict__ len, int S, int Tn, int Bp, int H,
+                                                          T* __restrict__ Cs, int ldcs) {
+  __shared__ float sa[16][64];
+  __shared__ float sh[64][65];
+  const int t = threadIdx.x, col = t & 63, jq = t >> 6;
+  const int b = blockIdx.y, j0 = blockIdx.z * 16, h0 = blockIdx.x * 64;
+  const int n = min(len[b], S);
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int s0 = 0; s0 < n; s0 += 64) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int idx = t + 256 * q, jj = idx >> 6, ss = idx & 63;
+      sa[jj][ss] = (j0 + jj < Tn && s0 + ss < n) ? a[((size_t)(j0 + jj) * Bp + b) * S + s0 + ss] : 0.f;
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int f = t + 256 * q, ss = f >> 3, oct = f & 7;
+      Frag<T> v;
+      if (s0 + ss < n && h0 + oct * 8 < H) v.load(Hs + ((size_t)(s0 + ss) * Bp + b) * lds + h0 + oct * 8);
+      else v.zero();
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sh[ss][oct * 8 + e] = v.get(e);
+    }
+    __syncthreads();
+    const int m = min(64, n - s0);
+    for (int ss = 0; ss < m; ++ss) {
+      const float hv = sh[ss][col];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) acc[q] += sa[jq * 4 + q][ss] * hv;
+    }
+    __syncthreads();
+  }
+  if (h0 + col < H)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int j = j0 + jq * 4 + q;
+      if (j < Tn) Cs[((size_t)j * Bp + b) * ldcs + h0 + col] = from_f<T>(acc[q]);
+    }
+}
+void launch_att_context(int prec, const void* Hs, int lds, const float* a, const int32_t* src_len, int S, int T, int Bp, int H,
+                        void* Cs, int ldcs, hipStream_t st) {
+  const dim3 grid((H + 63) / 64, Bp, (T + 15) / 16);
+  if (prec) hipLaunchKernelGGL(att_context_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)Hs, lds, a, src_len, S, T, Bp, H, (bf16_t*)Cs, ldcs);
+  else hipLaunchKernelGGL(att_context_kernel<float>, grid, dim3(256), 0, st, (const float*)Hs, lds, a, src_len, S, T, Bp, H, (float*)Cs, ldcs);
 }
 
 void launch_att_bwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds, const Planes& dCst, float* dCs_sum, const float* a,
@@ -1150,11 +1306,24 @@ void launch_att_bwd(int prec, const void* Kmat, int ldk, const void* Hs, int lds
   dim3 gd((S + 4 * PW - 1) / (4 * PW), Bp), gm((H + 63) / 64, Bp);
   if (prec) {
     hipLaunchKernelGGL((att_dots_planes_kernel<bf16_t, PW>), gd, dim3(256), 0, st, (const bf16_t*)Hs, lds, dCst, dCs_sum, src_len, S, Bp, H, dots);
-    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 1>), gm, dim3(256), 0, st, (const bf16_t*)Kmat, ldk, 0, dots, a, src_len, S, Bp, H, ds, dHt, dCst, H, cl, fuse, nullptr);
+    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 1>), gm, dim3(256), 0, st, (const bf16_t*)Kmat, ldk, 0, dots, a, src_len, S, Bp, H, ds, dHt, dCst, H, cl, fuse, nullptr, AttDropped{});
   } else {
     hipLaunchKernelGGL((att_dots_planes_kernel<float, PW>), gd, dim3(256), 0, st, (const float*)Hs, lds, dCst, dCs_sum, src_len, S, Bp, H, dots);
-    hipLaunchKernelGGL((att_mix_kernel<float, 1>), gm, dim3(256), 0, st, (const float*)Kmat, ldk, 0, dots, a, src_len, S, Bp, H, ds, dHt, dCst, H, cl, fuse, nullptr);
+    hipLaunchKernelGGL((att_mix_kernel<float, 1>), gm, dim3(256), 0, st, (const float*)Kmat, ldk, 0, dots, a, src_len, S, Bp, H, ds, dHt, dCst, H, cl, fuse, nullptr, AttDropped{});
   }
+}
+
+void launch_att_bwd_mix(int prec, const void* Kmat, int ldk, const Planes& add, int add_col, const float* a, const int32_t* src_len,
+                        int S, int Bp, int H, const float* dots, float* ds, float* dHt, hipStream_t st, const LstmBwdPoint* cell) {
+  const LstmBwdPoint cl = cell ? *cell : LstmBwdPoint{};
+  const int fuse = cell ? 1 : 0;
+  const dim3 gm((H + 63) / 64, Bp);
+  if (prec)
+    hipLaunchKernelGGL((att_mix_kernel<bf16_t, 1>), gm, dim3(256), 0, st, (const bf16_t*)Kmat, ldk, 0, dots, a, src_len, S, Bp, H, ds, dHt,
+                       add, add_col, cl, fuse, nullptr, AttDropped{});
+  else
+    hipLaunchKernelGGL((att_mix_kernel<float, 1>), gm, dim3(256), 0, st, (const float*)Kmat, ldk, 0, dots, a, src_len, S, Bp, H, ds, dHt,
+                       add, add_col, cl, fuse, nullptr, AttDropped{});
 }
 
 // After the decoder loop: for a block (sentence b, 256 hidden columns, ATT_DEF_IB source positions):

@@ -233,6 +233,31 @@ def test_every_form_of_the_backward_loops(prec, forms, B, S, T, H, E, L, monkeyp
 
 
 @pytest.mark.parametrize("prec", [0, 1])
+@pytest.mark.parametrize("reg", [None, (0.2, 0.1, 99)])
+@pytest.mark.parametrize("B,S,T,H,E,L", [(19, 9, 8, 80, 40, 3), (64, 6, 7, 256, 64, 2), (130, 3, 4, 64, 32, 2), (250, 3, 3, 32, 16, 1)])
+def test_attention_on_projected_source_rows(prec, reg, B, S, T, H, E, L, monkeypatch):
+    """Below 256 sentences the training step regroups Eq. 7 as W_c [C_s; H_t] = sum_i a_i (W_c1 H_s^i) + W_c2 H_t
+    with the rows W_c1 H_s^i made once per batch (and, in the fused decoder backward up to 128 sentences, takes
+    the score gradients as dpre . (W_c1 H_s^i)); CMT_ATT_PROJ=0 (read when the handle is created) keeps
+    the contexts inside the loop.  The four cases cover both loops regrouped, the forward alone (130
+    sentences) and neither (250).  Both forms meet the same bars against the oracle, intermediates (the
+    contexts C_s among them) included, and agree with each other to rounding order."""
+    cfg = dict(src_vocab=104, tgt_vocab=136, emb=E, hidden=H, layers=L)
+    rng = np.random.default_rng(900 + B)
+    params = I.make_params(cfg, seed=B + 2, scale=0.3 if H <= 128 else 0.05)
+    batch = ragged_batch(rng, B, S, T, cfg["src_vocab"], cfg["tgt_vocab"])
+    loss, oloss, worst, tr = run_case(cfg, params, batch, prec, reg=reg)
+    g = tr.get_grads().copy()
+    tr.close()
+    monkeypatch.setenv("CMT_ATT_PROJ", "0")
+    loss0, _, _, tr0 = run_case(cfg, params, batch, prec, reg=reg)
+    g0 = tr0.get_grads().copy()
+    tr0.close()
+    assert abs(loss - loss0) <= (1e-6 if prec == 0 else 2e-3) * abs(loss0)
+    assert np.linalg.norm(g - g0) <= (1e-5 if prec == 0 else 2e-2) * np.linalg.norm(g0)
+
+
+@pytest.mark.parametrize("prec", [0, 1])
 def test_second_stream_gemms_walking_their_tiles(prec, monkeypatch):
     """The weight-gradient GEMMs of the second stream may be launched with fewer workgroups than tiles
     (CMT_SIDE_WGS, CMT_SIDE_WGS_WO: a cap that leaves part of the chip to the recurrences' kernels); each
