@@ -116,7 +116,8 @@ struct cmt_handle {
   char* Y0 = nullptr; char* Y0T = nullptr; char* Kmat = nullptr;
   float* Pmat = nullptr; char* PmatT = nullptr;   // the source states through the context half of W_c, [S * Bp, H] in fp32 and in
                                         // the operand type (Eq. 7 regrouped)
-  int att_proj = 1;                     // the training step's attention runs on Pmat (see enqueue_step)
+  int att_proj = 1;                     // attention on the projected source rows (see enqueue_step): 1 both decoder loops,
+                                        // 2 the forward loop alone, 0 neither
   float* dHs = nullptr; char* dK = nullptr; char* dKT = nullptr;
   float* dYa = nullptr; float* dXs = nullptr; char* XsT = nullptr;
   // target side
@@ -932,7 +933,7 @@ int enqueue_step(cmt_handle* h, const int32_t* src_ids, const int32_t* src_len, 
         launch_tanh_bwd(p, h->dHoCE, h->ce_pos + (size_t)j * Bp, no_planes, h->HoBuf + (j + 1) * BP * esz, PH, dpre, PH, Bp, H,
                         drop_spec(h, DROP_SITE_HO, j), st, dpreF);
       int kbw = step_kblocks(p, 2 * H, H, Bp, h->kb_wc);
-      if (proj && h->wc_whole_k) {
+      if (proj && (h->att_proj & 1) && h->wc_whole_k) {
         dec_att_bwd_proj(h, j, S, last);
         for (int l = L - 1; l >= 0; --l) {
           const StepBwd gl = dec_bwd_gemm(h, l, j);
@@ -1798,7 +1799,7 @@ int cmt_time_kernel(cmt_handle* h, const char* name, int iters, float* us_per_la
     // dpre W_c is part of it: the fp32 projected rows and the keys of every sentence once, and W_c.  Else H_s and the
     // keys of every sentence once.
     const bool fused = (h->bwd_fused & 1) && Bp <= 128;
-    const bool proj = h->att_proj && Bp < 256 && fused && h->wc_whole_k;
+    const bool proj = (h->att_proj & 1) && Bp < 256 && fused && h->wc_whole_k;
     *algo_work = proj ? (double)Bp * S * H * (4 + esz) + 2.0 * H * H * esz : 2.0 * Bp * S * H * esz;
     const char* Hs = L > 1 ? h->enc[L].Hst + BP * es : h->Y0;
     const int ldHs = L > 1 ? PH : H;
