@@ -21,6 +21,7 @@
 
 #include <algorithm>
 #include <functional>
+#include <chrono>
 #include <string>
 #include <vector>
 
@@ -174,6 +175,7 @@ struct cmt_handle {
   // phase timing of a step on the caller's stream (measurement aid, env CMT_PHASE_TIMING=1)
   int phase_timing = 0;
   std::vector<hipEvent_t> phase_ev; std::vector<const char*> phase_name; size_t phase_n = 0;
+  std::vector<double> phase_host;       // host clock (ms) when each mark was enqueued
   // regularisation of the next steps (cmt_set_regularization)
   float drop_p = 0.f, drop_scale = 1.f, ls_eps = 0.f;
   unsigned drop_thresh = 0; unsigned long long drop_seed = 0;
@@ -464,6 +466,8 @@ void phase_mark(cmt_handle* h, const char* name) {
     h->phase_ev.push_back(e); h->phase_name.push_back(name);
   }
   h->phase_name[h->phase_n] = name;
+  if (h->phase_host.size() <= h->phase_n) h->phase_host.resize(h->phase_n + 1);
+  h->phase_host[h->phase_n] = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count();
   (void)hipEventRecord(h->phase_ev[h->phase_n++], h->st);
 }
 
@@ -1474,7 +1478,8 @@ int cmt_fetch_loss(cmt_handle* h, float* loss_host) {
     for (size_t i = 0; i + 1 < h->phase_n; ++i) {
       float ms = 0.f;
       if (hipEventElapsedTime(&ms, h->phase_ev[i], h->phase_ev[i + 1]) != hipSuccess) break;
-      fprintf(stderr, "[cytonmt_hip] %-40s %8.3f ms\n", h->phase_name[i], ms);
+      fprintf(stderr, "[cytonmt_hip] %-40s %8.3f ms   (enqueued in %6.3f ms)\n", h->phase_name[i], ms,
+              h->phase_host[i + 1] - h->phase_host[i]);
       total += ms;
     }
     fprintf(stderr, "[cytonmt_hip] %-40s %8.3f ms\n", "step", total);

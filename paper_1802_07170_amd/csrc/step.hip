@@ -113,11 +113,18 @@ __device__ __forceinline__ v4f step_tile_sum(const float* red, int rt, int bt) {
 // The same contraction on fragment-major operands (bf16): wt[rt] = first block of row tile rt (its k steps follow
 // each other), a0 / a1 = fragment-major activation segments of ns0 / ns1 k steps (batch tile bt at bt * ns blocks).
 // [s_begin, s_end) = the k steps this workgroup contracts (default: all).
-template <int RT, int KS, int U, int BT>
+// `after_first_loads` runs once, behind the loads of the first round: a kernel whose operand addresses arrived in
+// registers (leading kernel arguments) fetches the rest of its arguments there, in the shadow of those loads.
+struct StepNoHook { __device__ __forceinline__ void operator()() const {} };
+// HookLate: behind the first round's matrix operations instead (the hook's own loads then do not meet the first
+// round's fragments in the register file; for kernels at the register limit whose k range takes several rounds).
+template <int RT, int KS, int U, int BT, typename Hook = StepNoHook, bool HookLate = false>
 __device__ __forceinline__ void step_contract_fm(const bf16_t* const (&wt)[RT], const bf16_t* a0, int ns0, const bf16_t* a1, int ns1,
-                                                 int bt0, int nbt, float* red, int s_begin = 0, int s_end = 1 << 30) {
+                                                 int bt0, int nbt, float* red, int s_begin = 0, int s_end = 1 << 30,
+                                                 Hook after_first_loads = Hook{}) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int nsteps = min(ns0 + ns1, s_end);
+  bool hook_due = true;
   v4f acc[RT][BT];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt)
@@ -146,13 +153,16 @@ __device__ __forceinline__ void step_contract_fm(const bf16_t* const (&wt)[RT], 
         for (int b = 0; b < BT; ++b) fx[u][b].zero();
       }
     }
+    if (!HookLate && hook_due) { after_first_loads(); hook_due = false; }
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
         for (int b = 0; b < BT; ++b) mma16(acc[rt][b], fw[u][rt], fx[u][b]);
+    if (HookLate && hook_due) { after_first_loads(); hook_due = false; }
   }
+  if (hook_due) after_first_loads();
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
@@ -295,46 +305,72 @@ __device__ __forceinline__ void cell_finish(const LstmFwdDir& d, int b, int u, i
 // whole k range inside the workgroup.  Per workgroup RT weight slabs and BT activation slabs cross L2:
 // for 64 sentences RT = BT = 2 moves the fewest bytes (each weight slab is then read by two workgroups,
 // which the XCD-aware numbering puts on the same L2).
+// The operand addresses of the fragment-major contraction and the grid lead the argument list (for one instance:
+// W_fm0, x_fm0, hprev_fm0, Kx0 are that instance's), so that they arrive in registers and the first loads go out
+// before the argument buffer has been read; the rest (args) is fetched behind those loads.  The grid follows from
+// Hh, Bp and the instance count as the launcher computes it.
+// nlead = how many instances the leading arguments describe: 1, or 2 when the launch's two instances have no
+// input segment (Kx = 0: the bottom encoder layer's directions) — then W_fm1 / hprev_fm1 are the second one's.
 template <typename T, int RT, int KS, int U, int BT, bool FM = false>
-__global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(LstmFwdArgs args, int Bp, int Hh, StepGrid sg, int ndir) {
+__global__ __launch_bounds__(64 * KS) void lstm_fwd_kernel(const void* W_fm0, const void* x_fm0, const void* hprev_fm0,
+                                                           const void* W_fm1, const void* hprev_fm1, int Kx0, int Bp, int Hh,
+                                                           int ndir_nlead, LstmFwdArgs args) {
   __shared__ __align__(16) float red[KS * RT * BT * 256];
+  const int ndir = ndir_nlead & 0xffff, nlead = ndir_nlead >> 16;
+  const int nxd = (Hh + 4 * RT - 1) / (4 * RT);    // unit blocks per direction
+  const int nx = nxd * ndir, nz = ((Bp + 15) / 16 + BT - 1) / BT;
+  const StepGrid sg{nx, 1, nz};
   int x, kb, z;
   if (!decode_block(sg, x, kb, z)) return;
-  const int nxd = sg.nx / ndir;                    // unit blocks per direction
   const int dir = ndir == 1 ? 0 : x / nxd;
-  LstmFwdDir d = args.d[dir];
-  // what the epilogue needs is fetched now, not behind the barrier
-  CMT_PIN_UNIFORM_PTR(d.cnext); CMT_PIN_UNIFORM_PTR(d.gsave); CMT_PIN_UNIFORM_PTR(d.hnext); CMT_PIN_UNIFORM(d.ldhn);
-  CMT_PIN_UNIFORM_PTR(d.ycat); CMT_PIN_UNIFORM(d.ldy); CMT_PIN_UNIFORM_PTR(d.hnext_fm); CMT_PIN_UNIFORM_PTR(d.ycat_fm);
-  CMT_PIN_UNIFORM(d.drop.on); CMT_PIN_UNIFORM(d.drop_col0);
-  CMT_PIN_UNIFORM_PTR(d.gx); CMT_PIN_UNIFORM(d.ldgx); CMT_PIN_UNIFORM_PTR(d.bias); CMT_PIN_UNIFORM_PTR(d.cprev); CMT_PIN_UNIFORM_PTR(d.mask);
-  CMT_PIN_UNIFORM_PTR(d.hprev); CMT_PIN_UNIFORM(d.ldh);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int u0 = (x - dir * nxd) * 4 * RT;
   const int bt0 = z * BT;
   const int nbt = min(BT, (Bp + 15) / 16 - bt0);
-  // row m = lane % 16 of row tile rt: gate m % 4 of unit u0 + 4 * rt + m / 4
-  const int m = lane & 15;
-  const T* wrow[RT];
-#pragma unroll
-  for (int rt = 0; rt < RT; ++rt)
-    wrow[rt] = (const T*)d.W + (size_t)((m & 3) * Hh + min(u0 + 4 * rt + (m >> 2), Hh - 1)) * d.ldw;
-  // the first tile this wavefront will finish: fetch its cell inputs now
+  LstmFwdDir d;
   CellIn in0;
   bool have0 = false;
-  if (w < RT * BT) {
-    const int rt = w / BT, bt = w - rt * BT;
-    const int u = u0 + 4 * rt + (lane >> 4), b = 16 * (bt0 + bt) + (lane & 15);
-    have0 = bt < nbt && u < Hh && b < Bp;
-    if (have0) in0 = cell_load(d, b, u, Hh, sizeof(T) == 2);
-  }
+  auto fetch_rest = [&]() {
+    // (the instance index passes through an opaque register and a compiler barrier: otherwise the compiler moves this
+    // block, which depends on nothing before it, back in front of the contraction's loads)
+    int dsel = __builtin_amdgcn_readfirstlane(dir);
+    asm volatile("" : "+s"(dsel) : : "memory");
+    d = args.d[dsel];
+    // what the epilogue needs is fetched now, not behind the barrier
+    CMT_PIN_UNIFORM_PTR(d.cnext); CMT_PIN_UNIFORM_PTR(d.gsave); CMT_PIN_UNIFORM_PTR(d.hnext); CMT_PIN_UNIFORM(d.ldhn);
+    CMT_PIN_UNIFORM_PTR(d.ycat); CMT_PIN_UNIFORM(d.ldy); CMT_PIN_UNIFORM_PTR(d.hnext_fm); CMT_PIN_UNIFORM_PTR(d.ycat_fm);
+    CMT_PIN_UNIFORM(d.drop.on); CMT_PIN_UNIFORM(d.drop_col0);
+    CMT_PIN_UNIFORM_PTR(d.gx); CMT_PIN_UNIFORM(d.ldgx); CMT_PIN_UNIFORM_PTR(d.bias); CMT_PIN_UNIFORM_PTR(d.cprev); CMT_PIN_UNIFORM_PTR(d.mask);
+    CMT_PIN_UNIFORM_PTR(d.hprev); CMT_PIN_UNIFORM(d.ldh);
+    // the first tile this wavefront will finish: fetch its cell inputs now
+    if (w < RT * BT) {
+      const int rt = w / BT, bt = w - rt * BT;
+      const int u = u0 + 4 * rt + (lane >> 4), b = 16 * (bt0 + bt) + (lane & 15);
+      have0 = bt < nbt && u < Hh && b < Bp;
+      if (have0) in0 = cell_load(d, b, u, Hh, sizeof(T) == 2);
+    }
+  };
   if constexpr (FM) {
-    const int ns0 = d.Kx >> 5, ns1 = Hh >> 5;
+    const bf16_t *Wf = (const bf16_t*)W_fm0, *xf = (const bf16_t*)x_fm0, *hf = (const bf16_t*)hprev_fm0;
+    int Kx = Kx0;
+    if (dir == 1 && nlead == 2) { Wf = (const bf16_t*)W_fm1; hf = (const bf16_t*)hprev_fm1; }
+    else if (dir >= nlead) {
+      Wf = (const bf16_t*)args.d[dir].W_fm; xf = (const bf16_t*)args.d[dir].x_fm; hf = (const bf16_t*)args.d[dir].hprev_fm;
+      Kx = args.d[dir].Kx;
+    }
+    const int ns0 = Kx >> 5, ns1 = Hh >> 5;
     const bf16_t* wt[RT];
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) wt[rt] = (const bf16_t*)d.W_fm + (size_t)((u0 >> 2) + rt) * (ns0 + ns1) * 512;
-    step_contract_fm<RT, KS, U, BT>(wt, (const bf16_t*)d.x_fm, ns0, (const bf16_t*)d.hprev_fm, ns1, bt0, nbt, red);
+    for (int rt = 0; rt < RT; ++rt) wt[rt] = Wf + (size_t)((u0 >> 2) + rt) * (ns0 + ns1) * 512;
+    step_contract_fm<RT, KS, U, BT>(wt, xf, ns0, hf, ns1, bt0, nbt, red, 0, 1 << 30, fetch_rest);
   } else {
+    fetch_rest();
+    // row m = lane % 16 of row tile rt: gate m % 4 of unit u0 + 4 * rt + m / 4
+    const int m = lane & 15;
+    const T* wrow[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+      wrow[rt] = (const T*)d.W + (size_t)((m & 3) * Hh + min(u0 + 4 * rt + (m >> 2), Hh - 1)) * d.ldw;
     step_contract<T, RT, KS, U, BT>(wrow, d.wx_off, d.wh_off, (const T*)d.x, d.ldx, d.Kx, (const T*)d.hprev, d.ldh, Hh, Bp, bt0,
                                     nbt, red);
   }
@@ -355,13 +391,19 @@ template <typename T, int RT, int KS, int U, int BT = STEP_MAXBT>
 static void lstm_fwd_go(const LstmFwdArgs& a, int Bp, int Hh, int ndir, hipStream_t st, bool fm = false) {
   const int nbt = (Bp + 15) / 16;
   StepGrid sg{((Hh + 4 * RT - 1) / (4 * RT)) * ndir, 1, (nbt + BT - 1) / BT};
+  const LstmFwdDir& d0 = a.d[0];
+  const LstmFwdDir& d1 = a.d[ndir > 1 ? 1 : 0];
+  const int nlead = (ndir == 2 && d0.Kx == 0 && d1.Kx == 0) ? 2 : 1;
+  const int ndir_nlead = ndir | (nlead << 16);
   if constexpr (sizeof(T) == 2) {
     if (fm) {
-      hipLaunchKernelGGL((lstm_fwd_kernel<T, RT, KS, U, BT, true>), dim3(step_grid_blocks(sg)), dim3(64 * KS), 0, st, a, Bp, Hh, sg, ndir);
+      hipLaunchKernelGGL((lstm_fwd_kernel<T, RT, KS, U, BT, true>), dim3(step_grid_blocks(sg)), dim3(64 * KS), 0, st, d0.W_fm, d0.x_fm,
+                         d0.hprev_fm, d1.W_fm, d1.hprev_fm, d0.Kx, Bp, Hh, ndir_nlead, a);
       return;
     }
   }
-  hipLaunchKernelGGL((lstm_fwd_kernel<T, RT, KS, U, BT>), dim3(step_grid_blocks(sg)), dim3(64 * KS), 0, st, a, Bp, Hh, sg, ndir);
+  hipLaunchKernelGGL((lstm_fwd_kernel<T, RT, KS, U, BT>), dim3(step_grid_blocks(sg)), dim3(64 * KS), 0, st, d0.W_fm, d0.x_fm, d0.hprev_fm,
+                     d1.W_fm, d1.hprev_fm, d0.Kx, Bp, Hh, ndir_nlead, a);
 }
 
 // Shapes of the fused kernel: 16 / 32 / 64 gate rows per workgroup, with all sentences (up to 64) or
@@ -847,47 +889,62 @@ void launch_lstm_bwd_point(int prec, const LstmBwdPoint& p, int Bp, int Hh, hipS
 // second launch exist.  The epilogue's operands are fetched before the contraction starts.
 struct StepBwdArgs { StepBwd g[STEP_BWD_MAX_INST]; };
 
+// What the fragment-major contraction of an instance needs before its first load, as leading kernel arguments
+// (they arrive in registers): the operands, the contraction length and the column counts.  `on` = 0: read the
+// instance's own fields instead (further instances of a launch).
+struct StepBwdLead { const void* Wt_fm; const void* dg_fm; int K, wt_tile0, N, ncols0, on; };   // (on: see step_bwd_fused_kernel)
 template <typename T, int KS, int U, int BT, bool FM>
-__device__ __forceinline__ void step_bwd_body(const StepBwd& g, int Bp, const StepGrid& sg, float* red) {
+__device__ __forceinline__ void step_bwd_body(const StepBwdLead& ld, const StepBwd& g, int Bp, const StepGrid& sg, float* red) {
   int x, kb, z;
   if (!decode_block(sg, x, kb, z)) return;
-  const int N = g.part[0].ncols + g.part[1].ncols;
+  const int ncols0 = ld.on ? ld.ncols0 : g.part[0].ncols;
+  const int N = ld.on ? ld.N : g.part[0].ncols + g.part[1].ncols;
   const int n0 = x * 16;
   if (n0 >= N) return;                              // instances of one launch may differ in N
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int which = n0 >= g.part[0].ncols ? 1 : 0;
-  BwdEpi e = g.part[which];
-  // what the epilogue needs is fetched now, not behind the barrier
-  CMT_PIN_UNIFORM(e.kind); CMT_PIN_UNIFORM(e.ncols); CMT_PIN_UNIFORM(e.hh); CMT_PIN_UNIFORM_PTR(e.out); CMT_PIN_UNIFORM(e.ldout);
-  CMT_PIN_UNIFORM_PTR(e.dpre); CMT_PIN_UNIFORM(e.ldp); CMT_PIN_UNIFORM_PTR(e.dpre_fm); CMT_PIN_UNIFORM(e.drop.on);
-  CMT_PIN_UNIFORM_PTR(e.cell.dg); CMT_PIN_UNIFORM(e.cell.lddg); CMT_PIN_UNIFORM_PTR(e.cell.dg_fm); CMT_PIN_UNIFORM_PTR(e.cell.dc);
-  CMT_PIN_UNIFORM_PTR(e.cell.dh); CMT_PIN_UNIFORM(e.cell.drop_dy.on); CMT_PIN_UNIFORM(e.cell.dy_col);
-  const int c0 = n0 - (which ? g.part[0].ncols : 0);
+  const int which = n0 >= ncols0 ? 1 : 0;
+  const int c0 = n0 - (which ? ncols0 : 0);
   const int bt0 = z * BT;
   const int nbt = min(BT, (Bp + 15) / 16 - bt0);
-  const T* wrow[1] = {(const T*)g.Wt + (size_t)min(n0 + (lane & 15), N - 1) * g.ldw};
-  // the tile this wavefront will finish: fetch what its epilogue reads now
+  // the tile this wavefront will finish
   const int c = c0 + 4 * (lane >> 4);
   const int b = 16 * (bt0 + w) + (lane & 15);
-  const bool mine = w < nbt && b < Bp && c < e.ncols;
-  const bool is_cell = e.kind == BWD_EPI_CELL_DY || e.kind == BWD_EPI_CELL_REC;
+  BwdEpi e;
+  bool mine = false;
   CellBwdIn cin;
   float4 tce = make_float4(0.f, 0.f, 0.f, 0.f);
   float tho[4] = {0.f, 0.f, 0.f, 0.f};
-  if (mine) {
-    if (is_cell) cin = cell_bwd_load(e.cell, b, c, e.hh);
-    else if (e.kind == BWD_EPI_TANH) {
-      const int r = e.pos ? e.pos[b] : b;
-      if (r >= 0) tce = *reinterpret_cast<const float4*>(e.dce + (size_t)r * e.hh + c);
+  // the epilogue's description and operands: fetched now, not behind the barrier — and, where the contraction's
+  // operands came in registers, behind its first round of loads (the opaque index keeps the compiler from moving
+  // this block, which depends on nothing before it, back in front of them)
+  auto fetch_rest = [&]() {
+    int wsel = __builtin_amdgcn_readfirstlane(which);
+    asm volatile("" : "+s"(wsel) : : "memory");
+    e = g.part[wsel];
+    CMT_PIN_UNIFORM(e.kind); CMT_PIN_UNIFORM(e.ncols); CMT_PIN_UNIFORM(e.hh); CMT_PIN_UNIFORM_PTR(e.out); CMT_PIN_UNIFORM(e.ldout);
+    CMT_PIN_UNIFORM_PTR(e.dpre); CMT_PIN_UNIFORM(e.ldp); CMT_PIN_UNIFORM_PTR(e.dpre_fm); CMT_PIN_UNIFORM(e.drop.on);
+    CMT_PIN_UNIFORM_PTR(e.cell.dg); CMT_PIN_UNIFORM(e.cell.lddg); CMT_PIN_UNIFORM_PTR(e.cell.dg_fm); CMT_PIN_UNIFORM_PTR(e.cell.dc);
+    CMT_PIN_UNIFORM_PTR(e.cell.dh); CMT_PIN_UNIFORM(e.cell.drop_dy.on); CMT_PIN_UNIFORM(e.cell.dy_col);
+    mine = w < nbt && b < Bp && c < e.ncols;
+    if (mine) {
+      if (e.kind == BWD_EPI_CELL_DY || e.kind == BWD_EPI_CELL_REC) cin = cell_bwd_load(e.cell, b, c, e.hh);
+      else if (e.kind == BWD_EPI_TANH) {
+        const int r = e.pos ? e.pos[b] : b;
+        if (r >= 0) tce = *reinterpret_cast<const float4*>(e.dce + (size_t)r * e.hh + c);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) tho[i] = to_f<T>(((const T*)e.Ho)[(size_t)b * e.ldho + c + i]);
+        for (int i = 0; i < 4; ++i) tho[i] = to_f<T>(((const T*)e.Ho)[(size_t)b * e.ldho + c + i]);
+      }
     }
-  }
+  };
   if constexpr (FM) {
-    const int ns = g.K >> 5;
-    const bf16_t* wt[1] = {(const bf16_t*)g.Wt_fm + (size_t)(g.wt_tile0 + x) * ns * 512};
-    step_contract_fm<1, KS, U, BT>(wt, (const bf16_t*)g.dg_fm, ns, nullptr, 0, bt0, nbt, red);
+    const int ns = (ld.on ? ld.K : g.K) >> 5;
+    const bf16_t* Wf = (const bf16_t*)(ld.on ? ld.Wt_fm : g.Wt_fm);
+    const bf16_t* wt[1] = {Wf + (size_t)((ld.on ? ld.wt_tile0 : g.wt_tile0) + x) * ns * 512};
+    step_contract_fm<1, KS, U, BT, decltype(fetch_rest), KS == 16>(wt, (const bf16_t*)(ld.on ? ld.dg_fm : g.dg_fm), ns, nullptr, 0, bt0, nbt,
+                                                                   red, 0, 1 << 30, fetch_rest);
   } else {
+    fetch_rest();
+    const T* wrow[1] = {(const T*)g.Wt + (size_t)min(n0 + (lane & 15), N - 1) * g.ldw};
     step_contract<T, 1, KS, U, BT>(wrow, 0, 0, (const T*)g.dg, g.lddg, g.K, (const T*)nullptr, 0, 0, Bp, bt0, nbt, red);
   }
   if (!mine) return;                                // KS >= BT: wavefront w finishes sentence tile w
@@ -908,16 +965,26 @@ __device__ __forceinline__ void step_bwd_body(const StepBwd& g, int Bp, const St
     if (sizeof(T) == 2 && e.dpre_fm) store4<T>((T*)e.dpre_fm + fm_offset(b, c, e.hh >> 5), o);
   }
 }
+// The leading arguments describe instance 0 and, with nlead = 2, instance 1 (same shape, its own operands: the
+// bottom encoder layer's two directions).  nx = the launch's column tiles (of its widest instance).
 template <typename T, int KS, int U, int BT, bool FM = false>
-__global__ __launch_bounds__(64 * KS) void step_bwd_fused_kernel(StepBwdArgs args, int Bp, StepGrid sg) {
+__global__ __launch_bounds__(64 * KS) void step_bwd_fused_kernel(const void* Wt_fm0, const void* dg_fm0, const void* Wt_fm1,
+                                                                 const void* dg_fm1, int K0, int wt_tile00, int N0, int ncols00, int Bp,
+                                                                 int nx_nlead, StepBwdArgs args) {
   __shared__ __align__(16) float red[KS * BT * 256];
-  step_bwd_body<T, KS, U, BT, FM>(args.g[blockIdx.y], Bp, sg, red);
+  const int nx = nx_nlead & 0xffff, nlead = nx_nlead >> 16;
+  const int inst = blockIdx.y;
+  const StepBwdLead ld{inst == 1 ? Wt_fm1 : Wt_fm0, inst == 1 ? dg_fm1 : dg_fm0, K0, wt_tile00, N0, ncols00, inst < nlead ? 1 : 0};
+  step_bwd_body<T, KS, U, BT, FM>(ld, args.g[inst], Bp, StepGrid{nx, 1, ((Bp + 15) / 16 + BT - 1) / BT}, red);
 }
 // One instance and, in further workgroups of the same launch, attention scores that depend on the same input
 // alone (block n_gemm + ig * Bp + b: positions ig * KS + wavefront of sentence b).
 template <typename T, int KS, int U, int BT, bool FM = false>
-__global__ __launch_bounds__(64 * KS) void step_bwd_scores_kernel(StepBwd g, int Bp, StepGrid sg, int n_gemm, AttScores d) {
+__global__ __launch_bounds__(64 * KS) void step_bwd_scores_kernel(const void* Wt_fm0, const void* dg_fm0, int K0, int wt_tile00, int N0,
+                                                                  int ncols00, int Bp, int nx, int nz, int n_gemm, StepBwd g,
+                                                                  AttScores d) {
   __shared__ __align__(16) float red[KS * BT * 256];
+  const StepGrid sg{nx, 1, nz};
   if ((int)blockIdx.x >= n_gemm) {
     int ig, b;
     divmod_uniform((int)blockIdx.x - n_gemm, Bp, ig, b);
@@ -926,32 +993,43 @@ __global__ __launch_bounds__(64 * KS) void step_bwd_scores_kernel(StepBwd g, int
     else att_dots_row<T, T>((const T*)d.Mat, d.ldm, (const T*)d.vec, d.ldv, d.len, d.S, Bp, d.H, d.dots, i, b);
     return;
   }
-  step_bwd_body<T, KS, U, BT, FM>(g, Bp, sg, red);
+  const StepBwdLead ld{Wt_fm0, dg_fm0, K0, wt_tile00, N0, ncols00, 1};
+  step_bwd_body<T, KS, U, BT, FM>(ld, g, Bp, sg, red);
 }
 
 template <typename T, int KS, int U, int BT>
 static void step_bwd_go(const StepBwdArgs& a, int n, int Nmax, int Bp, hipStream_t st, bool fm, const AttScores* sc) {
   const int nbt = (Bp + 15) / 16;
   StepGrid sg{(Nmax + 15) / 16, 1, (nbt + BT - 1) / BT};
+  const StepBwd& g0 = a.g[0];
+  const int N0 = g0.part[0].ncols + g0.part[1].ncols;
   if (sc) {                                        // (one instance) the scores ride in the same launch
     const int n_gemm = step_grid_blocks(sg);
     const dim3 grid(n_gemm + ((sc->S + KS - 1) / KS) * Bp);
     if constexpr (sizeof(T) == 2) {
       if (fm) {
-        hipLaunchKernelGGL((step_bwd_scores_kernel<T, KS, U, BT, true>), grid, dim3(64 * KS), 0, st, a.g[0], Bp, sg, n_gemm, *sc);
+        hipLaunchKernelGGL((step_bwd_scores_kernel<T, KS, U, BT, true>), grid, dim3(64 * KS), 0, st, g0.Wt_fm, g0.dg_fm, g0.K, g0.wt_tile0,
+                           N0, g0.part[0].ncols, Bp, sg.nx, sg.nz, n_gemm, g0, *sc);
         return;
       }
     }
-    hipLaunchKernelGGL((step_bwd_scores_kernel<T, KS, U, BT>), grid, dim3(64 * KS), 0, st, a.g[0], Bp, sg, n_gemm, *sc);
+    hipLaunchKernelGGL((step_bwd_scores_kernel<T, KS, U, BT>), grid, dim3(64 * KS), 0, st, g0.Wt_fm, g0.dg_fm, g0.K, g0.wt_tile0, N0,
+                       g0.part[0].ncols, Bp, sg.nx, sg.nz, n_gemm, g0, *sc);
     return;
   }
+  const StepBwd& g1 = a.g[n > 1 ? 1 : 0];
+  const bool same = n > 1 && g1.K == g0.K && g1.wt_tile0 == g0.wt_tile0 && g1.part[0].ncols == g0.part[0].ncols &&
+                    g1.part[1].ncols == g0.part[1].ncols;
+  const int nx_nlead = sg.nx | ((same ? 2 : 1) << 16);
   if constexpr (sizeof(T) == 2) {
     if (fm) {
-      hipLaunchKernelGGL((step_bwd_fused_kernel<T, KS, U, BT, true>), dim3(step_grid_blocks(sg), n), dim3(64 * KS), 0, st, a, Bp, sg);
+      hipLaunchKernelGGL((step_bwd_fused_kernel<T, KS, U, BT, true>), dim3(step_grid_blocks(sg), n), dim3(64 * KS), 0, st, g0.Wt_fm,
+                         g0.dg_fm, g1.Wt_fm, g1.dg_fm, g0.K, g0.wt_tile0, N0, g0.part[0].ncols, Bp, nx_nlead, a);
       return;
     }
   }
-  hipLaunchKernelGGL((step_bwd_fused_kernel<T, KS, U, BT>), dim3(step_grid_blocks(sg), n), dim3(64 * KS), 0, st, a, Bp, sg);
+  hipLaunchKernelGGL((step_bwd_fused_kernel<T, KS, U, BT>), dim3(step_grid_blocks(sg), n), dim3(64 * KS), 0, st, g0.Wt_fm, g0.dg_fm,
+                     g1.Wt_fm, g1.dg_fm, g0.K, g0.wt_tile0, N0, g0.part[0].ncols, Bp, nx_nlead, a);
 }
 
 void launch_step_bwd_fused(int prec, const StepBwd* gs, int n, int Bp, hipStream_t st, const AttScores* scores) {
