@@ -1092,9 +1092,22 @@ __global__ __launch_bounds__(256) void att_dots_kernel(const T* __restrict__ Mat
 // The scores of a step and, in other workgroups of the same launch, the plain sums of a mode-3 step GEMM (the
 // attentional layer's H_t half): both depend on the top layer's new state alone, so neither waits for the other.
 // Blocks [0, n_gemm) are the GEMM's; block n_gemm + ig * Bp + b takes positions ig * KS + wavefront of sentence b.
+// The leading arguments (they arrive in registers) are all the fragment-major GEMM blocks need: W_fm / a1_fm / K0 /
+// K1 / N / out / ldout of `g`, which those blocks then never read.
 template <typename T, int KS, int U, bool FM>
-__global__ __launch_bounds__(64 * KS) void att_dots_pre_kernel(StepGemm g, int Bp, StepGrid sg, int n_gemm, AttScores d) {
+__global__ __launch_bounds__(64 * KS) void att_dots_pre_kernel(const void* W_fm0, const void* a1_fm0, float* out0, int K00, int K10, int N0,
+                                                               int ldout0, int Bp, int n_gemm, StepGemm g, AttScores d) {
   __shared__ __align__(16) float red[KS * 256];
+  const StepGrid sg{(N0 + 15) / 16, 1, (Bp + 15) / 16};
+  if constexpr (FM) {
+    if ((int)blockIdx.x < n_gemm) {
+      StepGemm gl{};
+      gl.W_fm = W_fm0; gl.a0_fm = a1_fm0; gl.a1_fm = a1_fm0; gl.K0 = K00; gl.K1 = K10; gl.N = N0; gl.out = out0; gl.ldout = ldout0;
+      gl.skip0 = 1; gl.mode = 3;
+      step_tanh_body<T, KS, U, true, true>(gl, Bp, sg, red);
+      return;
+    }
+  }
   if ((int)blockIdx.x >= n_gemm) {
     int ig, b;
     divmod_uniform((int)blockIdx.x - n_gemm, Bp, ig, b);
@@ -1307,8 +1320,10 @@ void launch_att_fwd_proj(int prec, const void* Kmat, int ldk, const void* Pmat, 
   const int ks = nsteps > 16 ? 16 : 8;
   const dim3 grid(n_gemm + ((S + ks - 1) / ks) * Bp);
   const AttScores d{Kmat, ldk, Ht, ldt, src_len, S, H, dots, 0};
-#define GO(TT, KS, FM) hipLaunchKernelGGL((att_dots_pre_kernel<TT, KS, 2, FM>), grid, dim3(64 * KS), 0, st, u, Bp, sg, n_gemm, d)
-  if (prec && step_gemm_has_fm(u)) { if (ks == 16) GO(bf16_t, 16, true); else GO(bf16_t, 8, true); }
+#define GO(TT, KS, FM) hipLaunchKernelGGL((att_dots_pre_kernel<TT, KS, 2, FM>), grid, dim3(64 * KS), 0, st, u.W_fm, u.a1_fm, u.out, u.K0, u.K1, \
+                                          u.N, u.ldout, Bp, n_gemm, u, d)
+  // (the fragment-major form reads the leading arguments alone: segment 1 of an unshifted W_fm)
+  if (prec && step_gemm_has_fm(u) && u.skip0 && u.w_tile0 == 0) { if (ks == 16) GO(bf16_t, 16, true); else GO(bf16_t, 8, true); }
   else if (prec) { if (ks == 16) GO(bf16_t, 16, false); else GO(bf16_t, 8, false); }
   else { if (ks == 16) GO(float, 16, false); else GO(float, 8, false); }
 #undef GO
