@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 # profiles/ gives the commands and the figures.  Valid for the workload and the kernel source it was
 # measured with: (workload, first 12 hex digits of the sha256 of csrc/step.hip + csrc/common.h) -> bytes;
 # with another source the figure is stale and reported as null.
-MEASURED_TRAFFIC_BYTES = {("medium", "4112a1dfb4a8"): 22850560}      # profiles/step_kernels_medium_bf16_memory_counters.md
+MEASURED_TRAFFIC_BYTES = {("medium", "22155112665a"): 22882304}      # profiles/step_kernels_medium_bf16_memory_counters.md
 
 
 def step_kernel_source_tag():
