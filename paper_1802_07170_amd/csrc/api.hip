@@ -1702,7 +1702,7 @@ int cmt_beam_decode(cmt_handle* h, const int32_t* src_ids_dev, const int32_t* sr
       launch_step_gemm(p, g, Rp, st);
     }
     launch_gemm_nt(p, h->HoBuf, PH, h->Pw(h->off_Wo), H, Rp, V, H, h->logits, nullptr, V, h->params + h->off_Bo, 0, st);
-    launch_beam_select(h->logits, V, bs, B, K, j, max_len, eos_id, length_penalty, st);
+    launch_beam_select(h->logits, V, bs, B, K, j, max_len, eos_id, length_penalty, st, p);
     launch_beam_reorder(p, ro, bs, R, H, L, st);
   }
   launch_beam_finish(bs, B, K, max_len, c.pad_id, out_ids_dev, out_len_dev, out_score_dev, st);

@@ -60,6 +60,15 @@ constexpr int BEAM_CAND_CAP = 2048;     // candidates a row's workgroup keeps in
 // (value, index) ordering: larger value first, then lower index
 __device__ __forceinline__ bool beam_better(float v, int f, float bv, int bf) { return v > bv || (v == bv && f < bf); }
 
+// Wavefront-wide best (value, index) pair; every lane gets the result.
+__device__ __forceinline__ void beam_wave_best(float& v, int& f) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(v, o, 64);
+    const int of = __shfl_xor(f, o, 64);
+    if (beam_better(ov, of, v, f)) { v = ov; f = of; }
+  }
+}
 // Workgroup-wide best (value, index) pair of 256 threads; every thread gets the result.
 __device__ __forceinline__ void beam_block_best(float& v, int& f, float* s_v, int* s_f) {
 #pragma unroll
@@ -87,6 +96,9 @@ __device__ __forceinline__ void beam_block_best(float& v, int& f, float* s_v, in
 //   pass 2: sum of exp(z - max), and the elements >= tau are appended to a list in LDS;
 //   then K rounds of a workgroup-wide arg-max over that list.  A list that overflows (many equal
 //   logits) falls back to K rounds over the row itself.
+// Both passes keep four 16-byte loads per thread in flight (a row is 128 KB at V = 32000 and the workgroup's 256 threads
+// would otherwise wait for one load at a time).  FAST (16-bit path): the hardware exponential in the log-sum-exp.
+template <bool FAST>
 __global__ __launch_bounds__(256) void beam_row_topk_kernel(const float* __restrict__ z, int V, BeamState bs, int K) {
   __shared__ float s_v[4];
   __shared__ int s_f[4];
@@ -101,38 +113,64 @@ __global__ __launch_bounds__(256) void beam_row_topk_kernel(const float* __restr
   const int nv4 = V >> 2;                                // V is a multiple of 8
   // ---- pass 1 ----------------------------------------------------------------------------------------
   float tv = -INFINITY; int ti = 0x7fffffff;
-  for (int c = t; c < nv4; c += 256) {
-    const float4 q = *reinterpret_cast<const float4*>(zr + 4 * c);
-    if (beam_better(q.x, 4 * c, tv, ti)) { tv = q.x; ti = 4 * c; }
-    if (beam_better(q.y, 4 * c + 1, tv, ti)) { tv = q.y; ti = 4 * c + 1; }
-    if (beam_better(q.z, 4 * c + 2, tv, ti)) { tv = q.z; ti = 4 * c + 2; }
-    if (beam_better(q.w, 4 * c + 3, tv, ti)) { tv = q.w; ti = 4 * c + 3; }
+  for (int c0 = t; c0 < nv4; c0 += 4 * 256) {
+    float4 q[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int c = c0 + 256 * k;
+      q[k] = c < nv4 ? *reinterpret_cast<const float4*>(zr + 4 * c) : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {                         // ascending token order, as one load at a time would visit them
+      const int c = c0 + 256 * k;
+      if (c >= nv4) break;
+      if (beam_better(q[k].x, 4 * c, tv, ti)) { tv = q[k].x; ti = 4 * c; }
+      if (beam_better(q[k].y, 4 * c + 1, tv, ti)) { tv = q[k].y; ti = 4 * c + 1; }
+      if (beam_better(q[k].z, 4 * c + 2, tv, ti)) { tv = q[k].z; ti = 4 * c + 2; }
+      if (beam_better(q[k].w, 4 * c + 3, tv, ti)) { tv = q[k].w; ti = 4 * c + 3; }
+    }
   }
+  // The K-th best of one wavefront's 64 thread-bests is already such a bound (its threads hold bests of disjoint
+  // parts of the row): K rounds of shuffles per wavefront, no barriers, then the largest of the four bounds.
   float mx = -INFINITY, tau = -INFINITY;
   {
     bool taken = false;
     for (int round = 0; round < K; ++round) {
       float v = taken ? -INFINITY : tv;
       int f = taken ? 0x7fffffff : ti;
-      beam_block_best(v, f, s_v, s_f);
+      beam_wave_best(v, f);
       if (round == 0) mx = v;
-      tau = v;                                           // -inf when fewer than K threads hold an element
+      tau = v;                                           // -inf when fewer than K of its threads hold an element
       if (!taken && f == ti) taken = true;
     }
   }
+  if (lane == 0) { s_v[w] = tau; s_sum[w] = mx; }
   if (t == 0) s_n = 0;
   __syncthreads();
+  tau = fmaxf(fmaxf(s_v[0], s_v[1]), fmaxf(s_v[2], s_v[3]));
+  mx = fmaxf(fmaxf(s_sum[0], s_sum[1]), fmaxf(s_sum[2], s_sum[3]));
+  __syncthreads();                                       // (s_sum is written again below)
   // ---- pass 2 ----------------------------------------------------------------------------------------
   float e = 0.f;
-  for (int c = t; c < nv4; c += 256) {
-    const float4 q = *reinterpret_cast<const float4*>(zr + 4 * c);
-    const float x[4] = {q.x, q.y, q.z, q.w};
+  for (int c0 = t; c0 < nv4; c0 += 4 * 256) {
+    float4 q[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      e += expf(x[i] - mx);
-      if (x[i] >= tau) {
-        const int pos = atomicAdd(&s_n, 1);
-        if (pos < BEAM_CAND_CAP) { s_cv[pos] = x[i]; s_ci[pos] = 4 * c + i; }
+    for (int k = 0; k < 4; ++k) {
+      const int c = c0 + 256 * k;
+      q[k] = c < nv4 ? *reinterpret_cast<const float4*>(zr + 4 * c) : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int c = c0 + 256 * k;
+      if (c >= nv4) break;
+      const float x[4] = {q[k].x, q[k].y, q[k].z, q[k].w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        e += FAST ? __expf(x[i] - mx) : expf(x[i] - mx);
+        if (x[i] >= tau) {
+          const int pos = atomicAdd(&s_n, 1);
+          if (pos < BEAM_CAND_CAP) { s_cv[pos] = x[i]; s_ci[pos] = 4 * c + i; }
+        }
       }
     }
   }
@@ -143,6 +181,20 @@ __global__ __launch_bounds__(256) void beam_row_topk_kernel(const float* __restr
   const int n = s_n;
   // ---- K rounds: the best element strictly after the previous winner in the (value, token) order ---------
   float pv = INFINITY; int pi = -1;
+  if (n <= 256) {                                        // (the usual case) a short list: one wavefront, shuffles only
+    if (w != 0) return;
+    for (int round = 0; round < K; ++round) {
+      float v = -INFINITY; int f = 0x7fffffff;
+      for (int q = lane; q < n; q += 64) {
+        const float x = s_cv[q]; const int xi = s_ci[q];
+        if ((x < pv || (x == pv && xi > pi)) && beam_better(x, xi, v, f)) { v = x; f = xi; }
+      }
+      beam_wave_best(v, f);
+      if (lane == 0) { bs.cand_z[(size_t)r * BEAM_MAX + round] = v; bs.cand_tok[(size_t)r * BEAM_MAX + round] = f; }
+      pv = v; pi = f;
+    }
+    return;
+  }
   for (int round = 0; round < K; ++round) {
     float v = -INFINITY; int f = 0x7fffffff;
     if (n <= BEAM_CAND_CAP) {
@@ -230,8 +282,9 @@ __global__ __launch_bounds__(256) void beam_merge_kernel(int V, BeamState bs, in
   }
 }
 void launch_beam_select(const float* z, int V, const BeamState& bs, int B, int K, int j, int max_len, int eos, float alpha,
-                        hipStream_t st) {
-  hipLaunchKernelGGL(beam_row_topk_kernel, dim3(B * K), dim3(256), 0, st, z, V, bs, K);
+                        hipStream_t st, int fast_exp) {
+  if (fast_exp) hipLaunchKernelGGL(beam_row_topk_kernel<true>, dim3(B * K), dim3(256), 0, st, z, V, bs, K);
+  else hipLaunchKernelGGL(beam_row_topk_kernel<false>, dim3(B * K), dim3(256), 0, st, z, V, bs, K);
   hipLaunchKernelGGL(beam_merge_kernel, dim3(B), dim3(256), 0, st, V, bs, K, j, max_len, eos, alpha);
 }
 

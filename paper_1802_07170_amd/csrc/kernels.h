@@ -359,9 +359,10 @@ struct BeamReorder {
 void launch_beam_expand(int elem_bytes, const void* src, int ld_src, int rows_src, void* dst, int ld_dst, int n_outer, int R, int Rp,
                         int K, int cols, hipStream_t st);
 void launch_beam_init(const BeamState& bs, int B, int Rp, int K, int bos, const int32_t* len_src, int32_t* len_exp, hipStream_t st);
-// z [Rp, V] = logits incl. bias.  Step j of max_len; K <= 16.
+// z [Rp, V] = logits incl. bias.  Step j of max_len; K <= 16.  fast_exp: the hardware exponential in the rows'
+// log-sum-exp (the 16-bit path).
 void launch_beam_select(const float* z, int V, const BeamState& bs, int B, int K, int j, int max_len, int eos, float alpha,
-                        hipStream_t st);
+                        hipStream_t st, int fast_exp = 0);
 void launch_beam_reorder(int prec, const BeamReorder& ro, const BeamState& bs, int R, int H, int L, hipStream_t st);
 void launch_beam_finish(const BeamState& bs, int B, int K, int max_len, int pad, int32_t* out_ids, int32_t* out_len, float* out_score,
                         hipStream_t st);
